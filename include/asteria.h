@@ -1,0 +1,199 @@
+/*
+ * asteria.h - C ABI of the MI355X (gfx950) Shampoo / SOAP preconditioner pipeline.
+ *
+ * The library implements, for a batch of independent gradient blocks G (m x n), the
+ * dense-math hot path of Kronecker-factored second-order training:
+ *
+ *   asteria_stats_update   L <- beta L + (1-beta) G G^T,  R <- beta R + (1-beta) G^T G
+ *                          (the Kronecker-factor statistics the method accumulates on the
+ *                          GPU every step; paper Sec. I, Sec. III-B "factor_matrices")
+ *   asteria_inverse_root   X = (A + eps I)^(-1/p), p = 4 by default, for every factor A = L
+ *                          or R (the O(d^3) inverse-root update; paper Sec. I, Sec. III-B
+ *                          "inv_factor_matrices", Eq. 1)
+ *   asteria_precondition   P = X_L G X_R   (paper Eq. 1)
+ *   asteria_soap_refresh   Q <- qr(A Q).Q  (eigenbasis refresh used with paper Eq. 2)
+ *   asteria_soap_step      N = Q_L phi(Q_L^T G Q_R) Q_R^T, phi = Adam in the rotated basis
+ *                          (paper Eq. 2)
+ *
+ * Conventions common to every entry point
+ *   - All matrix pointers are DEVICE pointers owned by the caller; descriptor arrays
+ *     (asteria_block[], asteria_factor[], ...) and option structs are HOST memory and are
+ *     consumed before the call returns.
+ *   - Matrices are dense row-major with an explicit leading dimension counted in elements.
+ *     Symmetric matrices are stored full; both triangles are read as given and both are valid
+ *     on return.  Inputs and outputs must not alias unless "in place" is stated.
+ *   - Blocks / factors of one call may have different shapes.
+ *   - `ws` is caller-owned device scratch of `ws_bytes` bytes, 256-byte aligned; the matching
+ *     *_workspace_bytes query returns the size that lets the whole batch run in one pass and
+ *     (where a min_bytes pointer is given) the smallest size the call accepts.  The library
+ *     itself allocates no device memory and keeps no state between calls.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  All work is
+ *     enqueued on it; no entry point waits for the device.  A call may stage its descriptor
+ *     tables with hipMemcpyAsync from host memory it owns until the call returns.
+ *   - The return value reports argument / launch errors only (nothing was enqueued when it
+ *     is ASTERIA_INVALID_ARG, ASTERIA_UNSUPPORTED or ASTERIA_WORKSPACE_TOO_SMALL).  Numerical
+ *     outcomes are per factor and device-side (`info`, `iters`, `resid`, `lambda_max`).
+ */
+#ifndef ASTERIA_H
+#define ASTERIA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum asteria_status {
+    ASTERIA_OK = 0,
+    ASTERIA_INVALID_ARG = 1,
+    ASTERIA_UNSUPPORTED = 2,
+    ASTERIA_WORKSPACE_TOO_SMALL = 3,
+    ASTERIA_HIP_ERROR = 4
+} asteria_status;
+
+typedef enum asteria_dtype {
+    ASTERIA_F32 = 0,
+    ASTERIA_BF16 = 1
+} asteria_dtype;
+
+/* per-factor numerical outcome written to the device `info` arrays */
+enum {
+    ASTERIA_INFO_OK = 0,
+    ASTERIA_INFO_NOT_CONVERGED = 1, /* iteration budget exhausted; X holds the last iterate      */
+    ASTERIA_INFO_NOT_PD = 2         /* A + eps I not positive definite or non-finite; X undefined */
+};
+
+/* One gradient block with its two statistics (asteria_stats_update). */
+typedef struct asteria_block {
+    const void *G; /* device, m x n, element type g_dtype, leading dimension ldg */
+    float *L;      /* device, m x m fp32, leading dimension ldl, updated in place */
+    float *R;      /* device, n x n fp32, leading dimension ldr, updated in place */
+    int32_t m, n;
+    int32_t ldg, ldl, ldr;
+    int32_t g_dtype; /* asteria_dtype */
+} asteria_block;
+
+/* One symmetric factor and the matrix produced from it. */
+typedef struct asteria_factor {
+    const float *A; /* device, n x n fp32 symmetric statistic (read only), leading dimension lda */
+    float *X;       /* device, n x n fp32: inverse root (asteria_inverse_root, written) or
+                       eigenbasis Q (asteria_soap_refresh, in place), leading dimension ldx    */
+    int32_t n;
+    int32_t lda, ldx;
+} asteria_factor;
+
+/* One block of the preconditioned update (asteria_precondition). */
+typedef struct asteria_pblock {
+    const float *XL; /* device, m x m fp32 symmetric, ldxl */
+    const void *G;   /* device, m x n, g_dtype, ldg        */
+    const float *XR; /* device, n x n fp32 symmetric, ldxr */
+    void *P;         /* device, m x n, p_dtype, ldp (written) */
+    int32_t m, n;
+    int32_t ldxl, ldg, ldxr, ldp;
+    int32_t g_dtype, p_dtype; /* asteria_dtype */
+} asteria_pblock;
+
+/* One block of the SOAP step (asteria_soap_step). */
+typedef struct asteria_sblock {
+    const void *G;   /* device, m x n, g_dtype, ldg                          */
+    const float *QL; /* device, m x m fp32, columns = basis vectors, ldql    */
+    const float *QR; /* device, n x n fp32, columns = basis vectors, ldqr    */
+    float *M;        /* device, m x n fp32 first moment in the rotated basis, in place, ldm  */
+    float *V;        /* device, m x n fp32 second moment in the rotated basis, in place, ldv */
+    float *N;        /* device, m x n fp32 update direction (written), ldn   */
+    int32_t m, n;
+    int32_t ldg, ldql, ldqr, ldm, ldv, ldn;
+    int32_t g_dtype;
+} asteria_sblock;
+
+typedef enum asteria_eps_mode {
+    ASTERIA_EPS_RELATIVE = 0, /* eps_i = eps[i] * lambda_max(A_i), lambda_max estimated on the device */
+    ASTERIA_EPS_ABSOLUTE = 1  /* eps_i = eps[i]                                                       */
+} asteria_eps_mode;
+
+/* Options of asteria_inverse_root.  Zero-initialise and call asteria_root_opts_default. */
+typedef struct asteria_root_opts {
+    int32_t max_iters;     /* upper bound on coupled iterations per factor (default 40)               */
+    int32_t fp64_iters;    /* leading iterations run on fp64 MFMA: -1 = choose from eps (default),
+                              0 = fp32 only, >= max_iters = fp64 throughout                            */
+    int32_t power_iters;   /* upper bound on power-iteration steps for lambda_max (default 256)       */
+    int32_t schedule;      /* 0 = classical coupled Newton coefficients (default); 1 = interval-adapted */
+    float stop_resid;      /* a factor takes its last step once ||M - I||_F < stop_resid (default 1e-2;
+                              the step after that squares the residual)                                */
+    float power_tol;       /* power iteration stops at ||A v - rho v|| <= power_tol * rho (default 1e-3) */
+    float lambda_margin;   /* spectrum is scaled by 1 / ((1 + lambda_margin) lambda_max + eps)
+                              (default 0.01) so an underestimated lambda_max stays inside (0, 1]      */
+    int32_t reserved;
+} asteria_root_opts;
+
+void asteria_root_opts_default(asteria_root_opts *opts);
+
+int asteria_version(void);
+const char *asteria_status_string(asteria_status s);
+
+/* ---- statistics (paper Sec. I, Sec. III-B) -------------------------------------------------
+ * For every block: L <- beta L + (1-beta) G G^T and R <- beta R + (1-beta) G^T G, products
+ * accumulated in fp32 (bf16 x bf16 products are exact in fp32).  L and R come back exactly
+ * symmetric (one triangle is computed, the other mirrored).  Either L or R may be NULL to skip
+ * that side.  Needs no workspace (ws may be NULL); 0 <= beta < 1.
+ * Errors: NULL G, m or n <= 0, ld too small, bad dtype, beta out of range -> INVALID_ARG.   */
+size_t asteria_stats_update_workspace_bytes(const asteria_block *blocks, int nblocks);
+asteria_status asteria_stats_update(const asteria_block *blocks, int nblocks, float beta,
+                                    void *ws, size_t ws_bytes, void *stream);
+
+/* ---- inverse p-th roots (paper Eq. 1, Sec. III-B) ------------------------------------------
+ * For every factor: X = ((A + A^T)/2 + eps I)^(-1/root), root in {2, 4, 8}... (4 = Eq. 1), by a
+ * coupled matrix iteration run entirely on the device:  lambda_max by power iteration;
+ * M_0 = s (A + eps I), X_0 = s^(1/root) I with s = 1 / ((1 + margin) lambda_max + eps);
+ * T = a I - g M, X <- X T, M <- T^root M (classical coefficients a = (root+1)/root,
+ * g = 1/root); a factor stops by itself once its residual ||M - I||_F has fallen below
+ * stop_resid (one more X update follows).  The leading fp64_iters iterations use the fp64
+ * matrix cores, the rest the fp32 matrix cores.
+ *   eps        host array, eps_count entries (1 = shared by all factors, else nfactors).
+ *   info       device int32[nfactors] or NULL   (ASTERIA_INFO_*)
+ *   iters      device int32[nfactors] or NULL   (number of X <- X T updates performed)
+ *   resid      device float[nfactors] or NULL   (last measured ||M - I||_F)
+ *   lambda_max device float[nfactors] or NULL   (the estimate used)
+ * Workspace: the call splits the batch into passes that fit ws_bytes; *min_bytes is the size
+ * needed for the largest single factor.
+ * Errors: NULL A or X, n <= 0, ld < n, unsupported root, eps < 0 or non-finite, eps_count not
+ * in {1, nfactors} -> INVALID_ARG / UNSUPPORTED; ws too small -> WORKSPACE_TOO_SMALL.        */
+size_t asteria_inverse_root_workspace_bytes(const asteria_factor *f, int nfactors,
+                                            const asteria_root_opts *opts, size_t *min_bytes);
+asteria_status asteria_inverse_root(const asteria_factor *f, int nfactors, int root,
+                                    asteria_eps_mode mode, const float *eps, int eps_count,
+                                    const asteria_root_opts *opts,
+                                    int32_t *info, int32_t *iters, float *resid, float *lambda_max,
+                                    void *ws, size_t ws_bytes, void *stream);
+
+/* ---- preconditioned update (paper Eq. 1) ---------------------------------------------------
+ * For every block: P = X_L G X_R, X_L and X_R symmetric fp32, fp32 matrix-core products with
+ * fp32 accumulation; P is written as fp32 or bf16 (round to nearest even).
+ * Workspace holds the intermediate G X_R of every block (fp32, m x n each).                 */
+size_t asteria_precondition_workspace_bytes(const asteria_pblock *blocks, int nblocks);
+asteria_status asteria_precondition(const asteria_pblock *blocks, int nblocks,
+                                    void *ws, size_t ws_bytes, void *stream);
+
+/* ---- SOAP eigenbasis refresh (paper Eq. 2) -------------------------------------------------
+ * For every factor: Z = A Q (one power iteration), Z = Q' R by Householder QR, column signs
+ * chosen so that diag(R) >= 0, and Q <- Q' in place (f[i].X is Q).
+ *   info  device int32[nfactors] or NULL (ASTERIA_INFO_OK, or ASTERIA_INFO_NOT_PD if a
+ *         non-finite value was met).                                                         */
+size_t asteria_soap_refresh_workspace_bytes(const asteria_factor *f, int nfactors, size_t *min_bytes);
+asteria_status asteria_soap_refresh(const asteria_factor *f, int nfactors, int32_t *info,
+                                    void *ws, size_t ws_bytes, void *stream);
+
+/* ---- SOAP step (paper Eq. 2, phi = Adam in the rotated basis) ------------------------------
+ * For every block, with step_t >= 1:
+ *   G' = Q_L^T G Q_R;  M <- beta1 M + (1-beta1) G';  V <- beta2 V + (1-beta2) G' o G';
+ *   N' = (M / (1-beta1^t)) / (sqrt(V / (1-beta2^t)) + adam_eps);  N = Q_L N' Q_R^T.          */
+size_t asteria_soap_step_workspace_bytes(const asteria_sblock *blocks, int nblocks);
+asteria_status asteria_soap_step(const asteria_sblock *blocks, int nblocks,
+                                 float beta1, float beta2, float adam_eps, int step_t,
+                                 void *ws, size_t ws_bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ASTERIA_H */

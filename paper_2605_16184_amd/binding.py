@@ -1,0 +1,340 @@
+"""ctypes view of libasteria.so.  Functions carry the names of the C entry points; they take
+torch tensors on the GPU, build the host descriptor arrays and pass raw pointers.  Nothing is
+computed here, and there is no fallback: a missing library is an ImportError."""
+from __future__ import annotations
+
+import ctypes
+import os
+from ctypes import c_float, c_int, c_int32, c_size_t, c_void_p, POINTER, Structure
+from typing import Optional, Sequence
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libasteria.so")
+
+OK, INVALID_ARG, UNSUPPORTED, WORKSPACE_TOO_SMALL, HIP_ERROR = range(5)
+F32, BF16 = 0, 1
+EPS_RELATIVE, EPS_ABSOLUTE = 0, 1
+INFO_OK, INFO_NOT_CONVERGED, INFO_NOT_PD = 0, 1, 2
+
+
+class AsteriaError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        super().__init__(f"{where}: {status_string(status)} (status {status})")
+        self.status = status
+
+
+class _Block(Structure):
+    _fields_ = [("G", c_void_p), ("L", c_void_p), ("R", c_void_p), ("m", c_int32), ("n", c_int32),
+                ("ldg", c_int32), ("ldl", c_int32), ("ldr", c_int32), ("g_dtype", c_int32)]
+
+
+class _Factor(Structure):
+    _fields_ = [("A", c_void_p), ("X", c_void_p), ("n", c_int32), ("lda", c_int32), ("ldx", c_int32)]
+
+
+class _PBlock(Structure):
+    _fields_ = [("XL", c_void_p), ("G", c_void_p), ("XR", c_void_p), ("P", c_void_p),
+                ("m", c_int32), ("n", c_int32), ("ldxl", c_int32), ("ldg", c_int32),
+                ("ldxr", c_int32), ("ldp", c_int32), ("g_dtype", c_int32), ("p_dtype", c_int32)]
+
+
+class _SBlock(Structure):
+    _fields_ = [("G", c_void_p), ("QL", c_void_p), ("QR", c_void_p), ("M", c_void_p), ("V", c_void_p),
+                ("N", c_void_p), ("m", c_int32), ("n", c_int32), ("ldg", c_int32), ("ldql", c_int32),
+                ("ldqr", c_int32), ("ldm", c_int32), ("ldv", c_int32), ("ldn", c_int32),
+                ("g_dtype", c_int32)]
+
+
+class RootOpts(Structure):
+    """Mirror of asteria_root_opts; constructed with the library defaults."""
+    _fields_ = [("max_iters", c_int32), ("fp64_iters", c_int32), ("power_iters", c_int32),
+                ("schedule", c_int32), ("stop_resid", c_float), ("power_tol", c_float),
+                ("lambda_margin", c_float), ("reserved", c_int32)]
+
+    def __init__(self, **kw):
+        super().__init__()
+        lib().asteria_root_opts_default(ctypes.byref(self))
+        for k, v in kw.items():
+            if k not in dict(self._fields_):
+                raise TypeError(f"unknown option {k}")
+            setattr(self, k, v)
+
+
+_lib = None
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise ImportError(f"{_LIB_PATH} is missing: build it with `python -m paper_2605_16184_amd.build` "
+                              "(there is no fallback path)")
+        L = ctypes.CDLL(_LIB_PATH)
+        L.asteria_version.restype = c_int
+        L.asteria_status_string.restype = ctypes.c_char_p
+        L.asteria_status_string.argtypes = [c_int]
+        L.asteria_root_opts_default.argtypes = [POINTER(RootOpts)]
+        L.asteria_root_opts_default.restype = None
+        L.asteria_stats_update_workspace_bytes.restype = c_size_t
+        L.asteria_stats_update_workspace_bytes.argtypes = [POINTER(_Block), c_int]
+        L.asteria_stats_update.restype = c_int
+        L.asteria_stats_update.argtypes = [POINTER(_Block), c_int, c_float, c_void_p, c_size_t, c_void_p]
+        L.asteria_inverse_root_workspace_bytes.restype = c_size_t
+        L.asteria_inverse_root_workspace_bytes.argtypes = [POINTER(_Factor), c_int, POINTER(RootOpts),
+                                                           POINTER(c_size_t)]
+        L.asteria_inverse_root.restype = c_int
+        L.asteria_inverse_root.argtypes = [POINTER(_Factor), c_int, c_int, c_int, POINTER(c_float), c_int,
+                                           POINTER(RootOpts), c_void_p, c_void_p, c_void_p, c_void_p,
+                                           c_void_p, c_size_t, c_void_p]
+        L.asteria_precondition_workspace_bytes.restype = c_size_t
+        L.asteria_precondition_workspace_bytes.argtypes = [POINTER(_PBlock), c_int]
+        L.asteria_precondition.restype = c_int
+        L.asteria_precondition.argtypes = [POINTER(_PBlock), c_int, c_void_p, c_size_t, c_void_p]
+        L.asteria_soap_refresh_workspace_bytes.restype = c_size_t
+        L.asteria_soap_refresh_workspace_bytes.argtypes = [POINTER(_Factor), c_int, POINTER(c_size_t)]
+        L.asteria_soap_refresh.restype = c_int
+        L.asteria_soap_refresh.argtypes = [POINTER(_Factor), c_int, c_void_p, c_void_p, c_size_t, c_void_p]
+        L.asteria_soap_step_workspace_bytes.restype = c_size_t
+        L.asteria_soap_step_workspace_bytes.argtypes = [POINTER(_SBlock), c_int]
+        L.asteria_soap_step.restype = c_int
+        L.asteria_soap_step.argtypes = [POINTER(_SBlock), c_int, c_float, c_float, c_float, c_int,
+                                        c_void_p, c_size_t, c_void_p]
+        _lib = L
+    return _lib
+
+
+def version() -> int:
+    return lib().asteria_version()
+
+
+def status_string(status: int) -> str:
+    return lib().asteria_status_string(int(status)).decode()
+
+
+# ---------------------------------------------------------------------------- marshalling
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return F32
+    if t.dtype == torch.bfloat16:
+        return BF16
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def _mat(t: Optional[torch.Tensor], name: str, dtype=None):
+    """(pointer, rows, cols, leading dimension) of a 2-D row-major device tensor."""
+    if t is None:
+        return None, 0, 0, 0
+    if t.dim() != 2 or t.stride(1) != 1 and t.shape[1] > 1:
+        raise ValueError(f"{name}: need a 2-D tensor with unit column stride")
+    if not t.is_cuda:
+        raise ValueError(f"{name}: need a GPU tensor")
+    if dtype is not None and t.dtype != dtype:
+        raise TypeError(f"{name}: expected {dtype}, got {t.dtype}")
+    ld = t.stride(0) if t.shape[0] > 1 else max(t.shape[1], t.stride(0))
+    return t.data_ptr(), t.shape[0], t.shape[1], ld
+
+
+class _Batch:
+    """A host descriptor array plus the tensors it points to (kept alive)."""
+    ctype = None
+
+    def __init__(self, items):
+        self.items = [tuple(i) for i in items]
+        self.count = len(self.items)
+        self.array = (self.ctype * max(self.count, 1))()
+        for k, it in enumerate(self.items):
+            self._fill(self.array[k], *it)
+
+    def __len__(self):
+        return self.count
+
+
+class Blocks(_Batch):
+    """[(G, L, R)] for stats_update; L or R may be None."""
+    ctype = _Block
+
+    def _fill(self, d, G, L, R):
+        d.G, d.m, d.n, d.ldg = _mat(G, "G")
+        d.g_dtype = _dtype_code(G)
+        d.L, _, _, d.ldl = _mat(L, "L", torch.float32)
+        d.R, _, _, d.ldr = _mat(R, "R", torch.float32)
+        if L is not None and tuple(L.shape) != (d.m, d.m) or R is not None and tuple(R.shape) != (d.n, d.n):
+            raise ValueError("L must be m x m and R n x n")
+
+
+class Factors(_Batch):
+    """[(A, X)] for inverse_root (X written) and soap_refresh (X = Q, in place)."""
+    ctype = _Factor
+
+    def _fill(self, d, A, X):
+        d.A, n, n2, d.lda = _mat(A, "A", torch.float32)
+        d.X, xn, xn2, d.ldx = _mat(X, "X", torch.float32)
+        if n != n2 or (xn, xn2) != (n, n):
+            raise ValueError("A and X must be square and of equal size")
+        d.n = n
+
+
+class PBlocks(_Batch):
+    """[(XL, G, XR, P)] for precondition."""
+    ctype = _PBlock
+
+    def _fill(self, d, XL, G, XR, P):
+        d.G, d.m, d.n, d.ldg = _mat(G, "G")
+        d.g_dtype = _dtype_code(G)
+        d.XL, a, b, d.ldxl = _mat(XL, "XL", torch.float32)
+        d.XR, c, e, d.ldxr = _mat(XR, "XR", torch.float32)
+        d.P, pm, pn, d.ldp = _mat(P, "P")
+        d.p_dtype = _dtype_code(P)
+        if (a, b) != (d.m, d.m) or (c, e) != (d.n, d.n) or (pm, pn) != (d.m, d.n):
+            raise ValueError("shape mismatch in precondition block")
+
+
+class SBlocks(_Batch):
+    """[(G, QL, QR, M, V, N)] for soap_step."""
+    ctype = _SBlock
+
+    def _fill(self, d, G, QL, QR, M, V, N):
+        d.G, d.m, d.n, d.ldg = _mat(G, "G")
+        d.g_dtype = _dtype_code(G)
+        d.QL, a, b, d.ldql = _mat(QL, "QL", torch.float32)
+        d.QR, c, e, d.ldqr = _mat(QR, "QR", torch.float32)
+        d.M, m1, n1, d.ldm = _mat(M, "M", torch.float32)
+        d.V, m2, n2, d.ldv = _mat(V, "V", torch.float32)
+        d.N, m3, n3, d.ldn = _mat(N, "N", torch.float32)
+        if (a, b) != (d.m, d.m) or (c, e) != (d.n, d.n) or {(m1, n1), (m2, n2), (m3, n3)} != {(d.m, d.n)}:
+            raise ValueError("shape mismatch in soap block")
+
+
+def _as(batch_type, items):
+    return items if isinstance(items, batch_type) else batch_type(items)
+
+
+def _stream(stream) -> c_void_p:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return c_void_p(stream.cuda_stream)
+
+
+def _workspace(ws: Optional[torch.Tensor], need: int, device) -> torch.Tensor:
+    if ws is None:
+        ws = torch.empty(max(int(need), 256), dtype=torch.uint8, device=device)
+    if not ws.is_cuda or ws.dtype != torch.uint8 or not ws.is_contiguous():
+        raise ValueError("workspace must be a contiguous uint8 GPU tensor")
+    return ws
+
+
+def _ptr(t: Optional[torch.Tensor], dtype, count, name):
+    if t is None:
+        return None
+    if not t.is_cuda or t.dtype != dtype or t.numel() < count or not t.is_contiguous():
+        raise ValueError(f"{name}: need a contiguous GPU tensor of {dtype} with >= {count} elements")
+    return c_void_p(t.data_ptr())
+
+
+def _check(st: int, where: str):
+    if st != OK:
+        raise AsteriaError(st, where)
+
+
+# ---------------------------------------------------------------------------- entry points
+
+def stats_update_workspace_bytes(blocks) -> int:
+    b = _as(Blocks, blocks)
+    return lib().asteria_stats_update_workspace_bytes(b.array, b.count)
+
+
+def stats_update(blocks, beta: float, ws: Optional[torch.Tensor] = None, stream=None) -> None:
+    """L <- beta L + (1-beta) G G^T, R <- beta R + (1-beta) G^T G for every (G, L, R)."""
+    b = _as(Blocks, blocks)
+    dev = b.items[0][0].device if b.count else None
+    ws = _workspace(ws, stats_update_workspace_bytes(b), dev)
+    _check(lib().asteria_stats_update(b.array, b.count, float(beta), c_void_p(ws.data_ptr()), ws.numel(),
+                                      _stream(stream)), "asteria_stats_update")
+
+
+def inverse_root_workspace_bytes(factors, opts: Optional[RootOpts] = None):
+    """(bytes for a single pass over the whole batch, smallest accepted size)."""
+    f = _as(Factors, factors)
+    mn = c_size_t(0)
+    full = lib().asteria_inverse_root_workspace_bytes(f.array, f.count, ctypes.byref(opts) if opts else None,
+                                                      ctypes.byref(mn))
+    return full, mn.value
+
+
+def inverse_root(factors, eps, relative: bool = True, root: int = 4, opts: Optional[RootOpts] = None,
+                 info: Optional[torch.Tensor] = None, iters: Optional[torch.Tensor] = None,
+                 resid: Optional[torch.Tensor] = None, lambda_max: Optional[torch.Tensor] = None,
+                 ws: Optional[torch.Tensor] = None, stream=None) -> None:
+    """X = (A + eps I)^(-1/root) for every (A, X).  ``eps``: float or sequence of one per factor."""
+    f = _as(Factors, factors)
+    eps_list = [float(eps)] if not isinstance(eps, (Sequence, torch.Tensor)) else [float(e) for e in eps]
+    eps_arr = (c_float * len(eps_list))(*eps_list)
+    dev = f.items[0][0].device if f.count else None
+    if ws is None:
+        full, _ = inverse_root_workspace_bytes(f, opts)
+        ws = _workspace(None, full, dev)
+    ws = _workspace(ws, 0, dev)
+    st = lib().asteria_inverse_root(f.array, f.count, int(root), EPS_RELATIVE if relative else EPS_ABSOLUTE,
+                                    eps_arr, len(eps_list), ctypes.byref(opts) if opts else None,
+                                    _ptr(info, torch.int32, f.count, "info"),
+                                    _ptr(iters, torch.int32, f.count, "iters"),
+                                    _ptr(resid, torch.float32, f.count, "resid"),
+                                    _ptr(lambda_max, torch.float32, f.count, "lambda_max"),
+                                    c_void_p(ws.data_ptr()), ws.numel(), _stream(stream))
+    _check(st, "asteria_inverse_root")
+
+
+def precondition_workspace_bytes(blocks) -> int:
+    b = _as(PBlocks, blocks)
+    return lib().asteria_precondition_workspace_bytes(b.array, b.count)
+
+
+def precondition(blocks, ws: Optional[torch.Tensor] = None, stream=None) -> None:
+    """P = X_L G X_R for every (XL, G, XR, P)."""
+    b = _as(PBlocks, blocks)
+    dev = b.items[0][1].device if b.count else None
+    ws = _workspace(ws, precondition_workspace_bytes(b), dev)
+    _check(lib().asteria_precondition(b.array, b.count, c_void_p(ws.data_ptr()), ws.numel(), _stream(stream)),
+           "asteria_precondition")
+
+
+def soap_refresh_workspace_bytes(factors):
+    f = _as(Factors, factors)
+    mn = c_size_t(0)
+    full = lib().asteria_soap_refresh_workspace_bytes(f.array, f.count, ctypes.byref(mn))
+    return full, mn.value
+
+
+def soap_refresh(factors, info: Optional[torch.Tensor] = None, ws: Optional[torch.Tensor] = None,
+                 stream=None) -> None:
+    """Q <- qr(A Q).Q for every (A, Q), in place."""
+    f = _as(Factors, factors)
+    dev = f.items[0][0].device if f.count else None
+    if ws is None:
+        ws = _workspace(None, soap_refresh_workspace_bytes(f)[0], dev)
+    ws = _workspace(ws, 0, dev)
+    _check(lib().asteria_soap_refresh(f.array, f.count, _ptr(info, torch.int32, f.count, "info"),
+                                      c_void_p(ws.data_ptr()), ws.numel(), _stream(stream)),
+           "asteria_soap_refresh")
+
+
+def soap_step_workspace_bytes(blocks) -> int:
+    b = _as(SBlocks, blocks)
+    return lib().asteria_soap_step_workspace_bytes(b.array, b.count)
+
+
+def soap_step(blocks, beta1: float, beta2: float, adam_eps: float, step_t: int,
+              ws: Optional[torch.Tensor] = None, stream=None) -> None:
+    """N = Q_L Adam(Q_L^T G Q_R) Q_R^T for every (G, QL, QR, M, V, N); M, V updated in place."""
+    b = _as(SBlocks, blocks)
+    dev = b.items[0][0].device if b.count else None
+    ws = _workspace(ws, soap_step_workspace_bytes(b), dev)
+    _check(lib().asteria_soap_step(b.array, b.count, float(beta1), float(beta2), float(adam_eps), int(step_t),
+                                   c_void_p(ws.data_ptr()), ws.numel(), _stream(stream)), "asteria_soap_step")

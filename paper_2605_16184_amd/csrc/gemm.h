@@ -1,0 +1,432 @@
+// Grouped GEMM core on the gfx950 matrix cores (fp32 and fp64 MFMA).
+//
+// One launch processes a device-resident table of independent problems
+//     C = alpha * A' * B'^T + beta * C          (A' is M x K, B' is N x K)
+// where each operand is either "k-contiguous" (element (r, k) at base[r * ld + k]) or
+// "k-major" (element (r, k) at base[k * ld + r]).  With symmetric commuting operands
+// (every product of the coupled root iteration, and G G^T / G^T G) only tiles on or below
+// the diagonal are computed and the result is mirrored, so the output is exactly symmetric.
+//
+// Workgroup = 256 threads = 4 wavefronts (2 x 2), macro-tile 128 x 128, each wavefront owns
+// 64 x 64.  K is walked in slabs of BK staged through LDS (two stages, register prefetch of
+// the next slab while the current one feeds the MFMA pipe).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace asteria {
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef double doublex4 __attribute__((ext_vector_type(4)));
+
+struct bf16_t { uint16_t bits; };
+
+__device__ __forceinline__ float bf16_to_f32(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
+// round-to-nearest-even, NaN kept quiet
+__device__ __forceinline__ uint16_t f32_to_bf16(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+enum : int {
+    GEMM_SYM = 1,        // compute tiles with ti >= tj only, mirror the result
+    GEMM_EPI_ROOT = 2,   // C2 = ep_a * I - ep_g * C ; partial[tile] = sum (C - I)^2
+    GEMM_C_BF16 = 4      // C is stored as bf16 (fp32 compute only)
+};
+
+struct GemmProblem {
+    const void *A;
+    const void *B;
+    void *C;
+    void *C2;
+    float *partial;
+    int M, N, K;
+    int lda, ldb, ldc, ldc2;
+    int tile_start;  // id of this problem's first tile within the launch
+    int tiles_n;     // tile columns (non-symmetric problems)
+    int state_idx;   // index into the launch's state[] array, or -1
+    int state_mask;  // problem runs iff (1 << state[state_idx]) & state_mask
+    float alpha, beta;
+    float ep_a, ep_g;
+    int flags;
+    int pad_;
+};
+
+constexpr int BM = 128;
+constexpr int BN = 128;
+constexpr int NTHREADS = 256;
+constexpr int NUM_XCD = 8;
+
+// ---- per-precision matrix-core traits -------------------------------------------------------
+template <typename TC> struct Mma;
+
+// v_mfma_f32_32x32x2_f32: A[i][k] in lane i + 32 k, B[k][j] in lane j + 32 k,
+// D[i][j] in lane j + 32 ((i / 4) % 2), register 4 (i / 8) + i % 4.
+template <> struct Mma<float> {
+    static constexpr int T = 32;       // MFMA tile edge
+    static constexpr int KG = 2;       // lane groups along k
+    static constexpr int NACC = 16;    // accumulator values per lane per tile
+    static constexpr int BK = 32;      // K slab
+    static constexpr int KPL = BK / KG;  // k values one lane consumes per slab
+    static constexpr int WT = 2;       // MFMA tiles per wavefront edge (64 / 32)
+    static constexpr int CH = 4;       // elements per 16-byte LDS chunk
+    static constexpr int PITCH_KC = BK + 4;   // k-contiguous LDS row pitch (144 B)
+    static constexpr int PITCH_KM = BM + 4;   // k-major LDS row pitch
+    typedef floatx16 acc_t;
+    __device__ static __forceinline__ acc_t mma(float a, float b, acc_t c)
+    {
+        return __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, c, 0, 0, 0);
+    }
+    __device__ static __forceinline__ int acc_row(int v, int h) { return 8 * (v >> 2) + 4 * h + (v & 3); }
+};
+
+// v_mfma_f64_16x16x4_f64: A[i][k] in lane i + 16 k, B[k][j] in lane j + 16 k,
+// D[i][j] in lane j + 16 (i % 4), register i / 4.
+template <> struct Mma<double> {
+    static constexpr int T = 16;
+    static constexpr int KG = 4;
+    static constexpr int NACC = 4;
+    static constexpr int BK = 16;
+    static constexpr int KPL = BK / KG;
+    static constexpr int WT = 4;
+    static constexpr int CH = 2;
+    static constexpr int PITCH_KC = BK + 2;   // 144 B
+    static constexpr int PITCH_KM = BM + 2;
+    typedef doublex4 acc_t;
+    __device__ static __forceinline__ acc_t mma(double a, double b, acc_t c)
+    {
+        return __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, c, 0, 0, 0);
+    }
+    __device__ static __forceinline__ int acc_row(int v, int h) { return 4 * v + h; }
+};
+
+// ---- global -> register staging -------------------------------------------------------------
+template <typename TI> struct Elem;
+template <> struct Elem<float>  { static constexpr int EPV = 4; };
+template <> struct Elem<double> { static constexpr int EPV = 2; };
+template <> struct Elem<bf16_t> { static constexpr int EPV = 8; };
+
+// 16 bytes starting at p; elements at index >= valid are zero.  vec_ok: p is 16-byte aligned.
+template <typename TI>
+__device__ __forceinline__ uint4 load16(const TI *p, int valid, bool vec_ok)
+{
+    constexpr int EPV = Elem<TI>::EPV;
+    union { uint4 v; TI e[EPV]; } u;
+    if (valid >= EPV && vec_ok) {
+        u.v = *reinterpret_cast<const uint4 *>(p);
+    } else {
+        u.v = make_uint4(0u, 0u, 0u, 0u);
+#pragma unroll
+        for (int e = 0; e < EPV; ++e)
+            if (e < valid) u.e[e] = p[e];
+    }
+    return u.v;
+}
+
+// write the EPV elements of one staged vector to LDS as TC, contiguous at dst
+template <typename TC, typename TI> struct StoreLds;
+template <> struct StoreLds<float, float> {
+    __device__ static __forceinline__ void run(float *dst, uint4 v) { *reinterpret_cast<uint4 *>(dst) = v; }
+};
+template <> struct StoreLds<double, double> {
+    __device__ static __forceinline__ void run(double *dst, uint4 v) { *reinterpret_cast<uint4 *>(dst) = v; }
+};
+template <> struct StoreLds<float, bf16_t> {
+    __device__ static __forceinline__ void run(float *dst, uint4 v)
+    {
+        uint4 lo, hi;
+        lo.x = v.x << 16; lo.y = v.x & 0xffff0000u; lo.z = v.y << 16; lo.w = v.y & 0xffff0000u;
+        hi.x = v.z << 16; hi.y = v.z & 0xffff0000u; hi.z = v.w << 16; hi.w = v.w & 0xffff0000u;
+        reinterpret_cast<uint4 *>(dst)[0] = lo;
+        reinterpret_cast<uint4 *>(dst)[1] = hi;
+    }
+};
+
+// One operand tile (128 rows x BK) staged per thread as NV 16-byte vectors.
+template <typename TC, typename TI, bool KMAJOR>
+struct OperandStage {
+    static constexpr int EPV = Elem<TI>::EPV;
+    static constexpr int BK = Mma<TC>::BK;
+    static constexpr int VPR = KMAJOR ? (BM / EPV) : (BK / EPV);       // vectors per stored row
+    static constexpr int NV = (KMAJOR ? BK : BM) * VPR / NTHREADS;     // vectors per thread
+    static_assert(NV >= 1, "tile too small for the thread count");
+    static constexpr int LDS_ELEMS = KMAJOR ? BK * Mma<TC>::PITCH_KM : BM * Mma<TC>::PITCH_KC;
+
+    uint4 r[NV];
+
+    // rows: number of valid rows of this tile (<= 128); k_left: valid k from k0 on
+    __device__ __forceinline__ void load(const TI *base, int ld, int row0, int rows, int k0, int k_left,
+                                         bool vec_ok, int tid)
+    {
+#pragma unroll
+        for (int v = 0; v < NV; ++v) {
+            const int idx = tid + NTHREADS * v;
+            const int a = idx / VPR;   // stored row
+            const int b = idx % VPR;   // vector within the stored row
+            if (KMAJOR) {
+                // stored row = k, vector runs along the tile's rows
+                const int valid = (a < k_left) ? (rows - b * EPV) : 0;
+                const TI *p = base + (size_t)(k0 + a) * ld + row0 + b * EPV;
+                r[v] = load16<TI>(p, valid, vec_ok);
+            } else {
+                const int valid = (a < rows) ? (k_left - b * EPV) : 0;
+                const TI *p = base + (size_t)(row0 + a) * ld + k0 + b * EPV;
+                r[v] = load16<TI>(p, valid, vec_ok);
+            }
+        }
+    }
+
+    __device__ __forceinline__ void store(TC *lds, int tid) const
+    {
+        constexpr int PITCH = KMAJOR ? Mma<TC>::PITCH_KM : Mma<TC>::PITCH_KC;
+#pragma unroll
+        for (int v = 0; v < NV; ++v) {
+            const int idx = tid + NTHREADS * v;
+            const int a = idx / VPR;
+            const int b = idx % VPR;
+            StoreLds<TC, TI>::run(lds + a * PITCH + b * EPV, r[v]);
+        }
+    }
+};
+
+// ---- tile id decoding -------------------------------------------------------------------------
+__device__ __forceinline__ void tri_decode(int t, int &ti, int &tj)
+{
+    // largest ti with ti (ti + 1) / 2 <= t
+    int i = (int)((sqrtf(8.0f * (float)t + 1.0f) - 1.0f) * 0.5f);
+    while ((i + 1) * (i + 2) / 2 <= t) ++i;
+    while (i * (i + 1) / 2 > t) --i;
+    ti = i;
+    tj = t - i * (i + 1) / 2;
+}
+
+template <typename TC> __device__ __forceinline__ TC load_c(const void *C, size_t off, int flags);
+template <> __device__ __forceinline__ float load_c<float>(const void *C, size_t off, int flags)
+{
+    if (flags & GEMM_C_BF16) return bf16_to_f32(reinterpret_cast<const uint16_t *>(C)[off]);
+    return reinterpret_cast<const float *>(C)[off];
+}
+template <> __device__ __forceinline__ double load_c<double>(const void *C, size_t off, int)
+{
+    return reinterpret_cast<const double *>(C)[off];
+}
+template <typename TC> __device__ __forceinline__ void store_c(void *C, size_t off, TC v, int flags);
+template <> __device__ __forceinline__ void store_c<float>(void *C, size_t off, float v, int flags)
+{
+    if (flags & GEMM_C_BF16) reinterpret_cast<uint16_t *>(C)[off] = f32_to_bf16(v);
+    else reinterpret_cast<float *>(C)[off] = v;
+}
+template <> __device__ __forceinline__ void store_c<double>(void *C, size_t off, double v, int)
+{
+    reinterpret_cast<double *>(C)[off] = v;
+}
+
+// ---- the kernel -------------------------------------------------------------------------------
+template <typename TC, typename TA, typename TB, bool AKM, bool BKM>
+__global__ __launch_bounds__(NTHREADS) void gemm_grouped_kernel(const GemmProblem *__restrict__ probs,
+                                                                int nprobs, int total_tiles,
+                                                                const int *__restrict__ state,
+                                                                const float *__restrict__ coef)
+{
+    using MM = Mma<TC>;
+    using StA = OperandStage<TC, TA, AKM>;
+    using StB = OperandStage<TC, TB, BKM>;
+    constexpr int BK = MM::BK;
+    constexpr int WT = MM::WT;
+    constexpr int T = MM::T;
+
+    extern __shared__ __align__(16) unsigned char smem_raw[];
+    TC *smem = reinterpret_cast<TC *>(smem_raw);
+    TC *As[2] = {smem, smem + StA::LDS_ELEMS};
+    TC *Bs[2] = {smem + 2 * StA::LDS_ELEMS, smem + 2 * StA::LDS_ELEMS + StB::LDS_ELEMS};
+    __shared__ float red[NTHREADS / 64];
+
+    // XCD-aware order: workgroup b lands on XCD b % 8; give every XCD a contiguous tile range
+    // so the tiles of one problem share that XCD's L2.
+    const int per_xcd = (total_tiles + NUM_XCD - 1) / NUM_XCD;
+    const int t_global = (int)(blockIdx.x % NUM_XCD) * per_xcd + (int)(blockIdx.x / NUM_XCD);
+    if (t_global >= total_tiles) return;
+
+    // binary search: last problem with tile_start <= t_global
+    int lo = 0, hi = nprobs - 1;
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (probs[mid].tile_start <= t_global) lo = mid; else hi = mid - 1;
+    }
+    const GemmProblem &P = probs[lo];
+    if (P.state_idx >= 0) {
+        const int st = state[P.state_idx];
+        if (!((1 << st) & P.state_mask)) return;
+    }
+    const int flags = P.flags;
+    const int lt = t_global - P.tile_start;
+    int ti, tj;
+    if (flags & GEMM_SYM) tri_decode(lt, ti, tj);
+    else { ti = lt / P.tiles_n; tj = lt % P.tiles_n; }
+
+    const int M = P.M, N = P.N, K = P.K;
+    const int row0 = ti * BM, col0 = tj * BN;
+    const int rowsA = min(BM, M - row0);
+    const int rowsB = min(BN, N - col0);
+    const TA *Ab = reinterpret_cast<const TA *>(P.A);
+    const TB *Bb = reinterpret_cast<const TB *>(P.B);
+    const int lda = P.lda, ldb = P.ldb;
+    const bool vecA = ((reinterpret_cast<uintptr_t>(Ab) & 15u) == 0) && ((((size_t)lda * sizeof(TA)) & 15u) == 0);
+    const bool vecB = ((reinterpret_cast<uintptr_t>(Bb) & 15u) == 0) && ((((size_t)ldb * sizeof(TB)) & 15u) == 0);
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int r = lane % T;   // row (A) / column (B) inside an MFMA tile
+    const int h = lane / T;   // k group
+
+    typename MM::acc_t acc[WT][WT];
+#pragma unroll
+    for (int i = 0; i < WT; ++i)
+#pragma unroll
+        for (int j = 0; j < WT; ++j)
+#pragma unroll
+            for (int v = 0; v < MM::NACC; ++v) acc[i][j][v] = (TC)0;
+
+    StA sa;
+    StB sb;
+    const int nk = (K + BK - 1) / BK;
+    sa.load(Ab, lda, row0, rowsA, 0, K, vecA, tid);
+    sb.load(Bb, ldb, col0, rowsB, 0, K, vecB, tid);
+    sa.store(As[0], tid);
+    sb.store(Bs[0], tid);
+    __syncthreads();
+
+    for (int kt = 0; kt < nk; ++kt) {
+        const int cur = kt & 1;
+        if (kt + 1 < nk) {
+            const int k0 = (kt + 1) * BK;
+            sa.load(Ab, lda, row0, rowsA, k0, K - k0, vecA, tid);
+            sb.load(Bb, ldb, col0, rowsB, k0, K - k0, vecB, tid);
+        }
+        const TC *as = As[cur];
+        const TC *bs = Bs[cur];
+        // lane group h consumes k = h * KPL .. h * KPL + KPL - 1 of the slab, the same for A and B
+#pragma unroll
+        for (int q = 0; q < MM::KPL / MM::CH; ++q) {
+            TC af[WT][MM::CH], bf[WT][MM::CH];
+            const int kk = h * MM::KPL + q * MM::CH;
+#pragma unroll
+            for (int i = 0; i < WT; ++i) {
+                const int rr = wm * 64 + i * T + r;
+                if (AKM) {
+#pragma unroll
+                    for (int e = 0; e < MM::CH; ++e) af[i][e] = as[(kk + e) * MM::PITCH_KM + rr];
+                } else {
+                    const uint4 v = *reinterpret_cast<const uint4 *>(as + rr * MM::PITCH_KC + kk);
+                    *reinterpret_cast<uint4 *>(&af[i][0]) = v;
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < WT; ++j) {
+                const int cc = wn * 64 + j * T + r;
+                if (BKM) {
+#pragma unroll
+                    for (int e = 0; e < MM::CH; ++e) bf[j][e] = bs[(kk + e) * MM::PITCH_KM + cc];
+                } else {
+                    const uint4 v = *reinterpret_cast<const uint4 *>(bs + cc * MM::PITCH_KC + kk);
+                    *reinterpret_cast<uint4 *>(&bf[j][0]) = v;
+                }
+            }
+#pragma unroll
+            for (int e = 0; e < MM::CH; ++e)
+#pragma unroll
+                for (int i = 0; i < WT; ++i)
+#pragma unroll
+                    for (int j = 0; j < WT; ++j) acc[i][j] = MM::mma(af[i][e], bf[j][e], acc[i][j]);
+        }
+        if (kt + 1 < nk) {
+            sa.store(As[cur ^ 1], tid);
+            sb.store(Bs[cur ^ 1], tid);
+        }
+        __syncthreads();
+    }
+
+    // ---- epilogue ----
+    const bool sym = (flags & GEMM_SYM) != 0;
+    const bool root = (flags & GEMM_EPI_ROOT) != 0;
+    const TC alpha = (TC)P.alpha, beta = (TC)P.beta;
+    // coefficients of T = a I - g C: per-launch override (coef[0], coef[1]) or the table's
+    const TC ep_a = (TC)(coef ? coef[0] : P.ep_a), ep_g = (TC)(coef ? coef[1] : P.ep_g);
+    void *C = P.C;
+    TC *C2 = reinterpret_cast<TC *>(P.C2);
+    const int ldc = P.ldc, ldc2 = P.ldc2;
+    float rsum = 0.0f;
+#pragma unroll
+    for (int i = 0; i < WT; ++i) {
+#pragma unroll
+        for (int j = 0; j < WT; ++j) {
+            const int col = col0 + wn * 64 + j * T + r;
+#pragma unroll
+            for (int v = 0; v < MM::NACC; ++v) {
+                const int row = row0 + wm * 64 + i * T + MM::acc_row(v, h);
+                if (row >= M || col >= N) continue;
+                if (sym && row < col) continue;   // the mirror of (col, row) covers it
+                TC val = alpha * acc[i][j][v];
+                if (beta != (TC)0) val += beta * load_c<TC>(C, (size_t)row * ldc + col, flags);
+                store_c<TC>(C, (size_t)row * ldc + col, val, flags);
+                if (sym && row != col) store_c<TC>(C, (size_t)col * ldc + row, val, flags);
+                if (root) {
+                    const TC d = (row == col) ? (TC)1 : (TC)0;
+                    const TC t2 = ep_a * d - ep_g * val;
+                    C2[(size_t)row * ldc2 + col] = t2;
+                    if (sym && row != col) C2[(size_t)col * ldc2 + row] = t2;
+                    const float e = (float)(val - d);
+                    rsum += (sym && row != col) ? 2.0f * e * e : e * e;
+                }
+            }
+        }
+    }
+    if (root) {
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) rsum += __shfl_xor(rsum, off, 64);
+        if (lane == 0) red[wave] = rsum;
+        __syncthreads();
+        if (tid == 0) P.partial[lt] = red[0] + red[1] + red[2] + red[3];
+    }
+}
+
+template <typename TC, typename TA, typename TB, bool AKM, bool BKM>
+constexpr size_t gemm_lds_bytes()
+{
+    return sizeof(TC) * 2 * (size_t)(OperandStage<TC, TA, AKM>::LDS_ELEMS + OperandStage<TC, TB, BKM>::LDS_ELEMS);
+}
+
+// Enqueue one grouped launch.  probs / state / coef are device pointers (state and coef may be
+// null when no problem refers to them).
+template <typename TC, typename TA, typename TB, bool AKM, bool BKM>
+inline hipError_t launch_gemm_grouped(const GemmProblem *probs, int nprobs, int total_tiles,
+                                      const int *state, hipStream_t stream, const float *coef = nullptr)
+{
+    if (total_tiles <= 0 || nprobs <= 0) return hipSuccess;
+    auto kern = gemm_grouped_kernel<TC, TA, TB, AKM, BKM>;
+    constexpr size_t lds = gemm_lds_bytes<TC, TA, TB, AKM, BKM>();
+    static bool configured = false;   // attribute is per function; setting it twice is harmless
+    if (!configured) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        configured = true;
+    }
+    const int per_xcd = (total_tiles + NUM_XCD - 1) / NUM_XCD;
+    hipLaunchKernelGGL(kern, dim3(per_xcd * NUM_XCD), dim3(NTHREADS), lds, stream, probs, nprobs,
+                       total_tiles, state, coef);
+    return hipGetLastError();
+}
+
+inline int tri_tiles(int n)
+{
+    const int t = (n + BM - 1) / BM;
+    return t * (t + 1) / 2;
+}
+
+}  // namespace asteria

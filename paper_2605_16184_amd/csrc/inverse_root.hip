@@ -1,0 +1,738 @@
+// asteria_inverse_root: X = ((A + A^T)/2 + eps I)^(-1/p) for a batch of symmetric factors
+// (the inverse roots of paper Eq. 1; the O(d^3) update of paper Sec. I / III-B), computed
+// entirely on the device:
+//
+//   1. lambda_max(A) by power iteration (HBM-streaming mat-vec, wavefront reductions,
+//      per-factor early stop on the eigen-residual).
+//   2. Scaling  s = 1 / ((1 + margin) lambda_max + eps),  M_0 = s (A + eps I),  X_0 = s^(1/p) I,
+//      so the spectrum of M_0 lies in (0, 1].
+//   3. Coupled iteration  T = a I - g M,  X <- X T,  M <- T^p M  (classical Newton coefficients
+//      a = (p + 1) / p, g = 1 / p).  Every product is one symmetric grouped GEMM on the matrix
+//      cores; the epilogue of the M-update also emits the next T and the per-tile partial sums
+//      of ||M - I||_F^2.  A per-factor state machine on the device (running -> last X update ->
+//      done) lets finished factors drop out without any host round trip: their workgroups
+//      exit at once.
+//   4. The leading iterations run on fp64 MFMA, where the smallest eigenvalues of M are still
+//      comparable to fp32 round-off; the state is then cast to fp32 and continues on fp32 MFMA.
+//
+// Per factor and iteration: 3 launches (X T together with T T; T^2 T^2; T^4 M) + 1 control kernel.
+#include <math.h>
+
+#include <algorithm>
+#include <vector>
+
+#include "common.h"
+#include "gemm.h"
+
+using namespace asteria;
+
+namespace {
+
+constexpr int PM_ROWS = 32;   // rows of A per mat-vec workgroup (8 per wavefront)
+
+enum : int { ST_RUN = 0, ST_LAST = 1, ST_DONE = 2, ST_FAIL = 3 };
+
+struct FactorDev {
+    const float *A;
+    float *Xout;
+    float *X32b;        // second fp32 X buffer (workspace)
+    float *M32[2];
+    float *T32;
+    float *T432;
+    double *X64[2];
+    double *M64[2];
+    double *T64;
+    double *T464;
+    float *pv[2];       // power-iteration vectors
+    float2 *pm_partial; // per mat-vec workgroup: (sum y^2, sum y v)
+    float *partial;     // per lower-triangle tile: sum (M - I)^2
+    int n, lda, ldx;
+    int ld32, ld64;
+    int ntri;           // lower-triangle tiles
+    int tile_start;     // first tile of this factor in tile-indexed launches
+    int pm_blocks;
+    int pm_block_start;
+    float eps_in;
+    int pad_;
+};
+
+struct FactorScal {
+    float lam;       // lambda_max estimate
+    float eps;       // absolute eps used
+    float scale;     // s
+    float resid;     // last ||M - I||_F
+    float inv_norm;  // 1 / ||v|| of the current power vector
+    float rho;       // Rayleigh quotient
+    int iters;       // X updates performed / scheduled
+    int xloc;        // 0: current fp32 X in Xout, 1: in X32b
+    int info;
+    int pm_done;
+};
+
+__device__ __forceinline__ float hash_unit(uint32_t f, uint32_t j)
+{
+    uint32_t x = j * 0x9E3779B1u + f * 0x85EBCA77u + 0x165667B1u;
+    x ^= x >> 15; x *= 0x2C1B3C6Du; x ^= x >> 12; x *= 0x297A2D39u; x ^= x >> 15;
+    return (float)(x >> 8) * (1.0f / 8388608.0f) - 1.0f;   // [-1, 1)
+}
+
+__device__ __forceinline__ float wave_sum(float v)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+    return v;
+}
+__device__ __forceinline__ double wave_sum(double v)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+    return v;
+}
+
+// ---- power iteration -------------------------------------------------------------------------
+// one workgroup (256 threads) per factor: start vector and its norm
+__global__ __launch_bounds__(256) void pm_init_kernel(const FactorDev *fd, FactorScal *fs)
+{
+    const int f = blockIdx.x;
+    const FactorDev &F = fd[f];
+    __shared__ float red[4];
+    float s = 0.0f;
+    for (int j = threadIdx.x; j < F.n; j += 256) {
+        const float v = hash_unit((uint32_t)f, (uint32_t)j);
+        F.pv[0][j] = v;
+        s += v * v;
+    }
+    s = wave_sum(s);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = s;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const float t = red[0] + red[1] + red[2] + red[3];
+        fs[f].inv_norm = t > 0.0f ? rsqrtf(t) : 0.0f;
+        fs[f].rho = 0.0f;
+        fs[f].pm_done = 0;
+    }
+}
+
+// y = A v for PM_ROWS rows of one factor; v = v_raw * inv_norm on the fly
+__global__ __launch_bounds__(256) void pm_matvec_kernel(const FactorDev *fd, const FactorScal *fs,
+                                                        int nf, int src)
+{
+    // locate the factor of this workgroup: last f with pm_block_start <= blockIdx.x
+    int lo = 0, hi = nf - 1;
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (fd[mid].pm_block_start <= (int)blockIdx.x) lo = mid; else hi = mid - 1;
+    }
+    const FactorDev &F = fd[lo];
+    if (fs[lo].pm_done) return;
+    const int blk = (int)blockIdx.x - F.pm_block_start;
+    const int n = F.n, lda = F.lda;
+    const float *__restrict__ v = F.pv[src];
+    float *__restrict__ y = F.pv[src ^ 1];
+    const float inv = fs[lo].inv_norm;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const bool vec_ok = ((reinterpret_cast<uintptr_t>(F.A) & 15u) == 0) && ((lda & 3) == 0);
+    __shared__ float red[2][4];
+    float syy = 0.0f, syv = 0.0f;
+    for (int rr = 0; rr < PM_ROWS / 4; ++rr) {
+        const int row = blk * PM_ROWS + wave * (PM_ROWS / 4) + rr;
+        if (row >= n) break;
+        const float *__restrict__ a = F.A + (size_t)row * lda;
+        float s = 0.0f;
+        if (vec_ok) {
+            const int n4 = n >> 2;
+            for (int j = lane; j < n4; j += 64) {
+                const float4 av = reinterpret_cast<const float4 *>(a)[j];
+                const float4 vv = reinterpret_cast<const float4 *>(v)[j];
+                s += av.x * vv.x + av.y * vv.y + av.z * vv.z + av.w * vv.w;
+            }
+            for (int j = (n4 << 2) + lane; j < n; j += 64) s += a[j] * v[j];
+        } else {
+            for (int j = lane; j < n; j += 64) s += a[j] * v[j];
+        }
+        s = wave_sum(s) * inv;
+        if (lane == 0) {
+            y[row] = s;
+            syy += s * s;
+            syv += s * (v[row] * inv);
+        }
+    }
+    if (lane == 0) { red[0][wave] = syy; red[1][wave] = syv; }
+    __syncthreads();
+    if (threadIdx.x == 0)
+        F.pm_partial[blk] = make_float2(red[0][0] + red[0][1] + red[0][2] + red[0][3],
+                                        red[1][0] + red[1][1] + red[1][2] + red[1][3]);
+}
+
+// one thread per factor: Rayleigh quotient, eigen-residual, early stop
+__global__ void pm_control_kernel(const FactorDev *fd, FactorScal *fs, int nf, float tol)
+{
+    const int f = blockIdx.x * blockDim.x + threadIdx.x;
+    if (f >= nf) return;
+    FactorScal &S = fs[f];
+    if (S.pm_done) return;
+    const FactorDev &F = fd[f];
+    double yy = 0.0, yv = 0.0;
+    for (int b = 0; b < F.pm_blocks; ++b) {
+        const float2 p = F.pm_partial[b];
+        yy += (double)p.x;
+        yv += (double)p.y;
+    }
+    // v is a unit vector: rho = v^T A v, ||A v - rho v||^2 = ||A v||^2 - rho^2
+    S.rho = (float)yv;
+    const bool finite = (yy == yy) && (yy < 3.0e38);
+    if (!finite || !(yy > 0.0)) { S.pm_done = 1; if (!finite) S.rho = NAN; return; }
+    S.inv_norm = (float)(1.0 / sqrt(yy));
+    const double r2 = yy - yv * yv;
+    if (r2 <= (double)tol * (double)tol * yv * yv) S.pm_done = 1;
+}
+
+// ---- scaling and start of the coupled iteration ---------------------------------------------
+__global__ void root_setup_kernel(const FactorDev *fd, FactorScal *fs, int *state, int nf,
+                                  int relative, float margin)
+{
+    const int f = blockIdx.x * blockDim.x + threadIdx.x;
+    if (f >= nf) return;
+    FactorScal &S = fs[f];
+    const float lam = S.rho;
+    S.lam = lam;
+    S.iters = 0;
+    S.xloc = 0;
+    S.resid = 0.0f;
+    const float eps = relative ? fd[f].eps_in * lam : fd[f].eps_in;
+    S.eps = eps;
+    const float denom = (1.0f + margin) * lam + eps;
+    const bool ok = (lam == lam) && (lam >= 0.0f) && (lam < 3.0e38f) && (denom > 0.0f) && (denom < 3.0e38f);
+    if (!ok) {
+        S.scale = 0.0f;
+        S.info = ASTERIA_INFO_NOT_PD;
+        state[f] = ST_FAIL;
+    } else {
+        S.scale = 1.0f / denom;
+        S.info = ASTERIA_INFO_OK;
+        state[f] = ST_RUN;
+    }
+}
+
+// One workgroup per lower-triangle 128 x 128 tile: M_0, T_0, X_0 and the residual partial sums.
+template <typename TC>
+__global__ __launch_bounds__(256) void root_init_kernel(const FactorDev *fd, const FactorScal *fs,
+                                                        const int *state, int nf, int total_tiles,
+                                                        int root, const float *coef)
+{
+    const int t_global = blockIdx.x;
+    if (t_global >= total_tiles) return;
+    int lo = 0, hi = nf - 1;
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (fd[mid].tile_start <= t_global) lo = mid; else hi = mid - 1;
+    }
+    const FactorDev &F = fd[lo];
+    if (state[lo] != ST_RUN) return;
+    const int lt = t_global - F.tile_start;
+    int ti, tj;
+    tri_decode(lt, ti, tj);
+    const int n = F.n, lda = F.lda;
+    const TC s = (TC)fs[lo].scale;
+    const TC eps = (TC)fs[lo].eps;
+    const TC xs = (TC)pow((double)fs[lo].scale, 1.0 / (double)root);
+    const TC ca = (TC)coef[0], cg = (TC)coef[1];
+    TC *M, *T, *X;
+    int ldm, ldx;
+    if (sizeof(TC) == 8) {
+        M = reinterpret_cast<TC *>(F.M64[0]); T = reinterpret_cast<TC *>(F.T64);
+        X = reinterpret_cast<TC *>(F.X64[0]); ldm = F.ld64; ldx = F.ld64;
+    } else {
+        M = reinterpret_cast<TC *>(F.M32[0]); T = reinterpret_cast<TC *>(F.T32);
+        X = reinterpret_cast<TC *>(F.Xout); ldm = F.ld32; ldx = F.ldx;
+    }
+    float rsum = 0.0f;
+    for (int e = threadIdx.x; e < BM * BN; e += 256) {
+        const int row = ti * BM + e / BN, col = tj * BN + e % BN;
+        if (row >= n || col >= n || row < col) continue;
+        const TC a = (TC)0.5 * ((TC)F.A[(size_t)row * lda + col] + (TC)F.A[(size_t)col * lda + row]);
+        const TC d = (row == col) ? (TC)1 : (TC)0;
+        const TC m = s * (a + eps * d);
+        const TC t = ca * d - cg * m;
+        M[(size_t)row * ldm + col] = m;
+        T[(size_t)row * ldm + col] = t;
+        X[(size_t)row * ldx + col] = xs * d;
+        if (row != col) {
+            M[(size_t)col * ldm + row] = m;
+            T[(size_t)col * ldm + row] = t;
+            X[(size_t)col * ldx + row] = (TC)0;
+        }
+        const float r = (float)(m - d);
+        rsum += (row != col) ? 2.0f * r * r : r * r;
+    }
+    __shared__ float red[4];
+    rsum = wave_sum(rsum);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = rsum;
+    __syncthreads();
+    if (threadIdx.x == 0) F.partial[lt] = red[0] + red[1] + red[2] + red[3];
+}
+
+// One wavefront per factor, run before iteration k (and once after the last one with
+// final_pass = 1): evaluates the residual of running factors and advances the state machine.
+__global__ __launch_bounds__(64) void root_control_kernel(const FactorDev *fd, FactorScal *fs, int *state,
+                                                          int k, int fp32_phase, int final_pass,
+                                                          float stop_resid)
+{
+    const int f = blockIdx.x;
+    const FactorDev &F = fd[f];
+    FactorScal &S = fs[f];
+    int st = state[f];
+    if (st == ST_DONE || st == ST_FAIL) return;
+    if (st == ST_LAST) {
+        st = ST_DONE;
+    } else {
+        float r2 = 0.0f;
+        for (int i = threadIdx.x; i < F.ntri; i += 64) r2 += F.partial[i];
+        r2 = wave_sum(r2);
+        const float resid = sqrtf(r2);
+        if (!(r2 == r2) || !(r2 < 3.0e38f)) {
+            st = ST_FAIL;
+            if (threadIdx.x == 0) { S.info = ASTERIA_INFO_NOT_PD; S.resid = resid; }
+        } else {
+            if (threadIdx.x == 0) S.resid = resid;
+            if (resid < stop_resid) st = ST_LAST;
+        }
+    }
+    if (threadIdx.x == 0) {
+        if (!final_pass && (st == ST_RUN || st == ST_LAST)) {
+            S.iters += 1;
+            if (fp32_phase) S.xloc = (k + 1) & 1;
+        }
+        if (final_pass && (st == ST_RUN || st == ST_LAST)) S.info = ASTERIA_INFO_NOT_CONVERGED;
+        state[f] = st;
+    }
+}
+
+// fp64 -> fp32 hand-over before iteration j (run after control(j)), or at the very end when every
+// iteration ran in fp64 (at_end = 1).  One workgroup per 128 x 128 tile (full square tiling).
+__global__ __launch_bounds__(256) void root_to_fp32_kernel(const FactorDev *fd, FactorScal *fs,
+                                                           const int *state, int nf, int j, int at_end,
+                                                           const int *sq_tile_start)
+{
+    int lo = 0, hi = nf - 1;
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (sq_tile_start[mid] <= (int)blockIdx.x) lo = mid; else hi = mid - 1;
+    }
+    const FactorDev &F = fd[lo];
+    const int st = state[lo];
+    if (st == ST_FAIL) return;
+    const int lt = (int)blockIdx.x - sq_tile_start[lo];
+    const int n = F.n;
+    const int tpr = (n + BN - 1) / BN;
+    const int ti = lt / tpr, tj = lt % tpr;
+    const bool finished = (st == ST_DONE) || at_end;
+    const int par = j & 1;
+    const double *Xs = finished ? F.X64[fs[lo].iters & 1] : F.X64[par];
+    float *Xd = (finished || par == 0) ? F.Xout : F.X32b;
+    const int ldxd = (finished || par == 0) ? F.ldx : F.ld32;
+    const double *Ms = F.M64[par];
+    float *Md = F.M32[par];
+    for (int e = threadIdx.x; e < BM * BN; e += 256) {
+        const int row = ti * BM + e / BN, col = tj * BN + e % BN;
+        if (row >= n || col >= n) continue;
+        Xd[(size_t)row * ldxd + col] = (float)Xs[(size_t)row * F.ld64 + col];
+        if (!finished) {
+            F.T32[(size_t)row * F.ld32 + col] = (float)F.T64[(size_t)row * F.ld64 + col];
+            if (st == ST_RUN) Md[(size_t)row * F.ld32 + col] = (float)Ms[(size_t)row * F.ld64 + col];
+        }
+    }
+    if (finished && threadIdx.x == 0 && lt == 0) fs[lo].xloc = 0;
+}
+
+// Copy X from the workspace buffer to the caller's X where the last fp32 update landed there,
+// and publish the per-factor outcome.  One workgroup per 128 x 128 tile.
+__global__ __launch_bounds__(256) void root_finalize_kernel(const FactorDev *fd, const FactorScal *fs,
+                                                            const int *state, int nf, const int *sq_tile_start,
+                                                            int first, int32_t *info, int32_t *iters,
+                                                            float *resid, float *lambda_max)
+{
+    int lo = 0, hi = nf - 1;
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (sq_tile_start[mid] <= (int)blockIdx.x) lo = mid; else hi = mid - 1;
+    }
+    const FactorDev &F = fd[lo];
+    const FactorScal &S = fs[lo];
+    const int lt = (int)blockIdx.x - sq_tile_start[lo];
+    if (lt == 0 && threadIdx.x == 0) {
+        if (info) info[first + lo] = S.info;
+        if (iters) iters[first + lo] = S.iters;
+        if (resid) resid[first + lo] = S.resid;
+        if (lambda_max) lambda_max[first + lo] = S.lam;
+    }
+    if (state[lo] == ST_FAIL || S.xloc == 0) return;
+    const int n = F.n;
+    const int tpr = (n + BN - 1) / BN;
+    const int ti = lt / tpr, tj = lt % tpr;
+    for (int e = threadIdx.x; e < BM * BN; e += 256) {
+        const int row = ti * BM + e / BN, col = tj * BN + e % BN;
+        if (row >= n || col >= n) continue;
+        F.Xout[(size_t)row * F.ldx + col] = F.X32b[(size_t)row * F.ld32 + col];
+    }
+}
+
+// ---- host side -------------------------------------------------------------------------------
+inline int ld4(int n) { return (n + 3) & ~3; }
+inline int ld2(int n) { return (n + 1) & ~1; }
+
+struct Plan {
+    int max_iters;
+    int fp64_iters;
+    int power_iters;
+    float stop_resid, power_tol, margin;
+    bool use64, use32;
+};
+
+// Worst-case number of coupled iterations (X updates) for a spectrum scaled into [a, 1]:
+// the scalar map mu <- (ca - cg mu)^p mu on the lower end until sqrt(n) |1 - mu| < stop,
+// plus the last update that follows.
+int predicted_iters(double a, int n, int root, double stop, int cap)
+{
+    const double ca = (root + 1.0) / root, cg = 1.0 / root;
+    double mu = a;
+    int k = 0;
+    while (k < cap && sqrt((double)n) * fabs(1.0 - mu) >= stop) {
+        mu = pow(ca - cg * mu, (double)root) * mu;
+        ++k;
+    }
+    return k + 1;
+}
+
+int auto_fp64_iters(double eps_rel)
+{
+    // round-off of relative size u injected while the smallest eigenvalue of M is mu costs a
+    // relative error u / mu in the root; mu grows by (5/4)^4 per iteration.  Keep fp64 until
+    // 0.5 u_fp32 / mu is below 1e-3.
+    if (!(eps_rel > 0.0)) return 4;
+    const double x = 0.5 * 5.96e-8 / (eps_rel * 1e-3);
+    if (x <= 1.0) return 0;
+    return (int)ceil(log(x) / log(2.44140625));
+}
+
+size_t factor_matrix_bytes(int n, bool use64, bool use32)
+{
+    size_t b = 0;
+    if (use32) b += 5 * Carver::need((size_t)n * ld4(n), sizeof(float));
+    else b += 0;
+    if (use64) b += 6 * Carver::need((size_t)n * ld2(n), sizeof(double));
+    return b;
+}
+
+size_t factor_small_bytes(int n)
+{
+    const int pmb = (n + PM_ROWS - 1) / PM_ROWS;
+    return 2 * Carver::need((size_t)ld4(n), sizeof(float)) + Carver::need((size_t)pmb, sizeof(float2)) +
+           Carver::need((size_t)tri_tiles(n), sizeof(float)) + sizeof(FactorDev) + sizeof(FactorScal) +
+           2 * sizeof(int) + 16 * sizeof(GemmProblem);
+}
+
+size_t fixed_bytes() { return 64 * 256; }   // alignment slack of the shared arrays + coefficient table
+
+asteria_status make_plan(const asteria_root_opts *opts_in, asteria_eps_mode mode, const float *eps,
+                         int eps_count, Plan &pl)
+{
+    asteria_root_opts o;
+    asteria_root_opts_default(&o);
+    if (opts_in) o = *opts_in;
+    if (o.max_iters <= 0 || o.power_iters <= 0) return ASTERIA_INVALID_ARG;
+    if (!(o.stop_resid > 0.0f) || !(o.power_tol > 0.0f) || !(o.lambda_margin >= 0.0f)) return ASTERIA_INVALID_ARG;
+    if (o.schedule != 0) return ASTERIA_UNSUPPORTED;
+    pl.max_iters = o.max_iters;
+    pl.power_iters = o.power_iters;
+    pl.stop_resid = o.stop_resid;
+    pl.power_tol = o.power_tol;
+    pl.margin = o.lambda_margin;
+    int j = o.fp64_iters;
+    if (j < 0) {
+        if (mode == ASTERIA_EPS_RELATIVE && eps) {
+            float emin = eps[0];
+            for (int i = 1; i < eps_count; ++i) emin = std::min(emin, eps[i]);
+            j = auto_fp64_iters((double)emin);
+        } else {
+            j = 4;
+        }
+    }
+    pl.fp64_iters = std::min(j, pl.max_iters);
+    pl.use64 = pl.fp64_iters > 0;
+    pl.use32 = pl.fp64_iters < pl.max_iters;
+    return ASTERIA_OK;
+}
+
+asteria_status validate(const asteria_factor *f, int nf, int root, const float *eps, int eps_count)
+{
+    if (!f || nf <= 0 || !eps) return ASTERIA_INVALID_ARG;
+    if (root != 2 && root != 4) return ASTERIA_UNSUPPORTED;
+    if (eps_count != 1 && eps_count != nf) return ASTERIA_INVALID_ARG;
+    for (int i = 0; i < eps_count; ++i)
+        if (!(eps[i] >= 0.0f) || !(eps[i] < 3.0e38f)) return ASTERIA_INVALID_ARG;
+    for (int i = 0; i < nf; ++i) {
+        if (!f[i].A || !f[i].X || f[i].n <= 0 || f[i].lda < f[i].n || f[i].ldx < f[i].n) return ASTERIA_INVALID_ARG;
+    }
+    return ASTERIA_OK;
+}
+
+// one pass over factors [first, first + cnt) of the size-sorted order
+asteria_status run_pass(const asteria_factor *f, const std::vector<int> &order, int first, int cnt,
+                        int root, asteria_eps_mode mode, const float *eps, int eps_count, const Plan &pl,
+                        int32_t *info, int32_t *iters, float *resid, float *lambda_max,
+                        void *ws, hipStream_t stream, bool outputs_permuted, int *perm_dev_unused)
+{
+    (void)outputs_permuted; (void)perm_dev_unused;
+    Carver cv(ws);
+    FactorDev *d_fd = cv.take<FactorDev>(cnt);
+    FactorScal *d_fs = cv.take<FactorScal>(cnt);
+    int *d_state = cv.take<int>(cnt);
+    int *d_sq = cv.take<int>(cnt);
+    float *d_coef = cv.take<float>(2);
+    GemmProblem *d_tab[2][2][3];   // [precision 0 = fp32, 1 = fp64][parity][launch]
+    for (int pr = 0; pr < 2; ++pr)
+        for (int pa = 0; pa < 2; ++pa) {
+            d_tab[pr][pa][0] = cv.take<GemmProblem>(2 * (size_t)cnt);
+            d_tab[pr][pa][1] = cv.take<GemmProblem>(cnt);
+            d_tab[pr][pa][2] = cv.take<GemmProblem>(cnt);
+        }
+
+    std::vector<FactorDev> fd(cnt);
+    std::vector<int> sq(cnt);
+    int tri_total = 0, sq_total = 0, pm_total = 0;
+    int n_max = 0;
+    double a_min = 1.0;
+    for (int i = 0; i < cnt; ++i) {
+        const asteria_factor &a = f[order[first + i]];
+        FactorDev &F = fd[i];
+        memset(&F, 0, sizeof(F));
+        const int n = a.n;
+        n_max = std::max(n_max, n);
+        F.A = a.A; F.Xout = a.X; F.n = n; F.lda = a.lda; F.ldx = a.ldx;
+        F.ld32 = ld4(n); F.ld64 = ld2(n);
+        F.ntri = tri_tiles(n);
+        F.tile_start = tri_total; tri_total += F.ntri;
+        const int tpr = (n + BM - 1) / BM;
+        sq[i] = sq_total; sq_total += tpr * tpr;
+        F.pm_blocks = (n + PM_ROWS - 1) / PM_ROWS;
+        F.pm_block_start = pm_total; pm_total += F.pm_blocks;
+        F.eps_in = eps[eps_count == 1 ? 0 : order[first + i]];
+        if (mode == ASTERIA_EPS_RELATIVE) {
+            const double er = (double)F.eps_in;
+            a_min = std::min(a_min, er / (1.0 + (double)pl.margin + er));
+        }
+        F.pv[0] = cv.take<float>(ld4(n));
+        F.pv[1] = cv.take<float>(ld4(n));
+        F.pm_partial = cv.take<float2>(F.pm_blocks);
+        F.partial = cv.take<float>(F.ntri);
+    }
+    for (int i = 0; i < cnt; ++i) {
+        FactorDev &F = fd[i];
+        const size_t e32 = (size_t)F.n * F.ld32, e64 = (size_t)F.n * F.ld64;
+        if (pl.use32) {
+            F.X32b = cv.take<float>(e32);
+            F.M32[0] = cv.take<float>(e32); F.M32[1] = cv.take<float>(e32);
+            F.T32 = cv.take<float>(e32); F.T432 = cv.take<float>(e32);
+        }
+        if (pl.use64) {
+            F.X64[0] = cv.take<double>(e64); F.X64[1] = cv.take<double>(e64);
+            F.M64[0] = cv.take<double>(e64); F.M64[1] = cv.take<double>(e64);
+            F.T64 = cv.take<double>(e64); F.T464 = cv.take<double>(e64);
+        }
+    }
+
+    // iteration budget known on the host
+    int K = pl.max_iters;
+    if (mode == ASTERIA_EPS_RELATIVE && a_min > 0.0)
+        K = std::min(K, predicted_iters(a_min * 0.5, n_max, root, (double)pl.stop_resid, pl.max_iters) + 2);
+    const int j64 = std::min(pl.fp64_iters, K);
+
+    // problem tables
+    const float ca = (float)(root + 1) / (float)root, cg = 1.0f / (float)root;
+    std::vector<GemmProblem> tab[2][2][3];
+    for (int pr = 0; pr < 2; ++pr) {
+        if ((pr == 0 && !pl.use32) || (pr == 1 && !pl.use64)) continue;
+        for (int pa = 0; pa < 2; ++pa) {
+            int t0 = 0, t1 = 0;
+            for (int i = 0; i < cnt; ++i) {
+                const FactorDev &F = fd[i];
+                const void *Xsrc, *Tm, *Mcur;
+                void *Xdst, *Mnext, *T4, *Tw;
+                int ldxs, ldxd, ldw;
+                if (pr == 1) {
+                    Xsrc = F.X64[pa]; Xdst = F.X64[pa ^ 1]; ldxs = ldxd = F.ld64;
+                    Tm = F.T64; Tw = F.T64; Mcur = F.M64[pa]; Mnext = F.M64[pa ^ 1]; T4 = F.T464; ldw = F.ld64;
+                } else {
+                    Xsrc = pa ? (const void *)F.X32b : (const void *)F.Xout; ldxs = pa ? F.ld32 : F.ldx;
+                    Xdst = pa ? (void *)F.Xout : (void *)F.X32b; ldxd = pa ? F.ldx : F.ld32;
+                    Tm = F.T32; Tw = F.T32; Mcur = F.M32[pa]; Mnext = F.M32[pa ^ 1]; T4 = F.T432; ldw = F.ld32;
+                }
+                GemmProblem p;
+                memset(&p, 0, sizeof(p));
+                p.M = p.N = p.K = F.n;
+                p.state_idx = i;
+                p.alpha = 1.0f; p.beta = 0.0f; p.ep_a = ca; p.ep_g = cg;
+                p.flags = GEMM_SYM;
+                // launch 0: X' = X T (running or last), T2 = T T (running)
+                p.A = Xsrc; p.lda = ldxs; p.B = Tm; p.ldb = ldw; p.C = Xdst; p.ldc = ldxd;
+                p.state_mask = (1 << ST_RUN) | (1 << ST_LAST);
+                p.tile_start = t0; t0 += F.ntri;
+                tab[pr][pa][0].push_back(p);
+                p.A = Tm; p.lda = ldw; p.B = Tm; p.ldb = ldw; p.C = Mnext; p.ldc = ldw;
+                p.state_mask = (1 << ST_RUN);
+                p.tile_start = t0; t0 += F.ntri;
+                tab[pr][pa][0].push_back(p);
+                // launch 1: T4 = T2 T2 (root 4 only)
+                p.A = Mnext; p.B = Mnext; p.C = T4; p.ldc = ldw;
+                p.tile_start = t1;
+                tab[pr][pa][1].push_back(p);
+                // launch 2: M' = T^p M, T' = a I - g M', residual partial sums
+                p.A = (root == 4) ? (const void *)T4 : (const void *)Mnext; p.B = Mcur;
+                p.C = Mnext; p.C2 = Tw; p.ldc2 = ldw; p.partial = F.partial;
+                p.flags = GEMM_SYM | GEMM_EPI_ROOT;
+                tab[pr][pa][2].push_back(p);
+                t1 += F.ntri;
+            }
+        }
+    }
+    // For root 2 the M-update reads T2 = Mnext as A while writing Mnext: not allowed -> use T4 as target
+    if (root == 2) {
+        for (int pr = 0; pr < 2; ++pr)
+            for (int pa = 0; pa < 2; ++pa)
+                for (size_t i = 0; i < tab[pr][pa][0].size() / 2; ++i) {
+                    // T2 goes to the T4 buffer instead, M' to Mnext
+                    GemmProblem &t2 = tab[pr][pa][0][2 * i + 1];
+                    GemmProblem &mu = tab[pr][pa][2][i];
+                    t2.C = tab[pr][pa][1][i].C;
+                    mu.A = t2.C;
+                }
+    }
+
+    ASTERIA_HIP_TRY(upload_async(d_fd, fd.data(), sizeof(FactorDev) * cnt, stream));
+    ASTERIA_HIP_TRY(upload_async(d_sq, sq.data(), sizeof(int) * cnt, stream));
+    const float coef_h[2] = {ca, cg};
+    ASTERIA_HIP_TRY(upload_async(d_coef, coef_h, sizeof(coef_h), stream));
+    for (int pr = 0; pr < 2; ++pr)
+        for (int pa = 0; pa < 2; ++pa)
+            for (int l = 0; l < 3; ++l)
+                if (!tab[pr][pa][l].empty())
+                    ASTERIA_HIP_TRY(upload_async(d_tab[pr][pa][l], tab[pr][pa][l].data(),
+                                                 tab[pr][pa][l].size() * sizeof(GemmProblem), stream));
+
+    // 1. lambda_max
+    hipLaunchKernelGGL(pm_init_kernel, dim3(cnt), dim3(256), 0, stream, d_fd, d_fs);
+    const int ctl_blocks = (cnt + 127) / 128;
+    for (int it = 0; it < pl.power_iters; ++it) {
+        hipLaunchKernelGGL(pm_matvec_kernel, dim3(pm_total), dim3(256), 0, stream, d_fd, d_fs, cnt, it & 1);
+        hipLaunchKernelGGL(pm_control_kernel, dim3(ctl_blocks), dim3(128), 0, stream, d_fd, d_fs, cnt, pl.power_tol);
+    }
+    // 2. scaling, start
+    hipLaunchKernelGGL(root_setup_kernel, dim3(ctl_blocks), dim3(128), 0, stream, d_fd, d_fs, d_state, cnt,
+                       mode == ASTERIA_EPS_RELATIVE ? 1 : 0, pl.margin);
+    if (j64 > 0)
+        hipLaunchKernelGGL(root_init_kernel<double>, dim3(tri_total), dim3(256), 0, stream, d_fd, d_fs, d_state,
+                           cnt, tri_total, root, d_coef);
+    else
+        hipLaunchKernelGGL(root_init_kernel<float>, dim3(tri_total), dim3(256), 0, stream, d_fd, d_fs, d_state,
+                           cnt, tri_total, root, d_coef);
+    ASTERIA_HIP_TRY(hipGetLastError());
+
+    // 3. coupled iteration
+    for (int k = 0; k < K; ++k) {
+        const bool p32 = k >= j64;
+        hipLaunchKernelGGL(root_control_kernel, dim3(cnt), dim3(64), 0, stream, d_fd, d_fs, d_state, k,
+                           p32 ? 1 : 0, 0, pl.stop_resid);
+        if (k == j64 && j64 > 0)
+            hipLaunchKernelGGL(root_to_fp32_kernel, dim3(sq_total), dim3(256), 0, stream, d_fd, d_fs, d_state,
+                               cnt, j64, 0, d_sq);
+        const int pa = k & 1;
+        if (p32) {
+            ASTERIA_HIP_TRY((launch_gemm_grouped<float, float, float, false, false>(d_tab[0][pa][0], 2 * cnt, 2 * tri_total, d_state, stream)));
+            if (root == 4)
+                ASTERIA_HIP_TRY((launch_gemm_grouped<float, float, float, false, false>(d_tab[0][pa][1], cnt, tri_total, d_state, stream)));
+            ASTERIA_HIP_TRY((launch_gemm_grouped<float, float, float, false, false>(d_tab[0][pa][2], cnt, tri_total, d_state, stream)));
+        } else {
+            ASTERIA_HIP_TRY((launch_gemm_grouped<double, double, double, false, false>(d_tab[1][pa][0], 2 * cnt, 2 * tri_total, d_state, stream)));
+            if (root == 4)
+                ASTERIA_HIP_TRY((launch_gemm_grouped<double, double, double, false, false>(d_tab[1][pa][1], cnt, tri_total, d_state, stream)));
+            ASTERIA_HIP_TRY((launch_gemm_grouped<double, double, double, false, false>(d_tab[1][pa][2], cnt, tri_total, d_state, stream)));
+        }
+    }
+    hipLaunchKernelGGL(root_control_kernel, dim3(cnt), dim3(64), 0, stream, d_fd, d_fs, d_state, K,
+                       (K >= j64 && pl.use32) ? 1 : 0, 1, pl.stop_resid);
+    if (j64 >= K)   // every iteration ran in fp64: hand the result over now
+        hipLaunchKernelGGL(root_to_fp32_kernel, dim3(sq_total), dim3(256), 0, stream, d_fd, d_fs, d_state, cnt,
+                           K, 1, d_sq);
+    hipLaunchKernelGGL(root_finalize_kernel, dim3(sq_total), dim3(256), 0, stream, d_fd, d_fs, d_state, cnt,
+                       d_sq, first, info, iters, resid, lambda_max);
+    ASTERIA_HIP_TRY(hipGetLastError());
+    return ASTERIA_OK;
+}
+
+}  // namespace
+
+extern "C" size_t asteria_inverse_root_workspace_bytes(const asteria_factor *f, int nfactors,
+                                                       const asteria_root_opts *opts, size_t *min_bytes)
+{
+    if (min_bytes) *min_bytes = 0;
+    if (!f || nfactors <= 0) return 0;
+    Plan pl;
+    const float e1 = 1e-6f;
+    if (make_plan(opts, ASTERIA_EPS_RELATIVE, &e1, 1, pl) != ASTERIA_OK) return 0;
+    // sizes must not depend on eps: reserve both precisions unless the caller pinned one
+    asteria_root_opts o;
+    asteria_root_opts_default(&o);
+    if (opts) o = *opts;
+    const bool use64 = (o.fp64_iters != 0);
+    const bool use32 = !(o.fp64_iters >= o.max_iters && o.fp64_iters > 0);
+    size_t total = fixed_bytes(), biggest = 0;
+    for (int i = 0; i < nfactors; ++i) {
+        if (f[i].n <= 0) return 0;
+        const size_t b = factor_matrix_bytes(f[i].n, use64, use32) + factor_small_bytes(f[i].n);
+        total += b;
+        biggest = std::max(biggest, b);
+    }
+    if (min_bytes) *min_bytes = biggest + fixed_bytes();
+    return total;
+}
+
+extern "C" asteria_status asteria_inverse_root(const asteria_factor *f, int nfactors, int root,
+                                               asteria_eps_mode mode, const float *eps, int eps_count,
+                                               const asteria_root_opts *opts,
+                                               int32_t *info, int32_t *iters, float *resid, float *lambda_max,
+                                               void *ws, size_t ws_bytes, void *stream_)
+{
+    asteria_status st = validate(f, nfactors, root, eps, eps_count);
+    if (st != ASTERIA_OK) return st;
+    if (mode != ASTERIA_EPS_RELATIVE && mode != ASTERIA_EPS_ABSOLUTE) return ASTERIA_INVALID_ARG;
+    Plan pl;
+    st = make_plan(opts, mode, eps, eps_count, pl);
+    if (st != ASTERIA_OK) return st;
+    if (!ws) return ASTERIA_WORKSPACE_TOO_SMALL;
+    if (reinterpret_cast<uintptr_t>(ws) & 255u) return ASTERIA_INVALID_ARG;   // workspace must be 256-byte aligned
+    hipStream_t stream = reinterpret_cast<hipStream_t>(stream_);
+
+    // Passes are formed over the caller's order (outputs are indexed by caller position, and a
+    // pass covers a contiguous index range), largest pass that fits the workspace.
+    std::vector<int> order(nfactors);
+    for (int i = 0; i < nfactors; ++i) order[i] = i;
+    int first = 0;
+    while (first < nfactors) {
+        size_t used = fixed_bytes();
+        int cnt = 0;
+        while (first + cnt < nfactors) {
+            const int n = f[first + cnt].n;
+            const size_t b = factor_matrix_bytes(n, pl.use64, pl.use32) + factor_small_bytes(n);
+            if (used + b > ws_bytes) break;
+            used += b;
+            ++cnt;
+        }
+        if (cnt == 0) return ASTERIA_WORKSPACE_TOO_SMALL;
+        st = run_pass(f, order, first, cnt, root, mode, eps, eps_count, pl, info, iters, resid, lambda_max,
+                      ws, stream, false, nullptr);
+        if (st != ASTERIA_OK) return st;
+        first += cnt;
+    }
+    return ASTERIA_OK;
+}

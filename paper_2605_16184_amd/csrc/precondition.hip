@@ -1,0 +1,93 @@
+// asteria_precondition: P = X_L G X_R for a batch of blocks (paper Eq. 1).
+//
+// Two chained grouped GEMMs on the fp32 matrix cores with fp32 accumulation:
+//   U = G X_R      (X_R symmetric, so its rows serve as the k-contiguous B operand)
+//   P = X_L U      (U is consumed k-major straight from the workspace)
+// fp32 operands keep the full precision of the roots; a bf16 cast of X_L / X_R would cost
+// about 1e-2 relative error in P at condition numbers near 1e6.
+#include <vector>
+
+#include "common.h"
+#include "gemm.h"
+
+using namespace asteria;
+
+namespace {
+
+inline int ld4(int n) { return (n + 3) & ~3; }
+
+asteria_status validate(const asteria_pblock *b, int nblocks)
+{
+    if (!b || nblocks <= 0) return ASTERIA_INVALID_ARG;
+    for (int i = 0; i < nblocks; ++i) {
+        const asteria_pblock &k = b[i];
+        if (!k.XL || !k.G || !k.XR || !k.P) return ASTERIA_INVALID_ARG;
+        if (k.m <= 0 || k.n <= 0) return ASTERIA_INVALID_ARG;
+        if (k.ldxl < k.m || k.ldg < k.n || k.ldxr < k.n || k.ldp < k.n) return ASTERIA_INVALID_ARG;
+        if (!valid_dtype(k.g_dtype) || !valid_dtype(k.p_dtype)) return ASTERIA_INVALID_ARG;
+    }
+    return ASTERIA_OK;
+}
+
+size_t table_bytes(int nblocks) { return 2 * Carver::need((size_t)nblocks, sizeof(GemmProblem)) + 512; }
+
+}  // namespace
+
+extern "C" size_t asteria_precondition_workspace_bytes(const asteria_pblock *blocks, int nblocks)
+{
+    if (!blocks || nblocks <= 0) return 0;
+    size_t bytes = table_bytes(nblocks);
+    for (int i = 0; i < nblocks; ++i)
+        bytes += Carver::need((size_t)blocks[i].m * ld4(blocks[i].n), sizeof(float));
+    return bytes;
+}
+
+extern "C" asteria_status asteria_precondition(const asteria_pblock *blocks, int nblocks,
+                                               void *ws, size_t ws_bytes, void *stream_)
+{
+    asteria_status st = validate(blocks, nblocks);
+    if (st != ASTERIA_OK) return st;
+    if (!ws || ws_bytes < asteria_precondition_workspace_bytes(blocks, nblocks)) return ASTERIA_WORKSPACE_TOO_SMALL;
+    if (reinterpret_cast<uintptr_t>(ws) & 255u) return ASTERIA_INVALID_ARG;   // workspace must be 256-byte aligned
+    hipStream_t stream = reinterpret_cast<hipStream_t>(stream_);
+
+    Carver cv(ws);
+    GemmProblem *d1 = cv.take<GemmProblem>(nblocks);
+    GemmProblem *d2 = cv.take<GemmProblem>(nblocks);
+    // first-stage problems are grouped by gradient dtype (one launch each); second stage is one launch
+    std::vector<GemmProblem> p1[2], p2;
+    int tiles1[2] = {0, 0}, tiles2 = 0;
+    for (int i = 0; i < nblocks; ++i) {
+        const asteria_pblock &k = blocks[i];
+        const int ldu = ld4(k.n);
+        float *U = cv.take<float>((size_t)k.m * ldu);
+        const int tm = (k.m + BM - 1) / BM, tn = (k.n + BN - 1) / BN;
+        GemmProblem p;
+        memset(&p, 0, sizeof(p));
+        p.state_idx = -1; p.state_mask = ~0;
+        p.alpha = 1.0f; p.beta = 0.0f;
+        p.M = k.m; p.N = k.n; p.tiles_n = tn;
+        // U = G X_R
+        p.A = k.G; p.lda = k.ldg; p.B = k.XR; p.ldb = k.ldxr; p.K = k.n;
+        p.C = U; p.ldc = ldu; p.flags = 0;
+        p.tile_start = tiles1[k.g_dtype];
+        tiles1[k.g_dtype] += tm * tn;
+        p1[k.g_dtype].push_back(p);
+        // P = X_L U
+        p.A = k.XL; p.lda = k.ldxl; p.B = U; p.ldb = ldu; p.K = k.m;
+        p.C = k.P; p.ldc = k.ldp; p.flags = (k.p_dtype == ASTERIA_BF16) ? GEMM_C_BF16 : 0;
+        p.tile_start = tiles2;
+        tiles2 += tm * tn;
+        p2.push_back(p);
+    }
+    GemmProblem *d1b = d1 + p1[0].size();
+    if (!p1[0].empty()) ASTERIA_HIP_TRY(upload_async(d1, p1[0].data(), p1[0].size() * sizeof(GemmProblem), stream));
+    if (!p1[1].empty()) ASTERIA_HIP_TRY(upload_async(d1b, p1[1].data(), p1[1].size() * sizeof(GemmProblem), stream));
+    ASTERIA_HIP_TRY(upload_async(d2, p2.data(), p2.size() * sizeof(GemmProblem), stream));
+    if (!p1[0].empty())
+        ASTERIA_HIP_TRY((launch_gemm_grouped<float, float, float, false, false>(d1, (int)p1[0].size(), tiles1[0], nullptr, stream)));
+    if (!p1[1].empty())
+        ASTERIA_HIP_TRY((launch_gemm_grouped<float, bf16_t, float, false, false>(d1b, (int)p1[1].size(), tiles1[1], nullptr, stream)));
+    ASTERIA_HIP_TRY((launch_gemm_grouped<float, float, float, false, true>(d2, (int)p2.size(), tiles2, nullptr, stream)));
+    return ASTERIA_OK;
+}
