@@ -193,6 +193,19 @@ asteria_status asteria_soap_step(const asteria_sblock *blocks, int nblocks,
                                  float beta1, float beta2, float adam_eps, int step_t,
                                  void *ws, size_t ws_bytes, void *stream);
 
+/* ---- measurement aid (not part of the method) -----------------------------------------------
+ * Between asteria_profile_enable and asteria_profile_collect every grouped-GEMM launch made by
+ * the entry points above is bracketed by a pair of HIP events on the caller's stream (at most
+ * max_launches launches are recorded; the events are created on the host, no device memory).
+ * asteria_profile_collect waits for the recorded events, writes one duration in milliseconds and
+ * one kernel-kind code per launch, in launch order, into the HOST arrays ms / kind (capacity
+ * cap), destroys the events, switches recording off and returns the number of entries written
+ * (-1 if recording was not on).  kind bits: 1 = fp64 matrix cores (else fp32), 2 = A operand
+ * bf16, 4 = B operand bf16, 8 = A read k-major, 16 = B read k-major.  Not thread safe; this is
+ * the only process-wide state the library has.                                                 */
+asteria_status asteria_profile_enable(int max_launches);
+int asteria_profile_collect(float *ms, int32_t *kind, int cap);
+
 #ifdef __cplusplus
 }
 #endif

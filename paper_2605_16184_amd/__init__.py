@@ -23,4 +23,6 @@ from .binding import (  # noqa: F401
     Factors,
     PBlocks,
     SBlocks,
+    profile_enable,
+    profile_collect,
 )

@@ -105,6 +105,10 @@ def lib():
         L.asteria_soap_step.restype = c_int
         L.asteria_soap_step.argtypes = [POINTER(_SBlock), c_int, c_float, c_float, c_float, c_int,
                                         c_void_p, c_size_t, c_void_p]
+        L.asteria_profile_enable.restype = c_int
+        L.asteria_profile_enable.argtypes = [c_int]
+        L.asteria_profile_collect.restype = c_int
+        L.asteria_profile_collect.argtypes = [POINTER(c_float), POINTER(c_int32), c_int]
         _lib = L
     return _lib
 
@@ -338,3 +342,18 @@ def soap_step(blocks, beta1: float, beta2: float, adam_eps: float, step_t: int,
     ws = _workspace(ws, soap_step_workspace_bytes(b), dev)
     _check(lib().asteria_soap_step(b.array, b.count, float(beta1), float(beta2), float(adam_eps), int(step_t),
                                    c_void_p(ws.data_ptr()), ws.numel(), _stream(stream)), "asteria_soap_step")
+
+
+def profile_enable(max_launches: int = 4096) -> None:
+    """Start bracketing every grouped-GEMM launch with HIP events (measurement aid)."""
+    _check(lib().asteria_profile_enable(int(max_launches)), "asteria_profile_enable")
+
+
+def profile_collect(cap: int = 4096):
+    """Stop recording; returns [(milliseconds, kind)] per launch in launch order."""
+    ms = (c_float * cap)()
+    kind = (c_int32 * cap)()
+    n = lib().asteria_profile_collect(ms, kind, cap)
+    if n < 0:
+        raise AsteriaError(INVALID_ARG, "asteria_profile_collect")
+    return [(ms[i], kind[i]) for i in range(n)]

@@ -1,5 +1,8 @@
 // Version, status strings and option defaults.
+#include <vector>
+
 #include "common.h"
+#include "gemm.h"
 
 extern "C" int asteria_version(void) { return 100; }
 
@@ -26,4 +29,62 @@ extern "C" void asteria_root_opts_default(asteria_root_opts *o)
     o->power_tol = 1e-3f;
     o->lambda_margin = 0.01f;
     o->reserved = 0;
+}
+
+// ---- measurement aid: HIP events around every grouped-GEMM launch ----------------------------
+namespace {
+struct ProfileState {
+    bool on = false;
+    int cap = 0;
+    std::vector<hipEvent_t> ev;   // 2 per recorded launch
+    std::vector<int> kind;
+} g_prof;
+}  // namespace
+
+void asteria::profile_begin(int kind, hipStream_t stream)
+{
+    if (!g_prof.on || (int)g_prof.kind.size() >= g_prof.cap) return;
+    hipEvent_t a, b;
+    if (hipEventCreate(&a) != hipSuccess) return;
+    if (hipEventCreate(&b) != hipSuccess) { (void)hipEventDestroy(a); return; }
+    g_prof.ev.push_back(a);
+    g_prof.ev.push_back(b);
+    g_prof.kind.push_back(kind);
+    (void)hipEventRecord(a, stream);
+}
+
+void asteria::profile_end(hipStream_t stream)
+{
+    if (!g_prof.on || g_prof.ev.empty() || g_prof.ev.size() != 2 * g_prof.kind.size()) return;
+    // the end event of the launch opened last; a launch skipped by the cap opened nothing
+    (void)hipEventRecord(g_prof.ev.back(), stream);
+}
+
+extern "C" asteria_status asteria_profile_enable(int max_launches)
+{
+    if (max_launches <= 0 || g_prof.on) return ASTERIA_INVALID_ARG;
+    g_prof.on = true;
+    g_prof.cap = max_launches;
+    g_prof.ev.clear();
+    g_prof.kind.clear();
+    return ASTERIA_OK;
+}
+
+extern "C" int asteria_profile_collect(float *ms, int32_t *kind, int cap)
+{
+    if (!g_prof.on) return -1;
+    g_prof.on = false;
+    const int n = (int)g_prof.kind.size();
+    int out = 0;
+    for (int i = 0; i < n; ++i) {
+        float t = 0.0f;
+        (void)hipEventSynchronize(g_prof.ev[2 * i + 1]);
+        const bool ok = hipEventElapsedTime(&t, g_prof.ev[2 * i], g_prof.ev[2 * i + 1]) == hipSuccess;
+        if (ok && out < cap && ms && kind) { ms[out] = t; kind[out] = g_prof.kind[i]; ++out; }
+        (void)hipEventDestroy(g_prof.ev[2 * i]);
+        (void)hipEventDestroy(g_prof.ev[2 * i + 1]);
+    }
+    g_prof.ev.clear();
+    g_prof.kind.clear();
+    return out;
 }

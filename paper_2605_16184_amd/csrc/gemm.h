@@ -55,6 +55,10 @@ struct GemmProblem {
     int pad_;
 };
 
+// Measurement aid (see asteria_profile_enable): bracket a launch with HIP events on its stream.
+void profile_begin(int kind, hipStream_t stream);
+void profile_end(hipStream_t stream);
+
 constexpr int BM = 128;
 constexpr int BN = 128;
 constexpr int NTHREADS = 256;
@@ -418,8 +422,12 @@ inline hipError_t launch_gemm_grouped(const GemmProblem *probs, int nprobs, int 
         configured = true;
     }
     const int per_xcd = (total_tiles + NUM_XCD - 1) / NUM_XCD;
+    constexpr int kind = (sizeof(TC) == 8 ? 1 : 0) | (sizeof(TA) == 2 ? 2 : 0) | (sizeof(TB) == 2 ? 4 : 0) |
+                         (AKM ? 8 : 0) | (BKM ? 16 : 0);
+    profile_begin(kind, stream);
     hipLaunchKernelGGL(kern, dim3(per_xcd * NUM_XCD), dim3(NTHREADS), lds, stream, probs, nprobs,
                        total_tiles, state, coef);
+    profile_end(stream);
     return hipGetLastError();
 }
 

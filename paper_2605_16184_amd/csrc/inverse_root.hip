@@ -98,7 +98,8 @@ __global__ __launch_bounds__(256) void pm_init_kernel(const FactorDev *fd, Facto
     __shared__ float red[4];
     float s = 0.0f;
     for (int j = threadIdx.x; j < F.n; j += 256) {
-        const float v = hash_unit((uint32_t)f, (uint32_t)j);
+        // the same start vector for every factor: a factor's result does not depend on its place in the batch
+        const float v = hash_unit(0u, (uint32_t)j);
         F.pv[0][j] = v;
         s += v * v;
     }

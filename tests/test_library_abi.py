@@ -1,0 +1,175 @@
+"""CPU-only checks of the C-ABI library: it loads, exports every symbol the header declares,
+and rejects bad arguments on the host before anything is launched (no GPU needed)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2605_16184_amd as ast
+from paper_2605_16184_amd import binding as B
+from paper_2605_16184_amd import workloads as W
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "asteria.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    names = set(re.findall(r"\b(asteria_[a-z0-9_]+)\s*\(", hdr))
+    assert {"asteria_stats_update", "asteria_inverse_root", "asteria_precondition", "asteria_soap_refresh",
+            "asteria_soap_step"} <= names
+    lib = ast.lib()
+    for n in sorted(names):
+        assert hasattr(lib, n), f"{n} declared in asteria.h but not exported"
+
+
+def test_version_status_strings_and_default_options():
+    assert ast.version() >= 100
+    assert ast.status_string(B.OK) == "ok"
+    assert "workspace" in ast.status_string(B.WORKSPACE_TOO_SMALL)
+    o = ast.RootOpts()
+    assert (o.max_iters, o.fp64_iters, o.power_iters, o.schedule) == (40, -1, 256, 0)
+    assert abs(o.stop_resid - 1e-2) < 1e-9 and abs(o.power_tol - 1e-3) < 1e-9 and abs(o.lambda_margin - 0.01) < 1e-9
+
+
+def _blk(**kw):
+    b = B._Block()
+    b.G, b.L, b.R = 0x1000, 0x2000, 0x3000
+    b.m = b.n = 8
+    b.ldg = b.ldl = b.ldr = 8
+    b.g_dtype = B.F32
+    for k, v in kw.items():
+        setattr(b, k, v)
+    return (B._Block * 1)(b)
+
+
+def test_stats_update_rejects_bad_arguments_without_launching():
+    f = ast.lib().asteria_stats_update
+    ws = ctypes.c_void_p(0x10000)
+    assert f(None, 1, 0.9, ws, 1 << 20, None) == B.INVALID_ARG
+    assert f(_blk(), 0, 0.9, ws, 1 << 20, None) == B.INVALID_ARG
+    assert f(_blk(), 1, 1.0, ws, 1 << 20, None) == B.INVALID_ARG
+    assert f(_blk(), 1, -0.1, ws, 1 << 20, None) == B.INVALID_ARG
+    assert f(_blk(G=None), 1, 0.9, ws, 1 << 20, None) == B.INVALID_ARG
+    assert f(_blk(m=0), 1, 0.9, ws, 1 << 20, None) == B.INVALID_ARG
+    assert f(_blk(ldg=7), 1, 0.9, ws, 1 << 20, None) == B.INVALID_ARG
+    assert f(_blk(ldl=7), 1, 0.9, ws, 1 << 20, None) == B.INVALID_ARG
+    assert f(_blk(g_dtype=5), 1, 0.9, ws, 1 << 20, None) == B.INVALID_ARG
+    assert f(_blk(L=None, R=None), 1, 0.9, ws, 1 << 20, None) == B.INVALID_ARG
+    assert f(_blk(), 1, 0.9, None, 0, None) == B.WORKSPACE_TOO_SMALL
+    assert f(_blk(), 1, 0.9, ws, 16, None) == B.WORKSPACE_TOO_SMALL
+    assert f(_blk(), 1, 0.9, ctypes.c_void_p(0x10010), 1 << 20, None) == B.INVALID_ARG   # misaligned workspace
+
+
+def _fac(**kw):
+    a = B._Factor()
+    a.A, a.X, a.n, a.lda, a.ldx = 0x1000, 0x2000, 8, 8, 8
+    for k, v in kw.items():
+        setattr(a, k, v)
+    return (B._Factor * 1)(a)
+
+
+def test_inverse_root_rejects_bad_arguments_without_launching():
+    f = ast.lib().asteria_inverse_root
+    eps = (ctypes.c_float * 1)(1e-6)
+    ws = ctypes.c_void_p(0x10000)
+    args = lambda fac=_fac(), n=1, root=4, mode=0, e=eps, ec=1, opts=None, w=ws, wb=1 << 30: (
+        fac, n, root, mode, e, ec, opts, None, None, None, None, w, wb, None)
+    assert f(*args(fac=None)) == B.INVALID_ARG
+    assert f(*args(n=0)) == B.INVALID_ARG
+    assert f(*args(root=3)) == B.UNSUPPORTED
+    assert f(*args(root=8)) == B.UNSUPPORTED
+    assert f(*args(mode=7)) == B.INVALID_ARG
+    assert f(*args(e=None)) == B.INVALID_ARG
+    assert f(*args(ec=2)) == B.INVALID_ARG
+    assert f(*args(e=(ctypes.c_float * 1)(-1.0))) == B.INVALID_ARG
+    assert f(*args(e=(ctypes.c_float * 1)(float("nan")))) == B.INVALID_ARG
+    assert f(*args(fac=_fac(A=None))) == B.INVALID_ARG
+    assert f(*args(fac=_fac(n=-1))) == B.INVALID_ARG
+    assert f(*args(fac=_fac(lda=4))) == B.INVALID_ARG
+    bad = ast.RootOpts(max_iters=0)
+    assert f(*args(opts=ctypes.byref(bad))) == B.INVALID_ARG
+    bad = ast.RootOpts(schedule=9)
+    assert f(*args(opts=ctypes.byref(bad))) == B.UNSUPPORTED
+    assert f(*args(w=None)) == B.WORKSPACE_TOO_SMALL
+    assert f(*args(wb=64)) == B.WORKSPACE_TOO_SMALL
+
+
+def test_precondition_and_soap_reject_bad_arguments_without_launching():
+    lib = ast.lib()
+    ws = ctypes.c_void_p(0x10000)
+    p = B._PBlock()
+    p.XL, p.G, p.XR, p.P = 0x1000, 0x2000, 0x3000, 0x4000
+    p.m, p.n, p.ldxl, p.ldg, p.ldxr, p.ldp = 4, 6, 4, 6, 6, 6
+    arr = (B._PBlock * 1)(p)
+    assert lib.asteria_precondition(arr, 1, None, 0, None) == B.WORKSPACE_TOO_SMALL
+    p.ldp = 5
+    assert lib.asteria_precondition((B._PBlock * 1)(p), 1, ws, 1 << 20, None) == B.INVALID_ARG
+    p.ldp = 6
+    p.p_dtype = 3
+    assert lib.asteria_precondition((B._PBlock * 1)(p), 1, ws, 1 << 20, None) == B.INVALID_ARG
+    assert lib.asteria_precondition(None, 1, ws, 1 << 20, None) == B.INVALID_ARG
+
+    s = B._SBlock()
+    s.G, s.QL, s.QR, s.M, s.V, s.N = 0x1000, 0x2000, 0x3000, 0x4000, 0x5000, 0x6000
+    s.m, s.n = 4, 6
+    s.ldg = s.ldqr = s.ldm = s.ldv = s.ldn = 6
+    s.ldql = 4
+    one = (B._SBlock * 1)(s)
+    assert lib.asteria_soap_step(one, 1, 0.9, 0.95, 1e-8, 0, ws, 1 << 20, None) == B.INVALID_ARG   # t >= 1
+    assert lib.asteria_soap_step(one, 1, 1.0, 0.95, 1e-8, 1, ws, 1 << 20, None) == B.INVALID_ARG
+    assert lib.asteria_soap_step(one, 1, 0.9, 0.95, 1e-8, 1, None, 0, None) == B.WORKSPACE_TOO_SMALL
+    s.ldql = 3
+    assert lib.asteria_soap_step((B._SBlock * 1)(s), 1, 0.9, 0.95, 1e-8, 1, ws, 1 << 20, None) == B.INVALID_ARG
+    assert lib.asteria_soap_refresh(None, 1, None, ws, 1 << 20, None) == B.INVALID_ARG
+    assert lib.asteria_soap_refresh(_fac(ldx=2), 1, None, ws, 1 << 20, None) == B.INVALID_ARG
+    assert lib.asteria_soap_refresh(_fac(), 1, None, None, 0, None) == B.WORKSPACE_TOO_SMALL
+    assert lib.asteria_soap_refresh(_fac(), 1, None, ws, 128, None) == B.WORKSPACE_TOO_SMALL
+
+
+def test_workspace_queries_scale_with_the_batch():
+    one = _fac(n=1024, lda=1024, ldx=1024)
+    mn = ctypes.c_size_t(0)
+    full = ast.lib().asteria_inverse_root_workspace_bytes(one, 1, None, ctypes.byref(mn))
+    # default options reserve 5 fp32 and 6 fp64 work matrices per factor
+    assert full >= (5 * 4 + 6 * 8) * 1024 * 1024 and full < 1.1 * (5 * 4 + 6 * 8) * 1024 * 1024
+    assert mn.value == full
+    o = ast.RootOpts(fp64_iters=0)
+    f32 = ast.lib().asteria_inverse_root_workspace_bytes(one, 1, ctypes.byref(o), None)
+    assert 5 * 4 * 1024 * 1024 <= f32 < 1.1 * 5 * 4 * 1024 * 1024
+    assert ast.lib().asteria_inverse_root_workspace_bytes(None, 1, None, None) == 0
+
+
+def test_model_block_census_matches_the_1p1b_configuration():
+    mats = W.llama_1b_matrices()
+    blocks = W.block_shapes(mats, 1024)
+    by_shape, by_factor, params = W.census(blocks)
+    assert params == 1_099_956_224 and len(blocks) == 1184
+    assert by_shape == {(1024, 1024): 960, (256, 1024): 92, (512, 1024): 88, (1024, 512): 44}
+    assert by_factor == {1024: 2144, 512: 132, 256: 92}
+    blocks = W.block_shapes(mats, 2048)
+    by_shape, by_factor, params = W.census(blocks)
+    assert len(blocks) == 318 and by_factor == {2048: 524, 1536: 66, 1280: 2, 256: 44}
+    assert W.split_dim(5632, 1024) == [1024] * 5 + [512] and W.split_dim(32000, 2048)[-1] == 1280
+
+
+def test_generators_are_seeded_and_shaped():
+    import torch
+    a = W.lowrank_block(64, 48, "cpu", 1, 2)
+    b = W.lowrank_block(64, 48, "cpu", 1, 2)
+    c = W.lowrank_block(64, 48, "cpu", 1, 3)
+    assert a.dtype == torch.bfloat16 and a.shape == (64, 48)
+    assert torch.equal(a, b) and not torch.equal(a, c)
+    q = W.haar(32, "cpu", 0, dtype=torch.float64)
+    assert q.is_contiguous() and torch.allclose(q.T @ q, torch.eye(32, dtype=torch.float64), atol=1e-12)
+    g = W.spectrum_block(q, q, W.powerlaw_sigma(32, "cpu"), "cpu", 9, rms=None, dtype=torch.float64)
+    s = torch.linalg.svdvals(g)
+    assert torch.allclose(s, W.powerlaw_sigma(32, "cpu"), atol=1e-12)
+
+
+def test_binding_refuses_cpu_tensors_and_wrong_shapes():
+    import torch
+    G = torch.zeros(4, 6)
+    with pytest.raises(ValueError):
+        ast.Blocks([(G, torch.zeros(4, 4), torch.zeros(6, 6))])

@@ -1,0 +1,434 @@
+"""GPU parity tests: every entry point of the C ABI is compared, stage by stage, with the
+float64 CPU oracle fed exactly the arrays the GPU call consumed.
+
+Tolerances (relative Frobenius error):
+  statistics                <= 1e-5   (fp32 accumulation of exact bf16 products + fp32 EMA)
+  inverse roots             <= 2e-3
+  preconditioned gradients  <= 1e-2   (also SOAP updates)
+  eigenbasis                ||Q^T Q - I||_F / sqrt(n) <= 1e-5, backward error <= 1e-5
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2605_16184_amd as ast
+from paper_2605_16184_amd import binding as B
+from paper_2605_16184_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+TOL_STATS, TOL_ROOT, TOL_PRECOND = 1e-5, 2e-3, 1e-2
+DEV = "cuda"
+
+
+def np64(t: torch.Tensor) -> np.ndarray:
+    return t.detach().to("cpu", torch.float32).double().numpy()
+
+
+def relF(a, b) -> float:
+    a = np64(a) if isinstance(a, torch.Tensor) else np.asarray(a)
+    b = np64(b) if isinstance(b, torch.Tensor) else np.asarray(b)
+    return float(np.linalg.norm(a - b) / np.linalg.norm(b))
+
+
+def padded(rows: int, cols: int, pad: int, dtype=torch.float32, fill=None) -> torch.Tensor:
+    """rows x cols view into a (cols + pad)-wide buffer; the pad columns hold a sentinel."""
+    buf = torch.full((rows, cols + pad), -777.0 if fill is None else fill, device=DEV, dtype=dtype)
+    return buf[:, :cols]
+
+
+def spd(n: int, *key: int) -> torch.Tensor:
+    a = W.gaussian_block(n, n, 1.0, DEV, 99, *key)
+    s = a @ a.T / n
+    return (0.5 * (s + s.T)).contiguous()
+
+
+def powerlaw_factor(n: int, *key: int) -> torch.Tensor:
+    """fp32 statistic with eigenvalues (1/i)^2 (times the EMA weight 0.05), built in fp64."""
+    U = W.haar(n, DEV, *key, dtype=torch.float64)
+    lam = 0.05 * W.powerlaw_sigma(n, DEV) ** 2
+    A = (U * lam) @ U.T
+    return (0.5 * (A + A.T)).float().contiguous()
+
+
+def logspaced_factor(n: int, decades: float, *key: int) -> torch.Tensor:
+    U = W.haar(n, DEV, *key, dtype=torch.float64)
+    lam = 0.05 * W.logspaced_sigma(n, decades, DEV) ** 2
+    A = (U * lam) @ U.T
+    return (0.5 * (A + A.T)).float().contiguous()
+
+
+def run_roots(As, eps, relative=True, root=4, opts=None, ws=None):
+    Xs = [torch.full_like(A, float("nan")) for A in As]
+    k = len(As)
+    info = torch.full((k,), -1, dtype=torch.int32, device=DEV)
+    iters = torch.full((k,), -1, dtype=torch.int32, device=DEV)
+    resid = torch.zeros(k, device=DEV)
+    lmax = torch.zeros(k, device=DEV)
+    ast.inverse_root(list(zip(As, Xs)), eps, relative=relative, root=root, opts=opts, info=info, iters=iters,
+                     resid=resid, lambda_max=lmax, ws=ws)
+    torch.cuda.synchronize()
+    return Xs, info.cpu().numpy(), iters.cpu().numpy(), resid.cpu().numpy(), lmax.cpu().numpy()
+
+
+# =============================================================================== a1 statistics
+
+def test_stats_single_fp32_block_eight_ema_updates_from_identity():
+    n = 128
+    L = torch.eye(n, device=DEV); R = torch.eye(n, device=DEV)
+    Lo, Ro = np.eye(n), np.eye(n)
+    for k in range(8):
+        G = W.gaussian_block(n, n, 0.01, DEV, 1, k)
+        Lin, Rin = np64(L), np64(R)
+        ast.stats_update([(G, L, R)], 0.95)
+        torch.cuda.synchronize()
+        Ls, Rs = oracle.stats_update(np64(G), Lin, Rin, 0.95)       # stage-wise: same inputs
+        assert relF(L, Ls) <= TOL_STATS and relF(R, Rs) <= TOL_STATS
+        Lo, Ro = oracle.stats_update(np64(G), Lo, Ro, 0.95)          # chained float64 pipeline
+    assert relF(L, Lo) <= TOL_STATS and relF(R, Ro) <= TOL_STATS
+    assert torch.equal(L, L.T) and torch.equal(R, R.T)
+
+
+def test_stats_ragged_batch_bf16_and_fp32_with_padded_leading_dimensions():
+    shapes = [(200, 328, torch.bfloat16), (1, 1, torch.float32), (3, 5, torch.bfloat16), (130, 257, torch.float32),
+              (256, 1024, torch.bfloat16), (129, 127, torch.bfloat16)]
+    items, refs = [], []
+    for i, (m, n, dt) in enumerate(shapes):
+        G = padded(m, n, 3 if i % 2 else 0, dt, fill=5.0)
+        G.copy_(W.gaussian_block(m, n, 0.1, DEV, 2, i, dtype=dt))
+        L = padded(m, m, 5); L.copy_(spd(m, 1, i))
+        R = padded(n, n, 0); R.copy_(spd(n, 2, i))
+        refs.append(oracle.stats_update(np64(G), np64(L), np64(R), 0.9))
+        items.append((G, L, R))
+    ast.stats_update(items, 0.9)
+    torch.cuda.synchronize()
+    for (G, L, R), (Lo, Ro) in zip(items, refs):
+        assert relF(L, Lo) <= TOL_STATS and relF(R, Ro) <= TOL_STATS
+        assert torch.equal(L, L.T) and torch.equal(R, R.T)
+        assert torch.all(L._base[:, L.shape[1]:] == -777.0)     # pad columns untouched
+
+
+def test_stats_one_sided_update_leaves_the_other_factor_alone():
+    G = W.gaussian_block(70, 90, 0.1, DEV, 3, dtype=torch.bfloat16)
+    L = spd(70, 3); R = spd(90, 4); R0 = R.clone()
+    Lo, _ = oracle.stats_update(np64(G), np64(L), np64(R), 0.5)
+    ast.stats_update([(G, L, None)], 0.5)
+    torch.cuda.synchronize()
+    assert relF(L, Lo) <= TOL_STATS and torch.equal(R, R0)
+
+
+def test_stats_full_size_1024_block_lowrank_bf16():
+    n = 1024
+    G = W.lowrank_block(n, n, DEV, 0)
+    L = torch.zeros(n, n, device=DEV); R = torch.zeros(n, n, device=DEV)
+    ast.stats_update([(G, L, R)], 0.95)
+    torch.cuda.synchronize()
+    Lo, Ro = oracle.stats_update(np64(G), np.zeros((n, n)), np.zeros((n, n)), 0.95)
+    assert relF(L, Lo) <= TOL_STATS and relF(R, Ro) <= TOL_STATS
+
+
+# =============================================================================== a2 inverse roots
+
+def test_root_single_block_config_absolute_and_relative_eps():
+    n = 128
+    L = torch.eye(n, device=DEV); R = torch.eye(n, device=DEV)
+    for k in range(8):
+        ast.stats_update([(W.gaussian_block(n, n, 0.01, DEV, 1, k), L, R)], 0.95)
+    for A in (L, R):
+        Xo, lmax_o, lam = oracle.inverse_root(np64(A), 1e-6)
+        assert lam.max() / lam.min() < 1.05
+        (X,), info, iters, resid, lmax = run_roots([A], 1e-6)
+        assert info[0] == B.INFO_OK and 1 <= iters[0] <= 4
+        # nearly flat spectrum (width ~1%): the power iteration stops on its eigen-residual test at
+        # once, so lambda_max is only known to within that width; eps = 1e-6 lambda_max then moves
+        # by the same fraction, which changes the root by < 1e-8 because every eigenvalue >> eps
+        assert abs(lmax[0] - lmax_o) <= 1.5e-2 * lmax_o
+        assert relF(X, Xo) <= TOL_ROOT
+        (Xa,), info, _, _, _ = run_roots([A], 1e-6 * lmax_o, relative=False)
+        assert info[0] == B.INFO_OK and relF(Xa, Xo) <= 1e-5
+        assert torch.equal(Xa, Xa.T)
+
+
+@pytest.mark.parametrize("n", [200, 320])
+def test_root_powerlaw_spectrum_ragged_sizes(n):
+    A = powerlaw_factor(n, 11)
+    Xo, lmax_o, lam = oracle.inverse_root(np64(A), 1e-6)
+    for j in (0, -1, 40):       # fp32 only, automatic fp64 prefix, fp64 throughout
+        (X,), info, iters, resid, lmax = run_roots([A], 1e-6, opts=ast.RootOpts(fp64_iters=j))
+        assert info[0] == B.INFO_OK
+        assert abs(lmax[0] - lmax_o) <= 1e-4 * lmax_o
+        assert relF(X, Xo) <= TOL_ROOT, (j, relF(X, Xo))
+        assert torch.equal(X, X.T)
+    assert relF(X, Xo) <= 1e-5      # the fp64 run is limited only by the fp32 output and lambda_max
+
+
+def test_root_of_lowrank_statistics_from_the_gpu_stats_kernel():
+    # batch-of-64 workload in miniature: rank-32 + noise gradients, ~all eigenvalues on the eps floor
+    n = 256
+    G = W.lowrank_block(n, n, DEV, 7)
+    L = torch.zeros(n, n, device=DEV); R = torch.zeros(n, n, device=DEV)
+    ast.stats_update([(G, L, R)], 0.95)
+    Xs, info, iters, resid, lmax = run_roots([L, R], 1e-6)
+    for A, X, i in zip((L, R), Xs, range(2)):
+        st, Xo, lmax_o, lam = oracle.inverse_root(np64(A), 1e-6, return_status=True)
+        assert st == oracle.OK
+        assert info[i] == B.INFO_OK and abs(lmax[i] - lmax_o) <= 1e-3 * lmax_o
+        assert relF(X, Xo) <= TOL_ROOT, relF(X, Xo)
+
+
+def test_root_ill_conditioned_logspaced_spectrum_eps_1e8():
+    # 4096-block stress workload in miniature: singular values 1e0 .. 1e-8, eps = 1e-8 lambda_max
+    n = 256
+    A = logspaced_factor(n, 8.0, 5)
+    st, Xo, lmax_o, lam = oracle.inverse_root(np64(A), 1e-8, return_status=True)
+    assert st == oracle.OK and lam.min() > -0.5e-8 * lmax_o      # precondition of the workload
+    (X,), info, iters, resid, lmax = run_roots([A], 1e-8)
+    assert info[0] == B.INFO_OK
+    assert relF(X, Xo) <= TOL_ROOT, relF(X, Xo)
+    assert 20 <= iters[0] <= 30
+
+
+def newton_count(a: float, n: int, stop: float = 1e-2, p: int = 4) -> int:
+    """Scalar model of the coupled iteration on the smallest eigenvalue a of M_0."""
+    mu, k = a, 0
+    while math.sqrt(n) * abs(1 - mu) >= stop and k < 100:
+        mu = ((p + 1 - mu) / p) ** p * mu
+        k += 1
+    return k + 1
+
+
+def test_root_iteration_counts_follow_the_scalar_recurrence():
+    n = 192
+    counts = {}
+    for kappa in (1e2, 1e4, 1e6):
+        U = W.haar(n, DEV, 21, dtype=torch.float64)
+        lam = torch.logspace(0, -math.log10(kappa), n, device=DEV, dtype=torch.float64)
+        A = ((U * lam) @ U.T)
+        A = (0.5 * (A + A.T)).float().contiguous()
+        (X,), info, iters, _, _ = run_roots([A], 1e-12)
+        assert info[0] == B.INFO_OK
+        counts[kappa] = int(iters[0])
+        # all n eigenvalues at the bottom is the worst case of the model; one at the bottom the best
+        assert newton_count(1 / (1.01 * kappa), 1) - 1 <= counts[kappa] <= newton_count(1 / (1.01 * kappa), n) + 1
+    assert counts[1e2] < counts[1e4] < counts[1e6]
+
+
+def test_root_inverse_square_root():
+    A = powerlaw_factor(160, 31)
+    Xo, _, _ = oracle.inverse_root(np64(A), 1e-4, p=2)
+    (X,), info, _, _, _ = run_roots([A], 1e-4, root=2)
+    assert info[0] == B.INFO_OK and relF(X, Xo) <= TOL_ROOT
+
+
+def test_root_mixed_batch_multiple_passes_and_padded_outputs():
+    sizes = [64, 300, 1, 129, 200, 17]
+    As = [powerlaw_factor(n, 40 + i) for i, n in enumerate(sizes)]
+    refs = [oracle.inverse_root(np64(A), 1e-5)[0] for A in As]
+    full, mn = ast.inverse_root_workspace_bytes(list(zip(As, As)))
+    assert mn < full
+    for nbytes in (full, mn + 4096):          # one pass, then as many passes as the smallest workspace forces
+        ws = torch.empty(nbytes, dtype=torch.uint8, device=DEV)
+        Xs = []
+        for A in As:
+            Xs.append(padded(A.shape[0], A.shape[0], 4))
+        info = torch.full((len(As),), -1, dtype=torch.int32, device=DEV)
+        ast.inverse_root(list(zip(As, Xs)), [1e-5] * len(As), info=info, ws=ws)
+        torch.cuda.synchronize()
+        assert torch.all(info == 0)
+        for X, Xo in zip(Xs, refs):
+            assert relF(X, Xo) <= TOL_ROOT
+            assert torch.all(X._base[:, X.shape[1]:] == -777.0)
+    with pytest.raises(ast.AsteriaError) as e:
+        ast.inverse_root(list(zip(As, Xs)), 1e-5, ws=torch.empty(mn - 4096, dtype=torch.uint8, device=DEV))
+    assert e.value.status == B.WORKSPACE_TOO_SMALL
+
+
+def test_root_failure_reporting_is_per_factor():
+    good = powerlaw_factor(96, 50)
+    bad = good.clone()
+    bad -= 0.5 * torch.eye(96, device=DEV) * good.diagonal().max()      # strongly indefinite
+    Xo, _, _ = oracle.inverse_root(np64(good), 1e-6)
+    st, _, _, _ = oracle.inverse_root(np64(bad), 1e-6, return_status=True)
+    assert st == oracle.NOT_PD
+    Xs, info, iters, resid, lmax = run_roots([good, bad, good], 1e-6)
+    assert info[0] == B.INFO_OK and info[2] == B.INFO_OK and info[1] in (B.INFO_NOT_PD, B.INFO_NOT_CONVERGED)
+    assert relF(Xs[0], Xo) <= TOL_ROOT and torch.equal(Xs[0], Xs[2])
+    # an exhausted iteration budget is reported, not hidden
+    _, info, iters, _, _ = run_roots([good], 1e-6, opts=ast.RootOpts(max_iters=1))
+    assert info[0] == B.INFO_NOT_CONVERGED and iters[0] == 1
+    # a zero matrix has no relative regularisation: not positive definite
+    _, info, _, _, _ = run_roots([torch.zeros(8, 8, device=DEV)], 1e-6)
+    assert info[0] == B.INFO_NOT_PD
+    # ... but with an absolute eps it is eps^-1/4 I
+    (X,), info, _, _, _ = run_roots([torch.zeros(8, 8, device=DEV)], 1e-4, relative=False)
+    assert info[0] == B.INFO_OK and relF(X, 10.0 * np.eye(8)) <= 1e-5
+
+
+def test_root_full_size_1024_factors_against_the_oracle():
+    # two factors at the size of the headline workload (oracle: ~1.5 min per factor, run in parallel)
+    n = 1024
+    bank = W.TemplateBank(DEV)
+    Gp = W.powerlaw_blocks([(n, n)], DEV, bank=bank)[0]
+    Gl = W.lowrank_block(n, n, DEV, 1)
+    Ls = [torch.zeros(n, n, device=DEV) for _ in range(2)]
+    ast.stats_update([(Gp, Ls[0], None), (Gl, Ls[1], None)], 0.95)
+    Xs, info, iters, resid, lmax = run_roots(Ls, 1e-6)
+    Xo, lmax_o, status = oracle.inverse_root_batch([np64(A) for A in Ls], 1e-6)
+    assert np.all(status == oracle.OK) and np.all(info == B.INFO_OK)
+    for i in range(2):
+        assert abs(lmax[i] - lmax_o[i]) <= 1e-3 * lmax_o[i]
+        assert relF(Xs[i], Xo[i]) <= TOL_ROOT, (i, relF(Xs[i], Xo[i]))
+    print("iters", iters, "relF", [relF(Xs[i], Xo[i]) for i in range(2)])
+
+
+# =============================================================================== a3 precondition
+
+def test_precondition_ragged_batch_fp32_and_bf16_outputs():
+    shapes = [(128, 128, torch.float32, torch.float32), (200, 328, torch.bfloat16, torch.float32),
+              (5, 3, torch.float32, torch.float32), (257, 130, torch.bfloat16, torch.bfloat16), (1, 1, torch.bfloat16, torch.float32)]
+    items, refs = [], []
+    for i, (m, n, gdt, pdt) in enumerate(shapes):
+        G = W.gaussian_block(m, n, 0.01, DEV, 5, i, dtype=gdt)
+        XL, XR = spd(m, 5, i), spd(n, 6, i)
+        P = padded(m, n, 2, pdt)
+        refs.append(oracle.precondition(np64(XL), np64(G), np64(XR)))
+        items.append((XL, G, XR, P))
+    ast.precondition(items)
+    torch.cuda.synchronize()
+    for (XL, G, XR, P), Po, (_, _, _, pdt) in zip(items, refs, shapes):
+        assert relF(P, Po) <= (TOL_PRECOND if pdt == torch.bfloat16 else 1e-5), relF(P, Po)
+        assert torch.all(P._base[:, P.shape[1]:] == -777.0)
+
+
+def test_precondition_full_size_1024_with_gpu_roots():
+    n = 1024
+    G = W.powerlaw_blocks([(n, n)], DEV)[0]
+    L = torch.zeros(n, n, device=DEV); R = torch.zeros(n, n, device=DEV)
+    ast.stats_update([(G, L, R)], 0.95)
+    (XL, XR), info, _, _, _ = run_roots([L, R], 1e-6)
+    assert np.all(info == 0)
+    P = torch.empty(n, n, device=DEV)
+    ast.precondition([(XL, G, XR, P)])
+    torch.cuda.synchronize()
+    Po = oracle.precondition(np64(XL), np64(G), np64(XR))
+    assert relF(P, Po) <= 1e-5
+
+
+def test_end_to_end_single_block_config_against_the_float64_pipeline():
+    n = 128
+    L = torch.eye(n, device=DEV); R = torch.eye(n, device=DEV)
+    Lo, Ro = np.eye(n), np.eye(n)
+    for k in range(8):
+        G = W.gaussian_block(n, n, 0.01, DEV, 1, k)
+        ast.stats_update([(G, L, R)], 0.95)
+        Lo, Ro = oracle.stats_update(np64(G), Lo, Ro, 0.95)
+    (XL, XR), info, _, _, _ = run_roots([L, R], 1e-6)
+    P = torch.empty(n, n, device=DEV)
+    ast.precondition([(XL, G, XR, P)])
+    torch.cuda.synchronize()
+    XLo, _, _ = oracle.inverse_root(Lo, 1e-6)
+    XRo, _, _ = oracle.inverse_root(Ro, 1e-6)
+    Po = oracle.precondition(XLo, np64(G), XRo)
+    assert relF(XL, XLo) <= TOL_ROOT and relF(XR, XRo) <= TOL_ROOT and relF(P, Po) <= TOL_PRECOND
+    assert abs(float(XL.diagonal().mean()) - 0.95 ** -2) < 0.01
+
+
+# =============================================================================== a4 SOAP refresh
+
+@pytest.mark.parametrize("n", [64, 200, 320])
+def test_soap_refresh_invariants_and_leading_columns(n):
+    A = powerlaw_factor(n, 60)
+    Q0 = W.haar(n, DEV, 61)
+    for _ in range(3):                                  # warm the basis from a random start
+        ast.soap_refresh([(A, Q0)])
+    Qin = Q0.clone()
+    info = torch.full((1,), -1, dtype=torch.int32, device=DEV)
+    ast.soap_refresh([(A, Q0)], info=info)
+    torch.cuda.synchronize()
+    assert info.item() == 0
+    Q = np64(Q0)
+    Z = np64(A) @ np64(Qin)
+    assert np.linalg.norm(Q.T @ Q - np.eye(n)) / math.sqrt(n) <= 1e-5
+    Rm = Q.T @ Z
+    assert np.linalg.norm(np.tril(Rm, -1)) <= 1e-5 * np.linalg.norm(Z)       # Q^T Z is upper triangular
+    assert np.linalg.norm(Q @ np.triu(Rm) - Z) <= 1e-5 * np.linalg.norm(Z)   # backward error
+    assert np.all(np.diag(Rm) >= -1e-7 * np.abs(Rm).max())
+    Qo, Ro = oracle.soap_refresh(np64(A), np64(Qin))
+    lead = min(32, n)
+    assert np.all(np.abs(np.sum(Q[:, :lead] * Qo[:, :lead], axis=0)) >= 0.999)
+    assert np.all(np.sum(Q[:, :lead] * Qo[:, :lead], axis=0) > 0)          # same sign convention
+
+
+def test_soap_refresh_fixed_points_and_batch():
+    d = torch.linspace(3.0, 0.5, 40, device=DEV)
+    A1 = torch.diag(d).contiguous(); Q1 = torch.eye(40, device=DEV)
+    n = 96
+    Qs = W.haar(n, DEV, 70, dtype=torch.float64)
+    lam = torch.linspace(2.0, 0.1, n, device=DEV, dtype=torch.float64)
+    A2 = ((Qs * lam) @ Qs.T)
+    A2 = (0.5 * (A2 + A2.T)).float().contiguous(); Q2 = Qs.float().contiguous()
+    Q2in = Q2.clone()
+    ast.soap_refresh([(A1, Q1), (A2, Q2)])
+    torch.cuda.synchronize()
+    assert relF(Q1, np.eye(40)) <= 1e-6
+    assert relF(Q2, Q2in) <= 1e-4
+
+
+# =============================================================================== a5 SOAP step
+
+def test_soap_step_same_basis_parity_over_three_steps():
+    shapes = [(128, 128, torch.float32), (200, 328, torch.bfloat16), (257, 64, torch.bfloat16)]
+    state = []
+    for i, (m, n, dt) in enumerate(shapes):
+        QL, QR = W.haar(m, DEV, 80 + i), W.haar(n, DEV, 90 + i)
+        M = torch.zeros(m, n, device=DEV); V = torch.zeros(m, n, device=DEV); N = padded(m, n, 1)
+        state.append((QL, QR, M, V, N, np.zeros((m, n)), np.zeros((m, n))))
+    for t in (1, 2, 3):
+        items, Gs = [], []
+        for i, (m, n, dt) in enumerate(shapes):
+            QL, QR, M, V, N, _, _ = state[i]
+            U, Vb = W.haar(m, DEV, 100 + i), W.haar(n, DEV, 110 + i)
+            G = W.soap_gradient(U, Vb, t, DEV, i, dtype=dt)
+            Gs.append(G)
+            items.append((G, QL, QR, M, V, N))
+        Min = [np64(s[2]) for s in state]; Vin = [np64(s[3]) for s in state]
+        ast.soap_step(items, 0.9, 0.95, 1e-8, t)
+        torch.cuda.synchronize()
+        for i in range(len(shapes)):
+            QL, QR, M, V, N, _, _ = state[i]
+            No, Mo, Vo = oracle.soap_step(np64(Gs[i]), np64(QL), np64(QR), Min[i], Vin[i], 0.9, 0.95, 1e-8, t)
+            assert relF(M, Mo) <= 1e-5 and relF(V, Vo) <= 1e-5
+            assert relF(N, No) <= TOL_PRECOND, (t, i, relF(N, No))
+            assert torch.all(N._base[:, N.shape[1]:] == -777.0)
+
+
+def test_soap_step_identity_bases_reduce_to_adam():
+    m, n = 33, 65
+    G = W.gaussian_block(m, n, 0.02, DEV, 120)
+    M = torch.zeros(m, n, device=DEV); V = torch.zeros(m, n, device=DEV); N = torch.empty(m, n, device=DEV)
+    ast.soap_step([(G, torch.eye(m, device=DEV), torch.eye(n, device=DEV), M, V, N)], 0.9, 0.95, 1e-8, 1)
+    torch.cuda.synchronize()
+    g = np64(G)
+    assert relF(N, g / (np.abs(g) + 1e-8)) <= 1e-5
+
+
+# =============================================================================== determinism
+
+def test_two_runs_are_bit_identical():
+    n = 200
+    G = W.lowrank_block(n, n, DEV, 130)
+    outs = []
+    for _ in range(2):
+        L = torch.zeros(n, n, device=DEV); R = torch.zeros(n, n, device=DEV)
+        ast.stats_update([(G, L, R)], 0.95)
+        (XL, XR), info, iters, _, _ = run_roots([L, R], 1e-6)
+        P = torch.empty(n, n, device=DEV)
+        ast.precondition([(XL, G, XR, P)])
+        torch.cuda.synchronize()
+        outs.append((L.clone(), XL.clone(), XR.clone(), P.clone(), iters.copy()))
+    for a, b in zip(outs[0][:4], outs[1][:4]):
+        assert torch.equal(a, b)
+    assert np.array_equal(outs[0][4], outs[1][4])
