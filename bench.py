@@ -38,11 +38,12 @@ def sym_gemm_flops(n: int) -> float:
 
 
 def newton_gemm_counts(iters: int, j64: int):
-    """(fp32 GEMMs, fp64 GEMMs) a factor executed: iteration k < iters does X <- X T, and for
-    k < iters - 1 also T^2, T^4 and T^4 M; iterations k < j64 run in fp64."""
+    """(fp32 GEMMs, fp64 GEMMs) a factor executed: iteration k < iters does X <- X T (except
+    k = 0, where X_1 is written by the start kernel), and for k < iters - 1 also T^2, T^4 and
+    T^4 M; iterations k < j64 run in fp64."""
     g32 = g64 = 0
     for k in range(iters):
-        c = 1 + (3 if k < iters - 1 else 0)
+        c = (1 if k > 0 else 0) + (3 if k < iters - 1 else 0)
         if k < j64:
             g64 += c
         else:
@@ -58,6 +59,7 @@ def main() -> int:
     ap.add_argument("--ws-gib", type=float, default=64.0, help="workspace handed to the library")
     ap.add_argument("--max-blocks", type=int, default=0, help="debug: truncate the batch")
     ap.add_argument("--fp64-iters", type=int, default=-1)
+    ap.add_argument("--schedule", type=int, default=1, help="1 = interval-adapted coefficients, 0 = classical Newton")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -95,7 +97,7 @@ def main() -> int:
     pblocks = ast.PBlocks(list(zip(XLs, Gs, XRs, Ps)))
     nf = len(factors)
     fsize = [m for m, n in shapes] + [n for m, n in shapes]
-    opts = ast.RootOpts(fp64_iters=args.fp64_iters)
+    opts = ast.RootOpts(fp64_iters=args.fp64_iters, schedule=args.schedule)
     full, mn = ast.inverse_root_workspace_bytes(factors, opts)
     ws_bytes = int(max(min(full, args.ws_gib * 2**30), mn, ast.precondition_workspace_bytes(pblocks),
                        ast.stats_update_workspace_bytes(blocks)))
@@ -121,9 +123,9 @@ def main() -> int:
         torch.cuda.synchronize()
         log(f"[bench] warmup {w}: {1e3 * (time.time() - t):.0f} ms")
 
-    # automatic fp64 prefix for eps_rel = 1e-6 (mirrors the library's rule; used for flop accounting)
-    import math
-    j64 = args.fp64_iters if args.fp64_iters >= 0 else max(0, math.ceil(math.log(0.5 * 5.96e-8 / (eps_rel * 1e-3)) / math.log(2.44140625)))
+    # fp64 prefix length: the library's automatic rule gives 2 for eps_rel = 1e-6 with the adapted
+    # schedule (4 with classical Newton coefficients); used here for flop accounting only
+    j64 = args.fp64_iters if args.fp64_iters >= 0 else (2 if args.schedule == 1 else 4)
 
     evs = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
     ast.profile_enable(200000)
@@ -179,6 +181,7 @@ def main() -> int:
         "config": {"workload": "1.1B LLaMA-style model, all 2-D grads blocked at <=1024 (1184 blocks, 2368 factors), "
                                "bf16 power-law gradients, fp32 statistics, eps=1e-6*lambda_max, beta=0.95",
                    "blocks": len(shapes), "factors": nf, "fp64_prefix_iters": j64,
+                   "schedule": "interval-adapted" if args.schedule == 1 else "classical Newton",
                    "workspace_gib": round(ws_bytes / 2**30, 1)},
         "breakdown_ms": {"stats_update": round(stats_ms, 3), "inverse_root": round(refresh_ms, 3),
                          "precondition": round(precond_ms, 3), "step_excl_refresh": round(stats_ms + precond_ms, 3),

@@ -118,7 +118,9 @@ typedef struct asteria_root_opts {
     int32_t fp64_iters;    /* leading iterations run on fp64 MFMA: -1 = choose from eps (default),
                               0 = fp32 only, >= max_iters = fp64 throughout                            */
     int32_t power_iters;   /* upper bound on power-iteration steps for lambda_max (default 256)       */
-    int32_t schedule;      /* 0 = classical coupled Newton coefficients (default); 1 = interval-adapted */
+    int32_t schedule;      /* coefficients of T = a I - g M: 1 = adapted per factor and iteration to the
+                              interval known to hold M's spectrum (default; about half the iterations),
+                              0 = classical coupled Newton, a = (root+1)/root, g = 1/root              */
     float stop_resid;      /* a factor takes its last step once ||M - I||_F < stop_resid (default 1e-2;
                               the step after that squares the residual)                                */
     float power_tol;       /* power iteration stops at ||A v - rho v|| <= power_tol * rho (default 1e-3) */
@@ -136,20 +138,21 @@ const char *asteria_status_string(asteria_status s);
  * For every block: L <- beta L + (1-beta) G G^T and R <- beta R + (1-beta) G^T G, products
  * accumulated in fp32 (bf16 x bf16 products are exact in fp32).  L and R come back exactly
  * symmetric (one triangle is computed, the other mirrored).  Either L or R may be NULL to skip
- * that side.  Needs no workspace (ws may be NULL); 0 <= beta < 1.
+ * that side.  The workspace only holds the problem tables; 0 <= beta < 1.
  * Errors: NULL G, m or n <= 0, ld too small, bad dtype, beta out of range -> INVALID_ARG.   */
 size_t asteria_stats_update_workspace_bytes(const asteria_block *blocks, int nblocks);
 asteria_status asteria_stats_update(const asteria_block *blocks, int nblocks, float beta,
                                     void *ws, size_t ws_bytes, void *stream);
 
 /* ---- inverse p-th roots (paper Eq. 1, Sec. III-B) ------------------------------------------
- * For every factor: X = ((A + A^T)/2 + eps I)^(-1/root), root in {2, 4, 8}... (4 = Eq. 1), by a
+ * For every factor: X = ((A + A^T)/2 + eps I)^(-1/root), root in {2, 4} (4 = Eq. 1), by a
  * coupled matrix iteration run entirely on the device:  lambda_max by power iteration;
- * M_0 = s (A + eps I), X_0 = s^(1/root) I with s = 1 / ((1 + margin) lambda_max + eps);
- * T = a I - g M, X <- X T, M <- T^root M (classical coefficients a = (root+1)/root,
- * g = 1/root); a factor stops by itself once its residual ||M - I||_F has fallen below
- * stop_resid (one more X update follows).  The leading fp64_iters iterations use the fp64
- * matrix cores, the rest the fp32 matrix cores.
+ * M_0 = s (A + eps I), X_0 = s^(1/root) I with s = 1 / ((1 + margin) lambda_max + eps), so the
+ * spectrum of M_0 lies in [~eps s, 1];  T = a I - g M, X <- X T, M <- T^root M, where (a, g)
+ * are chosen per factor and iteration for the interval that holds M's spectrum (or fixed at the
+ * Newton values, see `schedule`); a factor stops by itself once its residual ||M - I||_F has
+ * fallen below stop_resid (one more X update follows).  The leading fp64_iters iterations use
+ * the fp64 matrix cores, the rest the fp32 matrix cores.
  *   eps        host array, eps_count entries (1 = shared by all factors, else nfactors).
  *   info       device int32[nfactors] or NULL   (ASTERIA_INFO_*)
  *   iters      device int32[nfactors] or NULL   (number of X <- X T updates performed)

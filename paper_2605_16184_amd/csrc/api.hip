@@ -24,7 +24,7 @@ extern "C" void asteria_root_opts_default(asteria_root_opts *o)
     o->max_iters = 40;
     o->fp64_iters = -1;
     o->power_iters = 256;
-    o->schedule = 0;
+    o->schedule = 1;
     o->stop_resid = 1e-2f;
     o->power_tol = 1e-3f;
     o->lambda_margin = 0.01f;

@@ -18,8 +18,15 @@ namespace asteria {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef double doublex4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // 16-byte vector without class semantics
 
 struct bf16_t { uint16_t bits; };
+
+// Explicit address spaces: pointers that come out of a table or a runtime-indexed array are
+// "generic" to the compiler, which then emits FLAT instructions; FLAT accesses count against
+// both the vector-memory and the LDS wait counters and serialise the K loop.
+#define ASTERIA_GLOBAL __attribute__((address_space(1)))
+#define ASTERIA_LDS __attribute__((address_space(3)))
 
 __device__ __forceinline__ float bf16_to_f32(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
 // round-to-nearest-even, NaN kept quiet
@@ -43,6 +50,7 @@ struct GemmProblem {
     void *C;
     void *C2;
     float *partial;
+    const float *coef;  // root epilogue: device pointer to (a, g), or null to use ep_a / ep_g
     int M, N, K;
     int lda, ldb, ldc, ldc2;
     int tile_start;  // id of this problem's first tile within the launch
@@ -115,14 +123,14 @@ template <> struct Elem<bf16_t> { static constexpr int EPV = 8; };
 
 // 16 bytes starting at p; elements at index >= valid are zero.  vec_ok: p is 16-byte aligned.
 template <typename TI>
-__device__ __forceinline__ uint4 load16(const TI *p, int valid, bool vec_ok)
+__device__ __forceinline__ u32x4 load16(const TI *p, int valid, bool vec_ok)
 {
     constexpr int EPV = Elem<TI>::EPV;
-    union { uint4 v; TI e[EPV]; } u;
+    union { u32x4 v; TI e[EPV]; } u;
     if (valid >= EPV && vec_ok) {
-        u.v = *reinterpret_cast<const uint4 *>(p);
+        u.v = *(const ASTERIA_GLOBAL u32x4 *)(p);
     } else {
-        u.v = make_uint4(0u, 0u, 0u, 0u);
+        u.v = (u32x4){0u, 0u, 0u, 0u};
 #pragma unroll
         for (int e = 0; e < EPV; ++e)
             if (e < valid) u.e[e] = p[e];
@@ -133,19 +141,19 @@ __device__ __forceinline__ uint4 load16(const TI *p, int valid, bool vec_ok)
 // write the EPV elements of one staged vector to LDS as TC, contiguous at dst
 template <typename TC, typename TI> struct StoreLds;
 template <> struct StoreLds<float, float> {
-    __device__ static __forceinline__ void run(float *dst, uint4 v) { *reinterpret_cast<uint4 *>(dst) = v; }
+    __device__ static __forceinline__ void run(ASTERIA_LDS float *dst, u32x4 v) { *(ASTERIA_LDS u32x4 *)(dst) = v; }
 };
 template <> struct StoreLds<double, double> {
-    __device__ static __forceinline__ void run(double *dst, uint4 v) { *reinterpret_cast<uint4 *>(dst) = v; }
+    __device__ static __forceinline__ void run(ASTERIA_LDS double *dst, u32x4 v) { *(ASTERIA_LDS u32x4 *)(dst) = v; }
 };
 template <> struct StoreLds<float, bf16_t> {
-    __device__ static __forceinline__ void run(float *dst, uint4 v)
+    __device__ static __forceinline__ void run(ASTERIA_LDS float *dst, u32x4 v)
     {
-        uint4 lo, hi;
+        u32x4 lo, hi;
         lo.x = v.x << 16; lo.y = v.x & 0xffff0000u; lo.z = v.y << 16; lo.w = v.y & 0xffff0000u;
         hi.x = v.z << 16; hi.y = v.z & 0xffff0000u; hi.z = v.w << 16; hi.w = v.w & 0xffff0000u;
-        reinterpret_cast<uint4 *>(dst)[0] = lo;
-        reinterpret_cast<uint4 *>(dst)[1] = hi;
+        ((ASTERIA_LDS u32x4 *)dst)[0] = lo;
+        ((ASTERIA_LDS u32x4 *)dst)[1] = hi;
     }
 };
 
@@ -159,9 +167,11 @@ struct OperandStage {
     static_assert(NV >= 1, "tile too small for the thread count");
     static constexpr int LDS_ELEMS = KMAJOR ? BK * Mma<TC>::PITCH_KM : BM * Mma<TC>::PITCH_KC;
 
-    uint4 r[NV];
+    u32x4 r[NV];
 
-    // rows: number of valid rows of this tile (<= 128); k_left: valid k from k0 on
+    // rows: number of valid rows of this tile (<= 128); k_left: valid k from k0 on.
+    // GUARD = false: the tile is full, the slab is full and every vector is 16-byte aligned.
+    template <bool GUARD>
     __device__ __forceinline__ void load(const TI *base, int ld, int row0, int rows, int k0, int k_left,
                                          bool vec_ok, int tid)
     {
@@ -170,7 +180,11 @@ struct OperandStage {
             const int idx = tid + NTHREADS * v;
             const int a = idx / VPR;   // stored row
             const int b = idx % VPR;   // vector within the stored row
-            if (KMAJOR) {
+            if (!GUARD) {
+                const TI *p = KMAJOR ? base + (size_t)(k0 + a) * ld + row0 + b * EPV
+                                     : base + (size_t)(row0 + a) * ld + k0 + b * EPV;
+                r[v] = *(const ASTERIA_GLOBAL u32x4 *)(p);
+            } else if (KMAJOR) {
                 // stored row = k, vector runs along the tile's rows
                 const int valid = (a < k_left) ? (rows - b * EPV) : 0;
                 const TI *p = base + (size_t)(k0 + a) * ld + row0 + b * EPV;
@@ -183,7 +197,7 @@ struct OperandStage {
         }
     }
 
-    __device__ __forceinline__ void store(TC *lds, int tid) const
+    __device__ __forceinline__ void store(ASTERIA_LDS TC *lds, int tid) const
     {
         constexpr int PITCH = KMAJOR ? Mma<TC>::PITCH_KM : Mma<TC>::PITCH_KC;
 #pragma unroll
@@ -228,24 +242,96 @@ template <> __device__ __forceinline__ void store_c<double>(void *C, size_t off,
     reinterpret_cast<double *>(C)[off] = v;
 }
 
+// K loop of one 128 x 128 tile: two LDS stages, the next slab is fetched into registers while
+// the current one feeds the matrix cores.
+template <typename TC, typename TA, typename TB, bool AKM, bool BKM, bool GUARD>
+__device__ __forceinline__ void gemm_mainloop(typename Mma<TC>::acc_t (&acc)[Mma<TC>::WT][Mma<TC>::WT],
+                                              const TA *Ab, const TB *Bb, int lda, int ldb, int row0, int col0,
+                                              int rowsA, int rowsB, int K, bool vecA, bool vecB,
+                                              ASTERIA_LDS TC *smem,
+                                              int tid, int wm, int wn, int r, int h)
+{
+    using MM = Mma<TC>;
+    constexpr int BK = MM::BK;
+    constexpr int WT = MM::WT;
+    constexpr int T = MM::T;
+    using StA = OperandStage<TC, TA, AKM>;
+    using StB = OperandStage<TC, TB, BKM>;
+    StA sa;
+    StB sb;
+    // LDS map: A stage 0 | A stage 1 | B stage 0 | B stage 1
+    ASTERIA_LDS TC *const smemB = smem + 2 * StA::LDS_ELEMS;
+    const int nk = (K + BK - 1) / BK;
+    sa.template load<GUARD>(Ab, lda, row0, rowsA, 0, K, vecA, tid);
+    sb.template load<GUARD>(Bb, ldb, col0, rowsB, 0, K, vecB, tid);
+    sa.store(smem, tid);
+    sb.store(smemB, tid);
+    __syncthreads();
+
+    for (int kt = 0; kt < nk; ++kt) {
+        const int cur = kt & 1;
+        if (kt + 1 < nk) {
+            const int k0 = (kt + 1) * BK;
+            sa.template load<GUARD>(Ab, lda, row0, rowsA, k0, K - k0, vecA, tid);
+            sb.template load<GUARD>(Bb, ldb, col0, rowsB, k0, K - k0, vecB, tid);
+        }
+        const ASTERIA_LDS TC *as = smem + cur * StA::LDS_ELEMS;
+        const ASTERIA_LDS TC *bs = smemB + cur * StB::LDS_ELEMS;
+        // lane group h consumes k = h * KPL .. h * KPL + KPL - 1 of the slab, the same for A and B
+#pragma unroll
+        for (int q = 0; q < MM::KPL / MM::CH; ++q) {
+            TC af[WT][MM::CH], bf[WT][MM::CH];
+            const int kk = h * MM::KPL + q * MM::CH;
+#pragma unroll
+            for (int i = 0; i < WT; ++i) {
+                const int rr = wm * 64 + i * T + r;
+                if (AKM) {
+#pragma unroll
+                    for (int e = 0; e < MM::CH; ++e) af[i][e] = as[(kk + e) * MM::PITCH_KM + rr];
+                } else {
+                    const u32x4 v = *(const ASTERIA_LDS u32x4 *)(as + rr * MM::PITCH_KC + kk);
+                    *reinterpret_cast<u32x4 *>(&af[i][0]) = v;
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < WT; ++j) {
+                const int cc = wn * 64 + j * T + r;
+                if (BKM) {
+#pragma unroll
+                    for (int e = 0; e < MM::CH; ++e) bf[j][e] = bs[(kk + e) * MM::PITCH_KM + cc];
+                } else {
+                    const u32x4 v = *(const ASTERIA_LDS u32x4 *)(bs + cc * MM::PITCH_KC + kk);
+                    *reinterpret_cast<u32x4 *>(&bf[j][0]) = v;
+                }
+            }
+#pragma unroll
+            for (int e = 0; e < MM::CH; ++e)
+#pragma unroll
+                for (int i = 0; i < WT; ++i)
+#pragma unroll
+                    for (int j = 0; j < WT; ++j) acc[i][j] = MM::mma(af[i][e], bf[j][e], acc[i][j]);
+        }
+        if (kt + 1 < nk) {
+            sa.store(smem + (cur ^ 1) * StA::LDS_ELEMS, tid);
+            sb.store(smemB + (cur ^ 1) * StB::LDS_ELEMS, tid);
+        }
+        __syncthreads();
+    }
+}
+
 // ---- the kernel -------------------------------------------------------------------------------
 template <typename TC, typename TA, typename TB, bool AKM, bool BKM>
 __global__ __launch_bounds__(NTHREADS) void gemm_grouped_kernel(const GemmProblem *__restrict__ probs,
                                                                 int nprobs, int total_tiles,
-                                                                const int *__restrict__ state,
-                                                                const float *__restrict__ coef)
+                                                                const int *__restrict__ state)
 {
     using MM = Mma<TC>;
-    using StA = OperandStage<TC, TA, AKM>;
-    using StB = OperandStage<TC, TB, BKM>;
     constexpr int BK = MM::BK;
     constexpr int WT = MM::WT;
     constexpr int T = MM::T;
 
     extern __shared__ __align__(16) unsigned char smem_raw[];
-    TC *smem = reinterpret_cast<TC *>(smem_raw);
-    TC *As[2] = {smem, smem + StA::LDS_ELEMS};
-    TC *Bs[2] = {smem + 2 * StA::LDS_ELEMS, smem + 2 * StA::LDS_ELEMS + StB::LDS_ELEMS};
+    ASTERIA_LDS TC *smem = (ASTERIA_LDS TC *)smem_raw;
     __shared__ float red[NTHREADS / 64];
 
     // XCD-aware order: workgroup b lands on XCD b % 8; give every XCD a contiguous tile range
@@ -296,70 +382,21 @@ __global__ __launch_bounds__(NTHREADS) void gemm_grouped_kernel(const GemmProble
 #pragma unroll
             for (int v = 0; v < MM::NACC; ++v) acc[i][j][v] = (TC)0;
 
-    StA sa;
-    StB sb;
-    const int nk = (K + BK - 1) / BK;
-    sa.load(Ab, lda, row0, rowsA, 0, K, vecA, tid);
-    sb.load(Bb, ldb, col0, rowsB, 0, K, vecB, tid);
-    sa.store(As[0], tid);
-    sb.store(Bs[0], tid);
-    __syncthreads();
-
-    for (int kt = 0; kt < nk; ++kt) {
-        const int cur = kt & 1;
-        if (kt + 1 < nk) {
-            const int k0 = (kt + 1) * BK;
-            sa.load(Ab, lda, row0, rowsA, k0, K - k0, vecA, tid);
-            sb.load(Bb, ldb, col0, rowsB, k0, K - k0, vecB, tid);
-        }
-        const TC *as = As[cur];
-        const TC *bs = Bs[cur];
-        // lane group h consumes k = h * KPL .. h * KPL + KPL - 1 of the slab, the same for A and B
-#pragma unroll
-        for (int q = 0; q < MM::KPL / MM::CH; ++q) {
-            TC af[WT][MM::CH], bf[WT][MM::CH];
-            const int kk = h * MM::KPL + q * MM::CH;
-#pragma unroll
-            for (int i = 0; i < WT; ++i) {
-                const int rr = wm * 64 + i * T + r;
-                if (AKM) {
-#pragma unroll
-                    for (int e = 0; e < MM::CH; ++e) af[i][e] = as[(kk + e) * MM::PITCH_KM + rr];
-                } else {
-                    const uint4 v = *reinterpret_cast<const uint4 *>(as + rr * MM::PITCH_KC + kk);
-                    *reinterpret_cast<uint4 *>(&af[i][0]) = v;
-                }
-            }
-#pragma unroll
-            for (int j = 0; j < WT; ++j) {
-                const int cc = wn * 64 + j * T + r;
-                if (BKM) {
-#pragma unroll
-                    for (int e = 0; e < MM::CH; ++e) bf[j][e] = bs[(kk + e) * MM::PITCH_KM + cc];
-                } else {
-                    const uint4 v = *reinterpret_cast<const uint4 *>(bs + cc * MM::PITCH_KC + kk);
-                    *reinterpret_cast<uint4 *>(&bf[j][0]) = v;
-                }
-            }
-#pragma unroll
-            for (int e = 0; e < MM::CH; ++e)
-#pragma unroll
-                for (int i = 0; i < WT; ++i)
-#pragma unroll
-                    for (int j = 0; j < WT; ++j) acc[i][j] = MM::mma(af[i][e], bf[j][e], acc[i][j]);
-        }
-        if (kt + 1 < nk) {
-            sa.store(As[cur ^ 1], tid);
-            sb.store(Bs[cur ^ 1], tid);
-        }
-        __syncthreads();
-    }
+    // Fast path: full tile, whole slabs, aligned vectors -> no per-element guards in the loop.
+    const bool fast = vecA && vecB && rowsA == BM && rowsB == BN && (K % BK) == 0;
+    if (fast)
+        gemm_mainloop<TC, TA, TB, AKM, BKM, false>(acc, Ab, Bb, lda, ldb, row0, col0, rowsA, rowsB, K, vecA, vecB,
+                                                   smem, tid, wm, wn, r, h);
+    else
+        gemm_mainloop<TC, TA, TB, AKM, BKM, true>(acc, Ab, Bb, lda, ldb, row0, col0, rowsA, rowsB, K, vecA, vecB,
+                                                  smem, tid, wm, wn, r, h);
 
     // ---- epilogue ----
     const bool sym = (flags & GEMM_SYM) != 0;
     const bool root = (flags & GEMM_EPI_ROOT) != 0;
     const TC alpha = (TC)P.alpha, beta = (TC)P.beta;
-    // coefficients of T = a I - g C: per-launch override (coef[0], coef[1]) or the table's
+    // coefficients of T = a I - g C: per-problem device values (coef[0], coef[1]) or the table's
+    const float *coef = root ? P.coef : nullptr;
     const TC ep_a = (TC)(coef ? coef[0] : P.ep_a), ep_g = (TC)(coef ? coef[1] : P.ep_g);
     void *C = P.C;
     TC *C2 = reinterpret_cast<TC *>(P.C2);
@@ -405,11 +442,11 @@ constexpr size_t gemm_lds_bytes()
     return sizeof(TC) * 2 * (size_t)(OperandStage<TC, TA, AKM>::LDS_ELEMS + OperandStage<TC, TB, BKM>::LDS_ELEMS);
 }
 
-// Enqueue one grouped launch.  probs / state / coef are device pointers (state and coef may be
-// null when no problem refers to them).
+// Enqueue one grouped launch.  probs / state are device pointers (state may be null when no
+// problem refers to it).
 template <typename TC, typename TA, typename TB, bool AKM, bool BKM>
 inline hipError_t launch_gemm_grouped(const GemmProblem *probs, int nprobs, int total_tiles,
-                                      const int *state, hipStream_t stream, const float *coef = nullptr)
+                                      const int *state, hipStream_t stream)
 {
     if (total_tiles <= 0 || nprobs <= 0) return hipSuccess;
     auto kern = gemm_grouped_kernel<TC, TA, TB, AKM, BKM>;
@@ -426,7 +463,7 @@ inline hipError_t launch_gemm_grouped(const GemmProblem *probs, int nprobs, int 
                          (AKM ? 8 : 0) | (BKM ? 16 : 0);
     profile_begin(kind, stream);
     hipLaunchKernelGGL(kern, dim3(per_xcd * NUM_XCD), dim3(NTHREADS), lds, stream, probs, nprobs,
-                       total_tiles, state, coef);
+                       total_tiles, state);
     profile_end(stream);
     return hipGetLastError();
 }

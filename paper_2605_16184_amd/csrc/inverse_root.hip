@@ -17,12 +17,14 @@
 //
 // Per factor and iteration: 3 launches (X T together with T T; T^2 T^2; T^4 M) + 1 control kernel.
 #include <math.h>
+#include <stddef.h>
 
 #include <algorithm>
 #include <vector>
 
 #include "common.h"
 #include "gemm.h"
+#include "root_schedule.h"
 
 using namespace asteria;
 
@@ -45,6 +47,7 @@ struct FactorDev {
     double *T464;
     float *pv[2];       // power-iteration vectors
     float2 *pm_partial; // per mat-vec workgroup: (sum y^2, sum y v)
+    float2 *pm_partial2; // per mat-vec workgroup, first step only: (sum a_ij^2, sum a_ii)
     float *partial;     // per lower-triangle tile: sum (M - I)^2
     int n, lda, ldx;
     int ld32, ld64;
@@ -67,6 +70,10 @@ struct FactorScal {
     int xloc;        // 0: current fp32 X in Xout, 1: in X32b
     int info;
     int pm_done;
+    float lo, hi;    // interval assumed to contain the spectrum of the current M
+    float ca, cg;    // coefficients of the current T = ca I - cg M
+    float coef_next[2];   // coefficients the M-update epilogue uses for the next T
+    float fro2, trace;    // ||A||_F^2 and tr(A), gathered during the first power-iteration step
 };
 
 __device__ __forceinline__ float hash_unit(uint32_t f, uint32_t j)
@@ -77,12 +84,6 @@ __device__ __forceinline__ float hash_unit(uint32_t f, uint32_t j)
 }
 
 __device__ __forceinline__ float wave_sum(float v)
-{
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
-    return v;
-}
-__device__ __forceinline__ double wave_sum(double v)
 {
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
@@ -116,7 +117,7 @@ __global__ __launch_bounds__(256) void pm_init_kernel(const FactorDev *fd, Facto
 
 // y = A v for PM_ROWS rows of one factor; v = v_raw * inv_norm on the fly
 __global__ __launch_bounds__(256) void pm_matvec_kernel(const FactorDev *fd, const FactorScal *fs,
-                                                        int nf, int src)
+                                                        int nf, int src, int first)
 {
     // locate the factor of this workgroup: last f with pm_block_start <= blockIdx.x
     int lo = 0, hi = nf - 1;
@@ -133,46 +134,64 @@ __global__ __launch_bounds__(256) void pm_matvec_kernel(const FactorDev *fd, con
     const float inv = fs[lo].inv_norm;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const bool vec_ok = ((reinterpret_cast<uintptr_t>(F.A) & 15u) == 0) && ((lda & 3) == 0);
-    __shared__ float red[2][4];
-    float syy = 0.0f, syv = 0.0f;
+    __shared__ float red[4][4];
+    float syy = 0.0f, syv = 0.0f, saa = 0.0f, str = 0.0f;
     for (int rr = 0; rr < PM_ROWS / 4; ++rr) {
         const int row = blk * PM_ROWS + wave * (PM_ROWS / 4) + rr;
         if (row >= n) break;
         const float *__restrict__ a = F.A + (size_t)row * lda;
-        float s = 0.0f;
+        float s = 0.0f, q = 0.0f;   // q: sum of squares of the row (first step only uses it)
         if (vec_ok) {
             const int n4 = n >> 2;
             for (int j = lane; j < n4; j += 64) {
                 const float4 av = reinterpret_cast<const float4 *>(a)[j];
                 const float4 vv = reinterpret_cast<const float4 *>(v)[j];
                 s += av.x * vv.x + av.y * vv.y + av.z * vv.z + av.w * vv.w;
+                q += av.x * av.x + av.y * av.y + av.z * av.z + av.w * av.w;
             }
-            for (int j = (n4 << 2) + lane; j < n; j += 64) s += a[j] * v[j];
+            for (int j = (n4 << 2) + lane; j < n; j += 64) { s += a[j] * v[j]; q += a[j] * a[j]; }
         } else {
-            for (int j = lane; j < n; j += 64) s += a[j] * v[j];
+            for (int j = lane; j < n; j += 64) { s += a[j] * v[j]; q += a[j] * a[j]; }
         }
         s = wave_sum(s) * inv;
+        if (first) q = wave_sum(q);
         if (lane == 0) {
             y[row] = s;
             syy += s * s;
             syv += s * (v[row] * inv);
+            saa += q;
+            str += a[row];
         }
     }
-    if (lane == 0) { red[0][wave] = syy; red[1][wave] = syv; }
+    if (lane == 0) { red[0][wave] = syy; red[1][wave] = syv; red[2][wave] = saa; red[3][wave] = str; }
     __syncthreads();
-    if (threadIdx.x == 0)
+    if (threadIdx.x == 0) {
         F.pm_partial[blk] = make_float2(red[0][0] + red[0][1] + red[0][2] + red[0][3],
                                         red[1][0] + red[1][1] + red[1][2] + red[1][3]);
+        if (first)
+            F.pm_partial2[blk] = make_float2(red[2][0] + red[2][1] + red[2][2] + red[2][3],
+                                             red[3][0] + red[3][1] + red[3][2] + red[3][3]);
+    }
 }
 
 // one thread per factor: Rayleigh quotient, eigen-residual, early stop
-__global__ void pm_control_kernel(const FactorDev *fd, FactorScal *fs, int nf, float tol)
+__global__ void pm_control_kernel(const FactorDev *fd, FactorScal *fs, int nf, float tol, int first)
 {
     const int f = blockIdx.x * blockDim.x + threadIdx.x;
     if (f >= nf) return;
     FactorScal &S = fs[f];
     if (S.pm_done) return;
     const FactorDev &F = fd[f];
+    if (first) {
+        double aa = 0.0, tr = 0.0;
+        for (int b = 0; b < F.pm_blocks; ++b) {
+            const float2 p = F.pm_partial2[b];
+            aa += (double)p.x;
+            tr += (double)p.y;
+        }
+        S.fro2 = (float)aa;
+        S.trace = (float)tr;
+    }
     double yy = 0.0, yv = 0.0;
     for (int b = 0; b < F.pm_blocks; ++b) {
         const float2 p = F.pm_partial[b];
@@ -190,7 +209,7 @@ __global__ void pm_control_kernel(const FactorDev *fd, FactorScal *fs, int nf, f
 
 // ---- scaling and start of the coupled iteration ---------------------------------------------
 __global__ void root_setup_kernel(const FactorDev *fd, FactorScal *fs, int *state, int nf,
-                                  int relative, float margin)
+                                  int relative, float margin, int root, int adapted)
 {
     const int f = blockIdx.x * blockDim.x + threadIdx.x;
     if (f >= nf) return;
@@ -213,13 +232,32 @@ __global__ void root_setup_kernel(const FactorDev *fd, FactorScal *fs, int *stat
         S.info = ASTERIA_INFO_OK;
         state[f] = ST_RUN;
     }
+    // spectrum of M_0 = s (A + eps I): at most 1 by the scaling; at least eps s for a positive
+    // semi-definite A (halved: round-off in the statistics may push eigenvalues slightly below 0)
+    double lo = ok ? 0.5 * (double)eps / (double)denom : 1.0;
+    if (!(lo > 1e-12)) lo = 1e-12;
+    if (ok) {
+        // ||M_0 - I||_F^2 = s^2 ||A + eps I||_F^2 - 2 s tr(A + eps I) + n bounds every |mu - 1|:
+        // a well-conditioned factor gets a much tighter interval than [eps s, 1]
+        const double sc = 1.0 / (double)denom, e = (double)eps, n = (double)fd[f].n;
+        const double f2 = (double)S.fro2 + 2.0 * e * (double)S.trace + n * e * e;
+        const double tr = (double)S.trace + n * e;
+        double r2 = sc * sc * f2 - 2.0 * sc * tr + n;
+        r2 = r2 * (1.0 + 1e-3) + 1e-6 * n;           // slack for the fp32 sums
+        if (r2 > 0.0 && r2 < 1.0) { const double l1 = 1.0 - sqrt(r2); if (l1 > lo) lo = l1; }
+    }
+    double a, g;
+    root_coefficients(lo, 1.0, root, adapted != 0, ROOT_THETA, a, g);
+    S.lo = (float)lo; S.hi = 1.0f;
+    S.ca = (float)a; S.cg = (float)g;
+    S.coef_next[0] = (float)a; S.coef_next[1] = (float)g;
 }
 
 // One workgroup per lower-triangle 128 x 128 tile: M_0, T_0, X_0 and the residual partial sums.
 template <typename TC>
 __global__ __launch_bounds__(256) void root_init_kernel(const FactorDev *fd, const FactorScal *fs,
                                                         const int *state, int nf, int total_tiles,
-                                                        int root, const float *coef)
+                                                        int root)
 {
     const int t_global = blockIdx.x;
     if (t_global >= total_tiles) return;
@@ -237,15 +275,17 @@ __global__ __launch_bounds__(256) void root_init_kernel(const FactorDev *fd, con
     const TC s = (TC)fs[lo].scale;
     const TC eps = (TC)fs[lo].eps;
     const TC xs = (TC)pow((double)fs[lo].scale, 1.0 / (double)root);
-    const TC ca = (TC)coef[0], cg = (TC)coef[1];
+    const TC ca = (TC)fs[lo].ca, cg = (TC)fs[lo].cg;
+    // X_0 = xs I is never stored: the first update X_1 = X_0 T_0 = xs T_0 is written directly
+    // (into the buffer that holds X after an odd number of updates), which saves one product.
     TC *M, *T, *X;
     int ldm, ldx;
     if (sizeof(TC) == 8) {
         M = reinterpret_cast<TC *>(F.M64[0]); T = reinterpret_cast<TC *>(F.T64);
-        X = reinterpret_cast<TC *>(F.X64[0]); ldm = F.ld64; ldx = F.ld64;
+        X = reinterpret_cast<TC *>(F.X64[1]); ldm = F.ld64; ldx = F.ld64;
     } else {
         M = reinterpret_cast<TC *>(F.M32[0]); T = reinterpret_cast<TC *>(F.T32);
-        X = reinterpret_cast<TC *>(F.Xout); ldm = F.ld32; ldx = F.ldx;
+        X = reinterpret_cast<TC *>(F.X32b); ldm = F.ld32; ldx = F.ld32;
     }
     float rsum = 0.0f;
     for (int e = threadIdx.x; e < BM * BN; e += 256) {
@@ -257,11 +297,11 @@ __global__ __launch_bounds__(256) void root_init_kernel(const FactorDev *fd, con
         const TC t = ca * d - cg * m;
         M[(size_t)row * ldm + col] = m;
         T[(size_t)row * ldm + col] = t;
-        X[(size_t)row * ldx + col] = xs * d;
+        X[(size_t)row * ldx + col] = xs * t;
         if (row != col) {
             M[(size_t)col * ldm + row] = m;
             T[(size_t)col * ldm + row] = t;
-            X[(size_t)col * ldx + row] = (TC)0;
+            X[(size_t)col * ldx + row] = xs * t;
         }
         const float r = (float)(m - d);
         rsum += (row != col) ? 2.0f * r * r : r * r;
@@ -277,7 +317,7 @@ __global__ __launch_bounds__(256) void root_init_kernel(const FactorDev *fd, con
 // final_pass = 1): evaluates the residual of running factors and advances the state machine.
 __global__ __launch_bounds__(64) void root_control_kernel(const FactorDev *fd, FactorScal *fs, int *state,
                                                           int k, int fp32_phase, int final_pass,
-                                                          float stop_resid)
+                                                          float stop_resid, int root, int adapted)
 {
     const int f = blockIdx.x;
     const FactorDev &F = fd[f];
@@ -305,6 +345,22 @@ __global__ __launch_bounds__(64) void root_control_kernel(const FactorDev *fd, F
             if (fp32_phase) S.xloc = (k + 1) & 1;
         }
         if (final_pass && (st == ST_RUN || st == ST_LAST)) S.info = ASTERIA_INFO_NOT_CONVERGED;
+        if (!final_pass && st == ST_RUN) {
+            // iteration k will produce M_{k+1} = f(M_k) and T_{k+1}: advance the spectrum interval
+            // through the scalar map and pick the coefficients of T_{k+1} for that new interval
+            // every |mu - 1| is at most the measured ||M_k - I||_F: tighten the predicted interval
+            double lo_k = (double)S.lo, hi_k = (double)S.hi;
+            const double rb = (double)S.resid * 1.001 + 1e-5;
+            if (1.0 - rb > lo_k) lo_k = 1.0 - rb;
+            if (1.0 + rb < hi_k) hi_k = 1.0 + rb;
+            if (!(hi_k > lo_k)) { lo_k = 1.0 - rb; hi_k = 1.0 + rb; }
+            const RootInterval im = root_image(lo_k, hi_k, root, (double)S.ca, (double)S.cg);
+            double a, g;
+            root_coefficients(im.lo, im.hi, root, adapted != 0, ROOT_THETA, a, g);
+            S.lo = (float)im.lo; S.hi = (float)im.hi;
+            S.ca = (float)a; S.cg = (float)g;
+            S.coef_next[0] = (float)a; S.coef_next[1] = (float)g;
+        }
         state[f] = st;
     }
 }
@@ -386,34 +442,33 @@ struct Plan {
     int max_iters;
     int fp64_iters;
     int power_iters;
+    int root;
     float stop_resid, power_tol, margin;
-    bool use64, use32;
+    bool use64, use32, adapted;
 };
 
-// Worst-case number of coupled iterations (X updates) for a spectrum scaled into [a, 1]:
-// the scalar map mu <- (ca - cg mu)^p mu on the lower end until sqrt(n) |1 - mu| < stop,
-// plus the last update that follows.
-int predicted_iters(double a, int n, int root, double stop, int cap)
+// Host mirror of the device-side schedule for a spectrum of M_0 in [lo0, 1]:
+//   *iters  worst-case number of X updates: iterations until sqrt(n) * max|1 - mu| < stop over the
+//           interval, plus the last update that follows;
+//   *lead64 number of leading iterations that start while the bottom of the spectrum is still
+//           below `thr` (those run in fp64 under the automatic precision rule).
+void simulate_schedule(double lo0, int n, int root, bool adapted, double stop, double thr, int cap,
+                       int *iters, int *lead64)
 {
-    const double ca = (root + 1.0) / root, cg = 1.0 / root;
-    double mu = a;
-    int k = 0;
-    while (k < cap && sqrt((double)n) * fabs(1.0 - mu) >= stop) {
-        mu = pow(ca - cg * mu, (double)root) * mu;
+    double lo = lo0, hi = 1.0;
+    int k = 0, lead = 0;
+    while (k < cap) {
+        const double dev = std::max(fabs(1.0 - lo), fabs(1.0 - hi));
+        if (sqrt((double)n) * dev < stop) break;
+        if (lo < thr) lead = k + 1;
+        double a, g;
+        root_coefficients(lo, hi, root, adapted, ROOT_THETA, a, g);
+        const RootInterval im = root_image(lo, hi, root, a, g);
+        lo = im.lo; hi = im.hi;
         ++k;
     }
-    return k + 1;
-}
-
-int auto_fp64_iters(double eps_rel)
-{
-    // round-off of relative size u injected while the smallest eigenvalue of M is mu costs a
-    // relative error u / mu in the root; mu grows by (5/4)^4 per iteration.  Keep fp64 until
-    // 0.5 u_fp32 / mu is below 1e-3.
-    if (!(eps_rel > 0.0)) return 4;
-    const double x = 0.5 * 5.96e-8 / (eps_rel * 1e-3);
-    if (x <= 1.0) return 0;
-    return (int)ceil(log(x) / log(2.44140625));
+    *iters = k + 1;
+    *lead64 = lead;
 }
 
 size_t factor_matrix_bytes(int n, bool use64, bool use32)
@@ -428,22 +483,24 @@ size_t factor_matrix_bytes(int n, bool use64, bool use32)
 size_t factor_small_bytes(int n)
 {
     const int pmb = (n + PM_ROWS - 1) / PM_ROWS;
-    return 2 * Carver::need((size_t)ld4(n), sizeof(float)) + Carver::need((size_t)pmb, sizeof(float2)) +
+    return 2 * Carver::need((size_t)ld4(n), sizeof(float)) + 2 * Carver::need((size_t)pmb, sizeof(float2)) +
            Carver::need((size_t)tri_tiles(n), sizeof(float)) + sizeof(FactorDev) + sizeof(FactorScal) +
-           2 * sizeof(int) + 16 * sizeof(GemmProblem);
+           2 * sizeof(int) + 18 * sizeof(GemmProblem);
 }
 
 size_t fixed_bytes() { return 64 * 256; }   // alignment slack of the shared arrays + coefficient table
 
 asteria_status make_plan(const asteria_root_opts *opts_in, asteria_eps_mode mode, const float *eps,
-                         int eps_count, Plan &pl)
+                         int eps_count, int root, Plan &pl)
 {
     asteria_root_opts o;
     asteria_root_opts_default(&o);
     if (opts_in) o = *opts_in;
     if (o.max_iters <= 0 || o.power_iters <= 0) return ASTERIA_INVALID_ARG;
     if (!(o.stop_resid > 0.0f) || !(o.power_tol > 0.0f) || !(o.lambda_margin >= 0.0f)) return ASTERIA_INVALID_ARG;
-    if (o.schedule != 0) return ASTERIA_UNSUPPORTED;
+    if (o.schedule != 0 && o.schedule != 1) return ASTERIA_UNSUPPORTED;
+    pl.adapted = o.schedule == 1;
+    pl.root = root;
     pl.max_iters = o.max_iters;
     pl.power_iters = o.power_iters;
     pl.stop_resid = o.stop_resid;
@@ -451,12 +508,17 @@ asteria_status make_plan(const asteria_root_opts *opts_in, asteria_eps_mode mode
     pl.margin = o.lambda_margin;
     int j = o.fp64_iters;
     if (j < 0) {
+        // fp32 round-off of relative size u injected while the bottom of M's spectrum is mu costs
+        // about u / mu in the root: stay in fp64 while 0.5 u_fp32 / mu > 1e-3, i.e. mu < 3e-5.
         if (mode == ASTERIA_EPS_RELATIVE && eps) {
             float emin = eps[0];
             for (int i = 1; i < eps_count; ++i) emin = std::min(emin, eps[i]);
-            j = auto_fp64_iters((double)emin);
+            const double lo0 = (double)emin / (1.0 + (double)pl.margin + (double)emin);
+            int it = 0;
+            if (emin > 0.0f) simulate_schedule(lo0, 1, root, pl.adapted, 1e-3, 0.5 * 5.96e-8 / 1e-3, o.max_iters, &it, &j);
+            else j = o.max_iters;
         } else {
-            j = 4;
+            j = pl.adapted ? 2 : 4;   // the host cannot see eps / lambda_max here
         }
     }
     pl.fp64_iters = std::min(j, pl.max_iters);
@@ -490,8 +552,9 @@ asteria_status run_pass(const asteria_factor *f, const std::vector<int> &order, 
     FactorScal *d_fs = cv.take<FactorScal>(cnt);
     int *d_state = cv.take<int>(cnt);
     int *d_sq = cv.take<int>(cnt);
-    float *d_coef = cv.take<float>(2);
     GemmProblem *d_tab[2][2][3];   // [precision 0 = fp32, 1 = fp64][parity][launch]
+    GemmProblem *d_first[2];       // iteration 0: T T only (X_1 comes from the start kernel)
+    for (int pr = 0; pr < 2; ++pr) d_first[pr] = cv.take<GemmProblem>(cnt);
     for (int pr = 0; pr < 2; ++pr)
         for (int pa = 0; pa < 2; ++pa) {
             d_tab[pr][pa][0] = cv.take<GemmProblem>(2 * (size_t)cnt);
@@ -526,6 +589,7 @@ asteria_status run_pass(const asteria_factor *f, const std::vector<int> &order, 
         F.pv[0] = cv.take<float>(ld4(n));
         F.pv[1] = cv.take<float>(ld4(n));
         F.pm_partial = cv.take<float2>(F.pm_blocks);
+        F.pm_partial2 = cv.take<float2>(F.pm_blocks);
         F.partial = cv.take<float>(F.ntri);
     }
     for (int i = 0; i < cnt; ++i) {
@@ -545,13 +609,16 @@ asteria_status run_pass(const asteria_factor *f, const std::vector<int> &order, 
 
     // iteration budget known on the host
     int K = pl.max_iters;
-    if (mode == ASTERIA_EPS_RELATIVE && a_min > 0.0)
-        K = std::min(K, predicted_iters(a_min * 0.5, n_max, root, (double)pl.stop_resid, pl.max_iters) + 2);
+    if (mode == ASTERIA_EPS_RELATIVE && a_min > 0.0) {
+        int it = 0, lead = 0;
+        simulate_schedule(a_min * 0.5, n_max, root, pl.adapted, (double)pl.stop_resid, 0.0, pl.max_iters, &it, &lead);
+        K = std::min(K, it + 2);
+    }
     const int j64 = std::min(pl.fp64_iters, K);
 
     // problem tables
     const float ca = (float)(root + 1) / (float)root, cg = 1.0f / (float)root;
-    std::vector<GemmProblem> tab[2][2][3];
+    std::vector<GemmProblem> tab[2][2][3], tab_first[2];
     for (int pr = 0; pr < 2; ++pr) {
         if ((pr == 0 && !pl.use32) || (pr == 1 && !pl.use64)) continue;
         for (int pa = 0; pa < 2; ++pa) {
@@ -584,6 +651,7 @@ asteria_status run_pass(const asteria_factor *f, const std::vector<int> &order, 
                 p.state_mask = (1 << ST_RUN);
                 p.tile_start = t0; t0 += F.ntri;
                 tab[pr][pa][0].push_back(p);
+                if (pa == 0) { tab_first[pr].push_back(p); tab_first[pr].back().tile_start = t1; }
                 // launch 1: T4 = T2 T2 (root 4 only)
                 p.A = Mnext; p.B = Mnext; p.C = T4; p.ldc = ldw;
                 p.tile_start = t1;
@@ -591,6 +659,8 @@ asteria_status run_pass(const asteria_factor *f, const std::vector<int> &order, 
                 // launch 2: M' = T^p M, T' = a I - g M', residual partial sums
                 p.A = (root == 4) ? (const void *)T4 : (const void *)Mnext; p.B = Mcur;
                 p.C = Mnext; p.C2 = Tw; p.ldc2 = ldw; p.partial = F.partial;
+                p.coef = reinterpret_cast<const float *>(reinterpret_cast<const char *>(d_fs + i) +
+                                                         offsetof(FactorScal, coef_next));
                 p.flags = GEMM_SYM | GEMM_EPI_ROOT;
                 tab[pr][pa][2].push_back(p);
                 t1 += F.ntri;
@@ -607,13 +677,15 @@ asteria_status run_pass(const asteria_factor *f, const std::vector<int> &order, 
                     GemmProblem &mu = tab[pr][pa][2][i];
                     t2.C = tab[pr][pa][1][i].C;
                     mu.A = t2.C;
+                    if (pa == 0) tab_first[pr][i].C = t2.C;
                 }
     }
 
     ASTERIA_HIP_TRY(upload_async(d_fd, fd.data(), sizeof(FactorDev) * cnt, stream));
     ASTERIA_HIP_TRY(upload_async(d_sq, sq.data(), sizeof(int) * cnt, stream));
-    const float coef_h[2] = {ca, cg};
-    ASTERIA_HIP_TRY(upload_async(d_coef, coef_h, sizeof(coef_h), stream));
+    for (int pr = 0; pr < 2; ++pr)
+        if (!tab_first[pr].empty())
+            ASTERIA_HIP_TRY(upload_async(d_first[pr], tab_first[pr].data(), tab_first[pr].size() * sizeof(GemmProblem), stream));
     for (int pr = 0; pr < 2; ++pr)
         for (int pa = 0; pa < 2; ++pa)
             for (int l = 0; l < 3; ++l)
@@ -625,43 +697,49 @@ asteria_status run_pass(const asteria_factor *f, const std::vector<int> &order, 
     hipLaunchKernelGGL(pm_init_kernel, dim3(cnt), dim3(256), 0, stream, d_fd, d_fs);
     const int ctl_blocks = (cnt + 127) / 128;
     for (int it = 0; it < pl.power_iters; ++it) {
-        hipLaunchKernelGGL(pm_matvec_kernel, dim3(pm_total), dim3(256), 0, stream, d_fd, d_fs, cnt, it & 1);
-        hipLaunchKernelGGL(pm_control_kernel, dim3(ctl_blocks), dim3(128), 0, stream, d_fd, d_fs, cnt, pl.power_tol);
+        hipLaunchKernelGGL(pm_matvec_kernel, dim3(pm_total), dim3(256), 0, stream, d_fd, d_fs, cnt, it & 1, it == 0 ? 1 : 0);
+        hipLaunchKernelGGL(pm_control_kernel, dim3(ctl_blocks), dim3(128), 0, stream, d_fd, d_fs, cnt, pl.power_tol, it == 0 ? 1 : 0);
     }
     // 2. scaling, start
     hipLaunchKernelGGL(root_setup_kernel, dim3(ctl_blocks), dim3(128), 0, stream, d_fd, d_fs, d_state, cnt,
-                       mode == ASTERIA_EPS_RELATIVE ? 1 : 0, pl.margin);
+                       mode == ASTERIA_EPS_RELATIVE ? 1 : 0, pl.margin, root, pl.adapted ? 1 : 0);
     if (j64 > 0)
         hipLaunchKernelGGL(root_init_kernel<double>, dim3(tri_total), dim3(256), 0, stream, d_fd, d_fs, d_state,
-                           cnt, tri_total, root, d_coef);
+                           cnt, tri_total, root);
     else
         hipLaunchKernelGGL(root_init_kernel<float>, dim3(tri_total), dim3(256), 0, stream, d_fd, d_fs, d_state,
-                           cnt, tri_total, root, d_coef);
+                           cnt, tri_total, root);
     ASTERIA_HIP_TRY(hipGetLastError());
 
     // 3. coupled iteration
     for (int k = 0; k < K; ++k) {
         const bool p32 = k >= j64;
         hipLaunchKernelGGL(root_control_kernel, dim3(cnt), dim3(64), 0, stream, d_fd, d_fs, d_state, k,
-                           p32 ? 1 : 0, 0, pl.stop_resid);
+                           p32 ? 1 : 0, 0, pl.stop_resid, root, pl.adapted ? 1 : 0);
         if (k == j64 && j64 > 0)
             hipLaunchKernelGGL(root_to_fp32_kernel, dim3(sq_total), dim3(256), 0, stream, d_fd, d_fs, d_state,
                                cnt, j64, 0, d_sq);
         const int pa = k & 1;
         if (p32) {
-            ASTERIA_HIP_TRY((launch_gemm_grouped<float, float, float, false, false>(d_tab[0][pa][0], 2 * cnt, 2 * tri_total, d_state, stream)));
+            if (k == 0)
+                ASTERIA_HIP_TRY((launch_gemm_grouped<float, float, float, false, false>(d_first[0], cnt, tri_total, d_state, stream)));
+            else
+                ASTERIA_HIP_TRY((launch_gemm_grouped<float, float, float, false, false>(d_tab[0][pa][0], 2 * cnt, 2 * tri_total, d_state, stream)));
             if (root == 4)
                 ASTERIA_HIP_TRY((launch_gemm_grouped<float, float, float, false, false>(d_tab[0][pa][1], cnt, tri_total, d_state, stream)));
             ASTERIA_HIP_TRY((launch_gemm_grouped<float, float, float, false, false>(d_tab[0][pa][2], cnt, tri_total, d_state, stream)));
         } else {
-            ASTERIA_HIP_TRY((launch_gemm_grouped<double, double, double, false, false>(d_tab[1][pa][0], 2 * cnt, 2 * tri_total, d_state, stream)));
+            if (k == 0)
+                ASTERIA_HIP_TRY((launch_gemm_grouped<double, double, double, false, false>(d_first[1], cnt, tri_total, d_state, stream)));
+            else
+                ASTERIA_HIP_TRY((launch_gemm_grouped<double, double, double, false, false>(d_tab[1][pa][0], 2 * cnt, 2 * tri_total, d_state, stream)));
             if (root == 4)
                 ASTERIA_HIP_TRY((launch_gemm_grouped<double, double, double, false, false>(d_tab[1][pa][1], cnt, tri_total, d_state, stream)));
             ASTERIA_HIP_TRY((launch_gemm_grouped<double, double, double, false, false>(d_tab[1][pa][2], cnt, tri_total, d_state, stream)));
         }
     }
     hipLaunchKernelGGL(root_control_kernel, dim3(cnt), dim3(64), 0, stream, d_fd, d_fs, d_state, K,
-                       (K >= j64 && pl.use32) ? 1 : 0, 1, pl.stop_resid);
+                       (K >= j64 && pl.use32) ? 1 : 0, 1, pl.stop_resid, root, pl.adapted ? 1 : 0);
     if (j64 >= K)   // every iteration ran in fp64: hand the result over now
         hipLaunchKernelGGL(root_to_fp32_kernel, dim3(sq_total), dim3(256), 0, stream, d_fd, d_fs, d_state, cnt,
                            K, 1, d_sq);
@@ -680,7 +758,7 @@ extern "C" size_t asteria_inverse_root_workspace_bytes(const asteria_factor *f, 
     if (!f || nfactors <= 0) return 0;
     Plan pl;
     const float e1 = 1e-6f;
-    if (make_plan(opts, ASTERIA_EPS_RELATIVE, &e1, 1, pl) != ASTERIA_OK) return 0;
+    if (make_plan(opts, ASTERIA_EPS_RELATIVE, &e1, 1, 4, pl) != ASTERIA_OK) return 0;
     // sizes must not depend on eps: reserve both precisions unless the caller pinned one
     asteria_root_opts o;
     asteria_root_opts_default(&o);
@@ -708,7 +786,7 @@ extern "C" asteria_status asteria_inverse_root(const asteria_factor *f, int nfac
     if (st != ASTERIA_OK) return st;
     if (mode != ASTERIA_EPS_RELATIVE && mode != ASTERIA_EPS_ABSOLUTE) return ASTERIA_INVALID_ARG;
     Plan pl;
-    st = make_plan(opts, mode, eps, eps_count, pl);
+    st = make_plan(opts, mode, eps, eps_count, root, pl);
     if (st != ASTERIA_OK) return st;
     if (!ws) return ASTERIA_WORKSPACE_TOO_SMALL;
     if (reinterpret_cast<uintptr_t>(ws) & 255u) return ASTERIA_INVALID_ARG;   // workspace must be 256-byte aligned

@@ -29,7 +29,7 @@ def test_version_status_strings_and_default_options():
     assert ast.status_string(B.OK) == "ok"
     assert "workspace" in ast.status_string(B.WORKSPACE_TOO_SMALL)
     o = ast.RootOpts()
-    assert (o.max_iters, o.fp64_iters, o.power_iters, o.schedule) == (40, -1, 256, 0)
+    assert (o.max_iters, o.fp64_iters, o.power_iters, o.schedule) == (40, -1, 256, 1)
     assert abs(o.stop_resid - 1e-2) < 1e-9 and abs(o.power_tol - 1e-3) < 1e-9 and abs(o.lambda_margin - 0.01) < 1e-9
 
 

@@ -152,12 +152,13 @@ def test_root_single_block_config_absolute_and_relative_eps():
         assert torch.equal(Xa, Xa.T)
 
 
+@pytest.mark.parametrize("schedule", [1, 0])
 @pytest.mark.parametrize("n", [200, 320])
-def test_root_powerlaw_spectrum_ragged_sizes(n):
+def test_root_powerlaw_spectrum_ragged_sizes(n, schedule):
     A = powerlaw_factor(n, 11)
     Xo, lmax_o, lam = oracle.inverse_root(np64(A), 1e-6)
     for j in (0, -1, 40):       # fp32 only, automatic fp64 prefix, fp64 throughout
-        (X,), info, iters, resid, lmax = run_roots([A], 1e-6, opts=ast.RootOpts(fp64_iters=j))
+        (X,), info, iters, resid, lmax = run_roots([A], 1e-6, opts=ast.RootOpts(fp64_iters=j, schedule=schedule))
         assert info[0] == B.INFO_OK
         assert abs(lmax[0] - lmax_o) <= 1e-4 * lmax_o
         assert relF(X, Xo) <= TOL_ROOT, (j, relF(X, Xo))
@@ -165,13 +166,14 @@ def test_root_powerlaw_spectrum_ragged_sizes(n):
     assert relF(X, Xo) <= 1e-5      # the fp64 run is limited only by the fp32 output and lambda_max
 
 
-def test_root_of_lowrank_statistics_from_the_gpu_stats_kernel():
+@pytest.mark.parametrize("schedule", [1, 0])
+def test_root_of_lowrank_statistics_from_the_gpu_stats_kernel(schedule):
     # batch-of-64 workload in miniature: rank-32 + noise gradients, ~all eigenvalues on the eps floor
     n = 256
     G = W.lowrank_block(n, n, DEV, 7)
     L = torch.zeros(n, n, device=DEV); R = torch.zeros(n, n, device=DEV)
     ast.stats_update([(G, L, R)], 0.95)
-    Xs, info, iters, resid, lmax = run_roots([L, R], 1e-6)
+    Xs, info, iters, resid, lmax = run_roots([L, R], 1e-6, opts=ast.RootOpts(schedule=schedule))
     for A, X, i in zip((L, R), Xs, range(2)):
         st, Xo, lmax_o, lam = oracle.inverse_root(np64(A), 1e-6, return_status=True)
         assert st == oracle.OK
@@ -188,7 +190,11 @@ def test_root_ill_conditioned_logspaced_spectrum_eps_1e8():
     (X,), info, iters, resid, lmax = run_roots([A], 1e-8)
     assert info[0] == B.INFO_OK
     assert relF(X, Xo) <= TOL_ROOT, relF(X, Xo)
-    assert 20 <= iters[0] <= 30
+    assert 9 <= iters[0] <= 14                      # interval-adapted coefficients
+    # classical Newton coefficients need about twice as many iterations (and a longer fp64 prefix)
+    (Xc,), info, iters_c, _, _ = run_roots([A], 1e-8, opts=ast.RootOpts(schedule=0))
+    assert info[0] == B.INFO_OK and relF(Xc, Xo) <= TOL_ROOT
+    assert 20 <= iters_c[0] <= 30
 
 
 def newton_count(a: float, n: int, stop: float = 1e-2, p: int = 4) -> int:
@@ -202,18 +208,24 @@ def newton_count(a: float, n: int, stop: float = 1e-2, p: int = 4) -> int:
 
 def test_root_iteration_counts_follow_the_scalar_recurrence():
     n = 192
-    counts = {}
+    counts, adapted = {}, {}
     for kappa in (1e2, 1e4, 1e6):
         U = W.haar(n, DEV, 21, dtype=torch.float64)
         lam = torch.logspace(0, -math.log10(kappa), n, device=DEV, dtype=torch.float64)
         A = ((U * lam) @ U.T)
         A = (0.5 * (A + A.T)).float().contiguous()
-        (X,), info, iters, _, _ = run_roots([A], 1e-12)
+        (X,), info, iters, _, _ = run_roots([A], 1e-12, opts=ast.RootOpts(schedule=0))
         assert info[0] == B.INFO_OK
         counts[kappa] = int(iters[0])
+        # the adapted schedule is built for the interval [~0.5 eps s, 1]; pass eps = lambda_min so
+        # that the interval matches the spectrum
+        (X,), info, iters, _, _ = run_roots([A], 1.0 / kappa)
+        assert info[0] == B.INFO_OK
+        adapted[kappa] = int(iters[0])
         # all n eigenvalues at the bottom is the worst case of the model; one at the bottom the best
         assert newton_count(1 / (1.01 * kappa), 1) - 1 <= counts[kappa] <= newton_count(1 / (1.01 * kappa), n) + 1
     assert counts[1e2] < counts[1e4] < counts[1e6]
+    assert adapted[1e4] <= 0.7 * counts[1e4] and adapted[1e6] <= 0.6 * counts[1e6]
 
 
 def test_root_inverse_square_root():
