@@ -7,9 +7,10 @@
 // (every product of the coupled root iteration, and G G^T / G^T G) only tiles on or below
 // the diagonal are computed and the result is mirrored, so the output is exactly symmetric.
 //
-// Workgroup = 256 threads = 4 wavefronts (2 x 2), macro-tile 128 x 128, each wavefront owns
-// 64 x 64.  K is walked in slabs of BK staged through LDS (two stages, register prefetch of
-// the next slab while the current one feeds the MFMA pipe).
+// Workgroup = 512 threads = 8 wavefronts, macro-tile 128 x 128 (fp32: 2 x 4 wavefronts of
+// 64 x 32; fp64: 4 x 2 wavefronts of 32 x 64 - eight wavefronts keep the accumulators small enough
+// for two workgroups per CU).  K is walked in slabs of BK staged through LDS (two stages,
+// register prefetch of the next slab while the current one feeds the MFMA pipe).
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -17,6 +18,7 @@
 namespace asteria {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
 typedef double doublex4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // 16-byte vector without class semantics
 
@@ -69,7 +71,6 @@ void profile_end(hipStream_t stream);
 
 constexpr int BM = 128;
 constexpr int BN = 128;
-constexpr int NTHREADS = 256;
 constexpr int NUM_XCD = 8;
 
 // ---- per-precision matrix-core traits -------------------------------------------------------
@@ -83,7 +84,14 @@ template <> struct Mma<float> {
     static constexpr int NACC = 16;    // accumulator values per lane per tile
     static constexpr int BK = 32;      // K slab
     static constexpr int KPL = BK / KG;  // k values one lane consumes per slab
-    static constexpr int WT = 2;       // MFMA tiles per wavefront edge (64 / 32)
+#ifndef ASTERIA_F32_WAVES_M
+#define ASTERIA_F32_WAVES_M 2
+#define ASTERIA_F32_WAVES_N 4
+#endif
+    static constexpr int WAVES_M = ASTERIA_F32_WAVES_M, WAVES_N = ASTERIA_F32_WAVES_N;   // wavefront grid over the 128 x 128 tile
+    static constexpr int NTHR = 64 * WAVES_M * WAVES_N;
+    static constexpr int WTM = 128 / WAVES_M / T;              // MFMA tiles per wavefront, rows (64 / 32)
+    static constexpr int WTN = 128 / WAVES_N / T;              // MFMA tiles per wavefront, columns
     static constexpr int CH = 4;       // elements per 16-byte LDS chunk
     static constexpr int PITCH_KC = BK + 4;   // k-contiguous LDS row pitch (144 B)
     static constexpr int PITCH_KM = BM + 4;   // k-major LDS row pitch
@@ -103,7 +111,14 @@ template <> struct Mma<double> {
     static constexpr int NACC = 4;
     static constexpr int BK = 16;
     static constexpr int KPL = BK / KG;
-    static constexpr int WT = 4;
+#ifndef ASTERIA_F64_WAVES_M
+#define ASTERIA_F64_WAVES_M 4
+#define ASTERIA_F64_WAVES_N 2
+#endif
+    static constexpr int WAVES_M = ASTERIA_F64_WAVES_M, WAVES_N = ASTERIA_F64_WAVES_N;
+    static constexpr int NTHR = 64 * WAVES_M * WAVES_N;
+    static constexpr int WTM = 128 / WAVES_M / T;
+    static constexpr int WTN = 128 / WAVES_N / T;
     static constexpr int CH = 2;
     static constexpr int PITCH_KC = BK + 2;   // 144 B
     static constexpr int PITCH_KM = BM + 2;
@@ -163,6 +178,7 @@ struct OperandStage {
     static constexpr int EPV = Elem<TI>::EPV;
     static constexpr int BK = Mma<TC>::BK;
     static constexpr int VPR = KMAJOR ? (BM / EPV) : (BK / EPV);       // vectors per stored row
+    static constexpr int NTHREADS = Mma<TC>::NTHR;
     static constexpr int NV = (KMAJOR ? BK : BM) * VPR / NTHREADS;     // vectors per thread
     static_assert(NV >= 1, "tile too small for the thread count");
     static constexpr int LDS_ELEMS = KMAJOR ? BK * Mma<TC>::PITCH_KM : BM * Mma<TC>::PITCH_KC;
@@ -245,7 +261,7 @@ template <> __device__ __forceinline__ void store_c<double>(void *C, size_t off,
 // K loop of one 128 x 128 tile: two LDS stages, the next slab is fetched into registers while
 // the current one feeds the matrix cores.
 template <typename TC, typename TA, typename TB, bool AKM, bool BKM, bool GUARD>
-__device__ __forceinline__ void gemm_mainloop(typename Mma<TC>::acc_t (&acc)[Mma<TC>::WT][Mma<TC>::WT],
+__device__ __forceinline__ void gemm_mainloop(typename Mma<TC>::acc_t (&acc)[Mma<TC>::WTM][Mma<TC>::WTN],
                                               const TA *Ab, const TB *Bb, int lda, int ldb, int row0, int col0,
                                               int rowsA, int rowsB, int K, bool vecA, bool vecB,
                                               ASTERIA_LDS TC *smem,
@@ -253,7 +269,8 @@ __device__ __forceinline__ void gemm_mainloop(typename Mma<TC>::acc_t (&acc)[Mma
 {
     using MM = Mma<TC>;
     constexpr int BK = MM::BK;
-    constexpr int WT = MM::WT;
+    constexpr int WTM = MM::WTM, WTN = MM::WTN;
+    constexpr int WROWS = BM / MM::WAVES_M, WCOLS = BN / MM::WAVES_N;
     constexpr int T = MM::T;
     using StA = OperandStage<TC, TA, AKM>;
     using StB = OperandStage<TC, TB, BKM>;
@@ -280,11 +297,11 @@ __device__ __forceinline__ void gemm_mainloop(typename Mma<TC>::acc_t (&acc)[Mma
         // lane group h consumes k = h * KPL .. h * KPL + KPL - 1 of the slab, the same for A and B
 #pragma unroll
         for (int q = 0; q < MM::KPL / MM::CH; ++q) {
-            TC af[WT][MM::CH], bf[WT][MM::CH];
+            TC af[WTM][MM::CH], bf[WTN][MM::CH];
             const int kk = h * MM::KPL + q * MM::CH;
 #pragma unroll
-            for (int i = 0; i < WT; ++i) {
-                const int rr = wm * 64 + i * T + r;
+            for (int i = 0; i < WTM; ++i) {
+                const int rr = wm * WROWS + i * T + r;
                 if (AKM) {
 #pragma unroll
                     for (int e = 0; e < MM::CH; ++e) af[i][e] = as[(kk + e) * MM::PITCH_KM + rr];
@@ -294,8 +311,8 @@ __device__ __forceinline__ void gemm_mainloop(typename Mma<TC>::acc_t (&acc)[Mma
                 }
             }
 #pragma unroll
-            for (int j = 0; j < WT; ++j) {
-                const int cc = wn * 64 + j * T + r;
+            for (int j = 0; j < WTN; ++j) {
+                const int cc = wn * WCOLS + j * T + r;
                 if (BKM) {
 #pragma unroll
                     for (int e = 0; e < MM::CH; ++e) bf[j][e] = bs[(kk + e) * MM::PITCH_KM + cc];
@@ -307,9 +324,9 @@ __device__ __forceinline__ void gemm_mainloop(typename Mma<TC>::acc_t (&acc)[Mma
 #pragma unroll
             for (int e = 0; e < MM::CH; ++e)
 #pragma unroll
-                for (int i = 0; i < WT; ++i)
+                for (int i = 0; i < WTM; ++i)
 #pragma unroll
-                    for (int j = 0; j < WT; ++j) acc[i][j] = MM::mma(af[i][e], bf[j][e], acc[i][j]);
+                    for (int j = 0; j < WTN; ++j) acc[i][j] = MM::mma(af[i][e], bf[j][e], acc[i][j]);
         }
         if (kt + 1 < nk) {
             sa.store(smem + (cur ^ 1) * StA::LDS_ELEMS, tid);
@@ -321,18 +338,19 @@ __device__ __forceinline__ void gemm_mainloop(typename Mma<TC>::acc_t (&acc)[Mma
 
 // ---- the kernel -------------------------------------------------------------------------------
 template <typename TC, typename TA, typename TB, bool AKM, bool BKM>
-__global__ __launch_bounds__(NTHREADS) void gemm_grouped_kernel(const GemmProblem *__restrict__ probs,
+__global__ __launch_bounds__(Mma<TC>::NTHR) void gemm_grouped_kernel(const GemmProblem *__restrict__ probs,
                                                                 int nprobs, int total_tiles,
                                                                 const int *__restrict__ state)
 {
     using MM = Mma<TC>;
     constexpr int BK = MM::BK;
-    constexpr int WT = MM::WT;
+    constexpr int WTM = MM::WTM, WTN = MM::WTN;
+    constexpr int WROWS = BM / MM::WAVES_M, WCOLS = BN / MM::WAVES_N;
     constexpr int T = MM::T;
 
     extern __shared__ __align__(16) unsigned char smem_raw[];
     ASTERIA_LDS TC *smem = (ASTERIA_LDS TC *)smem_raw;
-    __shared__ float red[NTHREADS / 64];
+    __shared__ float red[MM::NTHR / 64];
 
     // XCD-aware order: workgroup b lands on XCD b % 8; give every XCD a contiguous tile range
     // so the tiles of one problem share that XCD's L2.
@@ -370,15 +388,15 @@ __global__ __launch_bounds__(NTHREADS) void gemm_grouped_kernel(const GemmProble
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
-    const int wm = wave >> 1, wn = wave & 1;
+    const int wm = wave / MM::WAVES_N, wn = wave % MM::WAVES_N;
     const int r = lane % T;   // row (A) / column (B) inside an MFMA tile
     const int h = lane / T;   // k group
 
-    typename MM::acc_t acc[WT][WT];
+    typename MM::acc_t acc[WTM][WTN];
 #pragma unroll
-    for (int i = 0; i < WT; ++i)
+    for (int i = 0; i < WTM; ++i)
 #pragma unroll
-        for (int j = 0; j < WT; ++j)
+        for (int j = 0; j < WTN; ++j)
 #pragma unroll
             for (int v = 0; v < MM::NACC; ++v) acc[i][j][v] = (TC)0;
 
@@ -402,14 +420,59 @@ __global__ __launch_bounds__(NTHREADS) void gemm_grouped_kernel(const GemmProble
     TC *C2 = reinterpret_cast<TC *>(P.C2);
     const int ldc = P.ldc, ldc2 = P.ldc2;
     float rsum = 0.0f;
+    // Fast fp32 stores need a full, aligned tile: in the 32 x 32 MFMA layout a lane owns 4
+    // consecutive rows of one column, so the mirrored group C[col][row .. row + 3] is one aligned
+    // 16-byte store (a scalar mirror store touches 64 different cache lines per instruction).
+    bool vec_c = false;
+    if constexpr (sizeof(TC) == 4)
+        vec_c = rowsA == BM && rowsB == BN && !(flags & GEMM_C_BF16) && (ldc & 3) == 0 &&
+                (reinterpret_cast<uintptr_t>(C) & 15u) == 0 &&
+                (!root || ((ldc2 & 3) == 0 && (reinterpret_cast<uintptr_t>(C2) & 15u) == 0));
 #pragma unroll
-    for (int i = 0; i < WT; ++i) {
+    for (int i = 0; i < WTM; ++i) {
 #pragma unroll
-        for (int j = 0; j < WT; ++j) {
-            const int col = col0 + wn * 64 + j * T + r;
+        for (int j = 0; j < WTN; ++j) {
+            // one T x T MFMA block; all three cases below are uniform over the wavefront
+            const int br = row0 + wm * WROWS + i * T, bc = col0 + wn * WCOLS + j * T;
+            if (sym && br + T - 1 < bc) continue;           // entirely above the diagonal: mirrored from below
+            const bool below = br >= bc + T;                // entirely below the diagonal
+            const int col = bc + r;
+            bool done = false;
+            if constexpr (sizeof(TC) == 4) {
+                if (vec_c && (!sym || below)) {
+                    ASTERIA_GLOBAL float *Cg = (ASTERIA_GLOBAL float *)C;
+                    ASTERIA_GLOBAL float *C2g = (ASTERIA_GLOBAL float *)C2;
+#pragma unroll
+                    for (int g4 = 0; g4 < MM::NACC / 4; ++g4) {
+                        const int rb = br + 8 * g4 + 4 * h;
+                        floatx4 v4, t4;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            float val = alpha * acc[i][j][4 * g4 + e];
+                            if (beta != 0.0f) val += beta * Cg[(size_t)(rb + e) * ldc + col];
+                            Cg[(size_t)(rb + e) * ldc + col] = val;
+                            v4[e] = val;
+                            if (root) {
+                                const float d = (rb + e == col) ? 1.0f : 0.0f;
+                                const float t2 = ep_a * d - ep_g * val;
+                                C2g[(size_t)(rb + e) * ldc2 + col] = t2;
+                                t4[e] = t2;
+                                const float er = val - d;
+                                rsum += sym ? 2.0f * er * er : er * er;
+                            }
+                        }
+                        if (sym) {
+                            *(ASTERIA_GLOBAL floatx4 *)(Cg + (size_t)col * ldc + rb) = v4;
+                            if (root) *(ASTERIA_GLOBAL floatx4 *)(C2g + (size_t)col * ldc2 + rb) = t4;
+                        }
+                    }
+                    done = true;
+                }
+            }
+            if (done) continue;
 #pragma unroll
             for (int v = 0; v < MM::NACC; ++v) {
-                const int row = row0 + wm * 64 + i * T + MM::acc_row(v, h);
+                const int row = br + MM::acc_row(v, h);
                 if (row >= M || col >= N) continue;
                 if (sym && row < col) continue;   // the mirror of (col, row) covers it
                 TC val = alpha * acc[i][j][v];
@@ -432,7 +495,12 @@ __global__ __launch_bounds__(NTHREADS) void gemm_grouped_kernel(const GemmProble
         for (int off = 32; off > 0; off >>= 1) rsum += __shfl_xor(rsum, off, 64);
         if (lane == 0) red[wave] = rsum;
         __syncthreads();
-        if (tid == 0) P.partial[lt] = red[0] + red[1] + red[2] + red[3];
+        if (tid == 0) {
+            float t = 0.0f;
+#pragma unroll
+            for (int w = 0; w < MM::NTHR / 64; ++w) t += red[w];
+            P.partial[lt] = t;
+        }
     }
 }
 
@@ -462,7 +530,7 @@ inline hipError_t launch_gemm_grouped(const GemmProblem *probs, int nprobs, int 
     constexpr int kind = (sizeof(TC) == 8 ? 1 : 0) | (sizeof(TA) == 2 ? 2 : 0) | (sizeof(TB) == 2 ? 4 : 0) |
                          (AKM ? 8 : 0) | (BKM ? 16 : 0);
     profile_begin(kind, stream);
-    hipLaunchKernelGGL(kern, dim3(per_xcd * NUM_XCD), dim3(NTHREADS), lds, stream, probs, nprobs,
+    hipLaunchKernelGGL(kern, dim3(per_xcd * NUM_XCD), dim3(Mma<TC>::NTHR), lds, stream, probs, nprobs,
                        total_tiles, state);
     profile_end(stream);
     return hipGetLastError();
