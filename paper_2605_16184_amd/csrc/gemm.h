@@ -336,80 +336,20 @@ __device__ __forceinline__ void gemm_mainloop(typename Mma<TC>::acc_t (&acc)[Mma
     }
 }
 
-// ---- the kernel -------------------------------------------------------------------------------
-template <typename TC, typename TA, typename TB, bool AKM, bool BKM>
-__global__ __launch_bounds__(Mma<TC>::NTHR) void gemm_grouped_kernel(const GemmProblem *__restrict__ probs,
-                                                                int nprobs, int total_tiles,
-                                                                const int *__restrict__ state)
+// Store one accumulated 128 x 128 tile: C = alpha acc + beta C, optional bf16 store, optional
+// mirror (symmetric problems) and the root epilogue (T' = a I - g C and the residual partial sum).
+// MM supplies the accumulator layout (tile edge T, NACC values per lane, acc_row) and the wave grid.
+template <typename MM, typename TC>
+__device__ __forceinline__ void gemm_epilogue(const GemmProblem &P, typename MM::acc_t (&acc)[MM::WTM][MM::WTN],
+                                              int lt, int ti, int tj, int row0, int col0, int rowsA, int rowsB,
+                                              int wm, int wn, int r, int h, int lane, int wave, int tid,
+                                              float *red)
 {
-    using MM = Mma<TC>;
-    constexpr int BK = MM::BK;
     constexpr int WTM = MM::WTM, WTN = MM::WTN;
     constexpr int WROWS = BM / MM::WAVES_M, WCOLS = BN / MM::WAVES_N;
     constexpr int T = MM::T;
-
-    extern __shared__ __align__(16) unsigned char smem_raw[];
-    ASTERIA_LDS TC *smem = (ASTERIA_LDS TC *)smem_raw;
-    __shared__ float red[MM::NTHR / 64];
-
-    // XCD-aware order: workgroup b lands on XCD b % 8; give every XCD a contiguous tile range
-    // so the tiles of one problem share that XCD's L2.
-    const int per_xcd = (total_tiles + NUM_XCD - 1) / NUM_XCD;
-    const int t_global = (int)(blockIdx.x % NUM_XCD) * per_xcd + (int)(blockIdx.x / NUM_XCD);
-    if (t_global >= total_tiles) return;
-
-    // binary search: last problem with tile_start <= t_global
-    int lo = 0, hi = nprobs - 1;
-    while (lo < hi) {
-        const int mid = (lo + hi + 1) >> 1;
-        if (probs[mid].tile_start <= t_global) lo = mid; else hi = mid - 1;
-    }
-    const GemmProblem &P = probs[lo];
-    if (P.state_idx >= 0) {
-        const int st = state[P.state_idx];
-        if (!((1 << st) & P.state_mask)) return;
-    }
     const int flags = P.flags;
-    const int lt = t_global - P.tile_start;
-    int ti, tj;
-    if (flags & GEMM_SYM) tri_decode(lt, ti, tj);
-    else { ti = lt / P.tiles_n; tj = lt % P.tiles_n; }
-
-    const int M = P.M, N = P.N, K = P.K;
-    const int row0 = ti * BM, col0 = tj * BN;
-    const int rowsA = min(BM, M - row0);
-    const int rowsB = min(BN, N - col0);
-    const TA *Ab = reinterpret_cast<const TA *>(P.A);
-    const TB *Bb = reinterpret_cast<const TB *>(P.B);
-    const int lda = P.lda, ldb = P.ldb;
-    const bool vecA = ((reinterpret_cast<uintptr_t>(Ab) & 15u) == 0) && ((((size_t)lda * sizeof(TA)) & 15u) == 0);
-    const bool vecB = ((reinterpret_cast<uintptr_t>(Bb) & 15u) == 0) && ((((size_t)ldb * sizeof(TB)) & 15u) == 0);
-
-    const int tid = threadIdx.x;
-    const int lane = tid & 63;
-    const int wave = tid >> 6;
-    const int wm = wave / MM::WAVES_N, wn = wave % MM::WAVES_N;
-    const int r = lane % T;   // row (A) / column (B) inside an MFMA tile
-    const int h = lane / T;   // k group
-
-    typename MM::acc_t acc[WTM][WTN];
-#pragma unroll
-    for (int i = 0; i < WTM; ++i)
-#pragma unroll
-        for (int j = 0; j < WTN; ++j)
-#pragma unroll
-            for (int v = 0; v < MM::NACC; ++v) acc[i][j][v] = (TC)0;
-
-    // Fast path: full tile, whole slabs, aligned vectors -> no per-element guards in the loop.
-    const bool fast = vecA && vecB && rowsA == BM && rowsB == BN && (K % BK) == 0;
-    if (fast)
-        gemm_mainloop<TC, TA, TB, AKM, BKM, false>(acc, Ab, Bb, lda, ldb, row0, col0, rowsA, rowsB, K, vecA, vecB,
-                                                   smem, tid, wm, wn, r, h);
-    else
-        gemm_mainloop<TC, TA, TB, AKM, BKM, true>(acc, Ab, Bb, lda, ldb, row0, col0, rowsA, rowsB, K, vecA, vecB,
-                                                  smem, tid, wm, wn, r, h);
-
-    // ---- epilogue ----
+    const int M = P.M, N = P.N;
     const bool sym = (flags & GEMM_SYM) != 0;
     const bool root = (flags & GEMM_EPI_ROOT) != 0;
     const TC alpha = (TC)P.alpha, beta = (TC)P.beta;
@@ -502,6 +442,81 @@ __global__ __launch_bounds__(Mma<TC>::NTHR) void gemm_grouped_kernel(const GemmP
             P.partial[lt] = t;
         }
     }
+}
+
+// ---- the kernel -------------------------------------------------------------------------------
+template <typename TC, typename TA, typename TB, bool AKM, bool BKM>
+__global__ __launch_bounds__(Mma<TC>::NTHR) void gemm_grouped_kernel(const GemmProblem *__restrict__ probs,
+                                                                int nprobs, int total_tiles,
+                                                                const int *__restrict__ state)
+{
+    using MM = Mma<TC>;
+    constexpr int BK = MM::BK;
+    constexpr int WTM = MM::WTM, WTN = MM::WTN;
+    constexpr int T = MM::T;
+
+    extern __shared__ __align__(16) unsigned char smem_raw[];
+    ASTERIA_LDS TC *smem = (ASTERIA_LDS TC *)smem_raw;
+    __shared__ float red[MM::NTHR / 64];
+
+    // XCD-aware order: workgroup b lands on XCD b % 8; give every XCD a contiguous tile range
+    // so the tiles of one problem share that XCD's L2.
+    const int per_xcd = (total_tiles + NUM_XCD - 1) / NUM_XCD;
+    const int t_global = (int)(blockIdx.x % NUM_XCD) * per_xcd + (int)(blockIdx.x / NUM_XCD);
+    if (t_global >= total_tiles) return;
+
+    // binary search: last problem with tile_start <= t_global
+    int lo = 0, hi = nprobs - 1;
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (probs[mid].tile_start <= t_global) lo = mid; else hi = mid - 1;
+    }
+    const GemmProblem &P = probs[lo];
+    if (P.state_idx >= 0) {
+        const int st = state[P.state_idx];
+        if (!((1 << st) & P.state_mask)) return;
+    }
+    const int flags = P.flags;
+    const int lt = t_global - P.tile_start;
+    int ti, tj;
+    if (flags & GEMM_SYM) tri_decode(lt, ti, tj);
+    else { ti = lt / P.tiles_n; tj = lt % P.tiles_n; }
+
+    const int M = P.M, N = P.N, K = P.K;
+    const int row0 = ti * BM, col0 = tj * BN;
+    const int rowsA = min(BM, M - row0);
+    const int rowsB = min(BN, N - col0);
+    const TA *Ab = reinterpret_cast<const TA *>(P.A);
+    const TB *Bb = reinterpret_cast<const TB *>(P.B);
+    const int lda = P.lda, ldb = P.ldb;
+    const bool vecA = ((reinterpret_cast<uintptr_t>(Ab) & 15u) == 0) && ((((size_t)lda * sizeof(TA)) & 15u) == 0);
+    const bool vecB = ((reinterpret_cast<uintptr_t>(Bb) & 15u) == 0) && ((((size_t)ldb * sizeof(TB)) & 15u) == 0);
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int wm = wave / MM::WAVES_N, wn = wave % MM::WAVES_N;
+    const int r = lane % T;   // row (A) / column (B) inside an MFMA tile
+    const int h = lane / T;   // k group
+
+    typename MM::acc_t acc[WTM][WTN];
+#pragma unroll
+    for (int i = 0; i < WTM; ++i)
+#pragma unroll
+        for (int j = 0; j < WTN; ++j)
+#pragma unroll
+            for (int v = 0; v < MM::NACC; ++v) acc[i][j][v] = (TC)0;
+
+    // Fast path: full tile, whole slabs, aligned vectors -> no per-element guards in the loop.
+    const bool fast = vecA && vecB && rowsA == BM && rowsB == BN && (K % BK) == 0;
+    if (fast)
+        gemm_mainloop<TC, TA, TB, AKM, BKM, false>(acc, Ab, Bb, lda, ldb, row0, col0, rowsA, rowsB, K, vecA, vecB,
+                                                   smem, tid, wm, wn, r, h);
+    else
+        gemm_mainloop<TC, TA, TB, AKM, BKM, true>(acc, Ab, Bb, lda, ldb, row0, col0, rowsA, rowsB, K, vecA, vecB,
+                                                  smem, tid, wm, wn, r, h);
+
+    gemm_epilogue<MM, TC>(P, acc, lt, ti, tj, row0, col0, rowsA, rowsB, wm, wn, r, h, lane, wave, tid, red);
 }
 
 template <typename TC, typename TA, typename TB, bool AKM, bool BKM>

@@ -1,0 +1,244 @@
+// Grouped GEMM on the gfx950 bf16 matrix cores (v_mfma_f32_32x32x16_bf16, fp32 accumulation).
+//
+// Same problem table, tile order and epilogue as gemm.h; operands are always k-contiguous.
+// An operand is either bf16 in memory (used as is - bf16 x bf16 products are exact in fp32) or
+// fp32 in memory and split on the fly into NT bf16 terms (x = hi + lo, hi = bf16(x),
+// lo = bf16(x - hi)): with two terms per operand the kernel issues hi*hi, hi*lo and lo*hi, which
+// keeps about 16 bits of the fp32 operands at three bf16 MFMA passes.
+//
+// Workgroup = 256 threads = 2 x 2 wavefronts of 64 x 64 (2 x 2 MFMA tiles each), K slabs of 64
+// (32 when operands are split, to fit both terms of both operands in LDS twice).
+#pragma once
+#include "gemm.h"
+
+namespace asteria {
+
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+struct MmaBf16 {
+    static constexpr int T = 32;
+    static constexpr int NACC = 16;
+    static constexpr int WAVES_M = 2, WAVES_N = 2;
+    static constexpr int NTHR = 256;
+    static constexpr int WTM = 2, WTN = 2;
+    typedef floatx16 acc_t;
+    __device__ static __forceinline__ acc_t mma(u32x4 a, u32x4 b, acc_t c)
+    {
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, a),
+                                                       __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
+    }
+    __device__ static __forceinline__ int acc_row(int v, int h) { return 8 * (v >> 2) + 4 * h + (v & 3); }
+};
+
+// hi / lo bf16 split of four fp32 values; returns packed pairs (two bf16 per 32-bit word)
+__device__ __forceinline__ void split4(u32x4 x, u32x2 &hi, u32x2 &lo, bool want_lo)
+{
+    uint16_t hb[4], lb[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const float f = __uint_as_float(x[e]);
+        hb[e] = f32_to_bf16(f);
+        lb[e] = want_lo ? f32_to_bf16(f - bf16_to_f32(hb[e])) : (uint16_t)0;
+    }
+    hi.x = (uint32_t)hb[0] | ((uint32_t)hb[1] << 16);
+    hi.y = (uint32_t)hb[2] | ((uint32_t)hb[3] << 16);
+    lo.x = (uint32_t)lb[0] | ((uint32_t)lb[1] << 16);
+    lo.y = (uint32_t)lb[2] | ((uint32_t)lb[3] << 16);
+}
+
+// One operand tile (128 rows x BK) of input type TI staged as bf16 terms in LDS.
+template <typename TI, int NT, int BK>
+struct Bf16Stage {
+    static constexpr int EPV = Elem<TI>::EPV;              // 8 (bf16) or 4 (fp32) elements per 16 bytes
+    static constexpr int VPR = BK / EPV;
+    static constexpr int NV = BM * VPR / 256;
+    static constexpr int PITCH = BK + 8;                   // bf16 elements; 16-byte pad keeps reads conflict free
+    static constexpr int TERM_ELEMS = BM * PITCH;
+    static constexpr int LDS_ELEMS = NT * TERM_ELEMS;      // per stage
+    static_assert(NV >= 1, "slab too small");
+    static_assert(sizeof(TI) == 2 ? NT == 1 : true, "bf16 operands are exact: one term");
+
+    u32x4 r[NV];
+
+    template <bool GUARD>
+    __device__ __forceinline__ void load(const TI *base, int ld, int row0, int rows, int k0, int k_left,
+                                         bool vec_ok, int tid)
+    {
+#pragma unroll
+        for (int v = 0; v < NV; ++v) {
+            const int idx = tid + 256 * v;
+            const int a = idx / VPR, b = idx % VPR;
+            const TI *p = base + (size_t)(row0 + a) * ld + k0 + b * EPV;
+            if (!GUARD) r[v] = *(const ASTERIA_GLOBAL u32x4 *)(p);
+            else r[v] = load16<TI>(p, (a < rows) ? (k_left - b * EPV) : 0, vec_ok);
+        }
+    }
+
+    __device__ __forceinline__ void store(ASTERIA_LDS uint16_t *lds, int tid) const
+    {
+#pragma unroll
+        for (int v = 0; v < NV; ++v) {
+            const int idx = tid + 256 * v;
+            const int a = idx / VPR, b = idx % VPR;
+            ASTERIA_LDS uint16_t *dst = lds + a * PITCH + b * EPV;
+            if (sizeof(TI) == 2) {
+                *(ASTERIA_LDS u32x4 *)dst = r[v];
+            } else {
+                u32x2 hi, lo;
+                split4(r[v], hi, lo, NT == 2);
+                *(ASTERIA_LDS u32x2 *)dst = hi;
+                if (NT == 2) *(ASTERIA_LDS u32x2 *)(dst + TERM_ELEMS) = lo;
+            }
+        }
+    }
+};
+
+template <typename TA, typename TB, int NTA, int NTB, bool GUARD>
+__device__ __forceinline__ void gemm_bf16_mainloop(floatx16 (&acc)[2][2], const TA *Ab, const TB *Bb, int lda,
+                                                   int ldb, int row0, int col0, int rowsA, int rowsB, int K,
+                                                   bool vecA, bool vecB, ASTERIA_LDS uint16_t *smem, int tid,
+                                                   int wm, int wn, int r, int h)
+{
+    constexpr int BK = (NTA + NTB > 2) ? 32 : 64;
+    using StA = Bf16Stage<TA, NTA, BK>;
+    using StB = Bf16Stage<TB, NTB, BK>;
+    constexpr int KPL = BK / 2;          // k values per lane half and slab
+    constexpr int STEPS = KPL / 8;       // MFMA k-steps per slab (8 bf16 per lane and step)
+    StA sa;
+    StB sb;
+    ASTERIA_LDS uint16_t *const smemB = smem + 2 * StA::LDS_ELEMS;
+    const int nk = (K + BK - 1) / BK;
+    sa.template load<GUARD>(Ab, lda, row0, rowsA, 0, K, vecA, tid);
+    sb.template load<GUARD>(Bb, ldb, col0, rowsB, 0, K, vecB, tid);
+    sa.store(smem, tid);
+    sb.store(smemB, tid);
+    __syncthreads();
+    for (int kt = 0; kt < nk; ++kt) {
+        const int cur = kt & 1;
+        if (kt + 1 < nk) {
+            const int k0 = (kt + 1) * BK;
+            sa.template load<GUARD>(Ab, lda, row0, rowsA, k0, K - k0, vecA, tid);
+            sb.template load<GUARD>(Bb, ldb, col0, rowsB, k0, K - k0, vecB, tid);
+        }
+        const ASTERIA_LDS uint16_t *as = smem + cur * StA::LDS_ELEMS;
+        const ASTERIA_LDS uint16_t *bs = smemB + cur * StB::LDS_ELEMS;
+#pragma unroll
+        for (int s = 0; s < STEPS; ++s) {
+            const int kk = h * KPL + s * 8;      // the lane half owns a contiguous k range of the slab
+            u32x4 ah[2], al[2], bh[2], bl[2];
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                const int rr = wm * 64 + i * 32 + r;
+                ah[i] = *(const ASTERIA_LDS u32x4 *)(as + rr * StA::PITCH + kk);
+                if (NTA == 2) al[i] = *(const ASTERIA_LDS u32x4 *)(as + StA::TERM_ELEMS + rr * StA::PITCH + kk);
+            }
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const int cc = wn * 64 + j * 32 + r;
+                bh[j] = *(const ASTERIA_LDS u32x4 *)(bs + cc * StB::PITCH + kk);
+                if (NTB == 2) bl[j] = *(const ASTERIA_LDS u32x4 *)(bs + StB::TERM_ELEMS + cc * StB::PITCH + kk);
+            }
+            // small cross terms first, the leading product last
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j) {
+                    if (NTA == 2) acc[i][j] = MmaBf16::mma(al[i], bh[j], acc[i][j]);
+                    if (NTB == 2) acc[i][j] = MmaBf16::mma(ah[i], bl[j], acc[i][j]);
+                }
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j) acc[i][j] = MmaBf16::mma(ah[i], bh[j], acc[i][j]);
+        }
+        if (kt + 1 < nk) {
+            sa.store(smem + (cur ^ 1) * StA::LDS_ELEMS, tid);
+            sb.store(smemB + (cur ^ 1) * StB::LDS_ELEMS, tid);
+        }
+        __syncthreads();
+    }
+}
+
+template <typename TA, typename TB, int NTA, int NTB>
+__global__ __launch_bounds__(256) void gemm_bf16_grouped_kernel(const GemmProblem *__restrict__ probs, int nprobs,
+                                                                int total_tiles, const int *__restrict__ state)
+{
+    using MM = MmaBf16;
+    constexpr int BK = (NTA + NTB > 2) ? 32 : 64;
+    extern __shared__ __align__(16) unsigned char smem_raw[];
+    ASTERIA_LDS uint16_t *smem = (ASTERIA_LDS uint16_t *)smem_raw;
+    __shared__ float red[4];
+
+    const int per_xcd = (total_tiles + NUM_XCD - 1) / NUM_XCD;
+    const int t_global = (int)(blockIdx.x % NUM_XCD) * per_xcd + (int)(blockIdx.x / NUM_XCD);
+    if (t_global >= total_tiles) return;
+    int lo = 0, hi = nprobs - 1;
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (probs[mid].tile_start <= t_global) lo = mid; else hi = mid - 1;
+    }
+    const GemmProblem &P = probs[lo];
+    if (P.state_idx >= 0) {
+        const int st = state[P.state_idx];
+        if (!((1 << st) & P.state_mask)) return;
+    }
+    const int lt = t_global - P.tile_start;
+    int ti, tj;
+    if (P.flags & GEMM_SYM) tri_decode(lt, ti, tj);
+    else { ti = lt / P.tiles_n; tj = lt % P.tiles_n; }
+    const int M = P.M, N = P.N, K = P.K;
+    const int row0 = ti * BM, col0 = tj * BN;
+    const int rowsA = min(BM, M - row0), rowsB = min(BN, N - col0);
+    const TA *Ab = reinterpret_cast<const TA *>(P.A);
+    const TB *Bb = reinterpret_cast<const TB *>(P.B);
+    const int lda = P.lda, ldb = P.ldb;
+    const bool vecA = ((reinterpret_cast<uintptr_t>(Ab) & 15u) == 0) && ((((size_t)lda * sizeof(TA)) & 15u) == 0);
+    const bool vecB = ((reinterpret_cast<uintptr_t>(Bb) & 15u) == 0) && ((((size_t)ldb * sizeof(TB)) & 15u) == 0);
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int r = lane & 31, h = lane >> 5;
+
+    floatx16 acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+
+    const bool fast = vecA && vecB && rowsA == BM && rowsB == BN && (K % BK) == 0;
+    if (fast)
+        gemm_bf16_mainloop<TA, TB, NTA, NTB, false>(acc, Ab, Bb, lda, ldb, row0, col0, rowsA, rowsB, K, vecA, vecB,
+                                                    smem, tid, wm, wn, r, h);
+    else
+        gemm_bf16_mainloop<TA, TB, NTA, NTB, true>(acc, Ab, Bb, lda, ldb, row0, col0, rowsA, rowsB, K, vecA, vecB,
+                                                   smem, tid, wm, wn, r, h);
+    gemm_epilogue<MM, float>(P, acc, lt, ti, tj, row0, col0, rowsA, rowsB, wm, wn, r, h, lane, wave, tid, red);
+}
+
+template <typename TA, typename TB, int NTA, int NTB>
+inline hipError_t launch_gemm_bf16_grouped(const GemmProblem *probs, int nprobs, int total_tiles,
+                                           const int *state, hipStream_t stream)
+{
+    if (total_tiles <= 0 || nprobs <= 0) return hipSuccess;
+    constexpr int BK = (NTA + NTB > 2) ? 32 : 64;
+    auto kern = gemm_bf16_grouped_kernel<TA, TB, NTA, NTB>;
+    constexpr size_t lds = sizeof(uint16_t) * 2 *
+                           (size_t)(Bf16Stage<TA, NTA, BK>::LDS_ELEMS + Bf16Stage<TB, NTB, BK>::LDS_ELEMS);
+    static bool configured = false;
+    if (!configured) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        configured = true;
+    }
+    const int per_xcd = (total_tiles + NUM_XCD - 1) / NUM_XCD;
+    constexpr int kind = 32 | (sizeof(TA) == 2 ? 2 : 0) | (sizeof(TB) == 2 ? 4 : 0) | (NTA == 2 ? 64 : 0) | (NTB == 2 ? 128 : 0);
+    profile_begin(kind, stream);
+    hipLaunchKernelGGL(kern, dim3(per_xcd * NUM_XCD), dim3(256), lds, stream, probs, nprobs, total_tiles, state);
+    profile_end(stream);
+    return hipGetLastError();
+}
+
+}  // namespace asteria

@@ -287,24 +287,57 @@ __global__ __launch_bounds__(256) void root_init_kernel(const FactorDev *fd, con
         M = reinterpret_cast<TC *>(F.M32[0]); T = reinterpret_cast<TC *>(F.T32);
         X = reinterpret_cast<TC *>(F.X32b); ldm = F.ld32; ldx = F.ld32;
     }
+    // The tile pair (ti, tj) / (tj, ti) is walked in 32 x 32 sub-tiles.  P = A[sub(ti, tj)] and
+    // Q = A[sub(tj, ti)] are both read along rows (coalesced) into LDS; the symmetrised value at
+    // (r, c) of tile (ti, tj) is (P[r][c] + Q[c][r]) / 2 and the one at (c, r) of tile (tj, ti) is
+    // the same number, so every global read and write of this kernel runs along rows.
+    __shared__ float Ps[32][33], Qs[32][33];
     float rsum = 0.0f;
-    for (int e = threadIdx.x; e < BM * BN; e += 256) {
-        const int row = ti * BM + e / BN, col = tj * BN + e % BN;
-        if (row >= n || col >= n || row < col) continue;
-        const TC a = (TC)0.5 * ((TC)F.A[(size_t)row * lda + col] + (TC)F.A[(size_t)col * lda + row]);
-        const TC d = (row == col) ? (TC)1 : (TC)0;
-        const TC m = s * (a + eps * d);
-        const TC t = ca * d - cg * m;
-        M[(size_t)row * ldm + col] = m;
-        T[(size_t)row * ldm + col] = t;
-        X[(size_t)row * ldx + col] = xs * t;
-        if (row != col) {
-            M[(size_t)col * ldm + row] = m;
-            T[(size_t)col * ldm + row] = t;
-            X[(size_t)col * ldx + row] = xs * t;
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;     // 32 x 8 threads
+    for (int sub = 0; sub < 16; ++sub) {
+        const int si = sub >> 2, sj = sub & 3;
+        const int r0 = ti * BM + si * 32, c0 = tj * BN + sj * 32;
+        if (r0 >= n || c0 >= n) continue;                        // uniform over the workgroup
+        if (ti == tj && si < sj) continue;                       // covered by the mirrored sub-tile
+        __syncthreads();
+        for (int rr = ty; rr < 32; rr += 8) {
+            const int r = r0 + rr, c = c0 + tx;
+            Ps[rr][tx] = (r < n && c < n) ? F.A[(size_t)r * lda + c] : 0.0f;
+            const int r2 = c0 + rr, c2 = r0 + tx;                // sub-tile (sj, si) of tile (tj, ti)
+            Qs[rr][tx] = (r2 < n && c2 < n) ? F.A[(size_t)r2 * lda + c2] : 0.0f;
         }
-        const float r = (float)(m - d);
-        rsum += (row != col) ? 2.0f * r * r : r * r;
+        __syncthreads();
+        const bool diag_sub = (ti == tj && si == sj);
+        for (int rr = ty; rr < 32; rr += 8) {
+            // element (r, c) of tile (ti, tj)
+            {
+                const int r = r0 + rr, c = c0 + tx;
+                if (r < n && c < n) {
+                    const TC av = (TC)0.5 * ((TC)Ps[rr][tx] + (TC)Qs[tx][rr]);
+                    const TC d = (r == c) ? (TC)1 : (TC)0;
+                    const TC m = s * (av + eps * d);
+                    const TC t = ca * d - cg * m;
+                    M[(size_t)r * ldm + c] = m;
+                    T[(size_t)r * ldm + c] = t;
+                    X[(size_t)r * ldx + c] = xs * t;
+                    const float e = (float)(m - d);
+                    // a diagonal sub-tile holds both triangles itself; every other one stands for two
+                    rsum += diag_sub ? e * e : 2.0f * e * e;
+                }
+            }
+            // element (r2, c2) of the mirrored tile (tj, ti): same value, written along its own rows
+            if (!diag_sub) {
+                const int r2 = c0 + rr, c2 = r0 + tx;
+                if (r2 < n && c2 < n) {
+                    const TC av = (TC)0.5 * ((TC)Ps[tx][rr] + (TC)Qs[rr][tx]);
+                    const TC m = s * av;                          // off the diagonal: no eps, d = 0
+                    const TC t = -cg * m;
+                    M[(size_t)r2 * ldm + c2] = m;
+                    T[(size_t)r2 * ldm + c2] = t;
+                    X[(size_t)r2 * ldx + c2] = xs * t;
+                }
+            }
+        }
     }
     __shared__ float red[4];
     rsum = wave_sum(rsum);

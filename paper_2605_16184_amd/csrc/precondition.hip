@@ -1,14 +1,18 @@
 // asteria_precondition: P = X_L G X_R for a batch of blocks (paper Eq. 1).
 //
-// Two chained grouped GEMMs on the fp32 matrix cores with fp32 accumulation:
-//   U = G X_R      (X_R symmetric, so its rows serve as the k-contiguous B operand)
-//   P = X_L U      (U is consumed k-major straight from the workspace)
-// fp32 operands keep the full precision of the roots; a bf16 cast of X_L / X_R would cost
-// about 1e-2 relative error in P at condition numbers near 1e6.
+// Two chained grouped GEMMs with fp32 accumulation.  A plain bf16 cast of X_L / X_R would cost
+// about 1e-2 relative error in P at condition numbers near 1e6, so the roots are never rounded
+// to a single bf16:
+//   bf16 gradients (the training case): bf16 matrix cores with the fp32 operands split into
+//     hi + lo bf16 terms on the fly (about 16 bits kept):
+//       U^T = X_R G^T   (X_R split, G exact: 2 MFMA passes; both operands k-contiguous)
+//       P   = X_L U     (X_L and U^T split: 3 MFMA passes; both operands k-contiguous)
+//   fp32 gradients: fp32 matrix cores,  U = G X_R  then  P = X_L U  (U read k-major).
 #include <vector>
 
 #include "common.h"
 #include "gemm.h"
+#include "gemm_bf16.h"
 
 using namespace asteria;
 
@@ -37,8 +41,11 @@ extern "C" size_t asteria_precondition_workspace_bytes(const asteria_pblock *blo
 {
     if (!blocks || nblocks <= 0) return 0;
     size_t bytes = table_bytes(nblocks);
-    for (int i = 0; i < nblocks; ++i)
-        bytes += Carver::need((size_t)blocks[i].m * ld4(blocks[i].n), sizeof(float));
+    for (int i = 0; i < nblocks; ++i) {
+        const asteria_pblock &k = blocks[i];
+        const size_t elems = (k.g_dtype == ASTERIA_BF16) ? (size_t)k.n * ld4(k.m) : (size_t)k.m * ld4(k.n);
+        bytes += Carver::need(elems, sizeof(float));
+    }
     return bytes;
 }
 
@@ -54,40 +61,58 @@ extern "C" asteria_status asteria_precondition(const asteria_pblock *blocks, int
     Carver cv(ws);
     GemmProblem *d1 = cv.take<GemmProblem>(nblocks);
     GemmProblem *d2 = cv.take<GemmProblem>(nblocks);
-    // first-stage problems are grouped by gradient dtype (one launch each); second stage is one launch
-    std::vector<GemmProblem> p1[2], p2;
-    int tiles1[2] = {0, 0}, tiles2 = 0;
+    // problems are grouped by gradient dtype: one launch per stage and dtype
+    std::vector<GemmProblem> p1[2], p2[2];
+    int tiles1[2] = {0, 0}, tiles2[2] = {0, 0};
     for (int i = 0; i < nblocks; ++i) {
         const asteria_pblock &k = blocks[i];
-        const int ldu = ld4(k.n);
-        float *U = cv.take<float>((size_t)k.m * ldu);
+        const int d = k.g_dtype;
         const int tm = (k.m + BM - 1) / BM, tn = (k.n + BN - 1) / BN;
         GemmProblem p;
         memset(&p, 0, sizeof(p));
         p.state_idx = -1; p.state_mask = ~0;
         p.alpha = 1.0f; p.beta = 0.0f;
-        p.M = k.m; p.N = k.n; p.tiles_n = tn;
-        // U = G X_R
-        p.A = k.G; p.lda = k.ldg; p.B = k.XR; p.ldb = k.ldxr; p.K = k.n;
-        p.C = U; p.ldc = ldu; p.flags = 0;
-        p.tile_start = tiles1[k.g_dtype];
-        tiles1[k.g_dtype] += tm * tn;
-        p1[k.g_dtype].push_back(p);
-        // P = X_L U
-        p.A = k.XL; p.lda = k.ldxl; p.B = U; p.ldb = ldu; p.K = k.m;
-        p.C = k.P; p.ldc = k.ldp; p.flags = (k.p_dtype == ASTERIA_BF16) ? GEMM_C_BF16 : 0;
-        p.tile_start = tiles2;
-        tiles2 += tm * tn;
-        p2.push_back(p);
+        if (d == ASTERIA_BF16) {
+            const int ldu = ld4(k.m);
+            float *Ut = cv.take<float>((size_t)k.n * ldu);
+            // U^T = X_R G^T : rows of X_R against rows of G, contraction over n
+            p.M = k.n; p.N = k.m; p.K = k.n; p.tiles_n = tm;
+            p.A = k.XR; p.lda = k.ldxr; p.B = k.G; p.ldb = k.ldg; p.C = Ut; p.ldc = ldu; p.flags = 0;
+            p.tile_start = tiles1[d]; tiles1[d] += tn * tm;
+            p1[d].push_back(p);
+            // P = X_L U : rows of X_L against rows of U^T, contraction over m
+            p.M = k.m; p.N = k.n; p.K = k.m; p.tiles_n = tn;
+            p.A = k.XL; p.lda = k.ldxl; p.B = Ut; p.ldb = ldu; p.C = k.P; p.ldc = k.ldp;
+            p.flags = (k.p_dtype == ASTERIA_BF16) ? GEMM_C_BF16 : 0;
+            p.tile_start = tiles2[d]; tiles2[d] += tm * tn;
+            p2[d].push_back(p);
+        } else {
+            const int ldu = ld4(k.n);
+            float *U = cv.take<float>((size_t)k.m * ldu);
+            p.M = k.m; p.N = k.n; p.tiles_n = tn;
+            // U = G X_R
+            p.A = k.G; p.lda = k.ldg; p.B = k.XR; p.ldb = k.ldxr; p.K = k.n; p.C = U; p.ldc = ldu; p.flags = 0;
+            p.tile_start = tiles1[d]; tiles1[d] += tm * tn;
+            p1[d].push_back(p);
+            // P = X_L U
+            p.A = k.XL; p.lda = k.ldxl; p.B = U; p.ldb = ldu; p.K = k.m; p.C = k.P; p.ldc = k.ldp;
+            p.flags = (k.p_dtype == ASTERIA_BF16) ? GEMM_C_BF16 : 0;
+            p.tile_start = tiles2[d]; tiles2[d] += tm * tn;
+            p2[d].push_back(p);
+        }
     }
-    GemmProblem *d1b = d1 + p1[0].size();
+    GemmProblem *d1b = d1 + p1[0].size(), *d2b = d2 + p2[0].size();
     if (!p1[0].empty()) ASTERIA_HIP_TRY(upload_async(d1, p1[0].data(), p1[0].size() * sizeof(GemmProblem), stream));
     if (!p1[1].empty()) ASTERIA_HIP_TRY(upload_async(d1b, p1[1].data(), p1[1].size() * sizeof(GemmProblem), stream));
-    ASTERIA_HIP_TRY(upload_async(d2, p2.data(), p2.size() * sizeof(GemmProblem), stream));
-    if (!p1[0].empty())
+    if (!p2[0].empty()) ASTERIA_HIP_TRY(upload_async(d2, p2[0].data(), p2[0].size() * sizeof(GemmProblem), stream));
+    if (!p2[1].empty()) ASTERIA_HIP_TRY(upload_async(d2b, p2[1].data(), p2[1].size() * sizeof(GemmProblem), stream));
+    if (!p1[0].empty()) {
         ASTERIA_HIP_TRY((launch_gemm_grouped<float, float, float, false, false>(d1, (int)p1[0].size(), tiles1[0], nullptr, stream)));
-    if (!p1[1].empty())
-        ASTERIA_HIP_TRY((launch_gemm_grouped<float, bf16_t, float, false, false>(d1b, (int)p1[1].size(), tiles1[1], nullptr, stream)));
-    ASTERIA_HIP_TRY((launch_gemm_grouped<float, float, float, false, true>(d2, (int)p2.size(), tiles2, nullptr, stream)));
+        ASTERIA_HIP_TRY((launch_gemm_grouped<float, float, float, false, true>(d2, (int)p2[0].size(), tiles2[0], nullptr, stream)));
+    }
+    if (!p1[1].empty()) {
+        ASTERIA_HIP_TRY((launch_gemm_bf16_grouped<float, bf16_t, 2, 1>(d1b, (int)p1[1].size(), tiles1[1], nullptr, stream)));
+        ASTERIA_HIP_TRY((launch_gemm_bf16_grouped<float, float, 2, 2>(d2b, (int)p2[1].size(), tiles2[1], nullptr, stream)));
+    }
     return ASTERIA_OK;
 }

@@ -1,17 +1,55 @@
 // asteria_stats_update: L <- beta L + (1-beta) G G^T, R <- beta R + (1-beta) G^T G for a batch
 // of blocks (the Kronecker-factor statistics kept on the GPU; paper Sec. I, Sec. III-B).
 //
-// Both products are symmetric grouped GEMMs on the matrix cores: G G^T reads G with k
-// contiguous, G^T G reads the same memory k-major, so G is never transposed in HBM.  The EMA
-// is fused in the epilogue; only tiles on/below the diagonal are computed and mirrored.
+// Both products are symmetric grouped GEMMs on the matrix cores with the EMA fused in the
+// epilogue; only tiles on/below the diagonal are computed and mirrored.
+//   bf16 gradients: bf16 MFMA (products exact in fp32).  G G^T reads G as is; for G^T G a
+//     transposed bf16 copy of G is written to the workspace first (one extra HBM round trip of
+//     G, ~10% of the call's traffic) so that both products read k-contiguous operands.
+//   fp32 gradients: fp32 MFMA; G^T G reads G k-major, no copy.
 #include <vector>
 
 #include "common.h"
 #include "gemm.h"
+#include "gemm_bf16.h"
 
 using namespace asteria;
 
 namespace {
+
+inline int ld8(int n) { return (n + 7) & ~7; }
+
+// G^T for a batch of bf16 blocks: 64 x 64 tiles through LDS, reads and writes along rows.
+struct TransposeJob {
+    const uint16_t *src;   // m x n, ld = lds_
+    uint16_t *dst;         // n x m, ld = ldd
+    int m, n, lds_, ldd;
+    int tile_start;
+};
+
+__global__ __launch_bounds__(256) void transpose_bf16_kernel(const TransposeJob *jobs, int njobs)
+{
+    int lo = 0, hi = njobs - 1;
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (jobs[mid].tile_start <= (int)blockIdx.x) lo = mid; else hi = mid - 1;
+    }
+    const TransposeJob &J = jobs[lo];
+    const int lt = (int)blockIdx.x - J.tile_start;
+    const int tcols = (J.n + 63) / 64;
+    const int ti = lt / tcols, tj = lt % tcols;       // tile of src: rows ti, columns tj
+    __shared__ uint16_t tile[64][66];
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    for (int rr = ty; rr < 64; rr += 4) {
+        const int r = ti * 64 + rr, c = tj * 64 + tx;
+        tile[rr][tx] = (r < J.m && c < J.n) ? J.src[(size_t)r * J.lds_ + c] : (uint16_t)0;
+    }
+    __syncthreads();
+    for (int rr = ty; rr < 64; rr += 4) {
+        const int r = tj * 64 + rr, c = ti * 64 + tx;  // element (r, c) of dst = src(c, r)
+        if (r < J.n && c < J.m) J.dst[(size_t)r * J.ldd + c] = tile[tx][rr];
+    }
+}
 
 struct StatsTables {
     std::vector<GemmProblem> L[2], R[2];   // by dtype
@@ -64,9 +102,13 @@ void build(const asteria_block *b, int nblocks, float beta, StatsTables &t)
 
 extern "C" size_t asteria_stats_update_workspace_bytes(const asteria_block *blocks, int nblocks)
 {
-    (void)blocks;
-    if (nblocks <= 0) return 0;
-    return 2 * Carver::need((size_t)nblocks, sizeof(GemmProblem)) + 4 * 256;
+    if (!blocks || nblocks <= 0) return 0;
+    size_t bytes = 2 * Carver::need((size_t)nblocks, sizeof(GemmProblem)) +
+                   Carver::need((size_t)nblocks, sizeof(TransposeJob)) + 8 * 256;
+    for (int i = 0; i < nblocks; ++i)
+        if (blocks[i].g_dtype == ASTERIA_BF16 && blocks[i].R && blocks[i].m > 0 && blocks[i].n > 0)
+            bytes += Carver::need((size_t)blocks[i].n * ld8(blocks[i].m), sizeof(uint16_t));
+    return bytes;
 }
 
 extern "C" asteria_status asteria_stats_update(const asteria_block *blocks, int nblocks, float beta,
@@ -81,6 +123,33 @@ extern "C" asteria_status asteria_stats_update(const asteria_block *blocks, int 
     StatsTables t;
     build(blocks, nblocks, beta, t);
     Carver cv(ws);
+    // transposed bf16 copies for the G^T G side
+    {
+        std::vector<TransposeJob> jobs;
+        int tiles = 0;
+        size_t ri = 0;
+        TransposeJob *d_jobs = cv.take<TransposeJob>(nblocks);
+        for (int i = 0; i < nblocks; ++i) {
+            const asteria_block &k = blocks[i];
+            if (k.g_dtype != ASTERIA_BF16 || !k.R) continue;
+            const int ldt = ld8(k.m);
+            uint16_t *Gt = cv.take<uint16_t>((size_t)k.n * ldt);
+            TransposeJob j;
+            j.src = reinterpret_cast<const uint16_t *>(k.G); j.dst = Gt;
+            j.m = k.m; j.n = k.n; j.lds_ = k.ldg; j.ldd = ldt;
+            j.tile_start = tiles;
+            tiles += ((k.m + 63) / 64) * ((k.n + 63) / 64);
+            jobs.push_back(j);
+            // the R problem of this block reads G^T with k (= m) contiguous
+            GemmProblem &p = t.R[ASTERIA_BF16][ri++];
+            p.A = Gt; p.B = Gt; p.lda = ldt; p.ldb = ldt;
+        }
+        if (!jobs.empty()) {
+            ASTERIA_HIP_TRY(upload_async(d_jobs, jobs.data(), jobs.size() * sizeof(TransposeJob), stream));
+            hipLaunchKernelGGL(transpose_bf16_kernel, dim3(tiles), dim3(256), 0, stream, d_jobs, (int)jobs.size());
+            ASTERIA_HIP_TRY(hipGetLastError());
+        }
+    }
     for (int d = 0; d < 2; ++d) {
         GemmProblem *dL = nullptr, *dR = nullptr;
         if (!t.L[d].empty()) {
@@ -95,8 +164,8 @@ extern "C" asteria_status asteria_stats_update(const asteria_block *blocks, int 
             if (dL) ASTERIA_HIP_TRY((launch_gemm_grouped<float, float, float, false, false>(dL, (int)t.L[d].size(), t.tilesL[d], nullptr, stream)));
             if (dR) ASTERIA_HIP_TRY((launch_gemm_grouped<float, float, float, true, true>(dR, (int)t.R[d].size(), t.tilesR[d], nullptr, stream)));
         } else {
-            if (dL) ASTERIA_HIP_TRY((launch_gemm_grouped<float, bf16_t, bf16_t, false, false>(dL, (int)t.L[d].size(), t.tilesL[d], nullptr, stream)));
-            if (dR) ASTERIA_HIP_TRY((launch_gemm_grouped<float, bf16_t, bf16_t, true, true>(dR, (int)t.R[d].size(), t.tilesR[d], nullptr, stream)));
+            if (dL) ASTERIA_HIP_TRY((launch_gemm_bf16_grouped<bf16_t, bf16_t, 1, 1>(dL, (int)t.L[d].size(), t.tilesL[d], nullptr, stream)));
+            if (dR) ASTERIA_HIP_TRY((launch_gemm_bf16_grouped<bf16_t, bf16_t, 1, 1>(dR, (int)t.R[d].size(), t.tilesR[d], nullptr, stream)));
         }
     }
     return ASTERIA_OK;

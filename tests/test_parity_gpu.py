@@ -310,8 +310,12 @@ def test_precondition_ragged_batch_fp32_and_bf16_outputs():
         items.append((XL, G, XR, P))
     ast.precondition(items)
     torch.cuda.synchronize()
-    for (XL, G, XR, P), Po, (_, _, _, pdt) in zip(items, refs, shapes):
-        assert relF(P, Po) <= (TOL_PRECOND if pdt == torch.bfloat16 else 1e-5), relF(P, Po)
+    for (XL, G, XR, P), Po, (_, _, gdt, pdt) in zip(items, refs, shapes):
+        # fp32 gradients run on the fp32 matrix cores; bf16 gradients on the bf16 cores with the
+        # roots split into two bf16 terms (~16 bits); a bf16 store rounds to 8 bits
+        tol = TOL_PRECOND if pdt == torch.bfloat16 else (1e-4 if gdt == torch.bfloat16 else 1e-5)
+        print("precondition", tuple(G.shape), gdt, pdt, relF(P, Po))
+        assert relF(P, Po) <= tol, relF(P, Po)
         assert torch.all(P._base[:, P.shape[1]:] == -777.0)
 
 
@@ -326,7 +330,8 @@ def test_precondition_full_size_1024_with_gpu_roots():
     ast.precondition([(XL, G, XR, P)])
     torch.cuda.synchronize()
     Po = oracle.precondition(np64(XL), np64(G), np64(XR))
-    assert relF(P, Po) <= 1e-5
+    print("precondition 1024 relF", relF(P, Po))
+    assert relF(P, Po) <= 1e-4      # split-bf16 roots; the stated bar is 1e-2
 
 
 def test_end_to_end_single_block_config_against_the_float64_pipeline():
