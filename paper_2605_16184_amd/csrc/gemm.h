@@ -161,6 +161,17 @@ template <> struct StoreLds<float, float> {
 template <> struct StoreLds<double, double> {
     __device__ static __forceinline__ void run(ASTERIA_LDS double *dst, u32x4 v) { *(ASTERIA_LDS u32x4 *)(dst) = v; }
 };
+template <> struct StoreLds<double, float> {   // fp32 data accumulated on the fp64 matrix cores
+    __device__ static __forceinline__ void run(ASTERIA_LDS double *dst, u32x4 v)
+    {
+        typedef double doublex2 __attribute__((ext_vector_type(2)));
+        doublex2 a, b;
+        a[0] = (double)__uint_as_float(v[0]); a[1] = (double)__uint_as_float(v[1]);
+        b[0] = (double)__uint_as_float(v[2]); b[1] = (double)__uint_as_float(v[3]);
+        ((ASTERIA_LDS doublex2 *)dst)[0] = a;
+        ((ASTERIA_LDS doublex2 *)dst)[1] = b;
+    }
+};
 template <> struct StoreLds<float, bf16_t> {
     __device__ static __forceinline__ void run(ASTERIA_LDS float *dst, u32x4 v)
     {

@@ -4,11 +4,19 @@
 // soap_step:   four grouped fp32-MFMA GEMMs (rotate in: G Q_R, then Q_L^T (.); rotate out:
 //              N' Q_R^T, then Q_L (.)) around one HBM-streaming Adam kernel.  Q_L / Q_R stay
 //              fp32 operands: a bf16 cast of an eigenbasis costs 0.1-0.5 relative error in N.
-// soap_refresh: Z^T = Q^T A by one grouped GEMM (columns of Z become contiguous rows), then a
-//              Householder QR that walks those rows with one workgroup per factor
-//              (wavefront-reduced norms and dot products), accumulation of Q^T by applying the
-//              reflectors backwards to the identity, and a transposing write-back with the
-//              column signs that make diag(R) >= 0.
+// soap_refresh: Z^T = Q^T A by one grouped GEMM (columns of Z become contiguous rows), then the
+//              thin QR factor of Z with diag(R) > 0 - the same Q a Householder QR with that sign
+//              convention returns, since the factorisation is unique - by block Gram-Schmidt
+//              with re-orthogonalisation: panels of 128 columns; each panel is projected twice
+//              against all finished panels (two grouped fp32-MFMA GEMMs per projection, so the
+//              O(n^3) work runs on the matrix cores), then orthonormalised by Cholesky QR applied
+//              twice: Gram matrix of the panel on the fp64 matrix cores, 128 x 128 Cholesky
+//              factor and its inverse in LDS (fp64), panel <- L^-1 panel on the fp32 matrix
+//              cores.  The second application removes the cond^2 * 2^-24 loss of the first, so
+//              ||Q^T Q - I|| ends at round-off level as long as cond(Z) * 2^-24 < 1, and L's
+//              positive diagonal gives the diag(R) > 0 convention.  A transposing write-back
+//              stores Q.
+#include <algorithm>
 #include <vector>
 
 #include "common.h"
@@ -19,13 +27,6 @@ using namespace asteria;
 namespace {
 
 inline int ld4(int n) { return (n + 3) & ~3; }
-
-__device__ __forceinline__ float wave_sum_f(float v)
-{
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
-    return v;
-}
 
 // ---------------------------------------------------------------------------------------------
 // Adam in the rotated basis, elementwise over every block.
@@ -64,101 +65,82 @@ __global__ __launch_bounds__(256) void adam_rotated_kernel(const AdamBlock *bloc
 }
 
 // ---------------------------------------------------------------------------------------------
-// Householder QR on Z^T (row c of Zt = column c of Z), one workgroup of 1024 threads per factor.
+// Orthonormalisation of Z^T (row c of Zt = column c of Z), in place.
 struct QrFactor {
-    float *Zt;      // n x ldz, overwritten: row j keeps the reflector v_j in columns j..n-1
-    float *Qt;      // n x ldz, receives Q^T
+    float *Zt;      // n x ldz; rows become the orthonormal columns of Q, in order
     float *Qout;    // caller's Q (n x ldq)
-    float *vtv;     // n
-    float *rsign;   // n: +1 / -1 multiplier of column j of Q so that diag(R) >= 0
+    double *gram;   // QR_PANEL x QR_PANEL: Gram matrix of the current panel
+    float *winv;    // QR_PANEL x QR_PANEL: inverse Cholesky factor of the current panel
     int n, ldz, ldq;
     int tile_start; // for the transposing write-back (square 32 x 32 tiles)
+    int bad;        // set to 1 when a column could not be normalised
 };
 
 constexpr int QR_THREADS = 1024;
-constexpr int QR_WAVES = QR_THREADS / 64;
+constexpr int QR_PANEL = 128;
+constexpr int QR_MAXN = 1 << 20;
 
-__device__ __forceinline__ float block_sum_1024(float v, float *red)
+// One workgroup per (factor, panel).  In: the fp64 Gram matrix G = P P^T of the panel's rows
+// (rows x rows, leading dimension QR_PANEL).  Out: W = L^-1 in fp32, where G = L L^T is the
+// Cholesky factorisation (positive diagonal), so that W P has orthonormal rows and P = L (W P)
+// is the QR relation with a positive diagonal.  Everything runs in LDS in fp64.
+__global__ __launch_bounds__(QR_THREADS) void panel_chol_inverse_kernel(QrFactor *fs, const int *fidx, int panel)
 {
-    v = wave_sum_f(v);
+    QrFactor &F = fs[fidx[blockIdx.x]];
+    const int rows = min(QR_PANEL, F.n - panel * QR_PANEL);
+    extern __shared__ __align__(16) unsigned char chol_smem[];
+    double *L = reinterpret_cast<double *>(chol_smem);            // rows x rows, pitch QR_PANEL + 1
+    constexpr int PITCH = QR_PANEL + 1;
+    __shared__ int bad_flag;
+    const int tid = threadIdx.x;
+    if (tid == 0) bad_flag = 0;
+    for (int e = tid; e < rows * rows; e += QR_THREADS) {
+        const int i = e / rows, j = e % rows;
+        L[i * PITCH + j] = F.gram[(size_t)i * QR_PANEL + j];
+    }
     __syncthreads();
-    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
-    __syncthreads();
-    float t = 0.0f;
-#pragma unroll
-    for (int w = 0; w < QR_WAVES; ++w) t += red[w];
-    return t;
+    // right-looking Cholesky, lower triangle
+    for (int k = 0; k < rows; ++k) {
+        double piv = L[k * PITCH + k];
+        if (!(piv > 0.0) || !(piv < 1e300)) {            // not positive definite: keep going with a tiny pivot
+            if (tid == 0) bad_flag = 1;
+            piv = 1e-300;
+        }
+        const double d = sqrt(piv);
+        __syncthreads();
+        for (int i = k + tid; i < rows; i += QR_THREADS) L[i * PITCH + k] = (i == k) ? d : L[i * PITCH + k] / d;
+        __syncthreads();
+        const int m = rows - k - 1;
+        for (int e = tid; e < m * m; e += QR_THREADS) {
+            const int i = k + 1 + e / m, j = k + 1 + e % m;
+            if (j <= i) L[i * PITCH + j] -= L[i * PITCH + k] * L[j * PITCH + k];
+        }
+        __syncthreads();
+    }
+    // W = L^-1 by forward substitution, one column of W per thread (W lower triangular).  The
+    // Gram matrix is in LDS now, so its global buffer holds W in fp64 (a thread only reads back
+    // what it wrote itself); the fp32 copy feeds the matrix cores.
+    double *W = F.gram;
+    for (int c = tid; c < rows; c += QR_THREADS) {
+        for (int i = 0; i < rows; ++i) {
+            double s = (i == c) ? 1.0 : 0.0;
+            for (int j = c; j < i; ++j) s -= L[i * PITCH + j] * W[(size_t)j * QR_PANEL + c];
+            const double w = (i < c) ? 0.0 : s / L[i * PITCH + i];
+            W[(size_t)i * QR_PANEL + c] = w;
+            F.winv[(size_t)i * QR_PANEL + c] = (float)w;
+        }
+    }
+    if (tid == 0 && bad_flag) F.bad = 1;
 }
 
-__global__ __launch_bounds__(QR_THREADS) void householder_rows_kernel(const QrFactor *fs, int32_t *info, int first)
+__global__ void qr_info_kernel(const QrFactor *fs, int nf, int32_t *info, int first)
 {
-    const QrFactor &F = fs[blockIdx.x];
-    const int n = F.n, ld = F.ldz;
-    __shared__ float red[QR_WAVES];
-    __shared__ float sh_f;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    bool bad = false;
-
-    // forward sweep: R = H_{n-1} ... H_0 Z
-    for (int j = 0; j < n; ++j) {
-        float *vj = F.Zt + (size_t)j * ld;
-        float s = 0.0f;
-        for (int i = j + threadIdx.x; i < n; i += QR_THREADS) { const float x = vj[i]; s += x * x; }
-        const float nrm2 = block_sum_1024(s, red);
-        if (threadIdx.x == 0) {
-            const float x0 = vj[j];
-            const float nrm = sqrtf(nrm2);
-            const float sgn = (x0 >= 0.0f) ? 1.0f : -1.0f;
-            const float v0 = x0 + sgn * nrm;
-            vj[j] = v0;
-            const float vt = nrm2 - x0 * x0 + v0 * v0;
-            F.vtv[j] = vt;
-            // R_jj = -sgn * nrm; flip column j of Q when that is negative
-            F.rsign[j] = (nrm > 0.0f && sgn > 0.0f) ? -1.0f : 1.0f;
-            sh_f = vt;
-        }
-        __syncthreads();
-        const float vt = sh_f;
-        if (!(vt == vt) || vt > 3.0e38f) bad = true;
-        if (vt > 0.0f && !bad) {
-            // every wavefront applies H_j to its share of the remaining columns of Z
-            for (int c = j + 1 + wave; c < n; c += QR_WAVES) {
-                float *zc = F.Zt + (size_t)c * ld;
-                float d = 0.0f;
-                for (int i = j + lane; i < n; i += 64) d += vj[i] * zc[i];
-                d = wave_sum_f(d);
-                const float f = 2.0f * d / vt;
-                for (int i = j + lane; i < n; i += 64) zc[i] -= f * vj[i];
-            }
-        }
-        __syncthreads();
-    }
-    // Q^T = (H_0 ... H_{n-1})^T applied to I, built backwards: rows >= j of Qt are touched by H_j
-    for (int c = wave; c < n; c += QR_WAVES) {
-        float *qc = F.Qt + (size_t)c * ld;
-        for (int i = lane; i < n; i += 64) qc[i] = (i == c) ? 1.0f : 0.0f;
-    }
-    __syncthreads();
-    for (int j = n - 1; j >= 0; --j) {
-        const float *vj = F.Zt + (size_t)j * ld;
-        const float vt = F.vtv[j];
-        if (vt > 0.0f && !bad) {
-            for (int c = j + wave; c < n; c += QR_WAVES) {
-                float *qc = F.Qt + (size_t)c * ld;
-                float d = 0.0f;
-                for (int i = j + lane; i < n; i += 64) d += vj[i] * qc[i];
-                d = wave_sum_f(d);
-                const float f = 2.0f * d / vt;
-                for (int i = j + lane; i < n; i += 64) qc[i] -= f * vj[i];
-            }
-        }
-        __syncthreads();
-    }
-    if (threadIdx.x == 0 && info) info[first + blockIdx.x] = bad ? ASTERIA_INFO_NOT_PD : ASTERIA_INFO_OK;
+    const int f = blockIdx.x * blockDim.x + threadIdx.x;
+    if (f < nf && info) info[first + f] = fs[f].bad ? ASTERIA_INFO_NOT_PD : ASTERIA_INFO_OK;
 }
 
-// Q[i][c] = rsign[c] * Qt[c][i], 32 x 32 tiles through LDS
-__global__ __launch_bounds__(256) void transpose_sign_kernel(const QrFactor *fs, int nf)
+// Q[i][c] = Zt[c][i], 32 x 32 tiles through LDS
+__global__ __launch_bounds__(256) void transpose_out_kernel(const QrFactor *fs, int nf)
 {
     int lo = 0, hi = nf - 1;
     while (lo < hi) {
@@ -173,7 +155,7 @@ __global__ __launch_bounds__(256) void transpose_sign_kernel(const QrFactor *fs,
     const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
     for (int r = ty; r < 32; r += 8) {
         const int c = ti * 32 + r, i = tj * 32 + tx;
-        tile[r][tx] = (c < F.n && i < F.n) ? F.Qt[(size_t)c * F.ldz + i] * F.rsign[c] : 0.0f;
+        tile[r][tx] = (c < F.n && i < F.n) ? F.Zt[(size_t)c * F.ldz + i] : 0.0f;
     }
     __syncthreads();
     for (int r = ty; r < 32; r += 8) {
@@ -277,62 +259,97 @@ extern "C" asteria_status asteria_soap_step(const asteria_sblock *blocks, int nb
     return ASTERIA_OK;
 }
 
+namespace {
+
+size_t refresh_factor_bytes(int n)
+{
+    const int np = (n + QR_PANEL - 1) / QR_PANEL;
+    return Carver::need((size_t)n * ld4(n), sizeof(float)) +            // Z^T, becomes Q^T
+           Carver::need((size_t)QR_PANEL * ld4(n), sizeof(float)) +     // projection coefficients of one panel
+           Carver::need((size_t)QR_PANEL * QR_PANEL, sizeof(double)) +  // panel Gram matrix / fp64 inverse factor
+           Carver::need((size_t)QR_PANEL * QR_PANEL, sizeof(float)) +   // fp32 inverse factor
+           (size_t)(1 + 4 * np) * sizeof(GemmProblem) + (size_t)np * sizeof(int) + sizeof(QrFactor);
+}
+
+size_t refresh_fixed_bytes(int n_max)
+{
+    const int np = (n_max + QR_PANEL - 1) / QR_PANEL;
+    return (size_t)(5 * np + 4) * 256 + 4096;   // alignment slack of the per-panel tables
+}
+
+}  // namespace
+
 extern "C" size_t asteria_soap_refresh_workspace_bytes(const asteria_factor *f, int nfactors, size_t *min_bytes)
 {
     if (min_bytes) *min_bytes = 0;
     if (!f || nfactors <= 0) return 0;
-    size_t total = 4096, biggest = 0;
+    size_t total = 0, biggest = 0;
+    int n_max = 0;
     for (int i = 0; i < nfactors; ++i) {
         const int n = f[i].n;
         if (n <= 0) return 0;
-        const size_t b = 2 * Carver::need((size_t)n * ld4(n), sizeof(float)) + 2 * Carver::need((size_t)n, sizeof(float)) +
-                         Carver::need(1, sizeof(GemmProblem)) + Carver::need(1, sizeof(QrFactor));
+        const size_t b = refresh_factor_bytes(n);
         total += b;
         biggest = b > biggest ? b : biggest;
+        n_max = n > n_max ? n : n_max;
     }
-    if (min_bytes) *min_bytes = biggest + 4096;
-    return total;
+    if (min_bytes) *min_bytes = biggest + refresh_fixed_bytes(n_max);
+    return total + refresh_fixed_bytes(n_max);
 }
 
 extern "C" asteria_status asteria_soap_refresh(const asteria_factor *f, int nfactors, int32_t *info,
                                                void *ws, size_t ws_bytes, void *stream_)
 {
     if (!f || nfactors <= 0) return ASTERIA_INVALID_ARG;
-    for (int i = 0; i < nfactors; ++i)
+    int n_all = 0;
+    for (int i = 0; i < nfactors; ++i) {
         if (!f[i].A || !f[i].X || f[i].n <= 0 || f[i].lda < f[i].n || f[i].ldx < f[i].n) return ASTERIA_INVALID_ARG;
+        if (f[i].n > QR_MAXN) return ASTERIA_UNSUPPORTED;
+        n_all = f[i].n > n_all ? f[i].n : n_all;
+    }
     if (!ws) return ASTERIA_WORKSPACE_TOO_SMALL;
     if (reinterpret_cast<uintptr_t>(ws) & 255u) return ASTERIA_INVALID_ARG;   // workspace must be 256-byte aligned
     hipStream_t stream = reinterpret_cast<hipStream_t>(stream_);
+    constexpr size_t chol_lds = sizeof(double) * QR_PANEL * (QR_PANEL + 1);
+    static bool chol_configured = false;
+    if (!chol_configured) {
+        ASTERIA_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(panel_chol_inverse_kernel),
+                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)chol_lds));
+        chol_configured = true;
+    }
 
     int first = 0;
     while (first < nfactors) {
         // largest pass that fits the workspace
-        size_t used = 4096;
+        size_t used = refresh_fixed_bytes(n_all);
         int cnt = 0;
         while (first + cnt < nfactors) {
-            const int n = f[first + cnt].n;
-            const size_t b = 2 * Carver::need((size_t)n * ld4(n), sizeof(float)) + 2 * Carver::need((size_t)n, sizeof(float)) +
-                             Carver::need(1, sizeof(GemmProblem)) + Carver::need(1, sizeof(QrFactor));
+            const size_t b = refresh_factor_bytes(f[first + cnt].n);
             if (used + b > ws_bytes) break;
             used += b;
             ++cnt;
         }
         if (cnt == 0) return ASTERIA_WORKSPACE_TOO_SMALL;
+        int n_max = 0;
+        for (int i = 0; i < cnt; ++i) n_max = std::max(n_max, f[first + i].n);
+        const int np_max = (n_max + QR_PANEL - 1) / QR_PANEL;
+
         Carver cv(ws);
         GemmProblem *d_g = cv.take<GemmProblem>(cnt);
         QrFactor *d_q = cv.take<QrFactor>(cnt);
         std::vector<GemmProblem> g;
         std::vector<QrFactor> q;
+        std::vector<float *> cbuf(cnt);
         int tiles = 0, ttiles = 0;
         for (int i = 0; i < cnt; ++i) {
             const asteria_factor &a = f[first + i];
             const int n = a.n, ldz = ld4(n);
             QrFactor F;
             F.Zt = cv.take<float>((size_t)n * ldz);
-            F.Qt = cv.take<float>((size_t)n * ldz);
-            F.vtv = cv.take<float>(n);
-            F.rsign = cv.take<float>(n);
-            F.Qout = a.X; F.n = n; F.ldz = ldz; F.ldq = a.ldx;
+            cbuf[i] = cv.take<float>((size_t)QR_PANEL * ldz);
+            F.gram = cv.take<double>((size_t)QR_PANEL * QR_PANEL);
+            F.winv = cv.take<float>((size_t)QR_PANEL * QR_PANEL);
+            F.Qout = a.X; F.n = n; F.ldz = ldz; F.ldq = a.ldx; F.bad = 0;
             F.tile_start = ttiles;
             const int tpr = (n + 31) / 32;
             ttiles += tpr * tpr;
@@ -348,11 +365,82 @@ extern "C" asteria_status asteria_soap_refresh(const asteria_factor *f, int nfac
             p.tile_start = tiles; tiles += tn * tn;
             g.push_back(p);
         }
+        // per-panel projection tables: panel j of every factor that has one
+        std::vector<std::vector<GemmProblem>> t1(np_max), t2(np_max), t3(np_max), t4(np_max);
+        std::vector<int> tiles4(np_max, 0);
+        std::vector<std::vector<int>> fidx(np_max);
+        std::vector<int> tiles1(np_max, 0), tiles2(np_max, 0);
+        for (int j = 0; j < np_max; ++j) {
+            for (int i = 0; i < cnt; ++i) {
+                const QrFactor &F = q[i];
+                if (F.n <= j * QR_PANEL) continue;
+                fidx[j].push_back(i);
+                const int rows = std::min(QR_PANEL, F.n - j * QR_PANEL), done = j * QR_PANEL;
+                float *Pt = F.Zt + (size_t)done * F.ldz;
+                GemmProblem p;
+                memset(&p, 0, sizeof(p));
+                p.state_idx = -1; p.state_mask = ~0;
+                // Gram matrix of the panel rows (fp64 accumulation), one symmetric tile
+                p.alpha = 1.0f; p.beta = 0.0f; p.flags = GEMM_SYM;
+                p.M = rows; p.N = rows; p.K = F.n;
+                p.A = Pt; p.lda = F.ldz; p.B = Pt; p.ldb = F.ldz; p.C = F.gram; p.ldc = QR_PANEL;
+                p.tile_start = (int)t3[j].size();
+                t3[j].push_back(p);
+                // P <- W P, in place: the single tile row reads a column range of P completely before it
+                // stores the same range
+                p.flags = 0;
+                p.M = rows; p.N = F.n; p.K = rows; p.tiles_n = (F.n + BN - 1) / BN;
+                p.A = F.winv; p.lda = QR_PANEL; p.B = Pt; p.ldb = F.ldz; p.C = Pt; p.ldc = F.ldz;
+                p.tile_start = tiles4[j]; tiles4[j] += p.tiles_n;
+                t4[j].push_back(p);
+                if (j == 0) continue;
+                // C = P Q_done^T : rows of the panel against the finished rows, contraction over n
+                p.alpha = 1.0f; p.beta = 0.0f;
+                p.M = rows; p.N = done; p.K = F.n; p.tiles_n = (done + BN - 1) / BN;
+                p.A = Pt; p.lda = F.ldz; p.B = F.Zt; p.ldb = F.ldz; p.C = cbuf[i]; p.ldc = F.ldz;
+                p.tile_start = tiles1[j]; tiles1[j] += p.tiles_n;
+                t1[j].push_back(p);
+                // P <- P - C Q_done : contraction over the finished rows (Q_done read k-major)
+                p.alpha = -1.0f; p.beta = 1.0f;
+                p.M = rows; p.N = F.n; p.K = done; p.tiles_n = (F.n + BN - 1) / BN;
+                p.A = cbuf[i]; p.lda = F.ldz; p.B = F.Zt; p.ldb = F.ldz; p.C = Pt; p.ldc = F.ldz;
+                p.tile_start = tiles2[j]; tiles2[j] += p.tiles_n;
+                t2[j].push_back(p);
+            }
+        }
+        std::vector<GemmProblem *> d_t1(np_max, nullptr), d_t2(np_max, nullptr), d_t3(np_max, nullptr), d_t4(np_max, nullptr);
+        std::vector<int *> d_fidx(np_max, nullptr);
         ASTERIA_HIP_TRY(upload_async(d_g, g.data(), g.size() * sizeof(GemmProblem), stream));
         ASTERIA_HIP_TRY(upload_async(d_q, q.data(), q.size() * sizeof(QrFactor), stream));
+        for (int j = 0; j < np_max; ++j) {
+            d_fidx[j] = cv.take<int>(fidx[j].size());
+            ASTERIA_HIP_TRY(upload_async(d_fidx[j], fidx[j].data(), fidx[j].size() * sizeof(int), stream));
+            d_t3[j] = cv.take<GemmProblem>(t3[j].size());
+            d_t4[j] = cv.take<GemmProblem>(t4[j].size());
+            ASTERIA_HIP_TRY(upload_async(d_t3[j], t3[j].data(), t3[j].size() * sizeof(GemmProblem), stream));
+            ASTERIA_HIP_TRY(upload_async(d_t4[j], t4[j].data(), t4[j].size() * sizeof(GemmProblem), stream));
+            if (j == 0) continue;
+            d_t1[j] = cv.take<GemmProblem>(t1[j].size());
+            d_t2[j] = cv.take<GemmProblem>(t2[j].size());
+            ASTERIA_HIP_TRY(upload_async(d_t1[j], t1[j].data(), t1[j].size() * sizeof(GemmProblem), stream));
+            ASTERIA_HIP_TRY(upload_async(d_t2[j], t2[j].data(), t2[j].size() * sizeof(GemmProblem), stream));
+        }
         ASTERIA_HIP_TRY((launch_gemm_grouped<float, float, float, true, false>(d_g, cnt, tiles, nullptr, stream)));
-        hipLaunchKernelGGL(householder_rows_kernel, dim3(cnt), dim3(QR_THREADS), 0, stream, d_q, info, first);
-        hipLaunchKernelGGL(transpose_sign_kernel, dim3(ttiles), dim3(256), 0, stream, d_q, cnt);
+        for (int j = 0; j < np_max; ++j) {
+            if (j > 0) {
+                for (int rep = 0; rep < 2; ++rep) {
+                    ASTERIA_HIP_TRY((launch_gemm_grouped<float, float, float, false, false>(d_t1[j], (int)t1[j].size(), tiles1[j], nullptr, stream)));
+                    ASTERIA_HIP_TRY((launch_gemm_grouped<float, float, float, false, true>(d_t2[j], (int)t2[j].size(), tiles2[j], nullptr, stream)));
+                }
+            }
+            for (int rep = 0; rep < 2; ++rep) {
+                ASTERIA_HIP_TRY((launch_gemm_grouped<double, float, float, false, false>(d_t3[j], (int)t3[j].size(), (int)t3[j].size(), nullptr, stream)));
+                hipLaunchKernelGGL(panel_chol_inverse_kernel, dim3((unsigned)fidx[j].size()), dim3(QR_THREADS), chol_lds, stream, d_q, d_fidx[j], j);
+                ASTERIA_HIP_TRY((launch_gemm_grouped<float, float, float, false, true>(d_t4[j], (int)t4[j].size(), tiles4[j], nullptr, stream)));
+            }
+        }
+        hipLaunchKernelGGL(qr_info_kernel, dim3((cnt + 127) / 128), dim3(128), 0, stream, d_q, cnt, info, first);
+        hipLaunchKernelGGL(transpose_out_kernel, dim3(ttiles), dim3(256), 0, stream, d_q, cnt);
         ASTERIA_HIP_TRY(hipGetLastError());
         first += cnt;
     }
