@@ -61,6 +61,7 @@ def main() -> int:
     ap.add_argument("--fp64-iters", type=int, default=-1)
     ap.add_argument("--schedule", type=int, default=1, help="1 = interval-adapted coefficients, 0 = classical Newton")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-soap", action="store_true", help="skip the SOAP section (blocks <= 2048)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
@@ -209,8 +210,85 @@ def main() -> int:
 
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(fsize, Ls, Rs, shapes, eps_rel)
+    if not args.no_soap:
+        del blocks, factors, pblocks, Gs, Ls, Rs, XLs, XRs, Ps, ws
+        torch.cuda.empty_cache()
+        out["soap"] = soap_section(args, torch, ast, W, dev)
     print(json.dumps(out), flush=True)
     return 0
+
+
+def soap_section(args, torch, ast, W, dev):
+    """SOAP variant on the same model, blocks <= 2048 (318 blocks, 636 factors): three warm
+    refreshes from Q = I, then `steps` x (soap_step + stats_update) and one eigenbasis refresh,
+    each timed with events on the stream the library launches on."""
+    beta, b1, b2, adam_eps = 0.95, 0.9, 0.95, 1e-8
+    shapes = W.block_shapes(W.llama_1b_matrices(), 2048)
+    if args.max_blocks:
+        shapes = shapes[:: max(1, len(shapes) // args.max_blocks)][: args.max_blocks]
+    bank = W.TemplateBank(dev)
+    bases = [(bank.get(m, b), bank.get(n, b + 3)) for b, (m, n) in enumerate(shapes)]
+    nsets = 2                                   # two gradient sets, used alternately
+    Gsets = [[W.soap_gradient(U, V, t, dev, b) for b, (U, V) in enumerate(bases)] for t in range(nsets)]
+    Ls = [torch.zeros(m, m, device=dev) for m, n in shapes]
+    Rs = [torch.zeros(n, n, device=dev) for m, n in shapes]
+    QLs = [torch.eye(m, device=dev) for m, n in shapes]
+    QRs = [torch.eye(n, device=dev) for m, n in shapes]
+    Ms = [torch.zeros(m, n, device=dev) for m, n in shapes]
+    Vs = [torch.zeros(m, n, device=dev) for m, n in shapes]
+    Ns = [torch.empty(m, n, device=dev) for m, n in shapes]
+    blocks = [ast.Blocks(list(zip(G, Ls, Rs))) for G in Gsets]
+    sblocks = [ast.SBlocks(list(zip(G, QLs, QRs, Ms, Vs, Ns))) for G in Gsets]
+    factors = ast.Factors(list(zip(Ls, QLs)) + list(zip(Rs, QRs)))
+    fsize = [m for m, n in shapes] + [n for m, n in shapes]
+    need = max(ast.soap_refresh_workspace_bytes(factors)[0], ast.soap_step_workspace_bytes(sblocks[0]),
+               ast.stats_update_workspace_bytes(blocks[0]))
+    ws = torch.empty(int(need), dtype=torch.uint8, device=dev)
+    info = torch.zeros(len(factors), dtype=torch.int32, device=dev)
+    torch.cuda.synchronize()
+    log(f"[bench] soap: {len(shapes)} blocks, {len(factors)} factors, workspace {need / 2**30:.1f} GiB, "
+        f"{torch.cuda.memory_allocated() / 2**30:.1f} GiB resident")
+    for w in range(3):                          # warm the bases from the identity
+        ast.stats_update(blocks[w % nsets], beta, ws=ws)
+        ast.soap_refresh(factors, info=info, ws=ws)
+    torch.cuda.synchronize()
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    for t in range(args.steps):
+        ev[t][0].record()
+        ast.soap_step(sblocks[t % nsets], b1, b2, adam_eps, t + 1, ws=ws)
+        ev[t][1].record()
+        ast.stats_update(blocks[t % nsets], beta, ws=ws)
+        ev[t][2].record()
+    r0, r1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    r0.record()
+    ast.soap_refresh(factors, info=info, ws=ws)
+    r1.record()
+    torch.cuda.synchronize()
+    step_ms = sum(e[0].elapsed_time(e[1]) for e in ev) / args.steps
+    stats_ms = sum(e[1].elapsed_time(e[2]) for e in ev) / args.steps
+    refresh_ms = r0.elapsed_time(r1)
+    # sanity of the refreshed bases (fp64 check of two factors, largest first)
+    orth = 0.0
+    for Q in (QLs[0], QRs[-1]):
+        q = Q.double()
+        orth = max(orth, float(torch.linalg.norm(q.T @ q - torch.eye(q.shape[0], device=dev, dtype=torch.float64)) /
+                               q.shape[0] ** 0.5))
+    step_flops = sum(2.0 * (2.0 * m * m * n + 2.0 * m * n * n) for m, n in shapes)
+    refresh_flops = sum((2.0 + 8.0 / 3.0) * float(n) ** 3 for n in fsize)
+    adam_bytes = sum(24.0 * m * n for m, n in shapes)
+    log(f"[bench] soap: step {step_ms:.1f} ms + stats {stats_ms:.1f} ms, refresh {refresh_ms:.1f} ms, "
+        f"orthogonality {orth:.1e}, info!=0: {int((info != 0).sum())}")
+    return {"workload": "same 1.1B model, blocks <=2048: 318 blocks, 636 factors; shared singular bases, "
+                        "+-30% sigma jitter, 10% dense noise; beta1=0.9, beta2=0.95",
+            "blocks": len(shapes), "factors": len(factors),
+            "soap_step_ms": round(step_ms, 3), "stats_update_ms": round(stats_ms, 3),
+            "refresh_ms": round(refresh_ms, 3),
+            "amortised_step_pf10": round(step_ms + stats_ms + refresh_ms / 10, 3),
+            "soap_step_tflops": round(step_flops / step_ms / 1e9, 1),
+            "soap_step_frac_fp32_mfma": round(step_flops / step_ms / 1e9 / PEAK_F32_MFMA, 4),
+            "refresh_dense_tflops": round(refresh_flops / refresh_ms / 1e9, 1),
+            "adam_bytes_gb": round(adam_bytes / 1e9, 2),
+            "orthogonality_max": orth, "not_ok": int((info != 0).sum())}
 
 
 def cpu_baseline(fsize, Ls, Rs, shapes, eps_rel):
