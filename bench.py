@@ -28,6 +28,18 @@ PEAK_F64_MFMA = 78.6    # TFLOP/s, MI355X dense fp64 matrix
 PEAK_HBM = 8000.0       # GB/s
 
 
+def stored_traffic(key: str):
+    """HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (each scaled by a
+    plain copy of known size); the runs and their summary live under profiles/."""
+    import re
+    path = os.path.join(ROOT, "profiles", "gemm_grouped__llama1b_b1024_hbm_traffic.md")
+    try:
+        m = re.search(rf"{key}\s*=\s*([0-9.eE+-]+)", open(path).read())
+        return float(m.group(1)) if m else None
+    except OSError:
+        return None
+
+
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
@@ -62,6 +74,10 @@ def main() -> int:
     ap.add_argument("--schedule", type=int, default=1, help="1 = interval-adapted coefficients, 0 = classical Newton")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-soap", action="store_true", help="skip the SOAP section (blocks <= 2048)")
+    ap.add_argument("--gaussian-inputs", action="store_true",
+                    help="plain N(0, 0.01^2) gradients instead of power-law spectra (counter runs: no QR in the generator)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy (reference for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
@@ -83,7 +99,10 @@ def main() -> int:
     log(f"[bench] {len(shapes)} blocks, factors {by_factor}, {params} parameters")
 
     t0 = time.time()
-    Gs = W.powerlaw_blocks(shapes, dev)
+    if args.gaussian_inputs:
+        Gs = [W.gaussian_block(m, n, 0.01, dev, 3, b, dtype=torch.bfloat16) for b, (m, n) in enumerate(shapes)]
+    else:
+        Gs = W.powerlaw_blocks(shapes, dev)
     Ls = [torch.zeros(m, m, device=dev) for m, n in shapes]
     Rs = [torch.zeros(n, n, device=dev) for m, n in shapes]
     XLs = [torch.empty(m, m, device=dev) for m, n in shapes]
@@ -117,6 +136,13 @@ def main() -> int:
         if ev: ev[2].record()
         ast.precondition(pblocks, ws=ws)
         if ev: ev[3].record()
+
+    if args.calibrate_copy:
+        src = torch.empty(2**28, dtype=torch.float32, device=dev).fill_(1.0)    # 1 GiB
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     for w in range(args.warmup):
         t = time.time()
@@ -192,12 +218,13 @@ def main() -> int:
         "wall_ms_timed_region": round(wall_ms, 1),
         "roofline": {"kernel": "gemm_grouped_kernel<float> (symmetric fp32-MFMA products of the root iteration)",
                      "bound": "mfma", "achieved": round(tf32, 2), "peak": PEAK_F32_MFMA, "unit": "TFLOP/s",
-                     "frac": round(tf32 / PEAK_F32_MFMA, 4), "traffic": None,
+                     "frac": round(tf32 / PEAK_F32_MFMA, 4), "traffic": stored_traffic("traffic_bytes_per_launch_fp32"),
                      "launches": len(k32), "avg_launch_ms": round(1e3 * t32 / max(len(k32), 1), 4),
                      "flops_per_launch": round(flops32 / max(len(k32), 1), 1)},
         "roofline_fp64": {"kernel": "gemm_grouped_kernel<double> (fp64-MFMA prefix iterations)", "bound": "mfma",
                           "achieved": round(tf64, 2), "peak": PEAK_F64_MFMA, "unit": "TFLOP/s",
-                          "frac": round(tf64 / PEAK_F64_MFMA, 4), "launches": len(k64),
+                          "frac": round(tf64 / PEAK_F64_MFMA, 4), "traffic": stored_traffic("traffic_bytes_per_launch_fp64"),
+                          "launches": len(k64),
                           "avg_launch_ms": round(1e3 * t64 / max(len(k64), 1), 4)},
         "roofline_stats": {"bound": "hbm", "achieved": round(stats_bytes / stats_ms / 1e6, 1), "peak": PEAK_HBM,
                            "unit": "GB/s", "frac": round(stats_bytes / stats_ms / 1e6 / PEAK_HBM, 4),
