@@ -25,6 +25,7 @@ sys.path.insert(0, ROOT)
 
 PEAK_F32_MFMA = 157.3   # TFLOP/s, MI355X dense fp32 matrix
 PEAK_F64_MFMA = 78.6    # TFLOP/s, MI355X dense fp64 matrix
+PEAK_BF16_MFMA = 2500.0 # TFLOP/s, MI355X dense bf16 matrix
 PEAK_HBM = 8000.0       # GB/s
 
 
@@ -49,18 +50,20 @@ def sym_gemm_flops(n: int) -> float:
     return float(n) * (n + 1) * n
 
 
-def newton_gemm_counts(iters: int, j64: int):
-    """(fp32 GEMMs, fp64 GEMMs) a factor executed: iteration k < iters does X <- X T (except
-    k = 0, where X_1 is written by the start kernel), and for k < iters - 1 also T^2, T^4 and
-    T^4 M; iterations k < j64 run in fp64."""
-    g32 = g64 = 0
+def newton_gemm_counts(iters: int, j64: int, jlow: int):
+    """(fp32 GEMMs, fp64 GEMMs, split-bf16 GEMMs) a factor executed: iteration k < iters does
+    X <- X T (except k = 0, where X_1 is written by the start kernel), and for k < iters - 1 also
+    T^2, T^4 and T^4 M; iterations k < j64 run on the fp64 cores, k >= jlow on the bf16 cores."""
+    g32 = g64 = g16 = 0
     for k in range(iters):
         c = (1 if k > 0 else 0) + (3 if k < iters - 1 else 0)
         if k < j64:
             g64 += c
+        elif k >= jlow and k > 0:
+            g16 += c
         else:
             g32 += c
-    return g32, g64
+    return g32, g64, g16
 
 
 def main() -> int:
@@ -71,6 +74,7 @@ def main() -> int:
     ap.add_argument("--ws-gib", type=float, default=64.0, help="workspace handed to the library")
     ap.add_argument("--max-blocks", type=int, default=0, help="debug: truncate the batch")
     ap.add_argument("--fp64-iters", type=int, default=-1)
+    ap.add_argument("--lowp-from", type=int, default=-1, help="first iteration on the bf16 cores (-1 = library rule)")
     ap.add_argument("--schedule", type=int, default=1, help="1 = interval-adapted coefficients, 0 = classical Newton")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-soap", action="store_true", help="skip the SOAP section (blocks <= 2048)")
@@ -117,7 +121,7 @@ def main() -> int:
     pblocks = ast.PBlocks(list(zip(XLs, Gs, XRs, Ps)))
     nf = len(factors)
     fsize = [m for m, n in shapes] + [n for m, n in shapes]
-    opts = ast.RootOpts(fp64_iters=args.fp64_iters, schedule=args.schedule)
+    opts = ast.RootOpts(fp64_iters=args.fp64_iters, schedule=args.schedule, lowp_from=args.lowp_from)
     full, mn = ast.inverse_root_workspace_bytes(factors, opts)
     ws_bytes = int(max(min(full, args.ws_gib * 2**30), mn, ast.precondition_workspace_bytes(pblocks),
                        ast.stats_update_workspace_bytes(blocks)))
@@ -150,13 +154,12 @@ def main() -> int:
         torch.cuda.synchronize()
         log(f"[bench] warmup {w}: {1e3 * (time.time() - t):.0f} ms")
 
-    # fp64 prefix length: the library's automatic rule gives 2 for eps_rel = 1e-6 with the adapted
-    # schedule (4 with classical Newton coefficients); used here for flop accounting only
-    j64 = args.fp64_iters if args.fp64_iters >= 0 else (2 if args.schedule == 1 else 4)
+    # precision schedule the library uses for these options (for flop accounting)
+    j64, jlow = ast.inverse_root_plan(eps_rel, relative=True, root=4, opts=opts)
 
     evs = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
     ast.profile_enable(200000)
-    flops32 = flops64 = 0.0
+    flops32 = flops64 = flops16 = 0.0
     torch.cuda.synchronize()
     t_wall = time.time()
     for s in range(args.steps):
@@ -164,9 +167,10 @@ def main() -> int:
         torch.cuda.synchronize()          # step boundary (also lets the iteration counts be read)
         it = iters.cpu().numpy()
         for n, c in zip(fsize, it):
-            g32, g64 = newton_gemm_counts(int(c), j64)
+            g32, g64, g16 = newton_gemm_counts(int(c), j64, jlow)
             flops32 += g32 * sym_gemm_flops(n)
             flops64 += g64 * sym_gemm_flops(n)
+            flops16 += g16 * sym_gemm_flops(n)
         log(f"[bench] step {s}: {evs[s][0].elapsed_time(evs[s][3]):.0f} ms")
     wall_ms = 1e3 * (time.time() - t_wall)
     prof = ast.profile_collect(200000)
@@ -180,6 +184,9 @@ def main() -> int:
 
     k32 = [ms for ms, kind in prof if kind == 0]
     k64 = [ms for ms, kind in prof if kind == 1]
+    k16 = [ms for ms, kind in prof if kind == 224]       # bf16 cores, both operands fp32 split in two terms
+    t16 = sum(k16) * 1e-3
+    tf16 = flops16 / t16 / 1e12 if t16 > 0 else 0.0
     t32, t64 = sum(k32) * 1e-3, sum(k64) * 1e-3
     tf32 = flops32 / t32 / 1e12 if t32 > 0 else 0.0
     tf64 = flops64 / t64 / 1e12 if t64 > 0 else 0.0
@@ -189,7 +196,8 @@ def main() -> int:
     precond_bytes = sum(4 * m * m + 4 * n * n + 2 * m * n + 4 * m * n for m, n in shapes)
     log(f"[bench] stats {stats_ms:.2f} ms  refresh {refresh_ms:.1f} ms  precondition {precond_ms:.2f} ms")
     log(f"[bench] fp32 GEMM: {len(k32)} launches, {t32 * 1e3:.1f} ms total, {tf32:.1f} TFLOP/s algorithmic; "
-        f"fp64 GEMM: {len(k64)} launches, {t64 * 1e3:.1f} ms total, {tf64:.1f} TFLOP/s")
+        f"fp64 GEMM: {len(k64)} launches, {t64 * 1e3:.1f} ms total, {tf64:.1f} TFLOP/s; "
+        f"split-bf16 GEMM: {len(k16)} launches, {t16 * 1e3:.1f} ms total, {tf16:.1f} fp32-equivalent TFLOP/s")
     log(f"[bench] Newton iterations min/mean/max {it.min()}/{it.mean():.1f}/{it.max()}, info!=0: {(info_h != 0).sum()}")
 
     out = {
@@ -207,7 +215,7 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": "1.1B LLaMA-style model, all 2-D grads blocked at <=1024 (1184 blocks, 2368 factors), "
                                "bf16 power-law gradients, fp32 statistics, eps=1e-6*lambda_max, beta=0.95",
-                   "blocks": len(shapes), "factors": nf, "fp64_prefix_iters": j64,
+                   "blocks": len(shapes), "factors": nf, "fp64_prefix_iters": j64, "bf16_split_from_iter": jlow,
                    "schedule": "interval-adapted" if args.schedule == 1 else "classical Newton",
                    "workspace_gib": round(ws_bytes / 2**30, 1)},
         "breakdown_ms": {"stats_update": round(stats_ms, 3), "inverse_root": round(refresh_ms, 3),
@@ -226,6 +234,13 @@ def main() -> int:
                           "frac": round(tf64 / PEAK_F64_MFMA, 4), "traffic": stored_traffic("traffic_bytes_per_launch_fp64"),
                           "launches": len(k64),
                           "avg_launch_ms": round(1e3 * t64 / max(len(k64), 1), 4)},
+        "roofline_split_bf16": {"kernel": "gemm_bf16_grouped_kernel<float, float, 2, 2> (late root iterations: fp32 operands "
+                                          "split in two bf16 terms, 3 bf16 MFMA passes per product)", "bound": "mfma",
+                                "achieved": round(3 * tf16, 2), "peak": PEAK_BF16_MFMA, "unit": "TFLOP/s (bf16 MFMA issued)",
+                                "frac": round(3 * tf16 / PEAK_BF16_MFMA, 4), "fp32_equivalent_tflops": round(tf16, 2),
+                                "launches": len(k16), "avg_launch_ms": round(1e3 * t16 / max(len(k16), 1), 4)},
+        "gemm_time_share_ms_per_step": {"fp32": round(1e3 * t32 / args.steps, 1), "fp64": round(1e3 * t64 / args.steps, 1),
+                                        "split_bf16": round(1e3 * t16 / args.steps, 1)},
         "roofline_stats": {"bound": "hbm", "achieved": round(stats_bytes / stats_ms / 1e6, 1), "peak": PEAK_HBM,
                            "unit": "GB/s", "frac": round(stats_bytes / stats_ms / 1e6 / PEAK_HBM, 4),
                            "tflops": round(stats_flops / stats_ms / 1e9, 1)},

@@ -126,7 +126,10 @@ typedef struct asteria_root_opts {
     float power_tol;       /* power iteration stops at ||A v - rho v|| <= power_tol * rho (default 1e-3) */
     float lambda_margin;   /* spectrum is scaled by 1 / ((1 + lambda_margin) lambda_max + eps)
                               (default 0.01) so an underestimated lambda_max stays inside (0, 1]      */
-    int32_t reserved;
+    int32_t lowp_from;     /* first iteration that may run on the bf16 matrix cores with the fp32 operands
+                              split into two bf16 terms (16 bits kept): -1 = choose from eps (default: once
+                              the bottom of M's spectrum is above 0.01 and n <= 2048; never for absolute eps),
+                              >= max_iters = never                                                      */
 } asteria_root_opts;
 
 void asteria_root_opts_default(asteria_root_opts *opts);
@@ -152,7 +155,8 @@ asteria_status asteria_stats_update(const asteria_block *blocks, int nblocks, fl
  * are chosen per factor and iteration for the interval that holds M's spectrum (or fixed at the
  * Newton values, see `schedule`); a factor stops by itself once its residual ||M - I||_F has
  * fallen below stop_resid (one more X update follows).  The leading fp64_iters iterations use
- * the fp64 matrix cores, the rest the fp32 matrix cores.
+ * the fp64 matrix cores, the middle ones the fp32 matrix cores, and the last ones (from
+ * `lowp_from` on) the bf16 matrix cores with split operands.
  *   eps        host array, eps_count entries (1 = shared by all factors, else nfactors).
  *   info       device int32[nfactors] or NULL   (ASTERIA_INFO_*)
  *   iters      device int32[nfactors] or NULL   (number of X <- X T updates performed)
@@ -162,6 +166,12 @@ asteria_status asteria_stats_update(const asteria_block *blocks, int nblocks, fl
  * needed for the largest single factor.
  * Errors: NULL A or X, n <= 0, ld < n, unsupported root, eps < 0 or non-finite, eps_count not
  * in {1, nfactors} -> INVALID_ARG / UNSUPPORTED; ws too small -> WORKSPACE_TOO_SMALL.        */
+/* The precision schedule asteria_inverse_root would use for these arguments (host only, nothing is
+ * launched): number of leading fp64 iterations and first iteration on the bf16 matrix cores
+ * (>= max_iters = never; factors larger than 2048 stay on the fp32 cores under the automatic rule). */
+asteria_status asteria_inverse_root_plan(int root, asteria_eps_mode mode, const float *eps, int eps_count,
+                                         const asteria_root_opts *opts, int32_t *fp64_iters,
+                                         int32_t *lowp_from);
 size_t asteria_inverse_root_workspace_bytes(const asteria_factor *f, int nfactors,
                                             const asteria_root_opts *opts, size_t *min_bytes);
 asteria_status asteria_inverse_root(const asteria_factor *f, int nfactors, int root,

@@ -9,6 +9,7 @@ from .binding import (  # noqa: F401
     library_path,
     stats_update,
     inverse_root,
+    inverse_root_plan,
     precondition,
     soap_refresh,
     soap_step,

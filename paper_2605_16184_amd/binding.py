@@ -51,7 +51,7 @@ class RootOpts(Structure):
     """Mirror of asteria_root_opts; constructed with the library defaults."""
     _fields_ = [("max_iters", c_int32), ("fp64_iters", c_int32), ("power_iters", c_int32),
                 ("schedule", c_int32), ("stop_resid", c_float), ("power_tol", c_float),
-                ("lambda_margin", c_float), ("reserved", c_int32)]
+                ("lambda_margin", c_float), ("lowp_from", c_int32)]
 
     def __init__(self, **kw):
         super().__init__()
@@ -88,6 +88,9 @@ def lib():
         L.asteria_inverse_root_workspace_bytes.restype = c_size_t
         L.asteria_inverse_root_workspace_bytes.argtypes = [POINTER(_Factor), c_int, POINTER(RootOpts),
                                                            POINTER(c_size_t)]
+        L.asteria_inverse_root_plan.restype = c_int
+        L.asteria_inverse_root_plan.argtypes = [c_int, c_int, POINTER(c_float), c_int, POINTER(RootOpts),
+                                                POINTER(c_int32), POINTER(c_int32)]
         L.asteria_inverse_root.restype = c_int
         L.asteria_inverse_root.argtypes = [POINTER(_Factor), c_int, c_int, c_int, POINTER(c_float), c_int,
                                            POINTER(RootOpts), c_void_p, c_void_p, c_void_p, c_void_p,
@@ -270,6 +273,17 @@ def inverse_root_workspace_bytes(factors, opts: Optional[RootOpts] = None):
     full = lib().asteria_inverse_root_workspace_bytes(f.array, f.count, ctypes.byref(opts) if opts else None,
                                                       ctypes.byref(mn))
     return full, mn.value
+
+
+def inverse_root_plan(eps, relative: bool = True, root: int = 4, opts: Optional[RootOpts] = None):
+    """(fp64 prefix length, first iteration on the bf16 matrix cores) the library would choose."""
+    eps_list = [float(eps)] if not isinstance(eps, (Sequence, torch.Tensor)) else [float(e) for e in eps]
+    eps_arr = (c_float * len(eps_list))(*eps_list)
+    j64, jl = c_int32(0), c_int32(0)
+    _check(lib().asteria_inverse_root_plan(int(root), EPS_RELATIVE if relative else EPS_ABSOLUTE, eps_arr,
+                                           len(eps_list), ctypes.byref(opts) if opts else None,
+                                           ctypes.byref(j64), ctypes.byref(jl)), "asteria_inverse_root_plan")
+    return j64.value, jl.value
 
 
 def inverse_root(factors, eps, relative: bool = True, root: int = 4, opts: Optional[RootOpts] = None,

@@ -28,7 +28,7 @@ extern "C" void asteria_root_opts_default(asteria_root_opts *o)
     o->stop_resid = 1e-2f;
     o->power_tol = 1e-3f;
     o->lambda_margin = 0.01f;
-    o->reserved = 0;
+    o->lowp_from = -1;
 }
 
 // ---- measurement aid: HIP events around every grouped-GEMM launch ----------------------------

@@ -2,8 +2,8 @@
 //
 // Same problem table, tile order and epilogue as gemm.h; operands are always k-contiguous.
 // An operand is either bf16 in memory (used as is - bf16 x bf16 products are exact in fp32) or
-// fp32 in memory and split on the fly into NT bf16 terms (x = hi + lo, hi = bf16(x),
-// lo = bf16(x - hi)): with two terms per operand the kernel issues hi*hi, hi*lo and lo*hi, which
+// fp32 in memory and split on the fly into NT bf16 terms (x ~ hi + lo, hi = upper half of x,
+// lo = upper half of x - hi): with two terms per operand the kernel issues hi*hi, hi*lo and lo*hi, which
 // keeps about 16 bits of the fp32 operands at three bf16 MFMA passes.
 //
 // Workgroup = 256 threads = 2 x 2 wavefronts of 64 x 64 (2 x 2 MFMA tiles each), K slabs of 64
@@ -31,20 +31,25 @@ struct MmaBf16 {
     __device__ static __forceinline__ int acc_row(int v, int h) { return 8 * (v >> 2) + 4 * h + (v & 3); }
 };
 
-// hi / lo bf16 split of four fp32 values; returns packed pairs (two bf16 per 32-bit word)
+// hi / lo bf16 split of four fp32 values, by truncation: hi = the upper 16 bits of x, lo = the
+// upper 16 bits of x - hi (that difference is exact in fp32).  hi + lo keeps 16 significant bits
+// (relative error <= 2^-16) at three VALU operations per element: the split runs once per tile
+// and slab, so its cost competes with the MFMA work it feeds.  Returns packed pairs.
 __device__ __forceinline__ void split4(u32x4 x, u32x2 &hi, u32x2 &lo, bool want_lo)
 {
-    uint16_t hb[4], lb[4];
+    // v_perm_b32 picks bytes 2..3 of both sources: (b & 0xffff0000) | (a >> 16)
+    hi[0] = __builtin_amdgcn_perm(x[1], x[0], 0x07060302u);
+    hi[1] = __builtin_amdgcn_perm(x[3], x[2], 0x07060302u);
+    if (want_lo) {
+        uint32_t d[4];
 #pragma unroll
-    for (int e = 0; e < 4; ++e) {
-        const float f = __uint_as_float(x[e]);
-        hb[e] = f32_to_bf16(f);
-        lb[e] = want_lo ? f32_to_bf16(f - bf16_to_f32(hb[e])) : (uint16_t)0;
+        for (int e = 0; e < 4; ++e)
+            d[e] = __float_as_uint(__uint_as_float(x[e]) - __uint_as_float(x[e] & 0xffff0000u));
+        lo[0] = __builtin_amdgcn_perm(d[1], d[0], 0x07060302u);
+        lo[1] = __builtin_amdgcn_perm(d[3], d[2], 0x07060302u);
+    } else {
+        lo[0] = 0u; lo[1] = 0u;
     }
-    hi.x = (uint32_t)hb[0] | ((uint32_t)hb[1] << 16);
-    hi.y = (uint32_t)hb[2] | ((uint32_t)hb[3] << 16);
-    lo.x = (uint32_t)lb[0] | ((uint32_t)lb[1] << 16);
-    lo.y = (uint32_t)lb[2] | ((uint32_t)lb[3] << 16);
 }
 
 // One operand tile (128 rows x BK) of input type TI staged as bf16 terms in LDS.

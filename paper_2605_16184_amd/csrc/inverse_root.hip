@@ -24,6 +24,7 @@
 
 #include "common.h"
 #include "gemm.h"
+#include "gemm_bf16.h"
 #include "root_schedule.h"
 
 using namespace asteria;
@@ -476,8 +477,9 @@ struct Plan {
     int fp64_iters;
     int power_iters;
     int root;
+    int lowp_from;     // first iteration that may run on the bf16 matrix cores (split operands)
     float stop_resid, power_tol, margin;
-    bool use64, use32, adapted;
+    bool use64, use32, adapted, lowp_auto;
 };
 
 // Host mirror of the device-side schedule for a spectrum of M_0 in [lo0, 1]:
@@ -486,14 +488,15 @@ struct Plan {
 //   *lead64 number of leading iterations that start while the bottom of the spectrum is still
 //           below `thr` (those run in fp64 under the automatic precision rule).
 void simulate_schedule(double lo0, int n, int root, bool adapted, double stop, double thr, int cap,
-                       int *iters, int *lead64)
+                       int *iters, int *lead64, double thr_lowp = 0.0, int *lead_full = nullptr)
 {
     double lo = lo0, hi = 1.0;
-    int k = 0, lead = 0;
+    int k = 0, lead = 0, leadf = 0;
     while (k < cap) {
         const double dev = std::max(fabs(1.0 - lo), fabs(1.0 - hi));
         if (sqrt((double)n) * dev < stop) break;
         if (lo < thr) lead = k + 1;
+        if (lo < thr_lowp) leadf = k + 1;
         double a, g;
         root_coefficients(lo, hi, root, adapted, ROOT_THETA, a, g);
         const RootInterval im = root_image(lo, hi, root, a, g);
@@ -502,6 +505,7 @@ void simulate_schedule(double lo0, int n, int root, bool adapted, double stop, d
     }
     *iters = k + 1;
     *lead64 = lead;
+    if (lead_full) *lead_full = leadf;
 }
 
 size_t factor_matrix_bytes(int n, bool use64, bool use32)
@@ -554,6 +558,24 @@ asteria_status make_plan(const asteria_root_opts *opts_in, asteria_eps_mode mode
             j = pl.adapted ? 2 : 4;   // the host cannot see eps / lambda_max here
         }
     }
+    // Late iterations: once the bottom of M's spectrum is above 0.01, products that keep 16 bits
+    // (fp32 operands split into two bf16 terms, three bf16 MFMA passes) add a few 1e-5 to the
+    // root's error (measured), and run nearly twice as fast as the fp32 matrix cores.
+    int jl = o.lowp_from;
+    if (jl < 0) {
+        jl = o.max_iters;
+        if (mode == ASTERIA_EPS_RELATIVE && eps) {
+            float emin = eps[0];
+            for (int i = 1; i < eps_count; ++i) emin = std::min(emin, eps[i]);
+            if (emin > 0.0f) {
+                const double lo0 = 0.5 * (double)emin / (1.0 + (double)pl.margin + (double)emin);
+                int it = 0, l64 = 0;
+                simulate_schedule(lo0, 1, root, pl.adapted, 1e-3, 0.0, o.max_iters, &it, &l64, 0.01, &jl);
+            }
+        }
+    }
+    pl.lowp_from = jl;
+    pl.lowp_auto = o.lowp_from < 0;
     pl.fp64_iters = std::min(j, pl.max_iters);
     pl.use64 = pl.fp64_iters > 0;
     pl.use32 = pl.fp64_iters < pl.max_iters;
@@ -648,6 +670,9 @@ asteria_status run_pass(const asteria_factor *f, const std::vector<int> &order, 
         K = std::min(K, it + 2);
     }
     const int j64 = std::min(pl.fp64_iters, K);
+    // 16-bit products put a floor of about 2e-6 n under the measured ||M - I||_F; above n = 2048 that
+    // floor approaches stop_resid, so the automatic rule keeps such factors on the fp32 cores
+    const int jlow = (pl.lowp_auto && n_max > 2048) ? K : pl.lowp_from;
 
     // problem tables
     const float ca = (float)(root + 1) / (float)root, cg = 1.0f / (float)root;
@@ -753,7 +778,12 @@ asteria_status run_pass(const asteria_factor *f, const std::vector<int> &order, 
             hipLaunchKernelGGL(root_to_fp32_kernel, dim3(sq_total), dim3(256), 0, stream, d_fd, d_fs, d_state,
                                cnt, j64, 0, d_sq);
         const int pa = k & 1;
-        if (p32) {
+        if (p32 && k >= jlow && k > 0) {
+            ASTERIA_HIP_TRY((launch_gemm_bf16_grouped<float, float, 2, 2>(d_tab[0][pa][0], 2 * cnt, 2 * tri_total, d_state, stream)));
+            if (root == 4)
+                ASTERIA_HIP_TRY((launch_gemm_bf16_grouped<float, float, 2, 2>(d_tab[0][pa][1], cnt, tri_total, d_state, stream)));
+            ASTERIA_HIP_TRY((launch_gemm_bf16_grouped<float, float, 2, 2>(d_tab[0][pa][2], cnt, tri_total, d_state, stream)));
+        } else if (p32) {
             if (k == 0)
                 ASTERIA_HIP_TRY((launch_gemm_grouped<float, float, float, false, false>(d_first[0], cnt, tri_total, d_state, stream)));
             else
@@ -783,6 +813,20 @@ asteria_status run_pass(const asteria_factor *f, const std::vector<int> &order, 
 }
 
 }  // namespace
+
+extern "C" asteria_status asteria_inverse_root_plan(int root, asteria_eps_mode mode, const float *eps, int eps_count,
+                                                    const asteria_root_opts *opts, int32_t *fp64_iters,
+                                                    int32_t *lowp_from)
+{
+    if (root != 2 && root != 4) return ASTERIA_UNSUPPORTED;
+    if (!eps || eps_count <= 0) return ASTERIA_INVALID_ARG;
+    Plan pl;
+    const asteria_status st = make_plan(opts, mode, eps, eps_count, root, pl);
+    if (st != ASTERIA_OK) return st;
+    if (fp64_iters) *fp64_iters = pl.fp64_iters;
+    if (lowp_from) *lowp_from = pl.lowp_from;
+    return ASTERIA_OK;
+}
 
 extern "C" size_t asteria_inverse_root_workspace_bytes(const asteria_factor *f, int nfactors,
                                                        const asteria_root_opts *opts, size_t *min_bytes)
