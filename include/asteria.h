@@ -128,7 +128,7 @@ typedef struct asteria_root_opts {
                               (default 0.01) so an underestimated lambda_max stays inside (0, 1]      */
     int32_t lowp_from;     /* first iteration that may run on the bf16 matrix cores with the fp32 operands
                               split into two bf16 terms (16 bits kept): -1 = choose from eps (default: once
-                              the bottom of M's spectrum is above 0.01 and n <= 2048; never for absolute eps),
+                              the bottom of M's spectrum is above 1e-3 and n <= 2048; never for absolute eps),
                               >= max_iters = never                                                      */
 } asteria_root_opts;
 

@@ -173,7 +173,9 @@ __global__ __launch_bounds__(256) void gemm_bf16_grouped_kernel(const GemmProble
     constexpr int BK = (NTA + NTB > 2) ? 32 : 64;
     extern __shared__ __align__(16) unsigned char smem_raw[];
     ASTERIA_LDS uint16_t *smem = (ASTERIA_LDS uint16_t *)smem_raw;
-    __shared__ float red[4];
+    // the reduction scratch of the epilogue reuses the operand buffer (free after the K loop): with
+    // no static LDS two workgroups of the split variants (80 KiB each) fit one CU's 160 KiB
+    float *red = reinterpret_cast<float *>(smem_raw);
 
     const int per_xcd = (total_tiles + NUM_XCD - 1) / NUM_XCD;
     const int t_global = (int)(blockIdx.x % NUM_XCD) * per_xcd + (int)(blockIdx.x / NUM_XCD);
