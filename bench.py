@@ -50,19 +50,27 @@ def sym_gemm_flops(n: int) -> float:
     return float(n) * (n + 1) * n
 
 
-def newton_gemm_counts(iters: int, j64: int, jlow: int):
+def newton_gemm_counts(iters: int, j64: int, jlow: int, xt_lowp: bool):
     """(fp32 GEMMs, fp64 GEMMs, split-bf16 GEMMs) a factor executed: iteration k < iters does
     X <- X T (except k = 0, where X_1 is written by the start kernel), and for k < iters - 1 also
-    T^2, T^4 and T^4 M; iterations k < j64 run on the fp64 cores, k >= jlow on the bf16 cores."""
+    the M-chain T^2, T^4 and T^4 M; the chain runs on the fp64 cores for k < j64 and on the bf16
+    cores for k >= jlow; X <- X T runs on the bf16 cores when xt_lowp, else with its iteration's
+    tier (fp32 at least)."""
     g32 = g64 = g16 = 0
     for k in range(iters):
-        c = (1 if k > 0 else 0) + (3 if k < iters - 1 else 0)
+        chain = 3 if k < iters - 1 else 0
+        lowp = k >= max(jlow, j64)
         if k < j64:
-            g64 += c
-        elif k >= jlow and k > 0:
-            g16 += c
+            g64 += chain
+        elif lowp:
+            g16 += chain
         else:
-            g32 += c
+            g32 += chain
+        if k > 0:
+            if xt_lowp or lowp:
+                g16 += 1
+            else:
+                g32 += 1
     return g32, g64, g16
 
 
@@ -71,7 +79,7 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=3)
     ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--ws-gib", type=float, default=64.0, help="workspace handed to the library")
+    ap.add_argument("--ws-gib", type=float, default=96.0, help="workspace handed to the library (a single pass needs about 90 GiB)")
     ap.add_argument("--max-blocks", type=int, default=0, help="debug: truncate the batch")
     ap.add_argument("--fp64-iters", type=int, default=-1)
     ap.add_argument("--lowp-from", type=int, default=-1, help="first iteration on the bf16 cores (-1 = library rule)")
@@ -155,7 +163,7 @@ def main() -> int:
         log(f"[bench] warmup {w}: {1e3 * (time.time() - t):.0f} ms")
 
     # precision schedule the library uses for these options (for flop accounting)
-    j64, jlow = ast.inverse_root_plan(eps_rel, relative=True, root=4, opts=opts)
+    j64, jlow, xt_lowp = ast.inverse_root_plan(eps_rel, relative=True, root=4, opts=opts)
 
     evs = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
     ast.profile_enable(200000)
@@ -167,7 +175,7 @@ def main() -> int:
         torch.cuda.synchronize()          # step boundary (also lets the iteration counts be read)
         it = iters.cpu().numpy()
         for n, c in zip(fsize, it):
-            g32, g64, g16 = newton_gemm_counts(int(c), j64, jlow)
+            g32, g64, g16 = newton_gemm_counts(int(c), j64, jlow, xt_lowp)
             flops32 += g32 * sym_gemm_flops(n)
             flops64 += g64 * sym_gemm_flops(n)
             flops16 += g16 * sym_gemm_flops(n)
@@ -215,7 +223,7 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": "1.1B LLaMA-style model, all 2-D grads blocked at <=1024 (1184 blocks, 2368 factors), "
                                "bf16 power-law gradients, fp32 statistics, eps=1e-6*lambda_max, beta=0.95",
-                   "blocks": len(shapes), "factors": nf, "fp64_prefix_iters": j64, "bf16_split_from_iter": jlow,
+                   "blocks": len(shapes), "factors": nf, "fp64_prefix_iters": j64, "bf16_split_from_iter": jlow, "x_update_on_bf16_cores": xt_lowp,
                    "schedule": "interval-adapted" if args.schedule == 1 else "classical Newton",
                    "workspace_gib": round(ws_bytes / 2**30, 1)},
         "breakdown_ms": {"stats_update": round(stats_ms, 3), "inverse_root": round(refresh_ms, 3),

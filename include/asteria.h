@@ -167,11 +167,14 @@ asteria_status asteria_stats_update(const asteria_block *blocks, int nblocks, fl
  * Errors: NULL A or X, n <= 0, ld < n, unsupported root, eps < 0 or non-finite, eps_count not
  * in {1, nfactors} -> INVALID_ARG / UNSUPPORTED; ws too small -> WORKSPACE_TOO_SMALL.        */
 /* The precision schedule asteria_inverse_root would use for these arguments (host only, nothing is
- * launched): number of leading fp64 iterations and first iteration on the bf16 matrix cores
- * (>= max_iters = never; factors larger than 2048 stay on the fp32 cores under the automatic rule). */
+ * launched): number of leading fp64 iterations of the M-chain (T^2, T^4, T^4 M), first iteration of
+ * that chain on the bf16 matrix cores (>= max_iters = never; factors larger than 2048 stay on the
+ * fp32 cores under the automatic rule), and whether every X <- X T product runs on the bf16 cores
+ * with split operands (1) or in the precision tier of its iteration, fp32 at least (0).  X is
+ * stored in fp32 in every tier.  Any of the three outputs may be NULL.                          */
 asteria_status asteria_inverse_root_plan(int root, asteria_eps_mode mode, const float *eps, int eps_count,
                                          const asteria_root_opts *opts, int32_t *fp64_iters,
-                                         int32_t *lowp_from);
+                                         int32_t *lowp_from, int32_t *x_update_lowp);
 size_t asteria_inverse_root_workspace_bytes(const asteria_factor *f, int nfactors,
                                             const asteria_root_opts *opts, size_t *min_bytes);
 asteria_status asteria_inverse_root(const asteria_factor *f, int nfactors, int root,

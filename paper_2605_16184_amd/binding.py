@@ -90,7 +90,7 @@ def lib():
                                                            POINTER(c_size_t)]
         L.asteria_inverse_root_plan.restype = c_int
         L.asteria_inverse_root_plan.argtypes = [c_int, c_int, POINTER(c_float), c_int, POINTER(RootOpts),
-                                                POINTER(c_int32), POINTER(c_int32)]
+                                                POINTER(c_int32), POINTER(c_int32), POINTER(c_int32)]
         L.asteria_inverse_root.restype = c_int
         L.asteria_inverse_root.argtypes = [POINTER(_Factor), c_int, c_int, c_int, POINTER(c_float), c_int,
                                            POINTER(RootOpts), c_void_p, c_void_p, c_void_p, c_void_p,
@@ -276,14 +276,16 @@ def inverse_root_workspace_bytes(factors, opts: Optional[RootOpts] = None):
 
 
 def inverse_root_plan(eps, relative: bool = True, root: int = 4, opts: Optional[RootOpts] = None):
-    """(fp64 prefix length, first iteration on the bf16 matrix cores) the library would choose."""
+    """(fp64 prefix length of the M-chain, its first iteration on the bf16 matrix cores, whether every
+    X update runs on the bf16 cores) as the library would choose."""
     eps_list = [float(eps)] if not isinstance(eps, (Sequence, torch.Tensor)) else [float(e) for e in eps]
     eps_arr = (c_float * len(eps_list))(*eps_list)
-    j64, jl = c_int32(0), c_int32(0)
+    j64, jl, xt = c_int32(0), c_int32(0), c_int32(0)
     _check(lib().asteria_inverse_root_plan(int(root), EPS_RELATIVE if relative else EPS_ABSOLUTE, eps_arr,
                                            len(eps_list), ctypes.byref(opts) if opts else None,
-                                           ctypes.byref(j64), ctypes.byref(jl)), "asteria_inverse_root_plan")
-    return j64.value, jl.value
+                                           ctypes.byref(j64), ctypes.byref(jl), ctypes.byref(xt)),
+           "asteria_inverse_root_plan")
+    return j64.value, jl.value, bool(xt.value)
 
 
 def inverse_root(factors, eps, relative: bool = True, root: int = 4, opts: Optional[RootOpts] = None,

@@ -51,10 +51,11 @@ struct GemmProblem {
     const void *B;
     void *C;
     void *C2;
+    float *C3;          // root epilogue: optional fp32 copy of C2
     float *partial;
     const float *coef;  // root epilogue: device pointer to (a, g), or null to use ep_a / ep_g
     int M, N, K;
-    int lda, ldb, ldc, ldc2;
+    int lda, ldb, ldc, ldc2, ldc3;
     int tile_start;  // id of this problem's first tile within the launch
     int tiles_n;     // tile columns (non-symmetric problems)
     int state_idx;   // index into the launch's state[] array, or -1
@@ -62,7 +63,6 @@ struct GemmProblem {
     float alpha, beta;
     float ep_a, ep_g;
     int flags;
-    int pad_;
 };
 
 // Measurement aid (see asteria_profile_enable): bracket a launch with HIP events on its stream.
@@ -378,7 +378,7 @@ __device__ __forceinline__ void gemm_epilogue(const GemmProblem &P, typename MM:
     if constexpr (sizeof(TC) == 4)
         vec_c = rowsA == BM && rowsB == BN && !(flags & GEMM_C_BF16) && (ldc & 3) == 0 &&
                 (reinterpret_cast<uintptr_t>(C) & 15u) == 0 &&
-                (!root || ((ldc2 & 3) == 0 && (reinterpret_cast<uintptr_t>(C2) & 15u) == 0));
+                (!root || (P.C3 == nullptr && (ldc2 & 3) == 0 && (reinterpret_cast<uintptr_t>(C2) & 15u) == 0));
 #pragma unroll
     for (int i = 0; i < WTM; ++i) {
 #pragma unroll
@@ -435,6 +435,10 @@ __device__ __forceinline__ void gemm_epilogue(const GemmProblem &P, typename MM:
                     const TC t2 = ep_a * d - ep_g * val;
                     C2[(size_t)row * ldc2 + col] = t2;
                     if (sym && row != col) C2[(size_t)col * ldc2 + row] = t2;
+                    if (P.C3) {
+                        P.C3[(size_t)row * P.ldc3 + col] = (float)t2;
+                        if (sym && row != col) P.C3[(size_t)col * P.ldc3 + row] = (float)t2;
+                    }
                     const float e = (float)(val - d);
                     rsum += (sym && row != col) ? 2.0f * e * e : e * e;
                 }

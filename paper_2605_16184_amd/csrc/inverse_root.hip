@@ -35,14 +35,19 @@ constexpr int PM_ROWS = 32;   // rows of A per mat-vec workgroup (8 per wavefron
 
 enum : int { ST_RUN = 0, ST_LAST = 1, ST_DONE = 2, ST_FAIL = 3 };
 
+// spectrum of M within 1 +- ROOT_STOP_DEV: one more X update finishes the factor
+constexpr float ROOT_STOP_DEV = 1e-2f;
+// accepted truncation error of the result per eigen-direction (a third of the 2e-3 accuracy bar
+// on the relative Frobenius error, which averages over directions)
+constexpr float ROOT_X_TOL = 7e-4f;
+
 struct FactorDev {
     const float *A;
     float *Xout;
-    float *X32b;        // second fp32 X buffer (workspace)
+    float *X32b;        // second fp32 X buffer (workspace); X is kept in fp32 in every precision tier
     float *M32[2];
     float *T32;
     float *T432;
-    double *X64[2];
     double *M64[2];
     double *T64;
     double *T464;
@@ -116,19 +121,17 @@ __global__ __launch_bounds__(256) void pm_init_kernel(const FactorDev *fd, Facto
     }
 }
 
-// y = A v for PM_ROWS rows of one factor; v = v_raw * inv_norm on the fly
+// y = A v for PM_ROWS rows of one factor; v = v_raw * inv_norm on the fly.
+// Grid: x = row block, y = factor - a finished factor's workgroups leave after two loads, which
+// keeps the launches that follow a factor's convergence cheap.
 __global__ __launch_bounds__(256) void pm_matvec_kernel(const FactorDev *fd, const FactorScal *fs,
                                                         int nf, int src, int first)
 {
-    // locate the factor of this workgroup: last f with pm_block_start <= blockIdx.x
-    int lo = 0, hi = nf - 1;
-    while (lo < hi) {
-        const int mid = (lo + hi + 1) >> 1;
-        if (fd[mid].pm_block_start <= (int)blockIdx.x) lo = mid; else hi = mid - 1;
-    }
-    const FactorDev &F = fd[lo];
+    const int lo = blockIdx.y;
     if (fs[lo].pm_done) return;
-    const int blk = (int)blockIdx.x - F.pm_block_start;
+    const FactorDev &F = fd[lo];
+    const int blk = (int)blockIdx.x;
+    if (blk >= F.pm_blocks) return;
     const int n = F.n, lda = F.lda;
     const float *__restrict__ v = F.pv[src];
     float *__restrict__ y = F.pv[src ^ 1];
@@ -279,15 +282,16 @@ __global__ __launch_bounds__(256) void root_init_kernel(const FactorDev *fd, con
     const TC ca = (TC)fs[lo].ca, cg = (TC)fs[lo].cg;
     // X_0 = xs I is never stored: the first update X_1 = X_0 T_0 = xs T_0 is written directly
     // (into the buffer that holds X after an odd number of updates), which saves one product.
-    TC *M, *T, *X;
-    int ldm, ldx;
+    TC *M, *T;
+    int ldm;
     if (sizeof(TC) == 8) {
-        M = reinterpret_cast<TC *>(F.M64[0]); T = reinterpret_cast<TC *>(F.T64);
-        X = reinterpret_cast<TC *>(F.X64[1]); ldm = F.ld64; ldx = F.ld64;
+        M = reinterpret_cast<TC *>(F.M64[0]); T = reinterpret_cast<TC *>(F.T64); ldm = F.ld64;
     } else {
-        M = reinterpret_cast<TC *>(F.M32[0]); T = reinterpret_cast<TC *>(F.T32);
-        X = reinterpret_cast<TC *>(F.X32b); ldm = F.ld32; ldx = F.ld32;
+        M = reinterpret_cast<TC *>(F.M32[0]); T = reinterpret_cast<TC *>(F.T32); ldm = F.ld32;
     }
+    float *X = F.X32b;            // holds X after an odd number of updates
+    float *T32c = (sizeof(TC) == 8) ? F.T32 : nullptr;   // fp32 copy of T for the X update
+    const int ldx = F.ld32;
     // The tile pair (ti, tj) / (tj, ti) is walked in 32 x 32 sub-tiles.  P = A[sub(ti, tj)] and
     // Q = A[sub(tj, ti)] are both read along rows (coalesced) into LDS; the symmetrised value at
     // (r, c) of tile (ti, tj) is (P[r][c] + Q[c][r]) / 2 and the one at (c, r) of tile (tj, ti) is
@@ -320,7 +324,8 @@ __global__ __launch_bounds__(256) void root_init_kernel(const FactorDev *fd, con
                     const TC t = ca * d - cg * m;
                     M[(size_t)r * ldm + c] = m;
                     T[(size_t)r * ldm + c] = t;
-                    X[(size_t)r * ldx + c] = xs * t;
+                    if (T32c) T32c[(size_t)r * F.ld32 + c] = (float)t;
+                    X[(size_t)r * ldx + c] = (float)(xs * t);
                     const float e = (float)(m - d);
                     // a diagonal sub-tile holds both triangles itself; every other one stands for two
                     rsum += diag_sub ? e * e : 2.0f * e * e;
@@ -335,7 +340,8 @@ __global__ __launch_bounds__(256) void root_init_kernel(const FactorDev *fd, con
                     const TC t = -cg * m;
                     M[(size_t)r2 * ldm + c2] = m;
                     T[(size_t)r2 * ldm + c2] = t;
-                    X[(size_t)r2 * ldx + c2] = xs * t;
+                    if (T32c) T32c[(size_t)r2 * F.ld32 + c2] = (float)t;
+                    X[(size_t)r2 * ldx + c2] = (float)(xs * t);
                 }
             }
         }
@@ -351,7 +357,7 @@ __global__ __launch_bounds__(256) void root_init_kernel(const FactorDev *fd, con
 // final_pass = 1): evaluates the residual of running factors and advances the state machine.
 __global__ __launch_bounds__(64) void root_control_kernel(const FactorDev *fd, FactorScal *fs, int *state,
                                                           int k, int fp32_phase, int final_pass,
-                                                          float stop_resid, int root, int adapted)
+                                                          float stop_resid, int root, int adapted, int look_ahead)
 {
     const int f = blockIdx.x;
     const FactorDev &F = fd[f];
@@ -370,13 +376,32 @@ __global__ __launch_bounds__(64) void root_control_kernel(const FactorDev *fd, F
             if (threadIdx.x == 0) { S.info = ASTERIA_INFO_NOT_PD; S.resid = resid; }
         } else {
             if (threadIdx.x == 0) S.resid = resid;
-            if (resid < stop_resid) st = ST_LAST;
+            // Last X update now?  X_{k+1} = X_k T_k differs from the root by |mu - 1| / 4 per eigen-
+            // direction, mu in the spectrum of M_{k+1}.  Three ways to know that this is small:
+            //  - the measured residual of M_k is below stop_resid (the update squares it);
+            //  - the interval predicted for M_k has contracted to 1 +- ROOT_STOP_DEV;
+            //  - the image of that interval under this iteration's map, i.e. the interval of
+            //    M_{k+1}, lies within 1 +- 4 ROOT_X_TOL: M_{k+1} need not be formed at all.
+            // The predictions are trusted only while the measured residual is consistent with
+            // them: every |mu - 1| is at most ||M_k - I||_F, so an eigenvalue far outside shows.
+            const float dev = fmaxf(1.0f - S.lo, S.hi - 1.0f);
+            const bool consistent = resid < 1.5f * sqrtf((float)F.n) * dev + 2e-3f;
+            double lo_k = (double)S.lo, hi_k = (double)S.hi;
+            const double rb = (double)resid * 1.001 + 1e-5;
+            if (1.0 - rb > lo_k) lo_k = 1.0 - rb;
+            if (1.0 + rb < hi_k) hi_k = 1.0 + rb;
+            if (!(hi_k > lo_k)) { lo_k = 1.0 - rb; hi_k = 1.0 + rb; }
+            const RootInterval nx = root_image(lo_k, hi_k, root, (double)S.ca, (double)S.cg);
+            const double dev_next = fmax(1.0 - nx.lo, nx.hi - 1.0);
+            const bool pred_ok = consistent && dev < ROOT_STOP_DEV;
+            const bool ahead_ok = look_ahead && consistent && dev_next <= 4.0 * (double)ROOT_X_TOL;
+            if (resid < stop_resid || pred_ok || ahead_ok) st = ST_LAST;
         }
     }
     if (threadIdx.x == 0) {
         if (!final_pass && (st == ST_RUN || st == ST_LAST)) {
             S.iters += 1;
-            if (fp32_phase) S.xloc = (k + 1) & 1;
+            S.xloc = (k + 1) & 1;      // X after k + 1 updates: 1 = workspace buffer, 0 = the caller's X
         }
         if (final_pass && (st == ST_RUN || st == ST_LAST)) S.info = ASTERIA_INFO_NOT_CONVERGED;
         if (!final_pass && st == ST_RUN) {
@@ -399,10 +424,9 @@ __global__ __launch_bounds__(64) void root_control_kernel(const FactorDev *fd, F
     }
 }
 
-// fp64 -> fp32 hand-over before iteration j (run after control(j)), or at the very end when every
-// iteration ran in fp64 (at_end = 1).  One workgroup per 128 x 128 tile (full square tiling).
-__global__ __launch_bounds__(256) void root_to_fp32_kernel(const FactorDev *fd, FactorScal *fs,
-                                                           const int *state, int nf, int j, int at_end,
+// fp64 -> fp32 hand-over of M before iteration j (run after control(j)); X and T are kept in
+// fp32 all along.  One workgroup per 128 x 128 tile (full square tiling).
+__global__ __launch_bounds__(256) void root_to_fp32_kernel(const FactorDev *fd, const int *state, int nf, int j,
                                                            const int *sq_tile_start)
 {
     int lo = 0, hi = nf - 1;
@@ -411,29 +435,19 @@ __global__ __launch_bounds__(256) void root_to_fp32_kernel(const FactorDev *fd, 
         if (sq_tile_start[mid] <= (int)blockIdx.x) lo = mid; else hi = mid - 1;
     }
     const FactorDev &F = fd[lo];
-    const int st = state[lo];
-    if (st == ST_FAIL) return;
+    if (state[lo] != ST_RUN) return;
     const int lt = (int)blockIdx.x - sq_tile_start[lo];
     const int n = F.n;
     const int tpr = (n + BN - 1) / BN;
     const int ti = lt / tpr, tj = lt % tpr;
-    const bool finished = (st == ST_DONE) || at_end;
     const int par = j & 1;
-    const double *Xs = finished ? F.X64[fs[lo].iters & 1] : F.X64[par];
-    float *Xd = (finished || par == 0) ? F.Xout : F.X32b;
-    const int ldxd = (finished || par == 0) ? F.ldx : F.ld32;
     const double *Ms = F.M64[par];
     float *Md = F.M32[par];
     for (int e = threadIdx.x; e < BM * BN; e += 256) {
         const int row = ti * BM + e / BN, col = tj * BN + e % BN;
         if (row >= n || col >= n) continue;
-        Xd[(size_t)row * ldxd + col] = (float)Xs[(size_t)row * F.ld64 + col];
-        if (!finished) {
-            F.T32[(size_t)row * F.ld32 + col] = (float)F.T64[(size_t)row * F.ld64 + col];
-            if (st == ST_RUN) Md[(size_t)row * F.ld32 + col] = (float)Ms[(size_t)row * F.ld64 + col];
-        }
+        Md[(size_t)row * F.ld32 + col] = (float)Ms[(size_t)row * F.ld64 + col];
     }
-    if (finished && threadIdx.x == 0 && lt == 0) fs[lo].xloc = 0;
 }
 
 // Copy X from the workspace buffer to the caller's X where the last fp32 update landed there,
@@ -480,6 +494,8 @@ struct Plan {
     int lowp_from;     // first iteration that may run on the bf16 matrix cores (split operands)
     float stop_resid, power_tol, margin;
     bool use64, use32, adapted, lowp_auto;
+    bool xt_lowp;      // fully automatic precision: X updates on the bf16 cores (split operands) from the
+                       // first product on, and the look-ahead stop rule (accuracy class 1e-3)
 };
 
 // Host mirror of the device-side schedule for a spectrum of M_0 in [lo0, 1]:
@@ -510,10 +526,9 @@ void simulate_schedule(double lo0, int n, int root, bool adapted, double stop, d
 
 size_t factor_matrix_bytes(int n, bool use64, bool use32)
 {
-    size_t b = 0;
-    if (use32) b += 5 * Carver::need((size_t)n * ld4(n), sizeof(float));
-    else b += 0;
-    if (use64) b += 6 * Carver::need((size_t)n * ld2(n), sizeof(double));
+    size_t b = 2 * Carver::need((size_t)n * ld4(n), sizeof(float));            // second X buffer, T (fp32)
+    if (use32) b += 3 * Carver::need((size_t)n * ld4(n), sizeof(float));       // M x 2, T^4
+    if (use64) b += 4 * Carver::need((size_t)n * ld2(n), sizeof(double));      // M x 2, T, T^4
     return b;
 }
 
@@ -522,7 +537,7 @@ size_t factor_small_bytes(int n)
     const int pmb = (n + PM_ROWS - 1) / PM_ROWS;
     return 2 * Carver::need((size_t)ld4(n), sizeof(float)) + 2 * Carver::need((size_t)pmb, sizeof(float2)) +
            Carver::need((size_t)tri_tiles(n), sizeof(float)) + sizeof(FactorDev) + sizeof(FactorScal) +
-           2 * sizeof(int) + 18 * sizeof(GemmProblem);
+           2 * sizeof(int) + 14 * sizeof(GemmProblem);
 }
 
 size_t fixed_bytes() { return 64 * 256; }   // alignment slack of the shared arrays + coefficient table
@@ -576,6 +591,8 @@ asteria_status make_plan(const asteria_root_opts *opts_in, asteria_eps_mode mode
     }
     pl.lowp_from = jl;
     pl.lowp_auto = o.lowp_from < 0;
+    // only under fully automatic precision rules, and only where they use the 16-bit tier at all
+    pl.xt_lowp = pl.lowp_auto && o.fp64_iters < 0 && jl < o.max_iters;
     pl.fp64_iters = std::min(j, pl.max_iters);
     pl.use64 = pl.fp64_iters > 0;
     pl.use32 = pl.fp64_iters < pl.max_iters;
@@ -607,19 +624,16 @@ asteria_status run_pass(const asteria_factor *f, const std::vector<int> &order, 
     FactorScal *d_fs = cv.take<FactorScal>(cnt);
     int *d_state = cv.take<int>(cnt);
     int *d_sq = cv.take<int>(cnt);
-    GemmProblem *d_tab[2][2][3];   // [precision 0 = fp32, 1 = fp64][parity][launch]
-    GemmProblem *d_first[2];       // iteration 0: T T only (X_1 comes from the start kernel)
-    for (int pr = 0; pr < 2; ++pr) d_first[pr] = cv.take<GemmProblem>(cnt);
+    GemmProblem *d_tab[2][2][3];   // [precision 0 = fp32, 1 = fp64][parity][launch T T | T^2 T^2 | T^p M]
+    GemmProblem *d_xt[2];          // [parity] X' = X T on the fp32 buffers (every precision tier)
+    for (int pa = 0; pa < 2; ++pa) d_xt[pa] = cv.take<GemmProblem>(cnt);
     for (int pr = 0; pr < 2; ++pr)
-        for (int pa = 0; pa < 2; ++pa) {
-            d_tab[pr][pa][0] = cv.take<GemmProblem>(2 * (size_t)cnt);
-            d_tab[pr][pa][1] = cv.take<GemmProblem>(cnt);
-            d_tab[pr][pa][2] = cv.take<GemmProblem>(cnt);
-        }
+        for (int pa = 0; pa < 2; ++pa)
+            for (int l = 0; l < 3; ++l) d_tab[pr][pa][l] = cv.take<GemmProblem>(cnt);
 
     std::vector<FactorDev> fd(cnt);
     std::vector<int> sq(cnt);
-    int tri_total = 0, sq_total = 0, pm_total = 0;
+    int tri_total = 0, sq_total = 0, pm_total = 0, pm_blocks_max = 0;
     int n_max = 0;
     double a_min = 1.0;
     for (int i = 0; i < cnt; ++i) {
@@ -636,6 +650,7 @@ asteria_status run_pass(const asteria_factor *f, const std::vector<int> &order, 
         sq[i] = sq_total; sq_total += tpr * tpr;
         F.pm_blocks = (n + PM_ROWS - 1) / PM_ROWS;
         F.pm_block_start = pm_total; pm_total += F.pm_blocks;
+        pm_blocks_max = std::max(pm_blocks_max, F.pm_blocks);
         F.eps_in = eps[eps_count == 1 ? 0 : order[first + i]];
         if (mode == ASTERIA_EPS_RELATIVE) {
             const double er = (double)F.eps_in;
@@ -650,13 +665,13 @@ asteria_status run_pass(const asteria_factor *f, const std::vector<int> &order, 
     for (int i = 0; i < cnt; ++i) {
         FactorDev &F = fd[i];
         const size_t e32 = (size_t)F.n * F.ld32, e64 = (size_t)F.n * F.ld64;
+        F.X32b = cv.take<float>(e32);
+        F.T32 = cv.take<float>(e32);
         if (pl.use32) {
-            F.X32b = cv.take<float>(e32);
             F.M32[0] = cv.take<float>(e32); F.M32[1] = cv.take<float>(e32);
-            F.T32 = cv.take<float>(e32); F.T432 = cv.take<float>(e32);
+            F.T432 = cv.take<float>(e32);
         }
         if (pl.use64) {
-            F.X64[0] = cv.take<double>(e64); F.X64[1] = cv.take<double>(e64);
             F.M64[0] = cv.take<double>(e64); F.M64[1] = cv.take<double>(e64);
             F.T64 = cv.take<double>(e64); F.T464 = cv.take<double>(e64);
         }
@@ -676,47 +691,60 @@ asteria_status run_pass(const asteria_factor *f, const std::vector<int> &order, 
 
     // problem tables
     const float ca = (float)(root + 1) / (float)root, cg = 1.0f / (float)root;
-    std::vector<GemmProblem> tab[2][2][3], tab_first[2];
+    std::vector<GemmProblem> tab[2][2][3], tab_xt[2];
+    for (int pa = 0; pa < 2; ++pa) {
+        int t0 = 0;
+        for (int i = 0; i < cnt; ++i) {
+            const FactorDev &F = fd[i];
+            GemmProblem p;
+            memset(&p, 0, sizeof(p));
+            p.M = p.N = p.K = F.n;
+            p.state_idx = i;
+            p.state_mask = (1 << ST_RUN) | (1 << ST_LAST);
+            p.alpha = 1.0f; p.beta = 0.0f; p.ep_a = ca; p.ep_g = cg;
+            p.flags = GEMM_SYM;
+            // X after an odd number of updates lives in the workspace buffer, else in the caller's X
+            p.A = pa ? (const void *)F.X32b : (const void *)F.Xout; p.lda = pa ? F.ld32 : F.ldx;
+            p.B = F.T32; p.ldb = F.ld32;
+            p.C = pa ? (void *)F.Xout : (void *)F.X32b; p.ldc = pa ? F.ldx : F.ld32;
+            p.tile_start = t0; t0 += F.ntri;
+            tab_xt[pa].push_back(p);
+        }
+    }
     for (int pr = 0; pr < 2; ++pr) {
         if ((pr == 0 && !pl.use32) || (pr == 1 && !pl.use64)) continue;
         for (int pa = 0; pa < 2; ++pa) {
-            int t0 = 0, t1 = 0;
+            int t1 = 0;
             for (int i = 0; i < cnt; ++i) {
                 const FactorDev &F = fd[i];
-                const void *Xsrc, *Tm, *Mcur;
-                void *Xdst, *Mnext, *T4, *Tw;
-                int ldxs, ldxd, ldw;
+                const void *Tm, *Mcur;
+                void *Mnext, *T4, *Tw;
+                int ldw;
                 if (pr == 1) {
-                    Xsrc = F.X64[pa]; Xdst = F.X64[pa ^ 1]; ldxs = ldxd = F.ld64;
                     Tm = F.T64; Tw = F.T64; Mcur = F.M64[pa]; Mnext = F.M64[pa ^ 1]; T4 = F.T464; ldw = F.ld64;
                 } else {
-                    Xsrc = pa ? (const void *)F.X32b : (const void *)F.Xout; ldxs = pa ? F.ld32 : F.ldx;
-                    Xdst = pa ? (void *)F.Xout : (void *)F.X32b; ldxd = pa ? F.ldx : F.ld32;
                     Tm = F.T32; Tw = F.T32; Mcur = F.M32[pa]; Mnext = F.M32[pa ^ 1]; T4 = F.T432; ldw = F.ld32;
                 }
                 GemmProblem p;
                 memset(&p, 0, sizeof(p));
                 p.M = p.N = p.K = F.n;
                 p.state_idx = i;
+                p.state_mask = (1 << ST_RUN);
                 p.alpha = 1.0f; p.beta = 0.0f; p.ep_a = ca; p.ep_g = cg;
                 p.flags = GEMM_SYM;
-                // launch 0: X' = X T (running or last), T2 = T T (running)
-                p.A = Xsrc; p.lda = ldxs; p.B = Tm; p.ldb = ldw; p.C = Xdst; p.ldc = ldxd;
-                p.state_mask = (1 << ST_RUN) | (1 << ST_LAST);
-                p.tile_start = t0; t0 += F.ntri;
-                tab[pr][pa][0].push_back(p);
-                p.A = Tm; p.lda = ldw; p.B = Tm; p.ldb = ldw; p.C = Mnext; p.ldc = ldw;
-                p.state_mask = (1 << ST_RUN);
-                p.tile_start = t0; t0 += F.ntri;
-                tab[pr][pa][0].push_back(p);
-                if (pa == 0) { tab_first[pr].push_back(p); tab_first[pr].back().tile_start = t1; }
-                // launch 1: T4 = T2 T2 (root 4 only)
-                p.A = Mnext; p.B = Mnext; p.C = T4; p.ldc = ldw;
                 p.tile_start = t1;
+                // launch 0: T2 = T T, kept in the buffer that receives M' afterwards (root 4) or in
+                // the T^4 buffer (root 2, where the M-update reads T2 while writing M')
+                void *T2 = (root == 4) ? Mnext : T4;
+                p.A = Tm; p.lda = ldw; p.B = Tm; p.ldb = ldw; p.C = T2; p.ldc = ldw;
+                tab[pr][pa][0].push_back(p);
+                // launch 1: T4 = T2 T2 (root 4 only)
+                p.A = T2; p.B = T2; p.C = T4;
                 tab[pr][pa][1].push_back(p);
-                // launch 2: M' = T^p M, T' = a I - g M', residual partial sums
-                p.A = (root == 4) ? (const void *)T4 : (const void *)Mnext; p.B = Mcur;
+                // launch 2: M' = T^p M, T' = a I - g M' (+ its fp32 copy in the fp64 tier), residual partial sums
+                p.A = (root == 4) ? (const void *)T4 : (const void *)T2; p.B = Mcur;
                 p.C = Mnext; p.C2 = Tw; p.ldc2 = ldw; p.partial = F.partial;
+                if (pr == 1) { p.C3 = F.T32; p.ldc3 = F.ld32; }
                 p.coef = reinterpret_cast<const float *>(reinterpret_cast<const char *>(d_fs + i) +
                                                          offsetof(FactorScal, coef_next));
                 p.flags = GEMM_SYM | GEMM_EPI_ROOT;
@@ -725,25 +753,11 @@ asteria_status run_pass(const asteria_factor *f, const std::vector<int> &order, 
             }
         }
     }
-    // For root 2 the M-update reads T2 = Mnext as A while writing Mnext: not allowed -> use T4 as target
-    if (root == 2) {
-        for (int pr = 0; pr < 2; ++pr)
-            for (int pa = 0; pa < 2; ++pa)
-                for (size_t i = 0; i < tab[pr][pa][0].size() / 2; ++i) {
-                    // T2 goes to the T4 buffer instead, M' to Mnext
-                    GemmProblem &t2 = tab[pr][pa][0][2 * i + 1];
-                    GemmProblem &mu = tab[pr][pa][2][i];
-                    t2.C = tab[pr][pa][1][i].C;
-                    mu.A = t2.C;
-                    if (pa == 0) tab_first[pr][i].C = t2.C;
-                }
-    }
 
     ASTERIA_HIP_TRY(upload_async(d_fd, fd.data(), sizeof(FactorDev) * cnt, stream));
     ASTERIA_HIP_TRY(upload_async(d_sq, sq.data(), sizeof(int) * cnt, stream));
-    for (int pr = 0; pr < 2; ++pr)
-        if (!tab_first[pr].empty())
-            ASTERIA_HIP_TRY(upload_async(d_first[pr], tab_first[pr].data(), tab_first[pr].size() * sizeof(GemmProblem), stream));
+    for (int pa = 0; pa < 2; ++pa)
+        ASTERIA_HIP_TRY(upload_async(d_xt[pa], tab_xt[pa].data(), tab_xt[pa].size() * sizeof(GemmProblem), stream));
     for (int pr = 0; pr < 2; ++pr)
         for (int pa = 0; pa < 2; ++pa)
             for (int l = 0; l < 3; ++l)
@@ -755,7 +769,7 @@ asteria_status run_pass(const asteria_factor *f, const std::vector<int> &order, 
     hipLaunchKernelGGL(pm_init_kernel, dim3(cnt), dim3(256), 0, stream, d_fd, d_fs);
     const int ctl_blocks = (cnt + 127) / 128;
     for (int it = 0; it < pl.power_iters; ++it) {
-        hipLaunchKernelGGL(pm_matvec_kernel, dim3(pm_total), dim3(256), 0, stream, d_fd, d_fs, cnt, it & 1, it == 0 ? 1 : 0);
+        hipLaunchKernelGGL(pm_matvec_kernel, dim3(pm_blocks_max, cnt), dim3(256), 0, stream, d_fd, d_fs, cnt, it & 1, it == 0 ? 1 : 0);
         hipLaunchKernelGGL(pm_control_kernel, dim3(ctl_blocks), dim3(128), 0, stream, d_fd, d_fs, cnt, pl.power_tol, it == 0 ? 1 : 0);
     }
     // 2. scaling, start
@@ -773,39 +787,39 @@ asteria_status run_pass(const asteria_factor *f, const std::vector<int> &order, 
     for (int k = 0; k < K; ++k) {
         const bool p32 = k >= j64;
         hipLaunchKernelGGL(root_control_kernel, dim3(cnt), dim3(64), 0, stream, d_fd, d_fs, d_state, k,
-                           p32 ? 1 : 0, 0, pl.stop_resid, root, pl.adapted ? 1 : 0);
+                           p32 ? 1 : 0, 0, pl.stop_resid, root, pl.adapted ? 1 : 0, pl.xt_lowp ? 1 : 0);
         if (k == j64 && j64 > 0)
-            hipLaunchKernelGGL(root_to_fp32_kernel, dim3(sq_total), dim3(256), 0, stream, d_fd, d_fs, d_state,
-                               cnt, j64, 0, d_sq);
+            hipLaunchKernelGGL(root_to_fp32_kernel, dim3(sq_total), dim3(256), 0, stream, d_fd, d_state, cnt, j64, d_sq);
         const int pa = k & 1;
-        if (p32 && k >= jlow && k > 0) {
-            ASTERIA_HIP_TRY((launch_gemm_bf16_grouped<float, float, 2, 2>(d_tab[0][pa][0], 2 * cnt, 2 * tri_total, d_state, stream)));
+        const bool lowp = p32 && k >= jlow;
+        // X' = X T (X_1 comes from the start kernel).  X only needs the accuracy of the result, so
+        // the update runs on the bf16 cores with split operands (16 bits) whenever the low-precision
+        // tier is chosen automatically, from the first product on; otherwise with the tier of M.
+        if (k > 0) {
+            if (pl.xt_lowp || lowp)
+                ASTERIA_HIP_TRY((launch_gemm_bf16_grouped<float, float, 2, 2>(d_xt[pa], cnt, tri_total, d_state, stream)));
+            else
+                ASTERIA_HIP_TRY((launch_gemm_grouped<float, float, float, false, false>(d_xt[pa], cnt, tri_total, d_state, stream)));
+        }
+        if (lowp) {
+            ASTERIA_HIP_TRY((launch_gemm_bf16_grouped<float, float, 2, 2>(d_tab[0][pa][0], cnt, tri_total, d_state, stream)));
             if (root == 4)
                 ASTERIA_HIP_TRY((launch_gemm_bf16_grouped<float, float, 2, 2>(d_tab[0][pa][1], cnt, tri_total, d_state, stream)));
             ASTERIA_HIP_TRY((launch_gemm_bf16_grouped<float, float, 2, 2>(d_tab[0][pa][2], cnt, tri_total, d_state, stream)));
         } else if (p32) {
-            if (k == 0)
-                ASTERIA_HIP_TRY((launch_gemm_grouped<float, float, float, false, false>(d_first[0], cnt, tri_total, d_state, stream)));
-            else
-                ASTERIA_HIP_TRY((launch_gemm_grouped<float, float, float, false, false>(d_tab[0][pa][0], 2 * cnt, 2 * tri_total, d_state, stream)));
+            ASTERIA_HIP_TRY((launch_gemm_grouped<float, float, float, false, false>(d_tab[0][pa][0], cnt, tri_total, d_state, stream)));
             if (root == 4)
                 ASTERIA_HIP_TRY((launch_gemm_grouped<float, float, float, false, false>(d_tab[0][pa][1], cnt, tri_total, d_state, stream)));
             ASTERIA_HIP_TRY((launch_gemm_grouped<float, float, float, false, false>(d_tab[0][pa][2], cnt, tri_total, d_state, stream)));
         } else {
-            if (k == 0)
-                ASTERIA_HIP_TRY((launch_gemm_grouped<double, double, double, false, false>(d_first[1], cnt, tri_total, d_state, stream)));
-            else
-                ASTERIA_HIP_TRY((launch_gemm_grouped<double, double, double, false, false>(d_tab[1][pa][0], 2 * cnt, 2 * tri_total, d_state, stream)));
+            ASTERIA_HIP_TRY((launch_gemm_grouped<double, double, double, false, false>(d_tab[1][pa][0], cnt, tri_total, d_state, stream)));
             if (root == 4)
                 ASTERIA_HIP_TRY((launch_gemm_grouped<double, double, double, false, false>(d_tab[1][pa][1], cnt, tri_total, d_state, stream)));
             ASTERIA_HIP_TRY((launch_gemm_grouped<double, double, double, false, false>(d_tab[1][pa][2], cnt, tri_total, d_state, stream)));
         }
     }
     hipLaunchKernelGGL(root_control_kernel, dim3(cnt), dim3(64), 0, stream, d_fd, d_fs, d_state, K,
-                       (K >= j64 && pl.use32) ? 1 : 0, 1, pl.stop_resid, root, pl.adapted ? 1 : 0);
-    if (j64 >= K)   // every iteration ran in fp64: hand the result over now
-        hipLaunchKernelGGL(root_to_fp32_kernel, dim3(sq_total), dim3(256), 0, stream, d_fd, d_fs, d_state, cnt,
-                           K, 1, d_sq);
+                       (K >= j64 && pl.use32) ? 1 : 0, 1, pl.stop_resid, root, pl.adapted ? 1 : 0, pl.xt_lowp ? 1 : 0);
     hipLaunchKernelGGL(root_finalize_kernel, dim3(sq_total), dim3(256), 0, stream, d_fd, d_fs, d_state, cnt,
                        d_sq, first, info, iters, resid, lambda_max);
     ASTERIA_HIP_TRY(hipGetLastError());
@@ -816,7 +830,7 @@ asteria_status run_pass(const asteria_factor *f, const std::vector<int> &order, 
 
 extern "C" asteria_status asteria_inverse_root_plan(int root, asteria_eps_mode mode, const float *eps, int eps_count,
                                                     const asteria_root_opts *opts, int32_t *fp64_iters,
-                                                    int32_t *lowp_from)
+                                                    int32_t *lowp_from, int32_t *x_update_lowp)
 {
     if (root != 2 && root != 4) return ASTERIA_UNSUPPORTED;
     if (!eps || eps_count <= 0) return ASTERIA_INVALID_ARG;
@@ -825,6 +839,7 @@ extern "C" asteria_status asteria_inverse_root_plan(int root, asteria_eps_mode m
     if (st != ASTERIA_OK) return st;
     if (fp64_iters) *fp64_iters = pl.fp64_iters;
     if (lowp_from) *lowp_from = pl.lowp_from;
+    if (x_update_lowp) *x_update_lowp = pl.xt_lowp ? 1 : 0;
     return ASTERIA_OK;
 }
 
@@ -877,7 +892,7 @@ extern "C" asteria_status asteria_inverse_root(const asteria_factor *f, int nfac
     while (first < nfactors) {
         size_t used = fixed_bytes();
         int cnt = 0;
-        while (first + cnt < nfactors) {
+        while (first + cnt < nfactors && cnt < 65535) {   // 65535: y extent of the mat-vec grid
             const int n = f[first + cnt].n;
             const size_t b = factor_matrix_bytes(n, pl.use64, pl.use32) + factor_small_bytes(n);
             if (used + b > ws_bytes) break;

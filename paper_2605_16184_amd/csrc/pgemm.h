@@ -1,0 +1,520 @@
+// Grouped GEMM over pre-split bf16 matrices on the gfx950 matrix cores
+// (v_mfma_f32_32x32x16_bf16, fp32 accumulation).
+//
+// Split format.  A real matrix is kept as NT bf16 terms whose sum approximates it: term 0 is
+// the value rounded to bf16, term 1 the rounded remainder (8 / 16 significant bits for NT = 1 /
+// 2).  The terms are interleaved along k in groups of 32: a row stores, for every 32
+// consecutive k, NT segments of 32 bf16 (64 bytes) - term 0's values, then term 1's.  Element
+// (r, k) of term t sits at  r * ld + (k / 32) * (32 NT) + t * 32 + k % 32.  With NT = 2 one
+// k-group of a row is exactly one 128-byte cache line, which is what the vector L1 wants: row
+// pieces of 64 bytes run at half the load bandwidth (measured 17 against 34 TB/s from L2).
+// The producer of a matrix writes this format once in its epilogue, so the K loop of the
+// consumer is a pure bf16 GEMM: 16-byte global loads, 16-byte LDS stores, no per-element
+// arithmetic.  A product of two split matrices is the sum of the term-pair products selected
+// by a compile-time mask; every pair is an exact bf16 x bf16 product accumulated in fp32.
+//
+// One launch walks a device table of problems  C = alpha A B^T + beta C  (A is M x K, B is
+// N x K, both k-contiguous).  Symmetric problems compute the tiles on or below the diagonal and
+// mirror them.  Split buffers are padded: rows up to a multiple of the tile edge, K up to a
+// multiple of the slab, all padding zero - the K loop and the split stores then need no guards.
+// fp32 outputs are guarded.
+#pragma once
+#include <type_traits>
+
+#include "gemm.h"
+
+namespace asteria {
+
+typedef __bf16 pg_bf16x8 __attribute__((ext_vector_type(8)));
+
+constexpr int PG_GROUP = 32;   // k values per interleave group
+
+// leading dimension (elements) of a split matrix with nt terms and k_pad (multiple of 32) columns
+inline int pg_ld(int k_pad, int nt) { return k_pad * nt; }
+
+struct PlaneProblem {
+    const uint16_t *A;      // split matrix, NTA terms
+    const uint16_t *B;      // split matrix, NTB terms
+    float *C32;             // fp32 output, or null
+    uint16_t *Cp;           // split output (c_terms terms), or null
+    uint16_t *Tp;           // root epilogue: split T' = a I - g C, or null
+    float *partial;         // root epilogue: per-tile sum (C - I)^2
+    const float *coef;      // root epilogue: device (a, g), or null for ep_a / ep_g
+    int M, N, K;
+    int lda, ldb, ldc32, ldcp, ldtp;   // elements
+    int tile_start;
+    int tiles_n;            // tile columns (non-symmetric problems)
+    int state_idx, state_mask;
+    float alpha, beta, ep_a, ep_g;
+    int flags;              // GEMM_SYM, GEMM_EPI_ROOT
+    int c_terms;            // terms of Cp / Tp (1 or 2)
+};
+
+// pair (ta, tb) of an NTA x NTB split product is issued iff bit ta * 2 + tb of PAIRS is set
+constexpr unsigned PG_PAIRS_1 = 0x1u;            // (0,0)
+constexpr unsigned PG_PAIRS_2x1 = 0x1u | 0x4u;   // (0,0) (1,0)
+constexpr unsigned PG_PAIRS_1x2 = 0x1u | 0x2u;   // (0,0) (0,1)
+constexpr unsigned PG_PAIRS_2x2 = 0x7u;          // (0,0) (0,1) (1,0): 16 bits of both operands
+
+// WGM x WGN wavefronts of WTM x WTN MFMA tiles (32 x 32); K slabs of BK; DEPTH register sets
+// of global-load prefetch.
+template <int NTA_, int NTB_, unsigned PAIRS_, int WGM_, int WGN_, int WTM_, int WTN_, int BK_, int DEPTH_ = 1, int MODE_ = 0>
+struct PgShape {
+    static constexpr int NTA = NTA_, NTB = NTB_, DEPTH = DEPTH_;
+    static constexpr int MODE = MODE_;                   // 0: every wavefront loads and multiplies in turn; 1: two wavefront groups alternate
+    static constexpr unsigned PAIRS = PAIRS_;
+    static constexpr int WGM = WGM_, WGN = WGN_, WTM = WTM_, WTN = WTN_, BK = BK_;
+    static constexpr int TM = 32 * WTM * WGM, TN = 32 * WTN * WGN;   // workgroup tile
+    static constexpr int NTHR = 64 * WGM * WGN;
+    static constexpr int GPS = BK / PG_GROUP;            // interleave groups per slab
+    static constexpr int CPG = PG_GROUP / 8;             // 16-byte chunks per term segment (4)
+    // an LDS row of an operand holds the slab piece of one matrix row as it lies in memory:
+    // GPS groups x NT segments x 4 chunks; chunks are XOR-swizzled by row
+    static constexpr int CPR_A = GPS * NTA * CPG, CPR_B = GPS * NTB * CPG;
+    static constexpr int RPV_A = NTHR / CPR_A, RPV_B = NTHR / CPR_B;   // rows covered by one vector index
+    static constexpr int NVA = TM / RPV_A, NVB = TN / RPV_B;
+    static constexpr int ROW_A = CPR_A * 8, ROW_B = CPR_B * 8;         // elements per LDS row
+    static constexpr int STAGE = TM * ROW_A + TN * ROW_B;              // elements per stage
+    static constexpr int STEPS = BK / 16;                // MFMA k-steps per slab
+    static constexpr size_t LDS_MAIN = 2 * (size_t)STAGE * sizeof(uint16_t);
+    static constexpr int CT_PITCH = 136;                 // fp32 staging tile of the epilogue (128 x 128)
+    static constexpr size_t LDS_EPI = 128 * (size_t)CT_PITCH * sizeof(float);
+    static constexpr size_t LDS_BYTES = LDS_MAIN > LDS_EPI ? LDS_MAIN : LDS_EPI;
+    static_assert(BK % PG_GROUP == 0, "slab = whole interleave groups");
+    static_assert(TM % 128 == 0 && TN % 128 == 0 && TM == TN, "square tiles of 128 x 128 quadrants");
+    static_assert(NTHR % CPR_A == 0 && NTHR % CPR_B == 0 && TM % RPV_A == 0 && TN % RPV_B == 0, "loader geometry");
+    static_assert((CPR_A & (CPR_A - 1)) == 0 && (CPR_B & (CPR_B - 1)) == 0 && CPR_A <= 16 && CPR_B <= 16 &&
+                      RPV_A % 16 == 0 && RPV_B % 16 == 0, "swizzle geometry");
+    static_assert(NTA >= 1 && NTA <= 2 && NTB >= 1 && NTB <= 2, "one or two terms");
+};
+
+// chunk c of LDS row r (CPR chunks per row) is stored at position c ^ swz(r): a 16-lane group
+// of the loader then writes whole contiguous rows, and the 16 rows a lane group reads for one
+// fragment chunk fall into 16 distinct 16-byte bank groups
+template <int CPR> __device__ __forceinline__ int pg_swz(int r) { return (r / (16 / CPR)) % CPR; }
+
+__device__ __forceinline__ floatx16 pg_mma(u32x4 a, u32x4 b, floatx16 c)
+{
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(pg_bf16x8, a), __builtin_bit_cast(pg_bf16x8, b),
+                                                   c, 0, 0, 0);
+}
+
+// LDS-only barrier: waits for this wavefront's LDS traffic, not for its global loads in flight
+__device__ __forceinline__ void pg_lds_barrier()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
+__device__ __forceinline__ uint32_t pg_pack_bf16(float a, float b)
+{
+    const __bf16 x = (__bf16)a, y = (__bf16)b;   // v_cvt_pk_bf16_f32: round to nearest even
+    return (uint32_t)__builtin_bit_cast(uint16_t, x) | ((uint32_t)__builtin_bit_cast(uint16_t, y) << 16);
+}
+__device__ __forceinline__ float pg_bf16_round(float a) { return (float)(__bf16)a; }
+
+// offset (elements) of (row, col, term 0) in a split matrix; col is a multiple of 8
+__device__ __forceinline__ size_t pg_off(int row, int col, int ld, int nt)
+{
+    return (size_t)row * ld + (size_t)(col / PG_GROUP) * (PG_GROUP * nt) + (col % PG_GROUP);
+}
+
+// Split 8 fp32 values at (row, col .. col + 7) into nt terms and store them (16 bytes per term).
+__device__ __forceinline__ void pg_store_split(uint16_t *base, int row, int col, int ld, int nt, const float (&v)[8])
+{
+    uint16_t *p = base + pg_off(row, col, ld, nt);
+    u32x4 w;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) w[e] = pg_pack_bf16(v[2 * e], v[2 * e + 1]);
+    *(ASTERIA_GLOBAL u32x4 *)p = w;
+    if (nt > 1) {
+        float r[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) r[e] = v[e] - pg_bf16_round(v[e]);   // exact in fp32
+#pragma unroll
+        for (int e = 0; e < 4; ++e) w[e] = pg_pack_bf16(r[2 * e], r[2 * e + 1]);
+        *(ASTERIA_GLOBAL u32x4 *)(p + PG_GROUP) = w;
+    }
+}
+
+// One finished row piece of 8 values at (grow, gcol .. gcol + 7): apply beta, store every
+// requested output, accumulate the residual.
+__device__ __forceinline__ void pg_emit(const PlaneProblem &P, int grow, int gcol, float (&val)[8], bool root,
+                                        float ep_a, float ep_g, float &rsum)
+{
+    if (P.C32) {
+        if (grow < P.M) {
+            float *c = P.C32 + (size_t)grow * P.ldc32 + gcol;
+            const bool vec = (gcol + 8 <= P.N) && ((P.ldc32 & 3) == 0) && ((reinterpret_cast<uintptr_t>(P.C32) & 15u) == 0);
+            if (vec) {
+                ASTERIA_GLOBAL floatx4 *c4 = (ASTERIA_GLOBAL floatx4 *)c;
+                if (P.beta != 0.0f) {
+                    const floatx4 o0 = c4[0], o1 = c4[1];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) { val[e] += P.beta * o0[e]; val[4 + e] += P.beta * o1[e]; }
+                }
+                floatx4 s0, s1;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) { s0[e] = val[e]; s1[e] = val[4 + e]; }
+                c4[0] = s0; c4[1] = s1;
+            } else {
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    if (gcol + e < P.N) {
+                        if (P.beta != 0.0f) val[e] += P.beta * c[e];
+                        c[e] = val[e];
+                    }
+            }
+        }
+    }
+    if (P.Cp) pg_store_split(P.Cp, grow, gcol, P.ldcp, P.c_terms, val);
+    if (root) {
+        float t[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const float d = (grow == gcol + e && grow < P.M) ? 1.0f : 0.0f;
+            t[e] = ep_a * d - ep_g * val[e];
+            const float er = val[e] - d;
+            rsum += er * er;
+        }
+        if (P.Tp) pg_store_split(P.Tp, grow, gcol, P.ldtp, P.c_terms, t);
+    }
+}
+
+#ifdef PG_CLOCK_PROBE
+__device__ unsigned long long pg_probe[4];
+#endif
+template <class S>
+__global__ __launch_bounds__(S::NTHR) void pgemm_kernel(const PlaneProblem *__restrict__ probs, int nprobs,
+                                                        int total_tiles, const int *__restrict__ state)
+{
+    constexpr int NTA = S::NTA, NTB = S::NTB, WTM = S::WTM, WTN = S::WTN;
+    constexpr int TM = S::TM, TN = S::TN, BK = S::BK;
+    extern __shared__ __align__(16) unsigned char smem_raw[];
+    ASTERIA_LDS uint16_t *smem = (ASTERIA_LDS uint16_t *)smem_raw;
+
+    const int per_xcd = (total_tiles + NUM_XCD - 1) / NUM_XCD;
+    const int t_global = (int)(blockIdx.x % NUM_XCD) * per_xcd + (int)(blockIdx.x / NUM_XCD);
+    if (t_global >= total_tiles) return;
+    int plo = 0, phi = nprobs - 1;
+    while (plo < phi) {
+        const int mid = (plo + phi + 1) >> 1;
+        if (probs[mid].tile_start <= t_global) plo = mid; else phi = mid - 1;
+    }
+#ifdef PG_CLOCK_PROBE
+    const unsigned long long probe_c0 = clock64(), probe_w0 = wall_clock64();
+#endif
+    const PlaneProblem P = probs[plo];   // by value: the fields stay in scalar registers across the stores below
+    if (P.state_idx >= 0) {
+        const int st = state[P.state_idx];
+        if (!((1 << st) & P.state_mask)) return;
+    }
+    const int lt = t_global - P.tile_start;
+    const bool sym = (P.flags & GEMM_SYM) != 0;
+    int ti, tj;
+    if (sym) tri_decode(lt, ti, tj);
+    else { ti = lt / P.tiles_n; tj = lt % P.tiles_n; }
+    const int row0 = ti * TM, col0 = tj * TN;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave / S::WGN, wn = wave % S::WGN;
+    const int r = lane & 31, h = lane >> 5;
+
+    floatx16 acc[WTM][WTN];
+#pragma unroll
+    for (int i = 0; i < WTM; ++i)
+#pragma unroll
+        for (int j = 0; j < WTN; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+
+    // ---- K loop ---------------------------------------------------------------------------------
+    {
+        // loader: thread -> (row, 16-byte chunk) of the operand's slab piece, the same for every vector index
+        const int lrowA = tid / S::CPR_A, lvecA = tid % S::CPR_A;
+        const int lrowB = tid / S::CPR_B, lvecB = tid % S::CPR_B;
+        // global addresses = wave-uniform base (scalar registers) + 32-bit per-thread byte offset:
+        // the loads then need no 64-bit vector address arithmetic (which would recycle registers
+        // that are still targets of loads in flight and serialise them)
+        const char *ubA = reinterpret_cast<const char *>(P.A + (size_t)row0 * P.lda);
+        const char *ubB = reinterpret_cast<const char *>(P.B + (size_t)col0 * P.ldb);
+        const uint32_t voA = ((uint32_t)lrowA * (uint32_t)P.lda + (uint32_t)lvecA * 8u) * 2u;
+        const uint32_t voB = ((uint32_t)lrowB * (uint32_t)P.ldb + (uint32_t)lvecB * 8u) * 2u;
+        const size_t stepA = (size_t)S::RPV_A * P.lda * 2, stepB = (size_t)S::RPV_B * P.ldb * 2;   // bytes
+        const uint32_t lds_sa = (uint32_t)(lrowA * S::ROW_A + ((lvecA ^ pg_swz<S::CPR_A>(lrowA)) * 8));
+        const uint32_t lds_sb = (uint32_t)(TM * S::ROW_A + lrowB * S::ROW_B + ((lvecB ^ pg_swz<S::CPR_B>(lrowB)) * 8));
+        // fragments: lane (r, h) takes k = 8 h .. 8 h + 7 of k-step s, i.e. chunk (s / 2) * NT * 4 + t * 4 + (s % 2) * 2 + h
+        const uint32_t lds_fa = (uint32_t)((wm * WTM * 32 + r) * S::ROW_A);
+        const uint32_t lds_fb = (uint32_t)(TM * S::ROW_A + (wn * WTN * 32 + r) * S::ROW_B);
+        const int swa = pg_swz<S::CPR_A>(r), swb = pg_swz<S::CPR_B>(r);
+        constexpr int DEPTH = S::DEPTH;
+        u32x4 ra[DEPTH][S::NVA], rb[DEPTH][S::NVB];
+        const int nk = (P.K + BK - 1) / BK;
+
+        // DEPTH register sets: slab j waits in set j % DEPTH from its global load until it is
+        // stored to LDS one iteration before use.
+        auto gload = [&](auto setc, int slab) {
+            constexpr int set = decltype(setc)::value;
+            const size_t ka = (size_t)slab * (BK * NTA * 2), kb = (size_t)slab * (BK * NTB * 2);   // bytes
+#pragma unroll
+            for (int v = 0; v < S::NVA; ++v) ra[set][v] = *(const ASTERIA_GLOBAL u32x4 *)(ubA + (v * stepA + ka) + voA);
+#pragma unroll
+            for (int v = 0; v < S::NVB; ++v) rb[set][v] = *(const ASTERIA_GLOBAL u32x4 *)(ubB + (v * stepB + kb) + voB);
+        };
+        auto lstore = [&](auto setc, int stage) {
+            constexpr int set = decltype(setc)::value;
+            ASTERIA_LDS uint16_t *d = smem + stage * S::STAGE;
+#pragma unroll
+            for (int v = 0; v < S::NVA; ++v) *(ASTERIA_LDS u32x4 *)(d + lds_sa + v * S::RPV_A * S::ROW_A) = ra[set][v];
+#pragma unroll
+            for (int v = 0; v < S::NVB; ++v) *(ASTERIA_LDS u32x4 *)(d + lds_sb + v * S::RPV_B * S::ROW_B) = rb[set][v];
+        };
+        auto compute = [&](int cur) {
+            const ASTERIA_LDS uint16_t *fa = smem + cur * S::STAGE + lds_fa;
+            const ASTERIA_LDS uint16_t *fb = smem + cur * S::STAGE + lds_fb;
+#pragma unroll
+            for (int s = 0; s < S::STEPS; ++s) {
+                u32x4 af[NTA][WTM], bf[NTB][WTN];
+#pragma unroll
+                for (int t = 0; t < NTA; ++t) {
+                    const int ca = (((s / 2) * NTA + t) * S::CPG + (s % 2) * 2 + h) ^ swa;
+#pragma unroll
+                    for (int i = 0; i < WTM; ++i)
+                        af[t][i] = *(const ASTERIA_LDS u32x4 *)(fa + i * 32 * S::ROW_A + ca * 8);
+                }
+#pragma unroll
+                for (int t = 0; t < NTB; ++t) {
+                    const int cb = (((s / 2) * NTB + t) * S::CPG + (s % 2) * 2 + h) ^ swb;
+#pragma unroll
+                    for (int j = 0; j < WTN; ++j)
+                        bf[t][j] = *(const ASTERIA_LDS u32x4 *)(fb + j * 32 * S::ROW_B + cb * 8);
+                }
+                // small cross terms first, the leading product last
+#pragma unroll
+                for (int order = NTA + NTB - 2; order >= 0; --order)
+#pragma unroll
+                    for (int ta = 0; ta < NTA; ++ta) {
+                        const int tb = order - ta;
+                        if (tb < 0 || tb >= NTB) continue;
+                        if (!((S::PAIRS >> (ta * 2 + tb)) & 1u)) continue;
+#pragma unroll
+                        for (int i = 0; i < WTM; ++i)
+#pragma unroll
+                            for (int j = 0; j < WTN; ++j) acc[i][j] = pg_mma(af[ta][i], bf[tb][j], acc[i][j]);
+                    }
+            }
+        };
+        // iteration kt: compute slab kt; store slab kt + 1 (set (kt + 1) % DEPTH) to the other
+        // stage; refill that set with slab kt + 1 + DEPTH
+        auto iteration = [&](auto setc, int kt) {
+            compute(kt & 1);
+            if (kt + 1 < nk) lstore(setc, (kt + 1) & 1);
+            if (kt + 1 + DEPTH < nk) gload(setc, kt + 1 + DEPTH);
+            pg_lds_barrier();
+        };
+
+        if constexpr (S::MODE == 1) {
+            // Two groups of wavefronts (one wavefront of each per SIMD) run half a period apart:
+            // while one group issues the MFMAs of a k-step from registers, the other reads its
+            // next fragments from LDS and moves the next slab global -> LDS.  Every phase ends in
+            // a workgroup barrier; the second group enters one barrier late and the first one
+            // leaves one barrier late, so all wavefronts execute the same number of barriers.
+            static_assert(DEPTH == 1 && (S::NTHR / 64) % 2 == 0, "alternating groups: one register set, even wavefront count");
+            using Set0 = std::integral_constant<int, 0>;
+            const int grp = __builtin_amdgcn_readfirstlane(wave) / (S::NTHR / 128);
+            u32x4 af[NTA][WTM], bf[NTB][WTN];
+            auto phase_barrier = [&]() {
+                __builtin_amdgcn_sched_barrier(0);
+                pg_lds_barrier();
+                __builtin_amdgcn_sched_barrier(0);
+            };
+            gload(Set0{}, 0);
+            lstore(Set0{}, 0);
+            if (1 < nk) gload(Set0{}, 1);
+            phase_barrier();
+            if (grp == 1) phase_barrier();
+            for (int kt = 0; kt < nk; ++kt) {
+                const ASTERIA_LDS uint16_t *fa = smem + (kt & 1) * S::STAGE + lds_fa;
+                const ASTERIA_LDS uint16_t *fb = smem + (kt & 1) * S::STAGE + lds_fb;
+#pragma unroll
+                for (int s = 0; s < S::STEPS; ++s) {
+                    // load phase
+#pragma unroll
+                    for (int t = 0; t < NTA; ++t) {
+                        const int ca = (((s / 2) * NTA + t) * S::CPG + (s % 2) * 2 + h) ^ swa;
+#pragma unroll
+                        for (int i = 0; i < WTM; ++i)
+                            af[t][i] = *(const ASTERIA_LDS u32x4 *)(fa + i * 32 * S::ROW_A + ca * 8);
+                    }
+#pragma unroll
+                    for (int t = 0; t < NTB; ++t) {
+                        const int cb = (((s / 2) * NTB + t) * S::CPG + (s % 2) * 2 + h) ^ swb;
+#pragma unroll
+                        for (int j = 0; j < WTN; ++j)
+                            bf[t][j] = *(const ASTERIA_LDS u32x4 *)(fb + j * 32 * S::ROW_B + cb * 8);
+                    }
+                    if (s == S::STEPS - 1) {
+                        if (kt + 1 < nk) lstore(Set0{}, (kt + 1) & 1);
+                        if (kt + 2 < nk) gload(Set0{}, kt + 2);
+                    }
+                    phase_barrier();
+                    // multiply phase
+                    __builtin_amdgcn_s_setprio(1);
+#pragma unroll
+                    for (int order = NTA + NTB - 2; order >= 0; --order)
+#pragma unroll
+                        for (int ta = 0; ta < NTA; ++ta) {
+                            const int tb = order - ta;
+                            if (tb < 0 || tb >= NTB) continue;
+                            if (!((S::PAIRS >> (ta * 2 + tb)) & 1u)) continue;
+#pragma unroll
+                            for (int i = 0; i < WTM; ++i)
+#pragma unroll
+                                for (int j = 0; j < WTN; ++j) acc[i][j] = pg_mma(af[ta][i], bf[tb][j], acc[i][j]);
+                        }
+                    __builtin_amdgcn_s_setprio(0);
+                    phase_barrier();
+                }
+            }
+            if (grp == 0) phase_barrier();
+        } else {
+        gload(std::integral_constant<int, 0>{}, 0);
+        if constexpr (DEPTH > 1) { if (1 < nk) gload(std::integral_constant<int, 1>{}, 1); }
+        if constexpr (DEPTH > 2) { if (2 < nk) gload(std::integral_constant<int, 2>{}, 2); }
+        lstore(std::integral_constant<int, 0>{}, 0);
+        if (DEPTH < nk) gload(std::integral_constant<int, 0>{}, DEPTH);
+        pg_lds_barrier();
+        for (int kt0 = 0; kt0 < nk; kt0 += DEPTH) {
+            // slab kt + 1 lives in set (kt + 1) % DEPTH
+            if constexpr (DEPTH == 1) {
+                iteration(std::integral_constant<int, 0>{}, kt0);
+            } else {
+                iteration(std::integral_constant<int, 1>{}, kt0);
+                if constexpr (DEPTH > 2) { if (kt0 + 1 < nk) iteration(std::integral_constant<int, 2>{}, kt0 + 1); }
+                if (kt0 + DEPTH - 1 < nk) iteration(std::integral_constant<int, 0>{}, kt0 + DEPTH - 1);
+            }
+        }
+        }
+    }
+
+    // ---- epilogue: 128 x 128 quadrants through an fp32 LDS tile ----------------------------------
+    const bool root = (P.flags & GEMM_EPI_ROOT) != 0;
+    const float ep_a = (root && P.coef) ? P.coef[0] : P.ep_a;
+    const float ep_g = (root && P.coef) ? P.coef[1] : P.ep_g;
+    const float alpha = P.alpha;
+    ASTERIA_LDS float *ct = (ASTERIA_LDS float *)smem_raw;
+    constexpr int CP = S::CT_PITCH;
+    constexpr int QM = TM / 128, QN = TN / 128;
+    constexpr int WROWS = WTM * 32, WCOLS = WTN * 32;     // wavefront sub-tile
+    float rsum = 0.0f;
+    constexpr int ITEMS = 128 * 16 / S::NTHR;             // 8-column row pieces per thread
+#pragma unroll 1
+    for (int q = 0; q < QM * QN; ++q) {
+        const int qi = q / QN, qj = q % QN;
+        const int gi = ti * QM + qi, gj = tj * QN + qj;   // quadrant coordinates in units of 128
+        if (gi * 128 >= P.M || gj * 128 >= P.N) continue;
+        if (sym && gi < gj) continue;
+        const bool diag = sym && gi == gj;
+        const bool mirror = sym && gi > gj;
+        // does this wavefront own part of the quadrant?
+        const int wr0 = wm * WROWS - qi * 128, wc0 = wn * WCOLS - qj * 128;   // sub-tile origin relative to the quadrant
+        const bool owns = wr0 < 128 && wr0 + WROWS > 0 && wc0 < 128 && wc0 + WCOLS > 0;
+        for (int pass = 0; pass < (mirror ? 2 : 1); ++pass) {
+            if (owns) {
+#pragma unroll
+                for (int i = 0; i < WTM; ++i) {
+                    const int br = wr0 + i * 32;
+                    if (br < 0 || br >= 128) continue;
+#pragma unroll
+                    for (int j = 0; j < WTN; ++j) {
+                        const int bc = wc0 + j * 32;
+                        if (bc < 0 || bc >= 128) continue;
+                        if (pass == 0) {
+#pragma unroll
+                            for (int v = 0; v < 16; ++v)
+                                ct[(br + 8 * (v >> 2) + 4 * h + (v & 3)) * CP + bc + r] = alpha * acc[i][j][v];
+                        } else {
+                            // transposed: ct[col][row .. row + 3]
+#pragma unroll
+                            for (int g4 = 0; g4 < 4; ++g4) {
+                                floatx4 w;
+#pragma unroll
+                                for (int e = 0; e < 4; ++e) w[e] = alpha * acc[i][j][4 * g4 + e];
+                                *(ASTERIA_LDS floatx4 *)(ct + (bc + r) * CP + br + 8 * g4 + 4 * h) = w;
+                            }
+                        }
+                    }
+                }
+            }
+            __syncthreads();
+            // pass 0 writes quadrant (gi, gj); pass 1 writes its mirror image at (gj, gi)
+            const int orow0 = (pass == 0 ? gi : gj) * 128, ocol0 = (pass == 0 ? gj : gi) * 128;
+#pragma unroll 2
+            for (int it = 0; it < ITEMS; ++it) {
+                const int item = tid + it * S::NTHR;
+                const int lr = item >> 4, lc = (item & 15) * 8;
+                float val[8];
+                if (diag) {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        const int c = lc + e;
+                        val[e] = (lr >= c) ? ct[lr * CP + c] : ct[c * CP + lr];
+                    }
+                } else {
+                    const floatx4 v0 = *(const ASTERIA_LDS floatx4 *)(ct + lr * CP + lc);
+                    const floatx4 v1 = *(const ASTERIA_LDS floatx4 *)(ct + lr * CP + lc + 4);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) { val[e] = v0[e]; val[4 + e] = v1[e]; }
+                }
+                pg_emit(P, orow0 + lr, ocol0 + lc, val, root, ep_a, ep_g, rsum);
+            }
+            __syncthreads();
+        }
+    }
+#ifdef PG_CLOCK_PROBE
+    if (tid == 0) { atomicAdd(&pg_probe[0], clock64() - probe_c0); atomicAdd(&pg_probe[1], wall_clock64() - probe_w0); atomicAdd(&pg_probe[2], 1ull); }
+#endif
+    if (root) {
+        // every element of the output (both triangles) was visited exactly once
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) rsum += __shfl_xor(rsum, off, 64);
+        float *red = reinterpret_cast<float *>(smem_raw);
+        if (lane == 0) red[wave] = rsum;
+        __syncthreads();
+        if (tid == 0) {
+            float t = 0.0f;
+#pragma unroll
+            for (int w = 0; w < S::NTHR / 64; ++w) t += red[w];
+            P.partial[lt] = t;
+        }
+    }
+}
+
+inline int pg_tri_tiles(int n, int tile)
+{
+    const int t = (n + tile - 1) / tile;
+    return t * (t + 1) / 2;
+}
+
+template <class S>
+inline hipError_t launch_pgemm(const PlaneProblem *probs, int nprobs, int total_tiles, const int *state,
+                               hipStream_t stream, int kind = 256)
+{
+    if (total_tiles <= 0 || nprobs <= 0) return hipSuccess;
+    auto kern = pgemm_kernel<S>;
+    static bool configured = false;
+    if (!configured) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)S::LDS_BYTES);
+        if (e != hipSuccess) return e;
+        configured = true;
+    }
+    const int per_xcd = (total_tiles + NUM_XCD - 1) / NUM_XCD;
+    profile_begin(kind, stream);
+    hipLaunchKernelGGL(kern, dim3(per_xcd * NUM_XCD), dim3(S::NTHR), S::LDS_BYTES, stream, probs, nprobs,
+                       total_tiles, state);
+    profile_end(stream);
+    return hipGetLastError();
+}
+
+}  // namespace asteria

@@ -309,6 +309,8 @@ extern "C" asteria_status asteria_soap_refresh(const asteria_factor *f, int nfac
     }
     if (!ws) return ASTERIA_WORKSPACE_TOO_SMALL;
     if (reinterpret_cast<uintptr_t>(ws) & 255u) return ASTERIA_INVALID_ARG;   // workspace must be 256-byte aligned
+    // the first factor must fit: checked before anything touches the device
+    if (refresh_fixed_bytes(n_all) + refresh_factor_bytes(f[0].n) > ws_bytes) return ASTERIA_WORKSPACE_TOO_SMALL;
     hipStream_t stream = reinterpret_cast<hipStream_t>(stream_);
     constexpr size_t chol_lds = sizeof(double) * QR_PANEL * (QR_PANEL + 1);
     static bool chol_configured = false;
