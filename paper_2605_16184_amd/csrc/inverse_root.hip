@@ -524,11 +524,20 @@ void simulate_schedule(double lo0, int n, int root, bool adapted, double stop, d
     if (lead_full) *lead_full = leadf;
 }
 
+// The fp32 work matrices of the M-chain (M x 2, T^4) are first written at the fp64 -> fp32 hand-over,
+// when the fp64 T and T^4 are dead: they share one region.
+size_t shared_region_bytes(int n, bool use64, bool use32)
+{
+    const size_t b32 = use32 ? 3 * Carver::need((size_t)n * ld4(n), sizeof(float)) : 0;
+    const size_t b64 = use64 ? 2 * Carver::need((size_t)n * ld2(n), sizeof(double)) : 0;
+    return b32 > b64 ? b32 : b64;
+}
+
 size_t factor_matrix_bytes(int n, bool use64, bool use32)
 {
     size_t b = 2 * Carver::need((size_t)n * ld4(n), sizeof(float));            // second X buffer, T (fp32)
-    if (use32) b += 3 * Carver::need((size_t)n * ld4(n), sizeof(float));       // M x 2, T^4
-    if (use64) b += 4 * Carver::need((size_t)n * ld2(n), sizeof(double));      // M x 2, T, T^4
+    b += shared_region_bytes(n, use64, use32);                                 // fp64 T, T^4 | fp32 M x 2, T^4
+    if (use64) b += 2 * Carver::need((size_t)n * ld2(n), sizeof(double));      // fp64 M x 2
     return b;
 }
 
@@ -667,13 +676,17 @@ asteria_status run_pass(const asteria_factor *f, const std::vector<int> &order, 
         const size_t e32 = (size_t)F.n * F.ld32, e64 = (size_t)F.n * F.ld64;
         F.X32b = cv.take<float>(e32);
         F.T32 = cv.take<float>(e32);
+        unsigned char *shared = cv.take<unsigned char>(shared_region_bytes(F.n, pl.use64, pl.use32));
         if (pl.use32) {
-            F.M32[0] = cv.take<float>(e32); F.M32[1] = cv.take<float>(e32);
-            F.T432 = cv.take<float>(e32);
+            const size_t step = Carver::need(e32, sizeof(float));
+            F.M32[0] = reinterpret_cast<float *>(shared);
+            F.M32[1] = reinterpret_cast<float *>(shared + step);
+            F.T432 = reinterpret_cast<float *>(shared + 2 * step);
         }
         if (pl.use64) {
+            F.T64 = reinterpret_cast<double *>(shared);
+            F.T464 = reinterpret_cast<double *>(shared + Carver::need(e64, sizeof(double)));
             F.M64[0] = cv.take<double>(e64); F.M64[1] = cv.take<double>(e64);
-            F.T64 = cv.take<double>(e64); F.T464 = cv.take<double>(e64);
         }
     }
 
