@@ -290,7 +290,8 @@ __global__ __launch_bounds__(256) void root_init_kernel(const FactorDev *fd, con
         M = reinterpret_cast<TC *>(F.M32[0]); T = reinterpret_cast<TC *>(F.T32); ldm = F.ld32;
     }
     float *X = F.X32b;            // holds X after an odd number of updates
-    float *T32c = (sizeof(TC) == 8) ? F.T32 : nullptr;   // fp32 copy of T for the X update
+    // no fp32 copy of T_0 is needed: X_1 = xs T_0 is written here, and the first X product (k = 1)
+    // reads the fp32 T_1 that the M-update epilogue of iteration 0 writes
     const int ldx = F.ld32;
     // The tile pair (ti, tj) / (tj, ti) is walked in 32 x 32 sub-tiles.  P = A[sub(ti, tj)] and
     // Q = A[sub(tj, ti)] are both read along rows (coalesced) into LDS; the symmetrised value at
@@ -324,7 +325,6 @@ __global__ __launch_bounds__(256) void root_init_kernel(const FactorDev *fd, con
                     const TC t = ca * d - cg * m;
                     M[(size_t)r * ldm + c] = m;
                     T[(size_t)r * ldm + c] = t;
-                    if (T32c) T32c[(size_t)r * F.ld32 + c] = (float)t;
                     X[(size_t)r * ldx + c] = (float)(xs * t);
                     const float e = (float)(m - d);
                     // a diagonal sub-tile holds both triangles itself; every other one stands for two
@@ -340,7 +340,6 @@ __global__ __launch_bounds__(256) void root_init_kernel(const FactorDev *fd, con
                     const TC t = -cg * m;
                     M[(size_t)r2 * ldm + c2] = m;
                     T[(size_t)r2 * ldm + c2] = t;
-                    if (T32c) T32c[(size_t)r2 * F.ld32 + c2] = (float)t;
                     X[(size_t)r2 * ldx + c2] = (float)(xs * t);
                 }
             }

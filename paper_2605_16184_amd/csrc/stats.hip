@@ -4,27 +4,39 @@
 // Both products are symmetric grouped GEMMs on the matrix cores with the EMA fused in the
 // epilogue; only tiles on/below the diagonal are computed and mirrored.
 //   bf16 gradients: bf16 MFMA (products exact in fp32).  G G^T reads G as is; for G^T G a
-//     transposed bf16 copy of G is written to the workspace first (one extra HBM round trip of
-//     G, ~10% of the call's traffic) so that both products read k-contiguous operands.
+//     transposed bf16 copy of G, zero-padded to whole tiles, is written to the workspace first
+//     (one extra HBM round trip of G, ~10% of the call's traffic) so that both products read
+//     k-contiguous operands.  Operands that are 16-byte aligned and fill whole tiles go through
+//     the guard-free bf16 kernel (pgemm.h: 16-byte row pieces, LDS-staged epilogue with vector
+//     loads of the old L / R); anything else through the guarded one.
 //   fp32 gradients: fp32 MFMA; G^T G reads G k-major, no copy.
 #include <vector>
 
 #include "common.h"
 #include "gemm.h"
 #include "gemm_bf16.h"
+#include "pgemm.h"
 
 using namespace asteria;
 
 namespace {
 
-inline int ld8(int n) { return (n + 7) & ~7; }
+inline int pad_to(int n, int q) { return (n + q - 1) / q * q; }
 
-// G^T for a batch of bf16 blocks: 64 x 64 tiles through LDS, reads and writes along rows.
+// guard-free kernel for the statistics: one bf16 term per operand, 128 x 128 tiles, slabs of 64
+using StatsShape = PgShape<1, 1, PG_PAIRS_1, 2, 2, 2, 2, 64, 1>;
+constexpr int ST_TILE = StatsShape::TM;   // 128
+constexpr int ST_BK = StatsShape::BK;     // 64
+
+// G^T for a batch of bf16 blocks: 64 x 64 tiles through LDS, reads and writes along rows.  The
+// destination is padded to n_pad x m_pad (whole tiles of the consumer) and the padding is zero.
 struct TransposeJob {
     const uint16_t *src;   // m x n, ld = lds_
-    uint16_t *dst;         // n x m, ld = ldd
+    uint16_t *dst;         // n_pad x m_pad, ld = ldd
     int m, n, lds_, ldd;
+    int m_pad, n_pad;
     int tile_start;
+    int pad_;
 };
 
 __global__ __launch_bounds__(256) void transpose_bf16_kernel(const TransposeJob *jobs, int njobs)
@@ -36,7 +48,7 @@ __global__ __launch_bounds__(256) void transpose_bf16_kernel(const TransposeJob 
     }
     const TransposeJob &J = jobs[lo];
     const int lt = (int)blockIdx.x - J.tile_start;
-    const int tcols = (J.n + 63) / 64;
+    const int tcols = J.n_pad / 64;
     const int ti = lt / tcols, tj = lt % tcols;       // tile of src: rows ti, columns tj
     __shared__ uint16_t tile[64][66];
     const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
@@ -46,15 +58,39 @@ __global__ __launch_bounds__(256) void transpose_bf16_kernel(const TransposeJob 
     }
     __syncthreads();
     for (int rr = ty; rr < 64; rr += 4) {
-        const int r = tj * 64 + rr, c = ti * 64 + tx;  // element (r, c) of dst = src(c, r)
-        if (r < J.n && c < J.m) J.dst[(size_t)r * J.ldd + c] = tile[tx][rr];
+        const int r = tj * 64 + rr, c = ti * 64 + tx;  // element (r, c) of dst = src(c, r), zero in the padding
+        J.dst[(size_t)r * J.ldd + c] = tile[tx][rr];
     }
 }
 
 struct StatsTables {
-    std::vector<GemmProblem> L[2], R[2];   // by dtype
+    std::vector<GemmProblem> L[2], R[2];   // by dtype (guarded kernels)
     int tilesL[2] = {0, 0}, tilesR[2] = {0, 0};
+    std::vector<PlaneProblem> fast;        // bf16 problems for the guard-free kernel (L and R sides)
+    int tiles_fast = 0;
 };
+
+// G itself can feed the guard-free kernel: 16-byte aligned rows, whole tiles and slabs
+inline bool fast_operand(const void *p, int rows, int k, int ld)
+{
+    return (reinterpret_cast<uintptr_t>(p) & 15u) == 0 && (ld % 8) == 0 && (rows % ST_TILE) == 0 && (k % ST_BK) == 0;
+}
+
+inline PlaneProblem fast_problem(const void *G, int rows, int k, int ld, float *C, int ldc, float beta, int tile_start)
+{
+    PlaneProblem q;
+    memset(&q, 0, sizeof(q));
+    q.A = reinterpret_cast<const uint16_t *>(G); q.B = q.A;
+    q.lda = ld; q.ldb = ld;
+    q.C32 = C; q.ldc32 = ldc;
+    q.M = rows; q.N = rows; q.K = k;
+    q.tile_start = tile_start;
+    q.state_idx = -1; q.state_mask = ~0;
+    q.alpha = 1.0f - beta; q.beta = beta;
+    q.flags = GEMM_SYM;
+    q.c_terms = 1;
+    return q;
+}
 
 asteria_status validate(const asteria_block *b, int nblocks, float beta)
 {
@@ -84,12 +120,17 @@ void build(const asteria_block *b, int nblocks, float beta, StatsTables &t)
         p.alpha = 1.0f - beta; p.beta = beta;
         p.flags = GEMM_SYM;
         if (k.L) {
-            p.C = k.L; p.ldc = k.ldl; p.M = k.m; p.N = k.m; p.K = k.n;
-            p.tile_start = t.tilesL[d];
-            t.tilesL[d] += tri_tiles(k.m);
-            t.L[d].push_back(p);
+            if (d == ASTERIA_BF16 && fast_operand(k.G, k.m, k.n, k.ldg)) {
+                t.fast.push_back(fast_problem(k.G, k.m, k.n, k.ldg, k.L, k.ldl, beta, t.tiles_fast));
+                t.tiles_fast += pg_tri_tiles(k.m, ST_TILE);
+            } else {
+                p.C = k.L; p.ldc = k.ldl; p.M = k.m; p.N = k.m; p.K = k.n;
+                p.tile_start = t.tilesL[d];
+                t.tilesL[d] += tri_tiles(k.m);
+                t.L[d].push_back(p);
+            }
         }
-        if (k.R) {
+        if (k.R && d != ASTERIA_BF16) {      // bf16: the transposed padded copy always feeds the guard-free kernel
             p.C = k.R; p.ldc = k.ldr; p.M = k.n; p.N = k.n; p.K = k.m;
             p.tile_start = t.tilesR[d];
             t.tilesR[d] += tri_tiles(k.n);
@@ -104,10 +145,11 @@ extern "C" size_t asteria_stats_update_workspace_bytes(const asteria_block *bloc
 {
     if (!blocks || nblocks <= 0) return 0;
     size_t bytes = 2 * Carver::need((size_t)nblocks, sizeof(GemmProblem)) +
+                   Carver::need(2 * (size_t)nblocks, sizeof(PlaneProblem)) +
                    Carver::need((size_t)nblocks, sizeof(TransposeJob)) + 8 * 256;
     for (int i = 0; i < nblocks; ++i)
         if (blocks[i].g_dtype == ASTERIA_BF16 && blocks[i].R && blocks[i].m > 0 && blocks[i].n > 0)
-            bytes += Carver::need((size_t)blocks[i].n * ld8(blocks[i].m), sizeof(uint16_t));
+            bytes += Carver::need((size_t)pad_to(blocks[i].n, ST_TILE) * pad_to(blocks[i].m, ST_BK), sizeof(uint16_t));
     return bytes;
 }
 
@@ -127,28 +169,34 @@ extern "C" asteria_status asteria_stats_update(const asteria_block *blocks, int 
     {
         std::vector<TransposeJob> jobs;
         int tiles = 0;
-        size_t ri = 0;
         TransposeJob *d_jobs = cv.take<TransposeJob>(nblocks);
         for (int i = 0; i < nblocks; ++i) {
             const asteria_block &k = blocks[i];
             if (k.g_dtype != ASTERIA_BF16 || !k.R) continue;
-            const int ldt = ld8(k.m);
-            uint16_t *Gt = cv.take<uint16_t>((size_t)k.n * ldt);
+            const int n_pad = pad_to(k.n, ST_TILE), m_pad = pad_to(k.m, ST_BK);
+            uint16_t *Gt = cv.take<uint16_t>((size_t)n_pad * m_pad);
             TransposeJob j;
+            memset(&j, 0, sizeof(j));
             j.src = reinterpret_cast<const uint16_t *>(k.G); j.dst = Gt;
-            j.m = k.m; j.n = k.n; j.lds_ = k.ldg; j.ldd = ldt;
+            j.m = k.m; j.n = k.n; j.lds_ = k.ldg; j.ldd = m_pad;
+            j.m_pad = m_pad; j.n_pad = n_pad;
             j.tile_start = tiles;
-            tiles += ((k.m + 63) / 64) * ((k.n + 63) / 64);
+            tiles += (m_pad / 64) * (n_pad / 64);
             jobs.push_back(j);
             // the R problem of this block reads G^T with k (= m) contiguous
-            GemmProblem &p = t.R[ASTERIA_BF16][ri++];
-            p.A = Gt; p.B = Gt; p.lda = ldt; p.ldb = ldt;
+            t.fast.push_back(fast_problem(Gt, k.n, k.m, m_pad, k.R, k.ldr, beta, t.tiles_fast));
+            t.tiles_fast += pg_tri_tiles(k.n, ST_TILE);
         }
         if (!jobs.empty()) {
             ASTERIA_HIP_TRY(upload_async(d_jobs, jobs.data(), jobs.size() * sizeof(TransposeJob), stream));
             hipLaunchKernelGGL(transpose_bf16_kernel, dim3(tiles), dim3(256), 0, stream, d_jobs, (int)jobs.size());
             ASTERIA_HIP_TRY(hipGetLastError());
         }
+    }
+    if (!t.fast.empty()) {
+        PlaneProblem *dF = cv.take<PlaneProblem>(t.fast.size());
+        ASTERIA_HIP_TRY(upload_async(dF, t.fast.data(), t.fast.size() * sizeof(PlaneProblem), stream));
+        ASTERIA_HIP_TRY((launch_pgemm<StatsShape>(dF, (int)t.fast.size(), t.tiles_fast, nullptr, stream, 512)));
     }
     for (int d = 0; d < 2; ++d) {
         GemmProblem *dL = nullptr, *dR = nullptr;
