@@ -76,15 +76,17 @@ struct QrFactor {
     int bad;        // set to 1 when a column could not be normalised
 };
 
-constexpr int QR_THREADS = 1024;
 constexpr int QR_PANEL = 128;
 constexpr int QR_MAXN = 1 << 20;
 
 // One workgroup per (factor, panel).  In: the fp64 Gram matrix G = P P^T of the panel's rows
 // (rows x rows, leading dimension QR_PANEL).  Out: W = L^-1 in fp32, where G = L L^T is the
 // Cholesky factorisation (positive diagonal), so that W P has orthonormal rows and P = L (W P)
-// is the QR relation with a positive diagonal.  Everything runs in LDS in fp64.
-__global__ __launch_bounds__(QR_THREADS) void panel_chol_inverse_kernel(QrFactor *fs, const int *fidx, int panel)
+// is the QR relation with a positive diagonal.  Everything runs in LDS in fp64: a right-looking
+// Cholesky on a 16 x 16 thread grid, then the triangular inverse in place, row by row (row i of
+// W needs row i of L and the rows of W above it; one thread per column).
+constexpr int CHOL_THREADS = 256;
+__global__ __launch_bounds__(CHOL_THREADS) void panel_chol_inverse_kernel(QrFactor *fs, const int *fidx, int panel)
 {
     QrFactor &F = fs[fidx[blockIdx.x]];
     const int rows = min(QR_PANEL, F.n - panel * QR_PANEL);
@@ -93,13 +95,11 @@ __global__ __launch_bounds__(QR_THREADS) void panel_chol_inverse_kernel(QrFactor
     constexpr int PITCH = QR_PANEL + 1;
     __shared__ int bad_flag;
     const int tid = threadIdx.x;
+    const int ti = tid >> 4, tj = tid & 15;
     if (tid == 0) bad_flag = 0;
-    for (int e = tid; e < rows * rows; e += QR_THREADS) {
-        const int i = e / rows, j = e % rows;
-        L[i * PITCH + j] = F.gram[(size_t)i * QR_PANEL + j];
-    }
+    for (int i = ti; i < rows; i += 16)
+        for (int j = tj; j < rows; j += 16) L[i * PITCH + j] = F.gram[(size_t)i * QR_PANEL + j];
     __syncthreads();
-    // right-looking Cholesky, lower triangle
     for (int k = 0; k < rows; ++k) {
         double piv = L[k * PITCH + k];
         if (!(piv > 0.0) || !(piv < 1e300)) {            // not positive definite: keep going with a tiny pivot
@@ -107,29 +107,35 @@ __global__ __launch_bounds__(QR_THREADS) void panel_chol_inverse_kernel(QrFactor
             piv = 1e-300;
         }
         const double d = sqrt(piv);
+        __syncthreads();                                  // every thread has read the pivot
+        for (int i = k + tid; i < rows; i += CHOL_THREADS) L[i * PITCH + k] = (i == k) ? d : L[i * PITCH + k] / d;
         __syncthreads();
-        for (int i = k + tid; i < rows; i += QR_THREADS) L[i * PITCH + k] = (i == k) ? d : L[i * PITCH + k] / d;
-        __syncthreads();
-        const int m = rows - k - 1;
-        for (int e = tid; e < m * m; e += QR_THREADS) {
-            const int i = k + 1 + e / m, j = k + 1 + e % m;
-            if (j <= i) L[i * PITCH + j] -= L[i * PITCH + k] * L[j * PITCH + k];
+        for (int i = k + 1 + ti; i < rows; i += 16) {
+            const double lik = L[i * PITCH + k];
+            for (int j = k + 1 + tj; j <= i; j += 16) L[i * PITCH + j] -= lik * L[j * PITCH + k];
         }
         __syncthreads();
     }
-    // W = L^-1 by forward substitution, one column of W per thread (W lower triangular).  The
-    // Gram matrix is in LDS now, so its global buffer holds W in fp64 (a thread only reads back
-    // what it wrote itself); the fp32 copy feeds the matrix cores.
-    double *W = F.gram;
-    for (int c = tid; c < rows; c += QR_THREADS) {
-        for (int i = 0; i < rows; ++i) {
-            double s = (i == c) ? 1.0 : 0.0;
-            for (int j = c; j < i; ++j) s -= L[i * PITCH + j] * W[(size_t)j * QR_PANEL + c];
-            const double w = (i < c) ? 0.0 : s / L[i * PITCH + i];
-            W[(size_t)i * QR_PANEL + c] = w;
-            F.winv[(size_t)i * QR_PANEL + c] = (float)w;
+    // W = L^-1 over L: W[i][i] = 1 / L[i][i], W[i][j] = -(sum_{k=j}^{i-1} L[i][k] W[k][j]) / L[i][i]
+    for (int i = 0; i < rows; ++i) {
+        double w = 0.0;
+        if (tid <= i) {
+            const double dinv = 1.0 / L[i * PITCH + i];
+            if (tid == i) {
+                w = dinv;
+            } else {
+                double sum = 0.0;
+                for (int k = tid; k < i; ++k) sum += L[i * PITCH + k] * L[k * PITCH + tid];
+                w = -sum * dinv;
+            }
         }
+        __syncthreads();                                  // row i of L fully read
+        if (tid <= i) L[i * PITCH + tid] = w;
+        __syncthreads();
     }
+    for (int i = ti; i < rows; i += 16)
+        for (int j = tj; j < rows; j += 16)
+            F.winv[(size_t)i * QR_PANEL + j] = (j <= i) ? (float)L[i * PITCH + j] : 0.0f;
     if (tid == 0 && bad_flag) F.bad = 1;
 }
 
@@ -437,7 +443,7 @@ extern "C" asteria_status asteria_soap_refresh(const asteria_factor *f, int nfac
             }
             for (int rep = 0; rep < 2; ++rep) {
                 ASTERIA_HIP_TRY((launch_gemm_grouped<double, float, float, false, false>(d_t3[j], (int)t3[j].size(), (int)t3[j].size(), nullptr, stream)));
-                hipLaunchKernelGGL(panel_chol_inverse_kernel, dim3((unsigned)fidx[j].size()), dim3(QR_THREADS), chol_lds, stream, d_q, d_fidx[j], j);
+                hipLaunchKernelGGL(panel_chol_inverse_kernel, dim3((unsigned)fidx[j].size()), dim3(CHOL_THREADS), chol_lds, stream, d_q, d_fidx[j], j);
                 ASTERIA_HIP_TRY((launch_gemm_grouped<float, float, float, false, true>(d_t4[j], (int)t4[j].size(), tiles4[j], nullptr, stream)));
             }
         }
