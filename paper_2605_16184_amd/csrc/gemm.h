@@ -43,7 +43,8 @@ __device__ __forceinline__ uint16_t f32_to_bf16(float f)
 enum : int {
     GEMM_SYM = 1,        // compute tiles with ti >= tj only, mirror the result
     GEMM_EPI_ROOT = 2,   // C2 = ep_a * I - ep_g * C ; partial[tile] = sum (C - I)^2
-    GEMM_C_BF16 = 4      // C is stored as bf16 (fp32 compute only)
+    GEMM_C_BF16 = 4,     // C is stored as bf16 (fp32 compute only)
+    GEMM_STORE_T = 8     // C is stored transposed: element (row, col) at C[col * ldc + row] (no beta, not symmetric)
 };
 
 struct GemmProblem {
@@ -390,7 +391,19 @@ __device__ __forceinline__ void gemm_epilogue(const GemmProblem &P, typename MM:
             const int col = bc + r;
             bool done = false;
             if constexpr (sizeof(TC) == 4) {
-                if (vec_c && (!sym || below)) {
+                if (vec_c && (flags & GEMM_STORE_T)) {
+                    // a lane owns 4 consecutive rows of one column: one 16-byte store per group
+                    ASTERIA_GLOBAL float *Cg = (ASTERIA_GLOBAL float *)C;
+#pragma unroll
+                    for (int g4 = 0; g4 < MM::NACC / 4; ++g4) {
+                        const int rb = br + 8 * g4 + 4 * h;
+                        floatx4 v4;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) v4[e] = alpha * acc[i][j][4 * g4 + e];
+                        *(ASTERIA_GLOBAL floatx4 *)(Cg + (size_t)col * ldc + rb) = v4;
+                    }
+                    done = true;
+                } else if (vec_c && (!sym || below)) {
                     ASTERIA_GLOBAL float *Cg = (ASTERIA_GLOBAL float *)C;
                     ASTERIA_GLOBAL float *C2g = (ASTERIA_GLOBAL float *)C2;
 #pragma unroll
@@ -427,8 +440,9 @@ __device__ __forceinline__ void gemm_epilogue(const GemmProblem &P, typename MM:
                 if (row >= M || col >= N) continue;
                 if (sym && row < col) continue;   // the mirror of (col, row) covers it
                 TC val = alpha * acc[i][j][v];
-                if (beta != (TC)0) val += beta * load_c<TC>(C, (size_t)row * ldc + col, flags);
-                store_c<TC>(C, (size_t)row * ldc + col, val, flags);
+                const size_t at = (flags & GEMM_STORE_T) ? (size_t)col * ldc + row : (size_t)row * ldc + col;
+                if (beta != (TC)0) val += beta * load_c<TC>(C, at, flags);
+                store_c<TC>(C, at, val, flags);
                 if (sym && row != col) store_c<TC>(C, (size_t)col * ldc + row, val, flags);
                 if (root) {
                     const TC d = (row == col) ? (TC)1 : (TC)0;

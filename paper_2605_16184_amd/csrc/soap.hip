@@ -1,9 +1,13 @@
 // SOAP variant (paper Eq. 2):  N = Q_L phi(Q_L^T G Q_R) Q_R^T with phi = Adam in the rotated
 // basis (asteria_soap_step), and the eigenbasis refresh Q <- qr(A Q).Q (asteria_soap_refresh).
 //
-// soap_step:   four grouped fp32-MFMA GEMMs (rotate in: G Q_R, then Q_L^T (.); rotate out:
-//              N' Q_R^T, then Q_L (.)) around one HBM-streaming Adam kernel.  Q_L / Q_R stay
-//              fp32 operands: a bf16 cast of an eigenbasis costs 0.1-0.5 relative error in N.
+// soap_step:   four grouped GEMMs (rotate in: G Q_R, then Q_L^T (.); rotate out: N' Q_R^T, then
+//              Q_L (.)) around one HBM-streaming Adam kernel, on the bf16 matrix cores with every
+//              fp32 operand split into two bf16 terms (16 bits kept, three MFMA passes per product,
+//              two when G is bf16): a plain bf16 cast of an eigenbasis costs 0.1-0.5 relative error
+//              in N, the split about 1e-5.  That kernel reads k-contiguous operands only, so the
+//              call first writes Q_L^T and Q_R^T to the workspace, and the first product of each
+//              rotation stores its result transposed.
 // soap_refresh: Z^T = Q^T A by one grouped GEMM (columns of Z become contiguous rows), then the
 //              thin QR factor of Z with diag(R) > 0 - the same Q a Householder QR with that sign
 //              convention returns, since the factorisation is unique - by block Gram-Schmidt
@@ -21,6 +25,7 @@
 
 #include "common.h"
 #include "gemm.h"
+#include "gemm_bf16.h"
 
 using namespace asteria;
 
@@ -61,6 +66,40 @@ __global__ __launch_bounds__(256) void adam_rotated_kernel(const AdamBlock *bloc
         mm[j] = m1;
         vv[j] = v1;
         np[j] = (m1 * inv_c1) / (sqrtf(v1 * inv_c2) + eps);
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// dst = src^T for a batch of fp32 matrices, 32 x 32 tiles through LDS (reads and writes along rows)
+struct TransposeF32Job {
+    const float *src;   // rows x cols, ld = lds_
+    float *dst;         // cols x rows, ld = ldd
+    int rows, cols, lds_, ldd;
+    int tile_start;
+    int pad_;
+};
+
+__global__ __launch_bounds__(256) void transpose_f32_kernel(const TransposeF32Job *jobs, int njobs)
+{
+    int lo = 0, hi = njobs - 1;
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (jobs[mid].tile_start <= (int)blockIdx.x) lo = mid; else hi = mid - 1;
+    }
+    const TransposeF32Job &J = jobs[lo];
+    const int lt = (int)blockIdx.x - J.tile_start;
+    const int tcols = (J.cols + 31) / 32;
+    const int ti = lt / tcols, tj = lt % tcols;
+    __shared__ float tile[32][33];
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+    for (int rr = ty; rr < 32; rr += 8) {
+        const int r = ti * 32 + rr, c = tj * 32 + tx;
+        tile[rr][tx] = (r < J.rows && c < J.cols) ? J.src[(size_t)r * J.lds_ + c] : 0.0f;
+    }
+    __syncthreads();
+    for (int rr = ty; rr < 32; rr += 8) {
+        const int r = tj * 32 + rr, c = ti * 32 + tx;   // element (r, c) of dst = src(c, r)
+        if (r < J.cols && c < J.rows) J.dst[(size_t)r * J.ldd + c] = tile[tx][rr];
     }
 }
 
@@ -190,9 +229,15 @@ asteria_status validate_step(const asteria_sblock *b, int nblocks, float b1, flo
 extern "C" size_t asteria_soap_step_workspace_bytes(const asteria_sblock *blocks, int nblocks)
 {
     if (!blocks || nblocks <= 0) return 0;
-    size_t bytes = 4 * Carver::need((size_t)nblocks, sizeof(GemmProblem)) + Carver::need((size_t)nblocks, sizeof(AdamBlock)) + 2048;
-    for (int i = 0; i < nblocks; ++i)
-        bytes += 2 * Carver::need((size_t)blocks[i].m * ld4(blocks[i].n), sizeof(float));
+    size_t bytes = 4 * Carver::need((size_t)nblocks, sizeof(GemmProblem)) + Carver::need((size_t)nblocks, sizeof(AdamBlock)) +
+                   Carver::need(2 * (size_t)nblocks, sizeof(TransposeF32Job)) + 2048;
+    for (int i = 0; i < nblocks; ++i) {
+        const int m = blocks[i].m, n = blocks[i].n;
+        bytes += 2 * Carver::need((size_t)m * ld4(n), sizeof(float));      // G' / N' (m x n)
+        bytes += Carver::need((size_t)n * ld4(m), sizeof(float));          // transposed intermediate (n x m)
+        bytes += Carver::need((size_t)m * ld4(m), sizeof(float));          // Q_L^T
+        bytes += Carver::need((size_t)n * ld4(n), sizeof(float));          // Q_R^T
+    }
     return bytes;
 }
 
@@ -210,39 +255,53 @@ extern "C" asteria_status asteria_soap_step(const asteria_sblock *blocks, int nb
     GemmProblem *d_g[4];
     for (int i = 0; i < 4; ++i) d_g[i] = cv.take<GemmProblem>(nblocks);
     AdamBlock *d_ab = cv.take<AdamBlock>(nblocks);
+    TransposeF32Job *d_tj = cv.take<TransposeF32Job>(2 * (size_t)nblocks);
     std::vector<GemmProblem> g1[2], g2, g3, g4;
     std::vector<AdamBlock> ab;
-    int tiles1[2] = {0, 0}, tiles = 0, rows = 0;
+    std::vector<TransposeF32Job> tj;
+    int tiles1[2] = {0, 0}, tiles = 0, tilesT = 0, rows = 0, ttiles = 0;
     for (int i = 0; i < nblocks; ++i) {
         const asteria_sblock &k = blocks[i];
-        const int ldw = ld4(k.n);
-        float *W = cv.take<float>((size_t)k.m * ldw);   // G Q_R, later N'
-        float *Gr = cv.take<float>((size_t)k.m * ldw);  // G', later N' Q_R^T
+        const int ldw = ld4(k.n), ldt = ld4(k.m), ldqlt = ld4(k.m), ldqrt = ld4(k.n);
+        float *Gr = cv.take<float>((size_t)k.m * ldw);   // G' (m x n)
+        float *Np = cv.take<float>((size_t)k.m * ldw);   // N' (m x n)
+        float *Tt = cv.take<float>((size_t)k.n * ldt);   // (G Q_R)^T, later (N' Q_R^T)^T  (n x m)
+        float *QLt = cv.take<float>((size_t)k.m * ldqlt);
+        float *QRt = cv.take<float>((size_t)k.n * ldqrt);
+        TransposeF32Job t;
+        memset(&t, 0, sizeof(t));
+        t.src = reinterpret_cast<const float *>(k.QL); t.dst = QLt; t.rows = k.m; t.cols = k.m; t.lds_ = k.ldql; t.ldd = ldqlt;
+        t.tile_start = ttiles; ttiles += ((k.m + 31) / 32) * ((k.m + 31) / 32);
+        tj.push_back(t);
+        t.src = reinterpret_cast<const float *>(k.QR); t.dst = QRt; t.rows = k.n; t.cols = k.n; t.lds_ = k.ldqr; t.ldd = ldqrt;
+        t.tile_start = ttiles; ttiles += ((k.n + 31) / 32) * ((k.n + 31) / 32);
+        tj.push_back(t);
         const int tm = (k.m + BM - 1) / BM, tn = (k.n + BN - 1) / BN;
         GemmProblem p;
         memset(&p, 0, sizeof(p));
         p.state_idx = -1; p.state_mask = ~0; p.alpha = 1.0f; p.beta = 0.0f;
-        p.M = k.m; p.N = k.n; p.tiles_n = tn;
-        // W = G Q_R            (B k-major)
-        p.A = k.G; p.lda = k.ldg; p.B = k.QR; p.ldb = k.ldqr; p.K = k.n; p.C = W; p.ldc = ldw;
+        // 1: (G Q_R)^T:   A' = G (m x n), B' = Q_R^T (B'(j, k) = Q_R[k][j]); m x n result stored transposed
+        p.M = k.m; p.N = k.n; p.K = k.n; p.tiles_n = tn;
+        p.A = k.G; p.lda = k.ldg; p.B = QRt; p.ldb = ldqrt; p.C = Tt; p.ldc = ldt; p.flags = GEMM_STORE_T;
         p.tile_start = tiles1[k.g_dtype]; tiles1[k.g_dtype] += tm * tn;
         g1[k.g_dtype].push_back(p);
+        // 2: G' = Q_L^T (G Q_R):   A' = Q_L^T (m x m), B' = (G Q_R)^T (n x m)
+        p.K = k.m; p.A = QLt; p.lda = ldqlt; p.B = Tt; p.ldb = ldt; p.C = Gr; p.ldc = ldw; p.flags = 0;
         p.tile_start = tiles;
-        // G' = Q_L^T W         (A and B k-major)
-        p.A = k.QL; p.lda = k.ldql; p.B = W; p.ldb = ldw; p.K = k.m; p.C = Gr; p.ldc = ldw;
         g2.push_back(p);
-        // Y = N' Q_R^T         (both k-contiguous); N' lives in W, Y in Gr
-        p.A = W; p.lda = ldw; p.B = k.QR; p.ldb = k.ldqr; p.K = k.n; p.C = Gr; p.ldc = ldw;
+        // 3: (N' Q_R^T)^T:   A' = N' (m x n), B' = Q_R (B'(j, k) = Q_R[j][k]); stored transposed
+        p.K = k.n; p.A = Np; p.lda = ldw; p.B = k.QR; p.ldb = k.ldqr; p.C = Tt; p.ldc = ldt; p.flags = GEMM_STORE_T;
         g3.push_back(p);
-        // N = Q_L Y            (B k-major)
-        p.A = k.QL; p.lda = k.ldql; p.B = Gr; p.ldb = ldw; p.K = k.m; p.C = k.N; p.ldc = k.ldn;
+        // 4: N = Q_L (N' Q_R^T):   A' = Q_L (m x m), B' = (N' Q_R^T)^T (n x m)
+        p.K = k.m; p.A = k.QL; p.lda = k.ldql; p.B = Tt; p.ldb = ldt; p.C = k.N; p.ldc = k.ldn; p.flags = 0;
         g4.push_back(p);
         tiles += tm * tn;
         AdamBlock a;
-        a.Gr = Gr; a.M = k.M; a.V = k.V; a.Np = W; a.m = k.m; a.n = k.n; a.ldw = ldw; a.ldm = k.ldm; a.ldv = k.ldv;
+        a.Gr = Gr; a.M = k.M; a.V = k.V; a.Np = Np; a.m = k.m; a.n = k.n; a.ldw = ldw; a.ldm = k.ldm; a.ldv = k.ldv;
         a.row_start = rows; rows += k.m;
         ab.push_back(a);
     }
+    (void)tilesT;
     GemmProblem *d_g1b = d_g[0] + g1[0].size();
     if (!g1[0].empty()) ASTERIA_HIP_TRY(upload_async(d_g[0], g1[0].data(), g1[0].size() * sizeof(GemmProblem), stream));
     if (!g1[1].empty()) ASTERIA_HIP_TRY(upload_async(d_g1b, g1[1].data(), g1[1].size() * sizeof(GemmProblem), stream));
@@ -250,18 +309,21 @@ extern "C" asteria_status asteria_soap_step(const asteria_sblock *blocks, int nb
     ASTERIA_HIP_TRY(upload_async(d_g[2], g3.data(), g3.size() * sizeof(GemmProblem), stream));
     ASTERIA_HIP_TRY(upload_async(d_g[3], g4.data(), g4.size() * sizeof(GemmProblem), stream));
     ASTERIA_HIP_TRY(upload_async(d_ab, ab.data(), ab.size() * sizeof(AdamBlock), stream));
+    ASTERIA_HIP_TRY(upload_async(d_tj, tj.data(), tj.size() * sizeof(TransposeF32Job), stream));
 
+    hipLaunchKernelGGL(transpose_f32_kernel, dim3(ttiles), dim3(256), 0, stream, d_tj, (int)tj.size());
+    ASTERIA_HIP_TRY(hipGetLastError());
     if (!g1[0].empty())
-        ASTERIA_HIP_TRY((launch_gemm_grouped<float, float, float, false, true>(d_g[0], (int)g1[0].size(), tiles1[0], nullptr, stream)));
+        ASTERIA_HIP_TRY((launch_gemm_bf16_grouped<float, float, 2, 2>(d_g[0], (int)g1[0].size(), tiles1[0], nullptr, stream)));
     if (!g1[1].empty())
-        ASTERIA_HIP_TRY((launch_gemm_grouped<float, bf16_t, float, false, true>(d_g1b, (int)g1[1].size(), tiles1[1], nullptr, stream)));
-    ASTERIA_HIP_TRY((launch_gemm_grouped<float, float, float, true, true>(d_g[1], nblocks, tiles, nullptr, stream)));
+        ASTERIA_HIP_TRY((launch_gemm_bf16_grouped<bf16_t, float, 1, 2>(d_g1b, (int)g1[1].size(), tiles1[1], nullptr, stream)));
+    ASTERIA_HIP_TRY((launch_gemm_bf16_grouped<float, float, 2, 2>(d_g[1], nblocks, tiles, nullptr, stream)));
     const float c1 = 1.0f - powf(beta1, (float)step_t), c2 = 1.0f - powf(beta2, (float)step_t);
     hipLaunchKernelGGL(adam_rotated_kernel, dim3(rows), dim3(256), 0, stream, d_ab, nblocks, beta1, beta2,
                        adam_eps, 1.0f / c1, 1.0f / c2);
     ASTERIA_HIP_TRY(hipGetLastError());
-    ASTERIA_HIP_TRY((launch_gemm_grouped<float, float, float, false, false>(d_g[2], nblocks, tiles, nullptr, stream)));
-    ASTERIA_HIP_TRY((launch_gemm_grouped<float, float, float, false, true>(d_g[3], nblocks, tiles, nullptr, stream)));
+    ASTERIA_HIP_TRY((launch_gemm_bf16_grouped<float, float, 2, 2>(d_g[2], nblocks, tiles, nullptr, stream)));
+    ASTERIA_HIP_TRY((launch_gemm_bf16_grouped<float, float, 2, 2>(d_g[3], nblocks, tiles, nullptr, stream)));
     return ASTERIA_OK;
 }
 

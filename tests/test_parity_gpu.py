@@ -420,7 +420,9 @@ def test_soap_step_same_basis_parity_over_three_steps():
         for i in range(len(shapes)):
             QL, QR, M, V, N, _, _ = state[i]
             No, Mo, Vo = oracle.soap_step(np64(Gs[i]), np64(QL), np64(QR), Min[i], Vin[i], 0.9, 0.95, 1e-8, t)
-            assert relF(M, Mo) <= 1e-5 and relF(V, Vo) <= 1e-5
+            # the rotations keep 16 bits of Q_L, Q_R and of the intermediate product (two bf16 terms
+            # each): the rotated gradient, and with it the moments, carry a few 2^-16 of relative error
+            assert relF(M, Mo) <= 2e-4 and relF(V, Vo) <= 2e-4
             assert relF(N, No) <= TOL_PRECOND, (t, i, relF(N, No))
             assert torch.all(N._base[:, N.shape[1]:] == -777.0)
 
@@ -432,7 +434,7 @@ def test_soap_step_identity_bases_reduce_to_adam():
     ast.soap_step([(G, torch.eye(m, device=DEV), torch.eye(n, device=DEV), M, V, N)], 0.9, 0.95, 1e-8, 1)
     torch.cuda.synchronize()
     g = np64(G)
-    assert relF(N, g / (np.abs(g) + 1e-8)) <= 1e-5
+    assert relF(N, g / (np.abs(g) + 1e-8)) <= 1e-4      # 16 bits of every operand are kept (two bf16 terms)
 
 
 # =============================================================================== determinism
