@@ -2,9 +2,9 @@
 //
 // Same problem table, tile order and epilogue as gemm.h; operands are always k-contiguous.
 // An operand is either bf16 in memory (used as is - bf16 x bf16 products are exact in fp32) or
-// fp32 in memory and split on the fly into NT bf16 terms (x ~ hi + lo, hi = upper half of x,
-// lo = upper half of x - hi): with two terms per operand the kernel issues hi*hi, hi*lo and lo*hi, which
-// keeps about 16 bits of the fp32 operands at three bf16 MFMA passes.
+// fp32 in memory and split on the fly into NT bf16 terms (x ~ hi + lo, hi = bf16(x),
+// lo = bf16(x - hi)): with two terms per operand the kernel issues hi*hi, hi*lo and lo*hi, which
+// keeps 16 to 18 bits of the fp32 operands at three bf16 MFMA passes.
 //
 // Workgroup = 256 threads = 2 x 2 wavefronts of 64 x 64 (2 x 2 MFMA tiles each), K slabs of 64
 // (32 when operands are split, to fit both terms of both operands in LDS twice).
@@ -31,22 +31,31 @@ struct MmaBf16 {
     __device__ static __forceinline__ int acc_row(int v, int h) { return 8 * (v >> 2) + 4 * h + (v & 3); }
 };
 
-// hi / lo bf16 split of four fp32 values, by truncation: hi = the upper 16 bits of x, lo = the
-// upper 16 bits of x - hi (that difference is exact in fp32).  hi + lo keeps 16 significant bits
-// (relative error <= 2^-16) at three VALU operations per element: the split runs once per tile
-// and slab, so its cost competes with the MFMA work it feeds.  Returns packed pairs.
+// hi / lo bf16 split of four fp32 values with round-to-nearest in both terms: hi = bf16(x),
+// lo = bf16(x - hi) (that difference is exact in fp32), so hi + lo keeps x to 2^-18 relative.
+// gfx950 converts two fp32 to a packed bf16 pair in one instruction (v_cvt_pk_bf16_f32), which
+// makes this as cheap as a truncating split: per pair one convert, two unpacks, two subtracts,
+// one convert.  The split runs once per tile and slab, so its cost competes with the MFMA work
+// it feeds.  Returns packed pairs.
+__device__ __forceinline__ uint32_t cvt_pk_bf16(float a, float b)
+{
+    typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+    typedef float floatx2_t __attribute__((ext_vector_type(2)));
+    const floatx2_t f = {a, b};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2_t));
+}
+
 __device__ __forceinline__ void split4(u32x4 x, u32x2 &hi, u32x2 &lo, bool want_lo)
 {
-    // v_perm_b32 picks bytes 2..3 of both sources: (b & 0xffff0000) | (a >> 16)
-    hi[0] = __builtin_amdgcn_perm(x[1], x[0], 0x07060302u);
-    hi[1] = __builtin_amdgcn_perm(x[3], x[2], 0x07060302u);
+    const float x0 = __uint_as_float(x[0]), x1 = __uint_as_float(x[1]);
+    const float x2 = __uint_as_float(x[2]), x3 = __uint_as_float(x[3]);
+    hi[0] = cvt_pk_bf16(x0, x1);
+    hi[1] = cvt_pk_bf16(x2, x3);
     if (want_lo) {
-        uint32_t d[4];
-#pragma unroll
-        for (int e = 0; e < 4; ++e)
-            d[e] = __float_as_uint(__uint_as_float(x[e]) - __uint_as_float(x[e] & 0xffff0000u));
-        lo[0] = __builtin_amdgcn_perm(d[1], d[0], 0x07060302u);
-        lo[1] = __builtin_amdgcn_perm(d[3], d[2], 0x07060302u);
+        const float d0 = x0 - __uint_as_float(hi[0] << 16), d1 = x1 - __uint_as_float(hi[0] & 0xffff0000u);
+        const float d2 = x2 - __uint_as_float(hi[1] << 16), d3 = x3 - __uint_as_float(hi[1] & 0xffff0000u);
+        lo[0] = cvt_pk_bf16(d0, d1);
+        lo[1] = cvt_pk_bf16(d2, d3);
     } else {
         lo[0] = 0u; lo[1] = 0u;
     }
