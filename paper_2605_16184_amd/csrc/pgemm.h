@@ -33,8 +33,8 @@ constexpr int PG_GROUP = 32;   // k values per interleave group
 inline int pg_ld(int k_pad, int nt) { return k_pad * nt; }
 
 struct PlaneProblem {
-    const uint16_t *A;      // split matrix, NTA terms
-    const uint16_t *B;      // split matrix, NTB terms
+    const void *A;          // split / bf16 matrix (NTA terms), or fp32 matrix when the shape says so
+    const void *B;          // the same for B
     float *C32;             // fp32 output, or null
     uint16_t *Cp;           // split output (c_terms terms), or null
     uint16_t *Tp;           // root epilogue: split T' = a I - g C, or null
@@ -46,7 +46,7 @@ struct PlaneProblem {
     int tiles_n;            // tile columns (non-symmetric problems)
     int state_idx, state_mask;
     float alpha, beta, ep_a, ep_g;
-    int flags;              // GEMM_SYM, GEMM_EPI_ROOT
+    int flags;              // GEMM_SYM, GEMM_EPI_ROOT, GEMM_STORE_T (fp32 output stored transposed, no beta)
     int c_terms;            // terms of Cp / Tp (1 or 2)
 };
 
@@ -58,8 +58,13 @@ constexpr unsigned PG_PAIRS_2x2 = 0x7u;          // (0,0) (0,1) (1,0): 16 bits o
 
 // WGM x WGN wavefronts of WTM x WTN MFMA tiles (32 x 32); K slabs of BK; DEPTH register sets
 // of global-load prefetch.
-template <int NTA_, int NTB_, unsigned PAIRS_, int WGM_, int WGN_, int WTM_, int WTN_, int BK_, int DEPTH_ = 1, int MODE_ = 0>
+template <int NTA_, int NTB_, unsigned PAIRS_, int WGM_, int WGN_, int WTM_, int WTN_, int BK_, int DEPTH_ = 1, int MODE_ = 0,
+          bool FA_ = false, bool FB_ = false>
 struct PgShape {
+    // FA / FB: the operand is a plain fp32 row-major matrix, split into two bf16 terms while it is
+    // staged (the LDS layout is that of a two-term split matrix); it then needs NT = 2
+    static constexpr bool FA = FA_, FB = FB_;
+    static_assert((!FA_ || NTA_ == 2) && (!FB_ || NTB_ == 2), "fp32 sources are split into two terms");
     static constexpr int NTA = NTA_, NTB = NTB_, DEPTH = DEPTH_;
     static constexpr int MODE = MODE_;                   // 0: every wavefront loads and multiplies in turn; 1: two wavefront groups alternate
     static constexpr unsigned PAIRS = PAIRS_;
@@ -114,6 +119,77 @@ __device__ __forceinline__ uint32_t pg_pack_bf16(float a, float b)
 }
 __device__ __forceinline__ float pg_bf16_round(float a) { return (float)(__bf16)a; }
 
+// Global -> register -> LDS staging of one operand's slab pieces.  Pre-split / bf16 source: one
+// 16-byte chunk per item, stored as loaded.  fp32 source: an item is 8 consecutive fp32 (two
+// 16-byte loads) and becomes one hi chunk and one lo chunk (round to nearest in both terms).
+template <class S, bool F32, int NT, int TROWS>
+struct PgLoader {
+    static constexpr int CPR = S::GPS * NT * S::CPG;      // 16-byte chunks per LDS row
+    static constexpr int ROW = CPR * 8;                    // elements per LDS row
+    static constexpr int IPR = F32 ? S::BK / 8 : CPR;      // items per row
+    static constexpr int RPV = S::NTHR / IPR;              // rows covered by one item index
+    static constexpr int NV = TROWS / RPV;
+    static constexpr int RPI = F32 ? 2 : 1;                // 16-byte registers per item
+    static constexpr int SRC_BYTES = F32 ? 4 : 2;
+    static constexpr int SLAB_BYTES = F32 ? S::BK * 4 : S::BK * NT * 2;   // bytes of one slab piece of a row
+    static_assert(S::NTHR % IPR == 0 && TROWS % RPV == 0 && RPV % 16 == 0, "loader geometry");
+    u32x4 r[S::DEPTH][NV][RPI];
+    const char *ub;      // wave-uniform base: the loads need no 64-bit vector address arithmetic
+    uint32_t vo;         // per-thread byte offset
+    size_t step;         // bytes between the rows of consecutive item indices
+    uint32_t lds_hi, lds_lo;   // element offsets of this thread's chunk(s) inside the operand's LDS block
+
+    __device__ __forceinline__ void init(const void *base, int ld, int row0, int tid)
+    {
+        const int lrow = tid / IPR, item = tid % IPR;
+        ub = reinterpret_cast<const char *>(base) + (size_t)row0 * ld * SRC_BYTES;
+        vo = ((uint32_t)lrow * (uint32_t)ld + (uint32_t)item * 8u) * SRC_BYTES;
+        step = (size_t)RPV * ld * SRC_BYTES;
+        const int sw = pg_swz<CPR>(lrow);
+        if (F32) {
+            const int g = item / S::CPG, q = item % S::CPG;          // interleave group, chunk inside a term segment
+            lds_hi = (uint32_t)(lrow * ROW + (((g * 2) * S::CPG + q) ^ sw) * 8);
+            lds_lo = (uint32_t)(lrow * ROW + (((g * 2 + 1) * S::CPG + q) ^ sw) * 8);
+        } else {
+            lds_hi = (uint32_t)(lrow * ROW + ((item ^ sw) * 8));
+            lds_lo = 0;
+        }
+    }
+    template <int SET> __device__ __forceinline__ void gload(int slab)
+    {
+        const size_t k = (size_t)slab * SLAB_BYTES;
+#pragma unroll
+        for (int v = 0; v < NV; ++v)
+#pragma unroll
+            for (int e = 0; e < RPI; ++e)
+                r[SET][v][e] = *(const ASTERIA_GLOBAL u32x4 *)(ub + (v * step + k + 16 * e) + vo);
+    }
+    template <int SET> __device__ __forceinline__ void lstore(ASTERIA_LDS uint16_t *d) const
+    {
+#pragma unroll
+        for (int v = 0; v < NV; ++v) {
+            if constexpr (F32) {
+                u32x4 hi, lo;
+#pragma unroll
+                for (int e = 0; e < 2; ++e) {
+                    const u32x4 x = r[SET][v][e];
+                    const float x0 = __uint_as_float(x[0]), x1 = __uint_as_float(x[1]);
+                    const float x2 = __uint_as_float(x[2]), x3 = __uint_as_float(x[3]);
+                    const uint32_t h0 = pg_pack_bf16(x0, x1), h1 = pg_pack_bf16(x2, x3);
+                    hi[2 * e] = h0; hi[2 * e + 1] = h1;
+                    lo[2 * e] = pg_pack_bf16(x0 - __uint_as_float(h0 << 16), x1 - __uint_as_float(h0 & 0xffff0000u));
+                    lo[2 * e + 1] = pg_pack_bf16(x2 - __uint_as_float(h1 << 16), x3 - __uint_as_float(h1 & 0xffff0000u));
+                }
+                *(ASTERIA_LDS u32x4 *)(d + lds_hi + v * RPV * ROW) = hi;
+                *(ASTERIA_LDS u32x4 *)(d + lds_lo + v * RPV * ROW) = lo;
+            } else {
+                *(ASTERIA_LDS u32x4 *)(d + lds_hi + v * RPV * ROW) = r[SET][v][0];
+            }
+        }
+    }
+};
+
+
 // offset (elements) of (row, col, term 0) in a split matrix; col is a multiple of 8
 __device__ __forceinline__ size_t pg_off(int row, int col, int ld, int nt)
 {
@@ -140,13 +216,13 @@ __device__ __forceinline__ void pg_store_split(uint16_t *base, int row, int col,
 
 // One finished row piece of 8 values at (grow, gcol .. gcol + 7): apply beta, store every
 // requested output, accumulate the residual.
-__device__ __forceinline__ void pg_emit(const PlaneProblem &P, int grow, int gcol, float (&val)[8], bool root,
-                                        float ep_a, float ep_g, float &rsum)
+__device__ __forceinline__ void pg_emit(const PlaneProblem &P, int grow, int gcol, int rlim, int clim, float (&val)[8],
+                                        bool root, float ep_a, float ep_g, float &rsum)
 {
     if (P.C32) {
-        if (grow < P.M) {
+        if (grow < rlim) {
             float *c = P.C32 + (size_t)grow * P.ldc32 + gcol;
-            const bool vec = (gcol + 8 <= P.N) && ((P.ldc32 & 3) == 0) && ((reinterpret_cast<uintptr_t>(P.C32) & 15u) == 0);
+            const bool vec = (gcol + 8 <= clim) && ((P.ldc32 & 3) == 0) && ((reinterpret_cast<uintptr_t>(P.C32) & 15u) == 0);
             if (vec) {
                 ASTERIA_GLOBAL floatx4 *c4 = (ASTERIA_GLOBAL floatx4 *)c;
                 if (P.beta != 0.0f) {
@@ -161,7 +237,7 @@ __device__ __forceinline__ void pg_emit(const PlaneProblem &P, int grow, int gco
             } else {
 #pragma unroll
                 for (int e = 0; e < 8; ++e)
-                    if (gcol + e < P.N) {
+                    if (gcol + e < clim) {
                         if (P.beta != 0.0f) val[e] += P.beta * c[e];
                         c[e] = val[e];
                     }
@@ -230,44 +306,29 @@ __global__ __launch_bounds__(S::NTHR) void pgemm_kernel(const PlaneProblem *__re
 
     // ---- K loop ---------------------------------------------------------------------------------
     {
-        // loader: thread -> (row, 16-byte chunk) of the operand's slab piece, the same for every vector index
-        const int lrowA = tid / S::CPR_A, lvecA = tid % S::CPR_A;
-        const int lrowB = tid / S::CPR_B, lvecB = tid % S::CPR_B;
-        // global addresses = wave-uniform base (scalar registers) + 32-bit per-thread byte offset:
-        // the loads then need no 64-bit vector address arithmetic (which would recycle registers
-        // that are still targets of loads in flight and serialise them)
-        const char *ubA = reinterpret_cast<const char *>(P.A + (size_t)row0 * P.lda);
-        const char *ubB = reinterpret_cast<const char *>(P.B + (size_t)col0 * P.ldb);
-        const uint32_t voA = ((uint32_t)lrowA * (uint32_t)P.lda + (uint32_t)lvecA * 8u) * 2u;
-        const uint32_t voB = ((uint32_t)lrowB * (uint32_t)P.ldb + (uint32_t)lvecB * 8u) * 2u;
-        const size_t stepA = (size_t)S::RPV_A * P.lda * 2, stepB = (size_t)S::RPV_B * P.ldb * 2;   // bytes
-        const uint32_t lds_sa = (uint32_t)(lrowA * S::ROW_A + ((lvecA ^ pg_swz<S::CPR_A>(lrowA)) * 8));
-        const uint32_t lds_sb = (uint32_t)(TM * S::ROW_A + lrowB * S::ROW_B + ((lvecB ^ pg_swz<S::CPR_B>(lrowB)) * 8));
+        PgLoader<S, S::FA, NTA, TM> la;
+        PgLoader<S, S::FB, NTB, TN> lb;
+        la.init(P.A, P.lda, row0, tid);
+        lb.init(P.B, P.ldb, col0, tid);
         // fragments: lane (r, h) takes k = 8 h .. 8 h + 7 of k-step s, i.e. chunk (s / 2) * NT * 4 + t * 4 + (s % 2) * 2 + h
         const uint32_t lds_fa = (uint32_t)((wm * WTM * 32 + r) * S::ROW_A);
         const uint32_t lds_fb = (uint32_t)(TM * S::ROW_A + (wn * WTN * 32 + r) * S::ROW_B);
         const int swa = pg_swz<S::CPR_A>(r), swb = pg_swz<S::CPR_B>(r);
         constexpr int DEPTH = S::DEPTH;
-        u32x4 ra[DEPTH][S::NVA], rb[DEPTH][S::NVB];
         const int nk = (P.K + BK - 1) / BK;
 
         // DEPTH register sets: slab j waits in set j % DEPTH from its global load until it is
         // stored to LDS one iteration before use.
         auto gload = [&](auto setc, int slab) {
             constexpr int set = decltype(setc)::value;
-            const size_t ka = (size_t)slab * (BK * NTA * 2), kb = (size_t)slab * (BK * NTB * 2);   // bytes
-#pragma unroll
-            for (int v = 0; v < S::NVA; ++v) ra[set][v] = *(const ASTERIA_GLOBAL u32x4 *)(ubA + (v * stepA + ka) + voA);
-#pragma unroll
-            for (int v = 0; v < S::NVB; ++v) rb[set][v] = *(const ASTERIA_GLOBAL u32x4 *)(ubB + (v * stepB + kb) + voB);
+            la.template gload<set>(slab);
+            lb.template gload<set>(slab);
         };
         auto lstore = [&](auto setc, int stage) {
             constexpr int set = decltype(setc)::value;
             ASTERIA_LDS uint16_t *d = smem + stage * S::STAGE;
-#pragma unroll
-            for (int v = 0; v < S::NVA; ++v) *(ASTERIA_LDS u32x4 *)(d + lds_sa + v * S::RPV_A * S::ROW_A) = ra[set][v];
-#pragma unroll
-            for (int v = 0; v < S::NVB; ++v) *(ASTERIA_LDS u32x4 *)(d + lds_sb + v * S::RPV_B * S::ROW_B) = rb[set][v];
+            la.template lstore<set>(d);
+            lb.template lstore<set>(d + TM * S::ROW_A);
         };
         auto compute = [&](int cur) {
             const ASTERIA_LDS uint16_t *fa = smem + cur * S::STAGE + lds_fa;
@@ -416,10 +477,11 @@ __global__ __launch_bounds__(S::NTHR) void pgemm_kernel(const PlaneProblem *__re
         if (sym && gi < gj) continue;
         const bool diag = sym && gi == gj;
         const bool mirror = sym && gi > gj;
+        const bool store_t = !sym && (P.flags & GEMM_STORE_T) != 0;   // only the transposed image is stored
         // does this wavefront own part of the quadrant?
         const int wr0 = wm * WROWS - qi * 128, wc0 = wn * WCOLS - qj * 128;   // sub-tile origin relative to the quadrant
         const bool owns = wr0 < 128 && wr0 + WROWS > 0 && wc0 < 128 && wc0 + WCOLS > 0;
-        for (int pass = 0; pass < (mirror ? 2 : 1); ++pass) {
+        for (int pass = store_t ? 1 : 0; pass < ((mirror || store_t) ? 2 : 1); ++pass) {
             if (owns) {
 #pragma unroll
                 for (int i = 0; i < WTM; ++i) {
@@ -466,7 +528,7 @@ __global__ __launch_bounds__(S::NTHR) void pgemm_kernel(const PlaneProblem *__re
 #pragma unroll
                     for (int e = 0; e < 4; ++e) { val[e] = v0[e]; val[4 + e] = v1[e]; }
                 }
-                pg_emit(P, orow0 + lr, ocol0 + lc, val, root, ep_a, ep_g, rsum);
+                pg_emit(P, orow0 + lr, ocol0 + lc, pass == 0 ? P.M : P.N, pass == 0 ? P.N : P.M, val, root, ep_a, ep_g, rsum);
             }
             __syncthreads();
         }
@@ -488,6 +550,18 @@ __global__ __launch_bounds__(S::NTHR) void pgemm_kernel(const PlaneProblem *__re
             P.partial[lt] = t;
         }
     }
+}
+
+// 256 x 256 tiles, 8 wavefronts in two alternating groups, both operands plain fp32 matrices split
+// into two bf16 terms while staged: the non-symmetric products of the precondition and of the SOAP
+// rotations whose shapes fill whole tiles
+using PgF32x2 = PgShape<2, 2, PG_PAIRS_2x2, 2, 4, 4, 2, 32, 1, 1, true, true>;
+
+// a plain fp32 matrix can feed PgF32x2: 16-byte aligned rows, whole tiles and slabs
+inline bool pg_f32_operand_ok(const void *p, int rows, int k, int ld)
+{
+    return (reinterpret_cast<uintptr_t>(p) & 15u) == 0 && (ld % 4) == 0 && (rows % PgF32x2::TM) == 0 &&
+           (k % PgF32x2::BK) == 0;
 }
 
 inline int pg_tri_tiles(int n, int tile)

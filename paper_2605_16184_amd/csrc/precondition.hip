@@ -6,13 +6,15 @@
 //   bf16 gradients (the training case): bf16 matrix cores with the fp32 operands split into
 //     hi + lo bf16 terms on the fly (about 16 bits kept):
 //       U^T = X_R G^T   (X_R split, G exact: 2 MFMA passes; both operands k-contiguous)
-//       P   = X_L U     (X_L and U^T split: 3 MFMA passes; both operands k-contiguous)
+//       P   = X_L U     (X_L and U^T split: 3 MFMA passes; both operands k-contiguous); blocks whose
+//                       shapes fill whole 256 x 256 tiles take the 8-wavefront kernel of pgemm.h
 //   fp32 gradients: fp32 matrix cores,  U = G X_R  then  P = X_L U  (U read k-major).
 #include <vector>
 
 #include "common.h"
 #include "gemm.h"
 #include "gemm_bf16.h"
+#include "pgemm.h"
 
 using namespace asteria;
 
@@ -33,7 +35,10 @@ asteria_status validate(const asteria_pblock *b, int nblocks)
     return ASTERIA_OK;
 }
 
-size_t table_bytes(int nblocks) { return 2 * Carver::need((size_t)nblocks, sizeof(GemmProblem)) + 512; }
+size_t table_bytes(int nblocks)
+{
+    return 2 * Carver::need((size_t)nblocks, sizeof(GemmProblem)) + Carver::need((size_t)nblocks, sizeof(PlaneProblem)) + 512;
+}
 
 }  // namespace
 
@@ -61,6 +66,9 @@ extern "C" asteria_status asteria_precondition(const asteria_pblock *blocks, int
     Carver cv(ws);
     GemmProblem *d1 = cv.take<GemmProblem>(nblocks);
     GemmProblem *d2 = cv.take<GemmProblem>(nblocks);
+    PlaneProblem *d2f = cv.take<PlaneProblem>(nblocks);
+    std::vector<PlaneProblem> p2f;       // second product of bf16 blocks that fill whole 256 x 256 tiles
+    int tiles2f = 0;
     // problems are grouped by gradient dtype: one launch per stage and dtype
     std::vector<GemmProblem> p1[2], p2[2];
     int tiles1[2] = {0, 0}, tiles2[2] = {0, 0};
@@ -82,10 +90,22 @@ extern "C" asteria_status asteria_precondition(const asteria_pblock *blocks, int
             p1[d].push_back(p);
             // P = X_L U : rows of X_L against rows of U^T, contraction over m
             p.M = k.m; p.N = k.n; p.K = k.m; p.tiles_n = tn;
-            p.A = k.XL; p.lda = k.ldxl; p.B = Ut; p.ldb = ldu; p.C = k.P; p.ldc = k.ldp;
-            p.flags = (k.p_dtype == ASTERIA_BF16) ? GEMM_C_BF16 : 0;
-            p.tile_start = tiles2[d]; tiles2[d] += tm * tn;
-            p2[d].push_back(p);
+            if (k.p_dtype == ASTERIA_F32 && pg_f32_operand_ok(k.XL, k.m, k.m, k.ldxl) && pg_f32_operand_ok(Ut, k.n, k.m, ldu)) {
+                PlaneProblem q;
+                memset(&q, 0, sizeof(q));
+                q.A = k.XL; q.lda = k.ldxl; q.B = Ut; q.ldb = ldu;
+                q.C32 = reinterpret_cast<float *>(k.P); q.ldc32 = k.ldp;
+                q.M = k.m; q.N = k.n; q.K = k.m;
+                q.tiles_n = k.n / PgF32x2::TN;
+                q.tile_start = tiles2f; tiles2f += (k.m / PgF32x2::TM) * q.tiles_n;
+                q.state_idx = -1; q.state_mask = ~0; q.alpha = 1.0f; q.beta = 0.0f; q.c_terms = 1;
+                p2f.push_back(q);
+            } else {
+                p.A = k.XL; p.lda = k.ldxl; p.B = Ut; p.ldb = ldu; p.C = k.P; p.ldc = k.ldp;
+                p.flags = (k.p_dtype == ASTERIA_BF16) ? GEMM_C_BF16 : 0;
+                p.tile_start = tiles2[d]; tiles2[d] += tm * tn;
+                p2[d].push_back(p);
+            }
         } else {
             const int ldu = ld4(k.n);
             float *U = cv.take<float>((size_t)k.m * ldu);
@@ -112,7 +132,12 @@ extern "C" asteria_status asteria_precondition(const asteria_pblock *blocks, int
     }
     if (!p1[1].empty()) {
         ASTERIA_HIP_TRY((launch_gemm_bf16_grouped<float, bf16_t, 2, 1>(d1b, (int)p1[1].size(), tiles1[1], nullptr, stream)));
-        ASTERIA_HIP_TRY((launch_gemm_bf16_grouped<float, float, 2, 2>(d2b, (int)p2[1].size(), tiles2[1], nullptr, stream)));
+        if (!p2[1].empty())
+            ASTERIA_HIP_TRY((launch_gemm_bf16_grouped<float, float, 2, 2>(d2b, (int)p2[1].size(), tiles2[1], nullptr, stream)));
+        if (!p2f.empty()) {
+            ASTERIA_HIP_TRY(upload_async(d2f, p2f.data(), p2f.size() * sizeof(PlaneProblem), stream));
+            ASTERIA_HIP_TRY((launch_pgemm<PgF32x2>(d2f, (int)p2f.size(), tiles2f, nullptr, stream, 513)));
+        }
     }
     return ASTERIA_OK;
 }

@@ -7,7 +7,8 @@
 //              two when G is bf16): a plain bf16 cast of an eigenbasis costs 0.1-0.5 relative error
 //              in N, the split about 1e-5.  That kernel reads k-contiguous operands only, so the
 //              call first writes Q_L^T and Q_R^T to the workspace, and the first product of each
-//              rotation stores its result transposed.
+//              rotation stores its result transposed.  Blocks whose shapes fill whole 256 x 256
+//              tiles run the three split x split products on the 8-wavefront kernel of pgemm.h.
 // soap_refresh: Z^T = Q^T A by one grouped GEMM (columns of Z become contiguous rows), then the
 //              thin QR factor of Z with diag(R) > 0 - the same Q a Householder QR with that sign
 //              convention returns, since the factorisation is unique - by block Gram-Schmidt
@@ -26,6 +27,7 @@
 #include "common.h"
 #include "gemm.h"
 #include "gemm_bf16.h"
+#include "pgemm.h"
 
 using namespace asteria;
 
@@ -230,7 +232,8 @@ extern "C" size_t asteria_soap_step_workspace_bytes(const asteria_sblock *blocks
 {
     if (!blocks || nblocks <= 0) return 0;
     size_t bytes = 4 * Carver::need((size_t)nblocks, sizeof(GemmProblem)) + Carver::need((size_t)nblocks, sizeof(AdamBlock)) +
-                   Carver::need(2 * (size_t)nblocks, sizeof(TransposeF32Job)) + 2048;
+                   Carver::need(2 * (size_t)nblocks, sizeof(TransposeF32Job)) +
+                   3 * Carver::need((size_t)nblocks, sizeof(PlaneProblem)) + 2048;
     for (int i = 0; i < nblocks; ++i) {
         const int m = blocks[i].m, n = blocks[i].n;
         bytes += 2 * Carver::need((size_t)m * ld4(n), sizeof(float));      // G' / N' (m x n)
@@ -256,6 +259,10 @@ extern "C" asteria_status asteria_soap_step(const asteria_sblock *blocks, int nb
     for (int i = 0; i < 4; ++i) d_g[i] = cv.take<GemmProblem>(nblocks);
     AdamBlock *d_ab = cv.take<AdamBlock>(nblocks);
     TransposeF32Job *d_tj = cv.take<TransposeF32Job>(2 * (size_t)nblocks);
+    PlaneProblem *d_f[3];
+    for (int i = 0; i < 3; ++i) d_f[i] = cv.take<PlaneProblem>(nblocks);
+    std::vector<PlaneProblem> f2, f3, f4;   // products 2-4 of blocks that fill whole 256 x 256 tiles
+    int tilesf = 0;
     std::vector<GemmProblem> g1[2], g2, g3, g4;
     std::vector<AdamBlock> ab;
     std::vector<TransposeF32Job> tj;
@@ -285,17 +292,34 @@ extern "C" asteria_status asteria_soap_step(const asteria_sblock *blocks, int nb
         p.A = k.G; p.lda = k.ldg; p.B = QRt; p.ldb = ldqrt; p.C = Tt; p.ldc = ldt; p.flags = GEMM_STORE_T;
         p.tile_start = tiles1[k.g_dtype]; tiles1[k.g_dtype] += tm * tn;
         g1[k.g_dtype].push_back(p);
-        // 2: G' = Q_L^T (G Q_R):   A' = Q_L^T (m x m), B' = (G Q_R)^T (n x m)
-        p.K = k.m; p.A = QLt; p.lda = ldqlt; p.B = Tt; p.ldb = ldt; p.C = Gr; p.ldc = ldw; p.flags = 0;
-        p.tile_start = tiles;
-        g2.push_back(p);
-        // 3: (N' Q_R^T)^T:   A' = N' (m x n), B' = Q_R (B'(j, k) = Q_R[j][k]); stored transposed
-        p.K = k.n; p.A = Np; p.lda = ldw; p.B = k.QR; p.ldb = k.ldqr; p.C = Tt; p.ldc = ldt; p.flags = GEMM_STORE_T;
-        g3.push_back(p);
-        // 4: N = Q_L (N' Q_R^T):   A' = Q_L (m x m), B' = (N' Q_R^T)^T (n x m)
-        p.K = k.m; p.A = k.QL; p.lda = k.ldql; p.B = Tt; p.ldb = ldt; p.C = k.N; p.ldc = k.ldn; p.flags = 0;
-        g4.push_back(p);
-        tiles += tm * tn;
+        const bool fast = pg_f32_operand_ok(QLt, k.m, k.m, ldqlt) && pg_f32_operand_ok(Tt, k.n, k.m, ldt) &&
+                          pg_f32_operand_ok(Np, k.m, k.n, ldw) && pg_f32_operand_ok(k.QR, k.n, k.n, k.ldqr) &&
+                          pg_f32_operand_ok(k.QL, k.m, k.m, k.ldql);
+        if (fast) {
+            PlaneProblem q;
+            memset(&q, 0, sizeof(q));
+            q.M = k.m; q.N = k.n; q.tiles_n = k.n / PgF32x2::TN; q.tile_start = tilesf;
+            q.state_idx = -1; q.state_mask = ~0; q.alpha = 1.0f; q.beta = 0.0f; q.c_terms = 1;
+            q.K = k.m; q.A = QLt; q.lda = ldqlt; q.B = Tt; q.ldb = ldt; q.C32 = Gr; q.ldc32 = ldw; q.flags = 0;
+            f2.push_back(q);
+            q.K = k.n; q.A = Np; q.lda = ldw; q.B = k.QR; q.ldb = k.ldqr; q.C32 = Tt; q.ldc32 = ldt; q.flags = GEMM_STORE_T;
+            f3.push_back(q);
+            q.K = k.m; q.A = k.QL; q.lda = k.ldql; q.B = Tt; q.ldb = ldt; q.C32 = k.N; q.ldc32 = k.ldn; q.flags = 0;
+            f4.push_back(q);
+            tilesf += (k.m / PgF32x2::TM) * q.tiles_n;
+        } else {
+            // 2: G' = Q_L^T (G Q_R):   A' = Q_L^T (m x m), B' = (G Q_R)^T (n x m)
+            p.K = k.m; p.A = QLt; p.lda = ldqlt; p.B = Tt; p.ldb = ldt; p.C = Gr; p.ldc = ldw; p.flags = 0;
+            p.tile_start = tiles;
+            g2.push_back(p);
+            // 3: (N' Q_R^T)^T:   A' = N' (m x n), B' = Q_R (B'(j, k) = Q_R[j][k]); stored transposed
+            p.K = k.n; p.A = Np; p.lda = ldw; p.B = k.QR; p.ldb = k.ldqr; p.C = Tt; p.ldc = ldt; p.flags = GEMM_STORE_T;
+            g3.push_back(p);
+            // 4: N = Q_L (N' Q_R^T):   A' = Q_L (m x m), B' = (N' Q_R^T)^T (n x m)
+            p.K = k.m; p.A = k.QL; p.lda = k.ldql; p.B = Tt; p.ldb = ldt; p.C = k.N; p.ldc = k.ldn; p.flags = 0;
+            g4.push_back(p);
+            tiles += tm * tn;
+        }
         AdamBlock a;
         a.Gr = Gr; a.M = k.M; a.V = k.V; a.Np = Np; a.m = k.m; a.n = k.n; a.ldw = ldw; a.ldm = k.ldm; a.ldv = k.ldv;
         a.row_start = rows; rows += k.m;
@@ -305,9 +329,16 @@ extern "C" asteria_status asteria_soap_step(const asteria_sblock *blocks, int nb
     GemmProblem *d_g1b = d_g[0] + g1[0].size();
     if (!g1[0].empty()) ASTERIA_HIP_TRY(upload_async(d_g[0], g1[0].data(), g1[0].size() * sizeof(GemmProblem), stream));
     if (!g1[1].empty()) ASTERIA_HIP_TRY(upload_async(d_g1b, g1[1].data(), g1[1].size() * sizeof(GemmProblem), stream));
-    ASTERIA_HIP_TRY(upload_async(d_g[1], g2.data(), g2.size() * sizeof(GemmProblem), stream));
-    ASTERIA_HIP_TRY(upload_async(d_g[2], g3.data(), g3.size() * sizeof(GemmProblem), stream));
-    ASTERIA_HIP_TRY(upload_async(d_g[3], g4.data(), g4.size() * sizeof(GemmProblem), stream));
+    if (!g2.empty()) {
+        ASTERIA_HIP_TRY(upload_async(d_g[1], g2.data(), g2.size() * sizeof(GemmProblem), stream));
+        ASTERIA_HIP_TRY(upload_async(d_g[2], g3.data(), g3.size() * sizeof(GemmProblem), stream));
+        ASTERIA_HIP_TRY(upload_async(d_g[3], g4.data(), g4.size() * sizeof(GemmProblem), stream));
+    }
+    if (!f2.empty()) {
+        ASTERIA_HIP_TRY(upload_async(d_f[0], f2.data(), f2.size() * sizeof(PlaneProblem), stream));
+        ASTERIA_HIP_TRY(upload_async(d_f[1], f3.data(), f3.size() * sizeof(PlaneProblem), stream));
+        ASTERIA_HIP_TRY(upload_async(d_f[2], f4.data(), f4.size() * sizeof(PlaneProblem), stream));
+    }
     ASTERIA_HIP_TRY(upload_async(d_ab, ab.data(), ab.size() * sizeof(AdamBlock), stream));
     ASTERIA_HIP_TRY(upload_async(d_tj, tj.data(), tj.size() * sizeof(TransposeF32Job), stream));
 
@@ -317,13 +348,16 @@ extern "C" asteria_status asteria_soap_step(const asteria_sblock *blocks, int nb
         ASTERIA_HIP_TRY((launch_gemm_bf16_grouped<float, float, 2, 2>(d_g[0], (int)g1[0].size(), tiles1[0], nullptr, stream)));
     if (!g1[1].empty())
         ASTERIA_HIP_TRY((launch_gemm_bf16_grouped<bf16_t, float, 1, 2>(d_g1b, (int)g1[1].size(), tiles1[1], nullptr, stream)));
-    ASTERIA_HIP_TRY((launch_gemm_bf16_grouped<float, float, 2, 2>(d_g[1], nblocks, tiles, nullptr, stream)));
+    if (!g2.empty()) ASTERIA_HIP_TRY((launch_gemm_bf16_grouped<float, float, 2, 2>(d_g[1], (int)g2.size(), tiles, nullptr, stream)));
+    if (!f2.empty()) ASTERIA_HIP_TRY((launch_pgemm<PgF32x2>(d_f[0], (int)f2.size(), tilesf, nullptr, stream, 513)));
     const float c1 = 1.0f - powf(beta1, (float)step_t), c2 = 1.0f - powf(beta2, (float)step_t);
     hipLaunchKernelGGL(adam_rotated_kernel, dim3(rows), dim3(256), 0, stream, d_ab, nblocks, beta1, beta2,
                        adam_eps, 1.0f / c1, 1.0f / c2);
     ASTERIA_HIP_TRY(hipGetLastError());
-    ASTERIA_HIP_TRY((launch_gemm_bf16_grouped<float, float, 2, 2>(d_g[2], nblocks, tiles, nullptr, stream)));
-    ASTERIA_HIP_TRY((launch_gemm_bf16_grouped<float, float, 2, 2>(d_g[3], nblocks, tiles, nullptr, stream)));
+    if (!g2.empty()) ASTERIA_HIP_TRY((launch_gemm_bf16_grouped<float, float, 2, 2>(d_g[2], (int)g3.size(), tiles, nullptr, stream)));
+    if (!f2.empty()) ASTERIA_HIP_TRY((launch_pgemm<PgF32x2>(d_f[1], (int)f3.size(), tilesf, nullptr, stream, 513)));
+    if (!g2.empty()) ASTERIA_HIP_TRY((launch_gemm_bf16_grouped<float, float, 2, 2>(d_g[3], (int)g4.size(), tiles, nullptr, stream)));
+    if (!f2.empty()) ASTERIA_HIP_TRY((launch_pgemm<PgF32x2>(d_f[2], (int)f4.size(), tilesf, nullptr, stream, 513)));
     return ASTERIA_OK;
 }
 

@@ -322,6 +322,25 @@ def test_precondition_ragged_batch_fp32_and_bf16_outputs():
         assert torch.all(P._base[:, P.shape[1]:] == -777.0)
 
 
+def test_precondition_whole_tile_blocks_mixed_with_ragged_ones():
+    # blocks whose shapes fill whole 256 x 256 tiles take another kernel for the second product than
+    # the ragged block in the same call
+    shapes = [(256, 512, torch.bfloat16), (200, 328, torch.bfloat16), (512, 256, torch.bfloat16), (256, 256, torch.bfloat16)]
+    items, refs = [], []
+    for i, (m, n, gdt) in enumerate(shapes):
+        G = W.gaussian_block(m, n, 0.01, DEV, 7, i, dtype=gdt)
+        XL, XR = spd(m, 8, i), spd(n, 9, i)
+        P = padded(m, n, 4 if i % 2 == 0 else 1, torch.float32)   # 16-byte rows, and rows that are not
+        refs.append(oracle.precondition(np64(XL), np64(G), np64(XR)))
+        items.append((XL, G, XR, P))
+    ast.precondition(items)
+    torch.cuda.synchronize()
+    for (XL, G, XR, P), Po in zip(items, refs):
+        print("precondition whole tiles", tuple(G.shape), relF(P, Po))
+        assert relF(P, Po) <= 1e-4, relF(P, Po)
+        assert torch.all(P._base[:, P.shape[1]:] == -777.0)
+
+
 def test_precondition_full_size_1024_with_gpu_roots():
     n = 1024
     G = W.powerlaw_blocks([(n, n)], DEV)[0]
@@ -422,6 +441,35 @@ def test_soap_step_same_basis_parity_over_three_steps():
             No, Mo, Vo = oracle.soap_step(np64(Gs[i]), np64(QL), np64(QR), Min[i], Vin[i], 0.9, 0.95, 1e-8, t)
             # the rotations keep 16 bits of Q_L, Q_R and of the intermediate product (two bf16 terms
             # each): the rotated gradient, and with it the moments, carry a few 2^-16 of relative error
+            assert relF(M, Mo) <= 2e-4 and relF(V, Vo) <= 2e-4
+            assert relF(N, No) <= TOL_PRECOND, (t, i, relF(N, No))
+            assert torch.all(N._base[:, N.shape[1]:] == -777.0)
+
+
+def test_soap_step_whole_tile_blocks_mixed_with_ragged_ones():
+    # whole 256 x 256 tiles: the three split x split products of each rotation pair run on the
+    # 8-wavefront kernel (one of them storing transposed); the ragged block keeps the other path
+    shapes = [(256, 512, torch.float32), (200, 328, torch.bfloat16), (512, 256, torch.bfloat16), (256, 256, torch.bfloat16)]
+    state = []
+    for i, (m, n, dt) in enumerate(shapes):
+        QL, QR = W.haar(m, DEV, 180 + i), W.haar(n, DEV, 190 + i)
+        M = torch.zeros(m, n, device=DEV); V = torch.zeros(m, n, device=DEV); N = padded(m, n, 4 if i != 3 else 1)
+        state.append((QL, QR, M, V, N))
+    for t in (1, 2):
+        items, Gs = [], []
+        for i, (m, n, dt) in enumerate(shapes):
+            QL, QR, M, V, N = state[i]
+            U, Vb = W.haar(m, DEV, 200 + i), W.haar(n, DEV, 210 + i)
+            G = W.soap_gradient(U, Vb, t, DEV, i, dtype=dt)
+            Gs.append(G)
+            items.append((G, QL, QR, M, V, N))
+        Min = [np64(s[2]) for s in state]; Vin = [np64(s[3]) for s in state]
+        ast.soap_step(items, 0.9, 0.95, 1e-8, t)
+        torch.cuda.synchronize()
+        for i in range(len(shapes)):
+            QL, QR, M, V, N = state[i]
+            No, Mo, Vo = oracle.soap_step(np64(Gs[i]), np64(QL), np64(QR), Min[i], Vin[i], 0.9, 0.95, 1e-8, t)
+            print("soap step whole tiles", shapes[i], t, relF(M, Mo), relF(V, Vo), relF(N, No))
             assert relF(M, Mo) <= 2e-4 and relF(V, Vo) <= 2e-4
             assert relF(N, No) <= TOL_PRECOND, (t, i, relF(N, No))
             assert torch.all(N._base[:, N.shape[1]:] == -777.0)
