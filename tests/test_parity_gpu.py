@@ -375,6 +375,57 @@ def test_end_to_end_single_block_config_against_the_float64_pipeline():
     assert abs(float(XL.diagonal().mean()) - 0.95 ** -2) < 0.01
 
 
+def test_full_model_batch_in_the_timed_launch_configuration_sampled_against_the_oracle():
+    # the headline workload exactly as the benchmark launches it: all 1184 blocks / 2368 factors of
+    # the 1.1B model in one call per stage on one shared workspace; a sample of blocks that covers
+    # every block shape and both ends of the batch is checked stage by stage against the oracle
+    shapes = W.block_shapes(W.llama_1b_matrices(), 1024)
+    nb = len(shapes)
+    Gs = W.powerlaw_blocks(shapes, DEV)
+    Ls = [torch.zeros(m, m, device=DEV) for m, n in shapes]
+    Rs = [torch.zeros(n, n, device=DEV) for m, n in shapes]
+    XLs = [torch.empty(m, m, device=DEV) for m, n in shapes]
+    XRs = [torch.empty(n, n, device=DEV) for m, n in shapes]
+    Ps = [torch.empty(m, n, device=DEV) for m, n in shapes]
+    blocks = ast.Blocks(list(zip(Gs, Ls, Rs)))
+    factors = ast.Factors([(L, X) for L, X in zip(Ls, XLs)] + [(R, X) for R, X in zip(Rs, XRs)])
+    pblocks = ast.PBlocks(list(zip(XLs, Gs, XRs, Ps)))
+    full, mn = ast.inverse_root_workspace_bytes(factors, None)
+    ws_bytes = int(max(min(full, 96 * 2**30), mn, ast.precondition_workspace_bytes(pblocks),
+                       ast.stats_update_workspace_bytes(blocks)))
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=DEV)
+    info = torch.full((2 * nb,), -1, dtype=torch.int32, device=DEV)
+    ast.stats_update(blocks, 0.95, ws=ws)
+    ast.inverse_root(factors, 1e-6, relative=True, root=4, info=info, ws=ws)
+    ast.precondition(pblocks, ws=ws)
+    torch.cuda.synchronize()
+    assert np.all(info.cpu().numpy() == B.INFO_OK)
+
+    # first and last block of every shape; the oracle's eigensolver sets the cost (about 1.5 min for
+    # n = 1024), so roots are checked on the small side of each sampled block, plus one 1024 factor
+    # from each end of the batch
+    sample = {}
+    for i, sh in enumerate(shapes):
+        sample.setdefault(sh, [i, i])[1] = i
+    picks = sorted({i for pair in sample.values() for i in pair})
+    root_jobs = []          # (GPU statistic, GPU root)
+    for i in picks:
+        m, n = shapes[i]
+        Lo, Ro = oracle.stats_update(np64(Gs[i]), np.zeros((m, m)), np.zeros((n, n)), 0.95)
+        assert relF(Ls[i], Lo) <= TOL_STATS and relF(Rs[i], Ro) <= TOL_STATS, (i, shapes[i])
+        Po = oracle.precondition(np64(XLs[i]), np64(Gs[i]), np64(XRs[i]))
+        assert relF(Ps[i], Po) <= 1e-4, (i, shapes[i], relF(Ps[i], Po))
+        if min(m, n) < 1024:
+            root_jobs.append((Ls[i], XLs[i]) if m <= n else (Rs[i], XRs[i]))
+    root_jobs.append((Ls[picks[0]], XLs[picks[0]]))
+    root_jobs.append((Rs[picks[-1]], XRs[picks[-1]]))
+    Xo, _, status = oracle.inverse_root_batch([np64(A) for A, _ in root_jobs], 1e-6)
+    assert np.all(status == oracle.OK)
+    errs = [relF(X, Xo[j]) for j, (_, X) in enumerate(root_jobs)]
+    print("full model: sampled blocks", [(i, shapes[i]) for i in picks], "root relF", errs)
+    assert max(errs) <= TOL_ROOT, errs
+
+
 # =============================================================================== a4 SOAP refresh
 
 @pytest.mark.parametrize("n", [64, 200, 320])
