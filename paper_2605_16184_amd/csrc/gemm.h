@@ -272,7 +272,13 @@ template <> __device__ __forceinline__ void store_c<double>(void *C, size_t off,
 
 // K loop of one 128 x 128 tile: two LDS stages, the next slab is fetched into registers while
 // the current one feeds the matrix cores.
-template <typename TC, typename TA, typename TB, bool AKM, bool BKM, bool GUARD>
+// TRI selects which MFMA blocks (i, j) of the wavefront's sub-tile are multiplied: TRI_ALL all,
+// TRI_NONE none (the wavefront still stages its share of the operands), any other value d the
+// blocks with j - i <= d.  In a diagonal tile of a symmetric product the blocks wholly above the
+// diagonal are never stored; for the wavefront at (wm, wn) those are the blocks with
+// j - i > d = (wm WROWS - wn WCOLS) / T.
+constexpr int TRI_ALL = 1000, TRI_NONE = -1000;
+template <typename TC, typename TA, typename TB, bool AKM, bool BKM, bool GUARD, int TRI = TRI_ALL>
 __device__ __forceinline__ void gemm_mainloop(typename Mma<TC>::acc_t (&acc)[Mma<TC>::WTM][Mma<TC>::WTN],
                                               const TA *Ab, const TB *Bb, int lda, int ldb, int row0, int col0,
                                               int rowsA, int rowsB, int K, bool vecA, bool vecB,
@@ -308,7 +314,7 @@ __device__ __forceinline__ void gemm_mainloop(typename Mma<TC>::acc_t (&acc)[Mma
         const ASTERIA_LDS TC *bs = smemB + cur * StB::LDS_ELEMS;
         // lane group h consumes k = h * KPL .. h * KPL + KPL - 1 of the slab, the same for A and B
 #pragma unroll
-        for (int q = 0; q < MM::KPL / MM::CH; ++q) {
+        for (int q = 0; q < (TRI == TRI_NONE ? 0 : MM::KPL / MM::CH); ++q) {
             TC af[WTM][MM::CH], bf[WTN][MM::CH];
             const int kk = h * MM::KPL + q * MM::CH;
 #pragma unroll
@@ -338,7 +344,8 @@ __device__ __forceinline__ void gemm_mainloop(typename Mma<TC>::acc_t (&acc)[Mma
 #pragma unroll
                 for (int i = 0; i < WTM; ++i)
 #pragma unroll
-                    for (int j = 0; j < WTN; ++j) acc[i][j] = MM::mma(af[i][e], bf[j][e], acc[i][j]);
+                    for (int j = 0; j < WTN; ++j)
+                        if (TRI == TRI_ALL || j - i <= TRI) acc[i][j] = MM::mma(af[i][e], bf[j][e], acc[i][j]);
         }
         if (kt + 1 < nk) {
             sa.store(smem + (cur ^ 1) * StA::LDS_ELEMS, tid);
@@ -473,6 +480,65 @@ __device__ __forceinline__ void gemm_epilogue(const GemmProblem &P, typename MM:
     }
 }
 
+// In a diagonal tile of a symmetric product a wavefront multiplies only the blocks of its sub-tile
+// that reach the diagonal or lie below it, so the positions of the wavefront grid carry unequal
+// work.  Wavefronts w and w + 4 of a workgroup share a SIMD: with 8 wavefronts the positions are
+// handed out so that each SIMD gets one of the four heaviest and, in reverse order, one of the four
+// lightest.  role(w) is the grid position (wm WAVES_N + wn) wavefront w takes in such a tile.
+template <class MM>
+struct DiagRoles {
+    static constexpr int NW = MM::WAVES_M * MM::WAVES_N;
+    static constexpr int kept(int pos)
+    {
+        const int d = (pos / MM::WAVES_N) * MM::WTM - (pos % MM::WAVES_N) * MM::WTN;
+        int c = 0;
+        for (int i = 0; i < MM::WTM; ++i)
+            for (int j = 0; j < MM::WTN; ++j)
+                if (j - i <= d) ++c;
+        return c;
+    }
+    static constexpr uint64_t packed()
+    {
+        int order[NW] = {};
+        for (int w = 0; w < NW; ++w) order[w] = w;
+        for (int a = 0; a < NW; ++a)              // stable selection sort, heaviest first
+            for (int b = a + 1; b < NW; ++b)
+                if (kept(order[b]) > kept(order[a])) {
+                    const int t = order[b];
+                    for (int c = b; c > a; --c) order[c] = order[c - 1];
+                    order[a] = t;
+                }
+        uint64_t p = 0;
+        for (int w = 0; w < NW; ++w) {
+            int pos = w;
+            if (NW == 8) pos = (w < 4) ? order[w] : order[NW - 1 - (w - 4)];
+            p |= (uint64_t)pos << (4 * w);
+        }
+        return p;
+    }
+    static_assert(NW <= 16, "4 bits per wavefront");
+    __device__ static __forceinline__ int role(int w)
+    {
+        constexpr uint64_t P = packed();
+        return (int)((P >> (4 * w)) & 15u);
+    }
+};
+
+// calls run(integral_constant<d>) for the value D in [LO, HI] equal to d; only values that a
+// wavefront grid with steps SM, SN can produce (combinations i SM - j SN) get an instance
+constexpr int tri_gcd(int a, int b) { return b == 0 ? a : tri_gcd(b, a % b); }
+template <int D, int HI, int SM, int SN, class F>
+__device__ __forceinline__ void tri_try(int d, bool &ran, F &run)
+{
+    if constexpr (D <= HI) {
+        constexpr int G = tri_gcd(SM, SN);
+        if constexpr ((D % G + G) % G == 0) {
+            if (!ran && d == D) { run(std::integral_constant<int, D>{}); ran = true; }
+        }
+        tri_try<D + 1, HI, SM, SN>(d, ran, run);
+    }
+}
+
 // ---- the kernel -------------------------------------------------------------------------------
 template <typename TC, typename TA, typename TB, bool AKM, bool BKM>
 __global__ __launch_bounds__(Mma<TC>::NTHR) void gemm_grouped_kernel(const GemmProblem *__restrict__ probs,
@@ -524,7 +590,12 @@ __global__ __launch_bounds__(Mma<TC>::NTHR) void gemm_grouped_kernel(const GemmP
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
-    const int wm = wave / MM::WAVES_N, wn = wave % MM::WAVES_N;
+    // position of the wavefront's sub-tile in the wavefront grid; diagonal tiles of symmetric
+    // products hand the positions out in another order (see DiagRoles)
+    int role = __builtin_amdgcn_readfirstlane(wave);
+    const bool diag_tri = !AKM && !BKM && (flags & GEMM_SYM) && ti == tj;
+    if (diag_tri) role = DiagRoles<MM>::role(role);
+    const int wm = role / MM::WAVES_N, wn = role % MM::WAVES_N;
     const int r = lane % T;   // row (A) / column (B) inside an MFMA tile
     const int h = lane / T;   // k group
 
@@ -538,9 +609,27 @@ __global__ __launch_bounds__(Mma<TC>::NTHR) void gemm_grouped_kernel(const GemmP
 
     // Fast path: full tile, whole slabs, aligned vectors -> no per-element guards in the loop.
     const bool fast = vecA && vecB && rowsA == BM && rowsB == BN && (K % BK) == 0;
-    if (fast)
-        gemm_mainloop<TC, TA, TB, AKM, BKM, false>(acc, Ab, Bb, lda, ldb, row0, col0, rowsA, rowsB, K, vecA, vecB,
-                                                   smem, tid, wm, wn, r, h);
+    // diagonal tile of a symmetric product: only the blocks on and below the diagonal are stored,
+    // so only those are multiplied (the choice is uniform over a wavefront)
+    auto run = [&](auto tri) {
+        gemm_mainloop<TC, TA, TB, AKM, BKM, false, decltype(tri)::value>(acc, Ab, Bb, lda, ldb, row0, col0, rowsA, rowsB,
+                                                                        K, vecA, vecB, smem, tid, wm, wn, r, h);
+    };
+    if (fast) {
+        constexpr int SM = BM / MM::WAVES_M / T, SN = BN / MM::WAVES_N / T;   // blocks per wavefront step
+        bool ran = false;
+        if constexpr (!AKM && !BKM) {
+            if (diag_tri) {
+                const int d = wm * SM - wn * SN;
+                if (d < -(WTM - 1)) { run(std::integral_constant<int, TRI_NONE>{}); ran = true; }
+                else if (d <= WTN - 2) {
+                    // the partial patterns this wavefront grid can produce, one loop instance each
+                    tri_try<-(WTM - 1), WTN - 2, SM, SN>(d, ran, run);
+                }
+            }
+        }
+        if (!ran) run(std::integral_constant<int, TRI_ALL>{});
+    }
     else
         gemm_mainloop<TC, TA, TB, AKM, BKM, true>(acc, Ab, Bb, lda, ldb, row0, col0, rowsA, rowsB, K, vecA, vecB,
                                                   smem, tid, wm, wn, r, h);

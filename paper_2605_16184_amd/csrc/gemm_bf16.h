@@ -108,7 +108,9 @@ struct Bf16Stage {
     }
 };
 
-template <typename TA, typename TB, int NTA, int NTB, bool GUARD>
+// TRI: which 32 x 32 blocks (i, j) of the wavefront's 64 x 64 sub-tile are multiplied (TRI_ALL,
+// TRI_NONE, or those with j - i <= TRI), as in gemm_mainloop
+template <typename TA, typename TB, int NTA, int NTB, bool GUARD, int TRI = TRI_ALL>
 __device__ __forceinline__ void gemm_bf16_mainloop(floatx16 (&acc)[2][2], const TA *Ab, const TB *Bb, int lda,
                                                    int ldb, int row0, int col0, int rowsA, int rowsB, int K,
                                                    bool vecA, bool vecB, ASTERIA_LDS uint16_t *smem, int tid,
@@ -138,7 +140,7 @@ __device__ __forceinline__ void gemm_bf16_mainloop(floatx16 (&acc)[2][2], const 
         const ASTERIA_LDS uint16_t *as = smem + cur * StA::LDS_ELEMS;
         const ASTERIA_LDS uint16_t *bs = smemB + cur * StB::LDS_ELEMS;
 #pragma unroll
-        for (int s = 0; s < STEPS; ++s) {
+        for (int s = 0; s < (TRI == TRI_NONE ? 0 : STEPS); ++s) {
             const int kk = h * KPL + s * 8;      // the lane half owns a contiguous k range of the slab
             u32x4 ah[2], al[2], bh[2], bl[2];
 #pragma unroll
@@ -158,13 +160,15 @@ __device__ __forceinline__ void gemm_bf16_mainloop(floatx16 (&acc)[2][2], const 
             for (int i = 0; i < 2; ++i)
 #pragma unroll
                 for (int j = 0; j < 2; ++j) {
+                    if (TRI != TRI_ALL && j - i > TRI) continue;
                     if (NTA == 2) acc[i][j] = MmaBf16::mma(al[i], bh[j], acc[i][j]);
                     if (NTB == 2) acc[i][j] = MmaBf16::mma(ah[i], bl[j], acc[i][j]);
                 }
 #pragma unroll
             for (int i = 0; i < 2; ++i)
 #pragma unroll
-                for (int j = 0; j < 2; ++j) acc[i][j] = MmaBf16::mma(ah[i], bh[j], acc[i][j]);
+                for (int j = 0; j < 2; ++j)
+                    if (TRI == TRI_ALL || j - i <= TRI) acc[i][j] = MmaBf16::mma(ah[i], bh[j], acc[i][j]);
         }
         if (kt + 1 < nk) {
             sa.store(smem + (cur ^ 1) * StA::LDS_ELEMS, tid);
@@ -224,7 +228,20 @@ __global__ __launch_bounds__(256) void gemm_bf16_grouped_kernel(const GemmProble
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
 
     const bool fast = vecA && vecB && rowsA == BM && rowsB == BN && (K % BK) == 0;
-    if (fast)
+    // diagonal tile of a symmetric product: blocks wholly above the diagonal are never stored and
+    // are not multiplied; the wavefront at (wm, wn) keeps the blocks with j - i <= 2 (wm - wn)
+    int d = 2;
+    if ((P.flags & GEMM_SYM) && ti == tj) {
+        const int w = __builtin_amdgcn_readfirstlane(wave);
+        d = 2 * ((w >> 1) - (w & 1));
+    }
+    if (fast && d == 0)
+        gemm_bf16_mainloop<TA, TB, NTA, NTB, false, 0>(acc, Ab, Bb, lda, ldb, row0, col0, rowsA, rowsB, K, vecA, vecB,
+                                                       smem, tid, wm, wn, r, h);
+    else if (fast && d < 0)
+        gemm_bf16_mainloop<TA, TB, NTA, NTB, false, TRI_NONE>(acc, Ab, Bb, lda, ldb, row0, col0, rowsA, rowsB, K, vecA,
+                                                              vecB, smem, tid, wm, wn, r, h);
+    else if (fast)
         gemm_bf16_mainloop<TA, TB, NTA, NTB, false>(acc, Ab, Bb, lda, ldb, row0, col0, rowsA, rowsB, K, vecA, vecB,
                                                     smem, tid, wm, wn, r, h);
     else
