@@ -94,6 +94,7 @@ template <> struct Mma<float> {
     static constexpr int WTM = 128 / WAVES_M / T;              // MFMA tiles per wavefront, rows (64 / 32)
     static constexpr int WTN = 128 / WAVES_N / T;              // MFMA tiles per wavefront, columns
     static constexpr int CH = 4;       // elements per 16-byte LDS chunk
+    static constexpr int MIN_WAVES = 4;       // wavefronts per SIMD the register budget is held to: two workgroups per CU
     static constexpr int PITCH_KC = BK + 4;   // k-contiguous LDS row pitch (144 B)
     static constexpr int PITCH_KM = BM + 4;   // k-major LDS row pitch
     typedef floatx16 acc_t;
@@ -121,6 +122,9 @@ template <> struct Mma<double> {
     static constexpr int WTM = 128 / WAVES_M / T;
     static constexpr int WTN = 128 / WAVES_N / T;
     static constexpr int CH = 2;
+    // wavefronts per SIMD the register budget is held to: one 8-wavefront workgroup per CU (a
+    // budget for two spills the staged operands inside the K loop: 30 instead of 52 TFLOP/s)
+    static constexpr int MIN_WAVES = 2;
     static constexpr int PITCH_KC = BK + 2;   // 144 B
     static constexpr int PITCH_KM = BM + 2;
     typedef doublex4 acc_t;
@@ -541,7 +545,7 @@ __device__ __forceinline__ void tri_try(int d, bool &ran, F &run)
 
 // ---- the kernel -------------------------------------------------------------------------------
 template <typename TC, typename TA, typename TB, bool AKM, bool BKM>
-__global__ __launch_bounds__(Mma<TC>::NTHR) void gemm_grouped_kernel(const GemmProblem *__restrict__ probs,
+__global__ __launch_bounds__(Mma<TC>::NTHR, Mma<TC>::MIN_WAVES) void gemm_grouped_kernel(const GemmProblem *__restrict__ probs,
                                                                 int nprobs, int total_tiles,
                                                                 const int *__restrict__ state)
 {
