@@ -620,6 +620,68 @@ asteria_status validate(const asteria_factor *f, int nf, int root, const float *
     return ASTERIA_OK;
 }
 
+// The grouped-GEMM problem tables of one pass: [parity] X' = X T on the fp32 buffers, and
+// [precision 0 = fp32, 1 = fp64][parity][T T | T^2 T^2 | T^p M] for the chain of M.
+struct RootTables {
+    GemmProblem *xt[2];
+    GemmProblem *tab[2][2][3];
+};
+
+// one thread per factor writes its entry of every table
+__global__ void root_tables_kernel(const FactorDev *__restrict__ fd, FactorScal *fs, int cnt, int root, int use32,
+                                   int use64, RootTables rt)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= cnt) return;
+    const FactorDev F = fd[i];
+    const float ca = (float)(root + 1) / (float)root, cg = 1.0f / (float)root;
+    GemmProblem p = {};
+    p.M = p.N = p.K = F.n;
+    p.state_idx = i;
+    p.alpha = 1.0f; p.beta = 0.0f; p.ep_a = ca; p.ep_g = cg;
+    p.flags = GEMM_SYM;
+    p.tile_start = F.tile_start;
+    for (int pa = 0; pa < 2; ++pa) {
+        // X after an odd number of updates lives in the workspace buffer, else in the caller's X
+        GemmProblem q = p;
+        q.state_mask = (1 << ST_RUN) | (1 << ST_LAST);
+        q.A = pa ? (const void *)F.X32b : (const void *)F.Xout; q.lda = pa ? F.ld32 : F.ldx;
+        q.B = F.T32; q.ldb = F.ld32;
+        q.C = pa ? (void *)F.Xout : (void *)F.X32b; q.ldc = pa ? F.ldx : F.ld32;
+        rt.xt[pa][i] = q;
+    }
+    p.state_mask = (1 << ST_RUN);
+    for (int pr = 0; pr < 2; ++pr) {
+        if ((pr == 0 && !use32) || (pr == 1 && !use64)) continue;
+        for (int pa = 0; pa < 2; ++pa) {
+            const void *Tm, *Mcur;
+            void *Mnext, *T4, *Tw;
+            int ldw;
+            if (pr == 1) {
+                Tm = F.T64; Tw = F.T64; Mcur = F.M64[pa]; Mnext = F.M64[pa ^ 1]; T4 = F.T464; ldw = F.ld64;
+            } else {
+                Tm = F.T32; Tw = F.T32; Mcur = F.M32[pa]; Mnext = F.M32[pa ^ 1]; T4 = F.T432; ldw = F.ld32;
+            }
+            GemmProblem q = p;
+            // launch 0: T2 = T T, kept in the buffer that receives M' afterwards (root 4) or in
+            // the T^4 buffer (root 2, where the M-update reads T2 while writing M')
+            void *T2 = (root == 4) ? Mnext : T4;
+            q.A = Tm; q.lda = ldw; q.B = Tm; q.ldb = ldw; q.C = T2; q.ldc = ldw;
+            rt.tab[pr][pa][0][i] = q;
+            // launch 1: T4 = T2 T2 (root 4 only)
+            q.A = T2; q.B = T2; q.C = T4;
+            rt.tab[pr][pa][1][i] = q;
+            // launch 2: M' = T^p M, T' = a I - g M' (+ its fp32 copy in the fp64 tier), residual partial sums
+            q.A = (root == 4) ? (const void *)T4 : (const void *)T2; q.B = Mcur;
+            q.C = Mnext; q.C2 = Tw; q.ldc2 = ldw; q.partial = F.partial;
+            if (pr == 1) { q.C3 = F.T32; q.ldc3 = F.ld32; }
+            q.coef = fs[i].coef_next;
+            q.flags = GEMM_SYM | GEMM_EPI_ROOT;
+            rt.tab[pr][pa][2][i] = q;
+        }
+    }
+}
+
 // one pass over factors [first, first + cnt) of the size-sorted order
 asteria_status run_pass(const asteria_factor *f, const std::vector<int> &order, int first, int cnt,
                         int root, asteria_eps_mode mode, const float *eps, int eps_count, const Plan &pl,
@@ -701,81 +763,18 @@ asteria_status run_pass(const asteria_factor *f, const std::vector<int> &order, 
     // floor approaches stop_resid, so the automatic rule keeps such factors on the fp32 cores
     const int jlow = (pl.lowp_auto && n_max > 2048) ? K : pl.lowp_from;
 
-    // problem tables
-    const float ca = (float)(root + 1) / (float)root, cg = 1.0f / (float)root;
-    std::vector<GemmProblem> tab[2][2][3], tab_xt[2];
-    for (int pa = 0; pa < 2; ++pa) {
-        int t0 = 0;
-        for (int i = 0; i < cnt; ++i) {
-            const FactorDev &F = fd[i];
-            GemmProblem p;
-            memset(&p, 0, sizeof(p));
-            p.M = p.N = p.K = F.n;
-            p.state_idx = i;
-            p.state_mask = (1 << ST_RUN) | (1 << ST_LAST);
-            p.alpha = 1.0f; p.beta = 0.0f; p.ep_a = ca; p.ep_g = cg;
-            p.flags = GEMM_SYM;
-            // X after an odd number of updates lives in the workspace buffer, else in the caller's X
-            p.A = pa ? (const void *)F.X32b : (const void *)F.Xout; p.lda = pa ? F.ld32 : F.ldx;
-            p.B = F.T32; p.ldb = F.ld32;
-            p.C = pa ? (void *)F.Xout : (void *)F.X32b; p.ldc = pa ? F.ldx : F.ld32;
-            p.tile_start = t0; t0 += F.ntri;
-            tab_xt[pa].push_back(p);
-        }
-    }
-    for (int pr = 0; pr < 2; ++pr) {
-        if ((pr == 0 && !pl.use32) || (pr == 1 && !pl.use64)) continue;
-        for (int pa = 0; pa < 2; ++pa) {
-            int t1 = 0;
-            for (int i = 0; i < cnt; ++i) {
-                const FactorDev &F = fd[i];
-                const void *Tm, *Mcur;
-                void *Mnext, *T4, *Tw;
-                int ldw;
-                if (pr == 1) {
-                    Tm = F.T64; Tw = F.T64; Mcur = F.M64[pa]; Mnext = F.M64[pa ^ 1]; T4 = F.T464; ldw = F.ld64;
-                } else {
-                    Tm = F.T32; Tw = F.T32; Mcur = F.M32[pa]; Mnext = F.M32[pa ^ 1]; T4 = F.T432; ldw = F.ld32;
-                }
-                GemmProblem p;
-                memset(&p, 0, sizeof(p));
-                p.M = p.N = p.K = F.n;
-                p.state_idx = i;
-                p.state_mask = (1 << ST_RUN);
-                p.alpha = 1.0f; p.beta = 0.0f; p.ep_a = ca; p.ep_g = cg;
-                p.flags = GEMM_SYM;
-                p.tile_start = t1;
-                // launch 0: T2 = T T, kept in the buffer that receives M' afterwards (root 4) or in
-                // the T^4 buffer (root 2, where the M-update reads T2 while writing M')
-                void *T2 = (root == 4) ? Mnext : T4;
-                p.A = Tm; p.lda = ldw; p.B = Tm; p.ldb = ldw; p.C = T2; p.ldc = ldw;
-                tab[pr][pa][0].push_back(p);
-                // launch 1: T4 = T2 T2 (root 4 only)
-                p.A = T2; p.B = T2; p.C = T4;
-                tab[pr][pa][1].push_back(p);
-                // launch 2: M' = T^p M, T' = a I - g M' (+ its fp32 copy in the fp64 tier), residual partial sums
-                p.A = (root == 4) ? (const void *)T4 : (const void *)T2; p.B = Mcur;
-                p.C = Mnext; p.C2 = Tw; p.ldc2 = ldw; p.partial = F.partial;
-                if (pr == 1) { p.C3 = F.T32; p.ldc3 = F.ld32; }
-                p.coef = reinterpret_cast<const float *>(reinterpret_cast<const char *>(d_fs + i) +
-                                                         offsetof(FactorScal, coef_next));
-                p.flags = GEMM_SYM | GEMM_EPI_ROOT;
-                tab[pr][pa][2].push_back(p);
-                t1 += F.ntri;
-            }
-        }
-    }
-
+    // problem tables: written on the device from the factor descriptors (the 14 tables are 11 times
+    // the size of the descriptors, and host tables would travel as kernel arguments)
     ASTERIA_HIP_TRY(upload_async(d_fd, fd.data(), sizeof(FactorDev) * cnt, stream));
     ASTERIA_HIP_TRY(upload_async(d_sq, sq.data(), sizeof(int) * cnt, stream));
-    for (int pa = 0; pa < 2; ++pa)
-        ASTERIA_HIP_TRY(upload_async(d_xt[pa], tab_xt[pa].data(), tab_xt[pa].size() * sizeof(GemmProblem), stream));
+    RootTables rt;
+    for (int pa = 0; pa < 2; ++pa) rt.xt[pa] = d_xt[pa];
     for (int pr = 0; pr < 2; ++pr)
         for (int pa = 0; pa < 2; ++pa)
-            for (int l = 0; l < 3; ++l)
-                if (!tab[pr][pa][l].empty())
-                    ASTERIA_HIP_TRY(upload_async(d_tab[pr][pa][l], tab[pr][pa][l].data(),
-                                                 tab[pr][pa][l].size() * sizeof(GemmProblem), stream));
+            for (int l = 0; l < 3; ++l) rt.tab[pr][pa][l] = d_tab[pr][pa][l];
+    hipLaunchKernelGGL(root_tables_kernel, dim3((cnt + 127) / 128), dim3(128), 0, stream, d_fd, d_fs, cnt, root,
+                       pl.use32 ? 1 : 0, pl.use64 ? 1 : 0, rt);
+    ASTERIA_HIP_TRY(hipGetLastError());
 
     // 1. lambda_max
     hipLaunchKernelGGL(pm_init_kernel, dim3(cnt), dim3(256), 0, stream, d_fd, d_fs);
