@@ -257,6 +257,17 @@ __global__ void root_setup_kernel(const FactorDev *fd, FactorScal *fs, int *stat
     S.coef_next[0] = (float)a; S.coef_next[1] = (float)g;
 }
 
+// 4 consecutive elements as 16-byte stores (the destination is 16-byte aligned)
+__device__ __forceinline__ void store4(float *p, const float (&v)[4])
+{
+    *reinterpret_cast<float4 *>(p) = make_float4(v[0], v[1], v[2], v[3]);
+}
+__device__ __forceinline__ void store4(double *p, const double (&v)[4])
+{
+    reinterpret_cast<double2 *>(p)[0] = make_double2(v[0], v[1]);
+    reinterpret_cast<double2 *>(p)[1] = make_double2(v[2], v[3]);
+}
+
 // One workgroup per lower-triangle 128 x 128 tile: M_0, T_0, X_0 and the residual partial sums.
 template <typename TC>
 __global__ __launch_bounds__(256) void root_init_kernel(const FactorDev *fd, const FactorScal *fs,
@@ -297,8 +308,73 @@ __global__ __launch_bounds__(256) void root_init_kernel(const FactorDev *fd, con
     // Q = A[sub(tj, ti)] are both read along rows (coalesced) into LDS; the symmetrised value at
     // (r, c) of tile (ti, tj) is (P[r][c] + Q[c][r]) / 2 and the one at (c, r) of tile (tj, ti) is
     // the same number, so every global read and write of this kernel runs along rows.
-    __shared__ float Ps[32][33], Qs[32][33];
     float rsum = 0.0f;
+    __shared__ float red[4];
+    // Full tiles with 16-byte aligned rows: 64 x 64 sub-tiles, 16-byte global loads, and 32-byte
+    // (fp64) or 16-byte (fp32) stores of 4 consecutive elements per thread; LDS rows of 65 words
+    // keep both the row-wise and the transposed reads free of bank conflicts.
+    const bool aligned = ti * BM + BM <= n && (lda & 3) == 0 && (reinterpret_cast<uintptr_t>(F.A) & 15u) == 0;
+    if (aligned) {
+        __shared__ float Pw[64][65], Qw[64][65];
+        const int g = threadIdx.x & 15, rw = threadIdx.x >> 4;     // 16 column groups of 4 x 16 rows
+        for (int sub = 0; sub < 4; ++sub) {
+            const int si = sub >> 1, sj = sub & 1;
+            if (ti == tj && si < sj) continue;                       // covered by the mirrored sub-tile
+            const int r0 = ti * BM + si * 64, c0 = tj * BN + sj * 64;
+            const bool diag_sub = (ti == tj && si == sj);
+            __syncthreads();
+            for (int rr = rw; rr < 64; rr += 16) {
+                const float4 pv = *reinterpret_cast<const float4 *>(F.A + (size_t)(r0 + rr) * lda + c0 + 4 * g);
+                Pw[rr][4 * g] = pv.x; Pw[rr][4 * g + 1] = pv.y; Pw[rr][4 * g + 2] = pv.z; Pw[rr][4 * g + 3] = pv.w;
+                const float4 qv = *reinterpret_cast<const float4 *>(F.A + (size_t)(c0 + rr) * lda + r0 + 4 * g);
+                Qw[rr][4 * g] = qv.x; Qw[rr][4 * g + 1] = qv.y; Qw[rr][4 * g + 2] = qv.z; Qw[rr][4 * g + 3] = qv.w;
+            }
+            __syncthreads();
+            for (int rr = rw; rr < 64; rr += 16) {
+                // elements (r, c .. c + 3) of tile (ti, tj)
+                {
+                    const int r = r0 + rr, c = c0 + 4 * g;
+                    TC mv[4], tv[4];
+                    float xv[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const TC av = (TC)0.5 * ((TC)Pw[rr][4 * g + e] + (TC)Qw[4 * g + e][rr]);
+                        const TC d = (r == c + e) ? (TC)1 : (TC)0;
+                        mv[e] = s * (av + eps * d);
+                        tv[e] = ca * d - cg * mv[e];
+                        xv[e] = (float)(xs * tv[e]);
+                        const float er = (float)(mv[e] - d);
+                        rsum += diag_sub ? er * er : 2.0f * er * er;
+                    }
+                    store4(M + (size_t)r * ldm + c, mv);
+                    store4(T + (size_t)r * ldm + c, tv);
+                    store4(X + (size_t)r * ldx + c, xv);
+                }
+                // elements (r2, c2 .. c2 + 3) of the mirrored tile (tj, ti): the same numbers transposed
+                if (!diag_sub) {
+                    const int r2 = c0 + rr, c2 = r0 + 4 * g;
+                    TC mv[4], tv[4];
+                    float xv[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const TC av = (TC)0.5 * ((TC)Pw[4 * g + e][rr] + (TC)Qw[rr][4 * g + e]);
+                        mv[e] = s * av;                              // off the diagonal: no eps, d = 0
+                        tv[e] = -cg * mv[e];
+                        xv[e] = (float)(xs * tv[e]);
+                    }
+                    store4(M + (size_t)r2 * ldm + c2, mv);
+                    store4(T + (size_t)r2 * ldm + c2, tv);
+                    store4(X + (size_t)r2 * ldx + c2, xv);
+                }
+            }
+        }
+        rsum = wave_sum(rsum);
+        if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = rsum;
+        __syncthreads();
+        if (threadIdx.x == 0) F.partial[lt] = red[0] + red[1] + red[2] + red[3];
+        return;
+    }
+    __shared__ float Ps[32][33], Qs[32][33];
     const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;     // 32 x 8 threads
     for (int sub = 0; sub < 16; ++sub) {
         const int si = sub >> 2, sj = sub & 3;
@@ -345,7 +421,6 @@ __global__ __launch_bounds__(256) void root_init_kernel(const FactorDev *fd, con
             }
         }
     }
-    __shared__ float red[4];
     rsum = wave_sum(rsum);
     if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = rsum;
     __syncthreads();
