@@ -258,9 +258,6 @@ __device__ __forceinline__ void pg_emit(const PlaneProblem &P, int grow, int gco
     }
 }
 
-#ifdef PG_CLOCK_PROBE
-__device__ unsigned long long pg_probe[4];
-#endif
 template <class S>
 __global__ __launch_bounds__(S::NTHR) void pgemm_kernel(const PlaneProblem *__restrict__ probs, int nprobs,
                                                         int total_tiles, const int *__restrict__ state)
@@ -278,9 +275,6 @@ __global__ __launch_bounds__(S::NTHR) void pgemm_kernel(const PlaneProblem *__re
         const int mid = (plo + phi + 1) >> 1;
         if (probs[mid].tile_start <= t_global) plo = mid; else phi = mid - 1;
     }
-#ifdef PG_CLOCK_PROBE
-    const unsigned long long probe_c0 = clock64(), probe_w0 = wall_clock64();
-#endif
     const PlaneProblem P = probs[plo];   // by value: the fields stay in scalar registers across the stores below
     if (P.state_idx >= 0) {
         const int st = state[P.state_idx];
@@ -533,9 +527,6 @@ __global__ __launch_bounds__(S::NTHR) void pgemm_kernel(const PlaneProblem *__re
             __syncthreads();
         }
     }
-#ifdef PG_CLOCK_PROBE
-    if (tid == 0) { atomicAdd(&pg_probe[0], clock64() - probe_c0); atomicAdd(&pg_probe[1], wall_clock64() - probe_w0); atomicAdd(&pg_probe[2], 1ull); }
-#endif
     if (root) {
         // every element of the output (both triangles) was visited exactly once
 #pragma unroll
