@@ -95,6 +95,9 @@ template <> struct Mma<float> {
     static constexpr int WTN = 128 / WAVES_N / T;              // MFMA tiles per wavefront, columns
     static constexpr int CH = 4;       // elements per 16-byte LDS chunk
     static constexpr int MIN_WAVES = 4;       // wavefronts per SIMD the register budget is held to: two workgroups per CU
+    // slabs of global loads in flight ahead of the one being multiplied (2 needs a second register
+    // set, which does not fit the budget above without spills, and gained 1 %)
+    static constexpr int PREFETCH = 1;
     static constexpr int PITCH_KC = BK + 4;   // k-contiguous LDS row pitch (144 B)
     static constexpr int PITCH_KM = BM + 4;   // k-major LDS row pitch
     typedef floatx16 acc_t;
@@ -125,6 +128,7 @@ template <> struct Mma<double> {
     // wavefronts per SIMD the register budget is held to: one 8-wavefront workgroup per CU (a
     // budget for two spills the staged operands inside the K loop: 30 instead of 52 TFLOP/s)
     static constexpr int MIN_WAVES = 2;
+    static constexpr int PREFETCH = 2;        // slabs of global loads in flight ahead of the one being multiplied
     static constexpr int PITCH_KC = BK + 2;   // 144 B
     static constexpr int PITCH_KM = BM + 2;
     typedef doublex4 acc_t;
@@ -296,24 +300,10 @@ __device__ __forceinline__ void gemm_mainloop(typename Mma<TC>::acc_t (&acc)[Mma
     constexpr int T = MM::T;
     using StA = OperandStage<TC, TA, AKM>;
     using StB = OperandStage<TC, TB, BKM>;
-    StA sa;
-    StB sb;
     // LDS map: A stage 0 | A stage 1 | B stage 0 | B stage 1
     ASTERIA_LDS TC *const smemB = smem + 2 * StA::LDS_ELEMS;
     const int nk = (K + BK - 1) / BK;
-    sa.template load<GUARD>(Ab, lda, row0, rowsA, 0, K, vecA, tid);
-    sb.template load<GUARD>(Bb, ldb, col0, rowsB, 0, K, vecB, tid);
-    sa.store(smem, tid);
-    sb.store(smemB, tid);
-    __syncthreads();
-
-    for (int kt = 0; kt < nk; ++kt) {
-        const int cur = kt & 1;
-        if (kt + 1 < nk) {
-            const int k0 = (kt + 1) * BK;
-            sa.template load<GUARD>(Ab, lda, row0, rowsA, k0, K - k0, vecA, tid);
-            sb.template load<GUARD>(Bb, ldb, col0, rowsB, k0, K - k0, vecB, tid);
-        }
+    auto compute = [&](int cur) {
         const ASTERIA_LDS TC *as = smem + cur * StA::LDS_ELEMS;
         const ASTERIA_LDS TC *bs = smemB + cur * StB::LDS_ELEMS;
         // lane group h consumes k = h * KPL .. h * KPL + KPL - 1 of the slab, the same for A and B
@@ -351,11 +341,59 @@ __device__ __forceinline__ void gemm_mainloop(typename Mma<TC>::acc_t (&acc)[Mma
                     for (int j = 0; j < WTN; ++j)
                         if (TRI == TRI_ALL || j - i <= TRI) acc[i][j] = MM::mma(af[i][e], bf[j][e], acc[i][j]);
         }
-        if (kt + 1 < nk) {
-            sa.store(smem + (cur ^ 1) * StA::LDS_ELEMS, tid);
-            sb.store(smemB + (cur ^ 1) * StB::LDS_ELEMS, tid);
-        }
+    };
+    if constexpr (!GUARD && MM::PREFETCH == 2) {
+        // two register sets: slab j waits in set j % 2 from its global load, issued two iterations
+        // ahead, until it is stored to LDS stage j % 2 at the end of iteration j - 1
+        StA sa[2];
+        StB sb[2];
+        auto load = [&](auto set, int slab) {
+            sa[decltype(set)::value].template load<false>(Ab, lda, row0, rowsA, slab * BK, BK, vecA, tid);
+            sb[decltype(set)::value].template load<false>(Bb, ldb, col0, rowsB, slab * BK, BK, vecB, tid);
+        };
+        auto store = [&](auto set) {
+            sa[decltype(set)::value].store(smem + decltype(set)::value * StA::LDS_ELEMS, tid);
+            sb[decltype(set)::value].store(smemB + decltype(set)::value * StB::LDS_ELEMS, tid);
+        };
+        using S0 = std::integral_constant<int, 0>;
+        using S1 = std::integral_constant<int, 1>;
+        load(S0{}, 0);
+        store(S0{});
+        if (nk > 1) load(S1{}, 1);
         __syncthreads();
+        for (int kt = 0; kt < nk; kt += 2) {
+            if (kt + 2 < nk) load(S0{}, kt + 2);
+            compute(0);
+            if (kt + 1 < nk) store(S1{});
+            __syncthreads();
+            if (kt + 1 >= nk) break;
+            if (kt + 3 < nk) load(S1{}, kt + 3);
+            compute(1);
+            if (kt + 2 < nk) store(S0{});
+            __syncthreads();
+        }
+    } else {
+        StA sa;
+        StB sb;
+        sa.template load<GUARD>(Ab, lda, row0, rowsA, 0, K, vecA, tid);
+        sb.template load<GUARD>(Bb, ldb, col0, rowsB, 0, K, vecB, tid);
+        sa.store(smem, tid);
+        sb.store(smemB, tid);
+        __syncthreads();
+        for (int kt = 0; kt < nk; ++kt) {
+            const int cur = kt & 1;
+            if (kt + 1 < nk) {
+                const int k0 = (kt + 1) * BK;
+                sa.template load<GUARD>(Ab, lda, row0, rowsA, k0, K - k0, vecA, tid);
+                sb.template load<GUARD>(Bb, ldb, col0, rowsB, k0, K - k0, vecB, tid);
+            }
+            compute(cur);
+            if (kt + 1 < nk) {
+                sa.store(smem + (cur ^ 1) * StA::LDS_ELEMS, tid);
+                sb.store(smemB + (cur ^ 1) * StB::LDS_ELEMS, tid);
+            }
+            __syncthreads();
+        }
     }
 }
 
