@@ -46,11 +46,14 @@ struct PlaneProblem {
     int tiles_n;            // tile columns (non-symmetric problems)
     int state_idx, state_mask;
     float alpha, beta, ep_a, ep_g;
-    int flags;              // GEMM_SYM, GEMM_EPI_ROOT, GEMM_STORE_T (fp32 output stored transposed, no beta)
+    int flags;              // GEMM_SYM, GEMM_EPI_ROOT, GEMM_STORE_T (fp32 output stored transposed, no beta), PG_KMAJOR
     int c_terms;            // terms of Cp / Tp (1 or 2)
 };
 
 // pair (ta, tb) of an NTA x NTB split product is issued iff bit ta * 2 + tb of PAIRS is set
+// problem flag (beside the GEMM_* ones): both operands are plain bf16 matrices stored k-major
+constexpr int PG_KMAJOR = 16;
+
 constexpr unsigned PG_PAIRS_1 = 0x1u;            // (0,0)
 constexpr unsigned PG_PAIRS_2x1 = 0x1u | 0x4u;   // (0,0) (1,0)
 constexpr unsigned PG_PAIRS_1x2 = 0x1u | 0x2u;   // (0,0) (0,1)
@@ -59,8 +62,14 @@ constexpr unsigned PG_PAIRS_2x2 = 0x7u;          // (0,0) (0,1) (1,0): 16 bits o
 // WGM x WGN wavefronts of WTM x WTN MFMA tiles (32 x 32); K slabs of BK; DEPTH register sets
 // of global-load prefetch.
 template <int NTA_, int NTB_, unsigned PAIRS_, int WGM_, int WGN_, int WTM_, int WTN_, int BK_, int DEPTH_ = 1, int MODE_ = 0,
-          bool FA_ = false, bool FB_ = false>
+          bool FA_ = false, bool FB_ = false, bool KM_ = false>
 struct PgShape {
+    // KM: the kernel also accepts problems flagged PG_KMAJOR, whose operands are bf16 matrices stored
+    // k-major (A'(i, k) = A[k * lda + i]); one term, 128 x 128 tiles of 4 wavefronts, slabs of 64
+    static constexpr bool KM = KM_;
+    static_assert(!KM_ || (NTA_ == 1 && NTB_ == 1 && WGM_ == 2 && WGN_ == 2 && WTM_ == 2 && WTN_ == 2 && BK_ == 64 &&
+                           !FA_ && !FB_ && MODE_ == 0),
+                  "k-major problems: plain bf16, 128 x 128 tiles, slabs of 64");
     // FA / FB: the operand is a plain fp32 row-major matrix, split into two bf16 terms while it is
     // staged (the LDS layout is that of a two-term split matrix); it then needs NT = 2
     static constexpr bool FA = FA_, FB = FB_;
@@ -258,6 +267,89 @@ __device__ __forceinline__ void pg_emit(const PlaneProblem &P, int grow, int gco
     }
 }
 
+// K loop of a 128 x 128 tile whose operands lie k-major in memory (G^T G read from G as it is).
+// A slab is 64 rows (k) of 128 consecutive elements per operand and is staged as it lies in memory:
+// LDS row = k, 256 bytes, its four 64-byte segments XOR-swizzled by k % 4.  The MFMA operands (8
+// consecutive k of one row i per lane) come out of LDS through ds_read_b64_tr_b16, which transposes
+// within 16 lanes: lane 4 e + q supplies the address of elements 4 q .. 4 q + 3 of row k0 + e, and
+// lane j receives element j of rows k0 .. k0 + 3.  Two such reads give the 8 values of a lane; a
+// 32-lane half then touches 4 rows x 64 bytes, which the swizzle spreads over all 64 banks.
+template <class S>
+__device__ __forceinline__ void pg_kmajor_loop(floatx16 (&acc)[2][2], const PlaneProblem &P, int row0, int col0,
+                                               ASTERIA_LDS uint16_t *smem, int tid, int wm, int wn, int lane)
+{
+    constexpr int BK = 64, ROWB = 256, OPB = BK * ROWB, STAGEB = 2 * OPB;
+    static_assert(2 * STAGEB <= (int)S::LDS_BYTES, "two stages fit");
+    typedef short pg_short4 __attribute__((ext_vector_type(4)));
+    ASTERIA_LDS char *lds = (ASTERIA_LDS char *)smem;
+    // loader: thread -> 16-byte vector v of slab row kr (+ 16 per register)
+    const int v = tid & 15, kr = tid >> 4;
+    const char *ga = reinterpret_cast<const char *>(P.A) + ((size_t)row0 + 8 * v) * 2 + (size_t)kr * P.lda * 2;
+    const char *gb = reinterpret_cast<const char *>(P.B) + ((size_t)col0 + 8 * v) * 2 + (size_t)kr * P.ldb * 2;
+    const size_t stepa = (size_t)16 * P.lda * 2, stepb = (size_t)16 * P.ldb * 2;       // 16 rows on
+    const size_t slaba = (size_t)BK * P.lda * 2, slabb = (size_t)BK * P.ldb * 2;
+    // (kr + 16 vi) % 4 = kr % 4: one store offset serves the four registers
+    const uint32_t st_off = (uint32_t)(kr * ROWB + (((v >> 2) ^ (kr & 3)) << 6) + ((v & 3) << 4));
+    u32x4 ra[4], rb[4];
+    auto gload = [&](int slab) {
+#pragma unroll
+        for (int vi = 0; vi < 4; ++vi) {
+            ra[vi] = *(const ASTERIA_GLOBAL u32x4 *)(ga + slab * slaba + vi * stepa);
+            rb[vi] = *(const ASTERIA_GLOBAL u32x4 *)(gb + slab * slabb + vi * stepb);
+        }
+    };
+    auto lstore = [&](int stage) {
+#pragma unroll
+        for (int vi = 0; vi < 4; ++vi) {
+            *(ASTERIA_LDS u32x4 *)(lds + stage * STAGEB + st_off + vi * 16 * ROWB) = ra[vi];
+            *(ASTERIA_LDS u32x4 *)(lds + stage * STAGEB + OPB + st_off + vi * 16 * ROWB) = rb[vi];
+        }
+    };
+    // fragment reads: 16-lane group g = (k half, i half), lane 4 e + q of it reads row e, elements 4 q ..
+    const int g = lane >> 4, e = (lane >> 2) & 3, q = lane & 3;
+    const uint32_t rd_row = (uint32_t)((8 * (g >> 1) + e) * ROWB);
+    const uint32_t rd_col = (uint32_t)((16 * (g & 1) + 4 * q) * 2);
+    uint32_t fa[2], fb[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        fa[i] = rd_row + ((uint32_t)((wm * 2 + i) ^ e) << 6) + rd_col;
+        fb[i] = (uint32_t)OPB + rd_row + ((uint32_t)((wn * 2 + i) ^ e) << 6) + rd_col;
+    }
+    auto frag = [&](uint32_t off) {
+        const pg_short4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((ASTERIA_LDS pg_short4 *)(lds + off));
+        const pg_short4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((ASTERIA_LDS pg_short4 *)(lds + off + 4 * ROWB));
+        typedef uint32_t pg_u32x2 __attribute__((ext_vector_type(2)));
+        const pg_u32x2 l2 = __builtin_bit_cast(pg_u32x2, lo), h2 = __builtin_bit_cast(pg_u32x2, hi);
+        u32x4 r;
+        r[0] = l2[0]; r[1] = l2[1]; r[2] = h2[0]; r[3] = h2[1];
+        return r;
+    };
+    const int nk = P.K / BK;
+    gload(0);
+    lstore(0);
+    if (1 < nk) gload(1);
+    pg_lds_barrier();
+    for (int kt = 0; kt < nk; ++kt) {
+        const uint32_t sb = (uint32_t)((kt & 1) * STAGEB);
+#pragma unroll
+        for (int s = 0; s < BK / 16; ++s) {
+            u32x4 af[2], bf[2];
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                af[i] = frag(sb + fa[i] + s * 16 * ROWB);
+                bf[i] = frag(sb + fb[i] + s * 16 * ROWB);
+            }
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j) acc[i][j] = pg_mma(af[i], bf[j], acc[i][j]);
+        }
+        if (kt + 1 < nk) lstore((kt + 1) & 1);
+        if (kt + 2 < nk) gload(kt + 2);
+        pg_lds_barrier();
+    }
+}
+
 template <class S>
 __global__ __launch_bounds__(S::NTHR) void pgemm_kernel(const PlaneProblem *__restrict__ probs, int nprobs,
                                                         int total_tiles, const int *__restrict__ state)
@@ -299,7 +391,12 @@ __global__ __launch_bounds__(S::NTHR) void pgemm_kernel(const PlaneProblem *__re
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
 
     // ---- K loop ---------------------------------------------------------------------------------
-    {
+    bool kmajor = false;
+    if constexpr (S::KM) {
+        kmajor = (P.flags & PG_KMAJOR) != 0;
+        if (kmajor) pg_kmajor_loop<S>(acc, P, row0, col0, smem, tid, wm, wn, lane);
+    }
+    if (!kmajor) {
         PgLoader<S, S::FA, NTA, TM> la;
         PgLoader<S, S::FB, NTB, TN> lb;
         la.init(P.A, P.lda, row0, tid);

@@ -3,12 +3,13 @@
 //
 // Both products are symmetric grouped GEMMs on the matrix cores with the EMA fused in the
 // epilogue; only tiles on/below the diagonal are computed and mirrored.
-//   bf16 gradients: bf16 MFMA (products exact in fp32).  G G^T reads G as is; for G^T G a
-//     transposed bf16 copy of G, zero-padded to whole tiles, is written to the workspace first
-//     (one extra HBM round trip of G, ~10% of the call's traffic) so that both products read
-//     k-contiguous operands.  Operands that are 16-byte aligned and fill whole tiles go through
-//     the guard-free bf16 kernel (pgemm.h: 16-byte row pieces, LDS-staged epilogue with vector
-//     loads of the old L / R); anything else through the guarded one.
+//   bf16 gradients: bf16 MFMA (products exact in fp32), guard-free kernel of pgemm.h (16-byte row
+//     pieces, LDS-staged epilogue with vector loads of the old L / R).  G G^T reads G as is
+//     (k-contiguous).  G^T G reads G as is too when G is 16-byte aligned and fills whole tiles:
+//     its operands are then k-major, staged as they lie and transposed by the LDS transpose reads
+//     of gfx950.  Otherwise a transposed bf16 copy of G, zero-padded to whole tiles, is written to
+//     the workspace first and read k-contiguous.  A G G^T whose operand is unaligned or ragged
+//     takes the guarded kernel.
 //   fp32 gradients: fp32 MFMA; G^T G reads G k-major, no copy.
 #include <vector>
 
@@ -24,7 +25,7 @@ namespace {
 inline int pad_to(int n, int q) { return (n + q - 1) / q * q; }
 
 // guard-free kernel for the statistics: one bf16 term per operand, 128 x 128 tiles, slabs of 64
-using StatsShape = PgShape<1, 1, PG_PAIRS_1, 2, 2, 2, 2, 64, 1>;
+using StatsShape = PgShape<1, 1, PG_PAIRS_1, 2, 2, 2, 2, 64, 1, 0, false, false, true>;
 constexpr int ST_TILE = StatsShape::TM;   // 128
 constexpr int ST_BK = StatsShape::BK;     // 64
 
@@ -74,6 +75,12 @@ struct StatsTables {
 inline bool fast_operand(const void *p, int rows, int k, int ld)
 {
     return (reinterpret_cast<uintptr_t>(p) & 15u) == 0 && (ld % 8) == 0 && (rows % ST_TILE) == 0 && (k % ST_BK) == 0;
+}
+
+// G can feed G^T G directly (k-major operands): columns fill whole tiles, rows whole slabs
+inline bool kmajor_operand(const void *p, int m, int n, int ld)
+{
+    return (reinterpret_cast<uintptr_t>(p) & 15u) == 0 && (ld % 8) == 0 && (n % ST_TILE) == 0 && (m % ST_BK) == 0;
 }
 
 inline PlaneProblem fast_problem(const void *G, int rows, int k, int ld, float *C, int ldc, float beta, int tile_start)
@@ -148,7 +155,8 @@ extern "C" size_t asteria_stats_update_workspace_bytes(const asteria_block *bloc
                    Carver::need(2 * (size_t)nblocks, sizeof(PlaneProblem)) +
                    Carver::need((size_t)nblocks, sizeof(TransposeJob)) + 8 * 256;
     for (int i = 0; i < nblocks; ++i)
-        if (blocks[i].g_dtype == ASTERIA_BF16 && blocks[i].R && blocks[i].m > 0 && blocks[i].n > 0)
+        if (blocks[i].g_dtype == ASTERIA_BF16 && blocks[i].R && blocks[i].m > 0 && blocks[i].n > 0 &&
+            !kmajor_operand(blocks[i].G, blocks[i].m, blocks[i].n, blocks[i].ldg))
             bytes += Carver::need((size_t)pad_to(blocks[i].n, ST_TILE) * pad_to(blocks[i].m, ST_BK), sizeof(uint16_t));
     return bytes;
 }
@@ -173,6 +181,13 @@ extern "C" asteria_status asteria_stats_update(const asteria_block *blocks, int 
         for (int i = 0; i < nblocks; ++i) {
             const asteria_block &k = blocks[i];
             if (k.g_dtype != ASTERIA_BF16 || !k.R) continue;
+            if (kmajor_operand(k.G, k.m, k.n, k.ldg)) {
+                PlaneProblem q = fast_problem(k.G, k.n, k.m, k.ldg, k.R, k.ldr, beta, t.tiles_fast);
+                q.flags |= PG_KMAJOR;
+                t.fast.push_back(q);
+                t.tiles_fast += pg_tri_tiles(k.n, ST_TILE);
+                continue;
+            }
             const int n_pad = pad_to(k.n, ST_TILE), m_pad = pad_to(k.m, ST_BK);
             uint16_t *Gt = cv.take<uint16_t>((size_t)n_pad * m_pad);
             TransposeJob j;

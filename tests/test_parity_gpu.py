@@ -111,6 +111,27 @@ def test_stats_ragged_batch_bf16_and_fp32_with_padded_leading_dimensions():
         assert torch.all(L._base[:, L.shape[1]:] == -777.0)     # pad columns untouched
 
 
+def test_stats_whole_tile_bf16_blocks_read_in_place_or_through_the_transposed_copy():
+    # G^T G of a 16-byte aligned bf16 block with whole tiles reads G in place (k-major operands);
+    # the same shapes with an odd leading dimension take the transposed copy: both in one call
+    shapes = [(64, 128), (192, 384), (512, 256), (128, 128), (320, 640)]
+    items, refs = [], []
+    for i, (m, n) in enumerate(shapes):
+        for pad in (8, 3, 0):
+            G = padded(m, n, pad, torch.bfloat16, fill=5.0)
+            G.copy_(W.gaussian_block(m, n, 0.1, DEV, 4, i, dtype=torch.bfloat16))
+            L = padded(m, m, 4); L.copy_(spd(m, 5, i))
+            R = padded(n, n, 1); R.copy_(spd(n, 6, i))
+            refs.append(oracle.stats_update(np64(G), np64(L), np64(R), 0.9))
+            items.append((G, L, R))
+    ast.stats_update(items, 0.9)
+    torch.cuda.synchronize()
+    for (G, L, R), (Lo, Ro) in zip(items, refs):
+        assert relF(L, Lo) <= TOL_STATS and relF(R, Ro) <= TOL_STATS, (tuple(G.shape), relF(L, Lo), relF(R, Ro))
+        assert torch.equal(L, L.T) and torch.equal(R, R.T)
+        assert torch.all(R._base[:, R.shape[1]:] == -777.0) and torch.all(G._base[:, G.shape[1]:] == 5.0)
+
+
 def test_stats_one_sided_update_leaves_the_other_factor_alone():
     G = W.gaussian_block(70, 90, 0.1, DEV, 3, dtype=torch.bfloat16)
     L = spd(70, 3); R = spd(90, 4); R0 = R.clone()
