@@ -115,7 +115,13 @@ struct QrFactor {
     int n, ldz, ldq;
     int tile_start; // for the transposing write-back (square 32 x 32 tiles)
     int bad;        // set to 1 when a column could not be normalised
+    // Two words the grouped launches read as their per-problem state (a problem runs while its word
+    // is 0): `run` stays 0; `skip3` is 1 unless the second sweep over the current panel found a row
+    // that needs a third one.
+    int run, skip3;
 };
+constexpr int QR_STATE_STRIDE = (int)(sizeof(QrFactor) / sizeof(int));
+static_assert(sizeof(QrFactor) % sizeof(int) == 0, "state words are addressed as ints inside the factor array");
 
 constexpr int QR_PANEL = 128;
 constexpr int QR_MAXN = 1 << 20;
@@ -127,9 +133,19 @@ constexpr int QR_MAXN = 1 << 20;
 // Cholesky on a 16 x 16 thread grid, then the triangular inverse in place, row by row (row i of
 // W needs row i of L and the rows of W above it; one thread per column).
 constexpr int CHOL_THREADS = 256;
-__global__ __launch_bounds__(CHOL_THREADS) void panel_chol_inverse_kernel(QrFactor *fs, const int *fidx, int panel)
+// Sweeps and failure reporting.  A pivot that is not positive (a zero row cannot be normalised)
+// fails the factor.  In the second sweep over a panel (sweep = 1) the rows are those the first
+// sweep normalised, projected once more: a pivot far below 1 there means that a row was
+// numerically dependent - the first normalisation blew round-off up to unit length, most of which
+// lay in the span of the rows before it - and this sweep's normalisation amplifies what the
+// projection left by 1 / sqrt(pivot).  Such a factor takes a third sweep (skip3 = 0), which only
+// its workgroups run; a pivot that small in the third sweep fails the factor.
+constexpr double CHOL_REPEAT_MIN = 0.1;
+__global__ __launch_bounds__(CHOL_THREADS) void panel_chol_inverse_kernel(QrFactor *fs, const int *fidx, int panel,
+                                                                          int sweep)
 {
     QrFactor &F = fs[fidx[blockIdx.x]];
+    if (sweep == 2 && F.skip3) return;              // uniform over the workgroup
     const int rows = min(QR_PANEL, F.n - panel * QR_PANEL);
     extern __shared__ __align__(16) unsigned char chol_smem[];
     double *L = reinterpret_cast<double *>(chol_smem);            // rows x rows, pitch QR_PANEL + 1
@@ -146,6 +162,8 @@ __global__ __launch_bounds__(CHOL_THREADS) void panel_chol_inverse_kernel(QrFact
         if (!(piv > 0.0) || !(piv < 1e300)) {            // not positive definite: keep going with a tiny pivot
             if (tid == 0) bad_flag = 1;
             piv = 1e-300;
+        } else if (sweep > 0 && piv < CHOL_REPEAT_MIN) {
+            if (tid == 0) bad_flag = 2;
         }
         const double d = sqrt(piv);
         __syncthreads();                                  // every thread has read the pivot
@@ -177,7 +195,11 @@ __global__ __launch_bounds__(CHOL_THREADS) void panel_chol_inverse_kernel(QrFact
     for (int i = ti; i < rows; i += 16)
         for (int j = tj; j < rows; j += 16)
             F.winv[(size_t)i * QR_PANEL + j] = (j <= i) ? (float)L[i * PITCH + j] : 0.0f;
-    if (tid == 0 && bad_flag) F.bad = 1;
+    if (tid == 0) {
+        if (bad_flag == 1 || (bad_flag == 2 && sweep == 2)) F.bad = 1;
+        if (sweep == 0) F.skip3 = 1;
+        if (sweep == 1 && bad_flag == 2) F.skip3 = 0;
+    }
 }
 
 __global__ void qr_info_kernel(const QrFactor *fs, int nf, int32_t *info, int first)
@@ -453,7 +475,7 @@ extern "C" asteria_status asteria_soap_refresh(const asteria_factor *f, int nfac
             cbuf[i] = cv.take<float>((size_t)QR_PANEL * ldz);
             F.gram = cv.take<double>((size_t)QR_PANEL * QR_PANEL);
             F.winv = cv.take<float>((size_t)QR_PANEL * QR_PANEL);
-            F.Qout = a.X; F.n = n; F.ldz = ldz; F.ldq = a.ldx; F.bad = 0;
+            F.Qout = a.X; F.n = n; F.ldz = ldz; F.ldq = a.ldx; F.bad = 0; F.run = 0; F.skip3 = 1;
             F.tile_start = ttiles;
             const int tpr = (n + 31) / 32;
             ttiles += tpr * tpr;
@@ -483,7 +505,8 @@ extern "C" asteria_status asteria_soap_refresh(const asteria_factor *f, int nfac
                 float *Pt = F.Zt + (size_t)done * F.ldz;
                 GemmProblem p;
                 memset(&p, 0, sizeof(p));
-                p.state_idx = -1; p.state_mask = ~0;
+                // runs while the factor's state word (`run`, or `skip3` in the third sweep) is 0
+                p.state_idx = i * QR_STATE_STRIDE; p.state_mask = 1;
                 // Gram matrix of the panel rows (fp64 accumulation), one symmetric tile
                 p.alpha = 1.0f; p.beta = 0.0f; p.flags = GEMM_SYM;
                 p.M = rows; p.N = rows; p.K = F.n;
@@ -531,16 +554,22 @@ extern "C" asteria_status asteria_soap_refresh(const asteria_factor *f, int nfac
         }
         ASTERIA_HIP_TRY((launch_gemm_grouped<float, float, float, true, false>(d_g, cnt, tiles, nullptr, stream)));
         for (int j = 0; j < np_max; ++j) {
-            if (j > 0) {
-                for (int rep = 0; rep < 2; ++rep) {
-                    ASTERIA_HIP_TRY((launch_gemm_grouped<float, float, float, false, false>(d_t1[j], (int)t1[j].size(), tiles1[j], nullptr, stream)));
-                    ASTERIA_HIP_TRY((launch_gemm_grouped<float, float, float, false, true>(d_t2[j], (int)t2[j].size(), tiles2[j], nullptr, stream)));
+            // sweeps of (project against the finished rows, orthonormalise the panel): the second
+            // projection acts on normalised rows, so what the first normalisation amplified - the
+            // residue of the first projection, O(1) for a row that was numerically dependent - is
+            // removed again and a rank-deficient A Q still yields an orthogonal Q; factors in which
+            // the second sweep met such a row run a third one
+            const int *st_run = reinterpret_cast<const int *>(d_q) + offsetof(QrFactor, run) / sizeof(int);
+            const int *st_third = reinterpret_cast<const int *>(d_q) + offsetof(QrFactor, skip3) / sizeof(int);
+            for (int sweep = 0; sweep < 3; ++sweep) {
+                const int *st = sweep < 2 ? st_run : st_third;
+                if (j > 0) {
+                    ASTERIA_HIP_TRY((launch_gemm_grouped<float, float, float, false, false>(d_t1[j], (int)t1[j].size(), tiles1[j], st, stream)));
+                    ASTERIA_HIP_TRY((launch_gemm_grouped<float, float, float, false, true>(d_t2[j], (int)t2[j].size(), tiles2[j], st, stream)));
                 }
-            }
-            for (int rep = 0; rep < 2; ++rep) {
-                ASTERIA_HIP_TRY((launch_gemm_grouped<double, float, float, false, false>(d_t3[j], (int)t3[j].size(), (int)t3[j].size(), nullptr, stream)));
-                hipLaunchKernelGGL(panel_chol_inverse_kernel, dim3((unsigned)fidx[j].size()), dim3(CHOL_THREADS), chol_lds, stream, d_q, d_fidx[j], j);
-                ASTERIA_HIP_TRY((launch_gemm_grouped<float, float, float, false, true>(d_t4[j], (int)t4[j].size(), tiles4[j], nullptr, stream)));
+                ASTERIA_HIP_TRY((launch_gemm_grouped<double, float, float, false, false>(d_t3[j], (int)t3[j].size(), (int)t3[j].size(), st, stream)));
+                hipLaunchKernelGGL(panel_chol_inverse_kernel, dim3((unsigned)fidx[j].size()), dim3(CHOL_THREADS), chol_lds, stream, d_q, d_fidx[j], j, sweep);
+                ASTERIA_HIP_TRY((launch_gemm_grouped<float, float, float, false, true>(d_t4[j], (int)t4[j].size(), tiles4[j], st, stream)));
             }
         }
         hipLaunchKernelGGL(qr_info_kernel, dim3((cnt + 127) / 128), dim3(128), 0, stream, d_q, cnt, info, first);

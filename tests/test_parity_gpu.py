@@ -488,6 +488,33 @@ def test_soap_refresh_fixed_points_and_batch():
     assert relF(Q2, Q2in) <= 1e-4
 
 
+def test_soap_refresh_rank_deficient_products():
+    # A Q of rank < n: a numerically dependent column (m x m statistic of one m x n gradient, n < m)
+    # still yields an orthogonal Q whose leading columns are the oracle's - what is left of such a
+    # column after the projections is round-off, normalised to some unit vector and orthogonalised
+    # again by the second sweep; a column that is exactly zero cannot be normalised and fails its
+    # factor, and only that factor
+    n = 64
+    A1 = torch.zeros(n, n, device=DEV); A1[:40, :40] = spd(40, 7)
+    G = W.gaussian_block(200, 136, 1.0, DEV, 8)
+    A2 = (0.05 * G @ G.T).contiguous()
+    A3 = spd(96, 9)
+    G4 = W.gaussian_block(512, 64, 1.0, DEV, 10)          # rank 64 of 512: three of four panels are round-off
+    A4 = (0.05 * G4 @ G4.T).contiguous()
+    Qs = [torch.eye(n, device=DEV), torch.eye(200, device=DEV), torch.eye(96, device=DEV), torch.eye(512, device=DEV)]
+    info = torch.full((4,), -1, dtype=torch.int32, device=DEV)
+    ast.soap_refresh([(A1, Qs[0]), (A2, Qs[1]), (A3, Qs[2]), (A4, Qs[3])], info=info)
+    torch.cuda.synchronize()
+    info = info.cpu().numpy()
+    assert info[0] == B.INFO_NOT_PD and np.all(info[1:] == B.INFO_OK), info
+    for A, Q in ((A2, Qs[1]), (A3, Qs[2]), (A4, Qs[3])):
+        k = Q.shape[0]
+        q = np64(Q)
+        assert np.linalg.norm(q.T @ q - np.eye(k)) / math.sqrt(k) <= 1e-5
+        Qo, _ = oracle.soap_refresh(np64(A), np.eye(k))
+        assert np.all(np.sum(q[:, :32] * Qo[:, :32], axis=0) >= 0.999)
+
+
 # =============================================================================== a5 SOAP step
 
 def test_soap_step_same_basis_parity_over_three_steps():
