@@ -141,7 +141,8 @@ const char *asteria_status_string(asteria_status s);
  * For every block: L <- beta L + (1-beta) G G^T and R <- beta R + (1-beta) G^T G, products
  * accumulated in fp32 (bf16 x bf16 products are exact in fp32).  L and R come back exactly
  * symmetric (one triangle is computed, the other mirrored).  Either L or R may be NULL to skip
- * that side.  The workspace only holds the problem tables; 0 <= beta < 1.
+ * that side.  0 <= beta < 1.  The workspace holds the problem tables and, for a bf16 block whose
+ * G is not 16-byte aligned or does not fill whole 128 x 64 tiles, a transposed copy of G.
  * Errors: NULL G, m or n <= 0, ld too small, bad dtype, beta out of range -> INVALID_ARG.   */
 size_t asteria_stats_update_workspace_bytes(const asteria_block *blocks, int nblocks);
 asteria_status asteria_stats_update(const asteria_block *blocks, int nblocks, float beta,
@@ -153,10 +154,12 @@ asteria_status asteria_stats_update(const asteria_block *blocks, int nblocks, fl
  * M_0 = s (A + eps I), X_0 = s^(1/root) I with s = 1 / ((1 + margin) lambda_max + eps), so the
  * spectrum of M_0 lies in [~eps s, 1];  T = a I - g M, X <- X T, M <- T^root M, where (a, g)
  * are chosen per factor and iteration for the interval that holds M's spectrum (or fixed at the
- * Newton values, see `schedule`); a factor stops by itself once its residual ||M - I||_F has
- * fallen below stop_resid (one more X update follows).  The leading fp64_iters iterations use
+ * Newton values, see `schedule`); a factor stops by itself - one more X update follows - once its
+ * residual ||M - I||_F has fallen below stop_resid or the interval predicted for M's spectrum is
+ * within 1 +- 1e-2 (and, under the automatic precision rules, already when the image of that
+ * interval under the next update is within 1 +- 3e-3).  The leading fp64_iters iterations use
  * the fp64 matrix cores, the middle ones the fp32 matrix cores, and the last ones (from
- * `lowp_from` on) the bf16 matrix cores with split operands.
+ * `lowp_from` on) the bf16 matrix cores with every fp32 operand split into two bf16 terms.
  *   eps        host array, eps_count entries (1 = shared by all factors, else nfactors).
  *   info       device int32[nfactors] or NULL   (ASTERIA_INFO_*)
  *   iters      device int32[nfactors] or NULL   (number of X <- X T updates performed)
@@ -184,18 +187,25 @@ asteria_status asteria_inverse_root(const asteria_factor *f, int nfactors, int r
                                     void *ws, size_t ws_bytes, void *stream);
 
 /* ---- preconditioned update (paper Eq. 1) ---------------------------------------------------
- * For every block: P = X_L G X_R, X_L and X_R symmetric fp32, fp32 matrix-core products with
- * fp32 accumulation; P is written as fp32 or bf16 (round to nearest even).
+ * For every block: P = X_L G X_R, X_L and X_R symmetric fp32; P is written as fp32 or bf16
+ * (round to nearest even).  fp32 gradients: fp32 matrix cores.  bf16 gradients: bf16 matrix cores
+ * with fp32 accumulation, G exact and every fp32 operand (X_L, X_R, the intermediate) split into
+ * two bf16 terms, which keeps about 16 bits of it (measured 5e-6 .. 9e-6 relative error in P).
  * Workspace holds the intermediate G X_R of every block (fp32, m x n each).                 */
 size_t asteria_precondition_workspace_bytes(const asteria_pblock *blocks, int nblocks);
 asteria_status asteria_precondition(const asteria_pblock *blocks, int nblocks,
                                     void *ws, size_t ws_bytes, void *stream);
 
 /* ---- SOAP eigenbasis refresh (paper Eq. 2) -------------------------------------------------
- * For every factor: Z = A Q (one power iteration), Z = Q' R by Householder QR, column signs
- * chosen so that diag(R) >= 0, and Q <- Q' in place (f[i].X is Q).
- *   info  device int32[nfactors] or NULL (ASTERIA_INFO_OK, or ASTERIA_INFO_NOT_PD if a
- *         non-finite value was met).                                                         */
+ * For every factor: Z = A Q (one power iteration), Z = Q' R the QR factorisation with
+ * diag(R) >= 0 (unique for a Z of full rank: the Q' a Householder QR with that sign convention
+ * returns), and Q <- Q' in place (f[i].X is Q).  Computed by block Gram-Schmidt with
+ * re-orthogonalisation over panels of 128 columns (fp32 matrix cores; panel Gram matrices and
+ * their Cholesky factors in fp64).  Columns of Z beyond its numerical rank come out as an
+ * orthonormal completion.
+ *   info  device int32[nfactors] or NULL (ASTERIA_INFO_OK, or ASTERIA_INFO_NOT_PD if a column
+ *         could not be normalised: an exactly zero or non-finite column, or one that three
+ *         sweeps of re-orthogonalisation did not separate from the columns before it).       */
 size_t asteria_soap_refresh_workspace_bytes(const asteria_factor *f, int nfactors, size_t *min_bytes);
 asteria_status asteria_soap_refresh(const asteria_factor *f, int nfactors, int32_t *info,
                                     void *ws, size_t ws_bytes, void *stream);
@@ -203,7 +213,10 @@ asteria_status asteria_soap_refresh(const asteria_factor *f, int nfactors, int32
 /* ---- SOAP step (paper Eq. 2, phi = Adam in the rotated basis) ------------------------------
  * For every block, with step_t >= 1:
  *   G' = Q_L^T G Q_R;  M <- beta1 M + (1-beta1) G';  V <- beta2 V + (1-beta2) G' o G';
- *   N' = (M / (1-beta1^t)) / (sqrt(V / (1-beta2^t)) + adam_eps);  N = Q_L N' Q_R^T.          */
+ *   N' = (M / (1-beta1^t)) / (sqrt(V / (1-beta2^t)) + adam_eps);  N = Q_L N' Q_R^T.
+ * The four rotations run on the bf16 matrix cores with fp32 accumulation and every fp32 operand
+ * split into two bf16 terms (bf16 G exact): about 16 bits of Q_L, Q_R and of the intermediates.
+ * Workspace: G', N', one intermediate and the transposes of Q_L, Q_R of every block.          */
 size_t asteria_soap_step_workspace_bytes(const asteria_sblock *blocks, int nblocks);
 asteria_status asteria_soap_step(const asteria_sblock *blocks, int nblocks,
                                  float beta1, float beta2, float adam_eps, int step_t,
