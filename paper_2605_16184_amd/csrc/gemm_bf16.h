@@ -67,7 +67,15 @@ struct Bf16Stage {
     static constexpr int EPV = Elem<TI>::EPV;              // 8 (bf16) or 4 (fp32) elements per 16 bytes
     static constexpr int VPR = BK / EPV;
     static constexpr int NV = BM * VPR / 256;
-    static constexpr int PITCH = BK + 8;                   // bf16 elements; 16-byte pad keeps reads conflict free
+    // LDS rows are unpadded (BK elements); the 16-byte chunks of a row are XOR-swizzled by the row
+    // index instead: the loader's lanes then write whole contiguous rows (4 rows = 256 bytes = all
+    // 64 banks per 32 lanes), and the 16 rows a quarter-wavefront reads for one fragment chunk fall
+    // into 16 distinct 16-byte bank groups.  (A 16-byte pad per row made the 8-byte stores of the
+    // split terms collide two ways: a third of the LDS cycles of this kernel were conflicts.)
+    static constexpr int PITCH = BK;
+    static constexpr int CPR = BK / 8;                     // 16-byte chunks per row
+    __device__ static __forceinline__ int swz(int row) { return (row / (16 / CPR)) % CPR; }
+    static_assert(CPR == 4 || CPR == 8, "swizzle geometry");
     static constexpr int TERM_ELEMS = BM * PITCH;
     static constexpr int LDS_ELEMS = NT * TERM_ELEMS;      // per stage
     static_assert(NV >= 1, "slab too small");
@@ -95,7 +103,9 @@ struct Bf16Stage {
         for (int v = 0; v < NV; ++v) {
             const int idx = tid + 256 * v;
             const int a = idx / VPR, b = idx % VPR;
-            ASTERIA_LDS uint16_t *dst = lds + a * PITCH + b * EPV;
+            // bf16 source: vector b is chunk b; fp32 source: vector b is half (b % 2) of chunk b / 2
+            const int chunk = (sizeof(TI) == 2) ? b : (b >> 1);
+            ASTERIA_LDS uint16_t *dst = lds + a * PITCH + ((chunk ^ swz(a)) << 3) + ((sizeof(TI) == 2) ? 0 : (b & 1) * 4);
             if (sizeof(TI) == 2) {
                 *(ASTERIA_LDS u32x4 *)dst = r[v];
             } else {
@@ -141,17 +151,19 @@ __device__ __forceinline__ void gemm_bf16_mainloop(floatx16 (&acc)[2][2], const 
         const ASTERIA_LDS uint16_t *bs = smemB + cur * StB::LDS_ELEMS;
 #pragma unroll
         for (int s = 0; s < (TRI == TRI_NONE ? 0 : STEPS); ++s) {
-            const int kk = h * KPL + s * 8;      // the lane half owns a contiguous k range of the slab
+            const int ck = h * (KPL / 8) + s;    // the lane half owns a contiguous k range of the slab: chunk index
             u32x4 ah[2], al[2], bh[2], bl[2];
 #pragma unroll
             for (int i = 0; i < 2; ++i) {
                 const int rr = wm * 64 + i * 32 + r;
+                const int kk = (ck ^ StA::swz(rr)) << 3;
                 ah[i] = *(const ASTERIA_LDS u32x4 *)(as + rr * StA::PITCH + kk);
                 if (NTA == 2) al[i] = *(const ASTERIA_LDS u32x4 *)(as + StA::TERM_ELEMS + rr * StA::PITCH + kk);
             }
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
                 const int cc = wn * 64 + j * 32 + r;
+                const int kk = (ck ^ StB::swz(cc)) << 3;
                 bh[j] = *(const ASTERIA_LDS u32x4 *)(bs + cc * StB::PITCH + kk);
                 if (NTB == 2) bl[j] = *(const ASTERIA_LDS u32x4 *)(bs + StB::TERM_ELEMS + cc * StB::PITCH + kk);
             }
@@ -187,7 +199,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_grouped_kernel(const GemmProble
     extern __shared__ __align__(16) unsigned char smem_raw[];
     ASTERIA_LDS uint16_t *smem = (ASTERIA_LDS uint16_t *)smem_raw;
     // the reduction scratch of the epilogue reuses the operand buffer (free after the K loop): with
-    // no static LDS two workgroups of the split variants (80 KiB each) fit one CU's 160 KiB
+    // no static LDS two workgroups of the split variants (64 KiB each) fit one CU's 160 KiB
     float *red = reinterpret_cast<float *>(smem_raw);
 
     const int per_xcd = (total_tiles + NUM_XCD - 1) / NUM_XCD;
