@@ -26,6 +26,10 @@ sys.path.insert(0, ROOT)
 PEAK_F32_MFMA = 157.3   # TFLOP/s, MI355X dense fp32 matrix
 PEAK_F64_MFMA = 78.6    # TFLOP/s, MI355X dense fp64 matrix
 PEAK_BF16_MFMA = 2500.0 # TFLOP/s, MI355X dense bf16 matrix
+# What a register-only loop of v_mfma_f64_16x16x4_f64 with random operands sustains on the box
+# (2 or 4 wavefronts per SIMD, 8 independent accumulators each, 2.38 GHz): context for the fp64
+# kernel's fraction of the published peak, never used as `peak`.
+MEASURED_F64_MFMA_LOOP = 58.8
 PEAK_HBM = 8000.0       # GB/s
 
 
@@ -241,6 +245,7 @@ def main() -> int:
         "roofline_fp64": {"kernel": "gemm_grouped_kernel<double> (fp64-MFMA products of the leading root iterations)",
                           "bound": "mfma", "achieved": round(tf64, 2), "peak": PEAK_F64_MFMA, "unit": "TFLOP/s",
                           "frac": round(tf64 / PEAK_F64_MFMA, 4), "traffic": stored_traffic("traffic_bytes_per_launch_fp64"),
+                          "instruction_loop_tflops_measured": MEASURED_F64_MFMA_LOOP,
                           "launches": len(k64), "avg_launch_ms": round(1e3 * t64 / max(len(k64), 1), 4),
                           "flops_per_launch": round(flops64 / max(len(k64), 1), 1)},
         "roofline_split_bf16": {"kernel": "gemm_bf16_grouped_kernel<float, float, 2, 2> (X updates and late root iterations: "
