@@ -26,9 +26,11 @@
  *   - `ws` is caller-owned device scratch of `ws_bytes` bytes, 256-byte aligned; the matching
  *     *_workspace_bytes query returns the size that lets the whole batch run in one pass and
  *     (where a min_bytes pointer is given) the smallest size the call accepts.  The library
- *     itself allocates no device memory and keeps no state between calls.
+ *     itself allocates no device memory and keeps no state between calls (apart from the two
+ *     internal streams of asteria_soap_refresh and the measurement aid at the end of this file).
  *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  All work is
- *     enqueued on it; no entry point waits for the device.  A call may stage its descriptor
+ *     enqueued on it (asteria_soap_refresh: or on internal streams ordered after and before it);
+ *     no entry point waits for the device.  A call may stage its descriptor
  *     tables with hipMemcpyAsync from host memory it owns until the call returns.
  *   - The return value reports argument / launch errors only (nothing was enqueued when it
  *     is ASTERIA_INVALID_ARG, ASTERIA_UNSUPPORTED or ASTERIA_WORKSPACE_TOO_SMALL).  Numerical
@@ -202,7 +204,9 @@ asteria_status asteria_precondition(const asteria_pblock *blocks, int nblocks,
  * returns), and Q <- Q' in place (f[i].X is Q).  Computed by block Gram-Schmidt with
  * re-orthogonalisation over panels of 128 columns (fp32 matrix cores; panel Gram matrices and
  * their Cholesky factors in fp64).  Columns of Z beyond its numerical rank come out as an
- * orthonormal completion.
+ * orthonormal completion.  The factors are worked on in two groups on two internal streams
+ * (created once per device, default priority) that start after everything already enqueued on
+ * `stream` and that `stream` waits for before the call's work counts as done on it.
  *   info  device int32[nfactors] or NULL (ASTERIA_INFO_OK, or ASTERIA_INFO_NOT_PD if a column
  *         could not be normalised: an exactly zero or non-finite column, or one that three
  *         sweeps of re-orthogonalisation did not separate from the columns before it).       */

@@ -119,6 +119,8 @@ struct QrFactor {
     // is 0): `run` stays 0; `skip3` is 1 unless the second sweep over the current panel found a row
     // that needs a third one.
     int run, skip3;
+    int out_index;  // position of this factor in the caller's arrays
+    int pad_;
 };
 constexpr int QR_STATE_STRIDE = (int)(sizeof(QrFactor) / sizeof(int));
 static_assert(sizeof(QrFactor) % sizeof(int) == 0, "state words are addressed as ints inside the factor array");
@@ -202,10 +204,10 @@ __global__ __launch_bounds__(CHOL_THREADS) void panel_chol_inverse_kernel(QrFact
     }
 }
 
-__global__ void qr_info_kernel(const QrFactor *fs, int nf, int32_t *info, int first)
+__global__ void qr_info_kernel(const QrFactor *fs, int nf, int32_t *info)
 {
     const int f = blockIdx.x * blockDim.x + threadIdx.x;
-    if (f < nf && info) info[first + f] = fs[f].bad ? ASTERIA_INFO_NOT_PD : ASTERIA_INFO_OK;
+    if (f < nf && info) info[fs[f].out_index] = fs[f].bad ? ASTERIA_INFO_NOT_PD : ASTERIA_INFO_OK;
 }
 
 // Q[i][c] = Zt[c][i], 32 x 32 tiles through LDS
@@ -395,10 +397,37 @@ size_t refresh_factor_bytes(int n)
            (size_t)(1 + 4 * np) * sizeof(GemmProblem) + (size_t)np * sizeof(int) + sizeof(QrFactor);
 }
 
+// Two auxiliary streams (default priority) and the events that fork them from and join them to
+// the caller's stream, created once per device and kept for the life of the process.
+constexpr int REFRESH_GROUPS = 2;   // 4 groups: 328 ms against 318 (every group brings its own chain of launches)
+struct RefreshStreams {
+    hipStream_t s[REFRESH_GROUPS];
+    hipEvent_t fork, join[REFRESH_GROUPS];
+};
+RefreshStreams *refresh_streams()
+{
+    constexpr int MAX_DEV = 64;
+    static RefreshStreams cache[MAX_DEV];
+    static bool ready[MAX_DEV] = {};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEV) return nullptr;
+    if (!ready[dev]) {
+        RefreshStreams r;
+        if (hipEventCreateWithFlags(&r.fork, hipEventDisableTiming) != hipSuccess) return nullptr;
+        for (int g = 0; g < REFRESH_GROUPS; ++g) {
+            if (hipStreamCreateWithFlags(&r.s[g], hipStreamNonBlocking) != hipSuccess) return nullptr;
+            if (hipEventCreateWithFlags(&r.join[g], hipEventDisableTiming) != hipSuccess) return nullptr;
+        }
+        cache[dev] = r;
+        ready[dev] = true;
+    }
+    return &cache[dev];
+}
+
 size_t refresh_fixed_bytes(int n_max)
 {
     const int np = (n_max + QR_PANEL - 1) / QR_PANEL;
-    return (size_t)(5 * np + 4) * 256 + 4096;   // alignment slack of the per-panel tables
+    return REFRESH_GROUPS * ((size_t)(5 * np + 4) * 256 + 4096);   // alignment slack of the per-panel tables, per group
 }
 
 }  // namespace
@@ -456,11 +485,18 @@ extern "C" asteria_status asteria_soap_refresh(const asteria_factor *f, int nfac
             ++cnt;
         }
         if (cnt == 0) return ASTERIA_WORKSPACE_TOO_SMALL;
+        // The factors of a pass are dealt to two groups, each enqueued as a whole on a stream of its
+        // own: the panel steps of a group are a chain of small launches (projection, Gram matrix,
+        // a latency-bound Cholesky kernel on one workgroup per factor, application), and two chains
+        // running side by side fill the gaps each leaves on the device.
+        Carver cv(ws);
+        auto enqueue_group = [&](const std::vector<int> &idx, hipStream_t stream) -> asteria_status {
+        const int cnt = (int)idx.size();
+        if (cnt == 0) return ASTERIA_OK;
         int n_max = 0;
-        for (int i = 0; i < cnt; ++i) n_max = std::max(n_max, f[first + i].n);
+        for (int i = 0; i < cnt; ++i) n_max = std::max(n_max, f[idx[i]].n);
         const int np_max = (n_max + QR_PANEL - 1) / QR_PANEL;
 
-        Carver cv(ws);
         GemmProblem *d_g = cv.take<GemmProblem>(cnt);
         QrFactor *d_q = cv.take<QrFactor>(cnt);
         std::vector<GemmProblem> g;
@@ -468,7 +504,7 @@ extern "C" asteria_status asteria_soap_refresh(const asteria_factor *f, int nfac
         std::vector<float *> cbuf(cnt);
         int tiles = 0, ttiles = 0;
         for (int i = 0; i < cnt; ++i) {
-            const asteria_factor &a = f[first + i];
+            const asteria_factor &a = f[idx[i]];
             const int n = a.n, ldz = ld4(n);
             QrFactor F;
             F.Zt = cv.take<float>((size_t)n * ldz);
@@ -476,6 +512,7 @@ extern "C" asteria_status asteria_soap_refresh(const asteria_factor *f, int nfac
             F.gram = cv.take<double>((size_t)QR_PANEL * QR_PANEL);
             F.winv = cv.take<float>((size_t)QR_PANEL * QR_PANEL);
             F.Qout = a.X; F.n = n; F.ldz = ldz; F.ldq = a.ldx; F.bad = 0; F.run = 0; F.skip3 = 1;
+            F.out_index = idx[i]; F.pad_ = 0;
             F.tile_start = ttiles;
             const int tpr = (n + 31) / 32;
             ttiles += tpr * tpr;
@@ -572,9 +609,32 @@ extern "C" asteria_status asteria_soap_refresh(const asteria_factor *f, int nfac
                 ASTERIA_HIP_TRY((launch_gemm_grouped<float, float, float, false, true>(d_t4[j], (int)t4[j].size(), tiles4[j], st, stream)));
             }
         }
-        hipLaunchKernelGGL(qr_info_kernel, dim3((cnt + 127) / 128), dim3(128), 0, stream, d_q, cnt, info, first);
+        hipLaunchKernelGGL(qr_info_kernel, dim3((cnt + 127) / 128), dim3(128), 0, stream, d_q, cnt, info);
         hipLaunchKernelGGL(transpose_out_kernel, dim3(ttiles), dim3(256), 0, stream, d_q, cnt);
         ASTERIA_HIP_TRY(hipGetLastError());
+        return ASTERIA_OK;
+        };
+        std::vector<int> grp[REFRESH_GROUPS];
+        for (int i = 0; i < cnt; ++i) grp[i % REFRESH_GROUPS].push_back(first + i);
+        RefreshStreams *rs = refresh_streams();
+        if (!rs || cnt < REFRESH_GROUPS) {
+            std::vector<int> all(cnt);
+            for (int i = 0; i < cnt; ++i) all[i] = first + i;
+            const asteria_status st = enqueue_group(all, stream);
+            if (st != ASTERIA_OK) return st;
+        } else {
+            // fork: both auxiliary streams start after everything already enqueued on the caller's
+            // stream (the previous pass included); join: the caller's stream continues after both
+            ASTERIA_HIP_TRY(hipEventRecord(rs->fork, stream));
+            for (int g2 = 0; g2 < REFRESH_GROUPS; ++g2) {
+                ASTERIA_HIP_TRY(hipStreamWaitEvent(rs->s[g2], rs->fork, 0));
+                const asteria_status st = enqueue_group(grp[g2], rs->s[g2]);
+                if (st != ASTERIA_OK) return st;
+                ASTERIA_HIP_TRY(hipEventRecord(rs->join[g2], rs->s[g2]));
+                ASTERIA_HIP_TRY(hipStreamWaitEvent(stream, rs->join[g2], 0));
+            }
+        }
+
         first += cnt;
     }
     return ASTERIA_OK;
