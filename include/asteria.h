@@ -32,6 +32,8 @@
  *     enqueued on it (asteria_soap_refresh: or on internal streams ordered after and before it);
  *     no entry point waits for the device.  A call may stage its descriptor
  *     tables with hipMemcpyAsync from host memory it owns until the call returns.
+ *   - Entry points are not re-entrant: call them from one host thread at a time (they cache
+ *     per-kernel launch attributes, and asteria_soap_refresh its internal streams, in statics).
  *   - The return value reports argument / launch errors only (nothing was enqueued when it
  *     is ASTERIA_INVALID_ARG, ASTERIA_UNSUPPORTED or ASTERIA_WORKSPACE_TOO_SMALL).  Numerical
  *     outcomes are per factor and device-side (`info`, `iters`, `resid`, `lambda_max`).
