@@ -282,6 +282,33 @@ def test_root_mixed_batch_multiple_passes_and_padded_outputs():
     assert e.value.status == B.WORKSPACE_TOO_SMALL
 
 
+def test_root_spectra_that_stress_the_stop_rules():
+    # spectra for which a stop test based on the interval predicted for M could stop too early or the
+    # adapted coefficients could misbehave: one dominant eigenvalue over a floor far below eps; two
+    # tight clusters three decades apart; a flat spectrum (kappa = 1); a gap right at eps
+    n = 256
+    U = W.haar(n, DEV, 60, dtype=torch.float64)
+    def build(lam):
+        A = (U * lam) @ U.T
+        return (0.5 * (A + A.T)).float().contiguous()
+    one = torch.ones(n, device=DEV, dtype=torch.float64)
+    spectra = {
+        "spike": torch.cat([torch.tensor([1.0], device=DEV, dtype=torch.float64), 1e-9 * one[1:]]),
+        "clusters": torch.cat([1.0 + 1e-3 * torch.arange(n // 2, device=DEV, dtype=torch.float64) / n,
+                               1e-3 * (1.0 + 1e-3 * torch.arange(n // 2, device=DEV, dtype=torch.float64) / n)]),
+        "flat": 0.37 * one,
+        "gap at eps": torch.cat([torch.linspace(1.0, 0.1, n // 2, device=DEV, dtype=torch.float64), 1e-6 * one[: n // 2]]),
+    }
+    As = [build(lam) for lam in spectra.values()]
+    for schedule in (1, 0):
+        Xs, info, iters, resid, _ = run_roots(As, 1e-6, opts=ast.RootOpts(schedule=schedule))
+        Xo, _, status = oracle.inverse_root_batch([np64(A) for A in As], 1e-6)
+        assert np.all(status == oracle.OK) and np.all(info == B.INFO_OK), (schedule, info)
+        errs = {k: relF(X, Xo[i]) for i, (k, X) in enumerate(zip(spectra, Xs))}
+        print("stop-rule stress, schedule", schedule, "iters", iters, errs)
+        assert max(errs.values()) <= TOL_ROOT, (schedule, errs)
+
+
 def test_root_failure_reporting_is_per_factor():
     good = powerlaw_factor(96, 50)
     bad = good.clone()
