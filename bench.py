@@ -25,7 +25,7 @@ sys.path.insert(0, ROOT)
 
 PEAK_F32_MFMA = 157.3   # TFLOP/s, MI355X dense fp32 matrix
 PEAK_F64_MFMA = 78.6    # TFLOP/s, MI355X dense fp64 matrix
-PEAK_BF16_MFMA = 2500.0 # TFLOP/s, MI355X dense bf16 matrix
+PEAK_BF16_MFMA = 2500.0 # TFLOP/s, MI355X dense bf16 and fp16 matrix
 # What a register-only loop of v_mfma_f64_16x16x4_f64 with random operands sustains on the box
 # (2 or 4 wavefronts per SIMD, 8 independent accumulators each, 2.38 GHz): context for the fp64
 # kernel's fraction of the published peak, never used as `peak`.
@@ -55,10 +55,10 @@ def sym_gemm_flops(n: int) -> float:
 
 
 def newton_gemm_counts(iters: int, j64: int, jlow: int, xt_lowp: bool):
-    """(fp32 GEMMs, fp64 GEMMs, split-bf16 GEMMs) a factor executed: iteration k < iters does
+    """(fp32 GEMMs, fp64 GEMMs, split-fp16 GEMMs) a factor executed: iteration k < iters does
     X <- X T (except k = 0, where X_1 is written by the start kernel), and for k < iters - 1 also
-    the M-chain T^2, T^4 and T^4 M; the chain runs on the fp64 cores for k < j64 and on the bf16
-    cores for k >= jlow; X <- X T runs on the bf16 cores when xt_lowp, else with its iteration's
+    the M-chain T^2, T^4 and T^4 M; the chain runs on the fp64 cores for k < j64 and on the fp16
+    cores (two-term split operands) for k >= jlow; X <- X T runs there too when xt_lowp, else with its iteration's
     tier (fp32 at least)."""
     g32 = g64 = g16 = 0
     for k in range(iters):
@@ -86,7 +86,7 @@ def main() -> int:
     ap.add_argument("--ws-gib", type=float, default=96.0, help="workspace handed to the library (a single pass needs about 90 GiB)")
     ap.add_argument("--max-blocks", type=int, default=0, help="debug: truncate the batch")
     ap.add_argument("--fp64-iters", type=int, default=-1)
-    ap.add_argument("--lowp-from", type=int, default=-1, help="first iteration on the bf16 cores (-1 = library rule)")
+    ap.add_argument("--lowp-from", type=int, default=-1, help="first iteration on the fp16 cores with split operands (-1 = library rule)")
     ap.add_argument("--schedule", type=int, default=1, help="1 = interval-adapted coefficients, 0 = classical Newton")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-soap", action="store_true", help="skip the SOAP section (blocks <= 2048)")
@@ -196,7 +196,7 @@ def main() -> int:
 
     k32 = [ms for ms, kind in prof if kind == 0]
     k64 = [ms for ms, kind in prof if kind == 1]
-    k16 = [ms for ms, kind in prof if kind == 224]       # bf16 cores, both operands fp32 split in two terms
+    k16 = [ms for ms, kind in prof if kind == 224]       # 16-bit cores, both operands fp32 split in two fp16 terms
     t16 = sum(k16) * 1e-3
     tf16 = flops16 / t16 / 1e12 if t16 > 0 else 0.0
     t32, t64 = sum(k32) * 1e-3, sum(k64) * 1e-3
@@ -210,7 +210,7 @@ def main() -> int:
     log(f"[bench] stats {stats_ms:.2f} ms  refresh {refresh_ms:.1f} ms  precondition {precond_ms:.2f} ms")
     log(f"[bench] fp32 GEMM: {len(k32)} launches, {t32 * 1e3:.1f} ms total, {tf32:.1f} TFLOP/s algorithmic; "
         f"fp64 GEMM: {len(k64)} launches, {t64 * 1e3:.1f} ms total, {tf64:.1f} TFLOP/s; "
-        f"split-bf16 GEMM: {len(k16)} launches, {t16 * 1e3:.1f} ms total, {tf16:.1f} fp32-equivalent TFLOP/s")
+        f"split-fp16 GEMM: {len(k16)} launches, {t16 * 1e3:.1f} ms total, {tf16:.1f} fp32-equivalent TFLOP/s")
     log(f"[bench] Newton iterations min/mean/max {it.min()}/{it.mean():.1f}/{it.max()}, info!=0: {(info_h != 0).sum()}")
 
     out = {
@@ -228,7 +228,7 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": "1.1B LLaMA-style model, all 2-D grads blocked at <=1024 (1184 blocks, 2368 factors), "
                                "bf16 power-law gradients, fp32 statistics, eps=1e-6*lambda_max, beta=0.95",
-                   "blocks": len(shapes), "factors": nf, "fp64_prefix_iters": j64, "bf16_split_from_iter": jlow, "x_update_on_bf16_cores": xt_lowp,
+                   "blocks": len(shapes), "factors": nf, "fp64_prefix_iters": j64, "fp16_split_from_iter": jlow, "x_update_on_fp16_cores": xt_lowp,
                    "schedule": "interval-adapted" if args.schedule == 1 else "classical Newton",
                    "workspace_gib": round(ws_bytes / 2**30, 1)},
         "breakdown_ms": {"stats_update": round(stats_ms, 3), "inverse_root": round(refresh_ms, 3),
@@ -248,16 +248,16 @@ def main() -> int:
                           "instruction_loop_tflops_measured": MEASURED_F64_MFMA_LOOP,
                           "launches": len(k64), "avg_launch_ms": round(1e3 * t64 / max(len(k64), 1), 4),
                           "flops_per_launch": round(flops64 / max(len(k64), 1), 1)},
-        "roofline_split_bf16": {"kernel": "gemm_bf16_grouped_kernel<float, float, 2, 2> (X updates and late root iterations: "
-                                          "fp32 operands split in two bf16 terms, 3 bf16 MFMA passes per product)",
+        "roofline_split_fp16": {"kernel": "gemm_bf16_grouped_kernel<float, float, 2, 2, fp16> (X updates and the root iterations "
+                                          "after the fp64 prefix: fp32 operands split in two fp16 terms, 3 fp16 MFMA passes per product)",
                                 "bound": "mfma", "achieved": round(3 * tf16, 2), "peak": PEAK_BF16_MFMA,
-                                "unit": "TFLOP/s (bf16 MFMA issued)", "frac": round(3 * tf16 / PEAK_BF16_MFMA, 4),
+                                "unit": "TFLOP/s (fp16 MFMA issued)", "frac": round(3 * tf16 / PEAK_BF16_MFMA, 4),
                                 "fp32_equivalent_tflops": round(tf16, 2),
-                                "traffic": stored_traffic("traffic_bytes_per_launch_bf16"), "launches": len(k16),
+                                "traffic": stored_traffic("traffic_bytes_per_launch_fp16"), "launches": len(k16),
                                 "avg_launch_ms": round(1e3 * t16 / max(len(k16), 1), 4),
                                 "flops_per_launch": round(3 * flops16 / max(len(k16), 1), 1)},
         "gemm_time_share_ms_per_step": {"fp32": round(1e3 * t32 / args.steps, 1), "fp64": round(1e3 * t64 / args.steps, 1),
-                                        "split_bf16": round(1e3 * t16 / args.steps, 1)},
+                                        "split_fp16": round(1e3 * t16 / args.steps, 1)},
         "roofline_stats": {"bound": "hbm", "achieved": round(stats_bytes / stats_ms / 1e6, 1), "peak": PEAK_HBM,
                            "unit": "GB/s", "frac": round(stats_bytes / stats_ms / 1e6 / PEAK_HBM, 4),
                            "tflops": round(stats_flops / stats_ms / 1e9, 1)},
@@ -270,7 +270,9 @@ def main() -> int:
     }
 
     # `roofline` = the kernel that takes the largest share of the timed region
-    shares = {"roofline_fp32": t32, "roofline_fp64": t64, "roofline_split_bf16": t16}
+    shares = {"roofline_fp32": t32, "roofline_fp64": t64, "roofline_split_fp16": t16}
+    if not k32:
+        del out["roofline_fp32"], shares["roofline_fp32"]     # the default precision rules launch no fp32 product
     dominant = max(shares, key=shares.get)
     out["roofline"] = dict(out[dominant], time_share_of_step=round(1e3 * shares[dominant] / args.steps / step_ms, 4))
 

@@ -130,9 +130,9 @@ typedef struct asteria_root_opts {
     float power_tol;       /* power iteration stops at ||A v - rho v|| <= power_tol * rho (default 1e-3) */
     float lambda_margin;   /* spectrum is scaled by 1 / ((1 + lambda_margin) lambda_max + eps)
                               (default 0.01) so an underestimated lambda_max stays inside (0, 1]      */
-    int32_t lowp_from;     /* first iteration that may run on the bf16 matrix cores with the fp32 operands
-                              split into two bf16 terms (16 bits kept): -1 = choose from eps (default: once
-                              the bottom of M's spectrum is above 1e-3 and n <= 2048; never for absolute eps),
+    int32_t lowp_from;     /* first iteration that may run on the fp16 matrix cores with the fp32 operands
+                              split into two fp16 terms (22 bits kept): -1 = choose from eps (default: right
+                              after the fp64 prefix, n <= 16384; never for absolute eps),
                               >= max_iters = never                                                      */
 } asteria_root_opts;
 
@@ -163,7 +163,9 @@ asteria_status asteria_stats_update(const asteria_block *blocks, int nblocks, fl
  * within 1 +- 1e-2 (and, under the automatic precision rules, already when the image of that
  * interval under the next update is within 1 +- 3e-3).  The leading fp64_iters iterations use
  * the fp64 matrix cores, the middle ones the fp32 matrix cores, and the last ones (from
- * `lowp_from` on) the bf16 matrix cores with every fp32 operand split into two bf16 terms.
+ * `lowp_from` on) the fp16 matrix cores with every fp32 operand split into two fp16 terms (scaled
+ * into the fp16 range by a power of two that the call derives from the bounds it keeps on M and X;
+ * the operands are kept to 2^-22).
  *   eps        host array, eps_count entries (1 = shared by all factors, else nfactors).
  *   info       device int32[nfactors] or NULL   (ASTERIA_INFO_*)
  *   iters      device int32[nfactors] or NULL   (number of X <- X T updates performed)
@@ -175,8 +177,8 @@ asteria_status asteria_stats_update(const asteria_block *blocks, int nblocks, fl
  * in {1, nfactors} -> INVALID_ARG / UNSUPPORTED; ws too small -> WORKSPACE_TOO_SMALL.        */
 /* The precision schedule asteria_inverse_root would use for these arguments (host only, nothing is
  * launched): number of leading fp64 iterations of the M-chain (T^2, T^4, T^4 M), first iteration of
- * that chain on the bf16 matrix cores (>= max_iters = never; factors larger than 2048 stay on the
- * fp32 cores under the automatic rule), and whether every X <- X T product runs on the bf16 cores
+ * that chain on the fp16 matrix cores (>= max_iters = never; factors larger than 16384 stay on the
+ * fp32 cores under the automatic rule), and whether every X <- X T product runs on the fp16 cores
  * with split operands (1) or in the precision tier of its iteration, fp32 at least (0).  X is
  * stored in fp32 in every tier.  Any of the three outputs may be NULL.                          */
 asteria_status asteria_inverse_root_plan(int root, asteria_eps_mode mode, const float *eps, int eps_count,

@@ -276,8 +276,8 @@ def inverse_root_workspace_bytes(factors, opts: Optional[RootOpts] = None):
 
 
 def inverse_root_plan(eps, relative: bool = True, root: int = 4, opts: Optional[RootOpts] = None):
-    """(fp64 prefix length of the M-chain, its first iteration on the bf16 matrix cores, whether every
-    X update runs on the bf16 cores) as the library would choose."""
+    """(fp64 prefix length of the M-chain, its first iteration on the fp16 matrix cores with split
+    operands, whether every X update runs there) as the library would choose."""
     eps_list = [float(eps)] if not isinstance(eps, (Sequence, torch.Tensor)) else [float(e) for e in eps]
     eps_arr = (c_float * len(eps_list))(*eps_list)
     j64, jl, xt = c_int32(0), c_int32(0), c_int32(0)

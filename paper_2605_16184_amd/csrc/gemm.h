@@ -55,6 +55,7 @@ struct GemmProblem {
     float *C3;          // root epilogue: optional fp32 copy of C2
     float *partial;
     const float *coef;  // root epilogue: device pointer to (a, g), or null to use ep_a / ep_g
+    const float *sa_dev; // fp16-split kernel: device pointer to the scale of operand A, or null to use sa
     int M, N, K;
     int lda, ldb, ldc, ldc2, ldc3;
     int tile_start;  // id of this problem's first tile within the launch
@@ -64,6 +65,7 @@ struct GemmProblem {
     float alpha, beta;
     float ep_a, ep_g;
     int flags;
+    float sa, sb;       // fp16-split kernel: powers of two the operands are multiplied by before the split
 };
 
 // Measurement aid (see asteria_profile_enable): bracket a launch with HIP events on its stream.

@@ -6,6 +6,13 @@
 // lo = bf16(x - hi)): with two terms per operand the kernel issues hi*hi, hi*lo and lo*hi, which
 // keeps 16 to 18 bits of the fp32 operands at three bf16 MFMA passes.
 //
+// With F16 = true the two terms of an fp32 operand are fp16 instead of bf16 (v_mfma_f32_32x32x16_f16):
+// 11 + 11 significant bits instead of 8 + 8, i.e. the operand to 2^-22, close to fp32, at the same
+// three passes.  fp16 has a 5-bit exponent, so each operand is first multiplied by a power of two
+// that brings its largest entries near the top of the fp16 range (the caller knows a bound) and the
+// accumulators are divided by the product of the two scales afterwards; entries more than 2^-25 of
+// the bound below it lose relative, not absolute, accuracy.
+//
 // Workgroup = 256 threads = 2 x 2 wavefronts of 64 x 64 (2 x 2 MFMA tiles each), K slabs of 64
 // (32 when operands are split, to fit both terms of both operands in LDS twice).
 #pragma once
@@ -14,6 +21,7 @@
 namespace asteria {
 
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x8_t __attribute__((ext_vector_type(8)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 struct MmaBf16 {
@@ -27,6 +35,11 @@ struct MmaBf16 {
     {
         return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, a),
                                                        __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
+    }
+    __device__ static __forceinline__ acc_t mma_f16(u32x4 a, u32x4 b, acc_t c)
+    {
+        return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8_t, a), __builtin_bit_cast(f16x8_t, b),
+                                                      c, 0, 0, 0);
     }
     __device__ static __forceinline__ int acc_row(int v, int h) { return 8 * (v >> 2) + 4 * h + (v & 3); }
 };
@@ -61,9 +74,25 @@ __device__ __forceinline__ void split4(u32x4 x, u32x2 &hi, u32x2 &lo, bool want_
     }
 }
 
-// One operand tile (128 rows x BK) of input type TI staged as bf16 terms in LDS.
-template <typename TI, int NT, int BK>
+// the same split into two fp16 terms of x * scale (round to nearest in both)
+__device__ __forceinline__ void split4_f16(u32x4 x, u32x2 &hi, u32x2 &lo, float scale)
+{
+    typedef _Float16 halfx2_t __attribute__((ext_vector_type(2)));
+    typedef float floatx2_t __attribute__((ext_vector_type(2)));
+#pragma unroll
+    for (int e = 0; e < 2; ++e) {
+        const floatx2_t v = {__uint_as_float(x[2 * e]) * scale, __uint_as_float(x[2 * e + 1]) * scale};
+        const halfx2_t h = __builtin_convertvector(v, halfx2_t);
+        const floatx2_t d = v - __builtin_convertvector(h, floatx2_t);
+        hi[e] = __builtin_bit_cast(uint32_t, h);
+        lo[e] = __builtin_bit_cast(uint32_t, __builtin_convertvector(d, halfx2_t));
+    }
+}
+
+// One operand tile (128 rows x BK) of input type TI staged as bf16 (or fp16) terms in LDS.
+template <typename TI, int NT, int BK, bool F16 = false>
 struct Bf16Stage {
+    static_assert(!F16 || (sizeof(TI) == 4 && NT == 2), "fp16 terms: fp32 source, two terms");
     static constexpr int EPV = Elem<TI>::EPV;              // 8 (bf16) or 4 (fp32) elements per 16 bytes
     static constexpr int VPR = BK / EPV;
     static constexpr int NV = BM * VPR / 256;
@@ -97,7 +126,7 @@ struct Bf16Stage {
         }
     }
 
-    __device__ __forceinline__ void store(ASTERIA_LDS uint16_t *lds, int tid) const
+    __device__ __forceinline__ void store(ASTERIA_LDS uint16_t *lds, int tid, float scale = 1.0f) const
     {
 #pragma unroll
         for (int v = 0; v < NV; ++v) {
@@ -110,7 +139,8 @@ struct Bf16Stage {
                 *(ASTERIA_LDS u32x4 *)dst = r[v];
             } else {
                 u32x2 hi, lo;
-                split4(r[v], hi, lo, NT == 2);
+                if (F16) split4_f16(r[v], hi, lo, scale);
+                else split4(r[v], hi, lo, NT == 2);
                 *(ASTERIA_LDS u32x2 *)dst = hi;
                 if (NT == 2) *(ASTERIA_LDS u32x2 *)(dst + TERM_ELEMS) = lo;
             }
@@ -120,15 +150,18 @@ struct Bf16Stage {
 
 // TRI: which 32 x 32 blocks (i, j) of the wavefront's 64 x 64 sub-tile are multiplied (TRI_ALL,
 // TRI_NONE, or those with j - i <= TRI), as in gemm_mainloop
-template <typename TA, typename TB, int NTA, int NTB, bool GUARD, int TRI = TRI_ALL>
+template <typename TA, typename TB, int NTA, int NTB, bool GUARD, int TRI = TRI_ALL, bool F16 = false>
 __device__ __forceinline__ void gemm_bf16_mainloop(floatx16 (&acc)[2][2], const TA *Ab, const TB *Bb, int lda,
                                                    int ldb, int row0, int col0, int rowsA, int rowsB, int K,
                                                    bool vecA, bool vecB, ASTERIA_LDS uint16_t *smem, int tid,
-                                                   int wm, int wn, int r, int h)
+                                                   int wm, int wn, int r, int h, float sca = 1.0f, float scb = 1.0f)
 {
     constexpr int BK = (NTA + NTB > 2) ? 32 : 64;
-    using StA = Bf16Stage<TA, NTA, BK>;
-    using StB = Bf16Stage<TB, NTB, BK>;
+    using StA = Bf16Stage<TA, NTA, BK, F16>;
+    using StB = Bf16Stage<TB, NTB, BK, F16>;
+    auto mma = [](u32x4 a, u32x4 b, floatx16 c) __attribute__((always_inline)) {
+        return F16 ? MmaBf16::mma_f16(a, b, c) : MmaBf16::mma(a, b, c);
+    };
     constexpr int KPL = BK / 2;          // k values per lane half and slab
     constexpr int STEPS = KPL / 8;       // MFMA k-steps per slab (8 bf16 per lane and step)
     StA sa;
@@ -137,8 +170,8 @@ __device__ __forceinline__ void gemm_bf16_mainloop(floatx16 (&acc)[2][2], const 
     const int nk = (K + BK - 1) / BK;
     sa.template load<GUARD>(Ab, lda, row0, rowsA, 0, K, vecA, tid);
     sb.template load<GUARD>(Bb, ldb, col0, rowsB, 0, K, vecB, tid);
-    sa.store(smem, tid);
-    sb.store(smemB, tid);
+    sa.store(smem, tid, sca);
+    sb.store(smemB, tid, scb);
     __syncthreads();
     for (int kt = 0; kt < nk; ++kt) {
         const int cur = kt & 1;
@@ -173,24 +206,24 @@ __device__ __forceinline__ void gemm_bf16_mainloop(floatx16 (&acc)[2][2], const 
 #pragma unroll
                 for (int j = 0; j < 2; ++j) {
                     if (TRI != TRI_ALL && j - i > TRI) continue;
-                    if (NTA == 2) acc[i][j] = MmaBf16::mma(al[i], bh[j], acc[i][j]);
-                    if (NTB == 2) acc[i][j] = MmaBf16::mma(ah[i], bl[j], acc[i][j]);
+                    if (NTA == 2) acc[i][j] = mma(al[i], bh[j], acc[i][j]);
+                    if (NTB == 2) acc[i][j] = mma(ah[i], bl[j], acc[i][j]);
                 }
 #pragma unroll
             for (int i = 0; i < 2; ++i)
 #pragma unroll
                 for (int j = 0; j < 2; ++j)
-                    if (TRI == TRI_ALL || j - i <= TRI) acc[i][j] = MmaBf16::mma(ah[i], bh[j], acc[i][j]);
+                    if (TRI == TRI_ALL || j - i <= TRI) acc[i][j] = mma(ah[i], bh[j], acc[i][j]);
         }
         if (kt + 1 < nk) {
-            sa.store(smem + (cur ^ 1) * StA::LDS_ELEMS, tid);
-            sb.store(smemB + (cur ^ 1) * StB::LDS_ELEMS, tid);
+            sa.store(smem + (cur ^ 1) * StA::LDS_ELEMS, tid, sca);
+            sb.store(smemB + (cur ^ 1) * StB::LDS_ELEMS, tid, scb);
         }
         __syncthreads();
     }
 }
 
-template <typename TA, typename TB, int NTA, int NTB>
+template <typename TA, typename TB, int NTA, int NTB, bool F16 = false>
 __global__ __launch_bounds__(256) void gemm_bf16_grouped_kernel(const GemmProblem *__restrict__ probs, int nprobs,
                                                                 int total_tiles, const int *__restrict__ state)
 {
@@ -247,28 +280,40 @@ __global__ __launch_bounds__(256) void gemm_bf16_grouped_kernel(const GemmProble
         const int w = __builtin_amdgcn_readfirstlane(wave);
         d = 2 * ((w >> 1) - (w & 1));
     }
+    // fp16 terms: the operands are scaled into the fp16 range before the split, the sums scaled back
+    float sca = 1.0f, scb = 1.0f;
+    if (F16) { sca = P.sa_dev ? *P.sa_dev : P.sa; scb = P.sb; }
     if (fast && d == 0)
-        gemm_bf16_mainloop<TA, TB, NTA, NTB, false, 0>(acc, Ab, Bb, lda, ldb, row0, col0, rowsA, rowsB, K, vecA, vecB,
-                                                       smem, tid, wm, wn, r, h);
+        gemm_bf16_mainloop<TA, TB, NTA, NTB, false, 0, F16>(acc, Ab, Bb, lda, ldb, row0, col0, rowsA, rowsB, K, vecA,
+                                                            vecB, smem, tid, wm, wn, r, h, sca, scb);
     else if (fast && d < 0)
-        gemm_bf16_mainloop<TA, TB, NTA, NTB, false, TRI_NONE>(acc, Ab, Bb, lda, ldb, row0, col0, rowsA, rowsB, K, vecA,
-                                                              vecB, smem, tid, wm, wn, r, h);
+        gemm_bf16_mainloop<TA, TB, NTA, NTB, false, TRI_NONE, F16>(acc, Ab, Bb, lda, ldb, row0, col0, rowsA, rowsB, K,
+                                                                   vecA, vecB, smem, tid, wm, wn, r, h, sca, scb);
     else if (fast)
-        gemm_bf16_mainloop<TA, TB, NTA, NTB, false>(acc, Ab, Bb, lda, ldb, row0, col0, rowsA, rowsB, K, vecA, vecB,
-                                                    smem, tid, wm, wn, r, h);
+        gemm_bf16_mainloop<TA, TB, NTA, NTB, false, TRI_ALL, F16>(acc, Ab, Bb, lda, ldb, row0, col0, rowsA, rowsB, K,
+                                                                  vecA, vecB, smem, tid, wm, wn, r, h, sca, scb);
     else
-        gemm_bf16_mainloop<TA, TB, NTA, NTB, true>(acc, Ab, Bb, lda, ldb, row0, col0, rowsA, rowsB, K, vecA, vecB,
-                                                   smem, tid, wm, wn, r, h);
+        gemm_bf16_mainloop<TA, TB, NTA, NTB, true, TRI_ALL, F16>(acc, Ab, Bb, lda, ldb, row0, col0, rowsA, rowsB, K,
+                                                                 vecA, vecB, smem, tid, wm, wn, r, h, sca, scb);
+    if (F16) {
+        const float inv = 1.0f / (sca * scb);     // powers of two: exact
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[i][j][v] *= inv;
+    }
     gemm_epilogue<MM, float>(P, acc, lt, ti, tj, row0, col0, rowsA, rowsB, wm, wn, r, h, lane, wave, tid, red);
 }
 
-template <typename TA, typename TB, int NTA, int NTB>
+template <typename TA, typename TB, int NTA, int NTB, bool F16 = false>
 inline hipError_t launch_gemm_bf16_grouped(const GemmProblem *probs, int nprobs, int total_tiles,
                                            const int *state, hipStream_t stream)
 {
     if (total_tiles <= 0 || nprobs <= 0) return hipSuccess;
     constexpr int BK = (NTA + NTB > 2) ? 32 : 64;
-    auto kern = gemm_bf16_grouped_kernel<TA, TB, NTA, NTB>;
+    auto kern = gemm_bf16_grouped_kernel<TA, TB, NTA, NTB, F16>;
     constexpr size_t lds = sizeof(uint16_t) * 2 *
                            (size_t)(Bf16Stage<TA, NTA, BK>::LDS_ELEMS + Bf16Stage<TB, NTB, BK>::LDS_ELEMS);
     static bool configured = false;

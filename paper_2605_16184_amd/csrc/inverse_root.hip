@@ -6,16 +6,20 @@
 //      per-factor early stop on the eigen-residual).
 //   2. Scaling  s = 1 / ((1 + margin) lambda_max + eps),  M_0 = s (A + eps I),  X_0 = s^(1/p) I,
 //      so the spectrum of M_0 lies in (0, 1].
-//   3. Coupled iteration  T = a I - g M,  X <- X T,  M <- T^p M  (classical Newton coefficients
-//      a = (p + 1) / p, g = 1 / p).  Every product is one symmetric grouped GEMM on the matrix
-//      cores; the epilogue of the M-update also emits the next T and the per-tile partial sums
-//      of ||M - I||_F^2.  A per-factor state machine on the device (running -> last X update ->
-//      done) lets finished factors drop out without any host round trip: their workgroups
-//      exit at once.
-//   4. The leading iterations run on fp64 MFMA, where the smallest eigenvalues of M are still
-//      comparable to fp32 round-off; the state is then cast to fp32 and continues on fp32 MFMA.
+//   3. Coupled iteration  T = a I - g M,  X <- X T,  M <- T^p M  (coefficients a, g adapted per
+//      factor and iteration to the interval that holds M's spectrum, or the classical Newton
+//      values a = (p + 1) / p, g = 1 / p).  Every product is one symmetric grouped GEMM on the
+//      matrix cores; the epilogue of the M-update also emits the next T and the per-tile partial
+//      sums of ||M - I||_F^2.  A per-factor state machine on the device (running -> last X
+//      update -> done) lets finished factors drop out without any host round trip: their
+//      workgroups exit at once.
+//   4. The leading iterations of the M-chain run on fp64 MFMA, where the smallest eigenvalues of
+//      M are still comparable to fp32 round-off; the state is then cast to fp32 and continues on
+//      the fp16 matrix cores with every fp32 operand split into two fp16 terms (2^-22 per
+//      operand; the fp32 matrix cores serve pinned options, absolute eps and very large n).  X
+//      is kept in fp32 throughout and its updates run on the fp16 cores from the start.
 //
-// Per factor and iteration: 3 launches (X T together with T T; T^2 T^2; T^4 M) + 1 control kernel.
+// Per iteration: 1 control kernel + up to 4 launches (X T; T T; T^2 T^2; T^4 M).
 #include <math.h>
 #include <stddef.h>
 
@@ -80,7 +84,12 @@ struct FactorScal {
     float ca, cg;    // coefficients of the current T = ca I - cg M
     float coef_next[2];   // coefficients the M-update epilogue uses for the next T
     float fro2, trace;    // ||A||_F^2 and tr(A), gathered during the first power-iteration step
+    float x_scale;        // power of two that brings X into the fp16 range for the 16-bit products
 };
+
+// Scale of M, T, T^2, T^4 in the fp16-split products: their entries stay below a^4 < 23 (a <= 2.2),
+// so 2^10 keeps them under 2^15 with the fp16 range ending at 65504.
+constexpr float ROOT_F16_SCALE = 1024.0f;
 
 __device__ __forceinline__ float hash_unit(uint32_t f, uint32_t j)
 {
@@ -249,6 +258,16 @@ __global__ void root_setup_kernel(const FactorDev *fd, FactorScal *fs, int *stat
         double r2 = sc * sc * f2 - 2.0 * sc * tr + n;
         r2 = r2 * (1.0 + 1e-3) + 1e-6 * n;           // slack for the fp32 sums
         if (r2 > 0.0 && r2 < 1.0) { const double l1 = 1.0 - sqrt(r2); if (l1 > lo) lo = l1; }
+    }
+    // Every iterate X_k = xs prod T_j has eigenvalues x with (x / xs)^root lambda = mu <= 2, lambda >= lo
+    // an eigenvalue of M_0 and mu the matching one of M_k: |X_k| <= xs (2 / lo)^(1/root).  The
+    // fp16-split products scale X by the largest power of two that keeps this bound below 30000.
+    {
+        const double xs = ok ? pow((double)S.scale, 1.0 / (double)root) : 1.0;
+        const double bound = xs * pow(2.0 / lo, 1.0 / (double)root);
+        int e = (int)floor(log2(30000.0 / bound));
+        e = e < -60 ? -60 : (e > 60 ? 60 : e);
+        S.x_scale = (float)ldexp(1.0, e);
     }
     double a, g;
     root_coefficients(lo, 1.0, root, adapted != 0, ROOT_THETA, a, g);
@@ -565,10 +584,10 @@ struct Plan {
     int fp64_iters;
     int power_iters;
     int root;
-    int lowp_from;     // first iteration that may run on the bf16 matrix cores (split operands)
+    int lowp_from;     // first iteration that may run on the fp16 matrix cores (operands split in two fp16 terms)
     float stop_resid, power_tol, margin;
     bool use64, use32, adapted, lowp_auto;
-    bool xt_lowp;      // fully automatic precision: X updates on the bf16 cores (split operands) from the
+    bool xt_lowp;      // fully automatic precision: X updates on the fp16 cores (split operands) from the
                        // first product on, and the look-ahead stop rule (accuracy class 1e-3)
 };
 
@@ -577,6 +596,9 @@ struct Plan {
 //           interval, plus the last update that follows;
 //   *lead64 number of leading iterations that start while the bottom of the spectrum is still
 //           below `thr` (those run in fp64 under the automatic precision rule).
+// bottom of M's spectrum from which the 16-bit-split tier may run under the automatic rule
+constexpr double ROOT_LOWP_FLOOR = 0.5 * 5.96e-8 / 1e-3;
+
 void simulate_schedule(double lo0, int n, int root, bool adapted, double stop, double thr, int cap,
                        int *iters, int *lead64, double thr_lowp = 0.0, int *lead_full = nullptr)
 {
@@ -656,9 +678,10 @@ asteria_status make_plan(const asteria_root_opts *opts_in, asteria_eps_mode mode
             j = pl.adapted ? 2 : 4;   // the host cannot see eps / lambda_max here
         }
     }
-    // Late iterations: once the bottom of M's spectrum is above 1e-3, products that keep 16 bits
-    // (fp32 operands split into two bf16 terms, three bf16 MFMA passes) add about 2e-4 to the
-    // root's relative error (measured at n = 1024, eps 1e-6; 8e-4 at eps 1e-8), and run nearly twice as fast as the fp32 matrix cores.
+    // Iterations after the fp64 prefix: products of fp32 operands split into two fp16 terms (three
+    // fp16 MFMA passes) keep the operands to 2^-22, within a factor 4 of fp32, and run twice as fast
+    // as the fp32 matrix cores; they take over as soon as the bottom of M's spectrum is above
+    // ROOT_LOWP_FLOOR, the bound below which the automatic rule keeps fp64.
     int jl = o.lowp_from;
     if (jl < 0) {
         jl = o.max_iters;
@@ -668,7 +691,7 @@ asteria_status make_plan(const asteria_root_opts *opts_in, asteria_eps_mode mode
             if (emin > 0.0f) {
                 const double lo0 = 0.5 * (double)emin / (1.0 + (double)pl.margin + (double)emin);
                 int it = 0, l64 = 0;
-                simulate_schedule(lo0, 1, root, pl.adapted, 1e-3, 0.0, o.max_iters, &it, &l64, 1e-3, &jl);
+                simulate_schedule(lo0, 1, root, pl.adapted, 1e-3, 0.0, o.max_iters, &it, &l64, ROOT_LOWP_FLOOR, &jl);
             }
         }
     }
@@ -716,6 +739,7 @@ __global__ void root_tables_kernel(const FactorDev *__restrict__ fd, FactorScal 
     p.alpha = 1.0f; p.beta = 0.0f; p.ep_a = ca; p.ep_g = cg;
     p.flags = GEMM_SYM;
     p.tile_start = F.tile_start;
+    p.sa = ROOT_F16_SCALE; p.sb = ROOT_F16_SCALE;       // read by the fp16-split kernel only
     for (int pa = 0; pa < 2; ++pa) {
         // X after an odd number of updates lives in the workspace buffer, else in the caller's X
         GemmProblem q = p;
@@ -723,6 +747,7 @@ __global__ void root_tables_kernel(const FactorDev *__restrict__ fd, FactorScal 
         q.A = pa ? (const void *)F.X32b : (const void *)F.Xout; q.lda = pa ? F.ld32 : F.ldx;
         q.B = F.T32; q.ldb = F.ld32;
         q.C = pa ? (void *)F.Xout : (void *)F.X32b; q.ldc = pa ? F.ldx : F.ld32;
+        q.sa_dev = &fs[i].x_scale;
         rt.xt[pa][i] = q;
     }
     p.state_mask = (1 << ST_RUN);
@@ -834,9 +859,8 @@ asteria_status run_pass(const asteria_factor *f, const std::vector<int> &order, 
         K = std::min(K, it + 2);
     }
     const int j64 = std::min(pl.fp64_iters, K);
-    // 16-bit products put a floor of about 2e-6 n under the measured ||M - I||_F; above n = 2048 that
-    // floor approaches stop_resid, so the automatic rule keeps such factors on the fp32 cores
-    const int jlow = (pl.lowp_auto && n_max > 2048) ? K : pl.lowp_from;
+    // checked up to n = 4096; beyond 16384 the automatic rule keeps the factors on the fp32 cores
+    const int jlow = (pl.lowp_auto && n_max > 16384) ? K : pl.lowp_from;
 
     // problem tables: written on the device from the factor descriptors (the 14 tables are 11 times
     // the size of the descriptors, and host tables would travel as kernel arguments)
@@ -879,19 +903,19 @@ asteria_status run_pass(const asteria_factor *f, const std::vector<int> &order, 
         const int pa = k & 1;
         const bool lowp = p32 && k >= jlow;
         // X' = X T (X_1 comes from the start kernel).  X only needs the accuracy of the result, so
-        // the update runs on the bf16 cores with split operands (16 bits) whenever the low-precision
+        // the update runs on the fp16 cores with split operands (22 bits) whenever the low-precision
         // tier is chosen automatically, from the first product on; otherwise with the tier of M.
         if (k > 0) {
             if (pl.xt_lowp || lowp)
-                ASTERIA_HIP_TRY((launch_gemm_bf16_grouped<float, float, 2, 2>(d_xt[pa], cnt, tri_total, d_state, stream)));
+                ASTERIA_HIP_TRY((launch_gemm_bf16_grouped<float, float, 2, 2, true>(d_xt[pa], cnt, tri_total, d_state, stream)));
             else
                 ASTERIA_HIP_TRY((launch_gemm_grouped<float, float, float, false, false>(d_xt[pa], cnt, tri_total, d_state, stream)));
         }
         if (lowp) {
-            ASTERIA_HIP_TRY((launch_gemm_bf16_grouped<float, float, 2, 2>(d_tab[0][pa][0], cnt, tri_total, d_state, stream)));
+            ASTERIA_HIP_TRY((launch_gemm_bf16_grouped<float, float, 2, 2, true>(d_tab[0][pa][0], cnt, tri_total, d_state, stream)));
             if (root == 4)
-                ASTERIA_HIP_TRY((launch_gemm_bf16_grouped<float, float, 2, 2>(d_tab[0][pa][1], cnt, tri_total, d_state, stream)));
-            ASTERIA_HIP_TRY((launch_gemm_bf16_grouped<float, float, 2, 2>(d_tab[0][pa][2], cnt, tri_total, d_state, stream)));
+                ASTERIA_HIP_TRY((launch_gemm_bf16_grouped<float, float, 2, 2, true>(d_tab[0][pa][1], cnt, tri_total, d_state, stream)));
+            ASTERIA_HIP_TRY((launch_gemm_bf16_grouped<float, float, 2, 2, true>(d_tab[0][pa][2], cnt, tri_total, d_state, stream)));
         } else if (p32) {
             ASTERIA_HIP_TRY((launch_gemm_grouped<float, float, float, false, false>(d_tab[0][pa][0], cnt, tri_total, d_state, stream)));
             if (root == 4)

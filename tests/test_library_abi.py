@@ -142,6 +142,23 @@ def test_workspace_queries_scale_with_the_batch():
     assert ast.lib().asteria_inverse_root_workspace_bytes(None, 1, None, None) == 0
 
 
+def test_precision_plan_follows_eps_and_pinned_options():
+    # host logic only: which leading iterations keep fp64, where the split-fp16 tier starts, and
+    # whether the X updates run there from the first product on
+    assert ast.inverse_root_plan(1e-6) == (2, 2, True)          # the headline setting: 2 fp64 iterations, no fp32 tier
+    j64, jl, xt = ast.inverse_root_plan(1e-8)
+    assert j64 == jl and 3 <= j64 <= 5 and xt                    # a smaller eps keeps fp64 longer
+    j64b, jlb, _ = ast.inverse_root_plan(1e-2)
+    assert j64b == 0 and jlb == 0                                # well above fp32 round-off: no fp64 at all
+    o = ast.RootOpts()
+    j64a, jla, xta = ast.inverse_root_plan(1e-6, relative=False)
+    assert jla >= o.max_iters and not xta                        # absolute eps: the host cannot place the spectrum
+    assert ast.inverse_root_plan(1e-6, opts=ast.RootOpts(fp64_iters=0))[::2] == (0, False)   # pinned: X follows M's tier
+    assert ast.inverse_root_plan(1e-6, opts=ast.RootOpts(lowp_from=5))[1:] == (5, False)
+    j64c, _, _ = ast.inverse_root_plan(1e-6, opts=ast.RootOpts(schedule=0))
+    assert j64c > 2                                              # classical coefficients lift the spectrum more slowly
+
+
 def test_model_block_census_matches_the_1p1b_configuration():
     mats = W.llama_1b_matrices()
     blocks = W.block_shapes(mats, 1024)

@@ -171,7 +171,7 @@ def test_root_single_block_config_absolute_and_relative_eps():
         (Xa,), info, _, _, _ = run_roots([A], 1e-6 * lmax_o, relative=False)
         assert info[0] == B.INFO_OK and relF(Xa, Xo) <= 1e-5
         assert torch.equal(Xa, Xa.T)
-        # default options: the last iterations run on split-bf16 products (16 bits) and the look-ahead
+        # default options: the iterations after the fp64 prefix run on split-fp16 products and the look-ahead
         # stop rule accepts a truncation error of 7e-4 per eigen-direction (bar: 2e-3)
         assert relF(X, Xo) <= 1e-3
 
