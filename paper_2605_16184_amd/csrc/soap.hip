@@ -121,9 +121,37 @@ struct QrFactor {
     int run, skip3;
     int out_index;  // position of this factor in the caller's arrays
     int pad_;
+    // Powers of two that bring the rows of the current panel into the fp16 range for the projection
+    // coefficients computed on the fp16 cores: a_scale for rows of Z^T as they come out of Q^T A
+    // (bounded by tr A), 2^14 once a sweep has normalised them; p_scale is the one in force.
+    float a_scale, p_scale;
+    const float *A;  // the statistic (read for its trace)
+    int lda, pad2_;
 };
+constexpr float QR_UNIT_SCALE = 16384.0f;
 constexpr int QR_STATE_STRIDE = (int)(sizeof(QrFactor) / sizeof(int));
 static_assert(sizeof(QrFactor) % sizeof(int) == 0, "state words are addressed as ints inside the factor array");
+
+// a_scale = p_scale = largest power of two with 2^e tr|A| <= 30000 (|Z_ij| <= ||A||_2 <= tr A for a
+// positive semi-definite A and orthonormal Q); one wavefront per factor
+__global__ __launch_bounds__(64) void qr_scale_kernel(QrFactor *fs, int nf)
+{
+    const int f = blockIdx.x;
+    if (f >= nf) return;
+    const float *a = fs[f].A;
+    const int n = fs[f].n, ld = fs[f].lda;
+    double t = 0.0;
+    for (int i = threadIdx.x; i < n; i += 64) t += fabs((double)a[(size_t)i * ld + i]);
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) t += __shfl_xor(t, off, 64);
+    if (threadIdx.x == 0) {
+        int e = (t > 0.0 && t < 1e300) ? (int)floor(log2(30000.0 / t)) : 0;
+        e = e < -100 ? -100 : (e > 100 ? 100 : e);
+        const float sc = (float)ldexp(1.0, e);
+        fs[f].a_scale = sc;
+        fs[f].p_scale = sc;
+    }
+}
 
 constexpr int QR_PANEL = 128;
 constexpr int QR_MAXN = 1 << 20;
@@ -199,8 +227,8 @@ __global__ __launch_bounds__(CHOL_THREADS) void panel_chol_inverse_kernel(QrFact
             F.winv[(size_t)i * QR_PANEL + j] = (j <= i) ? (float)L[i * PITCH + j] : 0.0f;
     if (tid == 0) {
         if (bad_flag == 1 || (bad_flag == 2 && sweep == 2)) F.bad = 1;
-        if (sweep == 0) F.skip3 = 1;
-        if (sweep == 1 && bad_flag == 2) F.skip3 = 0;
+        if (sweep == 0) { F.skip3 = 1; F.p_scale = QR_UNIT_SCALE; }       // the rows are normalised now
+        if (sweep == 1) { F.p_scale = F.a_scale; if (bad_flag == 2) F.skip3 = 0; }   // next panel: rows of Z^T again
     }
 }
 
@@ -513,6 +541,7 @@ extern "C" asteria_status asteria_soap_refresh(const asteria_factor *f, int nfac
             F.winv = cv.take<float>((size_t)QR_PANEL * QR_PANEL);
             F.Qout = a.X; F.n = n; F.ldz = ldz; F.ldq = a.ldx; F.bad = 0; F.run = 0; F.skip3 = 1;
             F.out_index = idx[i]; F.pad_ = 0;
+            F.a_scale = 1.0f; F.p_scale = 1.0f; F.A = a.A; F.lda = a.lda; F.pad2_ = 0;
             F.tile_start = ttiles;
             const int tpr = (n + 31) / 32;
             ttiles += tpr * tpr;
@@ -563,7 +592,12 @@ extern "C" asteria_status asteria_soap_refresh(const asteria_factor *f, int nfac
                 p.M = rows; p.N = done; p.K = F.n; p.tiles_n = (done + BN - 1) / BN;
                 p.A = Pt; p.lda = F.ldz; p.B = F.Zt; p.ldb = F.ldz; p.C = cbuf[i]; p.ldc = F.ldz;
                 p.tile_start = tiles1[j]; tiles1[j] += p.tiles_n;
+                // on the fp16 cores (sweeps 0 and 1): the panel rows scaled by the factor's p_scale,
+                // the finished rows are orthonormal
+                p.sa_dev = reinterpret_cast<const float *>(reinterpret_cast<const char *>(d_q + i) + offsetof(QrFactor, p_scale));
+                p.sb = QR_UNIT_SCALE;
                 t1[j].push_back(p);
+                p.sa_dev = nullptr;
                 // P <- P - C Q_done : contraction over the finished rows (Q_done read k-major)
                 p.alpha = -1.0f; p.beta = 1.0f;
                 p.M = rows; p.N = F.n; p.K = done; p.tiles_n = (F.n + BN - 1) / BN;
@@ -589,6 +623,7 @@ extern "C" asteria_status asteria_soap_refresh(const asteria_factor *f, int nfac
             ASTERIA_HIP_TRY(upload_async(d_t1[j], t1[j].data(), t1[j].size() * sizeof(GemmProblem), stream));
             ASTERIA_HIP_TRY(upload_async(d_t2[j], t2[j].data(), t2[j].size() * sizeof(GemmProblem), stream));
         }
+        hipLaunchKernelGGL(qr_scale_kernel, dim3(cnt), dim3(64), 0, stream, d_q, cnt);
         ASTERIA_HIP_TRY((launch_gemm_grouped<float, float, float, true, false>(d_g, cnt, tiles, nullptr, stream)));
         for (int j = 0; j < np_max; ++j) {
             // sweeps of (project against the finished rows, orthonormalise the panel): the second
@@ -601,7 +636,12 @@ extern "C" asteria_status asteria_soap_refresh(const asteria_factor *f, int nfac
             for (int sweep = 0; sweep < 3; ++sweep) {
                 const int *st = sweep < 2 ? st_run : st_third;
                 if (j > 0) {
-                    ASTERIA_HIP_TRY((launch_gemm_grouped<float, float, float, false, false>(d_t1[j], (int)t1[j].size(), tiles1[j], st, stream)));
+                    // projection coefficients: fp32 operands as two fp16 terms each (2^-22) in the two
+                    // regular sweeps; the rare third sweep stays on the fp32 cores
+                    if (sweep < 2)
+                        ASTERIA_HIP_TRY((launch_gemm_bf16_grouped<float, float, 2, 2, true>(d_t1[j], (int)t1[j].size(), tiles1[j], st, stream)));
+                    else
+                        ASTERIA_HIP_TRY((launch_gemm_grouped<float, float, float, false, false>(d_t1[j], (int)t1[j].size(), tiles1[j], st, stream)));
                     ASTERIA_HIP_TRY((launch_gemm_grouped<float, float, float, false, true>(d_t2[j], (int)t2[j].size(), tiles2[j], st, stream)));
                 }
                 ASTERIA_HIP_TRY((launch_gemm_grouped<double, float, float, false, false>(d_t3[j], (int)t3[j].size(), (int)t3[j].size(), st, stream)));
