@@ -206,9 +206,14 @@ asteria_status asteria_precondition(const asteria_pblock *blocks, int nblocks,
  * For every factor: Z = A Q (one power iteration), Z = Q' R the QR factorisation with
  * diag(R) >= 0 (unique for a Z of full rank: the Q' a Householder QR with that sign convention
  * returns), and Q <- Q' in place (f[i].X is Q).  Computed by block Gram-Schmidt with
- * re-orthogonalisation over panels of 128 columns (fp32 matrix cores; panel Gram matrices and
- * their Cholesky factors in fp64).  Columns of Z beyond its numerical rank come out as an
- * orthonormal completion.  The factors are worked on in two groups on two internal streams
+ * re-orthogonalisation over panels of 128 columns.  The large products - A Q, the projection
+ * coefficients of a panel against the finished columns and their subtraction - run on the fp16
+ * matrix cores with every fp32 operand split into two fp16 terms (22 bits kept) after a scaling
+ * by a power of two taken from tr A, with fp32 accumulation; panel Gram matrices and their
+ * Cholesky factors are fp64, the application of the inverse factor and a third sweep, where
+ * one is needed, use the fp32 matrix cores.  Columns of Z beyond its numerical rank come out as
+ * an orthonormal completion.  Q is used as scratch during the call (transposed in place, then
+ * overwritten panel by panel); where info reports a failure its content is unspecified.  The factors are worked on in two groups on two internal streams
  * (created once per device, default priority) that start after everything already enqueued on
  * `stream` and that `stream` waits for before the call's work counts as done on it.
  *   info  device int32[nfactors] or NULL (ASTERIA_INFO_OK, or ASTERIA_INFO_NOT_PD if a column

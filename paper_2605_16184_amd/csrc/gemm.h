@@ -56,6 +56,7 @@ struct GemmProblem {
     float *partial;
     const float *coef;  // root epilogue: device pointer to (a, g), or null to use ep_a / ep_g
     const float *sa_dev; // fp16-split kernel: device pointer to the scale of operand A, or null to use sa
+    const float *sb_dev; // the same for operand B (null: sb)
     int M, N, K;
     int lda, ldb, ldc, ldc2, ldc3;
     int tile_start;  // id of this problem's first tile within the launch

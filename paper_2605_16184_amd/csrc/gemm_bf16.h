@@ -282,7 +282,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_grouped_kernel(const GemmProble
     }
     // fp16 terms: the operands are scaled into the fp16 range before the split, the sums scaled back
     float sca = 1.0f, scb = 1.0f;
-    if (F16) { sca = P.sa_dev ? *P.sa_dev : P.sa; scb = P.sb; }
+    if (F16) { sca = P.sa_dev ? *P.sa_dev : P.sa; scb = P.sb_dev ? *P.sb_dev : P.sb; }
     if (fast && d == 0)
         gemm_bf16_mainloop<TA, TB, NTA, NTB, false, 0, F16>(acc, Ab, Bb, lda, ldb, row0, col0, rowsA, rowsB, K, vecA,
                                                             vecB, smem, tid, wm, wn, r, h, sca, scb);

@@ -113,7 +113,7 @@ struct QrFactor {
     double *gram;   // QR_PANEL x QR_PANEL: Gram matrix of the current panel
     float *winv;    // QR_PANEL x QR_PANEL: inverse Cholesky factor of the current panel
     int n, ldz, ldq;
-    int tile_start; // for the transposing write-back (square 32 x 32 tiles)
+    int pad0_;
     int bad;        // set to 1 when a column could not be normalised
     // Two words the grouped launches read as their per-problem state (a problem runs while its word
     // is 0): `run` stays 0; `skip3` is 1 unless the second sweep over the current panel found a row
@@ -238,27 +238,51 @@ __global__ void qr_info_kernel(const QrFactor *fs, int nf, int32_t *info)
     if (f < nf && info) info[fs[f].out_index] = fs[f].bad ? ASTERIA_INFO_NOT_PD : ASTERIA_INFO_OK;
 }
 
-// Q[i][c] = Zt[c][i], 32 x 32 tiles through LDS
-__global__ __launch_bounds__(256) void transpose_out_kernel(const QrFactor *fs, int nf)
+// Q <- Q^T in place: pairs of mirrored 32 x 32 tiles swapped through LDS.  Grid: x = tile (row-major
+// over the largest factor's tile grid; tiles below the diagonal or outside this factor do nothing),
+// y = factor.
+__global__ __launch_bounds__(256) void transpose_inplace_kernel(const QrFactor *fs)
 {
-    int lo = 0, hi = nf - 1;
-    while (lo < hi) {
-        const int mid = (lo + hi + 1) >> 1;
-        if (fs[mid].tile_start <= (int)blockIdx.x) lo = mid; else hi = mid - 1;
+    const QrFactor &F = fs[blockIdx.y];
+    const int tpr = (F.n + 31) / 32, tmax = (int)rintf(sqrtf((float)gridDim.x));
+    const int ti = (int)blockIdx.x / tmax, tj = (int)blockIdx.x % tmax;
+    if (ti > tj || tj >= tpr) return;
+    __shared__ float up[32][33], lo[32][33];
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+    for (int r = ty; r < 32; r += 8) {
+        const int i = ti * 32 + r, c = tj * 32 + tx;     // upper tile (ti, tj)
+        up[r][tx] = (i < F.n && c < F.n) ? F.Qout[(size_t)i * F.ldq + c] : 0.0f;
+        const int i2 = tj * 32 + r, c2 = ti * 32 + tx;   // its mirror (tj, ti)
+        lo[r][tx] = (i2 < F.n && c2 < F.n) ? F.Qout[(size_t)i2 * F.ldq + c2] : 0.0f;
     }
-    const QrFactor &F = fs[lo];
-    const int lt = (int)blockIdx.x - F.tile_start;
+    __syncthreads();
+    for (int r = ty; r < 32; r += 8) {
+        const int i = ti * 32 + r, c = tj * 32 + tx;
+        if (i < F.n && c < F.n) F.Qout[(size_t)i * F.ldq + c] = lo[tx][r];
+        const int i2 = tj * 32 + r, c2 = ti * 32 + tx;
+        if (ti != tj && i2 < F.n && c2 < F.n) F.Qout[(size_t)i2 * F.ldq + c2] = up[tx][r];
+    }
+}
+
+// Q[i][c] = Zt[c][i] for the rows c of one finished panel: 32 x 32 tiles through LDS.  Grid:
+// x = tile of the 128 x n strip, y = slot in the panel's factor list.  The caller's Q thus fills up
+// panel by panel, and the next panels read the finished columns from it with k contiguous.
+__global__ __launch_bounds__(256) void transpose_panel_kernel(const QrFactor *fs, const int *fidx, int panel)
+{
+    const QrFactor &F = fs[fidx[blockIdx.y]];
     const int tpr = (F.n + 31) / 32;
-    const int ti = lt / tpr, tj = lt % tpr;   // tile of Qt: rows c in ti, columns i in tj
+    const int ti = (int)blockIdx.x / tpr, tj = (int)blockIdx.x % tpr;   // tile row inside the panel, tile column
+    const int c0 = panel * QR_PANEL + ti * 32;
+    if (ti >= QR_PANEL / 32 || c0 >= F.n) return;
     __shared__ float tile[32][33];
     const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
     for (int r = ty; r < 32; r += 8) {
-        const int c = ti * 32 + r, i = tj * 32 + tx;
+        const int c = c0 + r, i = tj * 32 + tx;
         tile[r][tx] = (c < F.n && i < F.n) ? F.Zt[(size_t)c * F.ldz + i] : 0.0f;
     }
     __syncthreads();
     for (int r = ty; r < 32; r += 8) {
-        const int i = tj * 32 + r, c = ti * 32 + tx;
+        const int i = tj * 32 + r, c = c0 + tx;
         if (i < F.n && c < F.n) F.Qout[(size_t)i * F.ldq + c] = tile[tx][r];
     }
 }
@@ -530,7 +554,7 @@ extern "C" asteria_status asteria_soap_refresh(const asteria_factor *f, int nfac
         std::vector<GemmProblem> g;
         std::vector<QrFactor> q;
         std::vector<float *> cbuf(cnt);
-        int tiles = 0, ttiles = 0;
+        int tiles = 0;
         for (int i = 0; i < cnt; ++i) {
             const asteria_factor &a = f[idx[i]];
             const int n = a.n, ldz = ld4(n);
@@ -540,13 +564,12 @@ extern "C" asteria_status asteria_soap_refresh(const asteria_factor *f, int nfac
             F.gram = cv.take<double>((size_t)QR_PANEL * QR_PANEL);
             F.winv = cv.take<float>((size_t)QR_PANEL * QR_PANEL);
             F.Qout = a.X; F.n = n; F.ldz = ldz; F.ldq = a.ldx; F.bad = 0; F.run = 0; F.skip3 = 1;
-            F.out_index = idx[i]; F.pad_ = 0;
+            F.out_index = idx[i]; F.pad_ = 0; F.pad0_ = 0;
             F.a_scale = 1.0f; F.p_scale = 1.0f; F.A = a.A; F.lda = a.lda; F.pad2_ = 0;
-            F.tile_start = ttiles;
-            const int tpr = (n + 31) / 32;
-            ttiles += tpr * tpr;
             q.push_back(F);
-            // Z^T = Q^T A : A'(i, k) = Q[k][i] (k-major), B'(j, k) = A[j][k] (k-contiguous, A symmetric)
+            // Z^T = Q^T A on the fp16 cores (two terms per operand): A'(i, k) = Q^T[i][k] - the caller's
+            // Q has been transposed in place by then -, scaled by 2^14, and B'(j, k) = A[j][k] (A is
+            // symmetric), scaled by the factor's a_scale; both k-contiguous
             GemmProblem p;
             memset(&p, 0, sizeof(p));
             p.state_idx = -1; p.state_mask = ~0; p.alpha = 1.0f; p.beta = 0.0f;
@@ -554,6 +577,8 @@ extern "C" asteria_status asteria_soap_refresh(const asteria_factor *f, int nfac
             const int tn = (n + BN - 1) / BN;
             p.tiles_n = tn;
             p.A = a.X; p.lda = a.ldx; p.B = a.A; p.ldb = a.lda; p.C = F.Zt; p.ldc = ldz;
+            p.sa = QR_UNIT_SCALE;
+            p.sb_dev = reinterpret_cast<const float *>(reinterpret_cast<const char *>(d_q + i) + offsetof(QrFactor, a_scale));
             p.tile_start = tiles; tiles += tn * tn;
             g.push_back(p);
         }
@@ -598,12 +623,16 @@ extern "C" asteria_status asteria_soap_refresh(const asteria_factor *f, int nfac
                 p.sb = QR_UNIT_SCALE;
                 t1[j].push_back(p);
                 p.sa_dev = nullptr;
-                // P <- P - C Q_done : contraction over the finished rows (Q_done read k-major)
+                // P <- P - C Q_done : contraction over the finished rows, which the caller's Q already
+                // holds as columns (k contiguous); the coefficients share the scale of the panel rows
                 p.alpha = -1.0f; p.beta = 1.0f;
                 p.M = rows; p.N = F.n; p.K = done; p.tiles_n = (F.n + BN - 1) / BN;
-                p.A = cbuf[i]; p.lda = F.ldz; p.B = F.Zt; p.ldb = F.ldz; p.C = Pt; p.ldc = F.ldz;
+                p.A = cbuf[i]; p.lda = F.ldz; p.B = F.Qout; p.ldb = F.ldq; p.C = Pt; p.ldc = F.ldz;
+                p.sa_dev = reinterpret_cast<const float *>(reinterpret_cast<const char *>(d_q + i) + offsetof(QrFactor, p_scale));
+                p.sb = QR_UNIT_SCALE;
                 p.tile_start = tiles2[j]; tiles2[j] += p.tiles_n;
                 t2[j].push_back(p);
+                p.sa_dev = nullptr;
             }
         }
         std::vector<GemmProblem *> d_t1(np_max, nullptr), d_t2(np_max, nullptr), d_t3(np_max, nullptr), d_t4(np_max, nullptr);
@@ -624,7 +653,11 @@ extern "C" asteria_status asteria_soap_refresh(const asteria_factor *f, int nfac
             ASTERIA_HIP_TRY(upload_async(d_t2[j], t2[j].data(), t2[j].size() * sizeof(GemmProblem), stream));
         }
         hipLaunchKernelGGL(qr_scale_kernel, dim3(cnt), dim3(64), 0, stream, d_q, cnt);
-        ASTERIA_HIP_TRY((launch_gemm_grouped<float, float, float, true, false>(d_g, cnt, tiles, nullptr, stream)));
+        {
+            const unsigned tpr = (unsigned)((n_max + 31) / 32);
+            hipLaunchKernelGGL(transpose_inplace_kernel, dim3(tpr * tpr, (unsigned)cnt), dim3(256), 0, stream, d_q);
+        }
+        ASTERIA_HIP_TRY((launch_gemm_bf16_grouped<float, float, 2, 2, true>(d_g, cnt, tiles, nullptr, stream)));
         for (int j = 0; j < np_max; ++j) {
             // sweeps of (project against the finished rows, orthonormalise the panel): the second
             // projection acts on normalised rows, so what the first normalisation amplified - the
@@ -642,15 +675,20 @@ extern "C" asteria_status asteria_soap_refresh(const asteria_factor *f, int nfac
                         ASTERIA_HIP_TRY((launch_gemm_bf16_grouped<float, float, 2, 2, true>(d_t1[j], (int)t1[j].size(), tiles1[j], st, stream)));
                     else
                         ASTERIA_HIP_TRY((launch_gemm_grouped<float, float, float, false, false>(d_t1[j], (int)t1[j].size(), tiles1[j], st, stream)));
-                    ASTERIA_HIP_TRY((launch_gemm_grouped<float, float, float, false, true>(d_t2[j], (int)t2[j].size(), tiles2[j], st, stream)));
+                    if (sweep < 2)
+                        ASTERIA_HIP_TRY((launch_gemm_bf16_grouped<float, float, 2, 2, true>(d_t2[j], (int)t2[j].size(), tiles2[j], st, stream)));
+                    else
+                        ASTERIA_HIP_TRY((launch_gemm_grouped<float, float, float, false, false>(d_t2[j], (int)t2[j].size(), tiles2[j], st, stream)));
                 }
                 ASTERIA_HIP_TRY((launch_gemm_grouped<double, float, float, false, false>(d_t3[j], (int)t3[j].size(), (int)t3[j].size(), st, stream)));
                 hipLaunchKernelGGL(panel_chol_inverse_kernel, dim3((unsigned)fidx[j].size()), dim3(CHOL_THREADS), chol_lds, stream, d_q, d_fidx[j], j, sweep);
                 ASTERIA_HIP_TRY((launch_gemm_grouped<float, float, float, false, true>(d_t4[j], (int)t4[j].size(), tiles4[j], st, stream)));
             }
+            // the finished panel goes to the caller's Q as columns
+            hipLaunchKernelGGL(transpose_panel_kernel, dim3((QR_PANEL / 32) * ((n_max + 31) / 32), (unsigned)fidx[j].size()),
+                               dim3(256), 0, stream, d_q, d_fidx[j], j);
         }
         hipLaunchKernelGGL(qr_info_kernel, dim3((cnt + 127) / 128), dim3(128), 0, stream, d_q, cnt, info);
-        hipLaunchKernelGGL(transpose_out_kernel, dim3(ttiles), dim3(256), 0, stream, d_q, cnt);
         ASTERIA_HIP_TRY(hipGetLastError());
         return ASTERIA_OK;
         };
