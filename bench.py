@@ -26,6 +26,7 @@ sys.path.insert(0, ROOT)
 PEAK_F32_MFMA = 157.3   # TFLOP/s, MI355X dense fp32 matrix
 PEAK_F64_MFMA = 78.6    # TFLOP/s, MI355X dense fp64 matrix
 PEAK_BF16_MFMA = 2500.0 # TFLOP/s, MI355X dense bf16 and fp16 matrix
+PEAK_I8_MFMA = 5000.0   # TOP/s, MI355X dense int8 matrix
 # What a register-only loop of v_mfma_f64_16x16x4_f64 with random operands sustains on the box
 # (2 or 4 wavefronts per SIMD, 8 independent accumulators each, 2.38 GHz): context for the fp64
 # kernel's fraction of the published peak, never used as `peak`.
@@ -83,10 +84,11 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=3)
     ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--ws-gib", type=float, default=96.0, help="workspace handed to the library (a single pass needs about 90 GiB)")
+    ap.add_argument("--ws-gib", type=float, default=128.0, help="workspace handed to the library (a single pass needs about 107 GiB)")
     ap.add_argument("--max-blocks", type=int, default=0, help="debug: truncate the batch")
     ap.add_argument("--fp64-iters", type=int, default=-1)
     ap.add_argument("--lowp-from", type=int, default=-1, help="first iteration on the fp16 cores with split operands (-1 = library rule)")
+    ap.add_argument("--int8-slices", type=int, default=-1, help="products of the fp64 iterations: -1 = library default (int8 cores, 5 slices), 0 = fp64 cores, 4 | 5")
     ap.add_argument("--schedule", type=int, default=1, help="1 = interval-adapted coefficients, 0 = classical Newton")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-soap", action="store_true", help="skip the SOAP section (blocks <= 2048)")
@@ -133,7 +135,8 @@ def main() -> int:
     pblocks = ast.PBlocks(list(zip(XLs, Gs, XRs, Ps)))
     nf = len(factors)
     fsize = [m for m, n in shapes] + [n for m, n in shapes]
-    opts = ast.RootOpts(fp64_iters=args.fp64_iters, schedule=args.schedule, lowp_from=args.lowp_from)
+    opts = ast.RootOpts(fp64_iters=args.fp64_iters, schedule=args.schedule, lowp_from=args.lowp_from,
+                        int8_slices=args.int8_slices)
     full, mn = ast.inverse_root_workspace_bytes(factors, opts)
     ws_bytes = int(max(min(full, args.ws_gib * 2**30), mn, ast.precondition_workspace_bytes(pblocks),
                        ast.stats_update_workspace_bytes(blocks)))
@@ -197,6 +200,17 @@ def main() -> int:
     k32 = [ms for ms, kind in prof if kind == 0]
     k64 = [ms for ms, kind in prof if kind == 1]
     k16 = [ms for ms, kind in prof if kind == 224]       # 16-bit cores, both operands fp32 split in two fp16 terms
+    k8 = [ms for ms, kind in prof if kind in (304, 305)]  # int8 cores: fp64 operands as diagonal + 7-bit slices
+    t8 = sum(k8) * 1e-3
+    # int8 MFMA passes per product: 10 with 4 slices, 15 with 5; the count is chosen per factor and
+    # product on the device and not reported to the host, so the issue rate below is a lower bound
+    passes8 = 10.0
+    # the fp64 launches that follow the int8 ones take the products the device-side estimate declined;
+    # when they are (nearly) empty the flops of the fp64 iterations were done on the int8 cores
+    on_i8 = t8 > 0 and sum(k64) * 1e-3 < 0.05 * t8
+    flops8 = flops64 if on_i8 else 0.0
+    if on_i8: flops64 = 0.0
+    tf8 = flops8 / t8 / 1e12 if t8 > 0 else 0.0
     t16 = sum(k16) * 1e-3
     tf16 = flops16 / t16 / 1e12 if t16 > 0 else 0.0
     t32, t64 = sum(k32) * 1e-3, sum(k64) * 1e-3
@@ -210,7 +224,8 @@ def main() -> int:
     log(f"[bench] stats {stats_ms:.2f} ms  refresh {refresh_ms:.1f} ms  precondition {precond_ms:.2f} ms")
     log(f"[bench] fp32 GEMM: {len(k32)} launches, {t32 * 1e3:.1f} ms total, {tf32:.1f} TFLOP/s algorithmic; "
         f"fp64 GEMM: {len(k64)} launches, {t64 * 1e3:.1f} ms total, {tf64:.1f} TFLOP/s; "
-        f"split-fp16 GEMM: {len(k16)} launches, {t16 * 1e3:.1f} ms total, {tf16:.1f} fp32-equivalent TFLOP/s")
+        f"split-fp16 GEMM: {len(k16)} launches, {t16 * 1e3:.1f} ms total, {tf16:.1f} fp32-equivalent TFLOP/s; "
+        f"int8-slice GEMM: {len(k8)} launches, {t8 * 1e3:.1f} ms total, {tf8:.1f} fp64-equivalent TFLOP/s")
     log(f"[bench] Newton iterations min/mean/max {it.min()}/{it.mean():.1f}/{it.max()}, info!=0: {(info_h != 0).sum()}")
 
     out = {
@@ -256,8 +271,18 @@ def main() -> int:
                                 "traffic": stored_traffic("traffic_bytes_per_launch_fp16"), "launches": len(k16),
                                 "avg_launch_ms": round(1e3 * t16 / max(len(k16), 1), 4),
                                 "flops_per_launch": round(3 * flops16 / max(len(k16), 1), 1)},
+        "roofline_int8_slices": {"kernel": "gemm_i8_grouped_kernel<4 | 5 slices> (products of the fp64 iterations: each fp64 operand as its "
+                                           "diagonal plus 7-bit slices, 10 | 15 int8 MFMA passes per product, exact int32 sums, fp64 assembly; "
+                                           "the slice count is chosen per factor and product on the device)",
+                                 "bound": "mfma", "achieved": round(tf8 * passes8, 2), "peak": PEAK_I8_MFMA,
+                                 "unit": "TOP/s (int8 MFMA issued: lower bound, 10 passes per product)",
+                                 "frac": round(tf8 * passes8 / PEAK_I8_MFMA, 4),
+                                 "fp64_equivalent_tflops": round(tf8, 2),
+                                 "traffic": stored_traffic("traffic_bytes_per_launch_int8"),
+                                 "launches": len(k8), "avg_launch_ms": round(1e3 * t8 / max(len(k8), 1), 4),
+                                 "flops_per_launch": round(flops8 * passes8 / max(len(k8), 1), 1)},
         "gemm_time_share_ms_per_step": {"fp32": round(1e3 * t32 / args.steps, 1), "fp64": round(1e3 * t64 / args.steps, 1),
-                                        "split_fp16": round(1e3 * t16 / args.steps, 1)},
+                                        "split_fp16": round(1e3 * t16 / args.steps, 1), "int8_slices": round(1e3 * t8 / args.steps, 1)},
         "roofline_stats": {"bound": "hbm", "achieved": round(stats_bytes / stats_ms / 1e6, 1), "peak": PEAK_HBM,
                            "unit": "GB/s", "frac": round(stats_bytes / stats_ms / 1e6 / PEAK_HBM, 4),
                            "tflops": round(stats_flops / stats_ms / 1e9, 1)},
@@ -270,9 +295,13 @@ def main() -> int:
     }
 
     # `roofline` = the kernel that takes the largest share of the timed region
-    shares = {"roofline_fp32": t32, "roofline_fp64": t64, "roofline_split_fp16": t16}
+    shares = {"roofline_fp32": t32, "roofline_fp64": t64, "roofline_split_fp16": t16, "roofline_int8_slices": t8}
     if not k32:
         del out["roofline_fp32"], shares["roofline_fp32"]     # the default precision rules launch no fp32 product
+    if not k8:
+        del out["roofline_int8_slices"], shares["roofline_int8_slices"]
+    elif on_i8:
+        del out["roofline_fp64"], shares["roofline_fp64"]     # its launches were empty: every product passed the estimate
     dominant = max(shares, key=shares.get)
     out["roofline"] = dict(out[dominant], time_share_of_step=round(1e3 * shares[dominant] / args.steps / step_ms, 4))
 

@@ -134,6 +134,13 @@ typedef struct asteria_root_opts {
                               split into two fp16 terms (22 bits kept): -1 = choose from eps (default: right
                               after the fp64 prefix, n <= 16384; never for absolute eps),
                               >= max_iters = never                                                      */
+    int32_t int8_slices;   /* how the products of the fp64 iterations are computed: 0 = on the fp64 matrix
+                              cores; 4 or 5 = on the int8 matrix cores, each fp64 operand held as its
+                              diagonal plus that many 7-bit slices below a per-row exponent (29 / 36 bits),
+                              integer accumulation exact, result assembled in fp64 - per factor and
+                              product, and only where the part this drops is estimated on the device to
+                              stay below 2e-5 of the bottom of M's spectrum (otherwise that product runs
+                              on the fp64 cores); -1 = 5 (default)                                     */
 } asteria_root_opts;
 
 void asteria_root_opts_default(asteria_root_opts *opts);

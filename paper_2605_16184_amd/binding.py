@@ -51,7 +51,7 @@ class RootOpts(Structure):
     """Mirror of asteria_root_opts; constructed with the library defaults."""
     _fields_ = [("max_iters", c_int32), ("fp64_iters", c_int32), ("power_iters", c_int32),
                 ("schedule", c_int32), ("stop_resid", c_float), ("power_tol", c_float),
-                ("lambda_margin", c_float), ("lowp_from", c_int32)]
+                ("lambda_margin", c_float), ("lowp_from", c_int32), ("int8_slices", c_int32)]
 
     def __init__(self, **kw):
         super().__init__()

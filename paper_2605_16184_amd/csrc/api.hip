@@ -29,6 +29,7 @@ extern "C" void asteria_root_opts_default(asteria_root_opts *o)
     o->power_tol = 1e-3f;
     o->lambda_margin = 0.01f;
     o->lowp_from = -1;
+    o->int8_slices = -1;
 }
 
 // ---- measurement aid: HIP events around every grouped-GEMM launch ----------------------------

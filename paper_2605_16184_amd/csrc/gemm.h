@@ -57,6 +57,7 @@ struct GemmProblem {
     const float *coef;  // root epilogue: device pointer to (a, g), or null to use ep_a / ep_g
     const float *sa_dev; // fp16-split kernel: device pointer to the scale of operand A, or null to use sa
     const float *sb_dev; // the same for operand B (null: sb)
+    const int *gate;     // optional: the problem runs only while *gate == 0
     int M, N, K;
     int lda, ldb, ldc, ldc2, ldc3;
     int tile_start;  // id of this problem's first tile within the launch
@@ -616,6 +617,7 @@ __global__ __launch_bounds__(Mma<TC>::NTHR, Mma<TC>::MIN_WAVES) void gemm_groupe
         const int st = state[P.state_idx];
         if (!((1 << st) & P.state_mask)) return;
     }
+    if (P.gate && *P.gate != 0) return;
     const int flags = P.flags;
     const int lt = t_global - P.tile_start;
     int ti, tj;

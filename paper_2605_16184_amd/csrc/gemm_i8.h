@@ -1,0 +1,381 @@
+// gemm_i8.h - products of symmetric fp64 matrices on the int8 matrix cores.
+//
+// An fp64 operand S is written as  S = diag(S) + O  and the off-diagonal part O row by row as
+//     O[i][k] = 2^e_i * sum_{s < NS} d_s[i][k] 2^(-6 - 7 s),   d_s integers with |d_s| <= 64,
+// e_i = exponent of the largest |O[i][k]| of the row (so |O[i][k]| 2^-e_i < 1): NS slices of 7 bits
+// below a per-row exponent, 7 NS + 1 bits in all.  The product of two such operands is
+//     (Sa Sb)[i][j] = 2^(e_i + f_j) sum_l 2^(-12 - 7 l) sum_{s + t = l} sum_k d_s[i][k] d'_t[j][k]
+//                     + diag_a[i] Sb[i][j] + Sa[i][j] diag_b[j]            (i != j; B symmetric)
+// and diag_a[i] diag_b[i] in place of the last two terms for i = j.  The integer sums are exact in the
+// int32 accumulators of v_mfma_i32_32x32x32_i8 (|sum| <= NS K 2^12 < 2^31 for K <= 100000); the levels
+// l = s + t < NS are kept, the dropped ones are of relative size 2^(-7 NS) of the row scales.
+// Holding the diagonal out matters: a matrix a I - g M has a diagonal far above its off-diagonal
+// entries, and with it inside the slices the dropped levels would be measured against the diagonal.
+//
+// Slice layout in memory ("planes"): row i, block b of 32 consecutive k, slice s, 32 bytes:
+//     planes[((i * kb + b) * NS + s) * 32 + k % 32],   kb = ceil(n / 32),
+// rows padded with zero rows to a multiple of 128 and k padded with zeros to a multiple of 32, so
+// the product kernel reads whole tiles without guards.
+//
+// B mode 1: the B operand of the product is M, and the planes in buffer `bbuf` are those of
+// T = a I - g M (already cut for T T): off-diagonal M = -(off-diagonal T) / g, so the integer sums
+// are scaled by bscale = -1 / g and the diagonal of M is read from the matrix itself.  M is then
+// never cut into slices.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "gemm.h"
+
+namespace asteria {
+
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+typedef int i32x16 __attribute__((ext_vector_type(16)));
+typedef double doublex16 __attribute__((ext_vector_type(16)));
+typedef double doublex2_t __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+// Per factor: two sliced operand buffers (0: the A operand of every product, 1: the B operand where
+// it is another matrix) and the decision where the current product runs.
+struct I8Factor {
+    int8_t *planes[2];
+    int *expo[2];        // per row (padded): e_i
+    double *diag[2];     // per row (padded): S[i][i]
+    unsigned rmax[2];    // float bits: largest off-diagonal |entry| of the operand
+    unsigned dmax[2];    // float bits: largest |diagonal entry|
+    int gate;            // number of slices the current product is computed with on the int8 cores, or 0: fp64 cores
+    int n, kb;
+    float bscale;        // see the B modes of the product kernel
+};
+
+inline size_t i8_rows(int n) { return (size_t)((n + 127) & ~127); }
+inline size_t i8_plane_bytes(int n, int ns) { return i8_rows(n) * (size_t)((n + 31) / 32) * 32u * (size_t)ns; }
+
+// ---- slicing ------------------------------------------------------------------------------------
+// One wavefront per row.  Grid: x = groups of 4 rows (of the largest factor, padded), y = problem.
+// Reads operand A (use_b = 0) or B (use_b = 1) of the problem as an n x n fp64 matrix with an even
+// leading dimension and a 16-byte aligned base, writes buffer `buf` of the factor.
+template <int NS>
+__global__ __launch_bounds__(256) void i8_slice_kernel(const GemmProblem *__restrict__ probs, I8Factor *__restrict__ xf,
+                                                       const int *__restrict__ state, int use_b, int buf)
+{
+    const GemmProblem &P = probs[blockIdx.y];
+    if (P.state_idx >= 0) {
+        const int st = state[P.state_idx];
+        if (!((1 << st) & P.state_mask)) return;
+    }
+    I8Factor &X = xf[P.state_idx];
+    const int n = P.M;
+    const int npad = (n + 127) & ~127;
+    const int lane = threadIdx.x & 63;
+    const int row = (int)blockIdx.x * 4 + (int)(threadIdx.x >> 6);
+    if (row >= npad) return;
+    const int kb = X.kb;
+    const size_t rowbytes = (size_t)kb * (32 * NS);
+    int8_t *dst = X.planes[buf] + (size_t)row * rowbytes;
+    if (row >= n) {
+        for (size_t o = (size_t)lane * 16; o < rowbytes; o += 64 * 16)
+            *(ASTERIA_GLOBAL u32x4 *)(dst + o) = (u32x4){0u, 0u, 0u, 0u};
+        if (lane == 0) { X.expo[buf][row] = 0; X.diag[buf][row] = 0.0; }
+        return;
+    }
+    const double *S = reinterpret_cast<const double *>(use_b ? P.B : P.A);
+    const int ld = use_b ? P.ldb : P.lda;
+    const double *src = S + (size_t)row * ld;
+    // pass 1: largest off-diagonal magnitude of the row, and the diagonal entry
+    double mx = 0.0, dg = 0.0;
+    for (int k0 = lane * 2; k0 < n; k0 += 128) {
+        const doublex2_t v = *(const ASTERIA_GLOBAL doublex2_t *)(src + k0);
+        const double v0 = v[0], v1 = (k0 + 1 < n) ? v[1] : 0.0;
+        if (k0 == row) dg = v0; else mx = fmax(mx, fabs(v0));
+        if (k0 + 1 == row) dg = v1; else mx = fmax(mx, fabs(v1));
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        mx = fmax(mx, __shfl_xor(mx, off, 64));
+        dg += __shfl_xor(dg, off, 64);      // one lane holds the diagonal, the others 0
+    }
+    int e = 0;
+    if (mx > 0.0 && mx < 1e300) (void)frexp(mx, &e);   // mx = m 2^e, 0.5 <= m < 1
+    if (lane == 0) {
+        X.expo[buf][row] = e;
+        X.diag[buf][row] = dg;
+        atomicMax(&X.rmax[buf], __float_as_uint(fminf((float)mx * 1.0000002f, 3.0e38f)));
+        atomicMax(&X.dmax[buf], __float_as_uint(fminf((float)fabs(dg), 3.0e38f)));
+    }
+    // pass 2: 8 consecutive k per lane
+    const int kend = kb * 32;
+    for (int k0 = lane * 8; k0 < kend; k0 += 512) {
+        double u[8];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int k = k0 + 2 * j;
+            doublex2_t v = {0.0, 0.0};
+            if (k < n) v = *(const ASTERIA_GLOBAL doublex2_t *)(src + k);
+            u[2 * j] = (k == row) ? 0.0 : v[0];
+            u[2 * j + 1] = (k + 1 >= n || k + 1 == row) ? 0.0 : v[1];
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            double t = ldexp(u[j], 6 - e);      // |t| < 64
+            if (!(fabs(t) <= 64.0)) t = 0.0;    // non-finite input: the caller's state machine reports it
+            u[j] = t;
+        }
+        int8_t *d = dst + (size_t)(k0 >> 5) * (32 * NS) + (k0 & 31);
+#pragma unroll
+        for (int s = 0; s < NS; ++s) {
+            uint32_t w0 = 0u, w1 = 0u;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const double q = rint(u[j]);
+                u[j] = (u[j] - q) * 128.0;      // exact: the remainder has at most 46 bits left
+                const uint32_t b = (uint32_t)((int)q & 0xff);
+                if (j < 4) w0 |= b << (8 * j); else w1 |= b << (8 * (j - 4));
+            }
+            *(ASTERIA_GLOBAL u32x2 *)(d + s * 32) = (u32x2){w0, w1};
+        }
+    }
+}
+
+// ---- where a product runs ------------------------------------------------------------------------
+// The dropped levels s + t >= NS contribute, per entry, about 0.33 sqrt(K (NS - 1)) 2^(-7 NS) ra rb
+// (ra, rb: the row scales, bounded by the largest off-diagonal entries), measured here against
+// theta * lo * da * db: lo = the bottom of the spectrum of the current M (an error of relative size u
+// in the chain products costs about u / lo in the root), da db = the product of the largest diagonal
+// entries as a lower bound of ||Sa|| ||Sb||.  One thread per factor; clears the maxima for the next
+// operand.
+constexpr float I8_THETA = 2e-5f;
+
+// `scal` points at the factor's (lo, hi, g) of the current iteration: the interval that holds the
+// spectrum of the current M and the g of the current T = a I - g M.
+__global__ void i8_gate_kernel(I8Factor *__restrict__ xf, int nf, const float *__restrict__ scal, int scal_stride_bytes,
+                               int ns_min, int ns_max, int abuf, int bbuf, int bmode)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= nf) return;
+    I8Factor &X = xf[i];
+    const float *sc = reinterpret_cast<const float *>(reinterpret_cast<const char *>(scal) + (size_t)i * scal_stride_bytes);
+    const float lo = sc[0], hi = sc[1], g = sc[2];
+    const float ra = __uint_as_float(X.rmax[abuf]), da = __uint_as_float(X.dmax[abuf]);
+    float rb = __uint_as_float(X.rmax[bbuf]), db = __uint_as_float(X.dmax[bbuf]);
+    if (bmode == 1) {
+        // B = M seen through the planes of T: off-diagonal scale / g, and ||M|| is the top of its interval
+        rb = (g > 0.0f) ? rb / g : 3.0e38f;
+        db = hi;
+        X.bscale = (g > 0.0f) ? -1.0f / g : 0.0f;
+    }
+    const float allowed = I8_THETA * lo * da * db;
+    int gsel = 0;
+    for (int ns = ns_max; ns >= ns_min; --ns) {       // the fewest slices that pass
+        const float est = 0.33f * sqrtf((float)X.n * (float)(ns - 1)) * exp2f(-7.0f * (float)ns) * ra * rb;
+        if (est <= allowed && allowed > 0.0f) gsel = ns;
+    }
+    X.gate = gsel;
+    // buffer 0 is cut anew before every product; buffer 1 holds T from the first product of an
+    // iteration to the last (B mode 1)
+    X.rmax[0] = 0u; X.dmax[0] = 0u;
+    if (bmode == 1) { X.rmax[1] = 0u; X.dmax[1] = 0u; }
+}
+
+// ---- the product kernel --------------------------------------------------------------------------
+// 128 x 128 tile, 8 wavefronts in a 2 x 4 grid (64 x 32 each: two 32 x 32 MFMA tiles), one slab =
+// one block of 32 k for all NS slices: NS * 4 KB per operand, double-buffered in LDS as
+// [slice][k half][row][16 bytes], so the 32 lanes of one k half read 512 contiguous bytes per
+// fragment; each [slice][k half] piece is padded by 16 bytes, which spreads the 2 NS pieces of one
+// row, which consecutive lanes store, over different banks.  Per slab a wavefront reads 3 NS fragments and issues NS (NS + 1)
+// MFMAs into NS level accumulators per tile.  NSL is the number of slices the planes were written
+// with: a product may use only the leading NS of them (the slices are digits, most significant first).
+struct MmaI8 {
+    static constexpr int T = 32;
+    static constexpr int NACC = 16;
+    static constexpr int WAVES_M = 2, WAVES_N = 4;
+    static constexpr int NTHR = 512;
+    static constexpr int WTM = 2, WTN = 1;
+    typedef doublex16 acc_t;
+    __device__ static __forceinline__ int acc_row(int v, int h) { return 8 * (v >> 2) + 4 * h + (v & 3); }
+};
+
+// one tile with NS of the NSL slices the planes hold
+template <int NS, int NSL>
+__device__ __forceinline__ void i8_tile(const GemmProblem &P, const I8Factor &X, int lt, int abuf, int bbuf, int bmode,
+                                        unsigned char *smem_raw, float *red)
+{
+    constexpr int PIECE = 128 * 16 + 16;             // one k half of one slice of one operand: 128 rows x 16 bytes, padded
+    constexpr int OPERAND = 2 * NS * PIECE;
+    constexpr int STAGE = 2 * OPERAND;               // both operands
+    constexpr int CPR = 2 * NS;                      // 16-byte chunks per row and slab
+    constexpr int CHUNKS = 128 * CPR;                // per operand
+    constexpr int NV = (2 * CHUNKS) / 512;
+    static_assert((2 * CHUNKS) % 512 == 0, "chunks divide evenly over the threads");
+
+    ASTERIA_LDS unsigned char *smem_i8 = (ASTERIA_LDS unsigned char *)smem_raw;
+    int ti, tj;
+    tri_decode(lt, ti, tj);                          // symmetric products only
+    const int n = P.M;
+    const int row0 = ti * BM, col0 = tj * BN;
+    const int kb = X.kb;
+    const size_t rowbytes = (size_t)kb * (32 * NSL);
+    const int8_t *Ap = X.planes[abuf] + (size_t)row0 * rowbytes;
+    const int8_t *Bp = X.planes[bbuf] + (size_t)col0 * rowbytes;
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave / MmaI8::WAVES_N, wn = wave % MmaI8::WAVES_N;
+    const int r = lane & 31, h = lane >> 5;
+
+    // staging: chunk idx = tid + 512 v over both operands
+    const int8_t *gsrc[NV];
+    int ldst[NV];
+#pragma unroll
+    for (int v = 0; v < NV; ++v) {
+        const int idx = tid + 512 * v;
+        const int op = idx / CHUNKS, c = idx % CHUNKS;
+        const int row = c / CPR, piece = c % CPR;
+        gsrc[v] = (op ? Bp : Ap) + (size_t)row * rowbytes + piece * 16;
+        ldst[v] = op * OPERAND + piece * PIECE + row * 16;
+    }
+    constexpr int DEPTH = 1;                         // slabs in flight from global memory (2 was slower)
+    u32x4 stg[DEPTH][NV];
+    auto gload = [&](u32x4 (&set)[NV], int slab) {
+#pragma unroll
+        for (int v = 0; v < NV; ++v) set[v] = *(const ASTERIA_GLOBAL u32x4 *)(gsrc[v] + (size_t)slab * (32 * NSL));
+    };
+    auto lstore = [&](const u32x4 (&set)[NV], int buf) {
+#pragma unroll
+        for (int v = 0; v < NV; ++v) *(ASTERIA_LDS u32x4 *)(smem_i8 + buf * STAGE + ldst[v]) = set[v];
+    };
+
+    i32x16 acc[NS][2];
+#pragma unroll
+    for (int l = 0; l < NS; ++l)
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[l][i][v] = 0;
+
+    auto compute = [&](int cur) {
+        const ASTERIA_LDS unsigned char *LA = smem_i8 + cur * STAGE;
+        const ASTERIA_LDS unsigned char *LB = LA + OPERAND;
+        i32x4 a[NS][2], b[NS];
+#pragma unroll
+        for (int s = 0; s < NS; ++s) {
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+                a[s][i] = *(const ASTERIA_LDS i32x4 *)(LA + (2 * s + h) * PIECE + (wm * 64 + i * 32 + r) * 16);
+            b[s] = *(const ASTERIA_LDS i32x4 *)(LB + (2 * s + h) * PIECE + (wn * 32 + r) * 16);
+        }
+        // consecutive MFMAs write different accumulators
+#pragma unroll
+        for (int s = 0; s < NS; ++s)
+#pragma unroll
+            for (int t = 0; t < NS - s; ++t)
+#pragma unroll
+                for (int i = 0; i < 2; ++i)
+                    acc[s + t][i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[s][i], b[t], acc[s + t][i], 0, 0, 0);
+    };
+
+    gload(stg[0], 0);
+    lstore(stg[0], 0);
+    int cur = 0;
+    {
+        __syncthreads();
+        for (int slab = 0; slab < kb; ++slab) {
+            const bool more = slab + 1 < kb;
+            if (more) gload(stg[0], slab + 1);
+            compute(cur);
+            if (more) lstore(stg[0], cur ^ 1);
+            __syncthreads();
+            cur ^= 1;
+        }
+    }
+
+    // levels -> fp64, row and column scales, the held-out diagonals
+    const int *ea = X.expo[abuf], *eb = X.expo[bbuf];
+    const double *da = X.diag[abuf], *db = X.diag[bbuf];
+    const double *Sa = reinterpret_cast<const double *>(P.A), *Sb = reinterpret_cast<const double *>(P.B);
+    const int lda = P.lda, ldb = P.ldb;
+    doublex16 accd[2][1];
+    const int col = col0 + wn * 32 + r;
+    const bool col_ok = col < n;
+    const int ecol = eb[col];                  // the arrays are padded to whole tiles
+    const bool same = bmode == 0 && P.A == P.B && abuf == bbuf;
+    const double bs = bmode == 1 ? (double)X.bscale : 1.0;
+    const double dcol = bmode == 1 ? (col_ok ? Sb[(size_t)col * ldb + col] : 0.0) : db[col];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int row = row0 + wm * 64 + i * 32 + MmaI8::acc_row(v, h);
+            double s = 0.0;
+#pragma unroll
+            for (int l = NS - 1; l >= 0; --l) s += (double)acc[l][i][v] * (1.0 / (double)(1ull << (12 + 7 * l)));
+            double val = 0.0;
+            if (col_ok && row < n) {
+                val = ldexp(s, ea[row] + ecol) * bs;
+                const double drow = da[row];
+                if (row == col) val += drow * dcol;
+                else if (same) val += Sa[(size_t)row * lda + col] * (drow + dcol);     // a square: one load
+                else val += drow * Sb[(size_t)row * ldb + col] + Sa[(size_t)row * lda + col] * dcol;
+            }
+            accd[i][0][v] = val;
+        }
+    }
+    const int rowsA = min(BM, n - row0), rowsB = min(BN, n - col0);
+    gemm_epilogue<MmaI8, double>(P, accd, lt, ti, tj, row0, col0, rowsA, rowsB, wm, wn, r, h, lane, wave, tid, red);
+}
+
+// One launch serves every slice count the planes allow: the factor's gate picks the tile routine
+// (a launch per count would add a grid of workgroups that only look up their factor and leave).
+template <int NSL>
+__global__ __launch_bounds__(512, 2) void gemm_i8_grouped_kernel(const GemmProblem *__restrict__ probs,
+                                                                 const I8Factor *__restrict__ xf, int nprobs,
+                                                                 int total_tiles, const int *__restrict__ state, int abuf,
+                                                                 int bbuf, int bmode)
+{
+    extern __shared__ __align__(16) unsigned char smem_i8_raw[];
+    __shared__ float red[8];
+
+    const int per_xcd = (total_tiles + NUM_XCD - 1) / NUM_XCD;
+    const int t_global = (int)(blockIdx.x % NUM_XCD) * per_xcd + (int)(blockIdx.x / NUM_XCD);
+    if (t_global >= total_tiles) return;
+    int lo = 0, hi = nprobs - 1;
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (probs[mid].tile_start <= t_global) lo = mid; else hi = mid - 1;
+    }
+    const GemmProblem &P = probs[lo];
+    {
+        const int st = state[P.state_idx];
+        if (!((1 << st) & P.state_mask)) return;
+    }
+    const I8Factor &X = xf[P.state_idx];
+    const int g = X.gate;
+    const int lt = t_global - P.tile_start;
+    if (g == 4) i8_tile<4, NSL>(P, X, lt, abuf, bbuf, bmode, smem_i8_raw, red);
+    if constexpr (NSL >= 5) {
+        if (g == 5) i8_tile<5, NSL>(P, X, lt, abuf, bbuf, bmode, smem_i8_raw, red);
+    }
+}
+
+template <int NSL>
+hipError_t launch_gemm_i8_grouped(const GemmProblem *d_probs, const I8Factor *d_xf, int nprobs, int total_tiles,
+                                  const int *d_state, int abuf, int bbuf, int bmode, hipStream_t stream)
+{
+    if (nprobs <= 0 || total_tiles <= 0) return hipSuccess;
+    constexpr int LDS_BYTES = 2 * 2 * 2 * NSL * (128 * 16 + 16);
+    static bool configured = false;
+    if (!configured) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_i8_grouped_kernel<NSL>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
+        if (e != hipSuccess) return e;
+        configured = true;
+    }
+    const int per_xcd = (total_tiles + NUM_XCD - 1) / NUM_XCD;
+    profile_begin(300 + NSL, stream);
+    hipLaunchKernelGGL(gemm_i8_grouped_kernel<NSL>, dim3(per_xcd * NUM_XCD), dim3(512), LDS_BYTES, stream, d_probs, d_xf,
+                       nprobs, total_tiles, d_state, abuf, bbuf, bmode);
+    profile_end(stream);
+    return hipGetLastError();
+}
+
+}  // namespace asteria

@@ -29,6 +29,7 @@
 #include "common.h"
 #include "gemm.h"
 #include "gemm_bf16.h"
+#include "gemm_i8.h"
 #include "root_schedule.h"
 
 using namespace asteria;
@@ -85,6 +86,9 @@ struct FactorScal {
     float coef_next[2];   // coefficients the M-update epilogue uses for the next T
     float fro2, trace;    // ||A||_F^2 and tr(A), gathered during the first power-iteration step
     float x_scale;        // power of two that brings X into the fp16 range for the 16-bit products
+    // (lo, hi) of the M the current iteration starts from and the g of its T: lo, hi, ca, cg above
+    // are advanced to the next iteration's before the products of the current one run
+    float lo_cur, hi_cur, cg_cur;
 };
 
 // Scale of M, T, T^2, T^4 in the fp16-split products: their entries stay below a^4 < 23 (a <= 2.2),
@@ -509,6 +513,7 @@ __global__ __launch_bounds__(64) void root_control_kernel(const FactorDev *fd, F
             const RootInterval im = root_image(lo_k, hi_k, root, (double)S.ca, (double)S.cg);
             double a, g;
             root_coefficients(im.lo, im.hi, root, adapted != 0, ROOT_THETA, a, g);
+            S.lo_cur = S.lo; S.hi_cur = S.hi; S.cg_cur = S.cg;
             S.lo = (float)im.lo; S.hi = (float)im.hi;
             S.ca = (float)a; S.cg = (float)g;
             S.coef_next[0] = (float)a; S.coef_next[1] = (float)g;
@@ -587,6 +592,7 @@ struct Plan {
     int lowp_from;     // first iteration that may run on the fp16 matrix cores (operands split in two fp16 terms)
     float stop_resid, power_tol, margin;
     bool use64, use32, adapted, lowp_auto;
+    int i8_slices;     // 0, or the number of int8 slices the products of the fp64 iterations are computed with
     bool xt_lowp;      // fully automatic precision: X updates on the fp16 cores (split operands) from the
                        // first product on, and the look-ahead stop rule (accuracy class 1e-3)
 };
@@ -635,6 +641,14 @@ size_t factor_matrix_bytes(int n, bool use64, bool use32)
     b += shared_region_bytes(n, use64, use32);                                 // fp64 T, T^4 | fp32 M x 2, T^4
     if (use64) b += 2 * Carver::need((size_t)n * ld2(n), sizeof(double));      // fp64 M x 2
     return b;
+}
+
+// sliced operands of the int8 path: two buffers of planes, row exponents and diagonals
+size_t factor_i8_bytes(int n, int ns)
+{
+    if (ns <= 0) return 0;
+    return 2 * (Carver::need(i8_plane_bytes(n, ns), 1) + Carver::need(i8_rows(n), sizeof(int)) +
+                Carver::need(i8_rows(n), sizeof(double))) + Carver::need(1, sizeof(I8Factor));
 }
 
 size_t factor_small_bytes(int n)
@@ -702,6 +716,8 @@ asteria_status make_plan(const asteria_root_opts *opts_in, asteria_eps_mode mode
     pl.fp64_iters = std::min(j, pl.max_iters);
     pl.use64 = pl.fp64_iters > 0;
     pl.use32 = pl.fp64_iters < pl.max_iters;
+    if (o.int8_slices != -1 && o.int8_slices != 0 && o.int8_slices != 4 && o.int8_slices != 5) return ASTERIA_UNSUPPORTED;
+    pl.i8_slices = pl.use64 ? (o.int8_slices < 0 ? 5 : o.int8_slices) : 0;
     return ASTERIA_OK;
 }
 
@@ -727,7 +743,7 @@ struct RootTables {
 
 // one thread per factor writes its entry of every table
 __global__ void root_tables_kernel(const FactorDev *__restrict__ fd, FactorScal *fs, int cnt, int root, int use32,
-                                   int use64, RootTables rt)
+                                   int use64, RootTables rt, const I8Factor *xf)
 {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= cnt) return;
@@ -763,6 +779,8 @@ __global__ void root_tables_kernel(const FactorDev *__restrict__ fd, FactorScal 
                 Tm = F.T32; Tw = F.T32; Mcur = F.M32[pa]; Mnext = F.M32[pa ^ 1]; T4 = F.T432; ldw = F.ld32;
             }
             GemmProblem q = p;
+            // with the int8 path on, the fp64 launches take the products it declines
+            if (pr == 1 && xf) q.gate = &xf[i].gate;
             // launch 0: T2 = T T, kept in the buffer that receives M' afterwards (root 4) or in
             // the T^4 buffer (root 2, where the M-update reads T2 while writing M')
             void *T2 = (root == 4) ? Mnext : T4;
@@ -832,6 +850,26 @@ asteria_status run_pass(const asteria_factor *f, const std::vector<int> &order, 
         F.pm_partial2 = cv.take<float2>(F.pm_blocks);
         F.partial = cv.take<float>(F.ntri);
     }
+    // factors too large for exact int32 sums (never reached by the 16384 limit of the other tiers'
+    // workloads) keep the fp64 cores
+    const int ns8 = (pl.i8_slices > 0 && n_max <= 65536) ? pl.i8_slices : 0;
+    I8Factor *d_xf = nullptr;
+    std::vector<I8Factor> xfh;
+    if (ns8 > 0) {
+        d_xf = cv.take<I8Factor>(cnt);
+        xfh.resize(cnt);
+        for (int i = 0; i < cnt; ++i) {
+            I8Factor &X = xfh[i];
+            memset(&X, 0, sizeof(X));
+            const int n = fd[i].n;
+            for (int b = 0; b < 2; ++b) {
+                X.planes[b] = cv.take<int8_t>(i8_plane_bytes(n, ns8));
+                X.expo[b] = cv.take<int>(i8_rows(n));
+                X.diag[b] = cv.take<double>(i8_rows(n));
+            }
+            X.n = n; X.kb = (n + 31) / 32;
+        }
+    }
     for (int i = 0; i < cnt; ++i) {
         FactorDev &F = fd[i];
         const size_t e32 = (size_t)F.n * F.ld32, e64 = (size_t)F.n * F.ld64;
@@ -871,8 +909,9 @@ asteria_status run_pass(const asteria_factor *f, const std::vector<int> &order, 
     for (int pr = 0; pr < 2; ++pr)
         for (int pa = 0; pa < 2; ++pa)
             for (int l = 0; l < 3; ++l) rt.tab[pr][pa][l] = d_tab[pr][pa][l];
+    if (ns8 > 0) ASTERIA_HIP_TRY(upload_async(d_xf, xfh.data(), sizeof(I8Factor) * cnt, stream));
     hipLaunchKernelGGL(root_tables_kernel, dim3((cnt + 127) / 128), dim3(128), 0, stream, d_fd, d_fs, cnt, root,
-                       pl.use32 ? 1 : 0, pl.use64 ? 1 : 0, rt);
+                       pl.use32 ? 1 : 0, pl.use64 ? 1 : 0, rt, d_xf);
     ASTERIA_HIP_TRY(hipGetLastError());
 
     // 1. lambda_max
@@ -922,10 +961,25 @@ asteria_status run_pass(const asteria_factor *f, const std::vector<int> &order, 
                 ASTERIA_HIP_TRY((launch_gemm_grouped<float, float, float, false, false>(d_tab[0][pa][1], cnt, tri_total, d_state, stream)));
             ASTERIA_HIP_TRY((launch_gemm_grouped<float, float, float, false, false>(d_tab[0][pa][2], cnt, tri_total, d_state, stream)));
         } else {
-            ASTERIA_HIP_TRY((launch_gemm_grouped<double, double, double, false, false>(d_tab[1][pa][0], cnt, tri_total, d_state, stream)));
-            if (root == 4)
-                ASTERIA_HIP_TRY((launch_gemm_grouped<double, double, double, false, false>(d_tab[1][pa][1], cnt, tri_total, d_state, stream)));
-            ASTERIA_HIP_TRY((launch_gemm_grouped<double, double, double, false, false>(d_tab[1][pa][2], cnt, tri_total, d_state, stream)));
+            for (int l = 0; l < 3; ++l) {
+                if (l == 1 && root != 4) continue;
+                if (ns8 > 0) {
+                    // Cut the A operand into slices, decide per factor, multiply.  T goes to buffer 1
+                    // and stays there: T T reads it twice, and T^4 M reads it as M (B mode 1), so M
+                    // itself is never cut; T^2 and T^4 go to buffer 0.
+                    const dim3 sgrid((unsigned)((i8_rows(n_max) + 3) / 4), (unsigned)cnt);
+                    const int abuf = l == 0 ? 1 : 0, bbuf = l == 1 ? 0 : 1, bmode = l == 2 ? 1 : 0;
+                    if (ns8 == 5) hipLaunchKernelGGL(i8_slice_kernel<5>, sgrid, dim3(256), 0, stream, d_tab[1][pa][l], d_xf, d_state, 0, abuf);
+                    else hipLaunchKernelGGL(i8_slice_kernel<4>, sgrid, dim3(256), 0, stream, d_tab[1][pa][l], d_xf, d_state, 0, abuf);
+                    // per factor: 4 slices where the estimate allows, else 5 (if the planes have them), else fp64
+                    hipLaunchKernelGGL(i8_gate_kernel, dim3(ctl_blocks), dim3(128), 0, stream, d_xf, cnt, &d_fs[0].lo_cur,
+                                       (int)sizeof(FactorScal), 4, ns8, abuf, bbuf, bmode);
+                    ASTERIA_HIP_TRY(hipGetLastError());
+                    if (ns8 == 5) ASTERIA_HIP_TRY((launch_gemm_i8_grouped<5>(d_tab[1][pa][l], d_xf, cnt, tri_total, d_state, abuf, bbuf, bmode, stream)));
+                    else ASTERIA_HIP_TRY((launch_gemm_i8_grouped<4>(d_tab[1][pa][l], d_xf, cnt, tri_total, d_state, abuf, bbuf, bmode, stream)));
+                }
+                ASTERIA_HIP_TRY((launch_gemm_grouped<double, double, double, false, false>(d_tab[1][pa][l], cnt, tri_total, d_state, stream)));
+            }
         }
     }
     hipLaunchKernelGGL(root_control_kernel, dim3(cnt), dim3(64), 0, stream, d_fd, d_fs, d_state, K,
@@ -970,7 +1024,8 @@ extern "C" size_t asteria_inverse_root_workspace_bytes(const asteria_factor *f, 
     size_t total = fixed_bytes(), biggest = 0;
     for (int i = 0; i < nfactors; ++i) {
         if (f[i].n <= 0) return 0;
-        const size_t b = factor_matrix_bytes(f[i].n, use64, use32) + factor_small_bytes(f[i].n);
+        const size_t b = factor_matrix_bytes(f[i].n, use64, use32) + factor_small_bytes(f[i].n) +
+                         factor_i8_bytes(f[i].n, use64 ? (o.int8_slices < 0 ? 5 : o.int8_slices) : 0);
         total += b;
         biggest = std::max(biggest, b);
     }
@@ -1004,7 +1059,8 @@ extern "C" asteria_status asteria_inverse_root(const asteria_factor *f, int nfac
         int cnt = 0;
         while (first + cnt < nfactors && cnt < 65535) {   // 65535: y extent of the mat-vec grid
             const int n = f[first + cnt].n;
-            const size_t b = factor_matrix_bytes(n, pl.use64, pl.use32) + factor_small_bytes(n);
+            const size_t b = factor_matrix_bytes(n, pl.use64, pl.use32) + factor_small_bytes(n) +
+                             factor_i8_bytes(n, pl.i8_slices);
             if (used + b > ws_bytes) break;
             used += b;
             ++cnt;

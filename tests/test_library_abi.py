@@ -133,9 +133,13 @@ def test_workspace_queries_scale_with_the_batch():
     mn = ctypes.c_size_t(0)
     full = ast.lib().asteria_inverse_root_workspace_bytes(one, 1, None, ctypes.byref(mn))
     # default options reserve 2 fp32 and 4 fp64 work matrices per factor (X stays in fp32 in every
-    # tier; the fp32 matrices of the M-chain reuse the room of the fp64 T and T^4)
-    assert full >= (2 * 4 + 4 * 8) * 1024 * 1024 and full < 1.1 * (2 * 4 + 4 * 8) * 1024 * 1024
+    # tier; the fp32 matrices of the M-chain reuse the room of the fp64 T and T^4) and two operands
+    # of 5 int8 slices
+    assert full >= (2 * 4 + 4 * 8 + 2 * 5) * 1024 * 1024 and full < 1.1 * (2 * 4 + 4 * 8 + 2 * 5) * 1024 * 1024
     assert mn.value == full
+    o = ast.RootOpts(int8_slices=0)
+    f64 = ast.lib().asteria_inverse_root_workspace_bytes(one, 1, ctypes.byref(o), None)
+    assert (2 * 4 + 4 * 8) * 1024 * 1024 <= f64 < 1.1 * (2 * 4 + 4 * 8) * 1024 * 1024
     o = ast.RootOpts(fp64_iters=0)
     f32 = ast.lib().asteria_inverse_root_workspace_bytes(one, 1, ctypes.byref(o), None)
     assert 5 * 4 * 1024 * 1024 <= f32 < 1.1 * 5 * 4 * 1024 * 1024
