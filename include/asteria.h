@@ -168,8 +168,10 @@ asteria_status asteria_stats_update(const asteria_block *blocks, int nblocks, fl
  * Newton values, see `schedule`); a factor stops by itself - one more X update follows - once its
  * residual ||M - I||_F has fallen below stop_resid or the interval predicted for M's spectrum is
  * within 1 +- 1e-2 (and, under the automatic precision rules, already when the image of that
- * interval under the next update is within 1 +- 3e-3).  The leading fp64_iters iterations use
- * the fp64 matrix cores, the middle ones the fp32 matrix cores, and the last ones (from
+ * interval under the next update is within 1 +- 3e-3).  The leading fp64_iters iterations work
+ * on fp64 matrices - their products on the int8 matrix cores from integer slices of the operands,
+ * exact sums, fp64 assembly, or on the fp64 matrix cores, see `int8_slices` -, the middle ones use
+ * the fp32 matrix cores, and the last ones (from
  * `lowp_from` on) the fp16 matrix cores with every fp32 operand split into two fp16 terms (scaled
  * into the fp16 range by a power of two that the call derives from the bounds it keeps on M and X;
  * the operands are kept to 2^-22).
@@ -180,8 +182,9 @@ asteria_status asteria_stats_update(const asteria_block *blocks, int nblocks, fl
  *   lambda_max device float[nfactors] or NULL   (the estimate used)
  * Workspace: the call splits the batch into passes that fit ws_bytes; *min_bytes is the size
  * needed for the largest single factor.
- * Errors: NULL A or X, n <= 0, ld < n, unsupported root, eps < 0 or non-finite, eps_count not
- * in {1, nfactors} -> INVALID_ARG / UNSUPPORTED; ws too small -> WORKSPACE_TOO_SMALL.        */
+ * Errors: NULL A or X, n <= 0, ld < n, unsupported root or int8_slices, eps < 0 or non-finite,
+ * eps_count not in {1, nfactors} -> INVALID_ARG / UNSUPPORTED; ws too small ->
+ * WORKSPACE_TOO_SMALL.                                                                       */
 /* The precision schedule asteria_inverse_root would use for these arguments (host only, nothing is
  * launched): number of leading fp64 iterations of the M-chain (T^2, T^4, T^4 M), first iteration of
  * that chain on the fp16 matrix cores (>= max_iters = never; factors larger than 16384 stay on the

@@ -13,13 +13,20 @@
 //      sums of ||M - I||_F^2.  A per-factor state machine on the device (running -> last X
 //      update -> done) lets finished factors drop out without any host round trip: their
 //      workgroups exit at once.
-//   4. The leading iterations of the M-chain run on fp64 MFMA, where the smallest eigenvalues of
-//      M are still comparable to fp32 round-off; the state is then cast to fp32 and continues on
+//   4. The leading iterations of the M-chain keep fp64 matrices, where the smallest eigenvalues
+//      of M are still comparable to fp32 round-off.  Their products run on the int8 matrix cores:
+//      each operand is cut into its diagonal and 7-bit integer slices under a per-row exponent,
+//      the integer sums are exact and the result is assembled in fp64 (gemm_i8.h); per factor
+//      and product a device-side estimate of what the dropped slice pairs cost picks 4 or 5
+//      slices or sends the product to the fp64 matrix cores.  The state is then cast to fp32 and
+//      continues on
 //      the fp16 matrix cores with every fp32 operand split into two fp16 terms (2^-22 per
 //      operand; the fp32 matrix cores serve pinned options, absolute eps and very large n).  X
 //      is kept in fp32 throughout and its updates run on the fp16 cores from the start.
 //
-// Per iteration: 1 control kernel + up to 4 launches (X T; T T; T^2 T^2; T^4 M).
+// Per iteration: 1 control kernel + up to 4 launches (X T; T T; T^2 T^2; T^4 M); in the fp64
+// iterations each chain product is a slicing pass, a decision kernel, the int8 launch and the
+// fp64 launch for the factors the decision kept there.
 #include <math.h>
 #include <stddef.h>
 

@@ -161,6 +161,15 @@ def test_precision_plan_follows_eps_and_pinned_options():
     assert ast.inverse_root_plan(1e-6, opts=ast.RootOpts(lowp_from=5))[1:] == (5, False)
     j64c, _, _ = ast.inverse_root_plan(1e-6, opts=ast.RootOpts(schedule=0))
     assert j64c > 2                                              # classical coefficients lift the spectrum more slowly
+    # where the products of the fp64 iterations run is a separate option: default (int8 cores, up to 5
+    # slices), fp64 cores, at most 4 slices; other counts are refused
+    assert ast.RootOpts().int8_slices == -1
+    for ns in (0, 4, 5):
+        assert ast.inverse_root_plan(1e-6, opts=ast.RootOpts(int8_slices=ns)) == (2, 2, True)
+    eps1 = (ctypes.c_float * 1)(1e-6)
+    for ns in (3, 6, -2):
+        o = ast.RootOpts(int8_slices=ns)
+        assert ast.lib().asteria_inverse_root_plan(4, 0, eps1, 1, ctypes.byref(o), None, None, None) == B.UNSUPPORTED
 
 
 def test_model_block_census_matches_the_1p1b_configuration():

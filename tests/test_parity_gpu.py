@@ -221,6 +221,46 @@ def test_root_ill_conditioned_logspaced_spectrum_eps_1e8():
     assert 20 <= iters_c[0] <= 30
 
 
+def test_root_fp64_iterations_on_the_int8_cores_against_the_fp64_cores_and_the_oracle():
+    # The products of the fp64 iterations run on the int8 matrix cores (diagonal + 7-bit slices) where a
+    # device-side estimate allows it, else on the fp64 cores.  Spectra and structures on both sides of
+    # that decision: delocalised eigenvectors (small off-diagonal entries: 4 slices pass), an
+    # equicorrelated matrix and a block-diagonal one with localised eigenvectors (off-diagonal entries
+    # of the size of the diagonal: more slices, or the fp64 cores), a diagonal matrix (empty slices),
+    # ragged sizes that are no multiple of the 32-wide slice blocks.
+    n = 300
+    ones = torch.ones(n, n, device=DEV, dtype=torch.float64)
+    equi = 0.02 * (0.1 * torch.eye(n, device=DEV, dtype=torch.float64) + 0.9 * ones / n * 30)
+    blk = torch.zeros(n, n, device=DEV, dtype=torch.float64)
+    d = 0.05 * W.logspaced_sigma(n, 5.0, DEV).double() ** 2
+    for i in range(0, n - 1, 2):                       # 2 x 2 blocks [[a, b], [b, a]]: eigenvectors (1, +-1)
+        a_, b_ = 0.5 * (d[i] + d[i + 1]), 0.5 * (d[i] - d[i + 1])
+        blk[i, i] = blk[i + 1, i + 1] = a_; blk[i, i + 1] = blk[i + 1, i] = b_
+    cases = {"power law": powerlaw_factor(n, 21), "log-spaced": logspaced_factor(173, 6.0, 22),
+             "equicorrelated": equi.float().contiguous(), "2x2 blocks": blk.float().contiguous(),
+             "diagonal": torch.diag(d.float()).contiguous(), "small": powerlaw_factor(45, 23)}
+    for name, A in cases.items():
+        st, Xo, lmax_o, lam = oracle.inverse_root(np64(A), 1e-6, return_status=True)
+        assert st == oracle.OK, name
+        res = {}
+        for ns in (-1, 0, 4):                           # library rule (up to 5 slices), fp64 cores only, 4 slices at most
+            (X,), info, iters, resid, lmax = run_roots([A], 1e-6, opts=ast.RootOpts(int8_slices=ns))
+            assert info[0] == B.INFO_OK, (name, ns)
+            assert relF(X, Xo) <= TOL_ROOT, (name, ns, relF(X, Xo))
+            assert torch.equal(X, X.T)
+            res[ns] = (np64(X), int(iters[0]))
+        assert res[-1][1] == res[0][1] == res[4][1], name   # the schedule does not depend on where the products run
+        # the int8 path reproduces the fp64-core result far inside the tolerance
+        assert relF(res[-1][0], res[0][0]) <= 2.5e-4, (name, relF(res[-1][0], res[0][0]))
+        assert relF(res[4][0], res[0][0]) <= 2.5e-4, (name, relF(res[4][0], res[0][0]))
+    # a batch: every factor takes its own decision
+    As = list(cases.values())
+    Xs, info, iters, resid, lmax = run_roots(As, 1e-6)
+    for A, X in zip(As, Xs):
+        Xo, _, _ = oracle.inverse_root(np64(A), 1e-6)
+        assert relF(X, Xo) <= TOL_ROOT
+
+
 def newton_count(a: float, n: int, stop: float = 1e-2, p: int = 4) -> int:
     """Scalar model of the coupled iteration on the smallest eigenvalue a of M_0."""
     mu, k = a, 0
