@@ -52,18 +52,21 @@ inline size_t i8_rows(int n) { return (size_t)((n + 127) & ~127); }
 inline size_t i8_plane_bytes(int n, int ns) { return i8_rows(n) * (size_t)((n + 31) / 32) * 32u * (size_t)ns; }
 
 // ---- slicing ------------------------------------------------------------------------------------
-// One wavefront per row.  Grid: x = groups of 4 rows (of the largest factor, padded), y = problem.
+// One wavefront per row (rows of up to 2048 entries are parked in LDS between finding the row scale
+// and cutting, longer ones are read twice).  Grid: x = groups of 4 rows (of the largest factor, padded), y = problem.
 // Reads operand A (use_b = 0) or B (use_b = 1) of the problem as an n x n fp64 matrix with an even
 // leading dimension and a 16-byte aligned base, writes buffer `buf` of the factor.
+constexpr int I8_SLICE_LDS_K = 1024;   // longest (padded) row the slicing kernel parks in LDS
 template <int NS>
 __global__ __launch_bounds__(256) void i8_slice_kernel(const GemmProblem *__restrict__ probs, I8Factor *__restrict__ xf,
-                                                       const int *__restrict__ state, int use_b, int buf)
+                                                       const int *__restrict__ state, int use_b, int buf, int lds_k)
 {
     const GemmProblem &P = probs[blockIdx.y];
     if (P.state_idx >= 0) {
         const int st = state[P.state_idx];
         if (!((1 << st) & P.state_mask)) return;
     }
+    extern __shared__ __align__(16) double slice_lds[];   // 4 rows of ceil(lds_k / 16) * 17 doubles, or nothing
     I8Factor &X = xf[P.state_idx];
     const int n = P.M;
     const int npad = (n + 127) & ~127;
@@ -82,46 +85,31 @@ __global__ __launch_bounds__(256) void i8_slice_kernel(const GemmProblem *__rest
     const double *S = reinterpret_cast<const double *>(use_b ? P.B : P.A);
     const int ld = use_b ? P.ldb : P.lda;
     const double *src = S + (size_t)row * ld;
-    // pass 1: largest off-diagonal magnitude of the row, and the diagonal entry
-    double mx = 0.0, dg = 0.0;
-    for (int k0 = lane * 2; k0 < n; k0 += 128) {
-        const doublex2_t v = *(const ASTERIA_GLOBAL doublex2_t *)(src + k0);
-        const double v0 = v[0], v1 = (k0 + 1 < n) ? v[1] : 0.0;
-        if (k0 == row) dg = v0; else mx = fmax(mx, fabs(v0));
-        if (k0 + 1 == row) dg = v1; else mx = fmax(mx, fabs(v1));
-    }
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) {
-        mx = fmax(mx, __shfl_xor(mx, off, 64));
-        dg += __shfl_xor(dg, off, 64);      // one lane holds the diagonal, the others 0
-    }
-    int e = 0;
-    if (mx > 0.0 && mx < 1e300) (void)frexp(mx, &e);   // mx = m 2^e, 0.5 <= m < 1
-    if (lane == 0) {
-        X.expo[buf][row] = e;
-        X.diag[buf][row] = dg;
-        atomicMax(&X.rmax[buf], __float_as_uint(fminf((float)mx * 1.0000002f, 3.0e38f)));
-        atomicMax(&X.dmax[buf], __float_as_uint(fminf((float)fabs(dg), 3.0e38f)));
-    }
-    // pass 2: 8 consecutive k per lane
     const int kend = kb * 32;
-    for (int k0 = lane * 8; k0 < kend; k0 += 512) {
-        double u[8];
+    auto finish_scale = [&](double mx, double dg) -> int {
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int k = k0 + 2 * j;
-            doublex2_t v = {0.0, 0.0};
-            if (k < n) v = *(const ASTERIA_GLOBAL doublex2_t *)(src + k);
-            u[2 * j] = (k == row) ? 0.0 : v[0];
-            u[2 * j + 1] = (k + 1 >= n || k + 1 == row) ? 0.0 : v[1];
+        for (int off = 32; off > 0; off >>= 1) {
+            mx = fmax(mx, __shfl_xor(mx, off, 64));
+            dg += __shfl_xor(dg, off, 64);      // one lane holds the diagonal, the others 0
         }
+        int e = 0;
+        if (mx > 0.0 && mx < 1e300) (void)frexp(mx, &e);   // mx = m 2^e, 0.5 <= m < 1
+        if (lane == 0) {
+            X.expo[buf][row] = e;
+            X.diag[buf][row] = dg;
+            atomicMax(&X.rmax[buf], __float_as_uint(fminf((float)mx * 1.0000002f, 3.0e38f)));
+            atomicMax(&X.dmax[buf], __float_as_uint(fminf((float)fabs(dg), 3.0e38f)));
+        }
+        return e;
+    };
+    // 8 values (diagonal and padding already zeroed) -> NS x 8 bytes at d, d + 32, ...
+    auto cut8 = [&](double (&u)[8], int e, int8_t *d) {
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             double t = ldexp(u[j], 6 - e);      // |t| < 64
             if (!(fabs(t) <= 64.0)) t = 0.0;    // non-finite input: the caller's state machine reports it
             u[j] = t;
         }
-        int8_t *d = dst + (size_t)(k0 >> 5) * (32 * NS) + (k0 & 31);
 #pragma unroll
         for (int s = 0; s < NS; ++s) {
             uint32_t w0 = 0u, w1 = 0u;
@@ -134,8 +122,76 @@ __global__ __launch_bounds__(256) void i8_slice_kernel(const GemmProblem *__rest
             }
             *(ASTERIA_GLOBAL u32x2 *)(d + s * 32) = (u32x2){w0, w1};
         }
+    };
+    if (kend <= lds_k) {
+        // One read of the matrix: coalesced loads (2 consecutive k per lane), the row parked in the
+        // wavefront's LDS buffer, then 16 consecutive k per lane from there (16-byte stores).  Chunks
+        // of 16 doubles are 17 doubles apart, which spreads the lanes' chunk reads over the banks.
+        ASTERIA_LDS double *rowbuf = (ASTERIA_LDS double *)slice_lds + (threadIdx.x >> 6) * (lds_k / 16 * 17);
+        double mx = 0.0, dg = 0.0;
+#pragma unroll 4
+        for (int k0 = lane * 2; k0 < kend; k0 += 128) {
+            doublex2_t v = {0.0, 0.0};
+            if (k0 < n) v = *(const ASTERIA_GLOBAL doublex2_t *)(src + k0);
+            double v0 = v[0], v1 = (k0 + 1 < n) ? v[1] : 0.0;
+            if (k0 == row) { dg = v0; v0 = 0.0; }
+            if (k0 + 1 == row) { dg = v1; v1 = 0.0; }
+            mx = fmax(mx, fmax(fabs(v0), fabs(v1)));
+            ASTERIA_LDS double *w = rowbuf + (k0 >> 4) * 17 + (k0 & 15);
+            w[0] = v0; w[1] = v1;
+        }
+        const int e = finish_scale(mx, dg);
+        __builtin_amdgcn_s_waitcnt(0xc07f);      // lgkmcnt(0): the wavefront's LDS writes have landed
+        for (int k0 = lane * 16; k0 < kend; k0 += 1024) {
+            double u[16];
+            const ASTERIA_LDS double *rd = rowbuf + (k0 >> 4) * 17;
+#pragma unroll
+            for (int j = 0; j < 16; ++j) {
+                double t = ldexp(rd[j], 6 - e);      // |t| < 64
+                if (!(fabs(t) <= 64.0)) t = 0.0;
+                u[j] = t;
+            }
+            int8_t *d = dst + (size_t)(k0 >> 5) * (32 * NS) + (k0 & 31);
+#pragma unroll
+            for (int s = 0; s < NS; ++s) {
+                u32x4 w = {0u, 0u, 0u, 0u};
+#pragma unroll
+                for (int j = 0; j < 16; ++j) {
+                    const double q = rint(u[j]);
+                    u[j] = (u[j] - q) * 128.0;
+                    w[j >> 2] |= (uint32_t)((int)q & 0xff) << (8 * (j & 3));
+                }
+                *(ASTERIA_GLOBAL u32x4 *)(d + s * 32) = w;
+            }
+        }
+        return;
+    }
+    // longer rows: pass 1 finds the scale, pass 2 reads the row again
+    double mx = 0.0, dg = 0.0;
+    for (int k0 = lane * 2; k0 < n; k0 += 128) {
+        const doublex2_t v = *(const ASTERIA_GLOBAL doublex2_t *)(src + k0);
+        const double v0 = v[0], v1 = (k0 + 1 < n) ? v[1] : 0.0;
+        if (k0 == row) dg = v0; else mx = fmax(mx, fabs(v0));
+        if (k0 + 1 == row) dg = v1; else mx = fmax(mx, fabs(v1));
+    }
+    const int e = finish_scale(mx, dg);
+    for (int k0 = lane * 8; k0 < kend; k0 += 512) {
+        double u[8];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int k = k0 + 2 * j;
+            doublex2_t v = {0.0, 0.0};
+            if (k < n) v = *(const ASTERIA_GLOBAL doublex2_t *)(src + k);
+            u[2 * j] = (k == row) ? 0.0 : v[0];
+            u[2 * j + 1] = (k + 1 >= n || k + 1 == row) ? 0.0 : v[1];
+        }
+        cut8(u, e, dst + (size_t)(k0 >> 5) * (32 * NS) + (k0 & 31));
     }
 }
+
+// lds_k and the dynamic LDS size of a slicing launch whose longest row has n_max entries
+inline int i8_slice_lds_k(int n_max) { const int k = (n_max + 31) & ~31; return k <= I8_SLICE_LDS_K ? k : 0; }
+inline size_t i8_slice_lds_bytes(int lds_k) { return (size_t)4 * ((lds_k + 15) / 16 * 17) * sizeof(double); }
 
 // ---- where a product runs ------------------------------------------------------------------------
 // The dropped levels s + t >= NS contribute, per entry, about 0.33 sqrt(K (NS - 1)) 2^(-7 NS) ra rb

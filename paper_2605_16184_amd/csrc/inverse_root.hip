@@ -976,8 +976,9 @@ asteria_status run_pass(const asteria_factor *f, const std::vector<int> &order, 
                     // itself is never cut; T^2 and T^4 go to buffer 0.
                     const dim3 sgrid((unsigned)((i8_rows(n_max) + 3) / 4), (unsigned)cnt);
                     const int abuf = l == 0 ? 1 : 0, bbuf = l == 1 ? 0 : 1, bmode = l == 2 ? 1 : 0;
-                    if (ns8 == 5) hipLaunchKernelGGL(i8_slice_kernel<5>, sgrid, dim3(256), 0, stream, d_tab[1][pa][l], d_xf, d_state, 0, abuf);
-                    else hipLaunchKernelGGL(i8_slice_kernel<4>, sgrid, dim3(256), 0, stream, d_tab[1][pa][l], d_xf, d_state, 0, abuf);
+                    const int lds_k = i8_slice_lds_k(n_max);
+                    if (ns8 == 5) hipLaunchKernelGGL(i8_slice_kernel<5>, sgrid, dim3(256), i8_slice_lds_bytes(lds_k), stream, d_tab[1][pa][l], d_xf, d_state, 0, abuf, lds_k);
+                    else hipLaunchKernelGGL(i8_slice_kernel<4>, sgrid, dim3(256), i8_slice_lds_bytes(lds_k), stream, d_tab[1][pa][l], d_xf, d_state, 0, abuf, lds_k);
                     // per factor: 4 slices where the estimate allows, else 5 (if the planes have them), else fp64
                     hipLaunchKernelGGL(i8_gate_kernel, dim3(ctl_blocks), dim3(128), 0, stream, d_xf, cnt, &d_fs[0].lo_cur,
                                        (int)sizeof(FactorScal), 4, ns8, abuf, bbuf, bmode);
