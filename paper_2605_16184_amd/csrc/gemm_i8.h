@@ -13,7 +13,7 @@
 // entries, and with it inside the slices the dropped levels would be measured against the diagonal.
 //
 // Slice layout in memory ("planes"): row i, block b of 32 consecutive k, slice s, 32 bytes:
-//     planes[((i * kb + b) * NS + s) * 32 + k % 32],   kb = ceil(n / 32),
+//     planes[i * row_bytes + (b * NS + s) * 32 + k % 32],   kb = ceil(n / 32), row_bytes >= kb NS 32,
 // rows padded with zero rows to a multiple of 128 and k padded with zeros to a multiple of 32, so
 // the product kernel reads whole tiles without guards.
 //
@@ -49,14 +49,22 @@ struct I8Factor {
 };
 
 inline size_t i8_rows(int n) { return (size_t)((n + 127) & ~127); }
-inline size_t i8_plane_bytes(int n, int ns) { return i8_rows(n) * (size_t)((n + 31) / 32) * 32u * (size_t)ns; }
+// Bytes between the slice rows of consecutive matrix rows: the kb blocks, padded to an odd multiple
+// of 128 bytes - with a power-of-two stride the 128 rows a tile loads side by side fall on the same
+// L2 / memory channels.
+__host__ __device__ inline size_t i8_row_bytes(int kb, int ns)
+{
+    const size_t units = ((size_t)kb * 32u * (size_t)ns + 127) / 128;
+    return (units | 1) * 128;
+}
+inline size_t i8_plane_bytes(int n, int ns) { return i8_rows(n) * i8_row_bytes((n + 31) / 32, ns); }
 
 // ---- slicing ------------------------------------------------------------------------------------
 // One wavefront per row (rows of up to 2048 entries are parked in LDS between finding the row scale
 // and cutting, longer ones are read twice).  Grid: x = groups of 4 rows (of the largest factor, padded), y = problem.
 // Reads operand A (use_b = 0) or B (use_b = 1) of the problem as an n x n fp64 matrix with an even
 // leading dimension and a 16-byte aligned base, writes buffer `buf` of the factor.
-constexpr int I8_SLICE_LDS_K = 1024;   // longest (padded) row the slicing kernel parks in LDS
+constexpr int I8_SLICE_LDS_K = 2048;   // longest (padded) row the slicing kernel parks in LDS (4 rows per workgroup: 70 KB)
 template <int NS>
 __global__ __launch_bounds__(256) void i8_slice_kernel(const GemmProblem *__restrict__ probs, I8Factor *__restrict__ xf,
                                                        const int *__restrict__ state, int use_b, int buf, int lds_k)
@@ -74,7 +82,7 @@ __global__ __launch_bounds__(256) void i8_slice_kernel(const GemmProblem *__rest
     const int row = (int)blockIdx.x * 4 + (int)(threadIdx.x >> 6);
     if (row >= npad) return;
     const int kb = X.kb;
-    const size_t rowbytes = (size_t)kb * (32 * NS);
+    const size_t rowbytes = i8_row_bytes(kb, NS);
     int8_t *dst = X.planes[buf] + (size_t)row * rowbytes;
     if (row >= n) {
         for (size_t o = (size_t)lane * 16; o < rowbytes; o += 64 * 16)
@@ -234,71 +242,88 @@ __global__ void i8_gate_kernel(I8Factor *__restrict__ xf, int nf, const float *_
 }
 
 // ---- the product kernel --------------------------------------------------------------------------
-// 128 x 128 tile, 8 wavefronts in a 2 x 4 grid (64 x 32 each: two 32 x 32 MFMA tiles), one slab =
-// one block of 32 k for all NS slices: NS * 4 KB per operand, double-buffered in LDS as
-// [slice][k half][row][16 bytes], so the 32 lanes of one k half read 512 contiguous bytes per
+// A workgroup of 4 wavefronts (2 x 2, 64 x 32 each: two 32 x 32 MFMA tiles) computes one half
+// (128 rows x 64 columns) of a 128 x 128 lower-triangle tile, so that a CU holds two workgroups
+// and the epilogue of one (fp64 assembly, 16 + 16..40 bytes of HBM traffic per element) runs under
+// the K loop of the other.  One slab = one block of 32 k for all NS slices, double-buffered in LDS
+// as [slice][k half][row][16 bytes], so the 32 lanes of one k half read 512 contiguous bytes per
 // fragment; each [slice][k half] piece is padded by 16 bytes, which spreads the 2 NS pieces of one
-// row, which consecutive lanes store, over different banks.  Per slab a wavefront reads 3 NS fragments and issues NS (NS + 1)
-// MFMAs into NS level accumulators per tile.  NSL is the number of slices the planes were written
-// with: a product may use only the leading NS of them (the slices are digits, most significant first).
+// row, which consecutive lanes store, over different banks.  Per slab a wavefront reads 3 NS
+// fragments and issues NS (NS + 1) MFMAs into NS level accumulators per MFMA tile.  NSL is the
+// number of slices the planes were written with: a product may use only the leading NS of them
+// (the slices are digits, most significant first).
 struct MmaI8 {
     static constexpr int T = 32;
     static constexpr int NACC = 16;
+    // the common epilogue places a wavefront at (wm * 128 / WAVES_M, wn * 128 / WAVES_N): 64-row and
+    // 32-column steps; the column origin it is given is that of the half tile
     static constexpr int WAVES_M = 2, WAVES_N = 4;
-    static constexpr int NTHR = 512;
+    static constexpr int NTHR = 256;
     static constexpr int WTM = 2, WTN = 1;
     typedef doublex16 acc_t;
     __device__ static __forceinline__ int acc_row(int v, int h) { return 8 * (v >> 2) + 4 * h + (v & 3); }
 };
+constexpr int I8_TN = 64;        // columns per workgroup
 
-// one tile with NS of the NSL slices the planes hold
+// one half tile with NS of the NSL slices the planes hold; lt = tile within the problem, half = 0 | 1
 template <int NS, int NSL>
-__device__ __forceinline__ void i8_tile(const GemmProblem &P, const I8Factor &X, int lt, int abuf, int bbuf, int bmode,
-                                        unsigned char *smem_raw, float *red)
+__device__ __forceinline__ void i8_tile(const GemmProblem &P, const I8Factor &X, int lt, int half, int abuf, int bbuf,
+                                        int bmode, unsigned char *smem_raw, float *red)
 {
-    constexpr int PIECE = 128 * 16 + 16;             // one k half of one slice of one operand: 128 rows x 16 bytes, padded
-    constexpr int OPERAND = 2 * NS * PIECE;
-    constexpr int STAGE = 2 * OPERAND;               // both operands
+    constexpr int PIECE_A = 128 * 16 + 16;           // one k half of one slice: rows x 16 bytes, padded
+    constexpr int PIECE_B = I8_TN * 16 + 16;
+    constexpr int OPERAND_A = 2 * NS * PIECE_A;
+    constexpr int STAGE = OPERAND_A + 2 * NS * PIECE_B;
     constexpr int CPR = 2 * NS;                      // 16-byte chunks per row and slab
-    constexpr int CHUNKS = 128 * CPR;                // per operand
-    constexpr int NV = (2 * CHUNKS) / 512;
-    static_assert((2 * CHUNKS) % 512 == 0, "chunks divide evenly over the threads");
+    constexpr int CHUNKS_A = 128 * CPR;
+    constexpr int TOTAL = (128 + I8_TN) * CPR;
+    constexpr int NV = (TOTAL + 255) / 256;
 
     ASTERIA_LDS unsigned char *smem_i8 = (ASTERIA_LDS unsigned char *)smem_raw;
     int ti, tj;
     tri_decode(lt, ti, tj);                          // symmetric products only
     const int n = P.M;
-    const int row0 = ti * BM, col0 = tj * BN;
+    const int row0 = ti * BM, col0 = tj * BN + half * I8_TN;
     const int kb = X.kb;
-    const size_t rowbytes = (size_t)kb * (32 * NSL);
+    const size_t rowbytes = i8_row_bytes(kb, NSL);
     const int8_t *Ap = X.planes[abuf] + (size_t)row0 * rowbytes;
     const int8_t *Bp = X.planes[bbuf] + (size_t)col0 * rowbytes;
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm = wave / MmaI8::WAVES_N, wn = wave % MmaI8::WAVES_N;
+    const int wm = wave >> 1, wn = wave & 1;
     const int r = lane & 31, h = lane >> 5;
 
-    // staging: chunk idx = tid + 512 v over both operands
+    // staging: chunk idx = tid + 256 v over both operands
     const int8_t *gsrc[NV];
     int ldst[NV];
 #pragma unroll
     for (int v = 0; v < NV; ++v) {
-        const int idx = tid + 512 * v;
-        const int op = idx / CHUNKS, c = idx % CHUNKS;
+        const int idx = min(tid + 256 * v, TOTAL - 1);
+        const bool isb = idx >= CHUNKS_A;
+        const int c = isb ? idx - CHUNKS_A : idx;
         const int row = c / CPR, piece = c % CPR;
-        gsrc[v] = (op ? Bp : Ap) + (size_t)row * rowbytes + piece * 16;
-        ldst[v] = op * OPERAND + piece * PIECE + row * 16;
+        gsrc[v] = (isb ? Bp : Ap) + (size_t)row * rowbytes + piece * 16;
+        ldst[v] = isb ? OPERAND_A + piece * PIECE_B + row * 16 : piece * PIECE_A + row * 16;
     }
-    constexpr int DEPTH = 1;                         // slabs in flight from global memory (2 was slower)
+    // Register sets for slabs in flight from global memory.  Two (NS <= 4, where the budget allows)
+    // give a load two slabs of MFMA work to arrive: a third of the requests miss L2.  The loads of
+    // the deeper pipeline are unconditional (the slab index is clamped), so that the count of
+    // loads issued after the set being stored is known statically and the wait before the store
+    // leaves the younger set in flight.
+    constexpr int DEPTH = NS <= 4 ? 2 : 1;
     u32x4 stg[DEPTH][NV];
     auto gload = [&](u32x4 (&set)[NV], int slab) {
 #pragma unroll
-        for (int v = 0; v < NV; ++v) set[v] = *(const ASTERIA_GLOBAL u32x4 *)(gsrc[v] + (size_t)slab * (32 * NSL));
+        for (int v = 0; v < NV; ++v)
+            if (TOTAL % 256 == 0 || tid + 256 * v < TOTAL)
+                set[v] = *(const ASTERIA_GLOBAL u32x4 *)(gsrc[v] + (size_t)slab * (32 * NSL));
     };
     auto lstore = [&](const u32x4 (&set)[NV], int buf) {
 #pragma unroll
-        for (int v = 0; v < NV; ++v) *(ASTERIA_LDS u32x4 *)(smem_i8 + buf * STAGE + ldst[v]) = set[v];
+        for (int v = 0; v < NV; ++v)
+            if (TOTAL % 256 == 0 || tid + 256 * v < TOTAL)
+                *(ASTERIA_LDS u32x4 *)(smem_i8 + buf * STAGE + ldst[v]) = set[v];
     };
 
     i32x16 acc[NS][2];
@@ -311,14 +336,14 @@ __device__ __forceinline__ void i8_tile(const GemmProblem &P, const I8Factor &X,
 
     auto compute = [&](int cur) {
         const ASTERIA_LDS unsigned char *LA = smem_i8 + cur * STAGE;
-        const ASTERIA_LDS unsigned char *LB = LA + OPERAND;
+        const ASTERIA_LDS unsigned char *LB = LA + OPERAND_A;
         i32x4 a[NS][2], b[NS];
 #pragma unroll
         for (int s = 0; s < NS; ++s) {
 #pragma unroll
             for (int i = 0; i < 2; ++i)
-                a[s][i] = *(const ASTERIA_LDS i32x4 *)(LA + (2 * s + h) * PIECE + (wm * 64 + i * 32 + r) * 16);
-            b[s] = *(const ASTERIA_LDS i32x4 *)(LB + (2 * s + h) * PIECE + (wn * 32 + r) * 16);
+                a[s][i] = *(const ASTERIA_LDS i32x4 *)(LA + (2 * s + h) * PIECE_A + (wm * 64 + i * 32 + r) * 16);
+            b[s] = *(const ASTERIA_LDS i32x4 *)(LB + (2 * s + h) * PIECE_B + (wn * 32 + r) * 16);
         }
         // consecutive MFMAs write different accumulators
 #pragma unroll
@@ -332,9 +357,9 @@ __device__ __forceinline__ void i8_tile(const GemmProblem &P, const I8Factor &X,
 
     gload(stg[0], 0);
     lstore(stg[0], 0);
-    int cur = 0;
-    {
+    if constexpr (DEPTH == 1) {
         __syncthreads();
+        int cur = 0;
         for (int slab = 0; slab < kb; ++slab) {
             const bool more = slab + 1 < kb;
             if (more) gload(stg[0], slab + 1);
@@ -342,6 +367,21 @@ __device__ __forceinline__ void i8_tile(const GemmProblem &P, const I8Factor &X,
             if (more) lstore(stg[0], cur ^ 1);
             __syncthreads();
             cur ^= 1;
+        }
+    } else {
+        // set 0 carries the odd slabs, set 1 the even ones; slabs are taken in pairs
+        const int last = kb - 1;
+        gload(stg[0], min(1, last));
+        __syncthreads();
+        for (int slab = 0; slab < kb; slab += 2) {
+            gload(stg[DEPTH - 1], min(slab + 2, last));
+            compute(0);
+            lstore(stg[0], 1);                         // slab + 1 (a copy of the last slab if there is none)
+            __syncthreads();
+            gload(stg[0], min(slab + 3, last));
+            if (slab + 1 < kb) compute(1);
+            lstore(stg[DEPTH - 1], 0);                 // slab + 2
+            __syncthreads();
         }
     }
 
@@ -376,24 +416,30 @@ __device__ __forceinline__ void i8_tile(const GemmProblem &P, const I8Factor &X,
             accd[i][0][v] = val;
         }
     }
-    const int rowsA = min(BM, n - row0), rowsB = min(BN, n - col0);
-    gemm_epilogue<MmaI8, double>(P, accd, lt, ti, tj, row0, col0, rowsA, rowsB, wm, wn, r, h, lane, wave, tid, red);
+    const int rowsA = min(BM, n - row0), rowsB = min(I8_TN, n - col0);
+    // the residual partial sums of the two halves of a tile go to separate slots
+    const int tpr = (n + BM - 1) / BM;
+    const int slot = lt + half * (tpr * (tpr + 1) / 2);
+    gemm_epilogue<MmaI8, double>(P, accd, slot, ti, tj, row0, col0, rowsA, rowsB, wm, wn, r, h, lane, wave, tid, red);
 }
 
 // One launch serves every slice count the planes allow: the factor's gate picks the tile routine
 // (a launch per count would add a grid of workgroups that only look up their factor and leave).
+// Two consecutive workgroups share a 128 x 128 tile (and with it the A rows in L2).
 template <int NSL>
-__global__ __launch_bounds__(512, 2) void gemm_i8_grouped_kernel(const GemmProblem *__restrict__ probs,
+__global__ __launch_bounds__(256, 2) void gemm_i8_grouped_kernel(const GemmProblem *__restrict__ probs,
                                                                  const I8Factor *__restrict__ xf, int nprobs,
                                                                  int total_tiles, const int *__restrict__ state, int abuf,
                                                                  int bbuf, int bmode)
 {
     extern __shared__ __align__(16) unsigned char smem_i8_raw[];
-    __shared__ float red[8];
+    __shared__ float red[4];
 
-    const int per_xcd = (total_tiles + NUM_XCD - 1) / NUM_XCD;
-    const int t_global = (int)(blockIdx.x % NUM_XCD) * per_xcd + (int)(blockIdx.x / NUM_XCD);
-    if (t_global >= total_tiles) return;
+    const int total_wg = 2 * total_tiles;
+    const int per_xcd = (total_wg + NUM_XCD - 1) / NUM_XCD;
+    const int w_global = (int)(blockIdx.x % NUM_XCD) * per_xcd + (int)(blockIdx.x / NUM_XCD);
+    if (w_global >= total_wg) return;
+    const int t_global = w_global >> 1, half = w_global & 1;
     int lo = 0, hi = nprobs - 1;
     while (lo < hi) {
         const int mid = (lo + hi + 1) >> 1;
@@ -407,9 +453,9 @@ __global__ __launch_bounds__(512, 2) void gemm_i8_grouped_kernel(const GemmProbl
     const I8Factor &X = xf[P.state_idx];
     const int g = X.gate;
     const int lt = t_global - P.tile_start;
-    if (g == 4) i8_tile<4, NSL>(P, X, lt, abuf, bbuf, bmode, smem_i8_raw, red);
+    if (g == 4) i8_tile<4, NSL>(P, X, lt, half, abuf, bbuf, bmode, smem_i8_raw, red);
     if constexpr (NSL >= 5) {
-        if (g == 5) i8_tile<5, NSL>(P, X, lt, abuf, bbuf, bmode, smem_i8_raw, red);
+        if (g == 5) i8_tile<5, NSL>(P, X, lt, half, abuf, bbuf, bmode, smem_i8_raw, red);
     }
 }
 
@@ -418,7 +464,7 @@ hipError_t launch_gemm_i8_grouped(const GemmProblem *d_probs, const I8Factor *d_
                                   const int *d_state, int abuf, int bbuf, int bmode, hipStream_t stream)
 {
     if (nprobs <= 0 || total_tiles <= 0) return hipSuccess;
-    constexpr int LDS_BYTES = 2 * 2 * 2 * NSL * (128 * 16 + 16);
+    constexpr int LDS_BYTES = 2 * 2 * NSL * ((128 * 16 + 16) + (I8_TN * 16 + 16));
     static bool configured = false;
     if (!configured) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_i8_grouped_kernel<NSL>),
@@ -426,9 +472,9 @@ hipError_t launch_gemm_i8_grouped(const GemmProblem *d_probs, const I8Factor *d_
         if (e != hipSuccess) return e;
         configured = true;
     }
-    const int per_xcd = (total_tiles + NUM_XCD - 1) / NUM_XCD;
+    const int per_xcd = (2 * total_tiles + NUM_XCD - 1) / NUM_XCD;
     profile_begin(300 + NSL, stream);
-    hipLaunchKernelGGL(gemm_i8_grouped_kernel<NSL>, dim3(per_xcd * NUM_XCD), dim3(512), LDS_BYTES, stream, d_probs, d_xf,
+    hipLaunchKernelGGL(gemm_i8_grouped_kernel<NSL>, dim3(per_xcd * NUM_XCD), dim3(256), LDS_BYTES, stream, d_probs, d_xf,
                        nprobs, total_tiles, d_state, abuf, bbuf, bmode);
     profile_end(stream);
     return hipGetLastError();

@@ -66,7 +66,7 @@ struct FactorDev {
     float *pv[2];       // power-iteration vectors
     float2 *pm_partial; // per mat-vec workgroup: (sum y^2, sum y v)
     float2 *pm_partial2; // per mat-vec workgroup, first step only: (sum a_ij^2, sum a_ii)
-    float *partial;     // per lower-triangle tile: sum (M - I)^2
+    float *partial;     // per lower-triangle tile: sum (M - I)^2 (2 ntri entries: a second one per tile for kernels that split tiles)
     int n, lda, ldx;
     int ld32, ld64;
     int ntri;           // lower-triangle tiles
@@ -401,7 +401,7 @@ __global__ __launch_bounds__(256) void root_init_kernel(const FactorDev *fd, con
         rsum = wave_sum(rsum);
         if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = rsum;
         __syncthreads();
-        if (threadIdx.x == 0) F.partial[lt] = red[0] + red[1] + red[2] + red[3];
+        if (threadIdx.x == 0) { F.partial[lt] = red[0] + red[1] + red[2] + red[3]; F.partial[F.ntri + lt] = 0.0f; }
         return;
     }
     __shared__ float Ps[32][33], Qs[32][33];
@@ -454,7 +454,7 @@ __global__ __launch_bounds__(256) void root_init_kernel(const FactorDev *fd, con
     rsum = wave_sum(rsum);
     if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = rsum;
     __syncthreads();
-    if (threadIdx.x == 0) F.partial[lt] = red[0] + red[1] + red[2] + red[3];
+    if (threadIdx.x == 0) { F.partial[lt] = red[0] + red[1] + red[2] + red[3]; F.partial[F.ntri + lt] = 0.0f; }
 }
 
 // One wavefront per factor, run before iteration k (and once after the last one with
@@ -472,7 +472,12 @@ __global__ __launch_bounds__(64) void root_control_kernel(const FactorDev *fd, F
         st = ST_DONE;
     } else {
         float r2 = 0.0f;
-        for (int i = threadIdx.x; i < F.ntri; i += 64) r2 += F.partial[i];
+        // the int8 product writes two partial sums per tile (one per half), the other kernels the
+        // first only: the second is cleared once read
+        for (int i = threadIdx.x; i < F.ntri; i += 64) {
+            r2 += F.partial[i] + F.partial[F.ntri + i];
+            F.partial[F.ntri + i] = 0.0f;
+        }
         r2 = wave_sum(r2);
         const float resid = sqrtf(r2);
         if (!(r2 == r2) || !(r2 < 3.0e38f)) {
@@ -662,7 +667,7 @@ size_t factor_small_bytes(int n)
 {
     const int pmb = (n + PM_ROWS - 1) / PM_ROWS;
     return 2 * Carver::need((size_t)ld4(n), sizeof(float)) + 2 * Carver::need((size_t)pmb, sizeof(float2)) +
-           Carver::need((size_t)tri_tiles(n), sizeof(float)) + sizeof(FactorDev) + sizeof(FactorScal) +
+           Carver::need(2 * (size_t)tri_tiles(n), sizeof(float)) + sizeof(FactorDev) + sizeof(FactorScal) +
            2 * sizeof(int) + 14 * sizeof(GemmProblem);
 }
 
@@ -855,7 +860,7 @@ asteria_status run_pass(const asteria_factor *f, const std::vector<int> &order, 
         F.pv[1] = cv.take<float>(ld4(n));
         F.pm_partial = cv.take<float2>(F.pm_blocks);
         F.pm_partial2 = cv.take<float2>(F.pm_blocks);
-        F.partial = cv.take<float>(F.ntri);
+        F.partial = cv.take<float>(2 * (size_t)F.ntri);
     }
     // factors too large for exact int32 sums (never reached by the 16384 limit of the other tiers'
     // workloads) keep the fp64 cores
