@@ -18,6 +18,10 @@
 #pragma once
 #include "gemm.h"
 
+#ifndef ASTERIA_SPLIT_BK
+#define ASTERIA_SPLIT_BK 32   // K slab of the products with both operands split: 64 KiB of LDS, two workgroups per CU (64: one workgroup, 218 -> 168 TFLOP/s)
+#endif
+
 namespace asteria {
 
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
@@ -156,7 +160,7 @@ __device__ __forceinline__ void gemm_bf16_mainloop(floatx16 (&acc)[2][2], const 
                                                    bool vecA, bool vecB, ASTERIA_LDS uint16_t *smem, int tid,
                                                    int wm, int wn, int r, int h, float sca = 1.0f, float scb = 1.0f)
 {
-    constexpr int BK = (NTA + NTB > 2) ? 32 : 64;
+    constexpr int BK = (NTA + NTB > 2) ? ASTERIA_SPLIT_BK : 64;
     using StA = Bf16Stage<TA, NTA, BK, F16>;
     using StB = Bf16Stage<TB, NTB, BK, F16>;
     auto mma = [](u32x4 a, u32x4 b, floatx16 c) __attribute__((always_inline)) {
@@ -228,7 +232,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_grouped_kernel(const GemmProble
                                                                 int total_tiles, const int *__restrict__ state)
 {
     using MM = MmaBf16;
-    constexpr int BK = (NTA + NTB > 2) ? 32 : 64;
+    constexpr int BK = (NTA + NTB > 2) ? ASTERIA_SPLIT_BK : 64;
     extern __shared__ __align__(16) unsigned char smem_raw[];
     ASTERIA_LDS uint16_t *smem = (ASTERIA_LDS uint16_t *)smem_raw;
     // the reduction scratch of the epilogue reuses the operand buffer (free after the K loop): with
@@ -312,7 +316,7 @@ inline hipError_t launch_gemm_bf16_grouped(const GemmProblem *probs, int nprobs,
                                            const int *state, hipStream_t stream)
 {
     if (total_tiles <= 0 || nprobs <= 0) return hipSuccess;
-    constexpr int BK = (NTA + NTB > 2) ? 32 : 64;
+    constexpr int BK = (NTA + NTB > 2) ? ASTERIA_SPLIT_BK : 64;
     auto kern = gemm_bf16_grouped_kernel<TA, TB, NTA, NTB, F16>;
     constexpr size_t lds = sizeof(uint16_t) * 2 *
                            (size_t)(Bf16Stage<TA, NTA, BK>::LDS_ELEMS + Bf16Stage<TB, NTB, BK>::LDS_ELEMS);
