@@ -253,6 +253,22 @@ def test_root_fp64_iterations_on_the_int8_cores_against_the_fp64_cores_and_the_o
         # the int8 path reproduces the fp64-core result far inside the tolerance
         assert relF(res[-1][0], res[0][0]) <= 2.5e-4, (name, relF(res[-1][0], res[0][0]))
         assert relF(res[4][0], res[0][0]) <= 2.5e-4, (name, relF(res[4][0], res[0][0]))
+    # a factor longer than the rows the slicing kernel parks in LDS (2048): rows are read twice there;
+    # 65 blocks of 32 k (an odd count), a ragged last tile
+    # (too large for the oracle's Jacobi sweeps, minutes at this size: graded against the definition
+    # V (lambda + eps)^(-1/4) V^T written out with a float64 eigendecomposition, and against the
+    # fp64-core path)
+    A = powerlaw_factor(2080, 24)
+    w, V = torch.linalg.eigh(A.double())
+    Xdef = (V * (w + 1e-6 * w[-1]) ** -0.25) @ V.T
+    got = {}
+    for ns in (-1, 0):
+        (X,), info, iters, resid, lmax = run_roots([A], 1e-6, opts=ast.RootOpts(int8_slices=ns))
+        assert info[0] == B.INFO_OK
+        got[ns] = X.double()
+        err = float((got[ns] - Xdef).norm() / Xdef.norm())
+        assert err <= TOL_ROOT, (ns, err)
+    assert float((got[-1] - got[0]).norm() / got[0].norm()) <= 2.5e-4
     # a batch: every factor takes its own decision
     As = list(cases.values())
     Xs, info, iters, resid, lmax = run_roots(As, 1e-6)
