@@ -18,6 +18,14 @@
 #pragma once
 #include "gemm.h"
 
+#ifndef ASTERIA_BF16_MIN_WAVES
+// wavefronts per SIMD the register budget is held to.  Two workgroups per CU; a third (168 registers,
+// one LDS stage of 32 KiB and two barriers per slab) changed nothing: 219.6 against 218.3 TFLOP/s.
+#define ASTERIA_BF16_MIN_WAVES 2
+#endif
+#ifndef ASTERIA_SPLIT_STAGES
+#define ASTERIA_SPLIT_STAGES 2   // LDS stages of the products with both operands split
+#endif
 #ifndef ASTERIA_SPLIT_BK
 #define ASTERIA_SPLIT_BK 32   // K slab of the products with both operands split: 64 KiB of LDS, two workgroups per CU (64: one workgroup, 218 -> 168 TFLOP/s)
 #endif
@@ -170,7 +178,8 @@ __device__ __forceinline__ void gemm_bf16_mainloop(floatx16 (&acc)[2][2], const 
     constexpr int STEPS = KPL / 8;       // MFMA k-steps per slab (8 bf16 per lane and step)
     StA sa;
     StB sb;
-    ASTERIA_LDS uint16_t *const smemB = smem + 2 * StA::LDS_ELEMS;
+    constexpr int STAGES = (NTA + NTB > 2) ? ASTERIA_SPLIT_STAGES : 2;
+    ASTERIA_LDS uint16_t *const smemB = smem + STAGES * StA::LDS_ELEMS;
     const int nk = (K + BK - 1) / BK;
     sa.template load<GUARD>(Ab, lda, row0, rowsA, 0, K, vecA, tid);
     sb.template load<GUARD>(Bb, ldb, col0, rowsB, 0, K, vecB, tid);
@@ -178,7 +187,7 @@ __device__ __forceinline__ void gemm_bf16_mainloop(floatx16 (&acc)[2][2], const 
     sb.store(smemB, tid, scb);
     __syncthreads();
     for (int kt = 0; kt < nk; ++kt) {
-        const int cur = kt & 1;
+        const int cur = STAGES == 2 ? (kt & 1) : 0;
         if (kt + 1 < nk) {
             const int k0 = (kt + 1) * BK;
             sa.template load<GUARD>(Ab, lda, row0, rowsA, k0, K - k0, vecA, tid);
@@ -219,16 +228,18 @@ __device__ __forceinline__ void gemm_bf16_mainloop(floatx16 (&acc)[2][2], const 
                 for (int j = 0; j < 2; ++j)
                     if (TRI == TRI_ALL || j - i <= TRI) acc[i][j] = mma(ah[i], bh[j], acc[i][j]);
         }
+        if (STAGES == 1) __syncthreads();      // every wavefront has read the slab before it is overwritten
         if (kt + 1 < nk) {
-            sa.store(smem + (cur ^ 1) * StA::LDS_ELEMS, tid, sca);
-            sb.store(smemB + (cur ^ 1) * StB::LDS_ELEMS, tid, scb);
+            const int nxt = STAGES == 2 ? (cur ^ 1) : 0;
+            sa.store(smem + nxt * StA::LDS_ELEMS, tid, sca);
+            sb.store(smemB + nxt * StB::LDS_ELEMS, tid, scb);
         }
         __syncthreads();
     }
 }
 
 template <typename TA, typename TB, int NTA, int NTB, bool F16 = false>
-__global__ __launch_bounds__(256) void gemm_bf16_grouped_kernel(const GemmProblem *__restrict__ probs, int nprobs,
+__global__ __launch_bounds__(256, ASTERIA_BF16_MIN_WAVES) void gemm_bf16_grouped_kernel(const GemmProblem *__restrict__ probs, int nprobs,
                                                                 int total_tiles, const int *__restrict__ state)
 {
     using MM = MmaBf16;
@@ -318,7 +329,7 @@ inline hipError_t launch_gemm_bf16_grouped(const GemmProblem *probs, int nprobs,
     if (total_tiles <= 0 || nprobs <= 0) return hipSuccess;
     constexpr int BK = (NTA + NTB > 2) ? ASTERIA_SPLIT_BK : 64;
     auto kern = gemm_bf16_grouped_kernel<TA, TB, NTA, NTB, F16>;
-    constexpr size_t lds = sizeof(uint16_t) * 2 *
+    constexpr size_t lds = sizeof(uint16_t) * ((NTA + NTB > 2) ? ASTERIA_SPLIT_STAGES : 2) *
                            (size_t)(Bf16Stage<TA, NTA, BK>::LDS_ELEMS + Bf16Stage<TB, NTB, BK>::LDS_ELEMS);
     static bool configured = false;
     if (!configured) {

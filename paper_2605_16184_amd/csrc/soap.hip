@@ -171,6 +171,16 @@ constexpr int CHOL_THREADS = 256;
 // projection left by 1 / sqrt(pivot).  Such a factor takes a third sweep (skip3 = 0), which only
 // its workgroups run; a pivot that small in the third sweep fails the factor.
 constexpr double CHOL_REPEAT_MIN = 0.1;
+constexpr int CHOL_NB = 16;                                   // block size of the factorisation and the inverse
+constexpr int CHOL_PITCH = QR_PANEL + 1;
+// LDS: the matrix (QR_PANEL x CHOL_PITCH doubles) and a block row of CHOL_NB x QR_PANEL doubles
+constexpr size_t CHOL_LDS_BYTES = sizeof(double) * ((size_t)QR_PANEL * CHOL_PITCH + (size_t)CHOL_NB * QR_PANEL);
+
+// Both phases work on blocks of 16 so that the workgroup meets at a barrier a few times per block
+// instead of a few times per column: per block column of the Cholesky factorisation one wavefront
+// factors the 16 x 16 diagonal block (its lanes stay in step through LDS, which a wavefront accesses in
+// order), every row below solves against it, and the trailing matrix takes a rank-16 update; the
+// inverse is formed from the inverses of the diagonal blocks, block row by block row.
 __global__ __launch_bounds__(CHOL_THREADS) void panel_chol_inverse_kernel(QrFactor *fs, const int *fidx, int panel,
                                                                           int sweep)
 {
@@ -179,47 +189,126 @@ __global__ __launch_bounds__(CHOL_THREADS) void panel_chol_inverse_kernel(QrFact
     const int rows = min(QR_PANEL, F.n - panel * QR_PANEL);
     extern __shared__ __align__(16) unsigned char chol_smem[];
     double *L = reinterpret_cast<double *>(chol_smem);            // rows x rows, pitch QR_PANEL + 1
-    constexpr int PITCH = QR_PANEL + 1;
+    double *S = L + (size_t)QR_PANEL * CHOL_PITCH;                // CHOL_NB x QR_PANEL
+    constexpr int PITCH = CHOL_PITCH;
+    constexpr int NB = CHOL_NB;
     __shared__ int bad_flag;
     const int tid = threadIdx.x;
     const int ti = tid >> 4, tj = tid & 15;
+    const int lane = tid & 63, wave = tid >> 6;
     if (tid == 0) bad_flag = 0;
-    for (int i = ti; i < rows; i += 16)
-        for (int j = tj; j < rows; j += 16) L[i * PITCH + j] = F.gram[(size_t)i * QR_PANEL + j];
+    // rows and columns beyond `rows` are those of the identity: the blocks need no edge cases
+    for (int i = ti; i < QR_PANEL; i += 16)
+        for (int j = tj; j < QR_PANEL; j += 16)
+            L[i * PITCH + j] = (i < rows && j < rows) ? F.gram[(size_t)i * QR_PANEL + j] : (i == j ? 1.0 : 0.0);
     __syncthreads();
-    for (int k = 0; k < rows; ++k) {
-        double piv = L[k * PITCH + k];
-        if (!(piv > 0.0) || !(piv < 1e300)) {            // not positive definite: keep going with a tiny pivot
-            if (tid == 0) bad_flag = 1;
-            piv = 1e-300;
-        } else if (sweep > 0 && piv < CHOL_REPEAT_MIN) {
-            if (tid == 0) bad_flag = 2;
+    const int nblk = (rows + NB - 1) / NB;
+
+    // ---- Cholesky factorisation, lower triangle in place
+    for (int kb = 0; kb < nblk; ++kb) {
+        const int k0 = kb * NB;
+        if (wave == 0) {
+            // diagonal block: lane -> elements (i, j) = (e / 16, e % 16), e = lane + 64 q
+            for (int k = 0; k < NB; ++k) {
+                double piv = L[(k0 + k) * PITCH + k0 + k];
+                if (k0 + k < rows) {
+                    if (!(piv > 0.0) || !(piv < 1e300)) {        // not positive definite: keep going with a tiny pivot
+                        if (lane == 0) bad_flag = 1;
+                        piv = 1e-300;
+                    } else if (sweep > 0 && piv < CHOL_REPEAT_MIN) {
+                        if (lane == 0) bad_flag = 2;
+                    }
+                }
+                const double d = sqrt(piv);
+                double colv[4], rowv[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int e = lane + 64 * q, i = e >> 4, j = e & 15;
+                    colv[q] = L[(k0 + i) * PITCH + k0 + k];      // L[i][k] before scaling
+                    rowv[q] = L[(k0 + j) * PITCH + k0 + k];      // L[j][k] before scaling
+                }
+                __builtin_amdgcn_wave_barrier();                 // all reads of column k precede its rewrite
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int e = lane + 64 * q, i = e >> 4, j = e & 15;
+                    if (j == k && i >= k) L[(k0 + i) * PITCH + k0 + k] = (i == k) ? d : colv[q] / d;
+                    else if (j > k && j <= i) L[(k0 + i) * PITCH + k0 + j] -= (colv[q] / d) * (rowv[q] / d);
+                }
+                __builtin_amdgcn_wave_barrier();
+            }
         }
-        const double d = sqrt(piv);
-        __syncthreads();                                  // every thread has read the pivot
-        for (int i = k + tid; i < rows; i += CHOL_THREADS) L[i * PITCH + k] = (i == k) ? d : L[i * PITCH + k] / d;
         __syncthreads();
-        for (int i = k + 1 + ti; i < rows; i += 16) {
-            const double lik = L[i * PITCH + k];
-            for (int j = k + 1 + tj; j <= i; j += 16) L[i * PITCH + j] -= lik * L[j * PITCH + k];
+        // rows below: L21 = A21 L11^-T, one thread per row
+        for (int i = k0 + NB + tid; i < rows; i += CHOL_THREADS) {
+            double x[NB];
+#pragma unroll
+            for (int j = 0; j < NB; ++j) x[j] = L[i * PITCH + k0 + j];
+#pragma unroll
+            for (int j = 0; j < NB; ++j) {
+                double v = x[j];
+#pragma unroll
+                for (int m = 0; m < j; ++m) v -= x[m] * L[(k0 + j) * PITCH + k0 + m];
+                x[j] = v / L[(k0 + j) * PITCH + k0 + j];
+            }
+#pragma unroll
+            for (int j = 0; j < NB; ++j) L[i * PITCH + k0 + j] = x[j];
+        }
+        __syncthreads();
+        // trailing matrix: A22 -= L21 L21^T (lower triangle)
+        for (int i = k0 + NB + ti; i < rows; i += 16) {
+            double li[NB];
+#pragma unroll
+            for (int m = 0; m < NB; ++m) li[m] = L[i * PITCH + k0 + m];
+            for (int j = k0 + NB + tj; j <= i; j += 16) {
+                double acc = 0.0;
+#pragma unroll
+                for (int m = 0; m < NB; ++m) acc += li[m] * L[j * PITCH + k0 + m];
+                L[i * PITCH + j] -= acc;
+            }
         }
         __syncthreads();
     }
-    // W = L^-1 over L: W[i][i] = 1 / L[i][i], W[i][j] = -(sum_{k=j}^{i-1} L[i][k] W[k][j]) / L[i][i]
-    for (int i = 0; i < rows; ++i) {
-        double w = 0.0;
-        if (tid <= i) {
-            const double dinv = 1.0 / L[i * PITCH + i];
-            if (tid == i) {
-                w = dinv;
-            } else {
-                double sum = 0.0;
-                for (int k = tid; k < i; ++k) sum += L[i * PITCH + k] * L[k * PITCH + tid];
-                w = -sum * dinv;
+
+    // ---- W = L^-1 over L.  Diagonal blocks first: lane j of a 16-lane group owns column j of its block.
+    {
+        const int grp = tid >> 4;                                 // 16 groups of 16 lanes, one block each
+        if (grp < nblk) {
+            const int k0 = grp * NB, j = tj;
+            double w[NB];
+#pragma unroll
+            for (int i = 0; i < NB; ++i) {
+                double sum = (i == j) ? 1.0 : 0.0;
+#pragma unroll
+                for (int k = 0; k < i; ++k)
+                    if (k >= j) sum -= L[(k0 + i) * PITCH + k0 + k] * w[k];
+                w[i] = (i >= j) ? sum / L[(k0 + i) * PITCH + k0 + i] : 0.0;
             }
+            __builtin_amdgcn_wave_barrier();                      // the group's reads of the block precede the rewrite
+#pragma unroll
+            for (int i = 0; i < NB; ++i)
+                if (i >= j) L[(k0 + i) * PITCH + k0 + j] = w[i];
         }
-        __syncthreads();                                  // row i of L fully read
-        if (tid <= i) L[i * PITCH + tid] = w;
+    }
+    __syncthreads();
+    // Block rows: W_ij = -W_ii (sum_{k = j}^{i - 1} L_ik W_kj), j < i; rows above i already hold W.
+    for (int ib = 1; ib < nblk; ++ib) {
+        const int i0 = ib * NB;
+        // S[ti][c] = sum over k in [c, i0) of L[i0 + ti][k] W[k][c] (W is lower triangular; above its
+        // diagonal the array still holds the input), c < i0: thread (ti, tj) takes the columns
+        // c = tj, tj + 16, ...
+        for (int c = tj; c < i0; c += 16) {
+            double acc = 0.0;
+            for (int k = c; k < i0; ++k) acc += L[(i0 + ti) * PITCH + k] * L[k * PITCH + c];
+            S[ti * QR_PANEL + c] = acc;
+        }
+        __syncthreads();
+        for (int c = tj; c < i0; c += 16) {
+            double acc = 0.0;
+#pragma unroll
+            for (int m = 0; m < NB; ++m)
+                if (m <= ti) acc += L[(i0 + ti) * PITCH + i0 + m] * S[m * QR_PANEL + c];   // W_ii is lower triangular
+            L[(i0 + ti) * PITCH + c] = -acc;
+        }
         __syncthreads();
     }
     for (int i = ti; i < rows; i += 16)
@@ -517,7 +606,7 @@ extern "C" asteria_status asteria_soap_refresh(const asteria_factor *f, int nfac
     // the first factor must fit: checked before anything touches the device
     if (refresh_fixed_bytes(n_all) + refresh_factor_bytes(f[0].n) > ws_bytes) return ASTERIA_WORKSPACE_TOO_SMALL;
     hipStream_t stream = reinterpret_cast<hipStream_t>(stream_);
-    constexpr size_t chol_lds = sizeof(double) * QR_PANEL * (QR_PANEL + 1);
+    constexpr size_t chol_lds = CHOL_LDS_BYTES;
     static bool chol_configured = false;
     if (!chol_configured) {
         ASTERIA_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(panel_chol_inverse_kernel),
