@@ -243,7 +243,9 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": "1.1B LLaMA-style model, all 2-D grads blocked at <=1024 (1184 blocks, 2368 factors), "
                                "bf16 power-law gradients, fp32 statistics, eps=1e-6*lambda_max, beta=0.95",
-                   "blocks": len(shapes), "factors": nf, "fp64_prefix_iters": j64, "fp16_split_from_iter": jlow, "x_update_on_fp16_cores": xt_lowp,
+                   "blocks": len(shapes), "factors": nf, "fp64_prefix_iters": j64, "fp64_prefix_products": ("fp64 cores" if args.int8_slices == 0 else
+                                                                      "int8 cores, diagonal + 7-bit slices (fp64 cores where the device-side estimate declines)"),
+                   "fp16_split_from_iter": jlow, "x_update_on_fp16_cores": xt_lowp,
                    "schedule": "interval-adapted" if args.schedule == 1 else "classical Newton",
                    "workspace_gib": round(ws_bytes / 2**30, 1)},
         "breakdown_ms": {"stats_update": round(stats_ms, 3), "inverse_root": round(refresh_ms, 3),
