@@ -139,8 +139,9 @@ typedef struct asteria_root_opts {
                               diagonal plus that many 7-bit slices below a per-row exponent (29 / 36 bits),
                               integer accumulation exact, result assembled in fp64 - per factor and
                               product, and only where the part this drops is estimated on the device to
-                              stay below 2e-5 of the bottom of M's spectrum (otherwise that product runs
-                              on the fp64 cores); -1 = 5 (default)                                     */
+                              stay below a fixed fraction (2e-5, shared among the fp64 iterations) of the
+                              bottom of M's spectrum; otherwise that product runs on the fp64 cores;
+                              -1 = 5 (default)                                                         */
 } asteria_root_opts;
 
 void asteria_root_opts_default(asteria_root_opts *opts);

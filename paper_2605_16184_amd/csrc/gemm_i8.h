@@ -208,12 +208,14 @@ inline size_t i8_slice_lds_bytes(int lds_k) { return (size_t)4 * ((lds_k + 15) /
 // in the chain products costs about u / lo in the root), da db = the product of the largest diagonal
 // entries as a lower bound of ||Sa|| ||Sb||.  One thread per factor; clears the maxima for the next
 // operand.
+// theta for a prefix of two fp64 iterations (six products); a longer prefix shares the same total: the
+// host passes theta * 2 / (number of fp64 iterations)
 constexpr float I8_THETA = 2e-5f;
 
 // `scal` points at the factor's (lo, hi, g) of the current iteration: the interval that holds the
 // spectrum of the current M and the g of the current T = a I - g M.
 __global__ void i8_gate_kernel(I8Factor *__restrict__ xf, int nf, const float *__restrict__ scal, int scal_stride_bytes,
-                               int ns_min, int ns_max, int abuf, int bbuf, int bmode)
+                               int ns_min, int ns_max, int abuf, int bbuf, int bmode, float theta)
 {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= nf) return;
@@ -228,7 +230,7 @@ __global__ void i8_gate_kernel(I8Factor *__restrict__ xf, int nf, const float *_
         db = hi;
         X.bscale = (g > 0.0f) ? -1.0f / g : 0.0f;
     }
-    const float allowed = I8_THETA * lo * da * db;
+    const float allowed = theta * lo * da * db;
     int gsel = 0;
     for (int ns = ns_max; ns >= ns_min; --ns) {       // the fewest slices that pass
         const float est = 0.33f * sqrtf((float)X.n * (float)(ns - 1)) * exp2f(-7.0f * (float)ns) * ra * rb;
