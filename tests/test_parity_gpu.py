@@ -277,6 +277,50 @@ def test_root_fp64_iterations_on_the_int8_cores_against_the_fp64_cores_and_the_o
         assert relF(X, Xo) <= TOL_ROOT
 
 
+def test_root_int8_decision_over_spectra_structures_and_prefix_lengths():
+    # The device-side decision of the int8 path (4 slices, 5 slices or the fp64 cores, per factor and
+    # product) against the fp64-core path: spectra with wide and narrow gaps, eigenvectors spread over
+    # all coordinates or confined to 2 and 4 of them (off-diagonal entries as large as the diagonal),
+    # and eps = 1e-8, where the fp64 prefix is four iterations long and twelve products share the error
+    # budget.  Reference: the definition V (lambda + eps)^(-1/4) V^T with a float64 eigendecomposition
+    # (the oracle's Jacobi sweeps would take minutes for this many matrices).
+    def spec_matrix(n, lam, width):
+        if width == 0:
+            U = W.haar(n, DEV, 31, dtype=torch.float64)
+            A = (U * lam) @ U.T
+        else:
+            A = torch.zeros(n, n, device=DEV, dtype=torch.float64)
+            perm = torch.randperm(n, device=DEV, generator=torch.Generator(DEV).manual_seed(5))
+            lp = lam[perm]
+            for b in range(0, n, width):
+                w = min(width, n - b)
+                U = W.haar(w, DEV, 40 + b, dtype=torch.float64)
+                A[b:b + w, b:b + w] = (U * lp[b:b + w]) @ U.T
+        return (0.5 * (A + A.T)).float().contiguous()
+    worst = 0.0
+    for n in (96, 512):
+        i = torch.arange(1, n + 1, device=DEV, dtype=torch.float64)
+        spectra = {"power law": 0.05 / i ** 2, "8 decades": 0.05 * 10 ** (-8 * (i - 1) / (n - 1)),
+                   "two levels": torch.where(i <= n // 2, 1.0, 1e-5) * 0.05}
+        for sname, lam in spectra.items():
+            for width in (0, 4, 2):
+                A = spec_matrix(n, lam, width)
+                w, V = torch.linalg.eigh(A.double())
+                for eps in (1e-6, 1e-8):
+                    Xdef = (V * (w + eps * w[-1]).clamp_min(1e-300) ** -0.25) @ V.T
+                    got = {}
+                    for ns in (-1, 0):
+                        (X,), info, iters, resid, lmax = run_roots([A], eps, opts=ast.RootOpts(int8_slices=ns))
+                        assert info[0] == B.INFO_OK, (n, sname, width, eps, ns)
+                        got[ns] = X.double()
+                        err = float((got[ns] - Xdef).norm() / Xdef.norm())
+                        assert err <= TOL_ROOT, (n, sname, width, eps, ns, err)
+                    dev = float((got[-1] - got[0]).norm() / got[0].norm())
+                    worst = max(worst, dev)
+                    assert dev <= 2.5e-4, (n, sname, width, eps, dev)
+    print("int8 path against the fp64-core path, worst relF", worst)
+
+
 def newton_count(a: float, n: int, stop: float = 1e-2, p: int = 4) -> int:
     """Scalar model of the coupled iteration on the smallest eigenvalue a of M_0."""
     mu, k = a, 0
