@@ -600,6 +600,31 @@ def test_soap_refresh_invariants_and_leading_columns(n):
     assert np.all(np.sum(Q[:, :lead] * Qo[:, :lead], axis=0) > 0)          # same sign convention
 
 
+@pytest.mark.parametrize("n", [31, 129, 173, 257])
+def test_soap_refresh_odd_sizes_in_a_padded_buffer(n):
+    # Q lives in a buffer with an odd leading dimension (rows not 16-byte aligned): the split-fp16
+    # products read and the panel transposes write the caller's Q through their guarded paths, and the
+    # padding columns stay untouched
+    G = W.gaussian_block(n, 3 * n, 1.0, DEV, 80 + n)
+    A = (G @ G.T / (3 * n)).contiguous()
+    buf = torch.full((n, n + 3), 7.0, device=DEV)
+    buf[:, :n] = W.haar(n, DEV, 81 + n)
+    Q = buf[:, :n]
+    Qin = Q.clone()
+    info = torch.full((1,), -1, dtype=torch.int32, device=DEV)
+    ast.soap_refresh([(A, Q)], info=info)
+    torch.cuda.synchronize()
+    assert info.item() == 0 and bool((buf[:, n:] == 7.0).all())
+    q = np64(Q.contiguous()); Z = np64(A) @ np64(Qin.contiguous())
+    assert np.linalg.norm(q.T @ q - np.eye(n)) / math.sqrt(n) <= 1e-5
+    Rm = q.T @ Z
+    assert np.linalg.norm(np.tril(Rm, -1)) <= 1e-5 * np.linalg.norm(Z)
+    assert np.linalg.norm(q @ np.triu(Rm) - Z) <= 1e-5 * np.linalg.norm(Z)
+    Qo, Ro = oracle.soap_refresh(np64(A), np64(Qin.contiguous()))
+    lead = min(16, n)
+    assert np.all(np.sum(q[:, :lead] * Qo[:, :lead], axis=0) >= 0.999)
+
+
 def test_soap_refresh_fixed_points_and_batch():
     d = torch.linspace(3.0, 0.5, 40, device=DEV)
     A1 = torch.diag(d).contiguous(); Q1 = torch.eye(40, device=DEV)
