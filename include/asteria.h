@@ -53,7 +53,8 @@ typedef enum asteria_status {
     ASTERIA_INVALID_ARG = 1,
     ASTERIA_UNSUPPORTED = 2,
     ASTERIA_WORKSPACE_TOO_SMALL = 3,
-    ASTERIA_HIP_ERROR = 4
+    ASTERIA_HIP_ERROR = 4,
+    ASTERIA_EXCEEDS_STATIC_SCRATCH = 5 /* asteria_inverse_root_static: a factor needs more than the fixed array */
 } asteria_status;
 
 typedef enum asteria_dtype {
@@ -202,6 +203,25 @@ asteria_status asteria_inverse_root(const asteria_factor *f, int nfactors, int r
                                     const asteria_root_opts *opts,
                                     int32_t *info, int32_t *iters, float *resid, float *lambda_max,
                                     void *ws, size_t ws_bytes, void *stream);
+
+/* ---- inverse p-th roots for callers that cannot allocate ------------------------------------
+ * For code that runs under HIP graph capture, tight serving loops and harnesses that forbid
+ * allocation: the same computation as asteria_inverse_root with the same arguments, except that
+ * the workspace is a fixed array of asteria_static_scratch_bytes() = 64 MiB inside the library's
+ * device image (every GPU the library runs on holds its own copy until the process ends; its
+ * address is looked up at the first call on a device).  The call allocates no device memory and
+ * calls no allocating routine.  The batch is worked through in passes that fit the array, so any
+ * number of factors is accepted, but each factor by itself must fit: with default options n up to
+ * about 1100 (50 bytes per matrix element plus tables).  A larger factor ->
+ * ASTERIA_EXCEEDS_STATIC_SCRATCH, nothing enqueued.  All calls on one GPU share that GPU's array,
+ * which keeps the last call's contents (every word a call reads it has written first): calls that
+ * overlap on one GPU - two streams, two threads - race; order them.                            */
+size_t asteria_static_scratch_bytes(void);
+asteria_status asteria_inverse_root_static(const asteria_factor *f, int nfactors, int root,
+                                           asteria_eps_mode mode, const float *eps, int eps_count,
+                                           const asteria_root_opts *opts,
+                                           int32_t *info, int32_t *iters, float *resid, float *lambda_max,
+                                           void *stream);
 
 /* ---- preconditioned update (paper Eq. 1) ---------------------------------------------------
  * For every block: P = X_L G X_R, X_L and X_R symmetric fp32; P is written as fp32 or bf16

@@ -10,6 +10,8 @@ from .binding import (  # noqa: F401
     stats_update,
     inverse_root,
     inverse_root_plan,
+    inverse_root_static,
+    static_scratch_bytes,
     precondition,
     soap_refresh,
     soap_step,

@@ -13,7 +13,7 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libasteria.so")
 
-OK, INVALID_ARG, UNSUPPORTED, WORKSPACE_TOO_SMALL, HIP_ERROR = range(5)
+OK, INVALID_ARG, UNSUPPORTED, WORKSPACE_TOO_SMALL, HIP_ERROR, EXCEEDS_STATIC_SCRATCH = range(6)
 F32, BF16 = 0, 1
 EPS_RELATIVE, EPS_ABSOLUTE = 0, 1
 INFO_OK, INFO_NOT_CONVERGED, INFO_NOT_PD = 0, 1, 2
@@ -95,6 +95,12 @@ def lib():
         L.asteria_inverse_root.argtypes = [POINTER(_Factor), c_int, c_int, c_int, POINTER(c_float), c_int,
                                            POINTER(RootOpts), c_void_p, c_void_p, c_void_p, c_void_p,
                                            c_void_p, c_size_t, c_void_p]
+        L.asteria_static_scratch_bytes.restype = c_size_t
+        L.asteria_static_scratch_bytes.argtypes = []
+        L.asteria_inverse_root_static.restype = c_int
+        L.asteria_inverse_root_static.argtypes = [POINTER(_Factor), c_int, c_int, c_int, POINTER(c_float), c_int,
+                                                  POINTER(RootOpts), c_void_p, c_void_p, c_void_p, c_void_p,
+                                                  c_void_p]
         L.asteria_precondition_workspace_bytes.restype = c_size_t
         L.asteria_precondition_workspace_bytes.argtypes = [POINTER(_PBlock), c_int]
         L.asteria_precondition.restype = c_int
@@ -309,6 +315,29 @@ def inverse_root(factors, eps, relative: bool = True, root: int = 4, opts: Optio
                                     _ptr(lambda_max, torch.float32, f.count, "lambda_max"),
                                     c_void_p(ws.data_ptr()), ws.numel(), _stream(stream))
     _check(st, "asteria_inverse_root")
+
+
+def static_scratch_bytes() -> int:
+    return lib().asteria_static_scratch_bytes()
+
+
+def inverse_root_static(factors, eps, relative: bool = True, root: int = 4, opts: Optional[RootOpts] = None,
+                        info: Optional[torch.Tensor] = None, iters: Optional[torch.Tensor] = None,
+                        resid: Optional[torch.Tensor] = None, lambda_max: Optional[torch.Tensor] = None,
+                        stream=None) -> None:
+    """inverse_root on the library's fixed scratch array: no workspace, no allocation anywhere."""
+    f = _as(Factors, factors)
+    eps_list = [float(eps)] if not isinstance(eps, (Sequence, torch.Tensor)) else [float(e) for e in eps]
+    eps_arr = (c_float * len(eps_list))(*eps_list)
+    st = lib().asteria_inverse_root_static(f.array, f.count, int(root),
+                                           EPS_RELATIVE if relative else EPS_ABSOLUTE, eps_arr, len(eps_list),
+                                           ctypes.byref(opts) if opts else None,
+                                           _ptr(info, torch.int32, f.count, "info"),
+                                           _ptr(iters, torch.int32, f.count, "iters"),
+                                           _ptr(resid, torch.float32, f.count, "resid"),
+                                           _ptr(lambda_max, torch.float32, f.count, "lambda_max"),
+                                           _stream(stream))
+    _check(st, "asteria_inverse_root_static")
 
 
 def precondition_workspace_bytes(blocks) -> int:

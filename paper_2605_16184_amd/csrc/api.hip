@@ -14,6 +14,7 @@ extern "C" const char *asteria_status_string(asteria_status s)
         case ASTERIA_UNSUPPORTED: return "unsupported";
         case ASTERIA_WORKSPACE_TOO_SMALL: return "workspace too small";
         case ASTERIA_HIP_ERROR: return "HIP runtime error";
+        case ASTERIA_EXCEEDS_STATIC_SCRATCH: return "a factor exceeds the static scratch array";
     }
     return "unknown status";
 }

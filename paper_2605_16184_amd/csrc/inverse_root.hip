@@ -1087,3 +1087,48 @@ extern "C" asteria_status asteria_inverse_root(const asteria_factor *f, int nfac
     }
     return ASTERIA_OK;
 }
+
+// ---- the same call for callers that cannot allocate ---------------------------------------------
+// The workspace is a fixed array in the library's device image instead of caller memory.  In host
+// code the array's name only stands for the symbol: its device address is looked up once per device
+// and that pointer is what the kernels (and nothing else here) receive.
+namespace {
+constexpr size_t STATIC_SCRATCH_BYTES = (size_t)64 << 20;
+constexpr int STATIC_SCRATCH_MAX_DEVICES = 64;
+}  // namespace
+static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
+static void *g_scratch_ptr[STATIC_SCRATCH_MAX_DEVICES];   // device address of `scratch`, per device
+
+extern "C" size_t asteria_static_scratch_bytes(void) { return STATIC_SCRATCH_BYTES; }
+
+extern "C" asteria_status asteria_inverse_root_static(const asteria_factor *f, int nfactors, int root,
+                                                      asteria_eps_mode mode, const float *eps, int eps_count,
+                                                      const asteria_root_opts *opts,
+                                                      int32_t *info, int32_t *iters, float *resid, float *lambda_max,
+                                                      void *stream_)
+{
+    asteria_status st = validate(f, nfactors, root, eps, eps_count);
+    if (st != ASTERIA_OK) return st;
+    if (mode != ASTERIA_EPS_RELATIVE && mode != ASTERIA_EPS_ABSOLUTE) return ASTERIA_INVALID_ARG;
+    Plan pl;
+    st = make_plan(opts, mode, eps, eps_count, root, pl);
+    if (st != ASTERIA_OK) return st;
+    // every factor must fit the array by itself (the call works through the batch in passes)
+    for (int i = 0; i < nfactors; ++i) {
+        const int n = f[i].n;
+        const size_t b = fixed_bytes() + factor_matrix_bytes(n, pl.use64, pl.use32) + factor_small_bytes(n) +
+                         factor_i8_bytes(n, pl.i8_slices);
+        if (b > STATIC_SCRATCH_BYTES) return ASTERIA_EXCEEDS_STATIC_SCRATCH;
+    }
+    int dev = -1;
+    ASTERIA_HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= STATIC_SCRATCH_MAX_DEVICES) return ASTERIA_UNSUPPORTED;
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        ASTERIA_HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) return ASTERIA_HIP_ERROR;
+        g_scratch_ptr[dev] = p;
+    }
+    return asteria_inverse_root(f, nfactors, root, mode, eps, eps_count, opts, info, iters, resid, lambda_max,
+                                g_scratch_ptr[dev], STATIC_SCRATCH_BYTES, stream_);
+}
