@@ -62,6 +62,12 @@ typedef enum asteria_dtype {
     ASTERIA_BF16 = 1
 } asteria_dtype;
 
+/* how asteria_stats_update accumulates a block's products */
+typedef enum asteria_acc {
+    ASTERIA_ACC_F32 = 0, /* fp32 sums, fp32 EMA (bf16 gradients: bf16 matrix cores, products exact)   */
+    ASTERIA_ACC_F64 = 1  /* fp64 sums and EMA on the fp64 matrix cores, one rounding to the fp32 L, R */
+} asteria_acc;
+
 /* per-factor numerical outcome written to the device `info` arrays */
 enum {
     ASTERIA_INFO_OK = 0,
@@ -77,6 +83,7 @@ typedef struct asteria_block {
     int32_t m, n;
     int32_t ldg, ldl, ldr;
     int32_t g_dtype; /* asteria_dtype */
+    int32_t acc;     /* asteria_acc (0 = fp32 accumulation) */
 } asteria_block;
 
 /* One symmetric factor and the matrix produced from it. */
@@ -154,7 +161,12 @@ const char *asteria_status_string(asteria_status s);
  * For every block: L <- beta L + (1-beta) G G^T and R <- beta R + (1-beta) G^T G, products
  * accumulated in fp32 (bf16 x bf16 products are exact in fp32).  L and R come back exactly
  * symmetric (one triangle is computed, the other mirrored).  Either L or R may be NULL to skip
- * that side.  0 <= beta < 1.  The workspace holds the problem tables and, for a bf16 block whose
+ * that side.  0 <= beta < 1.  A block with acc = ASTERIA_ACC_F64 is accumulated in fp64 instead
+ * (exact products, fp64 sums and EMA, rounded once to fp32): L and R are then the fp32 numbers
+ * nearest to the exact update, whose eigenvalues lie within about 1e-9 lambda_max of the exact
+ * ones - what a relative eps of 1e-8 in asteria_inverse_root needs (with fp32 sums the smallest
+ * eigenvalue of a rank-deficient statistic can fall to -2e-8 lambda_max, below such an eps).  At
+ * about a tenth of the speed (fp64 matrix cores).  The workspace holds the problem tables and, for a bf16 block whose
  * G is not 16-byte aligned or does not fill whole 128 x 64 tiles, a transposed copy of G.
  * Errors: NULL G, m or n <= 0, ld too small, bad dtype, beta out of range -> INVALID_ARG.   */
 size_t asteria_stats_update_workspace_bytes(const asteria_block *blocks, int nblocks);

@@ -15,6 +15,7 @@ _LIB_PATH = os.path.join(_HERE, "libasteria.so")
 
 OK, INVALID_ARG, UNSUPPORTED, WORKSPACE_TOO_SMALL, HIP_ERROR, EXCEEDS_STATIC_SCRATCH = range(6)
 F32, BF16 = 0, 1
+ACC_F32, ACC_F64 = 0, 1
 EPS_RELATIVE, EPS_ABSOLUTE = 0, 1
 INFO_OK, INFO_NOT_CONVERGED, INFO_NOT_PD = 0, 1, 2
 
@@ -27,7 +28,7 @@ class AsteriaError(RuntimeError):
 
 class _Block(Structure):
     _fields_ = [("G", c_void_p), ("L", c_void_p), ("R", c_void_p), ("m", c_int32), ("n", c_int32),
-                ("ldg", c_int32), ("ldl", c_int32), ("ldr", c_int32), ("g_dtype", c_int32)]
+                ("ldg", c_int32), ("ldl", c_int32), ("ldr", c_int32), ("g_dtype", c_int32), ("acc", c_int32)]
 
 
 class _Factor(Structure):
@@ -170,10 +171,12 @@ class _Batch:
 
 
 class Blocks(_Batch):
-    """[(G, L, R)] for stats_update; L or R may be None."""
+    """[(G, L, R)] or [(G, L, R, acc)] for stats_update; L or R may be None, acc is ACC_F32 (default)
+    or ACC_F64."""
     ctype = _Block
 
-    def _fill(self, d, G, L, R):
+    def _fill(self, d, G, L, R, acc=ACC_F32):
+        d.acc = int(acc)
         d.G, d.m, d.n, d.ldg = _mat(G, "G")
         d.g_dtype = _dtype_code(G)
         d.L, _, _, d.ldl = _mat(L, "L", torch.float32)

@@ -44,7 +44,8 @@ enum : int {
     GEMM_SYM = 1,        // compute tiles with ti >= tj only, mirror the result
     GEMM_EPI_ROOT = 2,   // C2 = ep_a * I - ep_g * C ; partial[tile] = sum (C - I)^2
     GEMM_C_BF16 = 4,     // C is stored as bf16 (fp32 compute only)
-    GEMM_STORE_T = 8     // C is stored transposed: element (row, col) at C[col * ldc + row] (no beta, not symmetric)
+    GEMM_STORE_T = 8,    // C is stored transposed: element (row, col) at C[col * ldc + row] (no beta, not symmetric)
+    GEMM_C_F32 = 16      // C is stored as fp32 (fp64 compute only): read, combined in fp64, rounded once
 };
 
 struct GemmProblem {
@@ -185,6 +186,19 @@ template <> struct StoreLds<double, float> {   // fp32 data accumulated on the f
         ((ASTERIA_LDS doublex2 *)dst)[1] = b;
     }
 };
+template <> struct StoreLds<double, bf16_t> {  // bf16 data accumulated on the fp64 matrix cores
+    __device__ static __forceinline__ void run(ASTERIA_LDS double *dst, u32x4 v)
+    {
+        typedef double doublex2 __attribute__((ext_vector_type(2)));
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            doublex2 a;
+            a[0] = (double)__uint_as_float(v[w] << 16);
+            a[1] = (double)__uint_as_float(v[w] & 0xffff0000u);
+            ((ASTERIA_LDS doublex2 *)dst)[w] = a;
+        }
+    }
+};
 template <> struct StoreLds<float, bf16_t> {
     __device__ static __forceinline__ void run(ASTERIA_LDS float *dst, u32x4 v)
     {
@@ -203,8 +217,11 @@ struct OperandStage {
     static constexpr int BK = Mma<TC>::BK;
     static constexpr int VPR = KMAJOR ? (BM / EPV) : (BK / EPV);       // vectors per stored row
     static constexpr int NTHREADS = Mma<TC>::NTHR;
-    static constexpr int NV = (KMAJOR ? BK : BM) * VPR / NTHREADS;     // vectors per thread
-    static_assert(NV >= 1, "tile too small for the thread count");
+    static constexpr int TOTAL = (KMAJOR ? BK : BM) * VPR;             // vectors per tile
+    static constexpr int NV = (TOTAL + NTHREADS - 1) / NTHREADS;       // vectors per thread
+    // a tile with fewer vectors than threads (bf16 data under the 16-wide fp64 slab): the threads
+    // beyond the tile stage nothing
+    static constexpr bool PARTIAL = (TOTAL % NTHREADS) != 0;
     static constexpr int LDS_ELEMS = KMAJOR ? BK * Mma<TC>::PITCH_KM : BM * Mma<TC>::PITCH_KC;
 
     u32x4 r[NV];
@@ -220,6 +237,7 @@ struct OperandStage {
             const int idx = tid + NTHREADS * v;
             const int a = idx / VPR;   // stored row
             const int b = idx % VPR;   // vector within the stored row
+            if (PARTIAL && idx >= TOTAL) { r[v] = (u32x4){0u, 0u, 0u, 0u}; continue; }
             if (!GUARD) {
                 const TI *p = KMAJOR ? base + (size_t)(k0 + a) * ld + row0 + b * EPV
                                      : base + (size_t)(row0 + a) * ld + k0 + b * EPV;
@@ -245,6 +263,7 @@ struct OperandStage {
             const int idx = tid + NTHREADS * v;
             const int a = idx / VPR;
             const int b = idx % VPR;
+            if (PARTIAL && idx >= TOTAL) continue;
             StoreLds<TC, TI>::run(lds + a * PITCH + b * EPV, r[v]);
         }
     }
@@ -267,8 +286,9 @@ template <> __device__ __forceinline__ float load_c<float>(const void *C, size_t
     if (flags & GEMM_C_BF16) return bf16_to_f32(reinterpret_cast<const uint16_t *>(C)[off]);
     return reinterpret_cast<const float *>(C)[off];
 }
-template <> __device__ __forceinline__ double load_c<double>(const void *C, size_t off, int)
+template <> __device__ __forceinline__ double load_c<double>(const void *C, size_t off, int flags)
 {
+    if (flags & GEMM_C_F32) return (double)reinterpret_cast<const float *>(C)[off];
     return reinterpret_cast<const double *>(C)[off];
 }
 template <typename TC> __device__ __forceinline__ void store_c(void *C, size_t off, TC v, int flags);
@@ -277,9 +297,10 @@ template <> __device__ __forceinline__ void store_c<float>(void *C, size_t off, 
     if (flags & GEMM_C_BF16) reinterpret_cast<uint16_t *>(C)[off] = f32_to_bf16(v);
     else reinterpret_cast<float *>(C)[off] = v;
 }
-template <> __device__ __forceinline__ void store_c<double>(void *C, size_t off, double v, int)
+template <> __device__ __forceinline__ void store_c<double>(void *C, size_t off, double v, int flags)
 {
-    reinterpret_cast<double *>(C)[off] = v;
+    if (flags & GEMM_C_F32) reinterpret_cast<float *>(C)[off] = (float)v;
+    else reinterpret_cast<double *>(C)[off] = v;
 }
 
 // K loop of one 128 x 128 tile: two LDS stages, the next slab is fetched into registers while

@@ -11,6 +11,9 @@
 //     the workspace first and read k-contiguous.  A G G^T whose operand is unaligned or ragged
 //     takes the guarded kernel.
 //   fp32 gradients: fp32 MFMA; G^T G reads G k-major, no copy.
+//   Blocks that ask for fp64 accumulation (acc = ASTERIA_ACC_F64): products and sums on the fp64
+//     matrix cores from the bf16 / fp32 data (every product exact, sums to 2^-53), the EMA in fp64
+//     and one rounding to the fp32 L / R; G^T G reads G k-major, no copy.
 #include <vector>
 
 #include "common.h"
@@ -67,6 +70,8 @@ __global__ __launch_bounds__(256) void transpose_bf16_kernel(const TransposeJob 
 struct StatsTables {
     std::vector<GemmProblem> L[2], R[2];   // by dtype (guarded kernels)
     int tilesL[2] = {0, 0}, tilesR[2] = {0, 0};
+    std::vector<GemmProblem> L64[2], R64[2];   // by dtype: fp64 accumulation
+    int tilesL64[2] = {0, 0}, tilesR64[2] = {0, 0};
     std::vector<PlaneProblem> fast;        // bf16 problems for the guard-free kernel (L and R sides)
     int tiles_fast = 0;
 };
@@ -107,6 +112,7 @@ asteria_status validate(const asteria_block *b, int nblocks, float beta)
         const asteria_block &k = b[i];
         if (!k.G || k.m <= 0 || k.n <= 0 || k.ldg < k.n) return ASTERIA_INVALID_ARG;
         if (!valid_dtype(k.g_dtype)) return ASTERIA_INVALID_ARG;
+        if (k.acc != ASTERIA_ACC_F32 && k.acc != ASTERIA_ACC_F64) return ASTERIA_INVALID_ARG;
         if (!k.L && !k.R) return ASTERIA_INVALID_ARG;
         if (k.L && k.ldl < k.m) return ASTERIA_INVALID_ARG;
         if (k.R && k.ldr < k.n) return ASTERIA_INVALID_ARG;
@@ -126,6 +132,22 @@ void build(const asteria_block *b, int nblocks, float beta, StatsTables &t)
         p.state_idx = -1; p.state_mask = ~0;
         p.alpha = 1.0f - beta; p.beta = beta;
         p.flags = GEMM_SYM;
+        if (k.acc == ASTERIA_ACC_F64) {
+            p.flags |= GEMM_C_F32;
+            if (k.L) {
+                p.C = k.L; p.ldc = k.ldl; p.M = k.m; p.N = k.m; p.K = k.n;
+                p.tile_start = t.tilesL64[d];
+                t.tilesL64[d] += tri_tiles(k.m);
+                t.L64[d].push_back(p);
+            }
+            if (k.R) {
+                p.C = k.R; p.ldc = k.ldr; p.M = k.n; p.N = k.n; p.K = k.m;
+                p.tile_start = t.tilesR64[d];
+                t.tilesR64[d] += tri_tiles(k.n);
+                t.R64[d].push_back(p);
+            }
+            continue;
+        }
         if (k.L) {
             if (d == ASTERIA_BF16 && fast_operand(k.G, k.m, k.n, k.ldg)) {
                 t.fast.push_back(fast_problem(k.G, k.m, k.n, k.ldg, k.L, k.ldl, beta, t.tiles_fast));
@@ -151,12 +173,12 @@ void build(const asteria_block *b, int nblocks, float beta, StatsTables &t)
 extern "C" size_t asteria_stats_update_workspace_bytes(const asteria_block *blocks, int nblocks)
 {
     if (!blocks || nblocks <= 0) return 0;
-    size_t bytes = 2 * Carver::need((size_t)nblocks, sizeof(GemmProblem)) +
+    size_t bytes = 4 * Carver::need((size_t)nblocks, sizeof(GemmProblem)) +
                    Carver::need(2 * (size_t)nblocks, sizeof(PlaneProblem)) +
                    Carver::need((size_t)nblocks, sizeof(TransposeJob)) + 8 * 256;
     for (int i = 0; i < nblocks; ++i)
-        if (blocks[i].g_dtype == ASTERIA_BF16 && blocks[i].R && blocks[i].m > 0 && blocks[i].n > 0 &&
-            !kmajor_operand(blocks[i].G, blocks[i].m, blocks[i].n, blocks[i].ldg))
+        if (blocks[i].g_dtype == ASTERIA_BF16 && blocks[i].acc != ASTERIA_ACC_F64 && blocks[i].R && blocks[i].m > 0 &&
+            blocks[i].n > 0 && !kmajor_operand(blocks[i].G, blocks[i].m, blocks[i].n, blocks[i].ldg))
             bytes += Carver::need((size_t)pad_to(blocks[i].n, ST_TILE) * pad_to(blocks[i].m, ST_BK), sizeof(uint16_t));
     return bytes;
 }
@@ -180,7 +202,7 @@ extern "C" asteria_status asteria_stats_update(const asteria_block *blocks, int 
         TransposeJob *d_jobs = cv.take<TransposeJob>(nblocks);
         for (int i = 0; i < nblocks; ++i) {
             const asteria_block &k = blocks[i];
-            if (k.g_dtype != ASTERIA_BF16 || !k.R) continue;
+            if (k.g_dtype != ASTERIA_BF16 || !k.R || k.acc == ASTERIA_ACC_F64) continue;
             if (kmajor_operand(k.G, k.m, k.n, k.ldg)) {
                 PlaneProblem q = fast_problem(k.G, k.n, k.m, k.ldg, k.R, k.ldr, beta, t.tiles_fast);
                 q.flags |= PG_KMAJOR;
@@ -229,6 +251,25 @@ extern "C" asteria_status asteria_stats_update(const asteria_block *blocks, int 
         } else {
             if (dL) ASTERIA_HIP_TRY((launch_gemm_bf16_grouped<bf16_t, bf16_t, 1, 1>(dL, (int)t.L[d].size(), t.tilesL[d], nullptr, stream)));
             if (dR) ASTERIA_HIP_TRY((launch_gemm_bf16_grouped<bf16_t, bf16_t, 1, 1>(dR, (int)t.R[d].size(), t.tilesR[d], nullptr, stream)));
+        }
+    }
+    // fp64 accumulation
+    for (int d = 0; d < 2; ++d) {
+        GemmProblem *dL = nullptr, *dR = nullptr;
+        if (!t.L64[d].empty()) {
+            dL = cv.take<GemmProblem>(t.L64[d].size());
+            ASTERIA_HIP_TRY(upload_async(dL, t.L64[d].data(), t.L64[d].size() * sizeof(GemmProblem), stream));
+        }
+        if (!t.R64[d].empty()) {
+            dR = cv.take<GemmProblem>(t.R64[d].size());
+            ASTERIA_HIP_TRY(upload_async(dR, t.R64[d].data(), t.R64[d].size() * sizeof(GemmProblem), stream));
+        }
+        if (d == ASTERIA_F32) {
+            if (dL) ASTERIA_HIP_TRY((launch_gemm_grouped<double, float, float, false, false>(dL, (int)t.L64[d].size(), t.tilesL64[d], nullptr, stream)));
+            if (dR) ASTERIA_HIP_TRY((launch_gemm_grouped<double, float, float, true, true>(dR, (int)t.R64[d].size(), t.tilesR64[d], nullptr, stream)));
+        } else {
+            if (dL) ASTERIA_HIP_TRY((launch_gemm_grouped<double, bf16_t, bf16_t, false, false>(dL, (int)t.L64[d].size(), t.tilesL64[d], nullptr, stream)));
+            if (dR) ASTERIA_HIP_TRY((launch_gemm_grouped<double, bf16_t, bf16_t, true, true>(dR, (int)t.R64[d].size(), t.tilesR64[d], nullptr, stream)));
         }
     }
     return ASTERIA_OK;

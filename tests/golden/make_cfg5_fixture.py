@@ -10,6 +10,7 @@ its answer is computed once here and a sample of it is stored:
       A_rows_s  float32[32, n]   those rows of the fp32 statistic the root is taken of
       X_rows_s  float64[32, n]   the same rows of X = (A + eps I)^(-1/4), eps = 1e-8 lambda_max
       lam_s     float64[n]       Jacobi's spectrum of A (unsorted)
+      P_rows    float64[32, n]   rows rows_L of P = X_L G X_R (paper Eq. 1) from the two oracle roots
   cfg5_block<b>.json  seeds, sizes, lambda_max, oracle status, sha256 of the gradient's bf16 bits
                       and of the fp32 statistics, timings
 
@@ -45,8 +46,10 @@ WN = importlib.util.module_from_spec(_spec)
 _spec.loader.exec_module(WN)
 
 CFG = 5
-BETA = 0.95
-EPS_REL = 1e-8
+# beta and eps as the fp32 numbers the C ABI carries (1 - beta is then exact in fp32 too), so that the
+# stored statistics are the ones a float64 accumulation of the same call arguments rounds to
+BETA = float(np.float32(0.95))
+EPS_REL = float(np.float32(1e-8))
 NROWS = 32
 
 
@@ -98,6 +101,12 @@ def main() -> None:
             "A_f32_sha256": hashlib.sha256(A[side].tobytes()).hexdigest(),
             "X_fro": float(np.linalg.norm(X)) if st == oracle.OK else None,
             "oracle_seconds": round(dt, 1)}
+    if all(r[0] == oracle.OK for r in res.values()):
+        t0 = time.time()
+        P = oracle.precondition(res["L"][1], G, res["R"][1])
+        arrays["P_rows"] = P[arrays["rows_L"]]
+        meta["P_fro"] = float(np.linalg.norm(P))
+        print(f"[fixture] oracle precondition in {time.time() - t0:.0f} s", flush=True)
     tag = f"cfg5_block{b}" + ("" if n == 4096 else f"_n{n}")
     np.savez(os.path.join(args.out, tag + ".npz"), **arrays)
     with open(os.path.join(args.out, tag + ".json"), "w") as f:

@@ -56,6 +56,7 @@ def test_stats_update_rejects_bad_arguments_without_launching():
     assert f(_blk(ldg=7), 1, 0.9, ws, 1 << 20, None) == B.INVALID_ARG
     assert f(_blk(ldl=7), 1, 0.9, ws, 1 << 20, None) == B.INVALID_ARG
     assert f(_blk(g_dtype=5), 1, 0.9, ws, 1 << 20, None) == B.INVALID_ARG
+    assert f(_blk(acc=2), 1, 0.9, ws, 1 << 20, None) == B.INVALID_ARG
     assert f(_blk(L=None, R=None), 1, 0.9, ws, 1 << 20, None) == B.INVALID_ARG
     assert f(_blk(), 1, 0.9, None, 0, None) == B.WORKSPACE_TOO_SMALL
     assert f(_blk(), 1, 0.9, ws, 16, None) == B.WORKSPACE_TOO_SMALL

@@ -151,6 +151,72 @@ def test_stats_full_size_1024_block_lowrank_bf16():
     assert relF(L, Lo) <= TOL_STATS and relF(R, Ro) <= TOL_STATS
 
 
+def ulps(a: torch.Tensor, b: np.ndarray) -> np.ndarray:
+    """distance in fp32 units in the last place between a GPU fp32 tensor and float64 values rounded to fp32"""
+    ai = a.detach().cpu().contiguous().numpy().view(np.int32).astype(np.int64)
+    bi = np.ascontiguousarray(b.astype(np.float32)).view(np.int32).astype(np.int64)
+    ai = np.where(ai < 0, -(ai & 0x7fffffff), ai)
+    bi = np.where(bi < 0, -(bi & 0x7fffffff), bi)
+    return np.abs(ai - bi)
+
+
+def test_stats_fp64_accumulation_is_the_float64_update_rounded_once():
+    # acc = ACC_F64: exact products, fp64 sums and EMA, one rounding to fp32.  beta is handed to the
+    # oracle as the fp32 number the C ABI carries (1 - beta is then exact in fp32 as well), so the
+    # oracle's float64 result rounded to fp32 is what the call must return, up to the order of the
+    # float64 additions (which can move a value that lies within 1e-16 of a rounding boundary).
+    beta = float(np.float32(0.9))
+    shapes = [(200, 328, torch.bfloat16), (1, 1, torch.float32), (3, 5, torch.bfloat16), (130, 257, torch.float32),
+              (256, 1024, torch.bfloat16), (129, 127, torch.bfloat16), (384, 128, torch.float32)]
+    items, refs = [], []
+    for i, (m, n, dt) in enumerate(shapes):
+        G = padded(m, n, 3 if i % 2 else 0, dt, fill=5.0)
+        G.copy_(W.gaussian_block(m, n, 0.1, DEV, 12, i, dtype=dt))
+        L = padded(m, m, 5); L.copy_(spd(m, 11, i))
+        R = padded(n, n, 0); R.copy_(spd(n, 12, i))
+        refs.append(oracle.stats_update(np64(G), np64(L), np64(R), beta))
+        items.append((G, L, R, B.ACC_F64))
+    # one block of the same call keeps fp32 accumulation
+    G32 = W.gaussian_block(256, 128, 0.1, DEV, 13, dtype=torch.bfloat16)
+    L32, R32 = spd(256, 14), spd(128, 15)
+    ref32 = oracle.stats_update(np64(G32), np64(L32), np64(R32), beta)
+    ast.stats_update(items + [(G32, L32, R32)], beta)
+    torch.cuda.synchronize()
+    for (G, L, R, _), (Lo, Ro) in zip(items, refs):
+        for X, Xo in ((L, Lo), (R, Ro)):
+            u = ulps(X, Xo)
+            assert u.max() <= 1 and (u > 0).mean() <= 1e-4, (tuple(G.shape), int(u.max()), float((u > 0).mean()))
+            assert torch.equal(X, X.T)
+        assert torch.all(L._base[:, L.shape[1]:] == -777.0) and torch.all(G._base[:, G.shape[1]:] == 5.0)
+    assert relF(L32, ref32[0]) <= TOL_STATS and relF(R32, ref32[1]) <= TOL_STATS
+
+
+def test_stats_fp64_accumulation_keeps_an_ill_conditioned_statistic_above_minus_half_eps():
+    # the 4096 stress workload in miniature (singular values over 8 decades, eps = 1e-8 lambda_max):
+    # the statistics of one update from zero are positive semi-definite up to round-off, and the root
+    # needs lambda_min > -eps / 2.  fp64 accumulation leaves the rounding of the stored fp32 numbers as
+    # the only error (about 1.4e-9 lambda_max); the oracle then grades the root of that very matrix.
+    n = 512
+    beta = float(np.float32(0.95))
+    U, V = W.haar(n, DEV, 301, dtype=torch.float64), W.haar(n, DEV, 302, dtype=torch.float64)
+    G = ((U * W.logspaced_sigma(n, 8.0, DEV)) @ V.T).to(torch.bfloat16)
+    L = torch.zeros(n, n, device=DEV); R = torch.zeros(n, n, device=DEV)
+    ast.stats_update([(G, L, R, B.ACC_F64)], beta)
+    torch.cuda.synchronize()
+    Lo, Ro = oracle.stats_update(np64(G), np.zeros((n, n)), np.zeros((n, n)), beta)
+    assert ulps(L, Lo).max() <= 1 and ulps(R, Ro).max() <= 1
+    eps = float(np.float32(1e-8))
+    Xo, lmax_o, status = oracle.inverse_root_batch([np64(L), np64(R)], eps)
+    assert np.all(status == oracle.OK)                    # the oracle does not clamp: positive definite with eps
+    for A in (L, R):
+        lam = np.linalg.eigvalsh(np64(A))
+        assert lam[0] > -0.5 * eps * lam[-1], lam[0] / lam[-1]
+    Xs, info, iters, resid, lmax = run_roots([L, R], eps)
+    assert np.all(info == B.INFO_OK)
+    for i in range(2):
+        assert relF(Xs[i], Xo[i]) <= TOL_ROOT, relF(Xs[i], Xo[i])
+
+
 # =============================================================================== a2 inverse roots
 
 def test_root_single_block_config_absolute_and_relative_eps():
