@@ -258,11 +258,14 @@ def test_lowrank_batch_of_64_blocks_stage_by_stage(started):
             err_l = abs(S["lmax"][idx] - lmax_o) / lmax_o
             err = relF(X[b], Xo)
             print("block", b, side, "lambda_max error", err_l, "root relF", err)
-            assert err_l <= 1e-3 and err <= TOL_ROOT, (b, side, err_l, err)
+            assert err_l <= 1e-4 and err <= TOL_ROOT, (b, side, err_l, err)
         Po = J["precond"].result()
         err = relF(S["Ps"][b], Po)
         print("block", b, "precondition relF", err)
-        assert err <= 1e-4, err                      # stated bar 1e-2; split-bf16 roots keep 16 bits
+        # stated bar 1e-2.  The roots enter as two bf16 terms (16 bits below each entry's own exponent
+        # class): here they hold 32 directions of size lambda^-1/4 next to ~990 of size eps^-1/4, thirty
+        # times larger, and P is the small part times G - about 1e-4 (well-conditioned blocks: 1e-5)
+        assert err <= 1e-3, err
     # every other block: symmetric roots, finite outputs
     for b in range(S["nb"]):
         assert torch.equal(S["XLs"][b], S["XLs"][b].T) and bool(torch.isfinite(S["Ps"][b]).all())

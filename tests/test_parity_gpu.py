@@ -605,8 +605,9 @@ def test_full_model_batch_in_the_timed_launch_configuration_sampled_against_the_
     factors = ast.Factors([(L, X) for L, X in zip(Ls, XLs)] + [(R, X) for R, X in zip(Rs, XRs)])
     pblocks = ast.PBlocks(list(zip(XLs, Gs, XRs, Ps)))
     full, mn = ast.inverse_root_workspace_bytes(factors, None)
-    ws_bytes = int(max(min(full, 96 * 2**30), mn, ast.precondition_workspace_bytes(pblocks),
+    ws_bytes = int(max(min(full, 128 * 2**30), mn,       # as the benchmark: all 2368 factors in one pass (107 GiB) ast.precondition_workspace_bytes(pblocks),
                        ast.stats_update_workspace_bytes(blocks)))
+    assert ws_bytes >= full, "the timed configuration is a single pass"
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device=DEV)
     info = torch.full((2 * nb,), -1, dtype=torch.int32, device=DEV)
     ast.stats_update(blocks, 0.95, ws=ws)
