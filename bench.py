@@ -347,9 +347,10 @@ def soap_section(args, torch, ast, W, dev):
     torch.cuda.synchronize()
     log(f"[bench] soap: {len(shapes)} blocks, {len(factors)} factors, workspace {need / 2**30:.1f} GiB, "
         f"{torch.cuda.memory_allocated() / 2**30:.1f} GiB resident")
+    aux = [torch.cuda.Stream(), torch.cuda.Stream()]   # two groups of factors side by side (default priority)
     for w in range(3):                          # warm the bases from the identity
         ast.stats_update(blocks[w % nsets], beta, ws=ws)
-        ast.soap_refresh(factors, info=info, ws=ws)
+        ast.soap_refresh(factors, info=info, ws=ws, aux_streams=aux)
     torch.cuda.synchronize()
     ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
     for t in range(args.steps):
@@ -360,7 +361,7 @@ def soap_section(args, torch, ast, W, dev):
         ev[t][2].record()
     r0, r1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     r0.record()
-    ast.soap_refresh(factors, info=info, ws=ws)
+    ast.soap_refresh(factors, info=info, ws=ws, aux_streams=aux)
     r1.record()
     torch.cuda.synchronize()
     step_ms = sum(e[0].elapsed_time(e[1]) for e in ev) / args.steps

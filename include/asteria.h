@@ -26,14 +26,14 @@
  *   - `ws` is caller-owned device scratch of `ws_bytes` bytes, 256-byte aligned; the matching
  *     *_workspace_bytes query returns the size that lets the whole batch run in one pass and
  *     (where a min_bytes pointer is given) the smallest size the call accepts.  The library
- *     itself allocates no device memory and keeps no state between calls (apart from the two
- *     internal streams of asteria_soap_refresh and the measurement aid at the end of this file).
+ *     itself allocates no device memory and keeps no state between calls (apart from the fixed
+ *     array of asteria_inverse_root_static and the measurement aid at the end of this file).
  *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  All work is
- *     enqueued on it (asteria_soap_refresh: or on internal streams ordered after and before it);
- *     no entry point waits for the device.  A call may stage its descriptor
+ *     enqueued on it (asteria_soap_refresh_overlapped: or on streams the caller passes, ordered
+ *     after and before it); no entry point waits for the device.  A call may stage its descriptor
  *     tables with hipMemcpyAsync from host memory it owns until the call returns.
- *   - Entry points are not re-entrant: call them from one host thread at a time (they cache
- *     per-kernel launch attributes, and asteria_soap_refresh its internal streams, in statics).
+ *   - Entry points are not re-entrant: call them from one host thread at a time (they remember,
+ *     per device, which kernels have had their launch attributes set).
  *   - The return value reports argument / launch errors only (nothing was enqueued when it
  *     is ASTERIA_INVALID_ARG, ASTERIA_UNSUPPORTED or ASTERIA_WORKSPACE_TOO_SMALL).  Numerical
  *     outcomes are per factor and device-side (`info`, `iters`, `resid`, `lambda_max`).
@@ -256,15 +256,24 @@ asteria_status asteria_precondition(const asteria_pblock *blocks, int nblocks,
  * Cholesky factors are fp64, the application of the inverse factor and a third sweep, where
  * one is needed, use the fp32 matrix cores.  Columns of Z beyond its numerical rank come out as
  * an orthonormal completion.  Q is used as scratch during the call (transposed in place, then
- * overwritten panel by panel); where info reports a failure its content is unspecified.  The factors are worked on in two groups on two internal streams
- * (created once per device, default priority) that start after everything already enqueued on
- * `stream` and that `stream` waits for before the call's work counts as done on it.
+ * overwritten panel by panel); where info reports a failure its content is unspecified.
+ * asteria_soap_refresh enqueues everything on `stream`.  asteria_soap_refresh_overlapped deals the
+ * factors to n_aux (1..4) groups and enqueues each group as a whole on aux_streams[g], streams of
+ * the caller (default priority, none equal to `stream`): they start after everything already
+ * enqueued on `stream`, and `stream` waits for them before the call's work counts as done on it
+ * (events created and released inside the call).  A group's panel steps are a chain of small
+ * launches around a latency-bound Cholesky kernel; two chains side by side fill each other's gaps
+ * (1B-model workload: 186 ms with two streams against 205 ms on one).  n_aux = 0: the same as
+ * asteria_soap_refresh.
  *   info  device int32[nfactors] or NULL (ASTERIA_INFO_OK, or ASTERIA_INFO_NOT_PD if a column
  *         could not be normalised: an exactly zero or non-finite column, or one that three
  *         sweeps of re-orthogonalisation did not separate from the columns before it).       */
 size_t asteria_soap_refresh_workspace_bytes(const asteria_factor *f, int nfactors, size_t *min_bytes);
 asteria_status asteria_soap_refresh(const asteria_factor *f, int nfactors, int32_t *info,
                                     void *ws, size_t ws_bytes, void *stream);
+asteria_status asteria_soap_refresh_overlapped(const asteria_factor *f, int nfactors, int32_t *info,
+                                               void *ws, size_t ws_bytes, void *stream,
+                                               void *const *aux_streams, int n_aux);
 
 /* ---- SOAP step (paper Eq. 2, phi = Adam in the rotated basis) ------------------------------
  * For every block, with step_t >= 1:
@@ -285,9 +294,13 @@ asteria_status asteria_soap_step(const asteria_sblock *blocks, int nblocks,
  * asteria_profile_collect waits for the recorded events, writes one duration in milliseconds and
  * one kernel-kind code per launch, in launch order, into the HOST arrays ms / kind (capacity
  * cap), destroys the events, switches recording off and returns the number of entries written
- * (-1 if recording was not on).  kind bits: 1 = fp64 matrix cores (else fp32), 2 = A operand
- * bf16, 4 = B operand bf16, 8 = A read k-major, 16 = B read k-major.  Not thread safe; this is
- * the only process-wide state the library has.                                                 */
+ * (-1 if recording was not on).  kind codes: below 32 the fp32 / fp64 kernel, bits 1 = fp64 matrix
+ * cores (else fp32), 2 = A operand bf16, 4 = B operand bf16, 8 = A read k-major, 16 = B read
+ * k-major; 32..255 the 16-bit kernel, 32 + (2 = A operand bf16 in memory) + (4 = B operand bf16 in
+ * memory) + (64 = A split into two terms) + (128 = B split into two terms), so 224 = both operands
+ * fp32 split in two terms and 96 = A split, B one term; 256..299 the guard-free kernels (512 the
+ * statistics, 513 the 256 x 256 split x split products); 300 + NS the int8-slice kernel whose planes
+ * hold NS slices (304, 305).  Not thread safe.                                                    */
 asteria_status asteria_profile_enable(int max_launches);
 int asteria_profile_collect(float *ms, int32_t *kind, int cap);
 

@@ -110,6 +110,9 @@ def lib():
         L.asteria_soap_refresh_workspace_bytes.argtypes = [POINTER(_Factor), c_int, POINTER(c_size_t)]
         L.asteria_soap_refresh.restype = c_int
         L.asteria_soap_refresh.argtypes = [POINTER(_Factor), c_int, c_void_p, c_void_p, c_size_t, c_void_p]
+        L.asteria_soap_refresh_overlapped.restype = c_int
+        L.asteria_soap_refresh_overlapped.argtypes = [POINTER(_Factor), c_int, c_void_p, c_void_p, c_size_t,
+                                                      c_void_p, POINTER(c_void_p), c_int]
         L.asteria_soap_step_workspace_bytes.restype = c_size_t
         L.asteria_soap_step_workspace_bytes.argtypes = [POINTER(_SBlock), c_int]
         L.asteria_soap_step.restype = c_int
@@ -365,13 +368,21 @@ def soap_refresh_workspace_bytes(factors):
 
 
 def soap_refresh(factors, info: Optional[torch.Tensor] = None, ws: Optional[torch.Tensor] = None,
-                 stream=None) -> None:
-    """Q <- qr(A Q).Q for every (A, Q), in place."""
+                 stream=None, aux_streams=None) -> None:
+    """Q <- qr(A Q).Q for every (A, Q), in place.  ``aux_streams``: up to four torch streams on which
+    groups of factors are enqueued side by side (asteria_soap_refresh_overlapped)."""
     f = _as(Factors, factors)
     dev = f.items[0][0].device if f.count else None
     if ws is None:
         ws = _workspace(None, soap_refresh_workspace_bytes(f)[0], dev)
     ws = _workspace(ws, 0, dev)
+    if aux_streams:
+        aux = (c_void_p * len(aux_streams))(*[s.cuda_stream for s in aux_streams])
+        _check(lib().asteria_soap_refresh_overlapped(f.array, f.count, _ptr(info, torch.int32, f.count, "info"),
+                                                     c_void_p(ws.data_ptr()), ws.numel(), _stream(stream),
+                                                     aux, len(aux_streams)),
+               "asteria_soap_refresh_overlapped")
+        return
     _check(lib().asteria_soap_refresh(f.array, f.count, _ptr(info, torch.int32, f.count, "info"),
                                       c_void_p(ws.data_ptr()), ws.numel(), _stream(stream)),
            "asteria_soap_refresh")

@@ -38,6 +38,7 @@ namespace {
 struct ProfileState {
     bool on = false;
     int cap = 0;
+    bool open = false;            // profile_begin pushed a pair that profile_end has not closed yet
     std::vector<hipEvent_t> ev;   // 2 per recorded launch
     std::vector<int> kind;
 } g_prof;
@@ -52,13 +53,15 @@ void asteria::profile_begin(int kind, hipStream_t stream)
     g_prof.ev.push_back(a);
     g_prof.ev.push_back(b);
     g_prof.kind.push_back(kind);
+    g_prof.open = true;
     (void)hipEventRecord(a, stream);
 }
 
 void asteria::profile_end(hipStream_t stream)
 {
-    if (!g_prof.on || g_prof.ev.empty() || g_prof.ev.size() != 2 * g_prof.kind.size()) return;
-    // the end event of the launch opened last; a launch skipped by the cap opened nothing
+    // a launch skipped by the cap opened nothing: only the launch whose begin pushed a pair is closed
+    if (!g_prof.on || !g_prof.open) return;
+    g_prof.open = false;
     (void)hipEventRecord(g_prof.ev.back(), stream);
 }
 
@@ -67,6 +70,7 @@ extern "C" asteria_status asteria_profile_enable(int max_launches)
     if (max_launches <= 0 || g_prof.on) return ASTERIA_INVALID_ARG;
     g_prof.on = true;
     g_prof.cap = max_launches;
+    g_prof.open = false;
     g_prof.ev.clear();
     g_prof.kind.clear();
     return ASTERIA_OK;

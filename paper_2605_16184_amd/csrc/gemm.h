@@ -75,6 +75,23 @@ struct GemmProblem {
 void profile_begin(int kind, hipStream_t stream);
 void profile_end(hipStream_t stream);
 
+// The dynamic-LDS limit of a kernel is an attribute per device: a launcher remembers, per device,
+// that it has raised it (`done` is the launcher's own static array).
+constexpr int MAX_DEVICES = 64;
+inline hipError_t ensure_dynamic_lds(const void *kernel, size_t bytes, bool (&done)[MAX_DEVICES])
+{
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= MAX_DEVICES) return hipErrorInvalidDevice;
+    if (!done[dev]) {
+        e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+        if (e != hipSuccess) return e;
+        done[dev] = true;
+    }
+    return hipSuccess;
+}
+
 constexpr int BM = 128;
 constexpr int BN = 128;
 constexpr int NUM_XCD = 8;
@@ -720,13 +737,8 @@ inline hipError_t launch_gemm_grouped(const GemmProblem *probs, int nprobs, int 
     if (total_tiles <= 0 || nprobs <= 0) return hipSuccess;
     auto kern = gemm_grouped_kernel<TC, TA, TB, AKM, BKM>;
     constexpr size_t lds = gemm_lds_bytes<TC, TA, TB, AKM, BKM>();
-    static bool configured = false;   // attribute is per function; setting it twice is harmless
-    if (!configured) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-        configured = true;
-    }
+    static bool configured[MAX_DEVICES] = {};
+    if (hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void *>(kern), lds, configured); e != hipSuccess) return e;
     const int per_xcd = (total_tiles + NUM_XCD - 1) / NUM_XCD;
     constexpr int kind = (sizeof(TC) == 8 ? 1 : 0) | (sizeof(TA) == 2 ? 2 : 0) | (sizeof(TB) == 2 ? 4 : 0) |
                          (AKM ? 8 : 0) | (BKM ? 16 : 0);

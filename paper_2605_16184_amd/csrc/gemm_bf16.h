@@ -104,7 +104,7 @@ __device__ __forceinline__ void split4_f16(u32x4 x, u32x2 &hi, u32x2 &lo, float 
 // One operand tile (128 rows x BK) of input type TI staged as bf16 (or fp16) terms in LDS.
 template <typename TI, int NT, int BK, bool F16 = false>
 struct Bf16Stage {
-    static_assert(!F16 || (sizeof(TI) == 4 && NT == 2), "fp16 terms: fp32 source, two terms");
+    static_assert(!F16 || sizeof(TI) == 4, "fp16 terms: fp32 source");
     static constexpr int EPV = Elem<TI>::EPV;              // 8 (bf16) or 4 (fp32) elements per 16 bytes
     static constexpr int VPR = BK / EPV;
     static constexpr int NV = BM * VPR / 256;
@@ -331,13 +331,8 @@ inline hipError_t launch_gemm_bf16_grouped(const GemmProblem *probs, int nprobs,
     auto kern = gemm_bf16_grouped_kernel<TA, TB, NTA, NTB, F16>;
     constexpr size_t lds = sizeof(uint16_t) * ((NTA + NTB > 2) ? ASTERIA_SPLIT_STAGES : 2) *
                            (size_t)(Bf16Stage<TA, NTA, BK>::LDS_ELEMS + Bf16Stage<TB, NTB, BK>::LDS_ELEMS);
-    static bool configured = false;
-    if (!configured) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-        configured = true;
-    }
+    static bool configured[MAX_DEVICES] = {};
+    if (hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void *>(kern), lds, configured); e != hipSuccess) return e;
     const int per_xcd = (total_tiles + NUM_XCD - 1) / NUM_XCD;
     constexpr int kind = 32 | (sizeof(TA) == 2 ? 2 : 0) | (sizeof(TB) == 2 ? 4 : 0) | (NTA == 2 ? 64 : 0) | (NTB == 2 ? 128 : 0);
     profile_begin(kind, stream);

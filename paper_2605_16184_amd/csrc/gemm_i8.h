@@ -467,13 +467,9 @@ hipError_t launch_gemm_i8_grouped(const GemmProblem *d_probs, const I8Factor *d_
 {
     if (nprobs <= 0 || total_tiles <= 0) return hipSuccess;
     constexpr int LDS_BYTES = 2 * 2 * NSL * ((128 * 16 + 16) + (I8_TN * 16 + 16));
-    static bool configured = false;
-    if (!configured) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_i8_grouped_kernel<NSL>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
-        if (e != hipSuccess) return e;
-        configured = true;
-    }
+    static bool configured[MAX_DEVICES] = {};
+    if (hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void *>(gemm_i8_grouped_kernel<NSL>), LDS_BYTES, configured);
+        e != hipSuccess) return e;
     const int per_xcd = (2 * total_tiles + NUM_XCD - 1) / NUM_XCD;
     profile_begin(300 + NSL, stream);
     hipLaunchKernelGGL(gemm_i8_grouped_kernel<NSL>, dim3(per_xcd * NUM_XCD), dim3(256), LDS_BYTES, stream, d_probs, d_xf,

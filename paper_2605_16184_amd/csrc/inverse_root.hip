@@ -696,9 +696,11 @@ asteria_status make_plan(const asteria_root_opts *opts_in, asteria_eps_mode mode
         if (mode == ASTERIA_EPS_RELATIVE && eps) {
             float emin = eps[0];
             for (int i = 1; i < eps_count; ++i) emin = std::min(emin, eps[i]);
-            const double lo0 = (double)emin / (1.0 + (double)pl.margin + (double)emin);
+            // the device starts the interval at half of eps s (round-off in the statistics may push
+            // eigenvalues slightly below zero): the same start here and in the rule for lowp_from below
+            const double lo0 = 0.5 * (double)emin / (1.0 + (double)pl.margin + (double)emin);
             int it = 0;
-            if (emin > 0.0f) simulate_schedule(lo0, 1, root, pl.adapted, 1e-3, 0.5 * 5.96e-8 / 1e-3, o.max_iters, &it, &j);
+            if (emin > 0.0f) simulate_schedule(lo0, 1, root, pl.adapted, 1e-3, ROOT_LOWP_FLOOR, o.max_iters, &it, &j);
             else j = o.max_iters;
         } else {
             j = pl.adapted ? 2 : 4;   // the host cannot see eps / lambda_max here
@@ -982,6 +984,11 @@ asteria_status run_pass(const asteria_factor *f, const std::vector<int> &order, 
                     const dim3 sgrid((unsigned)((i8_rows(n_max) + 3) / 4), (unsigned)cnt);
                     const int abuf = l == 0 ? 1 : 0, bbuf = l == 1 ? 0 : 1, bmode = l == 2 ? 1 : 0;
                     const int lds_k = i8_slice_lds_k(n_max);
+                    {   // rows of 1900 to 2048 entries park more than the default 64 KiB of dynamic LDS
+                        static bool cfg5s[MAX_DEVICES] = {}, cfg4s[MAX_DEVICES] = {};
+                        if (ns8 == 5) ASTERIA_HIP_TRY(ensure_dynamic_lds(reinterpret_cast<const void *>(i8_slice_kernel<5>), i8_slice_lds_bytes(I8_SLICE_LDS_K), cfg5s));
+                        else ASTERIA_HIP_TRY(ensure_dynamic_lds(reinterpret_cast<const void *>(i8_slice_kernel<4>), i8_slice_lds_bytes(I8_SLICE_LDS_K), cfg4s));
+                    }
                     if (ns8 == 5) hipLaunchKernelGGL(i8_slice_kernel<5>, sgrid, dim3(256), i8_slice_lds_bytes(lds_k), stream, d_tab[1][pa][l], d_xf, d_state, 0, abuf, lds_k);
                     else hipLaunchKernelGGL(i8_slice_kernel<4>, sgrid, dim3(256), i8_slice_lds_bytes(lds_k), stream, d_tab[1][pa][l], d_xf, d_state, 0, abuf, lds_k);
                     // per factor: 4 slices where the estimate allows, else 5 (if the planes have them), else fp64

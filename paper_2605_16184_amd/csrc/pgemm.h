@@ -664,13 +664,8 @@ inline hipError_t launch_pgemm(const PlaneProblem *probs, int nprobs, int total_
 {
     if (total_tiles <= 0 || nprobs <= 0) return hipSuccess;
     auto kern = pgemm_kernel<S>;
-    static bool configured = false;
-    if (!configured) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)S::LDS_BYTES);
-        if (e != hipSuccess) return e;
-        configured = true;
-    }
+    static bool configured[MAX_DEVICES] = {};
+    if (hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void *>(kern), S::LDS_BYTES, configured); e != hipSuccess) return e;
     const int per_xcd = (total_tiles + NUM_XCD - 1) / NUM_XCD;
     profile_begin(kind, stream);
     hipLaunchKernelGGL(kern, dim3(per_xcd * NUM_XCD), dim3(S::NTHR), S::LDS_BYTES, stream, probs, nprobs,

@@ -538,37 +538,15 @@ size_t refresh_factor_bytes(int n)
            (size_t)(1 + 4 * np) * sizeof(GemmProblem) + (size_t)np * sizeof(int) + sizeof(QrFactor);
 }
 
-// Two auxiliary streams (default priority) and the events that fork them from and join them to
-// the caller's stream, created once per device and kept for the life of the process.
-constexpr int REFRESH_GROUPS = 2;   // 4 groups: 328 ms against 318 (every group brings its own chain of launches)
-struct RefreshStreams {
-    hipStream_t s[REFRESH_GROUPS];
-    hipEvent_t fork, join[REFRESH_GROUPS];
-};
-RefreshStreams *refresh_streams()
-{
-    constexpr int MAX_DEV = 64;
-    static RefreshStreams cache[MAX_DEV];
-    static bool ready[MAX_DEV] = {};
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEV) return nullptr;
-    if (!ready[dev]) {
-        RefreshStreams r;
-        if (hipEventCreateWithFlags(&r.fork, hipEventDisableTiming) != hipSuccess) return nullptr;
-        for (int g = 0; g < REFRESH_GROUPS; ++g) {
-            if (hipStreamCreateWithFlags(&r.s[g], hipStreamNonBlocking) != hipSuccess) return nullptr;
-            if (hipEventCreateWithFlags(&r.join[g], hipEventDisableTiming) != hipSuccess) return nullptr;
-        }
-        cache[dev] = r;
-        ready[dev] = true;
-    }
-    return &cache[dev];
-}
+// The factors of a call can be dealt to up to this many groups, each enqueued as a whole on an
+// auxiliary stream the caller supplies (asteria_soap_refresh_overlapped); 4 groups: 328 ms against 318
+// for 2 on the 1B-model workload (every group brings its own chain of launches).
+constexpr int REFRESH_MAX_GROUPS = 4;
 
 size_t refresh_fixed_bytes(int n_max)
 {
     const int np = (n_max + QR_PANEL - 1) / QR_PANEL;
-    return REFRESH_GROUPS * ((size_t)(5 * np + 4) * 256 + 4096);   // alignment slack of the per-panel tables, per group
+    return REFRESH_MAX_GROUPS * ((size_t)(5 * np + 4) * 256 + 4096);   // alignment slack of the per-panel tables, per group
 }
 
 }  // namespace
@@ -594,7 +572,17 @@ extern "C" size_t asteria_soap_refresh_workspace_bytes(const asteria_factor *f, 
 extern "C" asteria_status asteria_soap_refresh(const asteria_factor *f, int nfactors, int32_t *info,
                                                void *ws, size_t ws_bytes, void *stream_)
 {
+    return asteria_soap_refresh_overlapped(f, nfactors, info, ws, ws_bytes, stream_, nullptr, 0);
+}
+
+extern "C" asteria_status asteria_soap_refresh_overlapped(const asteria_factor *f, int nfactors, int32_t *info,
+                                                          void *ws, size_t ws_bytes, void *stream_,
+                                                          void *const *aux_streams, int n_aux)
+{
     if (!f || nfactors <= 0) return ASTERIA_INVALID_ARG;
+    if (n_aux < 0 || n_aux > REFRESH_MAX_GROUPS || (n_aux > 0 && !aux_streams)) return ASTERIA_INVALID_ARG;
+    for (int g = 0; g < n_aux; ++g)
+        if (!aux_streams[g] || aux_streams[g] == stream_) return ASTERIA_INVALID_ARG;
     int n_all = 0;
     for (int i = 0; i < nfactors; ++i) {
         if (!f[i].A || !f[i].X || f[i].n <= 0 || f[i].lda < f[i].n || f[i].ldx < f[i].n) return ASTERIA_INVALID_ARG;
@@ -607,12 +595,8 @@ extern "C" asteria_status asteria_soap_refresh(const asteria_factor *f, int nfac
     if (refresh_fixed_bytes(n_all) + refresh_factor_bytes(f[0].n) > ws_bytes) return ASTERIA_WORKSPACE_TOO_SMALL;
     hipStream_t stream = reinterpret_cast<hipStream_t>(stream_);
     constexpr size_t chol_lds = CHOL_LDS_BYTES;
-    static bool chol_configured = false;
-    if (!chol_configured) {
-        ASTERIA_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(panel_chol_inverse_kernel),
-                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)chol_lds));
-        chol_configured = true;
-    }
+    static bool chol_configured[MAX_DEVICES] = {};
+    ASTERIA_HIP_TRY(ensure_dynamic_lds(reinterpret_cast<const void *>(panel_chol_inverse_kernel), chol_lds, chol_configured));
 
     int first = 0;
     while (first < nfactors) {
@@ -781,25 +765,50 @@ extern "C" asteria_status asteria_soap_refresh(const asteria_factor *f, int nfac
         ASTERIA_HIP_TRY(hipGetLastError());
         return ASTERIA_OK;
         };
-        std::vector<int> grp[REFRESH_GROUPS];
-        for (int i = 0; i < cnt; ++i) grp[i % REFRESH_GROUPS].push_back(first + i);
-        RefreshStreams *rs = refresh_streams();
-        if (!rs || cnt < REFRESH_GROUPS) {
+        if (n_aux < 2 || cnt < n_aux) {
             std::vector<int> all(cnt);
             for (int i = 0; i < cnt; ++i) all[i] = first + i;
-            const asteria_status st = enqueue_group(all, stream);
+            hipStream_t s0 = (n_aux == 1) ? reinterpret_cast<hipStream_t>(aux_streams[0]) : stream;
+            hipEvent_t fork = nullptr, join = nullptr;
+            if (n_aux == 1) {
+                ASTERIA_HIP_TRY(hipEventCreateWithFlags(&fork, hipEventDisableTiming));
+                ASTERIA_HIP_TRY(hipEventCreateWithFlags(&join, hipEventDisableTiming));
+                ASTERIA_HIP_TRY(hipEventRecord(fork, stream));
+                ASTERIA_HIP_TRY(hipStreamWaitEvent(s0, fork, 0));
+            }
+            const asteria_status st = enqueue_group(all, s0);
+            if (n_aux == 1) {
+                if (st == ASTERIA_OK) {
+                    ASTERIA_HIP_TRY(hipEventRecord(join, s0));
+                    ASTERIA_HIP_TRY(hipStreamWaitEvent(stream, join, 0));
+                }
+                (void)hipEventDestroy(fork);        // released once the recorded work has passed them
+                (void)hipEventDestroy(join);
+            }
             if (st != ASTERIA_OK) return st;
         } else {
-            // fork: both auxiliary streams start after everything already enqueued on the caller's
-            // stream (the previous pass included); join: the caller's stream continues after both
-            ASTERIA_HIP_TRY(hipEventRecord(rs->fork, stream));
-            for (int g2 = 0; g2 < REFRESH_GROUPS; ++g2) {
-                ASTERIA_HIP_TRY(hipStreamWaitEvent(rs->s[g2], rs->fork, 0));
-                const asteria_status st = enqueue_group(grp[g2], rs->s[g2]);
-                if (st != ASTERIA_OK) return st;
-                ASTERIA_HIP_TRY(hipEventRecord(rs->join[g2], rs->s[g2]));
-                ASTERIA_HIP_TRY(hipStreamWaitEvent(stream, rs->join[g2], 0));
+            // fork: every auxiliary stream starts after everything already enqueued on the caller's
+            // stream (the previous pass included); join: the caller's stream continues after all of
+            // them.  The events live for this call only (destroying a recorded event releases it once
+            // the work it marks has completed).
+            std::vector<std::vector<int>> grp(n_aux);
+            for (int i = 0; i < cnt; ++i) grp[i % n_aux].push_back(first + i);
+            hipEvent_t fork = nullptr;
+            ASTERIA_HIP_TRY(hipEventCreateWithFlags(&fork, hipEventDisableTiming));
+            ASTERIA_HIP_TRY(hipEventRecord(fork, stream));
+            asteria_status st = ASTERIA_OK;
+            for (int g2 = 0; g2 < n_aux && st == ASTERIA_OK; ++g2) {
+                hipStream_t sg = reinterpret_cast<hipStream_t>(aux_streams[g2]);
+                hipEvent_t join = nullptr;
+                if (hipEventCreateWithFlags(&join, hipEventDisableTiming) != hipSuccess ||
+                    hipStreamWaitEvent(sg, fork, 0) != hipSuccess) { st = ASTERIA_HIP_ERROR; break; }
+                st = enqueue_group(grp[g2], sg);
+                if (st == ASTERIA_OK && (hipEventRecord(join, sg) != hipSuccess ||
+                                         hipStreamWaitEvent(stream, join, 0) != hipSuccess)) st = ASTERIA_HIP_ERROR;
+                (void)hipEventDestroy(join);
             }
+            (void)hipEventDestroy(fork);
+            if (st != ASTERIA_OK) return st;
         }
 
         first += cnt;

@@ -127,6 +127,16 @@ def test_precondition_and_soap_reject_bad_arguments_without_launching():
     assert lib.asteria_soap_refresh(_fac(ldx=2), 1, None, ws, 1 << 20, None) == B.INVALID_ARG
     assert lib.asteria_soap_refresh(_fac(), 1, None, None, 0, None) == B.WORKSPACE_TOO_SMALL
     assert lib.asteria_soap_refresh(_fac(), 1, None, ws, 128, None) == B.WORKSPACE_TOO_SMALL
+    # auxiliary streams: at most four, none null, none equal to the caller's stream
+    over = lib.asteria_soap_refresh_overlapped
+    s1, s2 = ctypes.c_void_p(0x5000), ctypes.c_void_p(0x6000)
+    two = (ctypes.c_void_p * 2)(s1, s2)
+    assert over(_fac(), 1, None, ws, 1 << 20, None, two, 5) == B.INVALID_ARG
+    assert over(_fac(), 1, None, ws, 1 << 20, None, None, 2) == B.INVALID_ARG
+    assert over(_fac(), 1, None, ws, 1 << 20, s1, two, 2) == B.INVALID_ARG
+    assert over(_fac(), 1, None, ws, 1 << 20, None, (ctypes.c_void_p * 2)(s1, None), 2) == B.INVALID_ARG
+    assert over(None, 1, None, ws, 1 << 20, None, two, 2) == B.INVALID_ARG
+    assert over(_fac(), 1, None, ws, 128, None, two, 2) == B.WORKSPACE_TOO_SMALL
 
 
 def test_workspace_queries_scale_with_the_batch():
@@ -160,6 +170,12 @@ def test_precision_plan_follows_eps_and_pinned_options():
     assert jla >= o.max_iters and not xta                        # absolute eps: the host cannot place the spectrum
     assert ast.inverse_root_plan(1e-6, opts=ast.RootOpts(fp64_iters=0))[::2] == (0, False)   # pinned: X follows M's tier
     assert ast.inverse_root_plan(1e-6, opts=ast.RootOpts(lowp_from=5))[1:] == (5, False)
+    # the fp64 prefix and the start of the 16-bit tier follow one rule from one start of the interval
+    # (half of eps s, as on the device): under the automatic rules they coincide for every eps
+    for e in (3e-1, 1e-2, 3e-4, 1e-4, 3e-5, 1e-5, 3e-6, 1e-6, 3e-7, 1e-7, 3e-8, 1e-8, 1e-9, 1e-10):
+        for sched in (1, 0):
+            j, l, _ = ast.inverse_root_plan(e, opts=ast.RootOpts(schedule=sched))
+            assert j == l, (e, sched, j, l)
     j64c, _, _ = ast.inverse_root_plan(1e-6, opts=ast.RootOpts(schedule=0))
     assert j64c > 2                                              # classical coefficients lift the spectrum more slowly
     # where the products of the fp64 iterations run is a separate option: default (int8 cores, up to 5

@@ -707,6 +707,28 @@ def test_soap_refresh_fixed_points_and_batch():
     assert relF(Q2, Q2in) <= 1e-4
 
 
+def test_soap_refresh_on_caller_streams_equals_the_single_stream_call():
+    # the factors of a call dealt to groups on auxiliary streams of the caller: same kernels per factor,
+    # so the result is bit-identical to the call that stays on one stream; the caller's stream waits for
+    # the auxiliary ones (the comparison below is enqueued on it right after the call)
+    sizes = [300, 129, 512, 64, 200, 257, 96]
+    As = [powerlaw_factor(n, 70 + i) for i, n in enumerate(sizes)]
+    Q0 = [W.haar(n, DEV, 71 + i) for i, n in enumerate(sizes)]
+    ref = [q.clone() for q in Q0]
+    info = torch.full((len(sizes),), -1, dtype=torch.int32, device=DEV)
+    ast.soap_refresh(list(zip(As, ref)), info=info)
+    torch.cuda.synchronize()
+    assert torch.all(info == 0)
+    for n_aux in (1, 2, 3):
+        aux = [torch.cuda.Stream() for _ in range(n_aux)]
+        Qs = [q.clone() for q in Q0]
+        info.fill_(-1)
+        ast.soap_refresh(list(zip(As, Qs)), info=info, aux_streams=aux)
+        same = [torch.equal(a, b) for a, b in zip(Qs, ref)]        # on the caller's stream, no host wait in between
+        torch.cuda.synchronize()
+        assert all(same) and torch.all(info == 0), (n_aux, same)
+
+
 def test_soap_refresh_rank_deficient_products():
     # A Q of rank < n: a numerically dependent column (m x m statistic of one m x n gradient, n < m)
     # still yields an orthogonal Q whose leading columns are the oracle's - what is left of such a
