@@ -11,12 +11,19 @@ One "step" = one pass of the whole path over that batch, inputs resident in HBM:
     preconditioner refresh") -> asteria_precondition (all blocks).
 `value` = milliseconds per full refresh (the inverse-root call over all factors);
 `ms_per_step` = the whole pass.  Prints ONE JSON line on stdout; progress goes to stderr.
+
+Further objects of the same line: `soap` (the SOAP variant on the same model, blocks <= 2048),
+`lowrank_batch` (64 blocks of 1024 x 1024, rank-32 + noise), `stress_4096` (8 blocks of 4096 x 4096,
+singular values over 8 decades, eps = 1e-8 lambda_max), `staleness` (the refresh on a second
+stream behind the steps, bounded staleness S) and `cpu_baseline` (the float64 oracle timed on the
+host cores).  `--sections` selects them.
 """
 from __future__ import annotations
 
 import argparse
 import json
 import os
+import re
 import sys
 import time
 
@@ -33,11 +40,13 @@ PEAK_I8_MFMA = 5000.0   # TOP/s, MI355X dense int8 matrix
 MEASURED_F64_MFMA_LOOP = 58.8
 PEAK_HBM = 8000.0       # GB/s
 
+ALL_SECTIONS = ("shampoo", "cpu", "soap", "lowrank", "stress", "staleness")
+
 
 def stored_traffic(key: str):
-    """HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (each scaled by a
-    plain copy of known size); the runs and their summary live under profiles/."""
-    import re
+    """HBM bytes per WORKING launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on this
+    workload (each scaled by a plain copy of known size); the runs and their summary live under
+    profiles/ (a launch that finds every factor finished moves no data and is left out)."""
     path = os.path.join(ROOT, "profiles", "gemm_grouped__llama1b_b1024_hbm_traffic.md")
     try:
         m = re.search(rf"{key}\s*=\s*([0-9.eE+-]+)", open(path).read())
@@ -58,7 +67,7 @@ def sym_gemm_flops(n: int) -> float:
 def newton_gemm_counts(iters: int, j64: int, jlow: int, xt_lowp: bool):
     """(fp32 GEMMs, fp64 GEMMs, split-fp16 GEMMs) a factor executed: iteration k < iters does
     X <- X T (except k = 0, where X_1 is written by the start kernel), and for k < iters - 1 also
-    the M-chain T^2, T^4 and T^4 M; the chain runs on the fp64 cores for k < j64 and on the fp16
+    the M-chain T^2, T^4 and T^4 M; the chain runs on the fp64 matrices for k < j64 and on the fp16
     cores (two-term split operands) for k >= jlow; X <- X T runs there too when xt_lowp, else with its iteration's
     tier (fp32 at least)."""
     g32 = g64 = g16 = 0
@@ -79,6 +88,154 @@ def newton_gemm_counts(iters: int, j64: int, jlow: int, xt_lowp: bool):
     return g32, g64, g16
 
 
+class RootRun:
+    """One inverse-root workload: statistics, roots and preconditioned gradients of a list of blocks,
+    timed stage by stage with events on the stream the library launches on, every grouped-GEMM
+    launch bracketed by the library's own events."""
+
+    def __init__(self, torch, ast, Gs, shapes, beta, eps_rel, opts, ws_gib, acc=0):
+        self.torch, self.ast = torch, ast
+        dev = Gs[0].device
+        self.shapes, self.beta, self.eps_rel, self.opts = shapes, beta, eps_rel, opts
+        self.Gs = Gs
+        self.Ls = [torch.zeros(m, m, device=dev) for m, n in shapes]
+        self.Rs = [torch.zeros(n, n, device=dev) for m, n in shapes]
+        self.XLs = [torch.empty(m, m, device=dev) for m, n in shapes]
+        self.XRs = [torch.empty(n, n, device=dev) for m, n in shapes]
+        self.Ps = [torch.empty(m, n, device=dev) for m, n in shapes]
+        self.blocks = ast.Blocks([(G, L, R, acc) for G, L, R in zip(Gs, self.Ls, self.Rs)])
+        self.factors = ast.Factors([(L, X) for L, X in zip(self.Ls, self.XLs)] + [(R, X) for R, X in zip(self.Rs, self.XRs)])
+        self.pblocks = ast.PBlocks(list(zip(self.XLs, Gs, self.XRs, self.Ps)))
+        self.nf = len(self.factors)
+        self.fsize = [m for m, n in shapes] + [n for m, n in shapes]
+        self.full, mn = ast.inverse_root_workspace_bytes(self.factors, opts)
+        self.ws_bytes = int(max(min(self.full, ws_gib * 2**30), mn, ast.precondition_workspace_bytes(self.pblocks),
+                                ast.stats_update_workspace_bytes(self.blocks)))
+        self.ws = torch.empty(self.ws_bytes, dtype=torch.uint8, device=dev)
+        self.info = torch.zeros(self.nf, dtype=torch.int32, device=dev)
+        self.iters = torch.zeros(self.nf, dtype=torch.int32, device=dev)
+        self.resid = torch.zeros(self.nf, device=dev)
+        self.plan = ast.inverse_root_plan(eps_rel, relative=True, root=4, opts=opts)
+
+    def step(self, ev=None):
+        ast = self.ast
+        if ev: ev[0].record()
+        ast.stats_update(self.blocks, self.beta, ws=self.ws)
+        if ev: ev[1].record()
+        ast.inverse_root(self.factors, self.eps_rel, relative=True, root=4, opts=self.opts, info=self.info,
+                         iters=self.iters, resid=self.resid, ws=self.ws)
+        if ev: ev[2].record()
+        ast.precondition(self.pblocks, ws=self.ws)
+        if ev: ev[3].record()
+
+    def timed(self, steps, warmup, tag):
+        torch, ast = self.torch, self.ast
+        for w in range(warmup):
+            t = time.time()
+            self.step()
+            torch.cuda.synchronize()
+            log(f"[bench] {tag} warmup {w}: {1e3 * (time.time() - t):.0f} ms")
+        j64, jlow, xt_lowp = self.plan
+        evs = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(steps)]
+        ast.profile_enable(200000)
+        flops = {"fp32": 0.0, "fp64": 0.0, "fp16": 0.0}
+        torch.cuda.synchronize()
+        t_wall = time.time()
+        for s in range(steps):
+            self.step(evs[s])
+            torch.cuda.synchronize()          # step boundary (also lets the iteration counts be read)
+            for n, c in zip(self.fsize, self.iters.cpu().numpy()):
+                g32, g64, g16 = newton_gemm_counts(int(c), j64, jlow, xt_lowp)
+                flops["fp32"] += g32 * sym_gemm_flops(n)
+                flops["fp64"] += g64 * sym_gemm_flops(n)
+                flops["fp16"] += g16 * sym_gemm_flops(n)
+            log(f"[bench] {tag} step {s}: {evs[s][0].elapsed_time(evs[s][3]):.0f} ms")
+        wall_ms = 1e3 * (time.time() - t_wall)
+        i8f = ast.profile_i8_flops()         # fp64-iteration products by where the device sent them
+        prof = ast.profile_collect(200000)
+        ms = lambda a, b: sum(e[a].elapsed_time(e[b]) for e in evs) / steps
+        return dict(stats_ms=ms(0, 1), refresh_ms=ms(1, 2), precond_ms=ms(2, 3), step_ms=ms(0, 3), wall_ms=wall_ms,
+                    prof=prof, flops=flops, i8_flops=i8f, info=self.info.cpu().numpy(), iters=self.iters.cpu().numpy())
+
+
+def gemm_rooflines(res, steps, step_ms):
+    """Per GEMM kernel of the refresh: algorithmic flops its launches executed / the sum of their
+    durations, against the published dense peak of the instruction it issues.  A launch that found
+    every factor finished (or, for the fp64 fall-back grid, every product taken by the int8 path)
+    does no work; such launches are counted and their (microsecond) durations left out of the rates."""
+    prof, flops, i8f = res["prof"], res["flops"], res["i8_flops"]
+    def split(kinds):
+        ms = [t for t, k in prof if k in kinds]
+        top = max(ms, default=0.0)
+        work = [t for t in ms if t > 0.05 * top]          # an empty grid takes ~0.1 ms, a working launch 5 - 50
+        return ms, work
+    out, shares = {}, {}
+    # fp64-iteration products: the device counted where each went
+    f64_cores, f_i8_4, f_i8_5 = i8f
+    if f64_cores + f_i8_4 + f_i8_5 == 0.0:                # int8 path off: the plan's fp64 products ran on the fp64 cores
+        f64_cores = flops["fp64"]
+    all32, w32 = split((0,))
+    all64, w64 = split((1,))
+    all16, w16 = split((224,))
+    all8, w8 = split((304, 305))
+    t32, t64, t16, t8 = (sum(x) * 1e-3 for x in (w32, w64, w16, w8))
+    if w32 and flops["fp32"] > 0:
+        tf = flops["fp32"] / t32 / 1e12
+        out["roofline_fp32"] = {"kernel": "gemm_grouped_kernel<float> (symmetric fp32-MFMA products of the root iteration)",
+                                "bound": "mfma", "achieved": round(tf, 2), "peak": PEAK_F32_MFMA, "unit": "TFLOP/s",
+                                "frac": round(tf / PEAK_F32_MFMA, 4), "traffic": stored_traffic("traffic_bytes_per_launch_fp32"),
+                                "launches": len(all32), "working_launches": len(w32),
+                                "avg_launch_ms": round(1e3 * t32 / len(w32), 4), "flops_per_launch": round(flops["fp32"] / len(w32), 1)}
+        shares["roofline_fp32"] = t32
+    if w64 and f64_cores > 0:
+        tf = f64_cores / t64 / 1e12
+        out["roofline_fp64"] = {"kernel": "gemm_grouped_kernel<double> (products of the leading root iterations on the fp64 matrix cores)",
+                                "bound": "mfma", "achieved": round(tf, 2), "peak": PEAK_F64_MFMA, "unit": "TFLOP/s",
+                                "frac": round(tf / PEAK_F64_MFMA, 4), "traffic": stored_traffic("traffic_bytes_per_launch_fp64"),
+                                "instruction_loop_tflops_measured": MEASURED_F64_MFMA_LOOP,
+                                "launches": len(all64), "working_launches": len(w64),
+                                "avg_launch_ms": round(1e3 * t64 / len(w64), 4), "flops_per_launch": round(f64_cores / len(w64), 1)}
+        shares["roofline_fp64"] = t64
+    if w16 and flops["fp16"] > 0:
+        tf = flops["fp16"] / t16 / 1e12
+        out["roofline_split_fp16"] = {
+            "kernel": "gemm_bf16_grouped_kernel<float, float, 2, 2, fp16> (X updates and the root iterations after the fp64 "
+                      "prefix: fp32 operands split in two fp16 terms, 3 fp16 MFMA passes per product)",
+            "bound": "mfma", "achieved": round(3 * tf, 2), "peak": PEAK_BF16_MFMA, "unit": "TFLOP/s (fp16 MFMA issued)",
+            "frac": round(3 * tf / PEAK_BF16_MFMA, 4),
+            "fp32_equivalent_tflops": round(tf, 2), "useful_frac": round(tf / PEAK_BF16_MFMA, 4),
+            "traffic": stored_traffic("traffic_bytes_per_launch_fp16"), "launches": len(all16), "working_launches": len(w16),
+            "avg_launch_ms": round(1e3 * t16 / len(w16), 4), "flops_per_launch": round(3 * flops["fp16"] / len(w16), 1)}
+        shares["roofline_split_fp16"] = t16
+    if w8 and f_i8_4 + f_i8_5 > 0:
+        ops = 10.0 * f_i8_4 + 15.0 * f_i8_5                # int8 MFMA passes per product: 10 with 4 slices, 15 with 5
+        useful = f_i8_4 + f_i8_5
+        out["roofline_int8_slices"] = {
+            "kernel": "gemm_i8_grouped_kernel<4 | 5 slices> (products of the fp64 iterations: each fp64 operand as its diagonal "
+                      "plus 7-bit slices, 10 | 15 int8 MFMA passes per product, exact int32 sums, fp64 assembly; the slice count "
+                      "is chosen per factor and product on the device and counted there)",
+            "bound": "mfma", "achieved": round(ops / t8 / 1e12, 2), "peak": PEAK_I8_MFMA, "unit": "TOP/s (int8 MFMA issued)",
+            "frac": round(ops / t8 / 1e12 / PEAK_I8_MFMA, 4),
+            "fp64_equivalent_tflops": round(useful / t8 / 1e12, 2), "useful_frac": round(useful / t8 / 1e12 / PEAK_I8_MFMA, 4),
+            "flops_share_4_slices": round(f_i8_4 / useful, 4), "flops_share_5_slices": round(f_i8_5 / useful, 4),
+            "flops_share_declined_to_fp64_cores": round(f64_cores / (useful + f64_cores), 6),
+            "traffic": stored_traffic("traffic_bytes_per_launch_int8"), "launches": len(all8), "working_launches": len(w8),
+            "avg_launch_ms": round(1e3 * t8 / len(w8), 4), "flops_per_launch": round(ops / len(w8), 1)}
+        shares["roofline_int8_slices"] = t8
+    out["gemm_time_share_ms_per_step"] = {k.replace("roofline_", ""): round(1e3 * v / steps, 1) for k, v in shares.items()}
+    dominant = max(shares, key=shares.get)
+    out["roofline"] = dict(out[dominant], time_share_of_step=round(1e3 * shares[dominant] / steps / step_ms, 4))
+    # the refresh as a whole: every kernel's fraction of its own peak weighted by its time, the time
+    # outside GEMM kernels (slicing, power iteration, start, hand-over, control) counting as zero
+    refresh_ms = res["refresh_ms"]
+    in_gemm = sum(1e3 * v / steps for v in shares.values())
+    weighted = sum(out[k]["frac"] * 1e3 * shares[k] / steps for k in shares) / refresh_ms
+    useful = sum(out[k].get("useful_frac", out[k]["frac"]) * 1e3 * shares[k] / steps for k in shares) / refresh_ms
+    out["refresh_mfma"] = {"issued_frac_time_weighted": round(weighted, 4), "useful_frac_time_weighted": round(useful, 4),
+                           "ms_in_gemm_kernels": round(in_gemm, 1), "ms_outside_gemm_kernels": round(refresh_ms - in_gemm, 1)}
+    return out
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -90,10 +247,10 @@ def main() -> int:
     ap.add_argument("--lowp-from", type=int, default=-1, help="first iteration on the fp16 cores with split operands (-1 = library rule)")
     ap.add_argument("--int8-slices", type=int, default=-1, help="products of the fp64 iterations: -1 = library default (int8 cores, 5 slices), 0 = fp64 cores, 4 | 5")
     ap.add_argument("--schedule", type=int, default=1, help="1 = interval-adapted coefficients, 0 = classical Newton")
+    ap.add_argument("--sections", default=",".join(ALL_SECTIONS),
+                    help="comma-separated subset of " + ",".join(ALL_SECTIONS) + " (shampoo always runs)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-soap", action="store_true", help="skip the SOAP section (blocks <= 2048)")
-    ap.add_argument("--gaussian-inputs", action="store_true",
-                    help="plain N(0, 0.01^2) gradients instead of power-law spectra (counter runs: no QR in the generator)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (reference for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -101,6 +258,9 @@ def main() -> int:
         print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
               "(no collectives or sharding in this library).", file=sys.stderr)
         return 2
+    sections = set(s for s in args.sections.split(",") if s)
+    if args.no_cpu_baseline: sections.discard("cpu")
+    if args.no_soap: sections.discard("soap")
 
     import torch
     import paper_2605_16184_amd as ast
@@ -117,44 +277,15 @@ def main() -> int:
     log(f"[bench] {len(shapes)} blocks, factors {by_factor}, {params} parameters")
 
     t0 = time.time()
-    if args.gaussian_inputs:
-        Gs = [W.gaussian_block(m, n, 0.01, dev, 3, b, dtype=torch.bfloat16) for b, (m, n) in enumerate(shapes)]
-    else:
-        Gs = W.powerlaw_blocks(shapes, dev)
-    Ls = [torch.zeros(m, m, device=dev) for m, n in shapes]
-    Rs = [torch.zeros(n, n, device=dev) for m, n in shapes]
-    XLs = [torch.empty(m, m, device=dev) for m, n in shapes]
-    XRs = [torch.empty(n, n, device=dev) for m, n in shapes]
-    Ps = [torch.empty(m, n, device=dev) for m, n in shapes]
-    torch.cuda.synchronize()
-    log(f"[bench] inputs generated on the GPU in {time.time() - t0:.1f} s; "
-        f"{torch.cuda.memory_allocated() / 2**30:.1f} GiB resident")
-
-    blocks = ast.Blocks(list(zip(Gs, Ls, Rs)))
-    factors = ast.Factors([(L, X) for L, X in zip(Ls, XLs)] + [(R, X) for R, X in zip(Rs, XRs)])
-    pblocks = ast.PBlocks(list(zip(XLs, Gs, XRs, Ps)))
-    nf = len(factors)
-    fsize = [m for m, n in shapes] + [n for m, n in shapes]
+    # the orthogonal templates are factorised by the host's LAPACK: the same inputs then serve runs
+    # under hardware counters, which keep the device's solver library out of the process
+    Gs = W.powerlaw_blocks(shapes, dev, bank=W.TemplateBank(dev, qr_on_host=True))
     opts = ast.RootOpts(fp64_iters=args.fp64_iters, schedule=args.schedule, lowp_from=args.lowp_from,
                         int8_slices=args.int8_slices)
-    full, mn = ast.inverse_root_workspace_bytes(factors, opts)
-    ws_bytes = int(max(min(full, args.ws_gib * 2**30), mn, ast.precondition_workspace_bytes(pblocks),
-                       ast.stats_update_workspace_bytes(blocks)))
-    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
-    info = torch.zeros(nf, dtype=torch.int32, device=dev)
-    iters = torch.zeros(nf, dtype=torch.int32, device=dev)
-    resid = torch.zeros(nf, device=dev)
-    log(f"[bench] workspace {ws_bytes / 2**30:.1f} GiB (single pass would need {full / 2**30:.1f} GiB)")
-
-    def one_step(ev=None):
-        if ev: ev[0].record()
-        ast.stats_update(blocks, beta, ws=ws)
-        if ev: ev[1].record()
-        ast.inverse_root(factors, eps_rel, relative=True, root=4, opts=opts, info=info, iters=iters,
-                         resid=resid, ws=ws)
-        if ev: ev[2].record()
-        ast.precondition(pblocks, ws=ws)
-        if ev: ev[3].record()
+    run = RootRun(torch, ast, Gs, shapes, beta, eps_rel, opts, args.ws_gib)
+    torch.cuda.synchronize()
+    log(f"[bench] inputs generated in {time.time() - t0:.1f} s; {torch.cuda.memory_allocated() / 2**30:.1f} GiB resident; "
+        f"workspace {run.ws_bytes / 2**30:.1f} GiB (single pass would need {run.full / 2**30:.1f} GiB)")
 
     if args.calibrate_copy:
         src = torch.empty(2**28, dtype=torch.float32, device=dev).fill_(1.0)    # 1 GiB
@@ -163,75 +294,23 @@ def main() -> int:
         torch.cuda.synchronize()
         del src, dst
 
-    for w in range(args.warmup):
-        t = time.time()
-        one_step()
-        torch.cuda.synchronize()
-        log(f"[bench] warmup {w}: {1e3 * (time.time() - t):.0f} ms")
-
-    # precision schedule the library uses for these options (for flop accounting)
-    j64, jlow, xt_lowp = ast.inverse_root_plan(eps_rel, relative=True, root=4, opts=opts)
-
-    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
-    ast.profile_enable(200000)
-    flops32 = flops64 = flops16 = 0.0
-    torch.cuda.synchronize()
-    t_wall = time.time()
-    for s in range(args.steps):
-        one_step(evs[s])
-        torch.cuda.synchronize()          # step boundary (also lets the iteration counts be read)
-        it = iters.cpu().numpy()
-        for n, c in zip(fsize, it):
-            g32, g64, g16 = newton_gemm_counts(int(c), j64, jlow, xt_lowp)
-            flops32 += g32 * sym_gemm_flops(n)
-            flops64 += g64 * sym_gemm_flops(n)
-            flops16 += g16 * sym_gemm_flops(n)
-        log(f"[bench] step {s}: {evs[s][0].elapsed_time(evs[s][3]):.0f} ms")
-    wall_ms = 1e3 * (time.time() - t_wall)
-    prof = ast.profile_collect(200000)
-
-    stats_ms = sum(e[0].elapsed_time(e[1]) for e in evs) / args.steps
-    refresh_ms = sum(e[1].elapsed_time(e[2]) for e in evs) / args.steps
-    precond_ms = sum(e[2].elapsed_time(e[3]) for e in evs) / args.steps
-    step_ms = sum(e[0].elapsed_time(e[3]) for e in evs) / args.steps
-    info_h = info.cpu().numpy()
-    it = iters.cpu().numpy()
-
-    k32 = [ms for ms, kind in prof if kind == 0]
-    k64 = [ms for ms, kind in prof if kind == 1]
-    k16 = [ms for ms, kind in prof if kind == 224]       # 16-bit cores, both operands fp32 split in two fp16 terms
-    k8 = [ms for ms, kind in prof if kind in (304, 305)]  # int8 cores: fp64 operands as diagonal + 7-bit slices
-    t8 = sum(k8) * 1e-3
-    # int8 MFMA passes per product: 10 with 4 slices, 15 with 5; the count is chosen per factor and
-    # product on the device and not reported to the host, so the issue rate below is a lower bound
-    passes8 = 10.0
-    # the fp64 launches that follow the int8 ones take the products the device-side estimate declined;
-    # when they are (nearly) empty the flops of the fp64 iterations were done on the int8 cores
-    on_i8 = t8 > 0 and sum(k64) * 1e-3 < 0.05 * t8
-    flops8 = flops64 if on_i8 else 0.0
-    if on_i8: flops64 = 0.0
-    tf8 = flops8 / t8 / 1e12 if t8 > 0 else 0.0
-    t16 = sum(k16) * 1e-3
-    tf16 = flops16 / t16 / 1e12 if t16 > 0 else 0.0
-    t32, t64 = sum(k32) * 1e-3, sum(k64) * 1e-3
-    tf32 = flops32 / t32 / 1e12 if t32 > 0 else 0.0
-    tf64 = flops64 / t64 / 1e12 if t64 > 0 else 0.0
+    res = run.timed(args.steps, args.warmup, "1.1B")
+    j64, jlow, xt_lowp = run.plan
+    stats_ms, refresh_ms, precond_ms, step_ms = res["stats_ms"], res["refresh_ms"], res["precond_ms"], res["step_ms"]
+    it, info_h = res["iters"], res["info"]
+    nf = run.nf
     stats_flops = sum(sym_gemm_flops(m) / m * n + sym_gemm_flops(n) / n * m for m, n in shapes)
     stats_bytes = sum(2 * m * n + 8 * (m * m + n * n) for m, n in shapes)
     precond_flops = sum(2.0 * m * n * (m + n) for m, n in shapes)
     precond_issued = sum(2.0 * (2.0 * m * n * n) + 3.0 * (2.0 * m * m * n) for m, n in shapes)
     precond_bytes = sum(4 * m * m + 4 * n * n + 2 * m * n + 4 * m * n for m, n in shapes)
     log(f"[bench] stats {stats_ms:.2f} ms  refresh {refresh_ms:.1f} ms  precondition {precond_ms:.2f} ms")
-    log(f"[bench] fp32 GEMM: {len(k32)} launches, {t32 * 1e3:.1f} ms total, {tf32:.1f} TFLOP/s algorithmic; "
-        f"fp64 GEMM: {len(k64)} launches, {t64 * 1e3:.1f} ms total, {tf64:.1f} TFLOP/s; "
-        f"split-fp16 GEMM: {len(k16)} launches, {t16 * 1e3:.1f} ms total, {tf16:.1f} fp32-equivalent TFLOP/s; "
-        f"int8-slice GEMM: {len(k8)} launches, {t8 * 1e3:.1f} ms total, {tf8:.1f} fp64-equivalent TFLOP/s")
     log(f"[bench] Newton iterations min/mean/max {it.min()}/{it.mean():.1f}/{it.max()}, info!=0: {(info_h != 0).sum()}")
 
     out = {
         "metric": "ms per full preconditioner refresh (1B model) + % MFMA peak; ms per step",
         "value": round(refresh_ms, 3),
-        "unit": "ms per full refresh (inverse 4th roots of all 2368 factors)",
+        "unit": f"ms per full refresh (inverse 4th roots of all {nf} factors)",
         "n_gpus": 1,
         "steps": args.steps,
         "warmup": args.warmup,
@@ -243,78 +322,127 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": "1.1B LLaMA-style model, all 2-D grads blocked at <=1024 (1184 blocks, 2368 factors), "
                                "bf16 power-law gradients, fp32 statistics, eps=1e-6*lambda_max, beta=0.95",
-                   "blocks": len(shapes), "factors": nf, "fp64_prefix_iters": j64, "fp64_prefix_products": ("fp64 cores" if args.int8_slices == 0 else
-                                                                      "int8 cores, diagonal + 7-bit slices (fp64 cores where the device-side estimate declines)"),
+                   "blocks": len(shapes), "factors": nf,
+                   "arithmetic": "fp32 storage; statistics: bf16 MFMA, fp32 sums; roots: the leading fp64 iterations as diagonal + "
+                                 "7-bit integer slices on the int8 MFMA with exact int32 sums and fp64 assembly, the rest and every "
+                                 "X update as two fp16 terms per fp32 operand on the fp16 MFMA (3 passes, fp32 sums); "
+                                 "preconditioned gradient: two bf16 terms per fp32 operand on the bf16 MFMA",
+                   "fp64_prefix_iters": j64,
+                   "fp64_prefix_products": ("fp64 cores" if args.int8_slices == 0 else
+                                            "int8 cores, diagonal + 7-bit slices (fp64 cores where the device-side estimate declines)"),
                    "fp16_split_from_iter": jlow, "x_update_on_fp16_cores": xt_lowp,
                    "schedule": "interval-adapted" if args.schedule == 1 else "classical Newton",
-                   "workspace_gib": round(ws_bytes / 2**30, 1)},
+                   "workspace_gib": round(run.ws_bytes / 2**30, 1)},
         "breakdown_ms": {"stats_update": round(stats_ms, 3), "inverse_root": round(refresh_ms, 3),
                          "precondition": round(precond_ms, 3), "step_excl_refresh": round(stats_ms + precond_ms, 3),
                          "amortised_step_pf10": round(stats_ms + precond_ms + refresh_ms / 10, 3)},
         "newton_iters": {"min": int(it.min()), "mean": round(float(it.mean()), 2), "max": int(it.max())},
         "not_converged": int((info_h != 0).sum()),
-        "wall_ms_timed_region": round(wall_ms, 1),
-        "roofline_fp32": {"kernel": "gemm_grouped_kernel<float> (symmetric fp32-MFMA products of the root iteration)",
-                          "bound": "mfma", "achieved": round(tf32, 2), "peak": PEAK_F32_MFMA, "unit": "TFLOP/s",
-                          "frac": round(tf32 / PEAK_F32_MFMA, 4), "traffic": stored_traffic("traffic_bytes_per_launch_fp32"),
-                          "launches": len(k32), "avg_launch_ms": round(1e3 * t32 / max(len(k32), 1), 4),
-                          "flops_per_launch": round(flops32 / max(len(k32), 1), 1)},
-        "roofline_fp64": {"kernel": "gemm_grouped_kernel<double> (fp64-MFMA products of the leading root iterations)",
-                          "bound": "mfma", "achieved": round(tf64, 2), "peak": PEAK_F64_MFMA, "unit": "TFLOP/s",
-                          "frac": round(tf64 / PEAK_F64_MFMA, 4), "traffic": stored_traffic("traffic_bytes_per_launch_fp64"),
-                          "instruction_loop_tflops_measured": MEASURED_F64_MFMA_LOOP,
-                          "launches": len(k64), "avg_launch_ms": round(1e3 * t64 / max(len(k64), 1), 4),
-                          "flops_per_launch": round(flops64 / max(len(k64), 1), 1)},
-        "roofline_split_fp16": {"kernel": "gemm_bf16_grouped_kernel<float, float, 2, 2, fp16> (X updates and the root iterations "
-                                          "after the fp64 prefix: fp32 operands split in two fp16 terms, 3 fp16 MFMA passes per product)",
-                                "bound": "mfma", "achieved": round(3 * tf16, 2), "peak": PEAK_BF16_MFMA,
-                                "unit": "TFLOP/s (fp16 MFMA issued)", "frac": round(3 * tf16 / PEAK_BF16_MFMA, 4),
-                                "fp32_equivalent_tflops": round(tf16, 2),
-                                "traffic": stored_traffic("traffic_bytes_per_launch_fp16"), "launches": len(k16),
-                                "avg_launch_ms": round(1e3 * t16 / max(len(k16), 1), 4),
-                                "flops_per_launch": round(3 * flops16 / max(len(k16), 1), 1)},
-        "roofline_int8_slices": {"kernel": "gemm_i8_grouped_kernel<4 | 5 slices> (products of the fp64 iterations: each fp64 operand as its "
-                                           "diagonal plus 7-bit slices, 10 | 15 int8 MFMA passes per product, exact int32 sums, fp64 assembly; "
-                                           "the slice count is chosen per factor and product on the device)",
-                                 "bound": "mfma", "achieved": round(tf8 * passes8, 2), "peak": PEAK_I8_MFMA,
-                                 "unit": "TOP/s (int8 MFMA issued: lower bound, 10 passes per product)",
-                                 "frac": round(tf8 * passes8 / PEAK_I8_MFMA, 4),
-                                 "fp64_equivalent_tflops": round(tf8, 2),
-                                 "traffic": stored_traffic("traffic_bytes_per_launch_int8"),
-                                 "launches": len(k8), "avg_launch_ms": round(1e3 * t8 / max(len(k8), 1), 4),
-                                 "flops_per_launch": round(flops8 * passes8 / max(len(k8), 1), 1)},
-        "gemm_time_share_ms_per_step": {"fp32": round(1e3 * t32 / args.steps, 1), "fp64": round(1e3 * t64 / args.steps, 1),
-                                        "split_fp16": round(1e3 * t16 / args.steps, 1), "int8_slices": round(1e3 * t8 / args.steps, 1)},
-        "roofline_stats": {"bound": "hbm", "achieved": round(stats_bytes / stats_ms / 1e6, 1), "peak": PEAK_HBM,
-                           "unit": "GB/s", "frac": round(stats_bytes / stats_ms / 1e6 / PEAK_HBM, 4),
-                           "tflops": round(stats_flops / stats_ms / 1e9, 1)},
-        # bf16 gradients: U^T = X_R G^T issues 2 bf16 MFMA passes (X_R split), P = X_L U issues 3 (both split)
-        "roofline_precondition": {"bound": "mfma", "achieved": round(precond_issued / precond_ms / 1e9, 1),
-                                  "peak": PEAK_BF16_MFMA, "unit": "TFLOP/s (bf16 MFMA issued)",
-                                  "frac": round(precond_issued / precond_ms / 1e9 / PEAK_BF16_MFMA, 4),
-                                  "fp32_equivalent_tflops": round(precond_flops / precond_ms / 1e9, 1),
-                                  "gbps": round(precond_bytes / precond_ms / 1e6, 1)},
+        "wall_ms_timed_region": round(res["wall_ms"], 1),
     }
+    out.update(gemm_rooflines(res, args.steps, step_ms))
+    out["roofline_stats"] = {"bound": "hbm", "achieved": round(stats_bytes / stats_ms / 1e6, 1), "peak": PEAK_HBM,
+                             "unit": "GB/s", "frac": round(stats_bytes / stats_ms / 1e6 / PEAK_HBM, 4),
+                             "tflops": round(stats_flops / stats_ms / 1e9, 1)}
+    # bf16 gradients: U^T = X_R G^T issues 2 bf16 MFMA passes (X_R split), P = X_L U issues 3 (both split)
+    out["roofline_precondition"] = {"bound": "mfma", "achieved": round(precond_issued / precond_ms / 1e9, 1),
+                                    "peak": PEAK_BF16_MFMA, "unit": "TFLOP/s (bf16 MFMA issued)",
+                                    "frac": round(precond_issued / precond_ms / 1e9 / PEAK_BF16_MFMA, 4),
+                                    "fp32_equivalent_tflops": round(precond_flops / precond_ms / 1e9, 1),
+                                    "gbps": round(precond_bytes / precond_ms / 1e6, 1)}
+    log(f"[bench] refresh: {out['refresh_mfma']}")
 
-    # `roofline` = the kernel that takes the largest share of the timed region
-    shares = {"roofline_fp32": t32, "roofline_fp64": t64, "roofline_split_fp16": t16, "roofline_int8_slices": t8}
-    if not k32:
-        del out["roofline_fp32"], shares["roofline_fp32"]     # the default precision rules launch no fp32 product
-    if not k8:
-        del out["roofline_int8_slices"], shares["roofline_int8_slices"]
-    elif on_i8:
-        del out["roofline_fp64"], shares["roofline_fp64"]     # its launches were empty: every product passed the estimate
-    dominant = max(shares, key=shares.get)
-    out["roofline"] = dict(out[dominant], time_share_of_step=round(1e3 * shares[dominant] / args.steps / step_ms, 4))
-
-    if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(fsize, Ls, Rs, shapes, eps_rel)
-    if not args.no_soap:
-        del blocks, factors, pblocks, Gs, Ls, Rs, XLs, XRs, Ps, ws
-        torch.cuda.empty_cache()
+    if "cpu" in sections:
+        out["cpu_baseline"] = cpu_baseline(run.fsize, run.Ls, run.Rs, shapes, eps_rel)
+    if "staleness" in sections:
+        out["staleness"] = staleness_section(args, torch, ast, run, stats_ms + precond_ms, refresh_ms)
+    del run, Gs, res
+    torch.cuda.empty_cache()
+    if "soap" in sections:
         out["soap"] = soap_section(args, torch, ast, W, dev)
+        torch.cuda.empty_cache()
+    if "lowrank" in sections:
+        out["lowrank_batch"] = lowrank_section(args, torch, ast, W, dev)
+        torch.cuda.empty_cache()
+    if "stress" in sections:
+        out["stress_4096"] = stress_section(args, torch, ast, W, dev)
     print(json.dumps(out), flush=True)
     return 0
+
+
+def staleness_section(args, torch, ast, run, step_ms, refresh_ms):
+    """The one part of the paper's runtime that applies to a single large-HBM GPU (its Sec. III-D
+    staleness barrier, swept in Sec. IV-C over S in {1, 2, 3, 5, 10}): the refresh runs on a second
+    stream behind the training steps and its roots are published under a version counter; a step may
+    use roots that are at most S refresh periods old and otherwise waits for the refresh in flight.
+    Mock loop: `pf` = 10 steps (statistics + preconditioned gradient of every block, the per-step work
+    of the method) per refresh period, three periods per setting; reported is the time the steps of one
+    period spend waiting for a refresh ("exposed" refresh time) and the period's wall time."""
+    from paper_2605_16184_amd.staleness import RefreshPipeline
+    pf, periods = 10, 3
+    out = {"pf": pf, "periods_timed": periods, "step_ms": round(step_ms, 3), "refresh_ms": round(refresh_ms, 3),
+           "synchronous_period_ms": round(pf * step_ms + refresh_ms, 1), "sweep": []}
+    pipe = RefreshPipeline(torch, ast, run, pf=pf)
+    for S in (0, 1, 2, 3, 5, 10):
+        r = pipe.run(periods, S)
+        out["sweep"].append({"S": S, "period_ms": round(r["period_ms"], 1), "exposed_refresh_ms": round(r["exposed_ms"], 1),
+                             "max_step_ms": round(r["max_step_ms"], 1), "median_step_ms": round(r["median_step_ms"], 1),
+                             "max_version_age_used": r["max_age"], "not_converged": r["not_converged"]})
+        log(f"[bench] staleness S={S}: period {r['period_ms']:.1f} ms, exposed refresh {r['exposed_ms']:.1f} ms, longest step "
+            f"{r['max_step_ms']:.1f} ms (median {r['median_step_ms']:.1f}), oldest roots used {r['max_age']} periods")
+    del pipe
+    return out
+
+
+def lowrank_section(args, torch, ast, W, dev):
+    """Batch of 64 independent 1024 x 1024 blocks, bf16 gradients = rank-32 Gaussian factors x 0.01 plus
+    N(0, 1e-4^2) noise, fp32 statistics, beta = 0.95, eps = 1e-6 lambda_max: stats + roots + precondition."""
+    nb, n = 64, 1024
+    shapes = [(n, n)] * nb
+    Gs = [W.lowrank_block(n, n, dev, 2, b) for b in range(nb)]
+    run = RootRun(torch, ast, Gs, shapes, 0.95, 1e-6, ast.RootOpts(), args.ws_gib)
+    steps = max(2, args.steps)
+    res = run.timed(steps, 1, "64x1024")
+    it = res["iters"]
+    r = gemm_rooflines(res, steps, res["step_ms"])
+    log(f"[bench] 64x1024 low-rank: stats {res['stats_ms']:.2f} ms, roots {res['refresh_ms']:.1f} ms, precondition {res['precond_ms']:.2f} ms")
+    return {"workload": "64 blocks 1024x1024, rank-32 + noise bf16 gradients, eps=1e-6*lambda_max", "blocks": nb, "factors": 2 * nb,
+            "stats_update_ms": round(res["stats_ms"], 3), "inverse_root_ms": round(res["refresh_ms"], 3),
+            "precondition_ms": round(res["precond_ms"], 3),
+            "newton_iters": {"min": int(it.min()), "mean": round(float(it.mean()), 2), "max": int(it.max())},
+            "not_converged": int((res["info"] != 0).sum()),
+            "precision_plan": {"fp64_prefix_iters": run.plan[0], "fp16_split_from_iter": run.plan[1]},
+            "refresh_mfma": r["refresh_mfma"], "gemm_time_share_ms_per_step": r["gemm_time_share_ms_per_step"]}
+
+
+def stress_section(args, torch, ast, W, dev):
+    """Ill-conditioned stress: 8 blocks of 4096 x 4096, bf16 gradients with singular values log-spaced over
+    1e0 .. 1e-8, fp32 statistics accumulated in fp64 (eps = 1e-8 lambda_max needs lambda_min > -eps / 2),
+    inverse 4th roots and preconditioned gradients; reports the Newton iteration count and the precision plan
+    (the accuracy against the oracle is what tests/test_configs_gpu.py grades)."""
+    nb, n = 8, 4096
+    shapes = [(n, n)] * nb
+    Gs = []
+    for b in range(nb):
+        U, V = W.haar(n, dev, 500 + b, dtype=torch.float64), W.haar(n, dev, 600 + b, dtype=torch.float64)
+        Gs.append(((U * W.logspaced_sigma(n, 8.0, dev)) @ V.T).to(torch.bfloat16))
+        del U, V
+    run = RootRun(torch, ast, Gs, shapes, 0.95, 1e-8, ast.RootOpts(), args.ws_gib, acc=1)
+    res = run.timed(2, 1, "8x4096")
+    it = res["iters"]
+    r = gemm_rooflines(res, 2, res["step_ms"])
+    log(f"[bench] 8x4096 stress: stats (fp64 accumulation) {res['stats_ms']:.1f} ms, roots {res['refresh_ms']:.1f} ms, "
+        f"precondition {res['precond_ms']:.1f} ms, iterations {it.min()}..{it.max()}")
+    return {"workload": "8 blocks 4096x4096, bf16 gradients with singular values log-spaced over 8 decades, "
+                        "fp32 statistics (fp64 accumulation), eps=1e-8*lambda_max", "blocks": nb, "factors": 2 * nb,
+            "stats_update_fp64_acc_ms": round(res["stats_ms"], 3),
+            "stats_update_fp64_tflops": round(2 * nb * sym_gemm_flops(n) / res["stats_ms"] / 1e9, 1),
+            "inverse_root_ms": round(res["refresh_ms"], 3), "precondition_ms": round(res["precond_ms"], 3),
+            "newton_iters": {"min": int(it.min()), "mean": round(float(it.mean()), 2), "max": int(it.max())},
+            "not_converged": int((res["info"] != 0).sum()),
+            "precision_plan": {"fp64_prefix_iters": run.plan[0], "fp16_split_from_iter": run.plan[1]},
+            "refresh_mfma": r["refresh_mfma"], "gemm_time_share_ms_per_step": r["gemm_time_share_ms_per_step"],
+            "roofline_int8_slices": r.get("roofline_int8_slices")}
 
 
 def soap_section(args, torch, ast, W, dev):
@@ -325,7 +453,7 @@ def soap_section(args, torch, ast, W, dev):
     shapes = W.block_shapes(W.llama_1b_matrices(), 2048)
     if args.max_blocks:
         shapes = shapes[:: max(1, len(shapes) // args.max_blocks)][: args.max_blocks]
-    bank = W.TemplateBank(dev)
+    bank = W.TemplateBank(dev, qr_on_host=True)
     bases = [(bank.get(m, b), bank.get(n, b + 3)) for b, (m, n) in enumerate(shapes)]
     nsets = 2                                   # two gradient sets, used alternately
     Gsets = [[W.soap_gradient(U, V, t, dev, b) for b, (U, V) in enumerate(bases)] for t in range(nsets)]
@@ -359,14 +487,16 @@ def soap_section(args, torch, ast, W, dev):
         ev[t][1].record()
         ast.stats_update(blocks[t % nsets], beta, ws=ws)
         ev[t][2].record()
-    r0, r1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    r0, r1, r2 = (torch.cuda.Event(enable_timing=True) for _ in range(3))
     r0.record()
     ast.soap_refresh(factors, info=info, ws=ws, aux_streams=aux)
     r1.record()
+    ast.soap_refresh(factors, info=info, ws=ws)            # the same refresh on the caller's stream alone
+    r2.record()
     torch.cuda.synchronize()
     step_ms = sum(e[0].elapsed_time(e[1]) for e in ev) / args.steps
     stats_ms = sum(e[1].elapsed_time(e[2]) for e in ev) / args.steps
-    refresh_ms = r0.elapsed_time(r1)
+    refresh_ms, refresh1_ms = r0.elapsed_time(r1), r1.elapsed_time(r2)
     # sanity of the refreshed bases (fp64 check of two factors, largest first, and of up to six
     # factors that the refresh reported as failed)
     def orth_of(Q):
@@ -386,13 +516,13 @@ def soap_section(args, torch, ast, W, dev):
     step_issued = sum((2.0 + 3.0) * 2.0 * m * n * n + (3.0 + 3.0) * 2.0 * m * m * n for m, n in shapes)
     refresh_flops = sum((2.0 + 8.0 / 3.0) * float(n) ** 3 for n in fsize)
     adam_bytes = sum(24.0 * m * n for m, n in shapes)
-    log(f"[bench] soap: step {step_ms:.1f} ms + stats {stats_ms:.1f} ms, refresh {refresh_ms:.1f} ms, "
-        f"orthogonality {orth:.1e}, info!=0: {int((info != 0).sum())}")
+    log(f"[bench] soap: step {step_ms:.1f} ms + stats {stats_ms:.1f} ms, refresh {refresh_ms:.1f} ms "
+        f"({refresh1_ms:.1f} ms on one stream), orthogonality {orth:.1e}, info!=0: {int((info != 0).sum())}")
     return {"workload": "same 1.1B model, blocks <=2048: 318 blocks, 636 factors; shared singular bases, "
                         "+-30% sigma jitter, 10% dense noise; beta1=0.9, beta2=0.95",
             "blocks": len(shapes), "factors": len(factors),
             "soap_step_ms": round(step_ms, 3), "stats_update_ms": round(stats_ms, 3),
-            "refresh_ms": round(refresh_ms, 3),
+            "refresh_ms": round(refresh_ms, 3), "refresh_single_stream_ms": round(refresh1_ms, 3),
             "amortised_step_pf10": round(step_ms + stats_ms + refresh_ms / 10, 3),
             "soap_step_tflops": round(step_flops / step_ms / 1e9, 1),
             # bf16 gradients: G Q_R issues 2 bf16 MFMA passes, the other three products 3 each (split operands)

@@ -303,6 +303,10 @@ asteria_status asteria_soap_step(const asteria_sblock *blocks, int nblocks,
  * hold NS slices (304, 305).  Not thread safe.                                                    */
 asteria_status asteria_profile_enable(int max_launches);
 int asteria_profile_collect(float *ms, int32_t *kind, int cap);
+/* Algorithmic flops (n^2 (n + 1) per symmetric product) of the products of the fp64 iterations since
+ * the last asteria_profile_enable, by where the device-side decision sent them: out3[0] fp64 matrix
+ * cores, out3[1] int8 cores with 4 slices, out3[2] with 5.  Waits for the device.               */
+asteria_status asteria_profile_i8_flops(double *out3);
 
 #ifdef __cplusplus
 }

@@ -28,4 +28,5 @@ from .binding import (  # noqa: F401
     SBlocks,
     profile_enable,
     profile_collect,
+    profile_i8_flops,
 )

@@ -122,6 +122,8 @@ def lib():
         L.asteria_profile_enable.argtypes = [c_int]
         L.asteria_profile_collect.restype = c_int
         L.asteria_profile_collect.argtypes = [POINTER(c_float), POINTER(c_int32), c_int]
+        L.asteria_profile_i8_flops.restype = c_int
+        L.asteria_profile_i8_flops.argtypes = [POINTER(ctypes.c_double)]
         _lib = L
     return _lib
 
@@ -416,3 +418,11 @@ def profile_collect(cap: int = 4096):
     if n < 0:
         raise AsteriaError(INVALID_ARG, "asteria_profile_collect")
     return [(ms[i], kind[i]) for i in range(n)]
+
+
+def profile_i8_flops():
+    """Algorithmic flops of the fp64 iterations' products since profile_enable, by where they ran:
+    (fp64 cores, int8 cores with 4 slices, int8 cores with 5 slices).  Waits for the device."""
+    out = (ctypes.c_double * 3)()
+    _check(lib().asteria_profile_i8_flops(out), "asteria_profile_i8_flops")
+    return tuple(out)

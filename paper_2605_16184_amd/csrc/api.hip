@@ -44,6 +44,23 @@ struct ProfileState {
 } g_prof;
 }  // namespace
 
+static __device__ double g_i8_flops[3];
+static double *g_i8_flops_ptr[asteria::MAX_DEVICES];   // device address of g_i8_flops, per device
+
+static double *i8_flops_ptr()
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= asteria::MAX_DEVICES) return nullptr;
+    if (!g_i8_flops_ptr[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(g_i8_flops)) != hipSuccess) return nullptr;
+        g_i8_flops_ptr[dev] = reinterpret_cast<double *>(p);
+    }
+    return g_i8_flops_ptr[dev];
+}
+
+double *asteria::profile_i8_counters() { return g_prof.on ? i8_flops_ptr() : nullptr; }
+
 void asteria::profile_begin(int kind, hipStream_t stream)
 {
     if (!g_prof.on || (int)g_prof.kind.size() >= g_prof.cap) return;
@@ -68,6 +85,9 @@ void asteria::profile_end(hipStream_t stream)
 extern "C" asteria_status asteria_profile_enable(int max_launches)
 {
     if (max_launches <= 0 || g_prof.on) return ASTERIA_INVALID_ARG;
+    if (double *c = i8_flops_ptr()) {
+        if (hipMemset(c, 0, 3 * sizeof(double)) != hipSuccess) return ASTERIA_HIP_ERROR;   // synchronous: measurement aid
+    }
     g_prof.on = true;
     g_prof.cap = max_launches;
     g_prof.open = false;
@@ -93,4 +113,13 @@ extern "C" int asteria_profile_collect(float *ms, int32_t *kind, int cap)
     g_prof.ev.clear();
     g_prof.kind.clear();
     return out;
+}
+
+extern "C" asteria_status asteria_profile_i8_flops(double *out3)
+{
+    if (!out3) return ASTERIA_INVALID_ARG;
+    double *c = i8_flops_ptr();
+    if (!c) return ASTERIA_HIP_ERROR;
+    ASTERIA_HIP_TRY(hipMemcpy(out3, c, 3 * sizeof(double), hipMemcpyDeviceToHost));   // waits for the device
+    return ASTERIA_OK;
 }

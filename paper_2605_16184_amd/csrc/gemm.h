@@ -74,6 +74,9 @@ struct GemmProblem {
 // Measurement aid (see asteria_profile_enable): bracket a launch with HIP events on its stream.
 void profile_begin(int kind, hipStream_t stream);
 void profile_end(hipStream_t stream);
+// While recording: device array of 3 doubles in which the int8 decision kernel adds up the algorithmic
+// flops of the products it sends to the fp64 cores [0], to 4 slices [1] and to 5 slices [2]; else null.
+double *profile_i8_counters();
 
 // The dynamic-LDS limit of a kernel is an attribute per device: a launcher remembers, per device,
 // that it has raised it (`done` is the launcher's own static array).

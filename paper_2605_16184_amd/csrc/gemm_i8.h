@@ -215,7 +215,8 @@ constexpr float I8_THETA = 2e-5f;
 // `scal` points at the factor's (lo, hi, g) of the current iteration: the interval that holds the
 // spectrum of the current M and the g of the current T = a I - g M.
 __global__ void i8_gate_kernel(I8Factor *__restrict__ xf, int nf, const float *__restrict__ scal, int scal_stride_bytes,
-                               int ns_min, int ns_max, int abuf, int bbuf, int bmode, float theta)
+                               int ns_min, int ns_max, int abuf, int bbuf, int bmode, float theta,
+                               const int *__restrict__ state, double *counters)
 {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= nf) return;
@@ -237,6 +238,8 @@ __global__ void i8_gate_kernel(I8Factor *__restrict__ xf, int nf, const float *_
         if (est <= allowed && allowed > 0.0f) gsel = ns;
     }
     X.gate = gsel;
+    if (counters && state[i] == 0)      // measurement aid: where the running factors' products go
+        atomicAdd(&counters[gsel == 0 ? 0 : gsel - 3], (double)X.n * (double)X.n * (double)(X.n + 1));
     // buffer 0 is cut anew before every product; buffer 1 holds T from the first product of an
     // iteration to the last (B mode 1)
     X.rmax[0] = 0u; X.dmax[0] = 0u;

@@ -994,7 +994,7 @@ asteria_status run_pass(const asteria_factor *f, const std::vector<int> &order, 
                     // per factor: 4 slices where the estimate allows, else 5 (if the planes have them), else fp64
                     hipLaunchKernelGGL(i8_gate_kernel, dim3(ctl_blocks), dim3(128), 0, stream, d_xf, cnt, &d_fs[0].lo_cur,
                                        (int)sizeof(FactorScal), 4, ns8, abuf, bbuf, bmode,
-                                       I8_THETA * 2.0f / (float)std::max(2, j64));
+                                       I8_THETA * 2.0f / (float)std::max(2, j64), d_state, profile_i8_counters());
                     ASTERIA_HIP_TRY(hipGetLastError());
                     if (ns8 == 5) ASTERIA_HIP_TRY((launch_gemm_i8_grouped<5>(d_tab[1][pa][l], d_xf, cnt, tri_total, d_state, abuf, bbuf, bmode, stream)));
                     else ASTERIA_HIP_TRY((launch_gemm_i8_grouped<4>(d_tab[1][pa][l], d_xf, cnt, tri_total, d_state, abuf, bbuf, bmode, stream)));

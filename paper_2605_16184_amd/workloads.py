@@ -70,10 +70,15 @@ def census(blocks: Sequence[Tuple[int, int]]):
 
 # --------------------------------------------------------------------------------- matrices
 
-def haar(n: int, device, *key: int, dtype=torch.float32) -> torch.Tensor:
-    """Orthogonal matrix from the QR of a Gaussian, column signs fixed by diag(R) > 0."""
+def haar(n: int, device, *key: int, dtype=torch.float32, qr_on_host: bool = False) -> torch.Tensor:
+    """Orthogonal matrix from the QR of a Gaussian, column signs fixed by diag(R) > 0.  With
+    ``qr_on_host`` the Gaussian is drawn on the device as usual but factorised by the host's LAPACK
+    (runs under hardware counters keep the device's solver library out of the process)."""
     g = _gen(device, 7, n, *key)
     a = torch.randn(n, n, generator=g, device=device, dtype=dtype)
+    if qr_on_host:
+        q, r = torch.linalg.qr(a.cpu())
+        return (q * torch.sign(torch.diagonal(r))).contiguous().to(device)
     q, r = torch.linalg.qr(a)
     return (q * torch.sign(torch.diagonal(r))).contiguous()
 
@@ -124,14 +129,14 @@ class TemplateBank:
     """A few Haar bases per dimension, reused across blocks (per-block permutation and signs
     make the blocks distinct) so that a 1B-model batch is generated in seconds."""
 
-    def __init__(self, device, per_dim: int = 8, dtype=torch.float32):
-        self.device, self.per_dim, self.dtype = device, per_dim, dtype
+    def __init__(self, device, per_dim: int = 8, dtype=torch.float32, qr_on_host: bool = False):
+        self.device, self.per_dim, self.dtype, self.qr_on_host = device, per_dim, dtype, qr_on_host
         self._bank = {}
 
     def get(self, n: int, idx: int) -> torch.Tensor:
         k = (n, idx % self.per_dim)
         if k not in self._bank:
-            self._bank[k] = haar(n, self.device, idx % self.per_dim, dtype=self.dtype)
+            self._bank[k] = haar(n, self.device, idx % self.per_dim, dtype=self.dtype, qr_on_host=self.qr_on_host)
         return self._bank[k]
 
 
