@@ -251,6 +251,9 @@ def main() -> int:
                     help="comma-separated subset of " + ",".join(ALL_SECTIONS) + " (shampoo always runs)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-soap", action="store_true", help="skip the SOAP section (blocks <= 2048)")
+    ap.add_argument("--save-inputs", default="", help="generate the headline workload's gradients, write them to this file and exit")
+    ap.add_argument("--load-inputs", default="", help="read the gradients from a file written by --save-inputs instead of generating "
+                    "them (runs under hardware counters: the process then launches no generator kernels)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (reference for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -279,7 +282,19 @@ def main() -> int:
     t0 = time.time()
     # the orthogonal templates are factorised by the host's LAPACK: the same inputs then serve runs
     # under hardware counters, which keep the device's solver library out of the process
-    Gs = W.powerlaw_blocks(shapes, dev, bank=W.TemplateBank(dev, qr_on_host=True))
+    if args.load_inputs:
+        flat = torch.load(args.load_inputs, weights_only=True)["G"].to(dev)
+        Gs, off = [], 0
+        for m, n in shapes:
+            Gs.append(flat[off:off + m * n].view(m, n))
+            off += m * n
+        assert off == flat.numel(), "the file holds another batch"
+    else:
+        Gs = W.powerlaw_blocks(shapes, dev, bank=W.TemplateBank(dev, qr_on_host=True))
+    if args.save_inputs:
+        torch.save({"G": torch.cat([g.reshape(-1) for g in Gs]).cpu()}, args.save_inputs)
+        log(f"[bench] gradients written to {args.save_inputs}")
+        return 0
     opts = ast.RootOpts(fp64_iters=args.fp64_iters, schedule=args.schedule, lowp_from=args.lowp_from,
                         int8_slices=args.int8_slices)
     run = RootRun(torch, ast, Gs, shapes, beta, eps_rel, opts, args.ws_gib)
@@ -352,6 +367,7 @@ def main() -> int:
                                     "gbps": round(precond_bytes / precond_ms / 1e6, 1)}
     log(f"[bench] refresh: {out['refresh_mfma']}")
 
+    out["packed_statistics"] = packed_section(args, torch, ast, run)
     if "cpu" in sections:
         out["cpu_baseline"] = cpu_baseline(run.fsize, run.Ls, run.Rs, shapes, eps_rel)
     if "staleness" in sections:
@@ -368,6 +384,39 @@ def main() -> int:
         out["stress_4096"] = stress_section(args, torch, ast, W, dev)
     print(json.dumps(out), flush=True)
     return 0
+
+
+def packed_section(args, torch, ast, run):
+    """The same statistics kept in packed lower tiles (the paper's packed triangular SPD storage, Sec. III-E):
+    asteria_stats_update reads and writes only the stored tiles, asteria_inverse_root reads them directly."""
+    dev = run.Gs[0].device
+    shapes = run.shapes
+    Lp = [torch.zeros(ast.packed_elems(m), device=dev) for m, n in shapes]
+    Rp = [torch.zeros(ast.packed_elems(n), device=dev) for m, n in shapes]
+    blocks = ast.Blocks([(G, L, R, 0, 1) for G, L, R in zip(run.Gs, Lp, Rp)])
+    factors = ast.Factors([(L, X, 1) for L, X in zip(Lp, run.XLs)] + [(R, X, 1) for R, X in zip(Rp, run.XRs)])
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(2 * args.steps + 2)]
+    ast.stats_update(blocks, run.beta, ws=run.ws)                     # warm-up, and statistics to take roots of
+    for s in range(args.steps):
+        ev[2 * s].record()
+        ast.stats_update(blocks, run.beta, ws=run.ws)
+        ev[2 * s + 1].record()
+    ev[-2].record()
+    ast.inverse_root(factors, run.eps_rel, relative=True, root=4, opts=run.opts, info=run.info, iters=run.iters, ws=run.ws)
+    ev[-1].record()
+    torch.cuda.synchronize()
+    stats_ms = sum(ev[2 * s].elapsed_time(ev[2 * s + 1]) for s in range(args.steps)) / args.steps
+    refresh_ms = ev[-2].elapsed_time(ev[-1])
+    stored = sum(4 * (ast.packed_elems(m) + ast.packed_elems(n)) for m, n in shapes)
+    full = sum(4 * (m * m + n * n) for m, n in shapes)
+    moved = sum(2 * m * n for m, n in shapes) + 2 * stored
+    log(f"[bench] packed statistics: stats {stats_ms:.2f} ms ({moved / stats_ms / 1e6:.0f} GB/s), refresh {refresh_ms:.1f} ms, "
+        f"{stored / 2**30:.2f} GiB instead of {full / 2**30:.2f} GiB")
+    return {"stats_update_ms": round(stats_ms, 3), "inverse_root_ms": round(refresh_ms, 3),
+            "statistics_gib": round(stored / 2**30, 3), "statistics_full_storage_gib": round(full / 2**30, 3),
+            "roofline_stats": {"bound": "hbm", "achieved": round(moved / stats_ms / 1e6, 1), "peak": PEAK_HBM, "unit": "GB/s",
+                               "frac": round(moved / stats_ms / 1e6 / PEAK_HBM, 4), "bytes": moved},
+            "not_converged": int((run.info != 0).sum())}
 
 
 def staleness_section(args, torch, ast, run, step_ms, refresh_ms):

@@ -68,6 +68,19 @@ typedef enum asteria_acc {
     ASTERIA_ACC_F64 = 1  /* fp64 sums and EMA on the fp64 matrix cores, one rounding to the fp32 L, R */
 } asteria_acc;
 
+/* storage of a symmetric fp32 matrix (statistics L, R; any matrix given to asteria_sym_pack) */
+typedef enum asteria_layout {
+    ASTERIA_LAYOUT_FULL = 0,   /* dense row-major n x n with a leading dimension, both triangles valid          */
+    ASTERIA_LAYOUT_PACKED = 1  /* packed lower tiles (the paper's packed triangular SPD storage, Sec. III-E):
+                                  the 128 x 128 tiles on and below the diagonal, tile (ti, tj), tj <= ti, at
+                                  tile index ti (ti + 1) / 2 + tj, each tile dense row-major; diagonal tiles
+                                  hold both of their triangles; the last tile row / column of an n that is no
+                                  multiple of 128 is padded (padding never read).  asteria_packed_elems(n)
+                                  floats, 16-byte aligned base, no leading dimension: 56 % of the full storage
+                                  at n = 1024.  Tiles, not a packed triangle of rows, so that every row piece
+                                  stays a whole number of aligned 16-byte vectors                               */
+} asteria_layout;
+
 /* per-factor numerical outcome written to the device `info` arrays */
 enum {
     ASTERIA_INFO_OK = 0,
@@ -84,6 +97,7 @@ typedef struct asteria_block {
     int32_t ldg, ldl, ldr;
     int32_t g_dtype; /* asteria_dtype */
     int32_t acc;     /* asteria_acc (0 = fp32 accumulation) */
+    int32_t lr_layout; /* asteria_layout of L and R (0 = full; packed: ldl, ldr unused) */
 } asteria_block;
 
 /* One symmetric factor and the matrix produced from it. */
@@ -93,6 +107,7 @@ typedef struct asteria_factor {
                        eigenbasis Q (asteria_soap_refresh, in place), leading dimension ldx    */
     int32_t n;
     int32_t lda, ldx;
+    int32_t a_layout; /* asteria_layout of A (asteria_inverse_root only; packed: lda unused).  X is always full */
 } asteria_factor;
 
 /* One block of the preconditioned update (asteria_precondition). */
@@ -172,6 +187,24 @@ const char *asteria_status_string(asteria_status s);
 size_t asteria_stats_update_workspace_bytes(const asteria_block *blocks, int nblocks);
 asteria_status asteria_stats_update(const asteria_block *blocks, int nblocks, float beta,
                                     void *ws, size_t ws_bytes, void *stream);
+
+/* ---- packed triangular storage utilities (paper Sec. III-E) ---------------------------------
+ * asteria_stats_update keeps L and R of a block in packed lower tiles when the block says so (it then
+ * reads and writes 4 (m^2 + n^2) (1 + 1/T) bytes instead of 8 (m^2 + n^2), T = n / 128 tiles per
+ * row), and asteria_inverse_root reads such statistics directly.  The roots and eigenbases stay full:
+ * they are operands of the products of asteria_precondition / asteria_soap_step, whose loaders read
+ * row pieces along k.  For storing them (or anything symmetric) off the hot path:
+ *   asteria_sym_pack    packed <- lower tiles of full        asteria_sym_unpack  full <- packed, both triangles
+ * items: host array; full: device n x n fp32, leading dimension ld; packed: device,
+ * asteria_packed_elems(n) floats, 16-byte aligned.  Errors: NULL pointers, n <= 0, ld < n -> INVALID_ARG. */
+typedef struct asteria_sympair {
+    float *full;
+    float *packed;
+    int32_t n, ld;
+} asteria_sympair;
+size_t asteria_packed_elems(int n);
+asteria_status asteria_sym_pack(const asteria_sympair *items, int nitems, void *stream);
+asteria_status asteria_sym_unpack(const asteria_sympair *items, int nitems, void *stream);
 
 /* ---- inverse p-th roots (paper Eq. 1, Sec. III-B) ------------------------------------------
  * For every factor: X = ((A + A^T)/2 + eps I)^(-1/root), root in {2, 4} (4 = Eq. 1), by a

@@ -16,6 +16,7 @@ _LIB_PATH = os.path.join(_HERE, "libasteria.so")
 OK, INVALID_ARG, UNSUPPORTED, WORKSPACE_TOO_SMALL, HIP_ERROR, EXCEEDS_STATIC_SCRATCH = range(6)
 F32, BF16 = 0, 1
 ACC_F32, ACC_F64 = 0, 1
+LAYOUT_FULL, LAYOUT_PACKED = 0, 1
 EPS_RELATIVE, EPS_ABSOLUTE = 0, 1
 INFO_OK, INFO_NOT_CONVERGED, INFO_NOT_PD = 0, 1, 2
 
@@ -28,11 +29,16 @@ class AsteriaError(RuntimeError):
 
 class _Block(Structure):
     _fields_ = [("G", c_void_p), ("L", c_void_p), ("R", c_void_p), ("m", c_int32), ("n", c_int32),
-                ("ldg", c_int32), ("ldl", c_int32), ("ldr", c_int32), ("g_dtype", c_int32), ("acc", c_int32)]
+                ("ldg", c_int32), ("ldl", c_int32), ("ldr", c_int32), ("g_dtype", c_int32), ("acc", c_int32), ("lr_layout", c_int32)]
 
 
 class _Factor(Structure):
-    _fields_ = [("A", c_void_p), ("X", c_void_p), ("n", c_int32), ("lda", c_int32), ("ldx", c_int32)]
+    _fields_ = [("A", c_void_p), ("X", c_void_p), ("n", c_int32), ("lda", c_int32), ("ldx", c_int32),
+                ("a_layout", c_int32)]
+
+
+class _SymPair(Structure):
+    _fields_ = [("full", c_void_p), ("packed", c_void_p), ("n", c_int32), ("ld", c_int32)]
 
 
 class _PBlock(Structure):
@@ -122,6 +128,11 @@ def lib():
         L.asteria_profile_enable.argtypes = [c_int]
         L.asteria_profile_collect.restype = c_int
         L.asteria_profile_collect.argtypes = [POINTER(c_float), POINTER(c_int32), c_int]
+        L.asteria_packed_elems.restype = c_size_t
+        L.asteria_packed_elems.argtypes = [c_int]
+        for fn in (L.asteria_sym_pack, L.asteria_sym_unpack):
+            fn.restype = c_int
+            fn.argtypes = [POINTER(_SymPair), c_int, c_void_p]
         L.asteria_profile_i8_flops.restype = c_int
         L.asteria_profile_i8_flops.argtypes = [POINTER(ctypes.c_double)]
         _lib = L
@@ -160,6 +171,19 @@ def _mat(t: Optional[torch.Tensor], name: str, dtype=None):
     return t.data_ptr(), t.shape[0], t.shape[1], ld
 
 
+def packed_elems(n: int) -> int:
+    """Floats a symmetric n x n matrix occupies in packed lower tiles."""
+    return lib().asteria_packed_elems(int(n))
+
+
+def _packed(t: Optional[torch.Tensor], n: int, name: str):
+    if t is None:
+        return None
+    if not t.is_cuda or t.dtype != torch.float32 or t.dim() != 1 or not t.is_contiguous() or t.numel() < packed_elems(n):
+        raise ValueError(f"{name}: need a flat contiguous fp32 GPU tensor of packed_elems({n}) = {packed_elems(n)} elements")
+    return t.data_ptr()
+
+
 class _Batch:
     """A host descriptor array plus the tensors it points to (kept alive)."""
     ctype = None
@@ -180,10 +204,15 @@ class Blocks(_Batch):
     or ACC_F64."""
     ctype = _Block
 
-    def _fill(self, d, G, L, R, acc=ACC_F32):
+    def _fill(self, d, G, L, R, acc=ACC_F32, layout=LAYOUT_FULL):
         d.acc = int(acc)
+        d.lr_layout = int(layout)
         d.G, d.m, d.n, d.ldg = _mat(G, "G")
         d.g_dtype = _dtype_code(G)
+        if layout == LAYOUT_PACKED:       # L, R: flat fp32 tensors of packed_elems(m), packed_elems(n)
+            d.L, d.R = _packed(L, d.m, "L"), _packed(R, d.n, "R")
+            d.ldl = d.ldr = 0
+            return
         d.L, _, _, d.ldl = _mat(L, "L", torch.float32)
         d.R, _, _, d.ldr = _mat(R, "R", torch.float32)
         if L is not None and tuple(L.shape) != (d.m, d.m) or R is not None and tuple(R.shape) != (d.n, d.n):
@@ -194,9 +223,15 @@ class Factors(_Batch):
     """[(A, X)] for inverse_root (X written) and soap_refresh (X = Q, in place)."""
     ctype = _Factor
 
-    def _fill(self, d, A, X):
-        d.A, n, n2, d.lda = _mat(A, "A", torch.float32)
+    def _fill(self, d, A, X, a_layout=LAYOUT_FULL):
         d.X, xn, xn2, d.ldx = _mat(X, "X", torch.float32)
+        d.a_layout = int(a_layout)
+        if a_layout == LAYOUT_PACKED:     # A: flat fp32 tensor of packed_elems(n)
+            if xn != xn2:
+                raise ValueError("X must be square")
+            d.A, d.lda, d.n = _packed(A, xn, "A"), 0, xn
+            return
+        d.A, n, n2, d.lda = _mat(A, "A", torch.float32)
         if n != n2 or (xn, xn2) != (n, n):
             raise ValueError("A and X must be square and of equal size")
         d.n = n
@@ -426,3 +461,24 @@ def profile_i8_flops():
     out = (ctypes.c_double * 3)()
     _check(lib().asteria_profile_i8_flops(out), "asteria_profile_i8_flops")
     return tuple(out)
+
+
+def _sympairs(items):
+    arr = (_SymPair * max(len(items), 1))()
+    for k, (full, packed) in enumerate(items):
+        arr[k].full, n, n2, arr[k].ld = _mat(full, "full", torch.float32)
+        if n != n2:
+            raise ValueError("full: need a square matrix")
+        arr[k].n = n
+        arr[k].packed = _packed(packed, n, "packed")
+    return arr
+
+
+def sym_pack(items, stream=None) -> None:
+    """packed <- lower tiles of full, for every (full, packed)."""
+    _check(lib().asteria_sym_pack(_sympairs(items), len(items), _stream(stream)), "asteria_sym_pack")
+
+
+def sym_unpack(items, stream=None) -> None:
+    """full <- packed (both triangles), for every (full, packed)."""
+    _check(lib().asteria_sym_unpack(_sympairs(items), len(items), _stream(stream)), "asteria_sym_unpack")

@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libasteria.so")
-SOURCES = ["api.hip", "stats.hip", "inverse_root.hip", "precondition.hip", "soap.hip"]
+SOURCES = ["api.hip", "stats.hip", "inverse_root.hip", "precondition.hip", "soap.hip", "packed.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

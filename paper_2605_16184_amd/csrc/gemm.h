@@ -45,8 +45,23 @@ enum : int {
     GEMM_EPI_ROOT = 2,   // C2 = ep_a * I - ep_g * C ; partial[tile] = sum (C - I)^2
     GEMM_C_BF16 = 4,     // C is stored as bf16 (fp32 compute only)
     GEMM_STORE_T = 8,    // C is stored transposed: element (row, col) at C[col * ldc + row] (no beta, not symmetric)
-    GEMM_C_F32 = 16      // C is stored as fp32 (fp64 compute only): read, combined in fp64, rounded once
+    GEMM_C_F32 = 16,     // C is stored as fp32 (fp64 compute only): read, combined in fp64, rounded once
+    GEMM_C_PACKED = 64   // symmetric C in packed lower-tile storage (see packed_off); ldc unused, nothing above the diagonal tiles
 };
+
+// Packed lower-tile storage of a symmetric n x n fp32 matrix: the 128 x 128 tiles on and below the
+// diagonal, tile (ti, tj), tj <= ti, at tile index ti (ti + 1) / 2 + tj, each tile dense row-major
+// (diagonal tiles hold both of their triangles; the last tile row / column of a ragged n is padded,
+// the padding is never read).  Every tile row is 512 bytes, so all accesses stay 16-byte aligned.
+constexpr int PACK_T = 128;
+__host__ __device__ inline size_t packed_tiles(int n) { const size_t t = (size_t)((n + PACK_T - 1) / PACK_T); return t * (t + 1) / 2; }
+__host__ __device__ inline size_t packed_elems(int n) { return packed_tiles(n) * PACK_T * PACK_T; }
+// offset of element (row, col); the tile of (row, col) must be on or below the diagonal
+__host__ __device__ inline size_t packed_off(int row, int col)
+{
+    const size_t ti = (size_t)(row / PACK_T), tj = (size_t)(col / PACK_T);
+    return ((ti * (ti + 1) / 2 + tj) * PACK_T + (size_t)(row % PACK_T)) * PACK_T + (size_t)(col % PACK_T);
+}
 
 struct GemmProblem {
     const void *A;
@@ -469,9 +484,10 @@ __device__ __forceinline__ void gemm_epilogue(const GemmProblem &P, typename MM:
     // Fast fp32 stores need a full, aligned tile: in the 32 x 32 MFMA layout a lane owns 4
     // consecutive rows of one column, so the mirrored group C[col][row .. row + 3] is one aligned
     // 16-byte store (a scalar mirror store touches 64 different cache lines per instruction).
+    const bool packed = (flags & GEMM_C_PACKED) != 0;
     bool vec_c = false;
     if constexpr (sizeof(TC) == 4)
-        vec_c = rowsA == BM && rowsB == BN && !(flags & GEMM_C_BF16) && (ldc & 3) == 0 &&
+        vec_c = !packed && rowsA == BM && rowsB == BN && !(flags & GEMM_C_BF16) && (ldc & 3) == 0 &&
                 (reinterpret_cast<uintptr_t>(C) & 15u) == 0 &&
                 (!root || (P.C3 == nullptr && (ldc2 & 3) == 0 && (reinterpret_cast<uintptr_t>(C2) & 15u) == 0));
 #pragma unroll
@@ -534,10 +550,14 @@ __device__ __forceinline__ void gemm_epilogue(const GemmProblem &P, typename MM:
                 if (row >= M || col >= N) continue;
                 if (sym && row < col) continue;   // the mirror of (col, row) covers it
                 TC val = alpha * acc[i][j][v];
-                const size_t at = (flags & GEMM_STORE_T) ? (size_t)col * ldc + row : (size_t)row * ldc + col;
+                const size_t at = packed ? packed_off(row, col)
+                                         : ((flags & GEMM_STORE_T) ? (size_t)col * ldc + row : (size_t)row * ldc + col);
                 if (beta != (TC)0) val += beta * load_c<TC>(C, at, flags);
                 store_c<TC>(C, at, val, flags);
-                if (sym && row != col) store_c<TC>(C, (size_t)col * ldc + row, val, flags);
+                if (sym && row != col) {
+                    if (!packed) store_c<TC>(C, (size_t)col * ldc + row, val, flags);
+                    else if (row / PACK_T == col / PACK_T) store_c<TC>(C, packed_off(col, row), val, flags);   // inside a diagonal tile
+                }
                 if (root) {
                     const TC d = (row == col) ? (TC)1 : (TC)0;
                     const TC t2 = ep_a * d - ep_g * val;

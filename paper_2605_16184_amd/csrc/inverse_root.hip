@@ -74,8 +74,10 @@ struct FactorDev {
     int pm_blocks;
     int pm_block_start;
     float eps_in;
-    int pad_;
+    int a_packed;       // A lies in packed lower tiles (gemm.h, packed_off): lda unused
+    float *pm_tile;     // packed A: per lower tile 2 x 128 partial products of the mat-vec and (sum a^2, trace part)
 };
+constexpr int PM_TILE_WORDS = 2 * PACK_T + 2;   // floats per tile in pm_tile
 
 struct FactorScal {
     float lam;       // lambda_max estimate
@@ -150,6 +152,7 @@ __global__ __launch_bounds__(256) void pm_matvec_kernel(const FactorDev *fd, con
     const int lo = blockIdx.y;
     if (fs[lo].pm_done) return;
     const FactorDev &F = fd[lo];
+    if (F.a_packed) return;                  // packed statistics take the tile kernels below
     const int blk = (int)blockIdx.x;
     if (blk >= F.pm_blocks) return;
     const int n = F.n, lda = F.lda;
@@ -195,6 +198,98 @@ __global__ __launch_bounds__(256) void pm_matvec_kernel(const FactorDev *fd, con
         if (first)
             F.pm_partial2[blk] = make_float2(red[2][0] + red[2][1] + red[2][2] + red[2][3],
                                              red[3][0] + red[3][1] + red[3][2] + red[3][3]);
+    }
+}
+
+// ---- the same mat-vec for statistics in packed lower tiles -----------------------------------
+// One workgroup per stored tile (ti, tj), tj <= ti: it serves both the rows of block ti (T v_tj) and,
+// off the diagonal, the rows of block tj (T^T v_ti), so every element is read once.  The partial
+// products go to the factor's pm_tile array and are summed in a fixed order by pm_packed_reduce_kernel
+// (no atomics: the result does not depend on the order in which workgroups finish).
+__global__ __launch_bounds__(256) void pm_packed_tile_kernel(const FactorDev *fd, const FactorScal *fs, int src, int first)
+{
+    const int f = blockIdx.y;
+    if (fs[f].pm_done) return;
+    const FactorDev &F = fd[f];
+    if (!F.a_packed || (int)blockIdx.x >= F.ntri) return;
+    int ti, tj;
+    tri_decode((int)blockIdx.x, ti, tj);
+    const int n = F.n;
+    const float *__restrict__ tile = F.A + (size_t)blockIdx.x * PACK_T * PACK_T;
+    const float *__restrict__ v = F.pv[src];
+    float *out = F.pm_tile + (size_t)blockIdx.x * PM_TILE_WORDS;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int c0 = tj * PACK_T + 2 * lane, r0 = ti * PACK_T;
+    __shared__ float colp[4][PACK_T];
+    __shared__ float red[2][4];
+    // this lane's two columns of the tile: entries of v_tj, zero beyond n
+    const float vj0 = c0 < n ? v[c0] : 0.0f, vj1 = c0 + 1 < n ? v[c0 + 1] : 0.0f;
+    float cs0 = 0.0f, cs1 = 0.0f, saa = 0.0f, str = 0.0f;
+    for (int rr = 0; rr < PACK_T / 4; ++rr) {
+        const int r = wave * (PACK_T / 4) + rr, gr = r0 + r;
+        float2 a = *reinterpret_cast<const float2 *>(tile + (size_t)r * PACK_T + 2 * lane);
+        if (gr >= n) { a.x = 0.0f; a.y = 0.0f; }               // padding of a ragged last tile row is undefined
+        if (c0 >= n) a.x = 0.0f;
+        if (c0 + 1 >= n) a.y = 0.0f;
+        float s = wave_sum(a.x * vj0 + a.y * vj1);
+        if (lane == 0) out[r] = s;                              // row part: (T v_tj)[r]
+        const float vi = gr < n ? v[gr] : 0.0f;
+        cs0 += a.x * vi; cs1 += a.y * vi;                       // column part: (T^T v_ti)[c]
+        if (first) {
+            saa += a.x * a.x + a.y * a.y;
+            if (ti == tj) { if (gr == c0) str += a.x; if (gr == c0 + 1) str += a.y; }
+        }
+    }
+    colp[wave][2 * lane] = cs0; colp[wave][2 * lane + 1] = cs1;
+    if (first) {
+        saa = wave_sum(saa); str = wave_sum(str);
+        if (lane == 0) { red[0][wave] = saa; red[1][wave] = str; }
+    }
+    __syncthreads();
+    if (threadIdx.x < PACK_T)
+        out[PACK_T + threadIdx.x] = colp[0][threadIdx.x] + colp[1][threadIdx.x] + colp[2][threadIdx.x] + colp[3][threadIdx.x];
+    if (first && threadIdx.x == 0) {
+        // an off-diagonal tile stands for its mirror image too
+        const float w = ti == tj ? 1.0f : 2.0f;
+        out[2 * PACK_T] = w * (red[0][0] + red[0][1] + red[0][2] + red[0][3]);
+        out[2 * PACK_T + 1] = red[1][0] + red[1][1] + red[1][2] + red[1][3];
+    }
+}
+
+// y[rows of block I] = sum over tj <= I of the row parts of tile (I, tj) + sum over ti > I of the column
+// parts of tile (ti, I), scaled by 1 / ||v||; per block the same partial sums pm_matvec_kernel leaves.
+__global__ __launch_bounds__(PACK_T) void pm_packed_reduce_kernel(const FactorDev *fd, const FactorScal *fs, int src, int first)
+{
+    const int f = blockIdx.y;
+    if (fs[f].pm_done) return;
+    const FactorDev &F = fd[f];
+    const int T = (F.n + PACK_T - 1) / PACK_T, I = (int)blockIdx.x;
+    if (!F.a_packed || I >= T) return;
+    const int i = threadIdx.x, row = I * PACK_T + i;
+    const float inv = fs[f].inv_norm;
+    const float *__restrict__ v = F.pv[src];
+    float s = 0.0f, saa = 0.0f, str = 0.0f;
+    for (int tj = 0; tj <= I; ++tj) {
+        const float *p = F.pm_tile + (size_t)(I * (I + 1) / 2 + tj) * PM_TILE_WORDS;
+        s += p[i];
+        if (first && i == 0) { saa += p[2 * PACK_T]; str += p[2 * PACK_T + 1]; }
+    }
+    for (int ti = I + 1; ti < T; ++ti) s += F.pm_tile[(size_t)(ti * (ti + 1) / 2 + I) * PM_TILE_WORDS + PACK_T + i];
+    s *= inv;
+    float syy = 0.0f, syv = 0.0f;
+    if (row < F.n) {
+        F.pv[src ^ 1][row] = s;
+        syy = s * s;
+        syv = s * (v[row] * inv);
+    }
+    __shared__ float red[2][PACK_T / 64];
+    syy = wave_sum(syy); syv = wave_sum(syv);
+    if ((i & 63) == 0) { red[0][i >> 6] = syy; red[1][i >> 6] = syv; }
+    __syncthreads();
+    if (i == 0) {
+        F.pm_partial[I] = make_float2(red[0][0] + red[0][1], red[1][0] + red[1][1]);
+        // the off-diagonal tiles of the block rows below this one were counted there (weight 2)
+        if (first) F.pm_partial2[I] = make_float2(saa, str);
     }
 }
 
@@ -343,7 +438,11 @@ __global__ __launch_bounds__(256) void root_init_kernel(const FactorDev *fd, con
     // Full tiles with 16-byte aligned rows: 64 x 64 sub-tiles, 16-byte global loads, and 32-byte
     // (fp64) or 16-byte (fp32) stores of 4 consecutive elements per thread; LDS rows of 65 words
     // keep both the row-wise and the transposed reads free of bank conflicts.
-    const bool aligned = ti * BM + BM <= n && (lda & 3) == 0 && (reinterpret_cast<uintptr_t>(F.A) & 15u) == 0;
+    // Packed lower tiles: tile (ti, tj) is stored once, dense with 128 floats per row, and stands for
+    // its mirror image; the value at (r, c) is the stored one (nothing to symmetrise).
+    const bool packed = F.a_packed != 0;
+    const float *Ap = packed ? F.A + (size_t)lt * PACK_T * PACK_T : nullptr;
+    const bool aligned = ti * BM + BM <= n && (packed || ((lda & 3) == 0 && (reinterpret_cast<uintptr_t>(F.A) & 15u) == 0));
     if (aligned) {
         __shared__ float Pw[64][65], Qw[64][65];
         const int g = threadIdx.x & 15, rw = threadIdx.x >> 4;     // 16 column groups of 4 x 16 rows
@@ -354,10 +453,13 @@ __global__ __launch_bounds__(256) void root_init_kernel(const FactorDev *fd, con
             const bool diag_sub = (ti == tj && si == sj);
             __syncthreads();
             for (int rr = rw; rr < 64; rr += 16) {
-                const float4 pv = *reinterpret_cast<const float4 *>(F.A + (size_t)(r0 + rr) * lda + c0 + 4 * g);
+                const float4 pv = packed ? *reinterpret_cast<const float4 *>(Ap + (size_t)(si * 64 + rr) * PACK_T + sj * 64 + 4 * g)
+                                         : *reinterpret_cast<const float4 *>(F.A + (size_t)(r0 + rr) * lda + c0 + 4 * g);
                 Pw[rr][4 * g] = pv.x; Pw[rr][4 * g + 1] = pv.y; Pw[rr][4 * g + 2] = pv.z; Pw[rr][4 * g + 3] = pv.w;
-                const float4 qv = *reinterpret_cast<const float4 *>(F.A + (size_t)(c0 + rr) * lda + r0 + 4 * g);
-                Qw[rr][4 * g] = qv.x; Qw[rr][4 * g + 1] = qv.y; Qw[rr][4 * g + 2] = qv.z; Qw[rr][4 * g + 3] = qv.w;
+                if (!packed) {
+                    const float4 qv = *reinterpret_cast<const float4 *>(F.A + (size_t)(c0 + rr) * lda + r0 + 4 * g);
+                    Qw[rr][4 * g] = qv.x; Qw[rr][4 * g + 1] = qv.y; Qw[rr][4 * g + 2] = qv.z; Qw[rr][4 * g + 3] = qv.w;
+                }
             }
             __syncthreads();
             for (int rr = rw; rr < 64; rr += 16) {
@@ -368,7 +470,7 @@ __global__ __launch_bounds__(256) void root_init_kernel(const FactorDev *fd, con
                     float xv[4];
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
-                        const TC av = (TC)0.5 * ((TC)Pw[rr][4 * g + e] + (TC)Qw[4 * g + e][rr]);
+                        const TC av = packed ? (TC)Pw[rr][4 * g + e] : (TC)0.5 * ((TC)Pw[rr][4 * g + e] + (TC)Qw[4 * g + e][rr]);
                         const TC d = (r == c + e) ? (TC)1 : (TC)0;
                         mv[e] = s * (av + eps * d);
                         tv[e] = ca * d - cg * mv[e];
@@ -387,7 +489,7 @@ __global__ __launch_bounds__(256) void root_init_kernel(const FactorDev *fd, con
                     float xv[4];
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
-                        const TC av = (TC)0.5 * ((TC)Pw[4 * g + e][rr] + (TC)Qw[rr][4 * g + e]);
+                        const TC av = packed ? (TC)Pw[4 * g + e][rr] : (TC)0.5 * ((TC)Pw[4 * g + e][rr] + (TC)Qw[rr][4 * g + e]);
                         mv[e] = s * av;                              // off the diagonal: no eps, d = 0
                         tv[e] = -cg * mv[e];
                         xv[e] = (float)(xs * tv[e]);
@@ -414,9 +516,9 @@ __global__ __launch_bounds__(256) void root_init_kernel(const FactorDev *fd, con
         __syncthreads();
         for (int rr = ty; rr < 32; rr += 8) {
             const int r = r0 + rr, c = c0 + tx;
-            Ps[rr][tx] = (r < n && c < n) ? F.A[(size_t)r * lda + c] : 0.0f;
+            Ps[rr][tx] = (r < n && c < n) ? (packed ? Ap[(size_t)(si * 32 + rr) * PACK_T + sj * 32 + tx] : F.A[(size_t)r * lda + c]) : 0.0f;
             const int r2 = c0 + rr, c2 = r0 + tx;                // sub-tile (sj, si) of tile (tj, ti)
-            Qs[rr][tx] = (r2 < n && c2 < n) ? F.A[(size_t)r2 * lda + c2] : 0.0f;
+            if (!packed) Qs[rr][tx] = (r2 < n && c2 < n) ? F.A[(size_t)r2 * lda + c2] : 0.0f;
         }
         __syncthreads();
         const bool diag_sub = (ti == tj && si == sj);
@@ -425,7 +527,7 @@ __global__ __launch_bounds__(256) void root_init_kernel(const FactorDev *fd, con
             {
                 const int r = r0 + rr, c = c0 + tx;
                 if (r < n && c < n) {
-                    const TC av = (TC)0.5 * ((TC)Ps[rr][tx] + (TC)Qs[tx][rr]);
+                    const TC av = packed ? (TC)Ps[rr][tx] : (TC)0.5 * ((TC)Ps[rr][tx] + (TC)Qs[tx][rr]);
                     const TC d = (r == c) ? (TC)1 : (TC)0;
                     const TC m = s * (av + eps * d);
                     const TC t = ca * d - cg * m;
@@ -441,7 +543,7 @@ __global__ __launch_bounds__(256) void root_init_kernel(const FactorDev *fd, con
             if (!diag_sub) {
                 const int r2 = c0 + rr, c2 = r0 + tx;
                 if (r2 < n && c2 < n) {
-                    const TC av = (TC)0.5 * ((TC)Ps[tx][rr] + (TC)Qs[rr][tx]);
+                    const TC av = packed ? (TC)Ps[tx][rr] : (TC)0.5 * ((TC)Ps[tx][rr] + (TC)Qs[rr][tx]);
                     const TC m = s * av;                          // off the diagonal: no eps, d = 0
                     const TC t = -cg * m;
                     M[(size_t)r2 * ldm + c2] = m;
@@ -667,7 +769,8 @@ size_t factor_small_bytes(int n)
 {
     const int pmb = (n + PM_ROWS - 1) / PM_ROWS;
     return 2 * Carver::need((size_t)ld4(n), sizeof(float)) + 2 * Carver::need((size_t)pmb, sizeof(float2)) +
-           Carver::need(2 * (size_t)tri_tiles(n), sizeof(float)) + sizeof(FactorDev) + sizeof(FactorScal) +
+           Carver::need(2 * (size_t)tri_tiles(n), sizeof(float)) + Carver::need((size_t)tri_tiles(n) * PM_TILE_WORDS, sizeof(float)) +
+           sizeof(FactorDev) + sizeof(FactorScal) +
            2 * sizeof(int) + 14 * sizeof(GemmProblem);
 }
 
@@ -743,7 +846,10 @@ asteria_status validate(const asteria_factor *f, int nf, int root, const float *
     for (int i = 0; i < eps_count; ++i)
         if (!(eps[i] >= 0.0f) || !(eps[i] < 3.0e38f)) return ASTERIA_INVALID_ARG;
     for (int i = 0; i < nf; ++i) {
-        if (!f[i].A || !f[i].X || f[i].n <= 0 || f[i].lda < f[i].n || f[i].ldx < f[i].n) return ASTERIA_INVALID_ARG;
+        if (!f[i].A || !f[i].X || f[i].n <= 0 || f[i].ldx < f[i].n) return ASTERIA_INVALID_ARG;
+        if (f[i].a_layout == ASTERIA_LAYOUT_FULL) { if (f[i].lda < f[i].n) return ASTERIA_INVALID_ARG; }
+        else if (f[i].a_layout == ASTERIA_LAYOUT_PACKED) { if (reinterpret_cast<uintptr_t>(f[i].A) & 15u) return ASTERIA_INVALID_ARG; }
+        else return ASTERIA_INVALID_ARG;
     }
     return ASTERIA_OK;
 }
@@ -835,7 +941,8 @@ asteria_status run_pass(const asteria_factor *f, const std::vector<int> &order, 
 
     std::vector<FactorDev> fd(cnt);
     std::vector<int> sq(cnt);
-    int tri_total = 0, sq_total = 0, pm_total = 0, pm_blocks_max = 0;
+    int tri_total = 0, sq_total = 0, pm_total = 0, pm_blocks_max = 0, tri_max = 0;
+    bool any_packed = false, any_full = false;
     int n_max = 0;
     double a_min = 1.0;
     for (int i = 0; i < cnt; ++i) {
@@ -850,9 +957,12 @@ asteria_status run_pass(const asteria_factor *f, const std::vector<int> &order, 
         F.tile_start = tri_total; tri_total += F.ntri;
         const int tpr = (n + BM - 1) / BM;
         sq[i] = sq_total; sq_total += tpr * tpr;
-        F.pm_blocks = (n + PM_ROWS - 1) / PM_ROWS;
+        F.a_packed = a.a_layout == ASTERIA_LAYOUT_PACKED ? 1 : 0;
+        // partial sums of the mat-vec: per block of PM_ROWS rows, or per block of 128 rows for packed tiles
+        F.pm_blocks = F.a_packed ? (n + PACK_T - 1) / PACK_T : (n + PM_ROWS - 1) / PM_ROWS;
         F.pm_block_start = pm_total; pm_total += F.pm_blocks;
-        pm_blocks_max = std::max(pm_blocks_max, F.pm_blocks);
+        if (F.a_packed) { any_packed = true; tri_max = std::max(tri_max, F.ntri); }
+        else { any_full = true; pm_blocks_max = std::max(pm_blocks_max, F.pm_blocks); }
         F.eps_in = eps[eps_count == 1 ? 0 : order[first + i]];
         if (mode == ASTERIA_EPS_RELATIVE) {
             const double er = (double)F.eps_in;
@@ -860,8 +970,9 @@ asteria_status run_pass(const asteria_factor *f, const std::vector<int> &order, 
         }
         F.pv[0] = cv.take<float>(ld4(n));
         F.pv[1] = cv.take<float>(ld4(n));
-        F.pm_partial = cv.take<float2>(F.pm_blocks);
-        F.pm_partial2 = cv.take<float2>(F.pm_blocks);
+        F.pm_partial = cv.take<float2>((n + PM_ROWS - 1) / PM_ROWS);
+        F.pm_partial2 = cv.take<float2>((n + PM_ROWS - 1) / PM_ROWS);
+        F.pm_tile = cv.take<float>((size_t)F.ntri * PM_TILE_WORDS);
         F.partial = cv.take<float>(2 * (size_t)F.ntri);
     }
     // factors too large for exact int32 sums (never reached by the 16384 limit of the other tiers'
@@ -932,7 +1043,12 @@ asteria_status run_pass(const asteria_factor *f, const std::vector<int> &order, 
     hipLaunchKernelGGL(pm_init_kernel, dim3(cnt), dim3(256), 0, stream, d_fd, d_fs);
     const int ctl_blocks = (cnt + 127) / 128;
     for (int it = 0; it < pl.power_iters; ++it) {
-        hipLaunchKernelGGL(pm_matvec_kernel, dim3(pm_blocks_max, cnt), dim3(256), 0, stream, d_fd, d_fs, cnt, it & 1, it == 0 ? 1 : 0);
+        if (any_full)
+            hipLaunchKernelGGL(pm_matvec_kernel, dim3(pm_blocks_max, cnt), dim3(256), 0, stream, d_fd, d_fs, cnt, it & 1, it == 0 ? 1 : 0);
+        if (any_packed) {
+            hipLaunchKernelGGL(pm_packed_tile_kernel, dim3(tri_max, cnt), dim3(256), 0, stream, d_fd, d_fs, it & 1, it == 0 ? 1 : 0);
+            hipLaunchKernelGGL(pm_packed_reduce_kernel, dim3((n_max + PACK_T - 1) / PACK_T, cnt), dim3(PACK_T), 0, stream, d_fd, d_fs, it & 1, it == 0 ? 1 : 0);
+        }
         hipLaunchKernelGGL(pm_control_kernel, dim3(ctl_blocks), dim3(128), 0, stream, d_fd, d_fs, cnt, pl.power_tol, it == 0 ? 1 : 0);
     }
     // 2. scaling, start

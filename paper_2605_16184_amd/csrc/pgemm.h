@@ -225,13 +225,15 @@ __device__ __forceinline__ void pg_store_split(uint16_t *base, int row, int col,
 
 // One finished row piece of 8 values at (grow, gcol .. gcol + 7): apply beta, store every
 // requested output, accumulate the residual.
+// `ctile`: for packed lower-tile output the base of the 128 x 128 tile this piece belongs to (row lr of
+// it, 128 floats per row), else null (row-major output at C32 + grow ldc32).
 __device__ __forceinline__ void pg_emit(const PlaneProblem &P, int grow, int gcol, int rlim, int clim, float (&val)[8],
-                                        bool root, float ep_a, float ep_g, float &rsum)
+                                        bool root, float ep_a, float ep_g, float &rsum, float *ctile = nullptr)
 {
     if (P.C32) {
         if (grow < rlim) {
-            float *c = P.C32 + (size_t)grow * P.ldc32 + gcol;
-            const bool vec = (gcol + 8 <= clim) && ((P.ldc32 & 3) == 0) && ((reinterpret_cast<uintptr_t>(P.C32) & 15u) == 0);
+            float *c = ctile ? ctile + (size_t)(grow % PACK_T) * PACK_T + (gcol % PACK_T) : P.C32 + (size_t)grow * P.ldc32 + gcol;
+            const bool vec = (gcol + 8 <= clim) && (ctile || (P.ldc32 & 3) == 0) && ((reinterpret_cast<uintptr_t>(P.C32) & 15u) == 0);
             if (vec) {
                 ASTERIA_GLOBAL floatx4 *c4 = (ASTERIA_GLOBAL floatx4 *)c;
                 if (P.beta != 0.0f) {
@@ -567,7 +569,10 @@ __global__ __launch_bounds__(S::NTHR) void pgemm_kernel(const PlaneProblem *__re
         if (gi * 128 >= P.M || gj * 128 >= P.N) continue;
         if (sym && gi < gj) continue;
         const bool diag = sym && gi == gj;
-        const bool mirror = sym && gi > gj;
+        // packed lower-tile output (tiles are 128 x 128, as the quadrants): nothing is stored above the diagonal
+        const bool packed = (P.flags & GEMM_C_PACKED) != 0;
+        const bool mirror = sym && gi > gj && !packed;
+        float *ctile = packed ? P.C32 + (((size_t)gi * (gi + 1) / 2 + gj) * PACK_T * PACK_T) : nullptr;
         const bool store_t = !sym && (P.flags & GEMM_STORE_T) != 0;   // only the transposed image is stored
         // does this wavefront own part of the quadrant?
         const int wr0 = wm * WROWS - qi * 128, wc0 = wn * WCOLS - qj * 128;   // sub-tile origin relative to the quadrant
@@ -619,7 +624,7 @@ __global__ __launch_bounds__(S::NTHR) void pgemm_kernel(const PlaneProblem *__re
 #pragma unroll
                     for (int e = 0; e < 4; ++e) { val[e] = v0[e]; val[4 + e] = v1[e]; }
                 }
-                pg_emit(P, orow0 + lr, ocol0 + lc, pass == 0 ? P.M : P.N, pass == 0 ? P.N : P.M, val, root, ep_a, ep_g, rsum);
+                pg_emit(P, orow0 + lr, ocol0 + lc, pass == 0 ? P.M : P.N, pass == 0 ? P.N : P.M, val, root, ep_a, ep_g, rsum, ctile);
             }
             __syncthreads();
         }

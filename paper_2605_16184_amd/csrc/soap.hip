@@ -586,6 +586,7 @@ extern "C" asteria_status asteria_soap_refresh_overlapped(const asteria_factor *
     int n_all = 0;
     for (int i = 0; i < nfactors; ++i) {
         if (!f[i].A || !f[i].X || f[i].n <= 0 || f[i].lda < f[i].n || f[i].ldx < f[i].n) return ASTERIA_INVALID_ARG;
+        if (f[i].a_layout != ASTERIA_LAYOUT_FULL) return ASTERIA_UNSUPPORTED;   // A is an operand of the product A Q: full storage
         if (f[i].n > QR_MAXN) return ASTERIA_UNSUPPORTED;
         n_all = f[i].n > n_all ? f[i].n : n_all;
     }

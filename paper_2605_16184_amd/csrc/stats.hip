@@ -88,7 +88,8 @@ inline bool kmajor_operand(const void *p, int m, int n, int ld)
     return (reinterpret_cast<uintptr_t>(p) & 15u) == 0 && (ld % 8) == 0 && (n % ST_TILE) == 0 && (m % ST_BK) == 0;
 }
 
-inline PlaneProblem fast_problem(const void *G, int rows, int k, int ld, float *C, int ldc, float beta, int tile_start)
+inline PlaneProblem fast_problem(const void *G, int rows, int k, int ld, float *C, int ldc, float beta, int tile_start,
+                                 bool packed = false)
 {
     PlaneProblem q;
     memset(&q, 0, sizeof(q));
@@ -99,7 +100,7 @@ inline PlaneProblem fast_problem(const void *G, int rows, int k, int ld, float *
     q.tile_start = tile_start;
     q.state_idx = -1; q.state_mask = ~0;
     q.alpha = 1.0f - beta; q.beta = beta;
-    q.flags = GEMM_SYM;
+    q.flags = GEMM_SYM | (packed ? GEMM_C_PACKED : 0);
     q.c_terms = 1;
     return q;
 }
@@ -113,9 +114,13 @@ asteria_status validate(const asteria_block *b, int nblocks, float beta)
         if (!k.G || k.m <= 0 || k.n <= 0 || k.ldg < k.n) return ASTERIA_INVALID_ARG;
         if (!valid_dtype(k.g_dtype)) return ASTERIA_INVALID_ARG;
         if (k.acc != ASTERIA_ACC_F32 && k.acc != ASTERIA_ACC_F64) return ASTERIA_INVALID_ARG;
+        if (k.lr_layout != ASTERIA_LAYOUT_FULL && k.lr_layout != ASTERIA_LAYOUT_PACKED) return ASTERIA_INVALID_ARG;
         if (!k.L && !k.R) return ASTERIA_INVALID_ARG;
-        if (k.L && k.ldl < k.m) return ASTERIA_INVALID_ARG;
-        if (k.R && k.ldr < k.n) return ASTERIA_INVALID_ARG;
+        const bool full = k.lr_layout == ASTERIA_LAYOUT_FULL;      // packed: no leading dimension
+        if (k.L && full && k.ldl < k.m) return ASTERIA_INVALID_ARG;
+        if (k.R && full && k.ldr < k.n) return ASTERIA_INVALID_ARG;
+        if (!full && ((k.L && (reinterpret_cast<uintptr_t>(k.L) & 15u)) || (k.R && (reinterpret_cast<uintptr_t>(k.R) & 15u))))
+            return ASTERIA_INVALID_ARG;                            // packed tiles are read and written as 16-byte vectors
     }
     return ASTERIA_OK;
 }
@@ -131,7 +136,8 @@ void build(const asteria_block *b, int nblocks, float beta, StatsTables &t)
         p.lda = k.ldg; p.ldb = k.ldg;
         p.state_idx = -1; p.state_mask = ~0;
         p.alpha = 1.0f - beta; p.beta = beta;
-        p.flags = GEMM_SYM;
+        const bool packed = k.lr_layout == ASTERIA_LAYOUT_PACKED;
+        p.flags = GEMM_SYM | (packed ? GEMM_C_PACKED : 0);
         if (k.acc == ASTERIA_ACC_F64) {
             p.flags |= GEMM_C_F32;
             if (k.L) {
@@ -150,7 +156,7 @@ void build(const asteria_block *b, int nblocks, float beta, StatsTables &t)
         }
         if (k.L) {
             if (d == ASTERIA_BF16 && fast_operand(k.G, k.m, k.n, k.ldg)) {
-                t.fast.push_back(fast_problem(k.G, k.m, k.n, k.ldg, k.L, k.ldl, beta, t.tiles_fast));
+                t.fast.push_back(fast_problem(k.G, k.m, k.n, k.ldg, k.L, k.ldl, beta, t.tiles_fast, packed));
                 t.tiles_fast += pg_tri_tiles(k.m, ST_TILE);
             } else {
                 p.C = k.L; p.ldc = k.ldl; p.M = k.m; p.N = k.m; p.K = k.n;
@@ -204,7 +210,7 @@ extern "C" asteria_status asteria_stats_update(const asteria_block *blocks, int 
             const asteria_block &k = blocks[i];
             if (k.g_dtype != ASTERIA_BF16 || !k.R || k.acc == ASTERIA_ACC_F64) continue;
             if (kmajor_operand(k.G, k.m, k.n, k.ldg)) {
-                PlaneProblem q = fast_problem(k.G, k.n, k.m, k.ldg, k.R, k.ldr, beta, t.tiles_fast);
+                PlaneProblem q = fast_problem(k.G, k.n, k.m, k.ldg, k.R, k.ldr, beta, t.tiles_fast, k.lr_layout == ASTERIA_LAYOUT_PACKED);
                 q.flags |= PG_KMAJOR;
                 t.fast.push_back(q);
                 t.tiles_fast += pg_tri_tiles(k.n, ST_TILE);
@@ -221,7 +227,7 @@ extern "C" asteria_status asteria_stats_update(const asteria_block *blocks, int 
             tiles += (m_pad / 64) * (n_pad / 64);
             jobs.push_back(j);
             // the R problem of this block reads G^T with k (= m) contiguous
-            t.fast.push_back(fast_problem(Gt, k.n, k.m, m_pad, k.R, k.ldr, beta, t.tiles_fast));
+            t.fast.push_back(fast_problem(Gt, k.n, k.m, m_pad, k.R, k.ldr, beta, t.tiles_fast, k.lr_layout == ASTERIA_LAYOUT_PACKED));
             t.tiles_fast += pg_tri_tiles(k.n, ST_TILE);
         }
         if (!jobs.empty()) {

@@ -57,6 +57,8 @@ def test_stats_update_rejects_bad_arguments_without_launching():
     assert f(_blk(ldl=7), 1, 0.9, ws, 1 << 20, None) == B.INVALID_ARG
     assert f(_blk(g_dtype=5), 1, 0.9, ws, 1 << 20, None) == B.INVALID_ARG
     assert f(_blk(acc=2), 1, 0.9, ws, 1 << 20, None) == B.INVALID_ARG
+    assert f(_blk(lr_layout=2), 1, 0.9, ws, 1 << 20, None) == B.INVALID_ARG
+    assert f(_blk(lr_layout=1, L=0x2004), 1, 0.9, ws, 1 << 20, None) == B.INVALID_ARG    # packed tiles: 16-byte aligned
     assert f(_blk(L=None, R=None), 1, 0.9, ws, 1 << 20, None) == B.INVALID_ARG
     assert f(_blk(), 1, 0.9, None, 0, None) == B.WORKSPACE_TOO_SMALL
     assert f(_blk(), 1, 0.9, ws, 16, None) == B.WORKSPACE_TOO_SMALL
@@ -221,3 +223,26 @@ def test_binding_refuses_cpu_tensors_and_wrong_shapes():
     G = torch.zeros(4, 6)
     with pytest.raises(ValueError):
         ast.Blocks([(G, torch.zeros(4, 4), torch.zeros(6, 6))])
+
+
+def test_packed_storage_sizes_and_argument_checks():
+    assert ast.packed_elems(1) == 128 * 128 and ast.packed_elems(128) == 128 * 128
+    assert ast.packed_elems(129) == 3 * 128 * 128 and ast.packed_elems(1024) == 36 * 128 * 128
+    assert ast.packed_elems(0) == 0
+    lib = ast.lib()
+    pair = B._SymPair()
+    pair.full, pair.packed, pair.n, pair.ld = 0x1000, 0x2000, 8, 8
+    arr = (B._SymPair * 1)(pair)
+    for fn in (lib.asteria_sym_pack, lib.asteria_sym_unpack):
+        assert fn(None, 1, None) == B.INVALID_ARG
+        assert fn(arr, 0, None) == B.INVALID_ARG
+        for field, bad in (("full", None), ("packed", None), ("n", 0), ("ld", 7), ("packed", 0x2004)):
+            q = B._SymPair()
+            q.full, q.packed, q.n, q.ld = 0x1000, 0x2000, 8, 8
+            setattr(q, field, bad)
+            assert fn((B._SymPair * 1)(q), 1, None) == B.INVALID_ARG, field
+    # a packed statistic cannot feed the eigenbasis refresh (A is a product operand there)
+    fac = _fac(a_layout=1)
+    assert lib.asteria_soap_refresh(fac, 1, None, ctypes.c_void_p(0x10000), 1 << 30, None) == B.UNSUPPORTED
+    assert lib.asteria_inverse_root(_fac(a_layout=2), 1, 4, 0, (ctypes.c_float * 1)(1e-6), 1, None, None, None, None, None,
+                                    ctypes.c_void_p(0x10000), 1 << 30, None) == B.INVALID_ARG

@@ -217,6 +217,83 @@ def test_stats_fp64_accumulation_keeps_an_ill_conditioned_statistic_above_minus_
         assert relF(Xs[i], Xo[i]) <= TOL_ROOT, relF(Xs[i], Xo[i])
 
 
+# =============================================================================== packed lower-tile storage
+
+def packed_reference(full64: np.ndarray) -> np.ndarray:
+    """Packed lower tiles written out on the host (test-side helper): tile (ti, tj), tj <= ti, at index
+    ti (ti + 1) / 2 + tj, 128 x 128 row-major, zero padding."""
+    n = full64.shape[0]
+    T = (n + 127) // 128
+    pad = np.zeros((T * 128, T * 128))
+    pad[:n, :n] = full64
+    out = np.zeros((T * (T + 1) // 2, 128, 128))
+    for ti in range(T):
+        for tj in range(ti + 1):
+            out[ti * (ti + 1) // 2 + tj] = pad[ti * 128:(ti + 1) * 128, tj * 128:(tj + 1) * 128]
+    return out.reshape(-1)
+
+
+def test_packed_storage_pack_and_unpack_round_trip():
+    sizes = [1, 127, 128, 129, 300, 512]
+    fulls = [padded(n, n, 3) for n in sizes]
+    for i, (n, F) in enumerate(zip(sizes, fulls)):
+        F.copy_(spd(n, 20, i))
+    packs = [torch.full((ast.packed_elems(n),), float("nan"), device=DEV) for n in sizes]
+    assert ast.packed_elems(1024) == 36 * 128 * 128 and ast.packed_elems(129) == 3 * 128 * 128
+    ast.sym_pack(list(zip(fulls, packs)))
+    backs = [padded(n, n, 1) for n in sizes]
+    ast.sym_unpack(list(zip(backs, packs)))
+    torch.cuda.synchronize()
+    for n, F, P, Bk in zip(sizes, fulls, packs, backs):
+        assert np.array_equal(P.cpu().numpy().astype(np.float64), packed_reference(np.tril(np64(F)) + np.tril(np64(F), -1).T))
+        assert torch.equal(Bk, F) and torch.all(Bk._base[:, n:] == -777.0)
+
+
+def test_stats_update_on_packed_statistics_and_roots_from_them():
+    # L and R kept in packed lower tiles: the update reads and writes only the stored tiles; the result
+    # equals the full-storage update bit for bit (same kernels, same sums), and the inverse root reads
+    # the packed statistics directly.  Whole-tile bf16 blocks (the guard-free kernel), a ragged bf16 block,
+    # an fp32 block and an fp64-accumulated one (the guarded kernels).
+    cases = [(256, 384, torch.bfloat16, B.ACC_F32), (512, 256, torch.bfloat16, B.ACC_F32), (200, 328, torch.bfloat16, B.ACC_F32),
+             (130, 257, torch.float32, B.ACC_F32), (129, 300, torch.bfloat16, B.ACC_F64)]
+    items_f, items_p, keep = [], [], []
+    for i, (m, n, dt, acc) in enumerate(cases):
+        G = W.gaussian_block(m, n, 0.1, DEV, 30, i, dtype=dt)
+        L, R = spd(m, 31, i), spd(n, 32, i)
+        Lp = torch.full((ast.packed_elems(m),), float("nan"), device=DEV)
+        Rp = torch.full((ast.packed_elems(n),), float("nan"), device=DEV)
+        ast.sym_pack([(L, Lp), (R, Rp)])
+        items_f.append((G, L, R, acc))
+        items_p.append((G, Lp, Rp, acc, B.LAYOUT_PACKED))
+        keep.append((m, n, L, R, Lp, Rp))
+    refs = [oracle.stats_update(np64(G), np64(L), np64(R), 0.9) for (G, L, R, _) in items_f]
+    ast.stats_update(items_f, 0.9)
+    ast.stats_update(items_p, 0.9)
+    torch.cuda.synchronize()
+    for (m, n, L, R, Lp, Rp), (Lo, Ro) in zip(keep, refs):
+        assert relF(L, Lo) <= TOL_STATS and relF(R, Ro) <= TOL_STATS
+        Lb, Rb = torch.empty_like(L), torch.empty_like(R)
+        ast.sym_unpack([(Lb, Lp), (Rb, Rp)])
+        torch.cuda.synchronize()
+        assert torch.equal(Lb, L) and torch.equal(Rb, R), (m, n)
+    # roots of the packed statistics against the oracle (fed the unpacked arrays) and against the full path
+    As_p = [k[4] for k in keep] + [k[5] for k in keep]
+    As_f = [k[2] for k in keep] + [k[3] for k in keep]
+    Xp = [torch.full_like(A, float("nan")) for A in As_f]
+    Xf = [torch.full_like(A, float("nan")) for A in As_f]
+    info = torch.full((2 * len(As_f),), -1, dtype=torch.int32, device=DEV)
+    lm = torch.zeros(2 * len(As_f), device=DEV)
+    ast.inverse_root([(A, X, B.LAYOUT_PACKED) for A, X in zip(As_p, Xp)] + list(zip(As_f, Xf)), 1e-4, info=info, lambda_max=lm)
+    torch.cuda.synchronize()
+    assert torch.all(info == 0)
+    k = len(As_f)
+    for i, (A, X, Xfull) in enumerate(zip(As_f, Xp, Xf)):
+        Xo, lmax_o, _ = oracle.inverse_root(np64(A), 1e-4)
+        assert relF(X, Xo) <= TOL_ROOT and relF(Xfull, Xo) <= TOL_ROOT
+        assert abs(float(lm[i]) - lmax_o) <= 1e-3 * lmax_o and abs(float(lm[k + i]) - lmax_o) <= 1e-3 * lmax_o
+        assert relF(X, np64(Xfull)) <= 1e-4        # the two mat-vec kernels sum in different orders
+
+
 # =============================================================================== a2 inverse roots
 
 def test_root_single_block_config_absolute_and_relative_eps():
