@@ -544,20 +544,30 @@ __device__ __forceinline__ void gemm_epilogue(const GemmProblem &P, typename MM:
                 }
             }
             if (done) continue;
+            // Offsets of the block's element (br, bc) and of its transposed image (bc, br), and the row
+            // pitch: dense row-major storage, or packed lower tiles - the whole MFMA block then lies in
+            // one stored 128 x 128 tile, and a mirror image exists only inside a diagonal tile.
+            size_t off_n = (size_t)br * ldc + bc, off_t = (size_t)bc * ldc + br;
+            int ld_c = ldc;
+            bool do_mirror = sym;
+            if (packed) {
+                off_n = packed_off(br, bc);
+                ld_c = PACK_T;
+                do_mirror = sym && br / PACK_T == bc / PACK_T;
+                off_t = do_mirror ? packed_off(bc, br) : 0;
+            }
 #pragma unroll
             for (int v = 0; v < MM::NACC; ++v) {
                 const int row = br + MM::acc_row(v, h);
                 if (row >= M || col >= N) continue;
                 if (sym && row < col) continue;   // the mirror of (col, row) covers it
                 TC val = alpha * acc[i][j][v];
-                const size_t at = packed ? packed_off(row, col)
-                                         : ((flags & GEMM_STORE_T) ? (size_t)col * ldc + row : (size_t)row * ldc + col);
+                const size_t at_n = off_n + (size_t)(row - br) * ld_c + (size_t)(col - bc);
+                const size_t at_t = off_t + (size_t)(col - bc) * ld_c + (size_t)(row - br);
+                const size_t at = (flags & GEMM_STORE_T) ? at_t : at_n;
                 if (beta != (TC)0) val += beta * load_c<TC>(C, at, flags);
                 store_c<TC>(C, at, val, flags);
-                if (sym && row != col) {
-                    if (!packed) store_c<TC>(C, (size_t)col * ldc + row, val, flags);
-                    else if (row / PACK_T == col / PACK_T) store_c<TC>(C, packed_off(col, row), val, flags);   // inside a diagonal tile
-                }
+                if (do_mirror && row != col) store_c<TC>(C, at_t, val, flags);
                 if (root) {
                     const TC d = (row == col) ? (TC)1 : (TC)0;
                     const TC t2 = ep_a * d - ep_g * val;
