@@ -58,6 +58,8 @@ def _load():
         lib.oracle_soap_step.argtypes = [ctypes.c_int, ctypes.c_int, dp, dp, dp, dp, dp,
                                          ctypes.c_double, ctypes.c_double, ctypes.c_double,
                                          ctypes.c_int, dp]
+        lib.oracle_soap_sort.argtypes = [ctypes.c_int, dp, dp, ip, dp]
+        lib.oracle_soap_reproject.argtypes = [ctypes.c_int, ctypes.c_int, dp, dp, dp, dp, dp]
         _lib = lib
     return _lib
 
@@ -196,3 +198,31 @@ def soap_step(G, QL, QR, M, V, beta1: float, beta2: float, adam_eps: float, t: i
     if st != OK:
         raise OracleError(st, "soap_step")
     return N, M, V
+
+
+def soap_sort(A, Q):
+    """Columns of Q ordered by decreasing q_i^T A q_i (ties: increasing index).
+    Returns (Q[:, perm], perm, est in the old order)."""
+    A = _f64(A)
+    Q = _f64(Q).copy()
+    n = A.shape[0]
+    assert A.shape == (n, n) and Q.shape == (n, n)
+    perm = np.zeros(n, dtype=np.intc)
+    est = np.empty(n)
+    st = _load().oracle_soap_sort(n, _p(A), _p(Q), perm.ctypes.data_as(ctypes.POINTER(ctypes.c_int)), _p(est))
+    if st != OK:
+        raise OracleError(st, "soap_sort")
+    return Q, perm.astype(np.int64), est
+
+
+def soap_reproject(M, QL_old, QR_old, QL_new, QR_new):
+    """A moment M held in the bases (QL_old, QR_old) re-expressed in (QL_new, QR_new):
+    QL_new^T (QL_old M QR_old^T) QR_new."""
+    M = _f64(M).copy()
+    m, n = M.shape
+    QLo, QRo, QLn, QRn = _f64(QL_old), _f64(QR_old), _f64(QL_new), _f64(QR_new)
+    assert QLo.shape == (m, m) == QLn.shape and QRo.shape == (n, n) == QRn.shape
+    st = _load().oracle_soap_reproject(m, n, _p(QLo), _p(QRo), _p(QLn), _p(QRn), _p(M))
+    if st != OK:
+        raise OracleError(st, "soap_reproject")
+    return M

@@ -18,6 +18,10 @@
  *                           iteration Z = A Q followed by Householder QR,
  *                           Q <- qr(Z).Q with diag(R) >= 0.
  *   oracle_soap_step      - Eq. 2 with phi = Adam in the rotated basis.
+ *   oracle_soap_sort      - the column order SOAP gives its basis before a refresh: by the
+ *                           estimated eigenvalues q_i^T A q_i, largest first.
+ *   oracle_soap_reproject - the moments of Eq. 2's rotated space carried from an old pair
+ *                           of bases to a new one (same matrix in the original space).
  *
  * All matrices are dense row-major doubles with leading dimension = #columns.
  * Build: gcc -O2 -fopenmp -shared -fPIC (no -ffast-math: summation order is
@@ -373,5 +377,66 @@ int oracle_soap_step(int m, int n, const double *G, const double *QL, const doub
     matmul_nt(m, n, n, T, QR, N);   /* N = T Q_R^T    */
     free(T);
     free(Gr);
+    return ORACLE_OK;
+}
+
+/* ------------------------------------------------------------------ */
+/* Column order of an eigenbasis estimate (SOAP, used with Eq. 2):     */
+/*   est_i = q_i^T A q_i  (q_i = column i of Q);  perm = indices by     */
+/*   decreasing est, ties in increasing index (a stable order);        */
+/*   Q <- Q[:, perm].  est_out (optional) receives est in the OLD      */
+/*   column order.                                                     */
+/* ------------------------------------------------------------------ */
+int oracle_soap_sort(int n, const double *A, double *Q, int *perm, double *est_out)
+{
+    if (n <= 0 || !A || !Q || !perm) return ORACLE_BAD_ARG;
+    double *est = (double *)malloc(sizeof(double) * (size_t)n);
+    double *Qs = (double *)malloc(sizeof(double) * (size_t)n * n);
+    if (!est || !Qs) { free(est); free(Qs); return ORACLE_BAD_ARG; }
+    for (int i = 0; i < n; ++i) {
+        double s = 0.0;
+        for (int k = 0; k < n; ++k) {
+            double aq = 0.0;                         /* (A q_i)_k */
+            for (int l = 0; l < n; ++l) aq += A[(size_t)k * n + l] * Q[(size_t)l * n + i];
+            s += Q[(size_t)k * n + i] * aq;
+        }
+        est[i] = s;
+    }
+    /* insertion sort of the indices: stable, largest estimate first */
+    for (int i = 0; i < n; ++i) perm[i] = i;
+    for (int i = 1; i < n; ++i) {
+        const int p = perm[i];
+        int j = i - 1;
+        while (j >= 0 && est[perm[j]] < est[p]) { perm[j + 1] = perm[j]; --j; }
+        perm[j + 1] = p;
+    }
+    for (int r = 0; r < n; ++r)
+        for (int c = 0; c < n; ++c) Qs[(size_t)r * n + c] = Q[(size_t)r * n + perm[c]];
+    memcpy(Q, Qs, sizeof(double) * (size_t)n * n);
+    if (est_out) memcpy(est_out, est, sizeof(double) * (size_t)n);
+    free(est);
+    free(Qs);
+    return ORACLE_OK;
+}
+
+/* ------------------------------------------------------------------ */
+/* Moments of the rotated space under a change of bases (Eq. 2):      */
+/* a matrix M' held in the bases (QLo, QRo) stands for                */
+/*   W = QLo M' QRo^T  in the original space; in the bases (QLn, QRn) */
+/* the same W is   M'' = QLn^T W QRn.   M (m x n) is updated in place. */
+/* ------------------------------------------------------------------ */
+int oracle_soap_reproject(int m, int n, const double *QLo, const double *QRo,
+                          const double *QLn, const double *QRn, double *M)
+{
+    if (m <= 0 || n <= 0 || !QLo || !QRo || !QLn || !QRn || !M) return ORACLE_BAD_ARG;
+    double *T = (double *)malloc(sizeof(double) * (size_t)m * n);
+    double *W = (double *)malloc(sizeof(double) * (size_t)m * n);
+    if (!T || !W) { free(T); free(W); return ORACLE_BAD_ARG; }
+    matmul_nn(m, n, m, QLo, M, T);    /* T = QLo M'        */
+    matmul_nt(m, n, n, T, QRo, W);    /* W = T QRo^T       */
+    matmul_tn(m, n, m, QLn, W, T);    /* T = QLn^T W       */
+    matmul_nn(m, n, n, T, QRn, M);    /* M'' = T QRn       */
+    free(T);
+    free(W);
     return ORACLE_OK;
 }

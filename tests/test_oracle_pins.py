@@ -332,3 +332,87 @@ def test_soap_step_column_sign_flip_invariance():
     Nf, Mf, Vf = oracle.soap_step(G, QL * sl, QR * sr, M0 * np.outer(sl, sr), V0, 0.9, 0.95, 1e-8, 3)
     assert np.allclose(N, Nf, atol=1e-13)
     assert np.allclose(Mf, M * np.outer(sl, sr), atol=1e-15) and np.allclose(Vf, V, atol=1e-15)
+
+
+# ----------------------------------------------------------------------------- SOAP column order and re-projection
+
+def test_soap_sort_orders_columns_by_estimated_eigenvalue_hand_example():
+    # A = diag(2, 5, 3, 5), Q = I: estimates (2, 5, 3, 5) -> order 1, 3 (tie: lower index first), 2, 0
+    A = np.diag([2.0, 5.0, 3.0, 5.0])
+    Qs, perm, est = oracle.soap_sort(A, np.eye(4))
+    assert perm.tolist() == [1, 3, 2, 0] and est.tolist() == [2.0, 5.0, 3.0, 5.0]
+    assert np.array_equal(Qs, np.eye(4)[:, [1, 3, 2, 0]])
+    # a rotated basis: estimates are Rayleigh quotients q_i^T A q_i, written out by hand for a 2 x 2
+    c, s = 0.6, 0.8
+    Q = np.array([[c, -s], [s, c]])
+    A = np.array([[1.0, 2.0], [2.0, 3.0]])
+    r0 = c * c * 1 + 2 * c * s * 2 + s * s * 3            # 0.36 + 1.92 + 1.92
+    r1 = s * s * 1 - 2 * c * s * 2 + c * c * 3            # 0.64 - 1.92 + 1.08
+    Qs, perm, est = oracle.soap_sort(A, Q)
+    assert math.isclose(est[0], r0, rel_tol=1e-15) and math.isclose(est[1], r1, abs_tol=1e-15)
+    assert perm.tolist() == [0, 1] and np.array_equal(Qs, Q)
+    Qs, perm, _ = oracle.soap_sort(A, Q[:, ::-1].copy())
+    assert perm.tolist() == [1, 0] and np.array_equal(Qs, Q)
+
+
+def test_soap_sort_is_a_permutation_with_non_increasing_estimates_and_matches_the_eigen_order_at_a_fixed_point():
+    n = 9
+    Qt = haar(n, RNG)
+    lam = np.array([0.3, 7.0, 1.5, 1.5, 0.01, 4.0, 2.0, 9.0, 0.7])
+    A = (Qt * lam) @ Qt.T
+    Qs, perm, est = oracle.soap_sort(A, Qt)
+    assert sorted(perm.tolist()) == list(range(n))
+    assert np.allclose(est, lam, atol=1e-13)                       # exact eigenvectors: the estimates are the eigenvalues
+    assert np.all(np.diff(est[perm]) <= 1e-13)
+    big = [i for i in perm if lam[i] not in (1.5,)]
+    assert [lam[i] for i in big] == sorted([l for l in lam if l != 1.5], reverse=True)
+    assert np.array_equal(Qs, Qt[:, perm])
+    # sorting then refreshing leaves an eigenbasis an eigenbasis, now in decreasing order of eigenvalue
+    Qr, R = oracle.soap_refresh(A, Qs)
+    simple = [k for k in range(n) if lam[perm[k]] != 1.5]                        # the degenerate pair may rotate
+    assert np.allclose(np.abs(np.diag(Qr.T @ Qs))[simple], 1.0, atol=1e-9)
+    assert np.allclose(np.diag(R), lam[perm], atol=1e-12)
+
+
+def test_soap_reproject_closed_forms():
+    m, n = 5, 4
+    QLo, QRo, QLn, QRn = haar(m, RNG), haar(n, RNG), haar(m, RNG), haar(n, RNG)
+    M = RNG.standard_normal((m, n))
+    # same bases: nothing changes
+    assert np.allclose(oracle.soap_reproject(M, QLo, QRo, QLo, QRo), M, atol=1e-14)
+    # the matrix the moment stands for in the original space does not change
+    M2 = oracle.soap_reproject(M, QLo, QRo, QLn, QRn)
+    assert np.allclose(QLn @ M2 @ QRn.T, QLo @ M @ QRo.T, atol=1e-14)
+    # and back again
+    assert np.allclose(oracle.soap_reproject(M2, QLn, QRn, QLo, QRo), M, atol=1e-13)
+    # new bases = old bases with permuted, sign-flipped columns: rows / columns of M follow
+    pl, pr = np.array([2, 0, 4, 1, 3]), np.array([3, 1, 0, 2])
+    sl, sr = np.array([1, -1, 1, -1, -1.0]), np.array([-1, 1, 1, -1.0])
+    M3 = oracle.soap_reproject(M, QLo, QRo, QLo[:, pl] * sl, QRo[:, pr] * sr)
+    assert np.allclose(M3, (M[pl][:, pr]) * np.outer(sl, sr), atol=1e-14)
+    # hand example, 2 x 2 rotation on the left only: M'' = G(theta)^T M
+    c, s = 0.6, 0.8
+    G = np.array([[c, -s], [s, c]])
+    Mh = np.array([[1.0, 2.0], [3.0, 4.0]])
+    exp = np.array([[c * 1 + s * 3, c * 2 + s * 4], [-s * 1 + c * 3, -s * 2 + c * 4]])
+    assert np.allclose(oracle.soap_reproject(Mh, np.eye(2), np.eye(2), G, np.eye(2)), exp, atol=1e-15)
+    # transposed operand mistakes show on a non-square block with a non-symmetric right rotation
+    Gr = np.array([[c, -s, 0], [s, c, 0], [0, 0, 1.0]])
+    Mr = np.arange(6.0).reshape(2, 3)
+    assert np.allclose(oracle.soap_reproject(Mr, np.eye(2), np.eye(3), np.eye(2), Gr), Mr @ Gr, atol=1e-15)
+    assert not np.allclose(Mr @ Gr, Mr @ Gr.T)
+
+
+def test_soap_step_after_reprojection_continues_the_same_trajectory_in_the_original_space():
+    # Adam's first moment is linear in the gradients: carried through a change of bases by
+    # re-projection it equals the moment accumulated entirely in the new bases
+    m, n = 4, 6
+    QLo, QRo, QLn, QRn = haar(m, RNG), haar(n, RNG), haar(m, RNG), haar(n, RNG)
+    G1, G2 = RNG.standard_normal((m, n)), RNG.standard_normal((m, n))
+    z = np.zeros((m, n))
+    _, M1o, _ = oracle.soap_step(G1, QLo, QRo, z, z, 0.9, 0.95, 1e-8, 1)
+    Mre = oracle.soap_reproject(M1o, QLo, QRo, QLn, QRn)
+    _, M2, _ = oracle.soap_step(G2, QLn, QRn, Mre, z, 0.9, 0.95, 1e-8, 2)
+    _, M1n, _ = oracle.soap_step(G1, QLn, QRn, z, z, 0.9, 0.95, 1e-8, 1)
+    _, M2n, _ = oracle.soap_step(G2, QLn, QRn, M1n, z, 0.9, 0.95, 1e-8, 2)
+    assert np.allclose(M2, M2n, atol=1e-14)
