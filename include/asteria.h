@@ -29,7 +29,7 @@
  *     itself allocates no device memory and keeps no state between calls (apart from the fixed
  *     array of asteria_inverse_root_static and the measurement aid at the end of this file).
  *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  All work is
- *     enqueued on it (asteria_soap_refresh_overlapped: or on streams the caller passes, ordered
+ *     enqueued on it (asteria_soap_refresh_ex: or on streams the caller passes, ordered
  *     after and before it); no entry point waits for the device.  A call may stage its descriptor
  *     tables with hipMemcpyAsync from host memory it owns until the call returns.
  *   - Entry points are not re-entrant: call them from one host thread at a time (they remember,
@@ -124,8 +124,8 @@ typedef struct asteria_pblock {
 /* One block of the SOAP step (asteria_soap_step). */
 typedef struct asteria_sblock {
     const void *G;   /* device, m x n, g_dtype, ldg                          */
-    const float *QL; /* device, m x m fp32, columns = basis vectors, ldql    */
-    const float *QR; /* device, n x n fp32, columns = basis vectors, ldqr    */
+    const float *QL; /* device, m x m fp32, columns = basis vectors, ldql; NULL = identity */
+    const float *QR; /* device, n x n fp32, columns = basis vectors, ldqr; NULL = identity */
     float *M;        /* device, m x n fp32 first moment in the rotated basis, in place, ldm  */
     float *V;        /* device, m x n fp32 second moment in the rotated basis, in place, ldv */
     float *N;        /* device, m x n fp32 update direction (written), ldn   */
@@ -290,23 +290,39 @@ asteria_status asteria_precondition(const asteria_pblock *blocks, int nblocks,
  * one is needed, use the fp32 matrix cores.  Columns of Z beyond its numerical rank come out as
  * an orthonormal completion.  Q is used as scratch during the call (transposed in place, then
  * overwritten panel by panel); where info reports a failure its content is unspecified.
- * asteria_soap_refresh enqueues everything on `stream`.  asteria_soap_refresh_overlapped deals the
- * factors to n_aux (1..4) groups and enqueues each group as a whole on aux_streams[g], streams of
- * the caller (default priority, none equal to `stream`): they start after everything already
- * enqueued on `stream`, and `stream` waits for them before the call's work counts as done on it
- * (events created and released inside the call).  A group's panel steps are a chain of small
- * launches around a latency-bound Cholesky kernel; two chains side by side fill each other's gaps
- * (1B-model workload: 186 ms with two streams against 205 ms on one).  n_aux = 0: the same as
- * asteria_soap_refresh.
+ * asteria_soap_refresh enqueues everything on `stream`.  asteria_soap_refresh_ex takes options
+ * (zero-initialise and call asteria_soap_refresh_opts_default):
+ *   n_aux, aux_streams  deal the factors to n_aux (1..4) groups and enqueue each group as a whole on
+ *       aux_streams[g], streams of the caller (default priority, none equal to `stream`): they start
+ *       after everything already enqueued on `stream`, and `stream` waits for them before the call's
+ *       work counts as done on it (events created and released inside the call).  A group's panel
+ *       steps are a chain of small launches around a latency-bound Cholesky kernel; two chains side
+ *       by side fill each other's gaps (1B-model workload: 186 ms with two streams, 205 ms on one).
+ *   sort  1: before the power iteration the columns of Q are put in the order of decreasing
+ *       estimated eigenvalue q_i^T A q_i, ties by column index (the order SOAP gives its basis; the
+ *       moments of asteria_soap_step then have to follow: asteria_soap_reproject).  `perm`, device
+ *       int32, the factors' orders one after the other (sum of n entries; perm[r] = input column
+ *       that became column r before the QR), or NULL.
+ *   from_identity  1: start from Q = I, whatever Q holds (first basis of a new statistic).
+ *   rounds  number of (power iteration, QR) rounds in the call, >= 1: from the identity, a few
+ *       sorted rounds are orthogonal iteration towards the eigenbasis - the device-side stand-in for
+ *       the eigendecomposition SOAP starts from.  `perm` needs rounds = 1.
  *   info  device int32[nfactors] or NULL (ASTERIA_INFO_OK, or ASTERIA_INFO_NOT_PD if a column
  *         could not be normalised: an exactly zero or non-finite column, or one that three
  *         sweeps of re-orthogonalisation did not separate from the columns before it).       */
 size_t asteria_soap_refresh_workspace_bytes(const asteria_factor *f, int nfactors, size_t *min_bytes);
 asteria_status asteria_soap_refresh(const asteria_factor *f, int nfactors, int32_t *info,
                                     void *ws, size_t ws_bytes, void *stream);
-asteria_status asteria_soap_refresh_overlapped(const asteria_factor *f, int nfactors, int32_t *info,
-                                               void *ws, size_t ws_bytes, void *stream,
-                                               void *const *aux_streams, int n_aux);
+typedef struct asteria_soap_refresh_opts {
+    int32_t sort;
+    int32_t from_identity;
+    int32_t rounds;
+    int32_t n_aux;
+    void *const *aux_streams;
+} asteria_soap_refresh_opts;
+void asteria_soap_refresh_opts_default(asteria_soap_refresh_opts *opts);
+asteria_status asteria_soap_refresh_ex(const asteria_factor *f, int nfactors, const asteria_soap_refresh_opts *opts,
+                                       int32_t *info, int32_t *perm, void *ws, size_t ws_bytes, void *stream);
 
 /* ---- SOAP step (paper Eq. 2, phi = Adam in the rotated basis) ------------------------------
  * For every block, with step_t >= 1:
@@ -314,11 +330,37 @@ asteria_status asteria_soap_refresh_overlapped(const asteria_factor *f, int nfac
  *   N' = (M / (1-beta1^t)) / (sqrt(V / (1-beta2^t)) + adam_eps);  N = Q_L N' Q_R^T.
  * The four rotations run on the bf16 matrix cores with fp32 accumulation and every fp32 operand
  * split into two bf16 terms (bf16 G exact): about 16 bits of Q_L, Q_R and of the intermediates.
- * Workspace: G', N', one intermediate and the transposes of Q_L, Q_R of every block.          */
+ * Workspace: G', N', one intermediate and the transposes of Q_L, Q_R of every block.
+ * One-sided blocks: QL or QR (not both) may be NULL and stands for the identity - a dimension above
+ * the preconditioner cap keeps no basis.  Such a block takes one product per rotation, on the fp32
+ * matrix cores with the operands read in place.                                                 */
 size_t asteria_soap_step_workspace_bytes(const asteria_sblock *blocks, int nblocks);
 asteria_status asteria_soap_step(const asteria_sblock *blocks, int nblocks,
                                  float beta1, float beta2, float adam_eps, int step_t,
                                  void *ws, size_t ws_bytes, void *stream);
+
+/* ---- moments under a change of bases (paper Eq. 2) ---------------------------------------------
+ * asteria_soap_step keeps the Adam moments in the rotated space of (Q_L, Q_R).  After a refresh has
+ * replaced the bases, the first moment is carried over so that it stands for the same matrix of the
+ * original space:  M <- Q_L,new^T (Q_L,old M Q_R,old^T) Q_R,new  (the caller keeps a copy of the old
+ * bases: the refresh works in place).  The second moment V is not linear in the gradient and only
+ * follows the column order of a sorted refresh: V[i][j] <- V[permL[i]][permR[j]] (permL, permR: the
+ * slices of asteria_soap_refresh_ex's `perm` for the block's two factors, device int32, or NULL for
+ * no reordering on that side).  M or V may be NULL to skip that part.  The four products of M run on
+ * the bf16 matrix cores with two-term split operands (16 bits kept), as in asteria_soap_step.
+ * Workspace: two intermediates and the transposes of the new bases per block.                     */
+typedef struct asteria_rblock {
+    const float *QL_old, *QL_new;  /* device, m x m fp32, columns = basis vectors */
+    const float *QR_old, *QR_new;  /* device, n x n fp32                           */
+    float *M;                      /* device, m x n fp32, in place, or NULL        */
+    float *V;                      /* device, m x n fp32, in place, or NULL        */
+    const int32_t *permL, *permR;  /* device, m and n entries, or NULL             */
+    int32_t m, n;
+    int32_t ldql_old, ldql_new, ldqr_old, ldqr_new, ldm, ldv;
+} asteria_rblock;
+size_t asteria_soap_reproject_workspace_bytes(const asteria_rblock *blocks, int nblocks);
+asteria_status asteria_soap_reproject(const asteria_rblock *blocks, int nblocks,
+                                      void *ws, size_t ws_bytes, void *stream);
 
 /* ---- measurement aid (not part of the method) -----------------------------------------------
  * Between asteria_profile_enable and asteria_profile_collect every grouped-GEMM launch made by

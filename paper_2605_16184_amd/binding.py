@@ -54,6 +54,19 @@ class _SBlock(Structure):
                 ("g_dtype", c_int32)]
 
 
+class _RBlock(Structure):
+    _fields_ = [("QL_old", c_void_p), ("QL_new", c_void_p), ("QR_old", c_void_p), ("QR_new", c_void_p),
+                ("M", c_void_p), ("V", c_void_p), ("permL", c_void_p), ("permR", c_void_p),
+                ("m", c_int32), ("n", c_int32), ("ldql_old", c_int32), ("ldql_new", c_int32),
+                ("ldqr_old", c_int32), ("ldqr_new", c_int32), ("ldm", c_int32), ("ldv", c_int32)]
+
+
+class SoapRefreshOpts(Structure):
+    """Mirror of asteria_soap_refresh_opts."""
+    _fields_ = [("sort", c_int32), ("from_identity", c_int32), ("rounds", c_int32), ("n_aux", c_int32),
+                ("aux_streams", POINTER(c_void_p))]
+
+
 class RootOpts(Structure):
     """Mirror of asteria_root_opts; constructed with the library defaults."""
     _fields_ = [("max_iters", c_int32), ("fp64_iters", c_int32), ("power_iters", c_int32),
@@ -116,9 +129,15 @@ def lib():
         L.asteria_soap_refresh_workspace_bytes.argtypes = [POINTER(_Factor), c_int, POINTER(c_size_t)]
         L.asteria_soap_refresh.restype = c_int
         L.asteria_soap_refresh.argtypes = [POINTER(_Factor), c_int, c_void_p, c_void_p, c_size_t, c_void_p]
-        L.asteria_soap_refresh_overlapped.restype = c_int
-        L.asteria_soap_refresh_overlapped.argtypes = [POINTER(_Factor), c_int, c_void_p, c_void_p, c_size_t,
-                                                      c_void_p, POINTER(c_void_p), c_int]
+        L.asteria_soap_refresh_opts_default.restype = None
+        L.asteria_soap_refresh_opts_default.argtypes = [POINTER(SoapRefreshOpts)]
+        L.asteria_soap_refresh_ex.restype = c_int
+        L.asteria_soap_refresh_ex.argtypes = [POINTER(_Factor), c_int, POINTER(SoapRefreshOpts), c_void_p, c_void_p,
+                                              c_void_p, c_size_t, c_void_p]
+        L.asteria_soap_reproject_workspace_bytes.restype = c_size_t
+        L.asteria_soap_reproject_workspace_bytes.argtypes = [POINTER(_RBlock), c_int]
+        L.asteria_soap_reproject.restype = c_int
+        L.asteria_soap_reproject.argtypes = [POINTER(_RBlock), c_int, c_void_p, c_size_t, c_void_p]
         L.asteria_soap_step_workspace_bytes.restype = c_size_t
         L.asteria_soap_step_workspace_bytes.argtypes = [POINTER(_SBlock), c_int]
         L.asteria_soap_step.restype = c_int
@@ -253,7 +272,7 @@ class PBlocks(_Batch):
 
 
 class SBlocks(_Batch):
-    """[(G, QL, QR, M, V, N)] for soap_step."""
+    """[(G, QL, QR, M, V, N)] for soap_step; QL or QR may be None (the identity on that side)."""
     ctype = _SBlock
 
     def _fill(self, d, G, QL, QR, M, V, N):
@@ -264,7 +283,8 @@ class SBlocks(_Batch):
         d.M, m1, n1, d.ldm = _mat(M, "M", torch.float32)
         d.V, m2, n2, d.ldv = _mat(V, "V", torch.float32)
         d.N, m3, n3, d.ldn = _mat(N, "N", torch.float32)
-        if (a, b) != (d.m, d.m) or (c, e) != (d.n, d.n) or {(m1, n1), (m2, n2), (m3, n3)} != {(d.m, d.n)}:
+        if (QL is not None and (a, b) != (d.m, d.m)) or (QR is not None and (c, e) != (d.n, d.n)) or \
+                {(m1, n1), (m2, n2), (m3, n3)} != {(d.m, d.n)}:
             raise ValueError("shape mismatch in soap block")
 
 
@@ -405,24 +425,66 @@ def soap_refresh_workspace_bytes(factors):
 
 
 def soap_refresh(factors, info: Optional[torch.Tensor] = None, ws: Optional[torch.Tensor] = None,
-                 stream=None, aux_streams=None) -> None:
+                 stream=None, aux_streams=None, sort: bool = False, from_identity: bool = False, rounds: int = 1,
+                 perm: Optional[torch.Tensor] = None) -> None:
     """Q <- qr(A Q).Q for every (A, Q), in place.  ``aux_streams``: up to four torch streams on which
-    groups of factors are enqueued side by side (asteria_soap_refresh_overlapped)."""
+    groups of factors are enqueued side by side; ``sort``: columns ordered by decreasing q^T A q first
+    (``perm``: int32 GPU tensor of sum(n) entries receiving the orders); ``from_identity`` / ``rounds``:
+    start from Q = I and run several rounds (asteria_soap_refresh_ex)."""
     f = _as(Factors, factors)
     dev = f.items[0][0].device if f.count else None
     if ws is None:
         ws = _workspace(None, soap_refresh_workspace_bytes(f)[0], dev)
     ws = _workspace(ws, 0, dev)
+    if not (aux_streams or sort or from_identity or rounds != 1 or perm is not None):
+        _check(lib().asteria_soap_refresh(f.array, f.count, _ptr(info, torch.int32, f.count, "info"),
+                                          c_void_p(ws.data_ptr()), ws.numel(), _stream(stream)),
+               "asteria_soap_refresh")
+        return
+    o = SoapRefreshOpts()
+    lib().asteria_soap_refresh_opts_default(ctypes.byref(o))
+    o.sort, o.from_identity, o.rounds = int(bool(sort)), int(bool(from_identity)), int(rounds)
+    aux = None
     if aux_streams:
         aux = (c_void_p * len(aux_streams))(*[s.cuda_stream for s in aux_streams])
-        _check(lib().asteria_soap_refresh_overlapped(f.array, f.count, _ptr(info, torch.int32, f.count, "info"),
-                                                     c_void_p(ws.data_ptr()), ws.numel(), _stream(stream),
-                                                     aux, len(aux_streams)),
-               "asteria_soap_refresh_overlapped")
-        return
-    _check(lib().asteria_soap_refresh(f.array, f.count, _ptr(info, torch.int32, f.count, "info"),
-                                      c_void_p(ws.data_ptr()), ws.numel(), _stream(stream)),
-           "asteria_soap_refresh")
+        o.n_aux, o.aux_streams = len(aux_streams), ctypes.cast(aux, POINTER(c_void_p))
+    total = sum(it[0].shape[0] for it in f.items)
+    _check(lib().asteria_soap_refresh_ex(f.array, f.count, ctypes.byref(o), _ptr(info, torch.int32, f.count, "info"),
+                                         _ptr(perm, torch.int32, total, "perm"), c_void_p(ws.data_ptr()), ws.numel(),
+                                         _stream(stream)), "asteria_soap_refresh_ex")
+
+
+class RBlocks(_Batch):
+    """[(QL_old, QL_new, QR_old, QR_new, M, V, permL, permR)] for soap_reproject; M, V, permL, permR may be None."""
+    ctype = _RBlock
+
+    def _fill(self, d, QLo, QLn, QRo, QRn, M, V=None, permL=None, permR=None):
+        ref = M if M is not None else V
+        d.m, d.n = ref.shape
+        d.M, _, _, d.ldm = _mat(M, "M", torch.float32)
+        d.V, _, _, d.ldv = _mat(V, "V", torch.float32)
+        d.QL_old, a, b, d.ldql_old = _mat(QLo, "QL_old", torch.float32)
+        d.QL_new, a2, b2, d.ldql_new = _mat(QLn, "QL_new", torch.float32)
+        d.QR_old, c, e, d.ldqr_old = _mat(QRo, "QR_old", torch.float32)
+        d.QR_new, c2, e2, d.ldqr_new = _mat(QRn, "QR_new", torch.float32)
+        if M is not None and not ((a, b) == (a2, b2) == (d.m, d.m) and (c, e) == (c2, e2) == (d.n, d.n)):
+            raise ValueError("shape mismatch in reproject block")
+        d.permL = _ptr(permL, torch.int32, d.m, "permL")
+        d.permR = _ptr(permR, torch.int32, d.n, "permR")
+
+
+def soap_reproject_workspace_bytes(blocks) -> int:
+    b = _as(RBlocks, blocks)
+    return lib().asteria_soap_reproject_workspace_bytes(b.array, b.count)
+
+
+def soap_reproject(blocks, ws: Optional[torch.Tensor] = None, stream=None) -> None:
+    """M <- QL_new^T (QL_old M QR_old^T) QR_new and V[i][j] <- V[permL[i]][permR[j]] for every block."""
+    b = _as(RBlocks, blocks)
+    ref = next(t for t in b.items[0] if t is not None)
+    ws = _workspace(ws, soap_reproject_workspace_bytes(b), ref.device)
+    _check(lib().asteria_soap_reproject(b.array, b.count, c_void_p(ws.data_ptr()), ws.numel(), _stream(stream)),
+           "asteria_soap_reproject")
 
 
 def soap_step_workspace_bytes(blocks) -> int:

@@ -127,6 +127,9 @@ struct QrFactor {
     float a_scale, p_scale;
     const float *A;  // the statistic (read for its trace)
     int lda, pad2_;
+    double *est;     // n estimated eigenvalues q_i^T A q_i (column order of the refresh's input)
+    int *perm;       // n: perm[r] = input column that becomes column r
+    int *perm_out;   // the caller's slice of the permutation output, or null
 };
 constexpr float QR_UNIT_SCALE = 16384.0f;
 constexpr int QR_STATE_STRIDE = (int)(sizeof(QrFactor) / sizeof(int));
@@ -376,15 +379,78 @@ __global__ __launch_bounds__(256) void transpose_panel_kernel(const QrFactor *fs
     }
 }
 
+// Q = I for every factor of the group (the refresh then starts from the identity)
+__global__ __launch_bounds__(256) void set_identity_kernel(const QrFactor *fs)
+{
+    const QrFactor &F = fs[blockIdx.y];
+    for (size_t e = (size_t)blockIdx.x * 256 + threadIdx.x; e < (size_t)F.n * F.n; e += (size_t)gridDim.x * 256) {
+        const int i = (int)(e / F.n), j = (int)(e % F.n);
+        F.Qout[(size_t)i * F.ldq + j] = (i == j) ? 1.0f : 0.0f;
+    }
+}
+
+// Column order of the basis before the refresh (the order SOAP uses): est_i = q_i^T A q_i, largest
+// first, ties by index.  With Q^T in the caller's buffer (rows q_i^T) and Z^T = Q^T A already formed,
+// est_i is the dot product of row i of the two; one wavefront per row, fp64 sums.
+__global__ __launch_bounds__(256) void sort_estimate_kernel(const QrFactor *fs)
+{
+    const QrFactor &F = fs[blockIdx.y];
+    const int row = (int)blockIdx.x * 4 + (int)(threadIdx.x >> 6), lane = threadIdx.x & 63;
+    if (row >= F.n) return;
+    const float *q = F.Qout + (size_t)row * F.ldq, *z = F.Zt + (size_t)row * F.ldz;
+    double s = 0.0;
+    for (int k = lane; k < F.n; k += 64) s += (double)q[k] * (double)z[k];
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
+    if (lane == 0) F.est[row] = s;
+}
+
+// rank of every estimate: the number of columns that come before it (larger estimate, or equal and a
+// lower index); perm[rank] = column.  n comparisons per column: cheap next to the products.
+__global__ __launch_bounds__(256) void sort_rank_kernel(const QrFactor *fs)
+{
+    const QrFactor &F = fs[blockIdx.y];
+    const int i = (int)blockIdx.x * 256 + threadIdx.x;
+    __shared__ double chunk[256];
+    const double mine = i < F.n ? F.est[i] : 0.0;
+    int rank = 0;
+    for (int j0 = 0; j0 < F.n; j0 += 256) {
+        __syncthreads();
+        chunk[threadIdx.x] = j0 + (int)threadIdx.x < F.n ? F.est[j0 + threadIdx.x] : 0.0;
+        __syncthreads();
+        const int lim = min(256, F.n - j0);
+        for (int t = 0; t < lim; ++t) {
+            const double o = chunk[t];
+            rank += (o > mine || (o == mine && j0 + t < i)) ? 1 : 0;
+        }
+    }
+    if (i < F.n) {
+        F.perm[rank] = i;
+        if (F.perm_out) F.perm_out[rank] = i;
+    }
+}
+
+// rows of Z^T gathered in the new order, through the caller's Q buffer (free between the product that
+// formed Z^T and the first finished panel): phase 0: Q[r] = Zt[perm[r]]; phase 1: Zt[r] = Q[r]
+__global__ __launch_bounds__(256) void sort_gather_kernel(const QrFactor *fs, int phase)
+{
+    const QrFactor &F = fs[blockIdx.y];
+    const int row = (int)blockIdx.x;
+    if (row >= F.n) return;
+    const float *src = phase == 0 ? F.Zt + (size_t)F.perm[row] * F.ldz : F.Qout + (size_t)row * F.ldq;
+    float *dst = phase == 0 ? F.Qout + (size_t)row * F.ldq : F.Zt + (size_t)row * F.ldz;
+    for (int k = threadIdx.x; k < F.n; k += 256) dst[k] = src[k];
+}
+
 asteria_status validate_step(const asteria_sblock *b, int nblocks, float b1, float b2, float eps, int t)
 {
     if (!b || nblocks <= 0 || t < 1) return ASTERIA_INVALID_ARG;
     if (!(b1 >= 0.0f && b1 < 1.0f) || !(b2 >= 0.0f && b2 < 1.0f) || !(eps >= 0.0f)) return ASTERIA_INVALID_ARG;
     for (int i = 0; i < nblocks; ++i) {
         const asteria_sblock &k = b[i];
-        if (!k.G || !k.QL || !k.QR || !k.M || !k.V || !k.N) return ASTERIA_INVALID_ARG;
+        if (!k.G || (!k.QL && !k.QR) || !k.M || !k.V || !k.N) return ASTERIA_INVALID_ARG;   // one side may be the identity
         if (k.m <= 0 || k.n <= 0) return ASTERIA_INVALID_ARG;
-        if (k.ldg < k.n || k.ldql < k.m || k.ldqr < k.n || k.ldm < k.n || k.ldv < k.n || k.ldn < k.n)
+        if (k.ldg < k.n || (k.QL && k.ldql < k.m) || (k.QR && k.ldqr < k.n) || k.ldm < k.n || k.ldv < k.n || k.ldn < k.n)
             return ASTERIA_INVALID_ARG;
         if (!valid_dtype(k.g_dtype)) return ASTERIA_INVALID_ARG;
     }
@@ -398,7 +464,7 @@ extern "C" size_t asteria_soap_step_workspace_bytes(const asteria_sblock *blocks
     if (!blocks || nblocks <= 0) return 0;
     size_t bytes = 4 * Carver::need((size_t)nblocks, sizeof(GemmProblem)) + Carver::need((size_t)nblocks, sizeof(AdamBlock)) +
                    Carver::need(2 * (size_t)nblocks, sizeof(TransposeF32Job)) +
-                   3 * Carver::need((size_t)nblocks, sizeof(PlaneProblem)) + 2048;
+                   3 * Carver::need((size_t)nblocks, sizeof(PlaneProblem)) + Carver::need(4 * (size_t)nblocks, sizeof(GemmProblem)) + 2048;
     for (int i = 0; i < nblocks; ++i) {
         const int m = blocks[i].m, n = blocks[i].n;
         bytes += 2 * Carver::need((size_t)m * ld4(n), sizeof(float));      // G' / N' (m x n)
@@ -429,6 +495,10 @@ extern "C" asteria_status asteria_soap_step(const asteria_sblock *blocks, int nb
     std::vector<PlaneProblem> f2, f3, f4;   // products 2-4 of blocks that fill whole 256 x 256 tiles
     int tilesf = 0;
     std::vector<GemmProblem> g1[2], g2, g3, g4;
+    // one-sided blocks (Q_L or Q_R absent = the identity on that side, e.g. a dimension above the
+    // preconditioner cap): one product per rotation, on the fp32 matrix cores, operands read in place
+    std::vector<GemmProblem> oL1[2], oL2, oR1[2], oR2;     // left only: Q_L^T G, Q_L N';  right only: G Q_R, N' Q_R^T
+    int tL1[2] = {0, 0}, tL2 = 0, tR1[2] = {0, 0}, tR2 = 0;
     std::vector<AdamBlock> ab;
     std::vector<TransposeF32Job> tj;
     int tiles1[2] = {0, 0}, tiles = 0, tilesT = 0, rows = 0, ttiles = 0;
@@ -437,6 +507,37 @@ extern "C" asteria_status asteria_soap_step(const asteria_sblock *blocks, int nb
         const int ldw = ld4(k.n), ldt = ld4(k.m), ldqlt = ld4(k.m), ldqrt = ld4(k.n);
         float *Gr = cv.take<float>((size_t)k.m * ldw);   // G' (m x n)
         float *Np = cv.take<float>((size_t)k.m * ldw);   // N' (m x n)
+        if (!k.QL || !k.QR) {
+            const int tm1 = (k.m + BM - 1) / BM, tn1 = (k.n + BN - 1) / BN;
+            GemmProblem p;
+            memset(&p, 0, sizeof(p));
+            p.state_idx = -1; p.state_mask = ~0; p.alpha = 1.0f; p.beta = 0.0f;
+            p.M = k.m; p.N = k.n; p.tiles_n = tn1;
+            if (k.QL) {
+                // G' = Q_L^T G: A'(i, l) = Q_L[l][i], B'(j, l) = G[l][j], both k-major
+                p.K = k.m; p.A = k.QL; p.lda = k.ldql; p.B = k.G; p.ldb = k.ldg; p.C = Gr; p.ldc = ldw;
+                p.tile_start = tL1[k.g_dtype]; tL1[k.g_dtype] += tm1 * tn1;
+                oL1[k.g_dtype].push_back(p);
+                // N = Q_L N': A'(i, l) = Q_L[i][l], B'(j, l) = N'[l][j] (k-major)
+                p.A = k.QL; p.lda = k.ldql; p.B = Np; p.ldb = ldw; p.C = k.N; p.ldc = k.ldn;
+                p.tile_start = tL2; tL2 += tm1 * tn1;
+                oL2.push_back(p);
+            } else {
+                // G' = G Q_R: A' = G, B'(j, l) = Q_R[l][j] (k-major)
+                p.K = k.n; p.A = k.G; p.lda = k.ldg; p.B = k.QR; p.ldb = k.ldqr; p.C = Gr; p.ldc = ldw;
+                p.tile_start = tR1[k.g_dtype]; tR1[k.g_dtype] += tm1 * tn1;
+                oR1[k.g_dtype].push_back(p);
+                // N = N' Q_R^T: A' = N', B'(j, l) = Q_R[j][l]
+                p.A = Np; p.lda = ldw; p.B = k.QR; p.ldb = k.ldqr; p.C = k.N; p.ldc = k.ldn;
+                p.tile_start = tR2; tR2 += tm1 * tn1;
+                oR2.push_back(p);
+            }
+            AdamBlock a1;
+            a1.Gr = Gr; a1.M = k.M; a1.V = k.V; a1.Np = Np; a1.m = k.m; a1.n = k.n; a1.ldw = ldw; a1.ldm = k.ldm; a1.ldv = k.ldv;
+            a1.row_start = rows; rows += k.m;
+            ab.push_back(a1);
+            continue;
+        }
         float *Tt = cv.take<float>((size_t)k.n * ldt);   // (G Q_R)^T, later (N' Q_R^T)^T  (n x m)
         float *QLt = cv.take<float>((size_t)k.m * ldqlt);
         float *QRt = cv.take<float>((size_t)k.n * ldqrt);
@@ -505,10 +606,29 @@ extern "C" asteria_status asteria_soap_step(const asteria_sblock *blocks, int nb
         ASTERIA_HIP_TRY(upload_async(d_f[2], f4.data(), f4.size() * sizeof(PlaneProblem), stream));
     }
     ASTERIA_HIP_TRY(upload_async(d_ab, ab.data(), ab.size() * sizeof(AdamBlock), stream));
-    ASTERIA_HIP_TRY(upload_async(d_tj, tj.data(), tj.size() * sizeof(TransposeF32Job), stream));
-
-    hipLaunchKernelGGL(transpose_f32_kernel, dim3(ttiles), dim3(256), 0, stream, d_tj, (int)tj.size());
-    ASTERIA_HIP_TRY(hipGetLastError());
+    // tables of the one-sided blocks, one after the other in a region of their own
+    GemmProblem *d_o = cv.take<GemmProblem>(4 * (size_t)nblocks);
+    GemmProblem *d_oL1[2], *d_oR1[2], *d_oL2, *d_oR2;
+    {
+        GemmProblem *q = d_o;
+        auto put = [&](const std::vector<GemmProblem> &v, GemmProblem *&dst) -> hipError_t {
+            dst = q;
+            q += v.size();
+            return v.empty() ? hipSuccess : upload_async(dst, v.data(), v.size() * sizeof(GemmProblem), stream);
+        };
+        ASTERIA_HIP_TRY(put(oL1[0], d_oL1[0])); ASTERIA_HIP_TRY(put(oL1[1], d_oL1[1])); ASTERIA_HIP_TRY(put(oL2, d_oL2));
+        ASTERIA_HIP_TRY(put(oR1[0], d_oR1[0])); ASTERIA_HIP_TRY(put(oR1[1], d_oR1[1])); ASTERIA_HIP_TRY(put(oR2, d_oR2));
+    }
+    if (!tj.empty()) {
+        ASTERIA_HIP_TRY(upload_async(d_tj, tj.data(), tj.size() * sizeof(TransposeF32Job), stream));
+        hipLaunchKernelGGL(transpose_f32_kernel, dim3(ttiles), dim3(256), 0, stream, d_tj, (int)tj.size());
+        ASTERIA_HIP_TRY(hipGetLastError());
+    }
+    // one-sided rotations into the eigenbasis
+    ASTERIA_HIP_TRY((launch_gemm_grouped<float, float, float, true, true>(d_oL1[0], (int)oL1[0].size(), tL1[0], nullptr, stream)));
+    ASTERIA_HIP_TRY((launch_gemm_grouped<float, float, bf16_t, true, true>(d_oL1[1], (int)oL1[1].size(), tL1[1], nullptr, stream)));
+    ASTERIA_HIP_TRY((launch_gemm_grouped<float, float, float, false, true>(d_oR1[0], (int)oR1[0].size(), tR1[0], nullptr, stream)));
+    ASTERIA_HIP_TRY((launch_gemm_grouped<float, bf16_t, float, false, true>(d_oR1[1], (int)oR1[1].size(), tR1[1], nullptr, stream)));
     if (!g1[0].empty())
         ASTERIA_HIP_TRY((launch_gemm_bf16_grouped<float, float, 2, 2>(d_g[0], (int)g1[0].size(), tiles1[0], nullptr, stream)));
     if (!g1[1].empty())
@@ -523,6 +643,9 @@ extern "C" asteria_status asteria_soap_step(const asteria_sblock *blocks, int nb
     if (!f2.empty()) ASTERIA_HIP_TRY((launch_pgemm<PgF32x2>(d_f[1], (int)f3.size(), tilesf, nullptr, stream, 513)));
     if (!g2.empty()) ASTERIA_HIP_TRY((launch_gemm_bf16_grouped<float, float, 2, 2>(d_g[3], (int)g4.size(), tiles, nullptr, stream)));
     if (!f2.empty()) ASTERIA_HIP_TRY((launch_pgemm<PgF32x2>(d_f[2], (int)f4.size(), tilesf, nullptr, stream, 513)));
+    // one-sided rotations back
+    ASTERIA_HIP_TRY((launch_gemm_grouped<float, float, float, false, true>(d_oL2, (int)oL2.size(), tL2, nullptr, stream)));
+    ASTERIA_HIP_TRY((launch_gemm_grouped<float, float, float, false, false>(d_oR2, (int)oR2.size(), tR2, nullptr, stream)));
     return ASTERIA_OK;
 }
 
@@ -535,6 +658,7 @@ size_t refresh_factor_bytes(int n)
            Carver::need((size_t)QR_PANEL * ld4(n), sizeof(float)) +     // projection coefficients of one panel
            Carver::need((size_t)QR_PANEL * QR_PANEL, sizeof(double)) +  // panel Gram matrix / fp64 inverse factor
            Carver::need((size_t)QR_PANEL * QR_PANEL, sizeof(float)) +   // fp32 inverse factor
+           Carver::need((size_t)n, sizeof(double)) + Carver::need((size_t)n, sizeof(int)) +   // column estimates and order
            (size_t)(1 + 4 * np) * sizeof(GemmProblem) + (size_t)np * sizeof(int) + sizeof(QrFactor);
 }
 
@@ -572,14 +696,28 @@ extern "C" size_t asteria_soap_refresh_workspace_bytes(const asteria_factor *f, 
 extern "C" asteria_status asteria_soap_refresh(const asteria_factor *f, int nfactors, int32_t *info,
                                                void *ws, size_t ws_bytes, void *stream_)
 {
-    return asteria_soap_refresh_overlapped(f, nfactors, info, ws, ws_bytes, stream_, nullptr, 0);
+    return asteria_soap_refresh_ex(f, nfactors, nullptr, info, nullptr, ws, ws_bytes, stream_);
 }
 
-extern "C" asteria_status asteria_soap_refresh_overlapped(const asteria_factor *f, int nfactors, int32_t *info,
-                                                          void *ws, size_t ws_bytes, void *stream_,
-                                                          void *const *aux_streams, int n_aux)
+extern "C" void asteria_soap_refresh_opts_default(asteria_soap_refresh_opts *o)
+{
+    if (!o) return;
+    o->sort = 0; o->from_identity = 0; o->rounds = 1; o->n_aux = 0; o->aux_streams = nullptr;
+}
+
+extern "C" asteria_status asteria_soap_refresh_ex(const asteria_factor *f, int nfactors,
+                                                  const asteria_soap_refresh_opts *opts_in, int32_t *info, int32_t *perm,
+                                                  void *ws, size_t ws_bytes, void *stream_)
 {
     if (!f || nfactors <= 0) return ASTERIA_INVALID_ARG;
+    asteria_soap_refresh_opts o;
+    asteria_soap_refresh_opts_default(&o);
+    if (opts_in) o = *opts_in;
+    if ((o.sort != 0 && o.sort != 1) || (o.from_identity != 0 && o.from_identity != 1) || o.rounds < 1 || o.rounds > 1000)
+        return ASTERIA_INVALID_ARG;
+    if (perm && (!o.sort || o.rounds != 1)) return ASTERIA_INVALID_ARG;   // the order of ONE sorted round can be reported
+    void *const *aux_streams = o.aux_streams;
+    const int n_aux = o.n_aux;
     if (n_aux < 0 || n_aux > REFRESH_MAX_GROUPS || (n_aux > 0 && !aux_streams)) return ASTERIA_INVALID_ARG;
     for (int g = 0; g < n_aux; ++g)
         if (!aux_streams[g] || aux_streams[g] == stream_) return ASTERIA_INVALID_ARG;
@@ -598,6 +736,10 @@ extern "C" asteria_status asteria_soap_refresh_overlapped(const asteria_factor *
     constexpr size_t chol_lds = CHOL_LDS_BYTES;
     static bool chol_configured[MAX_DEVICES] = {};
     ASTERIA_HIP_TRY(ensure_dynamic_lds(reinterpret_cast<const void *>(panel_chol_inverse_kernel), chol_lds, chol_configured));
+
+    // the caller's permutation array holds the factors' orders one after the other
+    std::vector<size_t> perm_offset(nfactors, 0);
+    for (int i = 1; i < nfactors; ++i) perm_offset[i] = perm_offset[i - 1] + (size_t)f[i - 1].n;
 
     int first = 0;
     while (first < nfactors) {
@@ -640,6 +782,9 @@ extern "C" asteria_status asteria_soap_refresh_overlapped(const asteria_factor *
             F.Qout = a.X; F.n = n; F.ldz = ldz; F.ldq = a.ldx; F.bad = 0; F.run = 0; F.skip3 = 1;
             F.out_index = idx[i]; F.pad_ = 0; F.pad0_ = 0;
             F.a_scale = 1.0f; F.p_scale = 1.0f; F.A = a.A; F.lda = a.lda; F.pad2_ = 0;
+            F.est = cv.take<double>((size_t)n);
+            F.perm = cv.take<int>((size_t)n);
+            F.perm_out = perm ? perm + perm_offset[idx[i]] : nullptr;
             q.push_back(F);
             // Z^T = Q^T A on the fp16 cores (two terms per operand): A'(i, k) = Q^T[i][k] - the caller's
             // Q has been transposed in place by then -, scaled by 2^14, and B'(j, k) = A[j][k] (A is
@@ -727,11 +872,25 @@ extern "C" asteria_status asteria_soap_refresh_overlapped(const asteria_factor *
             ASTERIA_HIP_TRY(upload_async(d_t2[j], t2[j].data(), t2[j].size() * sizeof(GemmProblem), stream));
         }
         hipLaunchKernelGGL(qr_scale_kernel, dim3(cnt), dim3(64), 0, stream, d_q, cnt);
+        if (o.from_identity)
+            hipLaunchKernelGGL(set_identity_kernel, dim3((unsigned)std::min<size_t>(((size_t)n_max * n_max + 255) / 256, 4096), (unsigned)cnt),
+                               dim3(256), 0, stream, d_q);
+        for (int round = 0; round < o.rounds; ++round) {
         {
             const unsigned tpr = (unsigned)((n_max + 31) / 32);
             hipLaunchKernelGGL(transpose_inplace_kernel, dim3(tpr * tpr, (unsigned)cnt), dim3(256), 0, stream, d_q);
         }
         ASTERIA_HIP_TRY((launch_gemm_bf16_grouped<float, float, 2, 2, true>(d_g, cnt, tiles, nullptr, stream)));
+        if (o.sort) {
+            // order the columns by q_i^T A q_i = (row i of Q^T) . (row i of Z^T), largest first: the rows of
+            // Z^T are gathered in that order (A (Q P) = (A Q) P: sorting the basis first, as SOAP does, and
+            // then multiplying gives the same Z)
+            hipLaunchKernelGGL(sort_estimate_kernel, dim3((unsigned)((n_max + 3) / 4), (unsigned)cnt), dim3(256), 0, stream, d_q);
+            hipLaunchKernelGGL(sort_rank_kernel, dim3((unsigned)((n_max + 255) / 256), (unsigned)cnt), dim3(256), 0, stream, d_q);
+            hipLaunchKernelGGL(sort_gather_kernel, dim3((unsigned)n_max, (unsigned)cnt), dim3(256), 0, stream, d_q, 0);
+            hipLaunchKernelGGL(sort_gather_kernel, dim3((unsigned)n_max, (unsigned)cnt), dim3(256), 0, stream, d_q, 1);
+            ASTERIA_HIP_TRY(hipGetLastError());
+        }
         for (int j = 0; j < np_max; ++j) {
             // sweeps of (project against the finished rows, orthonormalise the panel): the second
             // projection acts on normalised rows, so what the first normalisation amplified - the
@@ -762,6 +921,7 @@ extern "C" asteria_status asteria_soap_refresh_overlapped(const asteria_factor *
             hipLaunchKernelGGL(transpose_panel_kernel, dim3((QR_PANEL / 32) * ((n_max + 31) / 32), (unsigned)fidx[j].size()),
                                dim3(256), 0, stream, d_q, d_fidx[j], j);
         }
+        }   // rounds
         hipLaunchKernelGGL(qr_info_kernel, dim3((cnt + 127) / 128), dim3(128), 0, stream, d_q, cnt, info);
         ASTERIA_HIP_TRY(hipGetLastError());
         return ASTERIA_OK;
@@ -813,6 +973,154 @@ extern "C" asteria_status asteria_soap_refresh_overlapped(const asteria_factor *
         }
 
         first += cnt;
+    }
+    return ASTERIA_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// asteria_soap_reproject: the first moment M of asteria_soap_step lives in the rotated space of the
+// bases it was accumulated in.  When a refresh replaces (Q_L, Q_R), the matrix M stands for in the
+// original space, W = Q_L,old M Q_R,old^T, is re-expressed in the new bases: M <- Q_L,new^T W Q_R,new.
+// Four grouped products on the bf16 matrix cores with two-term split operands, as in
+// asteria_soap_step.  The second moment V is not a linear quantity; it follows the column order only
+// (V[i][j] <- V[permL[i]][permR[j]], the orders a sorted refresh reports).
+namespace {
+
+struct PermuteJob {
+    float *V;          // m x n, ldv
+    float *tmp;        // m x n, ldw
+    const int *pl, *pr;   // row / column order, or null for the identity
+    int m, n, ldv, ldw;
+    int row_start;
+    int pad_;
+};
+
+__global__ __launch_bounds__(256) void permute_moment_kernel(const PermuteJob *jobs, int njobs, int phase)
+{
+    int lo = 0, hi = njobs - 1;
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (jobs[mid].row_start <= (int)blockIdx.x) lo = mid; else hi = mid - 1;
+    }
+    const PermuteJob &J = jobs[lo];
+    const int i = (int)blockIdx.x - J.row_start;
+    if (phase == 0) {
+        const float *src = J.V + (size_t)(J.pl ? J.pl[i] : i) * J.ldv;
+        float *dst = J.tmp + (size_t)i * J.ldw;
+        for (int j = threadIdx.x; j < J.n; j += 256) dst[j] = src[J.pr ? J.pr[j] : j];
+    } else {
+        const float *src = J.tmp + (size_t)i * J.ldw;
+        float *dst = J.V + (size_t)i * J.ldv;
+        for (int j = threadIdx.x; j < J.n; j += 256) dst[j] = src[j];
+    }
+}
+
+asteria_status validate_reproject(const asteria_rblock *b, int nblocks)
+{
+    if (!b || nblocks <= 0) return ASTERIA_INVALID_ARG;
+    for (int i = 0; i < nblocks; ++i) {
+        const asteria_rblock &k = b[i];
+        if (k.m <= 0 || k.n <= 0) return ASTERIA_INVALID_ARG;
+        if (!k.M && !k.V) return ASTERIA_INVALID_ARG;
+        if (k.M && (!k.QL_old || !k.QL_new || !k.QR_old || !k.QR_new)) return ASTERIA_INVALID_ARG;
+        if (k.M && (k.ldql_old < k.m || k.ldql_new < k.m || k.ldqr_old < k.n || k.ldqr_new < k.n || k.ldm < k.n))
+            return ASTERIA_INVALID_ARG;
+        if (k.V && k.ldv < k.n) return ASTERIA_INVALID_ARG;
+    }
+    return ASTERIA_OK;
+}
+
+}  // namespace
+
+extern "C" size_t asteria_soap_reproject_workspace_bytes(const asteria_rblock *blocks, int nblocks)
+{
+    if (!blocks || nblocks <= 0) return 0;
+    size_t bytes = 4 * Carver::need((size_t)nblocks, sizeof(GemmProblem)) + Carver::need((size_t)nblocks, sizeof(PermuteJob)) +
+                   Carver::need(2 * (size_t)nblocks, sizeof(TransposeF32Job)) + 2048;
+    for (int i = 0; i < nblocks; ++i) {
+        const int m = blocks[i].m, n = blocks[i].n;
+        bytes += Carver::need((size_t)m * ld4(n), sizeof(float));          // W, also the copy of V while it is permuted
+        bytes += Carver::need((size_t)n * ld4(m), sizeof(float));          // transposed intermediate (n x m)
+        bytes += Carver::need((size_t)m * ld4(m), sizeof(float));          // Q_L,new^T
+        bytes += Carver::need((size_t)n * ld4(n), sizeof(float));          // Q_R,new^T
+    }
+    return bytes;
+}
+
+extern "C" asteria_status asteria_soap_reproject(const asteria_rblock *blocks, int nblocks,
+                                                 void *ws, size_t ws_bytes, void *stream_)
+{
+    asteria_status st = validate_reproject(blocks, nblocks);
+    if (st != ASTERIA_OK) return st;
+    if (!ws || ws_bytes < asteria_soap_reproject_workspace_bytes(blocks, nblocks)) return ASTERIA_WORKSPACE_TOO_SMALL;
+    if (reinterpret_cast<uintptr_t>(ws) & 255u) return ASTERIA_INVALID_ARG;
+    hipStream_t stream = reinterpret_cast<hipStream_t>(stream_);
+
+    Carver cv(ws);
+    GemmProblem *d_g[4];
+    for (int i = 0; i < 4; ++i) d_g[i] = cv.take<GemmProblem>(nblocks);
+    PermuteJob *d_pj = cv.take<PermuteJob>(nblocks);
+    TransposeF32Job *d_tj = cv.take<TransposeF32Job>(2 * (size_t)nblocks);
+    std::vector<GemmProblem> g[4];
+    std::vector<PermuteJob> pj;
+    std::vector<TransposeF32Job> tj;
+    int tiles = 0, ttiles = 0, prow = 0;
+    for (int i = 0; i < nblocks; ++i) {
+        const asteria_rblock &k = blocks[i];
+        const int ldw = ld4(k.n), ldt = ld4(k.m), ldqlt = ld4(k.m), ldqrt = ld4(k.n);
+        float *Wb = cv.take<float>((size_t)k.m * ldw);
+        float *Tt = cv.take<float>((size_t)k.n * ldt);
+        float *QLt = cv.take<float>((size_t)k.m * ldqlt);
+        float *QRt = cv.take<float>((size_t)k.n * ldqrt);
+        if (k.V && (k.permL || k.permR)) {
+            PermuteJob j;
+            memset(&j, 0, sizeof(j));
+            j.V = k.V; j.tmp = Wb; j.pl = k.permL; j.pr = k.permR; j.m = k.m; j.n = k.n; j.ldv = k.ldv; j.ldw = ldw;
+            j.row_start = prow; prow += k.m;
+            pj.push_back(j);
+        }
+        if (!k.M) continue;
+        TransposeF32Job t;
+        memset(&t, 0, sizeof(t));
+        t.src = k.QL_new; t.dst = QLt; t.rows = k.m; t.cols = k.m; t.lds_ = k.ldql_new; t.ldd = ldqlt;
+        t.tile_start = ttiles; ttiles += ((k.m + 31) / 32) * ((k.m + 31) / 32);
+        tj.push_back(t);
+        t.src = k.QR_new; t.dst = QRt; t.rows = k.n; t.cols = k.n; t.lds_ = k.ldqr_new; t.ldd = ldqrt;
+        t.tile_start = ttiles; ttiles += ((k.n + 31) / 32) * ((k.n + 31) / 32);
+        tj.push_back(t);
+        const int tm = (k.m + BM - 1) / BM, tn = (k.n + BN - 1) / BN;
+        GemmProblem p;
+        memset(&p, 0, sizeof(p));
+        p.state_idx = -1; p.state_mask = ~0; p.alpha = 1.0f; p.beta = 0.0f;
+        p.M = k.m; p.N = k.n; p.tiles_n = tn; p.tile_start = tiles;
+        // a: (M Q_R,old^T)^T:  A' = M, B'(j, k) = Q_R,old[j][k]; stored transposed
+        p.K = k.n; p.A = k.M; p.lda = k.ldm; p.B = k.QR_old; p.ldb = k.ldqr_old; p.C = Tt; p.ldc = ldt; p.flags = GEMM_STORE_T;
+        g[0].push_back(p);
+        // b: W = Q_L,old (M Q_R,old^T):  A' = Q_L,old, B' = the transposed intermediate
+        p.K = k.m; p.A = k.QL_old; p.lda = k.ldql_old; p.B = Tt; p.ldb = ldt; p.C = Wb; p.ldc = ldw; p.flags = 0;
+        g[1].push_back(p);
+        // c: (W Q_R,new)^T:  A' = W, B'(j, k) = Q_R,new[k][j] = its transposed copy; stored transposed
+        p.K = k.n; p.A = Wb; p.lda = ldw; p.B = QRt; p.ldb = ldqrt; p.C = Tt; p.ldc = ldt; p.flags = GEMM_STORE_T;
+        g[2].push_back(p);
+        // d: M = Q_L,new^T (W Q_R,new):  A' = Q_L,new^T, B' = the transposed intermediate
+        p.K = k.m; p.A = QLt; p.lda = ldqlt; p.B = Tt; p.ldb = ldt; p.C = k.M; p.ldc = k.ldm; p.flags = 0;
+        g[3].push_back(p);
+        tiles += tm * tn;
+    }
+    // V first: its copy uses the W buffer of the block
+    if (!pj.empty()) {
+        ASTERIA_HIP_TRY(upload_async(d_pj, pj.data(), pj.size() * sizeof(PermuteJob), stream));
+        for (int phase = 0; phase < 2; ++phase)
+            hipLaunchKernelGGL(permute_moment_kernel, dim3(prow), dim3(256), 0, stream, d_pj, (int)pj.size(), phase);
+        ASTERIA_HIP_TRY(hipGetLastError());
+    }
+    if (g[0].empty()) return ASTERIA_OK;
+    ASTERIA_HIP_TRY(upload_async(d_tj, tj.data(), tj.size() * sizeof(TransposeF32Job), stream));
+    hipLaunchKernelGGL(transpose_f32_kernel, dim3(ttiles), dim3(256), 0, stream, d_tj, (int)tj.size());
+    ASTERIA_HIP_TRY(hipGetLastError());
+    for (int i = 0; i < 4; ++i) {
+        ASTERIA_HIP_TRY(upload_async(d_g[i], g[i].data(), g[i].size() * sizeof(GemmProblem), stream));
+        ASTERIA_HIP_TRY((launch_gemm_bf16_grouped<float, float, 2, 2>(d_g[i], (int)g[i].size(), tiles, nullptr, stream)));
     }
     return ASTERIA_OK;
 }

@@ -125,20 +125,55 @@ def test_precondition_and_soap_reject_bad_arguments_without_launching():
     assert lib.asteria_soap_step(one, 1, 0.9, 0.95, 1e-8, 1, None, 0, None) == B.WORKSPACE_TOO_SMALL
     s.ldql = 3
     assert lib.asteria_soap_step((B._SBlock * 1)(s), 1, 0.9, 0.95, 1e-8, 1, ws, 1 << 20, None) == B.INVALID_ARG
+    s.QL = None                                  # one-sided block: the leading dimension of the absent basis is not looked at
+    assert lib.asteria_soap_step((B._SBlock * 1)(s), 1, 0.9, 0.95, 1e-8, 1, None, 0, None) == B.WORKSPACE_TOO_SMALL
+    s.QR = None                                  # ... but both absent is plain Adam, not this call
+    assert lib.asteria_soap_step((B._SBlock * 1)(s), 1, 0.9, 0.95, 1e-8, 1, ws, 1 << 20, None) == B.INVALID_ARG
     assert lib.asteria_soap_refresh(None, 1, None, ws, 1 << 20, None) == B.INVALID_ARG
     assert lib.asteria_soap_refresh(_fac(ldx=2), 1, None, ws, 1 << 20, None) == B.INVALID_ARG
     assert lib.asteria_soap_refresh(_fac(), 1, None, None, 0, None) == B.WORKSPACE_TOO_SMALL
     assert lib.asteria_soap_refresh(_fac(), 1, None, ws, 128, None) == B.WORKSPACE_TOO_SMALL
-    # auxiliary streams: at most four, none null, none equal to the caller's stream
-    over = lib.asteria_soap_refresh_overlapped
+    # extended call: auxiliary streams (at most four, none null, none equal to the caller's stream), options
+    ex = lib.asteria_soap_refresh_ex
     s1, s2 = ctypes.c_void_p(0x5000), ctypes.c_void_p(0x6000)
-    two = (ctypes.c_void_p * 2)(s1, s2)
-    assert over(_fac(), 1, None, ws, 1 << 20, None, two, 5) == B.INVALID_ARG
-    assert over(_fac(), 1, None, ws, 1 << 20, None, None, 2) == B.INVALID_ARG
-    assert over(_fac(), 1, None, ws, 1 << 20, s1, two, 2) == B.INVALID_ARG
-    assert over(_fac(), 1, None, ws, 1 << 20, None, (ctypes.c_void_p * 2)(s1, None), 2) == B.INVALID_ARG
-    assert over(None, 1, None, ws, 1 << 20, None, two, 2) == B.INVALID_ARG
-    assert over(_fac(), 1, None, ws, 128, None, two, 2) == B.WORKSPACE_TOO_SMALL
+    def opts(**kw):
+        o = B.SoapRefreshOpts()
+        lib.asteria_soap_refresh_opts_default(ctypes.byref(o))
+        assert (o.sort, o.from_identity, o.rounds, o.n_aux) == (0, 0, 1, 0)
+        for k, v in kw.items():
+            setattr(o, k, v)
+        return ctypes.byref(o)
+    two = ctypes.cast((ctypes.c_void_p * 2)(s1, s2), ctypes.POINTER(ctypes.c_void_p))
+    bad = ctypes.cast((ctypes.c_void_p * 2)(s1, None), ctypes.POINTER(ctypes.c_void_p))
+    assert ex(_fac(), 1, opts(n_aux=5, aux_streams=two), None, None, ws, 1 << 20, None) == B.INVALID_ARG
+    assert ex(_fac(), 1, opts(n_aux=2), None, None, ws, 1 << 20, None) == B.INVALID_ARG
+    assert ex(_fac(), 1, opts(n_aux=2, aux_streams=two), None, None, ws, 1 << 20, s1) == B.INVALID_ARG
+    assert ex(_fac(), 1, opts(n_aux=2, aux_streams=bad), None, None, ws, 1 << 20, None) == B.INVALID_ARG
+    assert ex(None, 1, opts(n_aux=2, aux_streams=two), None, None, ws, 1 << 20, None) == B.INVALID_ARG
+    assert ex(_fac(), 1, opts(n_aux=2, aux_streams=two), None, None, ws, 128, None) == B.WORKSPACE_TOO_SMALL
+    assert ex(_fac(), 1, opts(sort=2), None, None, ws, 1 << 20, None) == B.INVALID_ARG
+    assert ex(_fac(), 1, opts(rounds=0), None, None, ws, 1 << 20, None) == B.INVALID_ARG
+    perm = ctypes.c_void_p(0x7000)
+    assert ex(_fac(), 1, opts(), None, perm, ws, 1 << 20, None) == B.INVALID_ARG               # an order without sorting
+    assert ex(_fac(), 1, opts(sort=1, rounds=2), None, perm, ws, 1 << 20, None) == B.INVALID_ARG
+    # re-projection of the moments
+    rp = lib.asteria_soap_reproject
+    def rblk(**kw):
+        r = B._RBlock()
+        r.QL_old, r.QL_new, r.QR_old, r.QR_new, r.M, r.V = 0x1000, 0x2000, 0x3000, 0x4000, 0x5000, 0x6000
+        r.m = r.n = 8
+        r.ldql_old = r.ldql_new = r.ldqr_old = r.ldqr_new = r.ldm = r.ldv = 8
+        for k, v in kw.items():
+            setattr(r, k, v)
+        return (B._RBlock * 1)(r)
+    assert rp(None, 1, ws, 1 << 20, None) == B.INVALID_ARG
+    assert rp(rblk(m=0), 1, ws, 1 << 20, None) == B.INVALID_ARG
+    assert rp(rblk(M=None, V=None), 1, ws, 1 << 20, None) == B.INVALID_ARG
+    assert rp(rblk(QL_new=None), 1, ws, 1 << 20, None) == B.INVALID_ARG
+    assert rp(rblk(ldm=7), 1, ws, 1 << 20, None) == B.INVALID_ARG
+    assert rp(rblk(ldv=7), 1, ws, 1 << 20, None) == B.INVALID_ARG
+    assert rp(rblk(), 1, ws, 64, None) == B.WORKSPACE_TOO_SMALL
+    assert lib.asteria_soap_reproject_workspace_bytes(rblk(), 1) > 0
 
 
 def test_workspace_queries_scale_with_the_batch():

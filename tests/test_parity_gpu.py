@@ -806,6 +806,119 @@ def test_soap_refresh_on_caller_streams_equals_the_single_stream_call():
         assert all(same) and torch.all(info == 0), (n_aux, same)
 
 
+def spectrum_factor(n, lam, *key):
+    U = W.haar(n, DEV, *key, dtype=torch.float64)
+    A = (U * lam) @ U.T
+    return (0.5 * (A + A.T)).float().contiguous(), U.float().contiguous()
+
+
+def test_soap_refresh_with_columns_ordered_by_estimated_eigenvalue():
+    # sort = 1: the columns of the basis take the order of decreasing q^T A q before the power iteration
+    # (the order SOAP keeps its basis in).  Spectra with well separated estimates, so that the order is
+    # unique and the fp32 / fp64 estimates cannot disagree; the order is reported per factor.
+    sizes = [200, 129, 320]
+    As, Q0s = [], []
+    for i, n in enumerate(sizes):
+        lam = torch.logspace(0, -2, n, device=DEV, dtype=torch.float64)      # neighbours 2 - 4 % apart
+        A, U = spectrum_factor(n, lam, 400 + i)
+        g = torch.Generator(device=DEV).manual_seed(7 + i)
+        shuffle = torch.randperm(n, device=DEV, generator=g)
+        Q0 = U[:, shuffle].contiguous() if i < 2 else W.haar(n, DEV, 410 + i)    # shuffled eigenvectors, and a generic basis
+        As.append(A); Q0s.append(Q0)
+    Qs = [q.clone() for q in Q0s]
+    perm = torch.full((sum(sizes),), -1, dtype=torch.int32, device=DEV)
+    info = torch.full((len(sizes),), -1, dtype=torch.int32, device=DEV)
+    ast.soap_refresh(list(zip(As, Qs)), info=info, sort=True, perm=perm)
+    torch.cuda.synchronize()
+    assert torch.all(info == 0)
+    off = 0
+    for n, A, Q0, Q in zip(sizes, As, Q0s, Qs):
+        p_gpu = perm[off:off + n].cpu().numpy().astype(np.int64); off += n
+        Qsorted, p_or, est = oracle.soap_sort(np64(A), np64(Q0))
+        assert sorted(p_gpu.tolist()) == list(range(n))
+        # The order is unique where the estimates are apart; columns whose estimates agree to fp32
+        # round-off (a generic basis has many: every estimate is near tr A / n) may come in either
+        # order.  So: the same column as the oracle's wherever that column's estimate is isolated, and
+        # everywhere estimates that do not increase by more than the round-off of the fp32 data.
+        tol = 2e-6 * np.abs(est).max()
+        e_gpu, e_or = est[p_gpu], est[p_or]
+        assert np.all(np.diff(e_gpu) <= tol)
+        assert np.all(np.abs(e_gpu - e_or) <= tol)
+        isolated = np.ones(n, dtype=bool)
+        isolated[1:] &= -np.diff(e_or) > 2 * tol
+        isolated[:-1] &= -np.diff(e_or) > 2 * tol
+        assert np.array_equal(p_gpu[isolated], p_or[isolated])
+        if Q0 is Q0s[0] or Q0 is Q0s[1]:
+            assert isolated.all() and np.array_equal(p_gpu, p_or)      # shuffled eigenvectors: estimates = eigenvalues, all apart
+        # the refresh itself, stage-wise: the oracle refreshes the basis in the order the GPU chose
+        Qo, Ro = oracle.soap_refresh(np64(A), np64(Q0)[:, p_gpu])
+        q = np64(Q)
+        Z = np64(A) @ np64(Q0)[:, p_gpu]
+        assert np.linalg.norm(q.T @ q - np.eye(n)) / math.sqrt(n) <= 1e-5
+        Rm = q.T @ Z
+        assert np.linalg.norm(np.tril(Rm, -1)) <= 1e-5 * np.linalg.norm(Z)
+        assert np.linalg.norm(q @ np.triu(Rm) - Z) <= 1e-5 * np.linalg.norm(Z)
+        lead = 32
+        assert np.all(np.sum(q[:, :lead] * Qo[:, :lead], axis=0) >= 0.999)
+
+
+def test_soap_refresh_from_the_identity_in_several_sorted_rounds_approaches_the_eigenbasis():
+    # the device-side start of the basis: Q = I, then rounds of (sort, power iteration, QR) - orthogonal
+    # iteration.  The oracle takes the same steps; after a few rounds the leading columns are the leading
+    # eigenvectors of the oracle's Jacobi decomposition.
+    n, rounds = 160, 6
+    lam = torch.cat([torch.tensor([10.0, 5.0, 2.5, 1.2], device=DEV, dtype=torch.float64),
+                     torch.linspace(0.1, 0.01, n - 4, device=DEV, dtype=torch.float64)])
+    A, _ = spectrum_factor(n, lam, 420)
+    Q = torch.full((n, n), float("nan"), device=DEV)                  # ignored: the call starts from the identity
+    info = torch.full((1,), -1, dtype=torch.int32, device=DEV)
+    ast.soap_refresh([(A, Q)], info=info, sort=True, from_identity=True, rounds=rounds)
+    torch.cuda.synchronize()
+    assert info.item() == 0
+    Qo = np.eye(n)
+    for _ in range(rounds):
+        Qo, _, _ = oracle.soap_sort(np64(A), Qo)
+        Qo, _ = oracle.soap_refresh(np64(A), Qo)
+    q = np64(Q)
+    assert np.linalg.norm(q.T @ q - np.eye(n)) / math.sqrt(n) <= 1e-5
+    assert np.all(np.abs(np.sum(q[:, :4] * Qo[:, :4], axis=0)) >= 0.999)
+    lamJ, VJ, _ = oracle.jacobi_eigh(np64(A))
+    order = np.argsort(-lamJ)
+    assert np.all(np.abs(np.sum(q[:, :4] * VJ[:, order[:4]], axis=0)) >= 0.999)
+
+
+def test_soap_reproject_carries_the_moments_to_the_new_bases():
+    shapes = [(200, 328), (64, 64), (257, 130), (1, 5)]
+    items, refs, keep = [], [], []
+    for i, (m, n) in enumerate(shapes):
+        QLo, QLn = W.haar(m, DEV, 500 + i), W.haar(m, DEV, 510 + i)
+        QRo, QRn = W.haar(n, DEV, 520 + i), W.haar(n, DEV, 530 + i)
+        M = padded(m, n, 3); M.copy_(W.gaussian_block(m, n, 1.0, DEV, 540 + i))
+        V = padded(m, n, 1); V.copy_(W.gaussian_block(m, n, 1.0, DEV, 550 + i) ** 2)
+        g = torch.Generator(device=DEV).manual_seed(60 + i)
+        pl = torch.randperm(m, device=DEV, generator=g).to(torch.int32)
+        pr = torch.randperm(n, device=DEV, generator=g).to(torch.int32)
+        refs.append((oracle.soap_reproject(np64(M), np64(QLo), np64(QRo), np64(QLn), np64(QRn)),
+                     np64(V)[pl.cpu().numpy().astype(np.int64)][:, pr.cpu().numpy().astype(np.int64)]))
+        items.append((QLo, QLn, QRo, QRn, M, V, pl, pr if i != 1 else None))
+        if i == 1:
+            refs[-1] = (refs[-1][0], np64(V)[pl.cpu().numpy().astype(np.int64)])
+    ast.soap_reproject(items)
+    torch.cuda.synchronize()
+    for (QLo, QLn, QRo, QRn, M, V, pl, pr), (Mo, Vo) in zip(items, refs):
+        print("reproject", tuple(M.shape), relF(M, Mo))
+        assert relF(M, Mo) <= 1e-4                    # two bf16 terms per operand: 16 bits kept
+        assert np.array_equal(np64(V), Vo)            # a pure reordering
+        assert torch.all(M._base[:, M.shape[1]:] == -777.0) and torch.all(V._base[:, V.shape[1]:] == -777.0)
+    # only V, only M
+    m, n = 40, 24
+    V = W.gaussian_block(m, n, 1.0, DEV, 570); V0 = V.clone()
+    pl = torch.arange(m - 1, -1, -1, device=DEV, dtype=torch.int32)
+    ast.soap_reproject([(None, None, None, None, None, V, pl, None)])
+    torch.cuda.synchronize()
+    assert torch.equal(V, V0.flip(0))
+
+
 def test_soap_refresh_rank_deficient_products():
     # A Q of rank < n: a numerically dependent column (m x m statistic of one m x n gradient, n < m)
     # still yields an orthogonal Q whose leading columns are the oracle's - what is left of such a
@@ -889,6 +1002,37 @@ def test_soap_step_whole_tile_blocks_mixed_with_ragged_ones():
             print("soap step whole tiles", shapes[i], t, relF(M, Mo), relF(V, Vo), relF(N, No))
             assert relF(M, Mo) <= 2e-4 and relF(V, Vo) <= 2e-4
             assert relF(N, No) <= TOL_PRECOND, (t, i, relF(N, No))
+            assert torch.all(N._base[:, N.shape[1]:] == -777.0)
+
+
+def test_soap_step_one_sided_blocks():
+    # a block that keeps a basis on one side only (the other dimension is above the preconditioner cap):
+    # QL or QR absent stands for the identity; mixed with a two-sided block in one call
+    cases = [(200, 328, torch.bfloat16, "L"), (129, 70, torch.float32, "R"), (64, 256, torch.float32, "L"),
+             (257, 130, torch.bfloat16, "R"), (128, 128, torch.bfloat16, "LR")]
+    state = []
+    for i, (m, n, dt, side) in enumerate(cases):
+        QL = W.haar(m, DEV, 600 + i) if "L" in side else None
+        QR = W.haar(n, DEV, 610 + i) if "R" in side else None
+        M = torch.zeros(m, n, device=DEV); V = torch.zeros(m, n, device=DEV); N = padded(m, n, 2)
+        state.append((QL, QR, M, V, N))
+    for t in (1, 2):
+        items, Gs = [], []
+        for i, (m, n, dt, side) in enumerate(cases):
+            QL, QR, M, V, N = state[i]
+            G = W.soap_gradient(W.haar(m, DEV, 620 + i), W.haar(n, DEV, 630 + i), t, DEV, i, dtype=dt)
+            Gs.append(G)
+            items.append((G, QL, QR, M, V, N))
+        Min = [np64(s[2]) for s in state]; Vin = [np64(s[3]) for s in state]
+        ast.soap_step(items, 0.9, 0.95, 1e-8, t)
+        torch.cuda.synchronize()
+        for i, (m, n, dt, side) in enumerate(cases):
+            QL, QR, M, V, N = state[i]
+            ql = np64(QL) if QL is not None else np.eye(m)
+            qr = np64(QR) if QR is not None else np.eye(n)
+            No, Mo, Vo = oracle.soap_step(np64(Gs[i]), ql, qr, Min[i], Vin[i], 0.9, 0.95, 1e-8, t)
+            print("one-sided soap step", cases[i], t, relF(M, Mo), relF(V, Vo), relF(N, No))
+            assert relF(M, Mo) <= 2e-4 and relF(V, Vo) <= 2e-4 and relF(N, No) <= TOL_PRECOND
             assert torch.all(N._base[:, N.shape[1]:] == -777.0)
 
 
