@@ -249,6 +249,7 @@ def main() -> int:
     ap.add_argument("--schedule", type=int, default=1, help="1 = interval-adapted coefficients, 0 = classical Newton")
     ap.add_argument("--sections", default=",".join(ALL_SECTIONS),
                     help="comma-separated subset of " + ",".join(ALL_SECTIONS) + " (shampoo always runs)")
+    ap.add_argument("--soap-groups", type=int, default=2, help="auxiliary streams the SOAP refresh deals its factors to (1..4)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-soap", action="store_true", help="skip the SOAP section (blocks <= 2048)")
     ap.add_argument("--save-inputs", default="", help="generate the headline workload's gradients, write them to this file and exit")
@@ -524,7 +525,7 @@ def soap_section(args, torch, ast, W, dev):
     torch.cuda.synchronize()
     log(f"[bench] soap: {len(shapes)} blocks, {len(factors)} factors, workspace {need / 2**30:.1f} GiB, "
         f"{torch.cuda.memory_allocated() / 2**30:.1f} GiB resident")
-    aux = [torch.cuda.Stream(), torch.cuda.Stream()]   # two groups of factors side by side (default priority)
+    aux = [torch.cuda.Stream() for _ in range(max(1, min(4, args.soap_groups)))]   # groups of factors side by side (default priority)
     for w in range(3):                          # warm the bases from the identity
         ast.stats_update(blocks[w % nsets], beta, ws=ws)
         ast.soap_refresh(factors, info=info, ws=ws, aux_streams=aux)

@@ -902,16 +902,22 @@ extern "C" asteria_status asteria_soap_refresh_ex(const asteria_factor *f, int n
             for (int sweep = 0; sweep < 3; ++sweep) {
                 const int *st = sweep < 2 ? st_run : st_third;
                 if (j > 0) {
-                    // projection coefficients: fp32 operands as two fp16 terms each (2^-22) in the two
-                    // regular sweeps; the rare third sweep stays on the fp32 cores
-                    if (sweep < 2)
+                    // projection coefficients: fp32 operands as two fp16 terms each (2^-22) in the second
+                    // sweep; the rare third sweep stays on the fp32 cores
+                    // first sweep: the coefficients as one fp16 term per operand, and one term of them in
+                    // the update (the finished rows keep both terms, so the panel stays in the span of
+                    // its own rows and the finished ones to 2^-22): what this leaves along the finished
+                    // rows, 2^-11 of the coefficients, is what the second sweep removes at full accuracy
+                    if (sweep == 0) {
+                        ASTERIA_HIP_TRY((launch_gemm_bf16_grouped<float, float, 1, 1, true>(d_t1[j], (int)t1[j].size(), tiles1[j], st, stream)));
+                        ASTERIA_HIP_TRY((launch_gemm_bf16_grouped<float, float, 1, 2, true>(d_t2[j], (int)t2[j].size(), tiles2[j], st, stream)));
+                    } else if (sweep == 1) {
                         ASTERIA_HIP_TRY((launch_gemm_bf16_grouped<float, float, 2, 2, true>(d_t1[j], (int)t1[j].size(), tiles1[j], st, stream)));
-                    else
-                        ASTERIA_HIP_TRY((launch_gemm_grouped<float, float, float, false, false>(d_t1[j], (int)t1[j].size(), tiles1[j], st, stream)));
-                    if (sweep < 2)
                         ASTERIA_HIP_TRY((launch_gemm_bf16_grouped<float, float, 2, 2, true>(d_t2[j], (int)t2[j].size(), tiles2[j], st, stream)));
-                    else
+                    } else {
+                        ASTERIA_HIP_TRY((launch_gemm_grouped<float, float, float, false, false>(d_t1[j], (int)t1[j].size(), tiles1[j], st, stream)));
                         ASTERIA_HIP_TRY((launch_gemm_grouped<float, float, float, false, false>(d_t2[j], (int)t2[j].size(), tiles2[j], st, stream)));
+                    }
                 }
                 ASTERIA_HIP_TRY((launch_gemm_grouped<double, float, float, false, false>(d_t3[j], (int)t3[j].size(), (int)t3[j].size(), st, stream)));
                 hipLaunchKernelGGL(panel_chol_inverse_kernel, dim3((unsigned)fidx[j].size()), dim3(CHOL_THREADS), chol_lds, stream, d_q, d_fidx[j], j, sweep);
