@@ -207,21 +207,41 @@ asteria_status asteria_sym_pack(const asteria_sympair *items, int nitems, void *
 asteria_status asteria_sym_unpack(const asteria_sympair *items, int nitems, void *stream);
 
 /* ---- inverse p-th roots (paper Eq. 1, Sec. III-B) ------------------------------------------
- * For every factor: X = ((A + A^T)/2 + eps I)^(-1/root), root in {2, 4} (4 = Eq. 1), by a
- * coupled matrix iteration run entirely on the device:  lambda_max by power iteration;
- * M_0 = s (A + eps I), X_0 = s^(1/root) I with s = 1 / ((1 + margin) lambda_max + eps), so the
- * spectrum of M_0 lies in [~eps s, 1];  T = a I - g M, X <- X T, M <- T^root M, where (a, g)
- * are chosen per factor and iteration for the interval that holds M's spectrum (or fixed at the
- * Newton values, see `schedule`); a factor stops by itself - one more X update follows - once its
- * residual ||M - I||_F has fallen below stop_resid or the interval predicted for M's spectrum is
- * within 1 +- 1e-2 (and, under the automatic precision rules, already when the image of that
- * interval under the next update is within 1 +- 3e-3).  The leading fp64_iters iterations work
- * on fp64 matrices - their products on the int8 matrix cores from integer slices of the operands,
- * exact sums, fp64 assembly, or on the fp64 matrix cores, see `int8_slices` -, the middle ones use
- * the fp32 matrix cores, and the last ones (from
- * `lowp_from` on) the fp16 matrix cores with every fp32 operand split into two fp16 terms (scaled
- * into the fp16 range by a power of two that the call derives from the bounds it keeps on M and X;
- * the operands are kept to 2^-22).
+ * For every factor: X = ((A + A^T)/2 + eps I)^(-1/root), root in {2, 4} (4 = Eq. 1), by a coupled
+ * matrix iteration run entirely on the device.
+ *
+ *   step                what the device does
+ *   ------------------  --------------------------------------------------------------------------
+ *   lambda_max          power iteration on A, stopped per factor at ||A v - rho v|| <= power_tol rho
+ *   scaling             s = 1 / ((1 + margin) lambda_max + eps); M_0 = s (A + eps I), X_0 = s^(1/root) I;
+ *                       the spectrum of M_0 is taken to lie in [eps s / 2, 1]
+ *   iteration           T = a I - g M, X <- X T, M <- T^root M; (a, g) per factor and iteration from
+ *                       the interval that holds M's spectrum (`schedule` = 1) or the Newton values
+ *   stop (per factor)   one more X update follows once ||M - I||_F < stop_resid, or once the interval
+ *                       predicted for M's spectrum is within 1 +- 1e-2 and the measured residual is
+ *                       consistent with it; under the automatic precision rules already when the image
+ *                       of that interval under the next update is within 1 +- 3e-3
+ *
+ *   iterations          matrices  products run on
+ *   ------------------  --------  ----------------------------------------------------------------
+ *   first fp64_iters    fp64      int8 matrix cores (diagonal + 7-bit slices, exact integer sums, fp64
+ *                                 assembly) or fp64 matrix cores, per factor and product: `int8_slices`
+ *   up to lowp_from     fp32      fp32 matrix cores
+ *   from lowp_from on   fp32      fp16 matrix cores, every operand split into two fp16 terms (kept to
+ *                                 2^-22), scaled into the fp16 range by powers of two derived from the
+ *                                 bounds the call keeps on M and X
+ *
+ * What the interval-based choices rely on.  A is positive semi-definite up to round-off: eigenvalues
+ * down to -eps / 2 are covered by the lower end eps s / 2 (statistics accumulated in fp32 can fall
+ * further below zero when eps is of the order of 1e-8 lambda_max: accumulate those with
+ * ASTERIA_ACC_F64).  The power iteration's stop test bounds the distance of rho to SOME eigenvalue;
+ * rho is taken for lambda_max, and `lambda_margin` (1 %) is the allowance for the difference.  If
+ * either assumption fails for a factor - an eigenvalue of M_0 outside [eps s / 2, 1] - the predicted
+ * interval is wrong for it: the measured residual then disagrees with the prediction, the factor
+ * falls back to the residual rule and runs until ||M - I||_F < stop_resid or max_iters, where it
+ * reports ASTERIA_INFO_NOT_CONVERGED; a residual that still agrees within its tolerance
+ * (1.5 sqrt(n) times the predicted deviation + 2e-3) can hide one stray eigenvalue that far from 1.
+ *
  *   eps        host array, eps_count entries (1 = shared by all factors, else nfactors).
  *   info       device int32[nfactors] or NULL   (ASTERIA_INFO_*)
  *   iters      device int32[nfactors] or NULL   (number of X <- X T updates performed)

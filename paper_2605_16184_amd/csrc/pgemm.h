@@ -1,23 +1,22 @@
-// Grouped GEMM over pre-split bf16 matrices on the gfx950 matrix cores
+// Guard-free grouped GEMM over bf16 terms on the gfx950 matrix cores
 // (v_mfma_f32_32x32x16_bf16, fp32 accumulation).
 //
-// Split format.  A real matrix is kept as NT bf16 terms whose sum approximates it: term 0 is
-// the value rounded to bf16, term 1 the rounded remainder (8 / 16 significant bits for NT = 1 /
-// 2).  The terms are interleaved along k in groups of 32: a row stores, for every 32
-// consecutive k, NT segments of 32 bf16 (64 bytes) - term 0's values, then term 1's.  Element
-// (r, k) of term t sits at  r * ld + (k / 32) * (32 NT) + t * 32 + k % 32.  With NT = 2 one
-// k-group of a row is exactly one 128-byte cache line, which is what the vector L1 wants: row
-// pieces of 64 bytes run at half the load bandwidth (measured 17 against 34 TB/s from L2).
-// The producer of a matrix writes this format once in its epilogue, so the K loop of the
-// consumer is a pure bf16 GEMM: 16-byte global loads, 16-byte LDS stores, no per-element
-// arithmetic.  A product of two split matrices is the sum of the term-pair products selected
-// by a compile-time mask; every pair is an exact bf16 x bf16 product accumulated in fp32.
+// Operands.  A real matrix enters the product as NT bf16 terms whose sum approximates it: term 0
+// is the value rounded to bf16, term 1 the rounded remainder (8 / 16 significant bits for NT = 1 /
+// 2).  An operand is either a plain bf16 matrix (NT = 1), a plain fp32 matrix that the loader cuts
+// into two terms while it stages it (FA / FB), or a matrix stored as terms: interleaved along k in
+// groups of 32, a row holds, for every 32 consecutive k, NT segments of 32 bf16 (64 bytes) - term
+// 0's values, then term 1's - so that element (r, k) of term t sits at
+// r * ld + (k / 32) * (32 NT) + t * 32 + k % 32 and, with NT = 2, one k-group of a row is one
+// 128-byte cache line (row pieces of 64 bytes run at half the load bandwidth: 17 against 34 TB/s
+// from L2).  The LDS layout is that of the stored terms in every case.  A product of two operands
+// is the sum of the term-pair products selected by a compile-time mask; every pair is an exact
+// bf16 x bf16 product accumulated in fp32.
 //
 // One launch walks a device table of problems  C = alpha A B^T + beta C  (A is M x K, B is
 // N x K, both k-contiguous).  Symmetric problems compute the tiles on or below the diagonal and
-// mirror them.  Split buffers are padded: rows up to a multiple of the tile edge, K up to a
-// multiple of the slab, all padding zero - the K loop and the split stores then need no guards.
-// fp32 outputs are guarded.
+// mirror them.  Operand rows are whole tiles and K whole slabs (the callers send other shapes to
+// the guarded kernels), so the K loop has no guards; the fp32 output is guarded.
 #pragma once
 #include <type_traits>
 
@@ -29,25 +28,17 @@ typedef __bf16 pg_bf16x8 __attribute__((ext_vector_type(8)));
 
 constexpr int PG_GROUP = 32;   // k values per interleave group
 
-// leading dimension (elements) of a split matrix with nt terms and k_pad (multiple of 32) columns
-inline int pg_ld(int k_pad, int nt) { return k_pad * nt; }
-
 struct PlaneProblem {
     const void *A;          // split / bf16 matrix (NTA terms), or fp32 matrix when the shape says so
     const void *B;          // the same for B
-    float *C32;             // fp32 output, or null
-    uint16_t *Cp;           // split output (c_terms terms), or null
-    uint16_t *Tp;           // root epilogue: split T' = a I - g C, or null
-    float *partial;         // root epilogue: per-tile sum (C - I)^2
-    const float *coef;      // root epilogue: device (a, g), or null for ep_a / ep_g
+    float *C32;             // fp32 output
     int M, N, K;
-    int lda, ldb, ldc32, ldcp, ldtp;   // elements
+    int lda, ldb, ldc32;    // elements
     int tile_start;
     int tiles_n;            // tile columns (non-symmetric problems)
     int state_idx, state_mask;
-    float alpha, beta, ep_a, ep_g;
-    int flags;              // GEMM_SYM, GEMM_EPI_ROOT, GEMM_STORE_T (fp32 output stored transposed, no beta), PG_KMAJOR
-    int c_terms;            // terms of Cp / Tp (1 or 2)
+    float alpha, beta;
+    int flags;              // GEMM_SYM, GEMM_C_PACKED, GEMM_STORE_T (output stored transposed, no beta), PG_KMAJOR
 };
 
 // pair (ta, tb) of an NTA x NTB split product is issued iff bit ta * 2 + tb of PAIRS is set
@@ -126,7 +117,6 @@ __device__ __forceinline__ uint32_t pg_pack_bf16(float a, float b)
     const __bf16 x = (__bf16)a, y = (__bf16)b;   // v_cvt_pk_bf16_f32: round to nearest even
     return (uint32_t)__builtin_bit_cast(uint16_t, x) | ((uint32_t)__builtin_bit_cast(uint16_t, y) << 16);
 }
-__device__ __forceinline__ float pg_bf16_round(float a) { return (float)(__bf16)a; }
 
 // Global -> register -> LDS staging of one operand's slab pieces.  Pre-split / bf16 source: one
 // 16-byte chunk per item, stored as loaded.  fp32 source: an item is 8 consecutive fp32 (two
@@ -199,73 +189,33 @@ struct PgLoader {
 };
 
 
-// offset (elements) of (row, col, term 0) in a split matrix; col is a multiple of 8
-__device__ __forceinline__ size_t pg_off(int row, int col, int ld, int nt)
-{
-    return (size_t)row * ld + (size_t)(col / PG_GROUP) * (PG_GROUP * nt) + (col % PG_GROUP);
-}
-
-// Split 8 fp32 values at (row, col .. col + 7) into nt terms and store them (16 bytes per term).
-__device__ __forceinline__ void pg_store_split(uint16_t *base, int row, int col, int ld, int nt, const float (&v)[8])
-{
-    uint16_t *p = base + pg_off(row, col, ld, nt);
-    u32x4 w;
-#pragma unroll
-    for (int e = 0; e < 4; ++e) w[e] = pg_pack_bf16(v[2 * e], v[2 * e + 1]);
-    *(ASTERIA_GLOBAL u32x4 *)p = w;
-    if (nt > 1) {
-        float r[8];
-#pragma unroll
-        for (int e = 0; e < 8; ++e) r[e] = v[e] - pg_bf16_round(v[e]);   // exact in fp32
-#pragma unroll
-        for (int e = 0; e < 4; ++e) w[e] = pg_pack_bf16(r[2 * e], r[2 * e + 1]);
-        *(ASTERIA_GLOBAL u32x4 *)(p + PG_GROUP) = w;
-    }
-}
-
-// One finished row piece of 8 values at (grow, gcol .. gcol + 7): apply beta, store every
-// requested output, accumulate the residual.
+// One finished row piece of 8 values at (grow, gcol .. gcol + 7): apply beta, store.
 // `ctile`: for packed lower-tile output the base of the 128 x 128 tile this piece belongs to (row lr of
 // it, 128 floats per row), else null (row-major output at C32 + grow ldc32).
 __device__ __forceinline__ void pg_emit(const PlaneProblem &P, int grow, int gcol, int rlim, int clim, float (&val)[8],
-                                        bool root, float ep_a, float ep_g, float &rsum, float *ctile = nullptr)
+                                        float *ctile = nullptr)
 {
-    if (P.C32) {
-        if (grow < rlim) {
-            float *c = ctile ? ctile + (size_t)(grow % PACK_T) * PACK_T + (gcol % PACK_T) : P.C32 + (size_t)grow * P.ldc32 + gcol;
-            const bool vec = (gcol + 8 <= clim) && (ctile || (P.ldc32 & 3) == 0) && ((reinterpret_cast<uintptr_t>(P.C32) & 15u) == 0);
-            if (vec) {
-                ASTERIA_GLOBAL floatx4 *c4 = (ASTERIA_GLOBAL floatx4 *)c;
-                if (P.beta != 0.0f) {
-                    const floatx4 o0 = c4[0], o1 = c4[1];
+    if (grow >= rlim) return;
+    float *c = ctile ? ctile + (size_t)(grow % PACK_T) * PACK_T + (gcol % PACK_T) : P.C32 + (size_t)grow * P.ldc32 + gcol;
+    const bool vec = (gcol + 8 <= clim) && (ctile || (P.ldc32 & 3) == 0) && ((reinterpret_cast<uintptr_t>(P.C32) & 15u) == 0);
+    if (vec) {
+        ASTERIA_GLOBAL floatx4 *c4 = (ASTERIA_GLOBAL floatx4 *)c;
+        if (P.beta != 0.0f) {
+            const floatx4 o0 = c4[0], o1 = c4[1];
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) { val[e] += P.beta * o0[e]; val[4 + e] += P.beta * o1[e]; }
-                }
-                floatx4 s0, s1;
+            for (int e = 0; e < 4; ++e) { val[e] += P.beta * o0[e]; val[4 + e] += P.beta * o1[e]; }
+        }
+        floatx4 s0, s1;
 #pragma unroll
-                for (int e = 0; e < 4; ++e) { s0[e] = val[e]; s1[e] = val[4 + e]; }
-                c4[0] = s0; c4[1] = s1;
-            } else {
+        for (int e = 0; e < 4; ++e) { s0[e] = val[e]; s1[e] = val[4 + e]; }
+        c4[0] = s0; c4[1] = s1;
+    } else {
 #pragma unroll
-                for (int e = 0; e < 8; ++e)
-                    if (gcol + e < clim) {
-                        if (P.beta != 0.0f) val[e] += P.beta * c[e];
-                        c[e] = val[e];
-                    }
+        for (int e = 0; e < 8; ++e)
+            if (gcol + e < clim) {
+                if (P.beta != 0.0f) val[e] += P.beta * c[e];
+                c[e] = val[e];
             }
-        }
-    }
-    if (P.Cp) pg_store_split(P.Cp, grow, gcol, P.ldcp, P.c_terms, val);
-    if (root) {
-        float t[8];
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const float d = (grow == gcol + e && grow < P.M) ? 1.0f : 0.0f;
-            t[e] = ep_a * d - ep_g * val[e];
-            const float er = val[e] - d;
-            rsum += er * er;
-        }
-        if (P.Tp) pg_store_split(P.Tp, grow, gcol, P.ldtp, P.c_terms, t);
     }
 }
 
@@ -532,35 +482,31 @@ __global__ __launch_bounds__(S::NTHR) void pgemm_kernel(const PlaneProblem *__re
             }
             if (grp == 0) phase_barrier();
         } else {
-        gload(std::integral_constant<int, 0>{}, 0);
-        if constexpr (DEPTH > 1) { if (1 < nk) gload(std::integral_constant<int, 1>{}, 1); }
-        if constexpr (DEPTH > 2) { if (2 < nk) gload(std::integral_constant<int, 2>{}, 2); }
-        lstore(std::integral_constant<int, 0>{}, 0);
-        if (DEPTH < nk) gload(std::integral_constant<int, 0>{}, DEPTH);
-        pg_lds_barrier();
-        for (int kt0 = 0; kt0 < nk; kt0 += DEPTH) {
-            // slab kt + 1 lives in set (kt + 1) % DEPTH
-            if constexpr (DEPTH == 1) {
-                iteration(std::integral_constant<int, 0>{}, kt0);
-            } else {
-                iteration(std::integral_constant<int, 1>{}, kt0);
-                if constexpr (DEPTH > 2) { if (kt0 + 1 < nk) iteration(std::integral_constant<int, 2>{}, kt0 + 1); }
-                if (kt0 + DEPTH - 1 < nk) iteration(std::integral_constant<int, 0>{}, kt0 + DEPTH - 1);
+            gload(std::integral_constant<int, 0>{}, 0);
+            if constexpr (DEPTH > 1) { if (1 < nk) gload(std::integral_constant<int, 1>{}, 1); }
+            if constexpr (DEPTH > 2) { if (2 < nk) gload(std::integral_constant<int, 2>{}, 2); }
+            lstore(std::integral_constant<int, 0>{}, 0);
+            if (DEPTH < nk) gload(std::integral_constant<int, 0>{}, DEPTH);
+            pg_lds_barrier();
+            for (int kt0 = 0; kt0 < nk; kt0 += DEPTH) {
+                // slab kt + 1 lives in set (kt + 1) % DEPTH
+                if constexpr (DEPTH == 1) {
+                    iteration(std::integral_constant<int, 0>{}, kt0);
+                } else {
+                    iteration(std::integral_constant<int, 1>{}, kt0);
+                    if constexpr (DEPTH > 2) { if (kt0 + 1 < nk) iteration(std::integral_constant<int, 2>{}, kt0 + 1); }
+                    if (kt0 + DEPTH - 1 < nk) iteration(std::integral_constant<int, 0>{}, kt0 + DEPTH - 1);
+                }
             }
-        }
         }
     }
 
     // ---- epilogue: 128 x 128 quadrants through an fp32 LDS tile ----------------------------------
-    const bool root = (P.flags & GEMM_EPI_ROOT) != 0;
-    const float ep_a = (root && P.coef) ? P.coef[0] : P.ep_a;
-    const float ep_g = (root && P.coef) ? P.coef[1] : P.ep_g;
     const float alpha = P.alpha;
     ASTERIA_LDS float *ct = (ASTERIA_LDS float *)smem_raw;
     constexpr int CP = S::CT_PITCH;
     constexpr int QM = TM / 128, QN = TN / 128;
     constexpr int WROWS = WTM * 32, WCOLS = WTN * 32;     // wavefront sub-tile
-    float rsum = 0.0f;
     constexpr int ITEMS = 128 * 16 / S::NTHR;             // 8-column row pieces per thread
 #pragma unroll 1
     for (int q = 0; q < QM * QN; ++q) {
@@ -624,23 +570,9 @@ __global__ __launch_bounds__(S::NTHR) void pgemm_kernel(const PlaneProblem *__re
 #pragma unroll
                     for (int e = 0; e < 4; ++e) { val[e] = v0[e]; val[4 + e] = v1[e]; }
                 }
-                pg_emit(P, orow0 + lr, ocol0 + lc, pass == 0 ? P.M : P.N, pass == 0 ? P.N : P.M, val, root, ep_a, ep_g, rsum, ctile);
+                pg_emit(P, orow0 + lr, ocol0 + lc, pass == 0 ? P.M : P.N, pass == 0 ? P.N : P.M, val, ctile);
             }
             __syncthreads();
-        }
-    }
-    if (root) {
-        // every element of the output (both triangles) was visited exactly once
-#pragma unroll
-        for (int off = 32; off > 0; off >>= 1) rsum += __shfl_xor(rsum, off, 64);
-        float *red = reinterpret_cast<float *>(smem_raw);
-        if (lane == 0) red[wave] = rsum;
-        __syncthreads();
-        if (tid == 0) {
-            float t = 0.0f;
-#pragma unroll
-            for (int w = 0; w < S::NTHR / 64; ++w) t += red[w];
-            P.partial[lt] = t;
         }
     }
 }

@@ -98,7 +98,7 @@ extern "C" asteria_status asteria_precondition(const asteria_pblock *blocks, int
                 q.M = k.m; q.N = k.n; q.K = k.m;
                 q.tiles_n = k.n / PgF32x2::TN;
                 q.tile_start = tiles2f; tiles2f += (k.m / PgF32x2::TM) * q.tiles_n;
-                q.state_idx = -1; q.state_mask = ~0; q.alpha = 1.0f; q.beta = 0.0f; q.c_terms = 1;
+                q.state_idx = -1; q.state_mask = ~0; q.alpha = 1.0f; q.beta = 0.0f;
                 p2f.push_back(q);
             } else {
                 p.A = k.XL; p.lda = k.ldxl; p.B = Ut; p.ldb = ldu; p.C = k.P; p.ldc = k.ldp;

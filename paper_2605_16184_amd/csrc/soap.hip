@@ -565,7 +565,7 @@ extern "C" asteria_status asteria_soap_step(const asteria_sblock *blocks, int nb
             PlaneProblem q;
             memset(&q, 0, sizeof(q));
             q.M = k.m; q.N = k.n; q.tiles_n = k.n / PgF32x2::TN; q.tile_start = tilesf;
-            q.state_idx = -1; q.state_mask = ~0; q.alpha = 1.0f; q.beta = 0.0f; q.c_terms = 1;
+            q.state_idx = -1; q.state_mask = ~0; q.alpha = 1.0f; q.beta = 0.0f;
             q.K = k.m; q.A = QLt; q.lda = ldqlt; q.B = Tt; q.ldb = ldt; q.C32 = Gr; q.ldc32 = ldw; q.flags = 0;
             f2.push_back(q);
             q.K = k.n; q.A = Np; q.lda = ldw; q.B = k.QR; q.ldb = k.ldqr; q.C32 = Tt; q.ldc32 = ldt; q.flags = GEMM_STORE_T;

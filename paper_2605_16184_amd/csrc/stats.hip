@@ -101,7 +101,7 @@ inline PlaneProblem fast_problem(const void *G, int rows, int k, int ld, float *
     q.state_idx = -1; q.state_mask = ~0;
     q.alpha = 1.0f - beta; q.beta = beta;
     q.flags = GEMM_SYM | (packed ? GEMM_C_PACKED : 0);
-    q.c_terms = 1;
+   
     return q;
 }
 
