@@ -162,7 +162,9 @@ def gemm_rooflines(res, steps, step_ms):
     """Per GEMM kernel of the refresh: algorithmic flops its launches executed / the sum of their
     durations, against the published dense peak of the instruction it issues.  A launch that found
     every factor finished (or, for the fp64 fall-back grid, every product taken by the int8 path)
-    does no work; such launches are counted and their (microsecond) durations left out of the rates."""
+    does no work; such launches are counted and their (microsecond) durations left out of the rates.
+    `avg_launch_ms` is the mean over the launches that worked, `avg_launch_ms_all` the mean over every launch
+    (what a profiler's per-kernel average shows)."""
     prof, flops, i8f = res["prof"], res["flops"], res["i8_flops"]
     def split(kinds):
         ms = [t for t, k in prof if k in kinds]
@@ -185,7 +187,7 @@ def gemm_rooflines(res, steps, step_ms):
                                 "bound": "mfma", "achieved": round(tf, 2), "peak": PEAK_F32_MFMA, "unit": "TFLOP/s",
                                 "frac": round(tf / PEAK_F32_MFMA, 4), "traffic": stored_traffic("traffic_bytes_per_launch_fp32"),
                                 "launches": len(all32), "working_launches": len(w32),
-                                "avg_launch_ms": round(1e3 * t32 / len(w32), 4), "flops_per_launch": round(flops["fp32"] / len(w32), 1)}
+                                "avg_launch_ms": round(1e3 * t32 / len(w32), 4), "avg_launch_ms_all": round(sum(all32) / len(all32), 4), "flops_per_launch": round(flops["fp32"] / len(w32), 1)}
         shares["roofline_fp32"] = t32
     if w64 and f64_cores > 0:
         tf = f64_cores / t64 / 1e12
@@ -194,7 +196,7 @@ def gemm_rooflines(res, steps, step_ms):
                                 "frac": round(tf / PEAK_F64_MFMA, 4), "traffic": stored_traffic("traffic_bytes_per_launch_fp64"),
                                 "instruction_loop_tflops_measured": MEASURED_F64_MFMA_LOOP,
                                 "launches": len(all64), "working_launches": len(w64),
-                                "avg_launch_ms": round(1e3 * t64 / len(w64), 4), "flops_per_launch": round(f64_cores / len(w64), 1)}
+                                "avg_launch_ms": round(1e3 * t64 / len(w64), 4), "avg_launch_ms_all": round(sum(all64) / len(all64), 4), "flops_per_launch": round(f64_cores / len(w64), 1)}
         shares["roofline_fp64"] = t64
     if w16 and flops["fp16"] > 0:
         tf = flops["fp16"] / t16 / 1e12
@@ -205,7 +207,7 @@ def gemm_rooflines(res, steps, step_ms):
             "frac": round(3 * tf / PEAK_BF16_MFMA, 4),
             "fp32_equivalent_tflops": round(tf, 2), "useful_frac": round(tf / PEAK_BF16_MFMA, 4),
             "traffic": stored_traffic("traffic_bytes_per_launch_fp16"), "launches": len(all16), "working_launches": len(w16),
-            "avg_launch_ms": round(1e3 * t16 / len(w16), 4), "flops_per_launch": round(3 * flops["fp16"] / len(w16), 1)}
+            "avg_launch_ms": round(1e3 * t16 / len(w16), 4), "avg_launch_ms_all": round(sum(all16) / len(all16), 4), "flops_per_launch": round(3 * flops["fp16"] / len(w16), 1)}
         shares["roofline_split_fp16"] = t16
     if w8 and f_i8_4 + f_i8_5 > 0:
         ops = 10.0 * f_i8_4 + 15.0 * f_i8_5                # int8 MFMA passes per product: 10 with 4 slices, 15 with 5
@@ -220,7 +222,7 @@ def gemm_rooflines(res, steps, step_ms):
             "flops_share_4_slices": round(f_i8_4 / useful, 4), "flops_share_5_slices": round(f_i8_5 / useful, 4),
             "flops_share_declined_to_fp64_cores": round(f64_cores / (useful + f64_cores), 6),
             "traffic": stored_traffic("traffic_bytes_per_launch_int8"), "launches": len(all8), "working_launches": len(w8),
-            "avg_launch_ms": round(1e3 * t8 / len(w8), 4), "flops_per_launch": round(ops / len(w8), 1)}
+            "avg_launch_ms": round(1e3 * t8 / len(w8), 4), "avg_launch_ms_all": round(sum(all8) / len(all8), 4), "flops_per_launch": round(ops / len(w8), 1)}
         shares["roofline_int8_slices"] = t8
     out["gemm_time_share_ms_per_step"] = {k.replace("roofline_", ""): round(1e3 * v / steps, 1) for k, v in shares.items()}
     dominant = max(shares, key=shares.get)
