@@ -539,16 +539,21 @@ def soap_section(args, torch, ast, W, dev):
         ev[t][1].record()
         ast.stats_update(blocks[t % nsets], beta, ws=ws)
         ev[t][2].record()
-    r0, r1, r2 = (torch.cuda.Event(enable_timing=True) for _ in range(3))
+    r0, r1, r2, r3 = (torch.cuda.Event(enable_timing=True) for _ in range(4))
+    torch.cuda.synchronize()                                # the device is idle: the host time of the call means something
     r0.record()
+    t_host = time.time()
     ast.soap_refresh(factors, info=info, ws=ws, aux_streams=aux)
+    enqueue_ms = 1e3 * (time.time() - t_host)               # the call returns once everything is enqueued
     r1.record()
-    ast.soap_refresh(factors, info=info, ws=ws)            # the same refresh on the caller's stream alone
+    torch.cuda.synchronize()
     r2.record()
+    ast.soap_refresh(factors, info=info, ws=ws)            # the same refresh on the caller's stream alone
+    r3.record()
     torch.cuda.synchronize()
     step_ms = sum(e[0].elapsed_time(e[1]) for e in ev) / args.steps
     stats_ms = sum(e[1].elapsed_time(e[2]) for e in ev) / args.steps
-    refresh_ms, refresh1_ms = r0.elapsed_time(r1), r1.elapsed_time(r2)
+    refresh_ms, refresh1_ms = r0.elapsed_time(r1), r2.elapsed_time(r3)
     # sanity of the refreshed bases (fp64 check of two factors, largest first, and of up to six
     # factors that the refresh reported as failed)
     def orth_of(Q):
@@ -574,7 +579,7 @@ def soap_section(args, torch, ast, W, dev):
                         "+-30% sigma jitter, 10% dense noise; beta1=0.9, beta2=0.95",
             "blocks": len(shapes), "factors": len(factors),
             "soap_step_ms": round(step_ms, 3), "stats_update_ms": round(stats_ms, 3),
-            "refresh_ms": round(refresh_ms, 3), "refresh_single_stream_ms": round(refresh1_ms, 3),
+            "refresh_ms": round(refresh_ms, 3), "refresh_single_stream_ms": round(refresh1_ms, 3), "refresh_host_enqueue_ms": round(enqueue_ms, 1),
             "amortised_step_pf10": round(step_ms + stats_ms + refresh_ms / 10, 3),
             "soap_step_tflops": round(step_flops / step_ms / 1e9, 1),
             # bf16 gradients: G Q_R issues 2 bf16 MFMA passes, the other three products 3 each (split operands)
