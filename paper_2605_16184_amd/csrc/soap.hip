@@ -968,7 +968,11 @@ extern "C" asteria_status asteria_soap_refresh_ex(const asteria_factor *f, int n
                 hipStream_t sg = reinterpret_cast<hipStream_t>(aux_streams[g2]);
                 hipEvent_t join = nullptr;
                 if (hipEventCreateWithFlags(&join, hipEventDisableTiming) != hipSuccess ||
-                    hipStreamWaitEvent(sg, fork, 0) != hipSuccess) { st = ASTERIA_HIP_ERROR; break; }
+                    hipStreamWaitEvent(sg, fork, 0) != hipSuccess) {
+                    if (join) (void)hipEventDestroy(join);
+                    st = ASTERIA_HIP_ERROR;
+                    break;
+                }
                 st = enqueue_group(grp[g2], sg);
                 if (st == ASTERIA_OK && (hipEventRecord(join, sg) != hipSuccess ||
                                          hipStreamWaitEvent(stream, join, 0) != hipSuccess)) st = ASTERIA_HIP_ERROR;
