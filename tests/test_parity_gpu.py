@@ -1046,6 +1046,58 @@ def test_soap_step_identity_bases_reduce_to_adam():
     assert relF(N, g / (np.abs(g) + 1e-8)) <= 1e-4      # 16 bits of every operand are kept (two bf16 terms)
 
 
+# =============================================================================== degenerate shapes
+
+def test_tiny_and_vector_shaped_blocks_through_every_entry_point():
+    """1 x 1, 1 x n, m x 1 and 2 x 3 blocks (a 1-D slice of a blocked matrix is such a block): every
+    stage against the oracle, all shapes in one batch beside an ordinary block."""
+    shapes = [(1, 1), (1, 37), (45, 1), (2, 3), (130, 70)]
+    Gs = [W.gaussian_block(m, n, 1.0, DEV, 77, i) for i, (m, n) in enumerate(shapes)]
+    Ls = [torch.eye(m, device=DEV) for m, n in shapes]
+    Rs = [torch.eye(n, device=DEV) for m, n in shapes]
+    L0 = [np64(x) for x in Ls]; R0 = [np64(x) for x in Rs]
+    ast.stats_update(list(zip(Gs, Ls, Rs)), 0.95)
+    torch.cuda.synchronize()
+    for G, L, R, l0, r0 in zip(Gs, Ls, Rs, L0, R0):
+        Lo, Ro = oracle.stats_update(np64(G), l0, r0, 0.95)
+        assert relF(L, Lo) <= TOL_STATS and relF(R, Ro) <= TOL_STATS
+    As = Ls + Rs
+    Xs, info, iters, _, lmax = run_roots(As, 1e-6)
+    assert np.all(info == B.INFO_OK), info
+    for A, X, lm in zip(As, Xs, lmax):
+        Xo, lmo, _ = oracle.inverse_root(np64(A), 1e-6)
+        assert relF(X, Xo) <= TOL_ROOT, (tuple(A.shape), relF(X, Xo))
+        assert abs(lm - lmo) <= 1e-3 * lmo
+    k = len(shapes)
+    Ps = [torch.full((m, n), float("nan"), device=DEV) for m, n in shapes]
+    ast.precondition(list(zip(Xs[:k], Gs, Xs[k:], Ps)))
+    torch.cuda.synchronize()
+    for XL, G, XR, P in zip(Xs[:k], Gs, Xs[k:], Ps):
+        assert relF(P, oracle.precondition(np64(XL), np64(G), np64(XR))) <= TOL_PRECOND
+    # SOAP: refresh from the identity, then one step with the refreshed bases
+    Qs = [torch.eye(A.shape[0], device=DEV) for A in As]
+    qinfo = torch.full((2 * k,), -1, dtype=torch.int32, device=DEV)
+    ast.soap_refresh(list(zip(As, Qs)), info=qinfo)
+    torch.cuda.synchronize()
+    assert np.all(qinfo.cpu().numpy() == B.INFO_OK)
+    for A, Q in zip(As, Qs):
+        n = A.shape[0]
+        Qo, _ = oracle.soap_refresh(np64(A), np.eye(n))
+        q = np64(Q)
+        assert np.linalg.norm(q.T @ q - np.eye(n)) / n ** 0.5 <= 1e-5
+        assert np.linalg.norm(q[:, :1] - Qo[:, :1]) <= 1e-4          # leading column (the whole basis for n = 1)
+    Ms = [torch.zeros(m, n, device=DEV) for m, n in shapes]
+    Vs = [torch.zeros(m, n, device=DEV) for m, n in shapes]
+    Ns = [torch.full((m, n), float("nan"), device=DEV) for m, n in shapes]
+    ast.soap_step(list(zip(Gs, Qs[:k], Qs[k:], Ms, Vs, Ns)), 0.9, 0.95, 1e-8, 1)
+    torch.cuda.synchronize()
+    for i, (m, n) in enumerate(shapes):
+        No, Mo, Vo = oracle.soap_step(np64(Gs[i]), np64(Qs[i]), np64(Qs[k + i]), np.zeros((m, n)), np.zeros((m, n)),
+                                      0.9, 0.95, 1e-8, 1)
+        assert relF(Ms[i], Mo) <= 2e-4 and relF(Vs[i], Vo) <= 2e-4, shapes[i]
+        assert relF(Ns[i], No) <= TOL_PRECOND, (shapes[i], relF(Ns[i], No))
+
+
 # =============================================================================== determinism
 
 def test_two_runs_are_bit_identical():
