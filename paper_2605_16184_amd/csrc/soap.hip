@@ -222,7 +222,8 @@ __global__ __launch_bounds__(CHOL_THREADS) void panel_chol_inverse_kernel(QrFact
                         if (lane == 0) bad_flag = 2;
                     }
                 }
-                const double d = sqrt(piv);
+                const double d = sqrt(piv), rd = 1.0 / d;          // one division per column: the rest multiplies
+                if (lane == 0) S[k0 + k] = rd;                     // 1 / L_kk, read by the solves below and by the inverse
                 double colv[4], rowv[4];
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
@@ -234,8 +235,8 @@ __global__ __launch_bounds__(CHOL_THREADS) void panel_chol_inverse_kernel(QrFact
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
                     const int e = lane + 64 * q, i = e >> 4, j = e & 15;
-                    if (j == k && i >= k) L[(k0 + i) * PITCH + k0 + k] = (i == k) ? d : colv[q] / d;
-                    else if (j > k && j <= i) L[(k0 + i) * PITCH + k0 + j] -= (colv[q] / d) * (rowv[q] / d);
+                    if (j == k && i >= k) L[(k0 + i) * PITCH + k0 + k] = (i == k) ? d : colv[q] * rd;
+                    else if (j > k && j <= i) L[(k0 + i) * PITCH + k0 + j] -= (colv[q] * rd) * (rowv[q] * rd);
                 }
                 __builtin_amdgcn_wave_barrier();
             }
@@ -251,7 +252,7 @@ __global__ __launch_bounds__(CHOL_THREADS) void panel_chol_inverse_kernel(QrFact
                 double v = x[j];
 #pragma unroll
                 for (int m = 0; m < j; ++m) v -= x[m] * L[(k0 + j) * PITCH + k0 + m];
-                x[j] = v / L[(k0 + j) * PITCH + k0 + j];
+                x[j] = v * S[k0 + j];
             }
 #pragma unroll
             for (int j = 0; j < NB; ++j) L[i * PITCH + k0 + j] = x[j];
@@ -284,7 +285,7 @@ __global__ __launch_bounds__(CHOL_THREADS) void panel_chol_inverse_kernel(QrFact
 #pragma unroll
                 for (int k = 0; k < i; ++k)
                     if (k >= j) sum -= L[(k0 + i) * PITCH + k0 + k] * w[k];
-                w[i] = (i >= j) ? sum / L[(k0 + i) * PITCH + k0 + i] : 0.0;
+                w[i] = (i >= j) ? sum * S[k0 + i] : 0.0;
             }
             __builtin_amdgcn_wave_barrier();                      // the group's reads of the block precede the rewrite
 #pragma unroll
