@@ -127,6 +127,7 @@ struct QrFactor {
     float a_scale, p_scale;
     const float *A;  // the statistic (read for its trace)
     int lda, pad2_;
+    float *cbuf;     // QR_PANEL x ldz: projection coefficients of the current panel
     double *est;     // n estimated eigenvalues q_i^T A q_i (column order of the refresh's input)
     int *perm;       // n: perm[r] = input column that becomes column r
     int *perm_out;   // the caller's slice of the permutation output, or null
@@ -184,10 +185,9 @@ constexpr size_t CHOL_LDS_BYTES = sizeof(double) * ((size_t)QR_PANEL * CHOL_PITC
 // factors the 16 x 16 diagonal block (its lanes stay in step through LDS, which a wavefront accesses in
 // order), every row below solves against it, and the trailing matrix takes a rank-16 update; the
 // inverse is formed from the inverses of the diagonal blocks, block row by block row.
-__global__ __launch_bounds__(CHOL_THREADS) void panel_chol_inverse_kernel(QrFactor *fs, const int *fidx, int panel,
-                                                                          int sweep)
+__global__ __launch_bounds__(CHOL_THREADS) void panel_chol_inverse_kernel(QrFactor *fs, int panel, int sweep)
 {
-    QrFactor &F = fs[fidx[blockIdx.x]];
+    QrFactor &F = fs[blockIdx.x];                   // the factors that have this panel are the first ones (sorted by size)
     if (sweep == 2 && F.skip3) return;              // uniform over the workgroup
     const int rows = min(QR_PANEL, F.n - panel * QR_PANEL);
     extern __shared__ __align__(16) unsigned char chol_smem[];
@@ -358,11 +358,11 @@ __global__ __launch_bounds__(256) void transpose_inplace_kernel(const QrFactor *
 }
 
 // Q[i][c] = Zt[c][i] for the rows c of one finished panel: 32 x 32 tiles through LDS.  Grid:
-// x = tile of the 128 x n strip, y = slot in the panel's factor list.  The caller's Q thus fills up
+// x = tile of the 128 x n strip, y = factor (the first ones of the group have the panel).  The caller's Q thus fills up
 // panel by panel, and the next panels read the finished columns from it with k contiguous.
-__global__ __launch_bounds__(256) void transpose_panel_kernel(const QrFactor *fs, const int *fidx, int panel)
+__global__ __launch_bounds__(256) void transpose_panel_kernel(const QrFactor *fs, int panel)
 {
-    const QrFactor &F = fs[fidx[blockIdx.y]];
+    const QrFactor &F = fs[blockIdx.y];
     const int tpr = (F.n + 31) / 32;
     const int ti = (int)blockIdx.x / tpr, tj = (int)blockIdx.x % tpr;   // tile row inside the panel, tile column
     const int c0 = panel * QR_PANEL + ti * 32;
@@ -441,6 +441,75 @@ __global__ __launch_bounds__(256) void sort_gather_kernel(const QrFactor *fs, in
     const float *src = phase == 0 ? F.Zt + (size_t)F.perm[row] * F.ldz : F.Qout + (size_t)row * F.ldq;
     float *dst = phase == 0 ? F.Qout + (size_t)row * F.ldq : F.Zt + (size_t)row * F.ldz;
     for (int k = threadIdx.x; k < F.n; k += 256) dst[k] = src[k];
+}
+
+// Problem tables of one group of factors, written on the device from the factor descriptors (as host
+// tables they travel as kernel arguments: about 500 upload launches per group of the 1B-model workload).
+// The factors of a group are sorted by size, largest first, so those that have panel j are the first
+// count_j of the group and the entry of factor i in any table of panel j is entry i of that panel's run.
+struct RefreshTables {
+    GemmProblem *z;                    // Z^T = Q^T A: one entry per factor
+    GemmProblem *t1, *t2, *t3, *t4;    // projection coefficients, projection, Gram matrix, application of L^-1
+    const int *off;                    // np + 1: start of panel j's run in t1 .. t4
+    const int *pt;                     // cnt + 1: tile columns (ceil(n / 128)) of the factors before i
+    const int *pz;                     // cnt + 1: tiles of the Z product (ceil(n / 128)^2) of the factors before i
+};
+
+__global__ __launch_bounds__(128) void refresh_tables_kernel(QrFactor *fs, int cnt, RefreshTables T)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x, j = blockIdx.y;
+    if (i >= cnt) return;
+    const QrFactor F = fs[i];
+    const float *a_scale = &fs[i].a_scale, *p_scale = &fs[i].p_scale;
+    const int tn = (F.n + BN - 1) / BN;
+    GemmProblem p = {};
+    p.alpha = 1.0f; p.beta = 0.0f;
+    if (j == 0) {
+        // Z^T = Q^T A on the fp16 cores (two terms per operand): A'(i, k) = Q^T[i][k] - the caller's Q has
+        // been transposed in place by then -, scaled by 2^14, and B'(j, k) = A[j][k] (A is symmetric),
+        // scaled by the factor's a_scale; both k-contiguous
+        GemmProblem g = p;
+        g.state_idx = -1; g.state_mask = ~0;
+        g.M = g.N = g.K = F.n; g.tiles_n = tn;
+        g.A = F.Qout; g.lda = F.ldq; g.B = F.A; g.ldb = F.lda; g.C = F.Zt; g.ldc = F.ldz;
+        g.sa = QR_UNIT_SCALE; g.sb_dev = a_scale;
+        g.tile_start = T.pz[i];
+        T.z[i] = g;
+    }
+    if (F.n <= j * QR_PANEL) return;
+    const int e = T.off[j] + i;
+    const int rows = min(QR_PANEL, F.n - j * QR_PANEL), done = j * QR_PANEL;
+    float *Pt = F.Zt + (size_t)done * F.ldz;
+    // runs while the factor's state word (`run`, or `skip3` in the third sweep) is 0
+    p.state_idx = i * QR_STATE_STRIDE; p.state_mask = 1;
+    // Gram matrix of the panel rows (fp64 accumulation), one symmetric tile
+    p.flags = GEMM_SYM;
+    p.M = rows; p.N = rows; p.K = F.n;
+    p.A = Pt; p.lda = F.ldz; p.B = Pt; p.ldb = F.ldz; p.C = F.gram; p.ldc = QR_PANEL;
+    p.tile_start = i;
+    T.t3[e] = p;
+    // P <- W P, in place: the single tile row reads a column range of P completely before it stores
+    // the same range
+    p.flags = 0;
+    p.M = rows; p.N = F.n; p.K = rows; p.tiles_n = tn;
+    p.A = F.winv; p.lda = QR_PANEL; p.B = Pt; p.ldb = F.ldz; p.C = Pt; p.ldc = F.ldz;
+    p.tile_start = T.pt[i];
+    T.t4[e] = p;
+    if (j == 0) return;
+    // C = P Q_done^T: rows of the panel against the finished rows, contraction over n; on the fp16 cores
+    // the panel rows are scaled by the factor's p_scale, the finished rows are orthonormal
+    p.M = rows; p.N = done; p.K = F.n; p.tiles_n = j;
+    p.A = Pt; p.lda = F.ldz; p.B = F.Zt; p.ldb = F.ldz; p.C = F.cbuf; p.ldc = F.ldz;
+    p.tile_start = i * j;                      // every factor of the run has j tile columns here
+    p.sa_dev = p_scale; p.sb = QR_UNIT_SCALE;
+    T.t1[e] = p;
+    // P <- P - C Q_done: contraction over the finished rows, which the caller's Q already holds as
+    // columns (k contiguous); the coefficients share the scale of the panel rows
+    p.alpha = -1.0f; p.beta = 1.0f;
+    p.M = rows; p.N = F.n; p.K = done; p.tiles_n = tn;
+    p.A = F.cbuf; p.lda = F.ldz; p.B = F.Qout; p.ldb = F.ldq; p.C = Pt; p.ldc = F.ldz;
+    p.tile_start = T.pt[i];
+    T.t2[e] = p;
 }
 
 asteria_status validate_step(const asteria_sblock *b, int nblocks, float b1, float b2, float eps, int t)
@@ -660,7 +729,7 @@ size_t refresh_factor_bytes(int n)
            Carver::need((size_t)QR_PANEL * QR_PANEL, sizeof(double)) +  // panel Gram matrix / fp64 inverse factor
            Carver::need((size_t)QR_PANEL * QR_PANEL, sizeof(float)) +   // fp32 inverse factor
            Carver::need((size_t)n, sizeof(double)) + Carver::need((size_t)n, sizeof(int)) +   // column estimates and order
-           (size_t)(1 + 4 * np) * sizeof(GemmProblem) + (size_t)np * sizeof(int) + sizeof(QrFactor);
+           (size_t)(1 + 4 * np) * sizeof(GemmProblem) + (size_t)(np + 2) * sizeof(int) + sizeof(QrFactor);
 }
 
 // The factors of a call can be dealt to up to this many groups, each enqueued as a whole on an
@@ -759,119 +828,61 @@ extern "C" asteria_status asteria_soap_refresh_ex(const asteria_factor *f, int n
         // a latency-bound Cholesky kernel on one workgroup per factor, application), and two chains
         // running side by side fill the gaps each leaves on the device.
         Carver cv(ws);
-        auto enqueue_group = [&](const std::vector<int> &idx, hipStream_t stream) -> asteria_status {
+        auto enqueue_group = [&](std::vector<int> idx, hipStream_t stream) -> asteria_status {
         const int cnt = (int)idx.size();
         if (cnt == 0) return ASTERIA_OK;
-        int n_max = 0;
-        for (int i = 0; i < cnt; ++i) n_max = std::max(n_max, f[idx[i]].n);
+        // largest first: the factors that have panel j are then the first count[j] of the group
+        std::stable_sort(idx.begin(), idx.end(), [&](int a, int b) { return f[a].n > f[b].n; });
+        const int n_max = f[idx[0]].n;
         const int np_max = (n_max + QR_PANEL - 1) / QR_PANEL;
 
-        GemmProblem *d_g = cv.take<GemmProblem>(cnt);
         QrFactor *d_q = cv.take<QrFactor>(cnt);
-        std::vector<GemmProblem> g;
         std::vector<QrFactor> q;
-        std::vector<float *> cbuf(cnt);
-        int tiles = 0;
+        // off | pt | pz: see RefreshTables
+        std::vector<int> ints((size_t)(np_max + 1) + 2 * (size_t)(cnt + 1), 0);
+        int *off = ints.data(), *pt = off + np_max + 1, *pz = pt + cnt + 1;
+        std::vector<int> count(np_max, 0);
         for (int i = 0; i < cnt; ++i) {
             const asteria_factor &a = f[idx[i]];
             const int n = a.n, ldz = ld4(n);
             QrFactor F;
+            memset(&F, 0, sizeof(F));
             F.Zt = cv.take<float>((size_t)n * ldz);
-            cbuf[i] = cv.take<float>((size_t)QR_PANEL * ldz);
+            F.cbuf = cv.take<float>((size_t)QR_PANEL * ldz);
             F.gram = cv.take<double>((size_t)QR_PANEL * QR_PANEL);
             F.winv = cv.take<float>((size_t)QR_PANEL * QR_PANEL);
             F.Qout = a.X; F.n = n; F.ldz = ldz; F.ldq = a.ldx; F.bad = 0; F.run = 0; F.skip3 = 1;
-            F.out_index = idx[i]; F.pad_ = 0; F.pad0_ = 0;
-            F.a_scale = 1.0f; F.p_scale = 1.0f; F.A = a.A; F.lda = a.lda; F.pad2_ = 0;
+            F.out_index = idx[i];
+            F.a_scale = 1.0f; F.p_scale = 1.0f; F.A = a.A; F.lda = a.lda;
             F.est = cv.take<double>((size_t)n);
             F.perm = cv.take<int>((size_t)n);
             F.perm_out = perm ? perm + perm_offset[idx[i]] : nullptr;
             q.push_back(F);
-            // Z^T = Q^T A on the fp16 cores (two terms per operand): A'(i, k) = Q^T[i][k] - the caller's
-            // Q has been transposed in place by then -, scaled by 2^14, and B'(j, k) = A[j][k] (A is
-            // symmetric), scaled by the factor's a_scale; both k-contiguous
-            GemmProblem p;
-            memset(&p, 0, sizeof(p));
-            p.state_idx = -1; p.state_mask = ~0; p.alpha = 1.0f; p.beta = 0.0f;
-            p.M = p.N = p.K = n;
             const int tn = (n + BN - 1) / BN;
-            p.tiles_n = tn;
-            p.A = a.X; p.lda = a.ldx; p.B = a.A; p.ldb = a.lda; p.C = F.Zt; p.ldc = ldz;
-            p.sa = QR_UNIT_SCALE;
-            p.sb_dev = reinterpret_cast<const float *>(reinterpret_cast<const char *>(d_q + i) + offsetof(QrFactor, a_scale));
-            p.tile_start = tiles; tiles += tn * tn;
-            g.push_back(p);
+            pt[i + 1] = pt[i] + tn;
+            pz[i + 1] = pz[i] + tn * tn;
+            for (int j = 0; j < (n + QR_PANEL - 1) / QR_PANEL; ++j) ++count[j];
         }
-        // per-panel projection tables: panel j of every factor that has one
-        std::vector<std::vector<GemmProblem>> t1(np_max), t2(np_max), t3(np_max), t4(np_max);
-        std::vector<int> tiles4(np_max, 0);
-        std::vector<std::vector<int>> fidx(np_max);
-        std::vector<int> tiles1(np_max, 0), tiles2(np_max, 0);
-        for (int j = 0; j < np_max; ++j) {
-            for (int i = 0; i < cnt; ++i) {
-                const QrFactor &F = q[i];
-                if (F.n <= j * QR_PANEL) continue;
-                fidx[j].push_back(i);
-                const int rows = std::min(QR_PANEL, F.n - j * QR_PANEL), done = j * QR_PANEL;
-                float *Pt = F.Zt + (size_t)done * F.ldz;
-                GemmProblem p;
-                memset(&p, 0, sizeof(p));
-                // runs while the factor's state word (`run`, or `skip3` in the third sweep) is 0
-                p.state_idx = i * QR_STATE_STRIDE; p.state_mask = 1;
-                // Gram matrix of the panel rows (fp64 accumulation), one symmetric tile
-                p.alpha = 1.0f; p.beta = 0.0f; p.flags = GEMM_SYM;
-                p.M = rows; p.N = rows; p.K = F.n;
-                p.A = Pt; p.lda = F.ldz; p.B = Pt; p.ldb = F.ldz; p.C = F.gram; p.ldc = QR_PANEL;
-                p.tile_start = (int)t3[j].size();
-                t3[j].push_back(p);
-                // P <- W P, in place: the single tile row reads a column range of P completely before it
-                // stores the same range
-                p.flags = 0;
-                p.M = rows; p.N = F.n; p.K = rows; p.tiles_n = (F.n + BN - 1) / BN;
-                p.A = F.winv; p.lda = QR_PANEL; p.B = Pt; p.ldb = F.ldz; p.C = Pt; p.ldc = F.ldz;
-                p.tile_start = tiles4[j]; tiles4[j] += p.tiles_n;
-                t4[j].push_back(p);
-                if (j == 0) continue;
-                // C = P Q_done^T : rows of the panel against the finished rows, contraction over n
-                p.alpha = 1.0f; p.beta = 0.0f;
-                p.M = rows; p.N = done; p.K = F.n; p.tiles_n = (done + BN - 1) / BN;
-                p.A = Pt; p.lda = F.ldz; p.B = F.Zt; p.ldb = F.ldz; p.C = cbuf[i]; p.ldc = F.ldz;
-                p.tile_start = tiles1[j]; tiles1[j] += p.tiles_n;
-                // on the fp16 cores (sweeps 0 and 1): the panel rows scaled by the factor's p_scale,
-                // the finished rows are orthonormal
-                p.sa_dev = reinterpret_cast<const float *>(reinterpret_cast<const char *>(d_q + i) + offsetof(QrFactor, p_scale));
-                p.sb = QR_UNIT_SCALE;
-                t1[j].push_back(p);
-                p.sa_dev = nullptr;
-                // P <- P - C Q_done : contraction over the finished rows, which the caller's Q already
-                // holds as columns (k contiguous); the coefficients share the scale of the panel rows
-                p.alpha = -1.0f; p.beta = 1.0f;
-                p.M = rows; p.N = F.n; p.K = done; p.tiles_n = (F.n + BN - 1) / BN;
-                p.A = cbuf[i]; p.lda = F.ldz; p.B = F.Qout; p.ldb = F.ldq; p.C = Pt; p.ldc = F.ldz;
-                p.sa_dev = reinterpret_cast<const float *>(reinterpret_cast<const char *>(d_q + i) + offsetof(QrFactor, p_scale));
-                p.sb = QR_UNIT_SCALE;
-                p.tile_start = tiles2[j]; tiles2[j] += p.tiles_n;
-                t2[j].push_back(p);
-                p.sa_dev = nullptr;
-            }
-        }
-        std::vector<GemmProblem *> d_t1(np_max, nullptr), d_t2(np_max, nullptr), d_t3(np_max, nullptr), d_t4(np_max, nullptr);
-        std::vector<int *> d_fidx(np_max, nullptr);
-        ASTERIA_HIP_TRY(upload_async(d_g, g.data(), g.size() * sizeof(GemmProblem), stream));
+        for (int j = 0; j < np_max; ++j) off[j + 1] = off[j] + count[j];
+        const int tiles = pz[cnt], entries = off[np_max];
+        RefreshTables rt;
+        rt.z = cv.take<GemmProblem>(cnt);
+        rt.t1 = cv.take<GemmProblem>(entries); rt.t2 = cv.take<GemmProblem>(entries);
+        rt.t3 = cv.take<GemmProblem>(entries); rt.t4 = cv.take<GemmProblem>(entries);
+        int *d_ints = cv.take<int>(ints.size());
+        rt.off = d_ints; rt.pt = d_ints + np_max + 1; rt.pz = rt.pt + cnt + 1;
+        GemmProblem *d_g = rt.z;
         ASTERIA_HIP_TRY(upload_async(d_q, q.data(), q.size() * sizeof(QrFactor), stream));
-        for (int j = 0; j < np_max; ++j) {
-            d_fidx[j] = cv.take<int>(fidx[j].size());
-            ASTERIA_HIP_TRY(upload_async(d_fidx[j], fidx[j].data(), fidx[j].size() * sizeof(int), stream));
-            d_t3[j] = cv.take<GemmProblem>(t3[j].size());
-            d_t4[j] = cv.take<GemmProblem>(t4[j].size());
-            ASTERIA_HIP_TRY(upload_async(d_t3[j], t3[j].data(), t3[j].size() * sizeof(GemmProblem), stream));
-            ASTERIA_HIP_TRY(upload_async(d_t4[j], t4[j].data(), t4[j].size() * sizeof(GemmProblem), stream));
-            if (j == 0) continue;
-            d_t1[j] = cv.take<GemmProblem>(t1[j].size());
-            d_t2[j] = cv.take<GemmProblem>(t2[j].size());
-            ASTERIA_HIP_TRY(upload_async(d_t1[j], t1[j].data(), t1[j].size() * sizeof(GemmProblem), stream));
-            ASTERIA_HIP_TRY(upload_async(d_t2[j], t2[j].data(), t2[j].size() * sizeof(GemmProblem), stream));
-        }
+        ASTERIA_HIP_TRY(upload_async(d_ints, ints.data(), ints.size() * sizeof(int), stream));
+        hipLaunchKernelGGL(refresh_tables_kernel, dim3((cnt + 127) / 128, np_max), dim3(128), 0, stream, d_q, cnt, rt);
+        ASTERIA_HIP_TRY(hipGetLastError());
+        // panel j: count[j] entries per table; tile counts of its four launches
+        auto T1 = [&](int j) { return rt.t1 + off[j]; };
+        auto T2 = [&](int j) { return rt.t2 + off[j]; };
+        auto T3 = [&](int j) { return rt.t3 + off[j]; };
+        auto T4 = [&](int j) { return rt.t4 + off[j]; };
+        auto tiles1 = [&](int j) { return count[j] * j; };
+        auto tiles24 = [&](int j) { return pt[count[j]]; };
         hipLaunchKernelGGL(qr_scale_kernel, dim3(cnt), dim3(64), 0, stream, d_q, cnt);
         if (o.from_identity)
             hipLaunchKernelGGL(set_identity_kernel, dim3((unsigned)std::min<size_t>(((size_t)n_max * n_max + 255) / 256, 4096), (unsigned)cnt),
@@ -910,23 +921,23 @@ extern "C" asteria_status asteria_soap_refresh_ex(const asteria_factor *f, int n
                     // its own rows and the finished ones to 2^-22): what this leaves along the finished
                     // rows, 2^-11 of the coefficients, is what the second sweep removes at full accuracy
                     if (sweep == 0) {
-                        ASTERIA_HIP_TRY((launch_gemm_bf16_grouped<float, float, 1, 1, true>(d_t1[j], (int)t1[j].size(), tiles1[j], st, stream)));
-                        ASTERIA_HIP_TRY((launch_gemm_bf16_grouped<float, float, 1, 2, true>(d_t2[j], (int)t2[j].size(), tiles2[j], st, stream)));
+                        ASTERIA_HIP_TRY((launch_gemm_bf16_grouped<float, float, 1, 1, true>(T1(j), count[j], tiles1(j), st, stream)));
+                        ASTERIA_HIP_TRY((launch_gemm_bf16_grouped<float, float, 1, 2, true>(T2(j), count[j], tiles24(j), st, stream)));
                     } else if (sweep == 1) {
-                        ASTERIA_HIP_TRY((launch_gemm_bf16_grouped<float, float, 2, 2, true>(d_t1[j], (int)t1[j].size(), tiles1[j], st, stream)));
-                        ASTERIA_HIP_TRY((launch_gemm_bf16_grouped<float, float, 2, 2, true>(d_t2[j], (int)t2[j].size(), tiles2[j], st, stream)));
+                        ASTERIA_HIP_TRY((launch_gemm_bf16_grouped<float, float, 2, 2, true>(T1(j), count[j], tiles1(j), st, stream)));
+                        ASTERIA_HIP_TRY((launch_gemm_bf16_grouped<float, float, 2, 2, true>(T2(j), count[j], tiles24(j), st, stream)));
                     } else {
-                        ASTERIA_HIP_TRY((launch_gemm_grouped<float, float, float, false, false>(d_t1[j], (int)t1[j].size(), tiles1[j], st, stream)));
-                        ASTERIA_HIP_TRY((launch_gemm_grouped<float, float, float, false, false>(d_t2[j], (int)t2[j].size(), tiles2[j], st, stream)));
+                        ASTERIA_HIP_TRY((launch_gemm_grouped<float, float, float, false, false>(T1(j), count[j], tiles1(j), st, stream)));
+                        ASTERIA_HIP_TRY((launch_gemm_grouped<float, float, float, false, false>(T2(j), count[j], tiles24(j), st, stream)));
                     }
                 }
-                ASTERIA_HIP_TRY((launch_gemm_grouped<double, float, float, false, false>(d_t3[j], (int)t3[j].size(), (int)t3[j].size(), st, stream)));
-                hipLaunchKernelGGL(panel_chol_inverse_kernel, dim3((unsigned)fidx[j].size()), dim3(CHOL_THREADS), chol_lds, stream, d_q, d_fidx[j], j, sweep);
-                ASTERIA_HIP_TRY((launch_gemm_grouped<float, float, float, false, true>(d_t4[j], (int)t4[j].size(), tiles4[j], st, stream)));
+                ASTERIA_HIP_TRY((launch_gemm_grouped<double, float, float, false, false>(T3(j), count[j], count[j], st, stream)));
+                hipLaunchKernelGGL(panel_chol_inverse_kernel, dim3((unsigned)count[j]), dim3(CHOL_THREADS), chol_lds, stream, d_q, j, sweep);
+                ASTERIA_HIP_TRY((launch_gemm_grouped<float, float, float, false, true>(T4(j), count[j], tiles24(j), st, stream)));
             }
             // the finished panel goes to the caller's Q as columns
-            hipLaunchKernelGGL(transpose_panel_kernel, dim3((QR_PANEL / 32) * ((n_max + 31) / 32), (unsigned)fidx[j].size()),
-                               dim3(256), 0, stream, d_q, d_fidx[j], j);
+            hipLaunchKernelGGL(transpose_panel_kernel, dim3((QR_PANEL / 32) * ((n_max + 31) / 32), (unsigned)count[j]),
+                               dim3(256), 0, stream, d_q, j);
         }
         }   // rounds
         hipLaunchKernelGGL(qr_info_kernel, dim3((cnt + 127) / 128), dim3(128), 0, stream, d_q, cnt, info);
