@@ -517,7 +517,11 @@ def soap_section(args, torch, ast, W, dev):
     Vs = [torch.zeros(m, n, device=dev) for m, n in shapes]
     Ns = [torch.empty(m, n, device=dev) for m, n in shapes]
     blocks = [ast.Blocks(list(zip(G, Ls, Rs))) for G in Gsets]
-    sblocks = [ast.SBlocks(list(zip(G, QLs, QRs, Ms, Vs, Ns))) for G in Gsets]
+    # the step reads Q^T along rows: the transposes are kept beside the bases and redone after every refresh
+    QLts = [torch.empty(m, m, device=dev) for m, n in shapes]
+    QRts = [torch.empty(n, n, device=dev) for m, n in shapes]
+    tpairs = list(zip(QLs, QLts)) + list(zip(QRs, QRts))
+    sblocks = [ast.SBlocks(list(zip(G, QLs, QRs, Ms, Vs, Ns, QLts, QRts))) for G in Gsets]
     factors = ast.Factors(list(zip(Ls, QLs)) + list(zip(Rs, QRs)))
     fsize = [m for m, n in shapes] + [n for m, n in shapes]
     need = max(ast.soap_refresh_workspace_bytes(factors)[0], ast.soap_step_workspace_bytes(sblocks[0]),
@@ -531,6 +535,7 @@ def soap_section(args, torch, ast, W, dev):
     for w in range(3):                          # warm the bases from the identity
         ast.stats_update(blocks[w % nsets], beta, ws=ws)
         ast.soap_refresh(factors, info=info, ws=ws, aux_streams=aux)
+    ast.transpose(tpairs)
     torch.cuda.synchronize()
     ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
     for t in range(args.steps):
@@ -545,10 +550,12 @@ def soap_section(args, torch, ast, W, dev):
     t_host = time.time()
     ast.soap_refresh(factors, info=info, ws=ws, aux_streams=aux)
     enqueue_ms = 1e3 * (time.time() - t_host)               # the call returns once everything is enqueued
+    ast.transpose(tpairs)                                   # part of the refresh: the copies the steps read
     r1.record()
     torch.cuda.synchronize()
     r2.record()
     ast.soap_refresh(factors, info=info, ws=ws)            # the same refresh on the caller's stream alone
+    ast.transpose(tpairs)
     r3.record()
     torch.cuda.synchronize()
     step_ms = sum(e[0].elapsed_time(e[1]) for e in ev) / args.steps

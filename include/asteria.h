@@ -132,6 +132,11 @@ typedef struct asteria_sblock {
     int32_t m, n;
     int32_t ldg, ldql, ldqr, ldm, ldv, ldn;
     int32_t g_dtype;
+    /* optional: Q_L^T (m x m, ldqlt) and Q_R^T (n x n, ldqrt) kept by the caller (asteria_transpose); NULL =
+       the call transposes that basis into its workspace.  Unused by one-sided blocks.               */
+    int32_t ldqlt, ldqrt;
+    const float *QLt;
+    const float *QRt;
 } asteria_sblock;
 
 typedef enum asteria_eps_mode {
@@ -350,7 +355,11 @@ asteria_status asteria_soap_refresh_ex(const asteria_factor *f, int nfactors, co
  *   N' = (M / (1-beta1^t)) / (sqrt(V / (1-beta2^t)) + adam_eps);  N = Q_L N' Q_R^T.
  * The four rotations run on the bf16 matrix cores with fp32 accumulation and every fp32 operand
  * split into two bf16 terms (bf16 G exact): about 16 bits of Q_L, Q_R and of the intermediates.
- * Workspace: G', N', one intermediate and the transposes of Q_L, Q_R of every block.
+ * Workspace: G', N', one intermediate and the transposes of Q_L, Q_R of every block.  The products read
+ * Q_L^T and Q_R^T along rows; a basis changes only at a refresh, so a caller may keep the transposes
+ * (asteria_transpose after each refresh) and pass them in the block: the call then neither needs that
+ * workspace nor moves those 8 (m^2 + n^2) bytes per step.  A passed transpose must be that of the
+ * passed basis; the call does not check it.
  * One-sided blocks: QL or QR (not both) may be NULL and stands for the identity - a dimension above
  * the preconditioner cap keeps no basis.  Such a block takes one product per rotation, on the fp32
  * matrix cores with the operands read in place.                                                 */
@@ -358,6 +367,17 @@ size_t asteria_soap_step_workspace_bytes(const asteria_sblock *blocks, int nbloc
 asteria_status asteria_soap_step(const asteria_sblock *blocks, int nblocks,
                                  float beta1, float beta2, float adam_eps, int step_t,
                                  void *ws, size_t ws_bytes, void *stream);
+
+/* ---- transposed copies (utility for asteria_soap_step) -----------------------------------------
+ * dst (cols x rows, ldd) = src^T for every item (src: rows x cols, lds), 32 x 32 tiles through LDS.
+ * items: host array; src, dst: device, fp32, not overlapping.  Errors: NULL pointers, rows or
+ * cols <= 0, lds < cols, ldd < rows -> INVALID_ARG.                                              */
+typedef struct asteria_tpair {
+    const float *src;
+    float *dst;
+    int32_t rows, cols, lds, ldd;
+} asteria_tpair;
+asteria_status asteria_transpose(const asteria_tpair *items, int nitems, void *stream);
 
 /* ---- moments under a change of bases (paper Eq. 2) ---------------------------------------------
  * asteria_soap_step keeps the Adam moments in the rotated space of (Q_L, Q_R).  After a refresh has

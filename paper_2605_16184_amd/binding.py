@@ -51,7 +51,12 @@ class _SBlock(Structure):
     _fields_ = [("G", c_void_p), ("QL", c_void_p), ("QR", c_void_p), ("M", c_void_p), ("V", c_void_p),
                 ("N", c_void_p), ("m", c_int32), ("n", c_int32), ("ldg", c_int32), ("ldql", c_int32),
                 ("ldqr", c_int32), ("ldm", c_int32), ("ldv", c_int32), ("ldn", c_int32),
-                ("g_dtype", c_int32)]
+                ("g_dtype", c_int32), ("ldqlt", c_int32), ("ldqrt", c_int32), ("QLt", c_void_p), ("QRt", c_void_p)]
+
+
+class _TPair(Structure):
+    _fields_ = [("src", c_void_p), ("dst", c_void_p), ("rows", c_int32), ("cols", c_int32), ("lds", c_int32),
+                ("ldd", c_int32)]
 
 
 class _RBlock(Structure):
@@ -143,6 +148,8 @@ def lib():
         L.asteria_soap_step.restype = c_int
         L.asteria_soap_step.argtypes = [POINTER(_SBlock), c_int, c_float, c_float, c_float, c_int,
                                         c_void_p, c_size_t, c_void_p]
+        L.asteria_transpose.restype = c_int
+        L.asteria_transpose.argtypes = [POINTER(_TPair), c_int, c_void_p]
         L.asteria_profile_enable.restype = c_int
         L.asteria_profile_enable.argtypes = [c_int]
         L.asteria_profile_collect.restype = c_int
@@ -272,10 +279,11 @@ class PBlocks(_Batch):
 
 
 class SBlocks(_Batch):
-    """[(G, QL, QR, M, V, N)] for soap_step; QL or QR may be None (the identity on that side)."""
+    """[(G, QL, QR, M, V, N)] or [(G, QL, QR, M, V, N, QLt, QRt)] for soap_step; QL or QR may be None (the
+    identity on that side); QLt, QRt: transposed copies of the bases kept by the caller (`transpose`), or None."""
     ctype = _SBlock
 
-    def _fill(self, d, G, QL, QR, M, V, N):
+    def _fill(self, d, G, QL, QR, M, V, N, QLt=None, QRt=None):
         d.G, d.m, d.n, d.ldg = _mat(G, "G")
         d.g_dtype = _dtype_code(G)
         d.QL, a, b, d.ldql = _mat(QL, "QL", torch.float32)
@@ -286,6 +294,10 @@ class SBlocks(_Batch):
         if (QL is not None and (a, b) != (d.m, d.m)) or (QR is not None and (c, e) != (d.n, d.n)) or \
                 {(m1, n1), (m2, n2), (m3, n3)} != {(d.m, d.n)}:
             raise ValueError("shape mismatch in soap block")
+        d.QLt, a, b, d.ldqlt = _mat(QLt, "QLt", torch.float32)
+        d.QRt, c, e, d.ldqrt = _mat(QRt, "QRt", torch.float32)
+        if (QLt is not None and (a, b) != (d.m, d.m)) or (QRt is not None and (c, e) != (d.n, d.n)):
+            raise ValueError("shape mismatch in soap block (transposed bases)")
 
 
 def _as(batch_type, items):
@@ -500,6 +512,18 @@ def soap_step(blocks, beta1: float, beta2: float, adam_eps: float, step_t: int,
     ws = _workspace(ws, soap_step_workspace_bytes(b), dev)
     _check(lib().asteria_soap_step(b.array, b.count, float(beta1), float(beta2), float(adam_eps), int(step_t),
                                    c_void_p(ws.data_ptr()), ws.numel(), _stream(stream)), "asteria_soap_step")
+
+
+def transpose(pairs, stream=None) -> None:
+    """dst = src^T for every (src, dst) pair of fp32 device matrices (what soap_step takes as QLt, QRt)."""
+    pairs = list(pairs)
+    arr = (_TPair * len(pairs))()
+    for d, (src, dst) in zip(arr, pairs):
+        d.src, d.rows, d.cols, d.lds = _mat(src, "src", torch.float32)
+        d.dst, r2, c2, d.ldd = _mat(dst, "dst", torch.float32)
+        if (r2, c2) != (d.cols, d.rows):
+            raise ValueError("dst must have the transposed shape")
+    _check(lib().asteria_transpose(arr, len(pairs), _stream(stream)), "asteria_transpose")
 
 
 def profile_enable(max_launches: int = 4096) -> None:

@@ -523,11 +523,68 @@ asteria_status validate_step(const asteria_sblock *b, int nblocks, float b1, flo
         if (k.ldg < k.n || (k.QL && k.ldql < k.m) || (k.QR && k.ldqr < k.n) || k.ldm < k.n || k.ldv < k.n || k.ldn < k.n)
             return ASTERIA_INVALID_ARG;
         if (!valid_dtype(k.g_dtype)) return ASTERIA_INVALID_ARG;
+        if ((k.QLt && k.ldqlt < k.m) || (k.QRt && k.ldqrt < k.n)) return ASTERIA_INVALID_ARG;
     }
     return ASTERIA_OK;
 }
 
+// The same transposition for descriptors that travel as kernel arguments (asteria_transpose has no workspace).
+constexpr int TRANSPOSE_CHUNK = 64;
+struct TransposeChunk {
+    TransposeF32Job job[TRANSPOSE_CHUNK];
+};
+
+__global__ __launch_bounds__(256) void transpose_chunk_kernel(TransposeChunk c, int njobs)
+{
+    int lo = 0, hi = njobs - 1;
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (c.job[mid].tile_start <= (int)blockIdx.x) lo = mid; else hi = mid - 1;
+    }
+    const TransposeF32Job &J = c.job[lo];
+    const int lt = (int)blockIdx.x - J.tile_start;
+    const int tcols = (J.cols + 31) / 32;
+    const int ti = lt / tcols, tj = lt % tcols;
+    __shared__ float tile[32][33];
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+    for (int rr = ty; rr < 32; rr += 8) {
+        const int r = ti * 32 + rr, cc = tj * 32 + tx;
+        tile[rr][tx] = (r < J.rows && cc < J.cols) ? J.src[(size_t)r * J.lds_ + cc] : 0.0f;
+    }
+    __syncthreads();
+    for (int rr = ty; rr < 32; rr += 8) {
+        const int r = tj * 32 + rr, cc = ti * 32 + tx;   // element (r, cc) of dst = src(cc, r)
+        if (r < J.cols && cc < J.rows) J.dst[(size_t)r * J.ldd + cc] = tile[tx][rr];
+    }
+}
+
 }  // namespace
+
+extern "C" asteria_status asteria_transpose(const asteria_tpair *items, int nitems, void *stream_)
+{
+    if (!items || nitems <= 0) return ASTERIA_INVALID_ARG;
+    for (int i = 0; i < nitems; ++i) {
+        const asteria_tpair &t = items[i];
+        if (!t.src || !t.dst || t.rows <= 0 || t.cols <= 0 || t.lds < t.cols || t.ldd < t.rows) return ASTERIA_INVALID_ARG;
+    }
+    hipStream_t stream = reinterpret_cast<hipStream_t>(stream_);
+    for (int first = 0; first < nitems; first += TRANSPOSE_CHUNK) {
+        const int cnt = std::min(TRANSPOSE_CHUNK, nitems - first);
+        TransposeChunk c;
+        memset(&c, 0, sizeof(c));
+        int tiles = 0;
+        for (int i = 0; i < cnt; ++i) {
+            const asteria_tpair &t = items[first + i];
+            TransposeF32Job &J = c.job[i];
+            J.src = t.src; J.dst = t.dst; J.rows = t.rows; J.cols = t.cols; J.lds_ = t.lds; J.ldd = t.ldd;
+            J.tile_start = tiles;
+            tiles += ((t.rows + 31) / 32) * ((t.cols + 31) / 32);
+        }
+        hipLaunchKernelGGL(transpose_chunk_kernel, dim3(tiles), dim3(256), 0, stream, c, cnt);
+        ASTERIA_HIP_TRY(hipGetLastError());
+    }
+    return ASTERIA_OK;
+}
 
 extern "C" size_t asteria_soap_step_workspace_bytes(const asteria_sblock *blocks, int nblocks)
 {
@@ -539,8 +596,8 @@ extern "C" size_t asteria_soap_step_workspace_bytes(const asteria_sblock *blocks
         const int m = blocks[i].m, n = blocks[i].n;
         bytes += 2 * Carver::need((size_t)m * ld4(n), sizeof(float));      // G' / N' (m x n)
         bytes += Carver::need((size_t)n * ld4(m), sizeof(float));          // transposed intermediate (n x m)
-        bytes += Carver::need((size_t)m * ld4(m), sizeof(float));          // Q_L^T
-        bytes += Carver::need((size_t)n * ld4(n), sizeof(float));          // Q_R^T
+        if (!blocks[i].QLt) bytes += Carver::need((size_t)m * ld4(m), sizeof(float));   // Q_L^T, unless the caller keeps it
+        if (!blocks[i].QRt) bytes += Carver::need((size_t)n * ld4(n), sizeof(float));   // Q_R^T
     }
     return bytes;
 }
@@ -574,7 +631,8 @@ extern "C" asteria_status asteria_soap_step(const asteria_sblock *blocks, int nb
     int tiles1[2] = {0, 0}, tiles = 0, tilesT = 0, rows = 0, ttiles = 0;
     for (int i = 0; i < nblocks; ++i) {
         const asteria_sblock &k = blocks[i];
-        const int ldw = ld4(k.n), ldt = ld4(k.m), ldqlt = ld4(k.m), ldqrt = ld4(k.n);
+        const int ldw = ld4(k.n), ldt = ld4(k.m);
+        const int ldqlt = k.QLt ? k.ldqlt : ld4(k.m), ldqrt = k.QRt ? k.ldqrt : ld4(k.n);
         float *Gr = cv.take<float>((size_t)k.m * ldw);   // G' (m x n)
         float *Np = cv.take<float>((size_t)k.m * ldw);   // N' (m x n)
         if (!k.QL || !k.QR) {
@@ -609,16 +667,24 @@ extern "C" asteria_status asteria_soap_step(const asteria_sblock *blocks, int nb
             continue;
         }
         float *Tt = cv.take<float>((size_t)k.n * ldt);   // (G Q_R)^T, later (N' Q_R^T)^T  (n x m)
-        float *QLt = cv.take<float>((size_t)k.m * ldqlt);
-        float *QRt = cv.take<float>((size_t)k.n * ldqrt);
+        // transposed bases: the caller's copies, or made here
+        const float *QLt = k.QLt, *QRt = k.QRt;
         TransposeF32Job t;
         memset(&t, 0, sizeof(t));
-        t.src = reinterpret_cast<const float *>(k.QL); t.dst = QLt; t.rows = k.m; t.cols = k.m; t.lds_ = k.ldql; t.ldd = ldqlt;
-        t.tile_start = ttiles; ttiles += ((k.m + 31) / 32) * ((k.m + 31) / 32);
-        tj.push_back(t);
-        t.src = reinterpret_cast<const float *>(k.QR); t.dst = QRt; t.rows = k.n; t.cols = k.n; t.lds_ = k.ldqr; t.ldd = ldqrt;
-        t.tile_start = ttiles; ttiles += ((k.n + 31) / 32) * ((k.n + 31) / 32);
-        tj.push_back(t);
+        if (!QLt) {
+            float *dst = cv.take<float>((size_t)k.m * ldqlt);
+            t.src = k.QL; t.dst = dst; t.rows = k.m; t.cols = k.m; t.lds_ = k.ldql; t.ldd = ldqlt;
+            t.tile_start = ttiles; ttiles += ((k.m + 31) / 32) * ((k.m + 31) / 32);
+            tj.push_back(t);
+            QLt = dst;
+        }
+        if (!QRt) {
+            float *dst = cv.take<float>((size_t)k.n * ldqrt);
+            t.src = k.QR; t.dst = dst; t.rows = k.n; t.cols = k.n; t.lds_ = k.ldqr; t.ldd = ldqrt;
+            t.tile_start = ttiles; ttiles += ((k.n + 31) / 32) * ((k.n + 31) / 32);
+            tj.push_back(t);
+            QRt = dst;
+        }
         const int tm = (k.m + BM - 1) / BM, tn = (k.n + BN - 1) / BN;
         GemmProblem p;
         memset(&p, 0, sizeof(p));

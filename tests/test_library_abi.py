@@ -114,6 +114,13 @@ def test_precondition_and_soap_reject_bad_arguments_without_launching():
     assert lib.asteria_precondition((B._PBlock * 1)(p), 1, ws, 1 << 20, None) == B.INVALID_ARG
     assert lib.asteria_precondition(None, 1, ws, 1 << 20, None) == B.INVALID_ARG
 
+    t = B._TPair()
+    t.src, t.dst, t.rows, t.cols, t.lds, t.ldd = 0x1000, 0x2000, 4, 6, 6, 3
+    assert lib.asteria_transpose((B._TPair * 1)(t), 1, None) == B.INVALID_ARG          # ldd < rows
+    t.ldd, t.dst = 4, None
+    assert lib.asteria_transpose((B._TPair * 1)(t), 1, None) == B.INVALID_ARG
+    assert lib.asteria_transpose(None, 1, None) == B.INVALID_ARG
+
     s = B._SBlock()
     s.G, s.QL, s.QR, s.M, s.V, s.N = 0x1000, 0x2000, 0x3000, 0x4000, 0x5000, 0x6000
     s.m, s.n = 4, 6
@@ -125,6 +132,10 @@ def test_precondition_and_soap_reject_bad_arguments_without_launching():
     assert lib.asteria_soap_step(one, 1, 0.9, 0.95, 1e-8, 1, None, 0, None) == B.WORKSPACE_TOO_SMALL
     s.ldql = 3
     assert lib.asteria_soap_step((B._SBlock * 1)(s), 1, 0.9, 0.95, 1e-8, 1, ws, 1 << 20, None) == B.INVALID_ARG
+    s.ldql = 4
+    s.QLt, s.ldqlt = 0x9000, 3                   # a kept transpose needs its leading dimension too
+    assert lib.asteria_soap_step((B._SBlock * 1)(s), 1, 0.9, 0.95, 1e-8, 1, ws, 1 << 20, None) == B.INVALID_ARG
+    s.QLt, s.ldqlt, s.ldql = None, 0, 3
     s.QL = None                                  # one-sided block: the leading dimension of the absent basis is not looked at
     assert lib.asteria_soap_step((B._SBlock * 1)(s), 1, 0.9, 0.95, 1e-8, 1, None, 0, None) == B.WORKSPACE_TOO_SMALL
     s.QR = None                                  # ... but both absent is plain Adam, not this call

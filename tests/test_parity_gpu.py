@@ -1036,6 +1036,46 @@ def test_soap_step_one_sided_blocks():
             assert torch.all(N._base[:, N.shape[1]:] == -777.0)
 
 
+def test_soap_step_with_transposed_bases_kept_by_the_caller_is_bit_identical():
+    """Q_L^T and Q_R^T passed in the block (asteria_transpose, once per refresh) instead of transposed by
+    every step: same products on the same values, so the results must agree bit for bit; and the utility
+    against the definition, on ragged shapes with padded leading dimensions."""
+    src = padded(70, 133, 5); src.copy_(W.gaussian_block(70, 133, 1.0, DEV, 91))
+    dst = padded(133, 70, 3)
+    ast.transpose([(src, dst)])
+    torch.cuda.synchronize()
+    assert torch.equal(dst, src.T)
+    shapes = [(200, 328), (256, 512), (129, 70)]
+    Gs = [W.gaussian_block(m, n, 1.0, DEV, 92, i, dtype=torch.bfloat16) for i, (m, n) in enumerate(shapes)]
+    QLs = [W.haar(m, DEV, 93, i) for i, (m, n) in enumerate(shapes)]
+    QRs = [W.haar(n, DEV, 94, i) for i, (m, n) in enumerate(shapes)]
+    QLt = [torch.empty_like(q) for q in QLs]; QRt = [torch.empty_like(q) for q in QRs]
+    ast.transpose(list(zip(QLs, QLt)) + list(zip(QRs, QRt)))
+    out = []
+    for cached in (False, True):
+        Ms = [torch.zeros(m, n, device=DEV) for m, n in shapes]
+        Vs = [torch.zeros(m, n, device=DEV) for m, n in shapes]
+        Ns = [torch.full((m, n), float("nan"), device=DEV) for m, n in shapes]
+        items = list(zip(Gs, QLs, QRs, Ms, Vs, Ns, QLt, QRt)) if cached else list(zip(Gs, QLs, QRs, Ms, Vs, Ns))
+        need = [ast.soap_step_workspace_bytes(items)]
+        for t in (1, 2):
+            ast.soap_step(items, 0.9, 0.95, 1e-8, t)
+        torch.cuda.synchronize()
+        out.append((Ms, Vs, Ns, need[0]))
+    for a, b in zip(out[0][:3], out[1][:3]):
+        assert all(torch.equal(x, y) for x, y in zip(a, b))
+    assert out[1][3] < out[0][3]                       # and the workspace no longer holds the copies
+    # only one of the two kept: the other is still made by the call
+    Ms = [torch.zeros(m, n, device=DEV) for m, n in shapes]
+    Vs = [torch.zeros(m, n, device=DEV) for m, n in shapes]
+    Ns = [torch.full((m, n), float("nan"), device=DEV) for m, n in shapes]
+    items = list(zip(Gs, QLs, QRs, Ms, Vs, Ns, QLt, [None] * 3))
+    for t in (1, 2):
+        ast.soap_step(items, 0.9, 0.95, 1e-8, t)
+    torch.cuda.synchronize()
+    assert all(torch.equal(x, y) for x, y in zip(Ns, out[0][2]))
+
+
 def test_soap_step_identity_bases_reduce_to_adam():
     m, n = 33, 65
     G = W.gaussian_block(m, n, 0.02, DEV, 120)
