@@ -517,10 +517,11 @@ def soap_section(args, torch, ast, W, dev):
     Vs = [torch.zeros(m, n, device=dev) for m, n in shapes]
     Ns = [torch.empty(m, n, device=dev) for m, n in shapes]
     blocks = [ast.Blocks(list(zip(G, Ls, Rs))) for G in Gsets]
-    # the step reads Q^T along rows: the transposes are kept beside the bases and redone after every refresh
-    QLts = [torch.empty(m, m, device=dev) for m, n in shapes]
-    QRts = [torch.empty(n, n, device=dev) for m, n in shapes]
-    tpairs = list(zip(QLs, QLts)) + list(zip(QRs, QRts))
+    # the step reads Q^T along rows: the transposes are kept beside the bases, and every refresh leaves the
+    # new ones there (the bases start as the identity, which is its own transpose)
+    QLts = [torch.eye(m, device=dev) for m, n in shapes]
+    QRts = [torch.eye(n, device=dev) for m, n in shapes]
+    qts = QLts + QRts
     sblocks = [ast.SBlocks(list(zip(G, QLs, QRs, Ms, Vs, Ns, QLts, QRts))) for G in Gsets]
     factors = ast.Factors(list(zip(Ls, QLs)) + list(zip(Rs, QRs)))
     fsize = [m for m, n in shapes] + [n for m, n in shapes]
@@ -534,8 +535,7 @@ def soap_section(args, torch, ast, W, dev):
     aux = [torch.cuda.Stream() for _ in range(max(1, min(4, args.soap_groups)))]   # groups of factors side by side (default priority)
     for w in range(3):                          # warm the bases from the identity
         ast.stats_update(blocks[w % nsets], beta, ws=ws)
-        ast.soap_refresh(factors, info=info, ws=ws, aux_streams=aux)
-    ast.transpose(tpairs)
+        ast.soap_refresh(factors, info=info, ws=ws, aux_streams=aux, qt=qts, qt_valid=True)
     torch.cuda.synchronize()
     ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
     for t in range(args.steps):
@@ -548,14 +548,12 @@ def soap_section(args, torch, ast, W, dev):
     torch.cuda.synchronize()                                # the device is idle: the host time of the call means something
     r0.record()
     t_host = time.time()
-    ast.soap_refresh(factors, info=info, ws=ws, aux_streams=aux)
+    ast.soap_refresh(factors, info=info, ws=ws, aux_streams=aux, qt=qts, qt_valid=True)
     enqueue_ms = 1e3 * (time.time() - t_host)               # the call returns once everything is enqueued
-    ast.transpose(tpairs)                                   # part of the refresh: the copies the steps read
     r1.record()
     torch.cuda.synchronize()
     r2.record()
-    ast.soap_refresh(factors, info=info, ws=ws)            # the same refresh on the caller's stream alone
-    ast.transpose(tpairs)
+    ast.soap_refresh(factors, info=info, ws=ws, qt=qts, qt_valid=True)   # the same refresh on the caller's stream alone
     r3.record()
     torch.cuda.synchronize()
     step_ms = sum(e[0].elapsed_time(e[1]) for e in ev) / args.steps

@@ -332,6 +332,11 @@ asteria_status asteria_precondition(const asteria_pblock *blocks, int nblocks,
  *   rounds  number of (power iteration, QR) rounds in the call, >= 1: from the identity, a few
  *       sorted rounds are orthogonal iteration towards the eigenbasis - the device-side stand-in for
  *       the eigendecomposition SOAP starts from.  `perm` needs rounds = 1.
+ *   Xt, ldxt, xt_in  a caller that keeps Q^T beside Q (asteria_soap_step reads it) passes the buffers: the
+ *       call leaves the transpose of the new basis there - the rows it has orthonormalised, a plain copy -
+ *       and reads the product's operand Q^T from there instead of transposing Q in place; xt_in = 1 says
+ *       the buffers hold the transpose of the incoming Q already (they do after a call that was given them),
+ *       otherwise the call fills them first.  Xt[i] must not be f[i].X.
  *   info  device int32[nfactors] or NULL (ASTERIA_INFO_OK, or ASTERIA_INFO_NOT_PD if a column
  *         could not be normalised: an exactly zero or non-finite column, or one that three
  *         sweeps of re-orthogonalisation did not separate from the columns before it).       */
@@ -344,6 +349,9 @@ typedef struct asteria_soap_refresh_opts {
     int32_t rounds;
     int32_t n_aux;
     void *const *aux_streams;
+    float *const *Xt;       /* NULL, or nfactors pointers (each may be NULL): device n x n fp32 buffers for Q^T */
+    const int32_t *ldxt;    /* their leading dimensions (with Xt)                                            */
+    int32_t xt_in;          /* 1: every Xt[i] already holds the transpose of the incoming Q                  */
 } asteria_soap_refresh_opts;
 void asteria_soap_refresh_opts_default(asteria_soap_refresh_opts *opts);
 asteria_status asteria_soap_refresh_ex(const asteria_factor *f, int nfactors, const asteria_soap_refresh_opts *opts,

@@ -69,7 +69,8 @@ class _RBlock(Structure):
 class SoapRefreshOpts(Structure):
     """Mirror of asteria_soap_refresh_opts."""
     _fields_ = [("sort", c_int32), ("from_identity", c_int32), ("rounds", c_int32), ("n_aux", c_int32),
-                ("aux_streams", POINTER(c_void_p))]
+                ("aux_streams", POINTER(c_void_p)), ("Xt", POINTER(c_void_p)), ("ldxt", POINTER(c_int32)),
+                ("xt_in", c_int32)]
 
 
 class RootOpts(Structure):
@@ -438,8 +439,9 @@ def soap_refresh_workspace_bytes(factors):
 
 def soap_refresh(factors, info: Optional[torch.Tensor] = None, ws: Optional[torch.Tensor] = None,
                  stream=None, aux_streams=None, sort: bool = False, from_identity: bool = False, rounds: int = 1,
-                 perm: Optional[torch.Tensor] = None) -> None:
-    """Q <- qr(A Q).Q for every (A, Q), in place.  ``aux_streams``: up to four torch streams on which
+                 perm: Optional[torch.Tensor] = None, qt=None, qt_valid: bool = False) -> None:
+    """Q <- qr(A Q).Q for every (A, Q), in place.  ``qt``: per factor a tensor that receives Q^T (or None);
+    ``qt_valid``: those tensors already hold the transpose of the incoming Q.  ``aux_streams``: up to four torch streams on which
     groups of factors are enqueued side by side; ``sort``: columns ordered by decreasing q^T A q first
     (``perm``: int32 GPU tensor of sum(n) entries receiving the orders); ``from_identity`` / ``rounds``:
     start from Q = I and run several rounds (asteria_soap_refresh_ex)."""
@@ -448,7 +450,7 @@ def soap_refresh(factors, info: Optional[torch.Tensor] = None, ws: Optional[torc
     if ws is None:
         ws = _workspace(None, soap_refresh_workspace_bytes(f)[0], dev)
     ws = _workspace(ws, 0, dev)
-    if not (aux_streams or sort or from_identity or rounds != 1 or perm is not None):
+    if not (aux_streams or sort or from_identity or rounds != 1 or perm is not None or qt is not None):
         _check(lib().asteria_soap_refresh(f.array, f.count, _ptr(info, torch.int32, f.count, "info"),
                                           c_void_p(ws.data_ptr()), ws.numel(), _stream(stream)),
                "asteria_soap_refresh")
@@ -460,6 +462,18 @@ def soap_refresh(factors, info: Optional[torch.Tensor] = None, ws: Optional[torc
     if aux_streams:
         aux = (c_void_p * len(aux_streams))(*[s.cuda_stream for s in aux_streams])
         o.n_aux, o.aux_streams = len(aux_streams), ctypes.cast(aux, POINTER(c_void_p))
+    xt_arr = ld_arr = None
+    if qt is not None:
+        qt = list(qt)
+        if len(qt) != f.count:
+            raise ValueError("qt: one entry per factor")
+        xt_arr, ld_arr = (c_void_p * f.count)(), (c_int32 * f.count)()
+        for i, t in enumerate(qt):
+            ptr, r, c, ld = _mat(t, "qt", torch.float32)
+            if t is not None and (r, c) != tuple(f.items[i][1].shape):
+                raise ValueError("qt: shape of the basis expected")
+            xt_arr[i], ld_arr[i] = ptr, ld
+        o.Xt, o.ldxt, o.xt_in = ctypes.cast(xt_arr, POINTER(c_void_p)), ctypes.cast(ld_arr, POINTER(c_int32)), int(bool(qt_valid))
     total = sum(it[0].shape[0] for it in f.items)
     _check(lib().asteria_soap_refresh_ex(f.array, f.count, ctypes.byref(o), _ptr(info, torch.int32, f.count, "info"),
                                          _ptr(perm, torch.int32, total, "perm"), c_void_p(ws.data_ptr()), ws.numel(),

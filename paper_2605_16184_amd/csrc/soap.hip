@@ -128,6 +128,10 @@ struct QrFactor {
     const float *A;  // the statistic (read for its trace)
     int lda, pad2_;
     float *cbuf;     // QR_PANEL x ldz: projection coefficients of the current panel
+    // Where Q^T stands when a round starts (rows q_i^T: the k-contiguous operand of Z^T = Q^T A): the
+    // caller's Q buffer, transposed in place, or a buffer of the caller that holds Q^T beside Q
+    float *Qt;
+    int ldqt, pad3_;
     double *est;     // n estimated eigenvalues q_i^T A q_i (column order of the refresh's input)
     int *perm;       // n: perm[r] = input column that becomes column r
     int *perm_out;   // the caller's slice of the permutation output, or null
@@ -337,6 +341,7 @@ __global__ void qr_info_kernel(const QrFactor *fs, int nf, int32_t *info)
 __global__ __launch_bounds__(256) void transpose_inplace_kernel(const QrFactor *fs)
 {
     const QrFactor &F = fs[blockIdx.y];
+    if (F.Qt != F.Qout) return;                       // the caller keeps Q^T beside Q: nothing to transpose
     const int tpr = (F.n + 31) / 32, tmax = (int)rintf(sqrtf((float)gridDim.x));
     const int ti = (int)blockIdx.x / tmax, tj = (int)blockIdx.x % tmax;
     if (ti > tj || tj >= tpr) return;
@@ -387,6 +392,38 @@ __global__ __launch_bounds__(256) void set_identity_kernel(const QrFactor *fs)
     for (size_t e = (size_t)blockIdx.x * 256 + threadIdx.x; e < (size_t)F.n * F.n; e += (size_t)gridDim.x * 256) {
         const int i = (int)(e / F.n), j = (int)(e % F.n);
         F.Qout[(size_t)i * F.ldq + j] = (i == j) ? 1.0f : 0.0f;
+        if (F.Qt != F.Qout) F.Qt[(size_t)i * F.ldqt + j] = (i == j) ? 1.0f : 0.0f;
+    }
+}
+
+// Q^T kept beside Q by the caller.  mode 0: Qt <- Q^T (the buffer does not hold it yet), 32 x 32 tiles
+// through LDS; mode 1: Qt <- Zt (the rows of Z^T are the new basis vectors when a round ends), a plain
+// copy.  Grid: x = 32 x 32 tile of the largest factor's tile grid, y = factor; factors without such a
+// buffer do nothing.
+__global__ __launch_bounds__(256) void keep_qt_kernel(const QrFactor *fs, int mode)
+{
+    const QrFactor &F = fs[blockIdx.y];
+    if (F.Qt == F.Qout) return;
+    const int tpr = (F.n + 31) / 32, tmax = (int)rintf(sqrtf((float)gridDim.x));
+    const int ti = (int)blockIdx.x / tmax, tj = (int)blockIdx.x % tmax;
+    if (ti >= tpr || tj >= tpr) return;
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+    if (mode == 1) {
+        for (int r = ty; r < 32; r += 8) {
+            const int i = ti * 32 + r, c = tj * 32 + tx;
+            if (i < F.n && c < F.n) F.Qt[(size_t)i * F.ldqt + c] = F.Zt[(size_t)i * F.ldz + c];
+        }
+        return;
+    }
+    __shared__ float tile[32][33];
+    for (int r = ty; r < 32; r += 8) {
+        const int i = ti * 32 + r, c = tj * 32 + tx;
+        tile[r][tx] = (i < F.n && c < F.n) ? F.Qout[(size_t)i * F.ldq + c] : 0.0f;
+    }
+    __syncthreads();
+    for (int r = ty; r < 32; r += 8) {
+        const int i = tj * 32 + r, c = ti * 32 + tx;     // Qt(i, c) = Q(c, i)
+        if (i < F.n && c < F.n) F.Qt[(size_t)i * F.ldqt + c] = tile[tx][r];
     }
 }
 
@@ -398,7 +435,7 @@ __global__ __launch_bounds__(256) void sort_estimate_kernel(const QrFactor *fs)
     const QrFactor &F = fs[blockIdx.y];
     const int row = (int)blockIdx.x * 4 + (int)(threadIdx.x >> 6), lane = threadIdx.x & 63;
     if (row >= F.n) return;
-    const float *q = F.Qout + (size_t)row * F.ldq, *z = F.Zt + (size_t)row * F.ldz;
+    const float *q = F.Qt + (size_t)row * F.ldqt, *z = F.Zt + (size_t)row * F.ldz;
     double s = 0.0;
     for (int k = lane; k < F.n; k += 64) s += (double)q[k] * (double)z[k];
 #pragma unroll
@@ -466,12 +503,12 @@ __global__ __launch_bounds__(128) void refresh_tables_kernel(QrFactor *fs, int c
     p.alpha = 1.0f; p.beta = 0.0f;
     if (j == 0) {
         // Z^T = Q^T A on the fp16 cores (two terms per operand): A'(i, k) = Q^T[i][k] - the caller's Q has
-        // been transposed in place by then -, scaled by 2^14, and B'(j, k) = A[j][k] (A is symmetric),
+        // been transposed in place by then, or the caller keeps Q^T -, scaled by 2^14, and B'(j, k) = A[j][k] (A is symmetric),
         // scaled by the factor's a_scale; both k-contiguous
         GemmProblem g = p;
         g.state_idx = -1; g.state_mask = ~0;
         g.M = g.N = g.K = F.n; g.tiles_n = tn;
-        g.A = F.Qout; g.lda = F.ldq; g.B = F.A; g.ldb = F.lda; g.C = F.Zt; g.ldc = F.ldz;
+        g.A = F.Qt; g.lda = F.ldqt; g.B = F.A; g.ldb = F.lda; g.C = F.Zt; g.ldc = F.ldz;
         g.sa = QR_UNIT_SCALE; g.sb_dev = a_scale;
         g.tile_start = T.pz[i];
         T.z[i] = g;
@@ -839,6 +876,7 @@ extern "C" void asteria_soap_refresh_opts_default(asteria_soap_refresh_opts *o)
 {
     if (!o) return;
     o->sort = 0; o->from_identity = 0; o->rounds = 1; o->n_aux = 0; o->aux_streams = nullptr;
+    o->Xt = nullptr; o->ldxt = nullptr; o->xt_in = 0;
 }
 
 extern "C" asteria_status asteria_soap_refresh_ex(const asteria_factor *f, int nfactors,
@@ -852,6 +890,8 @@ extern "C" asteria_status asteria_soap_refresh_ex(const asteria_factor *f, int n
     if ((o.sort != 0 && o.sort != 1) || (o.from_identity != 0 && o.from_identity != 1) || o.rounds < 1 || o.rounds > 1000)
         return ASTERIA_INVALID_ARG;
     if (perm && (!o.sort || o.rounds != 1)) return ASTERIA_INVALID_ARG;   // the order of ONE sorted round can be reported
+    if (o.xt_in != 0 && o.xt_in != 1) return ASTERIA_INVALID_ARG;
+    if ((o.Xt != nullptr) != (o.ldxt != nullptr)) return ASTERIA_INVALID_ARG;
     void *const *aux_streams = o.aux_streams;
     const int n_aux = o.n_aux;
     if (n_aux < 0 || n_aux > REFRESH_MAX_GROUPS || (n_aux > 0 && !aux_streams)) return ASTERIA_INVALID_ARG;
@@ -862,6 +902,7 @@ extern "C" asteria_status asteria_soap_refresh_ex(const asteria_factor *f, int n
         if (!f[i].A || !f[i].X || f[i].n <= 0 || f[i].lda < f[i].n || f[i].ldx < f[i].n) return ASTERIA_INVALID_ARG;
         if (f[i].a_layout != ASTERIA_LAYOUT_FULL) return ASTERIA_UNSUPPORTED;   // A is an operand of the product A Q: full storage
         if (f[i].n > QR_MAXN) return ASTERIA_UNSUPPORTED;
+        if (o.Xt && o.Xt[i] && (o.ldxt[i] < f[i].n || o.Xt[i] == f[i].X)) return ASTERIA_INVALID_ARG;
         n_all = f[i].n > n_all ? f[i].n : n_all;
     }
     if (!ws) return ASTERIA_WORKSPACE_TOO_SMALL;
@@ -904,6 +945,7 @@ extern "C" asteria_status asteria_soap_refresh_ex(const asteria_factor *f, int n
 
         QrFactor *d_q = cv.take<QrFactor>(cnt);
         std::vector<QrFactor> q;
+        bool any_qt = false;                       // some factor's Q^T is kept by the caller
         // off | pt | pz: see RefreshTables
         std::vector<int> ints((size_t)(np_max + 1) + 2 * (size_t)(cnt + 1), 0);
         int *off = ints.data(), *pt = off + np_max + 1, *pz = pt + cnt + 1;
@@ -919,6 +961,8 @@ extern "C" asteria_status asteria_soap_refresh_ex(const asteria_factor *f, int n
             F.winv = cv.take<float>((size_t)QR_PANEL * QR_PANEL);
             F.Qout = a.X; F.n = n; F.ldz = ldz; F.ldq = a.ldx; F.bad = 0; F.run = 0; F.skip3 = 1;
             F.out_index = idx[i];
+            F.Qt = a.X; F.ldqt = a.ldx;
+            if (o.Xt && o.Xt[idx[i]]) { F.Qt = o.Xt[idx[i]]; F.ldqt = o.ldxt[idx[i]]; any_qt = true; }
             F.a_scale = 1.0f; F.p_scale = 1.0f; F.A = a.A; F.lda = a.lda;
             F.est = cv.take<double>((size_t)n);
             F.perm = cv.take<int>((size_t)n);
@@ -953,11 +997,13 @@ extern "C" asteria_status asteria_soap_refresh_ex(const asteria_factor *f, int n
         if (o.from_identity)
             hipLaunchKernelGGL(set_identity_kernel, dim3((unsigned)std::min<size_t>(((size_t)n_max * n_max + 255) / 256, 4096), (unsigned)cnt),
                                dim3(256), 0, stream, d_q);
+        const unsigned tpr32 = (unsigned)((n_max + 31) / 32);
+        // a kept Q^T that the caller has not filled (or a start from the identity, which the kernel above
+        // wrote to both buffers) is made from Q once; every round then leaves the new one there
+        if (any_qt && !o.xt_in && !o.from_identity)
+            hipLaunchKernelGGL(keep_qt_kernel, dim3(tpr32 * tpr32, (unsigned)cnt), dim3(256), 0, stream, d_q, 0);
         for (int round = 0; round < o.rounds; ++round) {
-        {
-            const unsigned tpr = (unsigned)((n_max + 31) / 32);
-            hipLaunchKernelGGL(transpose_inplace_kernel, dim3(tpr * tpr, (unsigned)cnt), dim3(256), 0, stream, d_q);
-        }
+        hipLaunchKernelGGL(transpose_inplace_kernel, dim3(tpr32 * tpr32, (unsigned)cnt), dim3(256), 0, stream, d_q);
         ASTERIA_HIP_TRY((launch_gemm_bf16_grouped<float, float, 2, 2, true>(d_g, cnt, tiles, nullptr, stream)));
         if (o.sort) {
             // order the columns by q_i^T A q_i = (row i of Q^T) . (row i of Z^T), largest first: the rows of
@@ -1005,6 +1051,8 @@ extern "C" asteria_status asteria_soap_refresh_ex(const asteria_factor *f, int n
             hipLaunchKernelGGL(transpose_panel_kernel, dim3((QR_PANEL / 32) * ((n_max + 31) / 32), (unsigned)count[j]),
                                dim3(256), 0, stream, d_q, j);
         }
+        if (any_qt)
+            hipLaunchKernelGGL(keep_qt_kernel, dim3(tpr32 * tpr32, (unsigned)cnt), dim3(256), 0, stream, d_q, 1);
         }   // rounds
         hipLaunchKernelGGL(qr_info_kernel, dim3((cnt + 127) / 128), dim3(128), 0, stream, d_q, cnt, info);
         ASTERIA_HIP_TRY(hipGetLastError());

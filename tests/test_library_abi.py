@@ -167,6 +167,16 @@ def test_precondition_and_soap_reject_bad_arguments_without_launching():
     perm = ctypes.c_void_p(0x7000)
     assert ex(_fac(), 1, opts(), None, perm, ws, 1 << 20, None) == B.INVALID_ARG               # an order without sorting
     assert ex(_fac(), 1, opts(sort=1, rounds=2), None, perm, ws, 1 << 20, None) == B.INVALID_ARG
+    # buffers for Q^T: pointers and leading dimensions come together, a buffer is not Q itself, ld >= n
+    xt = ctypes.cast((ctypes.c_void_p * 1)(0x8000), ctypes.POINTER(ctypes.c_void_p))
+    xq = ctypes.cast((ctypes.c_void_p * 1)(0x2000), ctypes.POINTER(ctypes.c_void_p))
+    ld8 = ctypes.cast((ctypes.c_int32 * 1)(8), ctypes.POINTER(ctypes.c_int32))
+    ld7 = ctypes.cast((ctypes.c_int32 * 1)(7), ctypes.POINTER(ctypes.c_int32))
+    assert ex(_fac(), 1, opts(Xt=xt), None, None, ws, 1 << 20, None) == B.INVALID_ARG
+    assert ex(_fac(), 1, opts(Xt=xt, ldxt=ld7), None, None, ws, 1 << 20, None) == B.INVALID_ARG
+    assert ex(_fac(), 1, opts(Xt=xq, ldxt=ld8), None, None, ws, 1 << 20, None) == B.INVALID_ARG
+    assert ex(_fac(), 1, opts(Xt=xt, ldxt=ld8, xt_in=2), None, None, ws, 1 << 20, None) == B.INVALID_ARG
+    assert ex(_fac(), 1, opts(Xt=xt, ldxt=ld8, xt_in=1), None, None, ws, 128, None) == B.WORKSPACE_TOO_SMALL
     # re-projection of the moments
     rp = lib.asteria_soap_reproject
     def rblk(**kw):

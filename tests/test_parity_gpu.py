@@ -812,6 +812,40 @@ def spectrum_factor(n, lam, *key):
     return (0.5 * (A + A.T)).float().contiguous(), U.float().contiguous()
 
 
+def test_soap_refresh_leaves_the_transposed_basis_in_a_buffer_of_the_caller():
+    """With buffers for Q^T the refresh reads its operand from them instead of transposing Q in place and
+    leaves the new Q^T there: same values through the same products, so Q is bit-identical to the plain
+    call, Q^T is its exact transpose, and a second refresh that is told the buffers are valid agrees too."""
+    ns = [200, 257, 64, 320]
+    As = [powerlaw_factor(n, 120 + i) for i, n in enumerate(ns)]
+    Q0 = [W.haar(n, DEV, 130 + i) for i, n in enumerate(ns)]
+    ref = [q.clone() for q in Q0]
+    ast.soap_refresh(list(zip(As, ref)))
+    ast.soap_refresh(list(zip(As, ref)))
+    Qs = [q.clone() for q in Q0]
+    Qt = [padded(n, n, 4) if i % 2 else torch.full((n, n), float("nan"), device=DEV) for i, n in enumerate(ns)]
+    Qt[2] = None                                                     # a factor without such a buffer
+    info = torch.full((len(ns),), -1, dtype=torch.int32, device=DEV)
+    ast.soap_refresh(list(zip(As, Qs)), info=info, qt=Qt)                      # buffers not filled yet
+    ast.soap_refresh(list(zip(As, Qs)), info=info, qt=Qt, qt_valid=True)       # ... now they are
+    torch.cuda.synchronize()
+    assert np.all(info.cpu().numpy() == B.INFO_OK)
+    for q, r, t in zip(Qs, ref, Qt):
+        assert torch.equal(q, r)
+        if t is not None:
+            assert torch.equal(t, q.T)
+    # sorted, from the identity, two rounds, on two streams: the same against the call without buffers
+    ref = [torch.empty_like(q) for q in Q0]
+    aux = [torch.cuda.Stream(), torch.cuda.Stream()]
+    ast.soap_refresh(list(zip(As, ref)), sort=True, from_identity=True, rounds=2, aux_streams=aux)
+    Qs = [torch.empty_like(q) for q in Q0]
+    Qt = [torch.full((n, n), float("nan"), device=DEV) for n in ns]
+    ast.soap_refresh(list(zip(As, Qs)), sort=True, from_identity=True, rounds=2, aux_streams=aux, qt=Qt)
+    torch.cuda.synchronize()
+    for q, r, t in zip(Qs, ref, Qt):
+        assert torch.equal(q, r) and torch.equal(t, q.T)
+
+
 def test_soap_refresh_with_columns_ordered_by_estimated_eigenvalue():
     # sort = 1: the columns of the basis take the order of decreasing q^T A q before the power iteration
     # (the order SOAP keeps its basis in).  Spectra with well separated estimates, so that the order is
