@@ -428,19 +428,23 @@ def staleness_section(args, torch, ast, run, step_ms, refresh_ms):
     stream behind the training steps and its roots are published under a version counter; a step may
     use roots that are at most S refresh periods old and otherwise waits for the refresh in flight.
     Mock loop: `pf` = 10 steps (statistics + preconditioned gradient of every block, the per-step work
-    of the method) per refresh period, three periods per setting; reported is the time the steps of one
-    period spend waiting for a refresh ("exposed" refresh time) and the period's wall time."""
+    of the method) per refresh period, five periods per setting; reported is the time the steps of one
+    period spend waiting for a refresh ("exposed" refresh time), the period's wall time and how many
+    refreshes were started in the window (without waiting the steps of a period can finish before its
+    refresh does; the next refresh then starts late)."""
     from paper_2605_16184_amd.staleness import RefreshPipeline
-    pf, periods = 10, 3
+    pf, periods = 10, 5
     out = {"pf": pf, "periods_timed": periods, "step_ms": round(step_ms, 3), "refresh_ms": round(refresh_ms, 3),
            "synchronous_period_ms": round(pf * step_ms + refresh_ms, 1), "sweep": []}
     pipe = RefreshPipeline(torch, ast, run, pf=pf)
     for S in (0, 1, 2, 3, 5, 10):
         r = pipe.run(periods, S)
-        out["sweep"].append({"S": S, "period_ms": round(r["period_ms"], 1), "exposed_refresh_ms": round(r["exposed_ms"], 1),
+        out["sweep"].append({"S": S, "period_ms": round(r["period_ms"], 1), "refreshes_started": r["refreshes_started"],
+                             "exposed_refresh_ms": round(r["exposed_ms"], 1),
                              "max_step_ms": round(r["max_step_ms"], 1), "median_step_ms": round(r["median_step_ms"], 1),
                              "max_version_age_used": r["max_age"], "not_converged": r["not_converged"]})
-        log(f"[bench] staleness S={S}: period {r['period_ms']:.1f} ms, exposed refresh {r['exposed_ms']:.1f} ms, longest step "
+        log(f"[bench] staleness S={S}: period {r['period_ms']:.1f} ms ({r['refreshes_started']} refreshes started in {periods}), "
+            f"exposed refresh {r['exposed_ms']:.1f} ms, longest step "
             f"{r['max_step_ms']:.1f} ms (median {r['median_step_ms']:.1f}), oldest roots used {r['max_age']} periods")
     del pipe
     return out

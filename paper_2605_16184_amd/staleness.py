@@ -100,11 +100,11 @@ class RefreshPipeline:
         self._publish()
         torch.cuda.synchronize()
         waited, max_age, step_events = 0.0, 0, []
-        t_start, launched = None, -1
+        t_start, launched, n_launched = None, -1, 0
         for p in range(warm_periods + periods):
             if p == warm_periods:
                 torch.cuda.synchronize()
-                waited, max_age, step_events = 0.0, 0, []
+                waited, max_age, step_events, n_launched = 0.0, 0, [], 0
                 t_start = time.time()
             for s in range(self.pf):
                 if self.pending is not None and self.pending[1].query():
@@ -112,6 +112,7 @@ class RefreshPipeline:
                 if self.pending is None and launched < p:
                     self._launch_refresh(p)                      # a refresh is due once per period, as soon as
                     launched = p                                 # the one before it has been published
+                    n_launched += 1
                 if p - self.version > self.S and self.pending is not None:
                     t = time.time()
                     self.pending[1].synchronize()                # staleness barrier: wait for the refresh in flight
@@ -129,7 +130,10 @@ class RefreshPipeline:
             self.pending[1].synchronize()
             self._publish()
             torch.cuda.synchronize()
-        return {"period_ms": 1e3 * wall / periods, "exposed_ms": 1e3 * waited / periods, "max_age": int(max_age),
+        # without waiting (large S) the steps of a period can finish before its refresh does: the refresh of
+        # the next period then starts late, and fewer than `periods` refreshes fall into the timed window
+        return {"period_ms": 1e3 * wall / periods, "refreshes_started": int(n_launched),
+                "exposed_ms": 1e3 * waited / periods, "max_age": int(max_age),
                 "max_step_ms": max(lat) if lat else 0.0, "median_step_ms": sorted(lat)[len(lat) // 2] if lat else 0.0,
                 "not_converged": int((self.info != 0).sum())}
 
