@@ -846,6 +846,28 @@ def test_soap_refresh_leaves_the_transposed_basis_in_a_buffer_of_the_caller():
         assert torch.equal(q, r) and torch.equal(t, q.T)
 
 
+def test_soap_refresh_in_several_passes_through_a_small_workspace():
+    """A workspace that holds the largest factor only: the call works through the batch in passes (with
+    two stream groups and kept transposes) and must return what the one-pass call returns."""
+    ns = [257, 64, 200, 130, 31]
+    As = [powerlaw_factor(n, 140 + i) for i, n in enumerate(ns)]
+    Q0 = [W.haar(n, DEV, 150 + i) for i, n in enumerate(ns)]
+    ref = [q.clone() for q in Q0]
+    ast.soap_refresh(list(zip(As, ref)), sort=True)
+    full, smallest = ast.soap_refresh_workspace_bytes(list(zip(As, Q0)))
+    assert smallest < full
+    ws = torch.empty(smallest, dtype=torch.uint8, device=DEV)
+    aux = [torch.cuda.Stream(), torch.cuda.Stream()]
+    Qs = [q.clone() for q in Q0]
+    Qt = [torch.full((n, n), float("nan"), device=DEV) for n in ns]
+    info = torch.full((len(ns),), -1, dtype=torch.int32, device=DEV)
+    ast.soap_refresh(list(zip(As, Qs)), info=info, ws=ws, sort=True, aux_streams=aux, qt=Qt)
+    torch.cuda.synchronize()
+    assert np.all(info.cpu().numpy() == B.INFO_OK)
+    for q, r, t in zip(Qs, ref, Qt):
+        assert torch.equal(q, r) and torch.equal(t, q.T)
+
+
 def test_soap_refresh_with_columns_ordered_by_estimated_eigenvalue():
     # sort = 1: the columns of the basis take the order of decreasing q^T A q before the power iteration
     # (the order SOAP keeps its basis in).  Spectra with well separated estimates, so that the order is
