@@ -311,8 +311,9 @@ asteria_status asteria_precondition(const asteria_pblock *blocks, int nblocks,
  * coefficients of a panel against the finished columns and their subtraction - run on the fp16
  * matrix cores with every fp32 operand split into two fp16 terms (22 bits kept) after a scaling
  * by a power of two taken from tr A, with fp32 accumulation; panel Gram matrices and their
- * Cholesky factors are fp64, the application of the inverse factor and a third sweep, where
- * one is needed, use the fp32 matrix cores.  Columns of Z beyond its numerical rank come out as
+ * Cholesky factors are fp64, the application of the inverse factor uses the fp32 matrix cores; a
+ * panel whose second sweep meets a row that was numerically dependent takes a third one.  The first
+ * sweep of a panel works with one fp16 term of the coefficients (the second removes what that leaves).  Columns of Z beyond its numerical rank come out as
  * an orthonormal completion.  Q is used as scratch during the call (transposed in place, then
  * overwritten panel by panel); where info reports a failure its content is unspecified.
  * asteria_soap_refresh enqueues everything on `stream`.  asteria_soap_refresh_ex takes options

@@ -325,7 +325,9 @@ __global__ __launch_bounds__(CHOL_THREADS) void panel_chol_inverse_kernel(QrFact
     if (tid == 0) {
         if (bad_flag == 1 || (bad_flag == 2 && sweep == 2)) F.bad = 1;
         if (sweep == 0) { F.skip3 = 1; F.p_scale = QR_UNIT_SCALE; }       // the rows are normalised now
-        if (sweep == 1) { F.p_scale = F.a_scale; if (bad_flag == 2) F.skip3 = 0; }   // next panel: rows of Z^T again
+        // after the last sweep of a panel the scale goes back to that of the rows of Z^T (the next panel)
+        if (sweep == 1) { if (bad_flag == 2) F.skip3 = 0; else F.p_scale = F.a_scale; }
+        if (sweep == 2) F.p_scale = F.a_scale;
     }
 }
 
@@ -1027,7 +1029,8 @@ extern "C" asteria_status asteria_soap_refresh_ex(const asteria_factor *f, int n
                 const int *st = sweep < 2 ? st_run : st_third;
                 if (j > 0) {
                     // projection coefficients: fp32 operands as two fp16 terms each (2^-22) in the second
-                    // sweep; the rare third sweep stays on the fp32 cores
+                    // sweep and in the third, which only the factors that need it run (their rows are still
+                    // normalised there: the Cholesky kernel keeps the unit scale until a panel's last sweep)
                     // first sweep: the coefficients as one fp16 term per operand, and one term of them in
                     // the update (the finished rows keep both terms, so the panel stays in the span of
                     // its own rows and the finished ones to 2^-22): what this leaves along the finished
@@ -1039,8 +1042,8 @@ extern "C" asteria_status asteria_soap_refresh_ex(const asteria_factor *f, int n
                         ASTERIA_HIP_TRY((launch_gemm_bf16_grouped<float, float, 2, 2, true>(T1(j), count[j], tiles1(j), st, stream)));
                         ASTERIA_HIP_TRY((launch_gemm_bf16_grouped<float, float, 2, 2, true>(T2(j), count[j], tiles24(j), st, stream)));
                     } else {
-                        ASTERIA_HIP_TRY((launch_gemm_grouped<float, float, float, false, false>(T1(j), count[j], tiles1(j), st, stream)));
-                        ASTERIA_HIP_TRY((launch_gemm_grouped<float, float, float, false, false>(T2(j), count[j], tiles24(j), st, stream)));
+                        ASTERIA_HIP_TRY((launch_gemm_bf16_grouped<float, float, 2, 2, true>(T1(j), count[j], tiles1(j), st, stream)));
+                        ASTERIA_HIP_TRY((launch_gemm_bf16_grouped<float, float, 2, 2, true>(T2(j), count[j], tiles24(j), st, stream)));
                     }
                 }
                 ASTERIA_HIP_TRY((launch_gemm_grouped<double, float, float, false, false>(T3(j), count[j], count[j], st, stream)));
