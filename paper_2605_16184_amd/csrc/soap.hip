@@ -411,9 +411,16 @@ __global__ __launch_bounds__(256) void keep_qt_kernel(const QrFactor *fs, int mo
     if (ti >= tpr || tj >= tpr) return;
     const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
     if (mode == 1) {
-        for (int r = ty; r < 32; r += 8) {
-            const int i = ti * 32 + r, c = tj * 32 + tx;
-            if (i < F.n && c < F.n) F.Qt[(size_t)i * F.ldqt + c] = F.Zt[(size_t)i * F.ldz + c];
+        // one 16-byte piece per thread where the caller's buffer allows it (the workspace rows always do)
+        const bool vec = ((reinterpret_cast<uintptr_t>(F.Qt) & 15u) == 0) && ((F.ldqt & 3) == 0);
+        const int i = ti * 32 + (int)(threadIdx.x >> 3), c = tj * 32 + 4 * (int)(threadIdx.x & 7);
+        if (i >= F.n || c >= F.n) return;
+        const float *src = F.Zt + (size_t)i * F.ldz + c;
+        float *dst = F.Qt + (size_t)i * F.ldqt + c;
+        if (vec && c + 4 <= F.n) {
+            *reinterpret_cast<float4 *>(dst) = *reinterpret_cast<const float4 *>(src);
+        } else {
+            for (int e = 0; e < 4 && c + e < F.n; ++e) dst[e] = src[e];
         }
         return;
     }
