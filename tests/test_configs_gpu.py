@@ -158,7 +158,7 @@ def _spectral_root(A: torch.Tensor, eps_rel: float) -> torch.Tensor:
     return (V * (w + eps_rel * w[-1]) ** -0.25) @ V.T
 
 
-@pytest.mark.parametrize("n,nblocks", [(512, 2), (4096, 8)])
+@pytest.mark.parametrize("n,nblocks", [(512, 2), (2048, 4), (4096, 8)])
 def test_ill_conditioned_blocks_against_stored_oracle_rows(started, n, nblocks):
     # (`started`: this test runs while the oracle threads of the other configurations work)
     if not os.path.exists(os.path.join(GOLDEN, "cfg5_block0" + ("" if n == 4096 else f"_n{n}") + ".npz")):
