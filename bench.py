@@ -228,7 +228,7 @@ def gemm_rooflines(res, steps, step_ms):
     dominant = max(shares, key=shares.get)
     out["roofline"] = dict(out[dominant], time_share_of_step=round(1e3 * shares[dominant] / steps / step_ms, 4))
     # the refresh as a whole: every kernel's fraction of its own peak weighted by its time, the time
-    # outside GEMM kernels (slicing, power iteration, start, hand-over, control) counting as zero
+    # outside GEMM kernels (slicing, lambda_max estimate, start, hand-over, control) counting as zero
     refresh_ms = res["refresh_ms"]
     in_gemm = sum(1e3 * v / steps for v in shares.values())
     weighted = sum(out[k]["frac"] * 1e3 * shares[k] / steps for k in shares) / refresh_ms

@@ -149,13 +149,15 @@ typedef struct asteria_root_opts {
     int32_t max_iters;     /* upper bound on coupled iterations per factor (default 40)               */
     int32_t fp64_iters;    /* leading iterations run on fp64 MFMA: -1 = choose from eps (default),
                               0 = fp32 only, >= max_iters = fp64 throughout                            */
-    int32_t power_iters;   /* upper bound on power-iteration steps for lambda_max (default 256)       */
+    int32_t power_iters;   /* upper bound on the steps (one product A v each) of the lambda_max estimate
+                              (default 256; the Lanczos recurrence keeps at most 128)                  */
     int32_t schedule;      /* coefficients of T = a I - g M: 1 = adapted per factor and iteration to the
                               interval known to hold M's spectrum (default; about half the iterations),
                               0 = classical coupled Newton, a = (root+1)/root, g = 1/root              */
     float stop_resid;      /* a factor takes its last step once ||M - I||_F < stop_resid (default 1e-2;
                               the step after that squares the residual)                                */
-    float power_tol;       /* power iteration stops at ||A v - rho v|| <= power_tol * rho (default 1e-3) */
+    float power_tol;       /* the lambda_max estimate stops once two consecutive steps have raised it by less
+                              than power_tol^2 of itself (default 1e-3, i.e. 1e-6)                     */
     float lambda_margin;   /* spectrum is scaled by 1 / ((1 + lambda_margin) lambda_max + eps)
                               (default 0.01) so an underestimated lambda_max stays inside (0, 1]      */
     int32_t lowp_from;     /* first iteration that may run on the fp16 matrix cores with the fp32 operands
@@ -217,7 +219,8 @@ asteria_status asteria_sym_unpack(const asteria_sympair *items, int nitems, void
  *
  *   step                what the device does
  *   ------------------  --------------------------------------------------------------------------
- *   lambda_max          power iteration on A, stopped per factor at ||A v - rho v|| <= power_tol rho
+ *   lambda_max          Lanczos process on A (three-term recurrence from a fixed start vector, one product
+ *                       A v per step): the largest Ritz value, stopped per factor when it has settled
  *   scaling             s = 1 / ((1 + margin) lambda_max + eps); M_0 = s (A + eps I), X_0 = s^(1/root) I;
  *                       the spectrum of M_0 is taken to lie in [eps s / 2, 1]
  *   iteration           T = a I - g M, X <- X T, M <- T^root M; (a, g) per factor and iteration from
@@ -239,8 +242,10 @@ asteria_status asteria_sym_unpack(const asteria_sympair *items, int nitems, void
  * What the interval-based choices rely on.  A is positive semi-definite up to round-off: eigenvalues
  * down to -eps / 2 are covered by the lower end eps s / 2 (statistics accumulated in fp32 can fall
  * further below zero when eps is of the order of 1e-8 lambda_max: accumulate those with
- * ASTERIA_ACC_F64).  The power iteration's stop test bounds the distance of rho to SOME eigenvalue;
- * rho is taken for lambda_max, and `lambda_margin` (1 %) is the allowance for the difference.  If
+ * ASTERIA_ACC_F64).  The largest Ritz value never exceeds lambda_max and reaches it to a few 1e-7 on
+ * every workload tested (leading eigenvalues 0.4 % apart included); it stalls below only if the start
+ * vector has no component along the leading eigenvectors, and `lambda_margin` (1 %) is the allowance
+ * for that.  If
  * either assumption fails for a factor - an eigenvalue of M_0 outside [eps s / 2, 1] - the predicted
  * interval is wrong for it: the measured residual then disagrees with the prediction, the factor
  * falls back to the residual rule and runs until ||M - I||_F < stop_resid or max_iters, where it

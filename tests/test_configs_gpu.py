@@ -212,7 +212,7 @@ def test_ill_conditioned_blocks_against_stored_oracle_rows(started, n, nblocks):
         worst_row = float(np.max(np.linalg.norm(np64(X[rows]) - Xr, axis=1) / np.linalg.norm(Xr, axis=1)))
         print(f"n={n} side {side}: lambda_max error {err_l:.2e}, root relF on the stored rows {err:.2e} "
               f"(worst single row {worst_row:.2e}), {iters[f]} iterations")
-        assert err_l <= 1e-3 and err <= TOL_ROOT and worst_row <= 2 * TOL_ROOT, (side, err_l, err, worst_row)
+        assert err_l <= 1e-4 and err <= TOL_ROOT and worst_row <= 2 * TOL_ROOT, (side, err_l, err, worst_row)
         assert torch.equal(X, X.T)
     # preconditioned gradient of block 0, end to end against the oracle chain (its own roots)
     Pr = arr["P_rows"]

@@ -306,10 +306,8 @@ def test_root_single_block_config_absolute_and_relative_eps():
         assert lam.max() / lam.min() < 1.05
         (X,), info, iters, resid, lmax = run_roots([A], 1e-6)
         assert info[0] == B.INFO_OK and 1 <= iters[0] <= 4
-        # nearly flat spectrum (width ~1%): the power iteration stops on its eigen-residual test at
-        # once, so lambda_max is only known to within that width; eps = 1e-6 lambda_max then moves
-        # by the same fraction, which changes the root by < 1e-8 because every eigenvalue >> eps
-        assert abs(lmax[0] - lmax_o) <= 1.5e-2 * lmax_o
+        # nearly flat spectrum (width ~1%): 128 eigenvalues within 1 % of each other
+        assert abs(lmax[0] - lmax_o) <= 1e-4 * lmax_o
         assert relF(X, Xo) <= TOL_ROOT
         (Xa,), info, _, _, _ = run_roots([A], 1e-6 * lmax_o, relative=False)
         assert info[0] == B.INFO_OK and relF(Xa, Xo) <= 1e-5
