@@ -46,6 +46,8 @@ enum : int {
     GEMM_C_BF16 = 4,     // C is stored as bf16 (fp32 compute only)
     GEMM_STORE_T = 8,    // C is stored transposed: element (row, col) at C[col * ldc + row] (no beta, not symmetric)
     GEMM_C_F32 = 16,     // C is stored as fp32 (fp64 compute only): read, combined in fp64, rounded once
+    GEMM_EPI_HANDOVER = 32,  // root epilogue of the last fp64 iteration: C and C2 are not stored (nothing reads the
+                             // fp64 M and T again), C goes to C4 in fp32 instead (C3, the fp32 T, as usual)
     GEMM_C_PACKED = 64   // symmetric C in packed lower-tile storage (see packed_off); ldc unused, nothing above the diagonal tiles
 };
 
@@ -69,13 +71,14 @@ struct GemmProblem {
     void *C;
     void *C2;
     float *C3;          // root epilogue: optional fp32 copy of C2
+    float *C4;          // root epilogue with GEMM_EPI_HANDOVER: fp32 copy of C
     float *partial;
     const float *coef;  // root epilogue: device pointer to (a, g), or null to use ep_a / ep_g
     const float *sa_dev; // fp16-split kernel: device pointer to the scale of operand A, or null to use sa
     const float *sb_dev; // the same for operand B (null: sb)
     const int *gate;     // optional: the problem runs only while *gate == 0
     int M, N, K;
-    int lda, ldb, ldc, ldc2, ldc3;
+    int lda, ldb, ldc, ldc2, ldc3, ldc4;
     int tile_start;  // id of this problem's first tile within the launch
     int tiles_n;     // tile columns (non-symmetric problems)
     int state_idx;   // index into the launch's state[] array, or -1
@@ -485,9 +488,11 @@ __device__ __forceinline__ void gemm_epilogue(const GemmProblem &P, typename MM:
     // consecutive rows of one column, so the mirrored group C[col][row .. row + 3] is one aligned
     // 16-byte store (a scalar mirror store touches 64 different cache lines per instruction).
     const bool packed = (flags & GEMM_C_PACKED) != 0;
+    bool handover = false;                      // fp64 compute only (a compile-time no for the fp32 kernels)
+    if constexpr (sizeof(TC) == 8) handover = root && (flags & GEMM_EPI_HANDOVER) != 0;
     bool vec_c = false;
     if constexpr (sizeof(TC) == 4)
-        vec_c = !packed && rowsA == BM && rowsB == BN && !(flags & GEMM_C_BF16) && (ldc & 3) == 0 &&
+        vec_c = !packed && rowsA == BM && rowsB == BN && !(flags & (GEMM_C_BF16 | GEMM_EPI_HANDOVER)) && (ldc & 3) == 0 &&
                 (reinterpret_cast<uintptr_t>(C) & 15u) == 0 &&
                 (!root || (P.C3 == nullptr && (ldc2 & 3) == 0 && (reinterpret_cast<uintptr_t>(C2) & 15u) == 0));
 #pragma unroll
@@ -566,13 +571,20 @@ __device__ __forceinline__ void gemm_epilogue(const GemmProblem &P, typename MM:
                 const size_t at_t = off_t + (size_t)(col - bc) * ld_c + (size_t)(row - br);
                 const size_t at = (flags & GEMM_STORE_T) ? at_t : at_n;
                 if (beta != (TC)0) val += beta * load_c<TC>(C, at, flags);
-                store_c<TC>(C, at, val, flags);
-                if (do_mirror && row != col) store_c<TC>(C, at_t, val, flags);
+                if (!handover) {
+                    store_c<TC>(C, at, val, flags);
+                    if (do_mirror && row != col) store_c<TC>(C, at_t, val, flags);
+                } else {
+                    P.C4[(size_t)row * P.ldc4 + col] = (float)val;
+                    if (sym && row != col) P.C4[(size_t)col * P.ldc4 + row] = (float)val;
+                }
                 if (root) {
                     const TC d = (row == col) ? (TC)1 : (TC)0;
                     const TC t2 = ep_a * d - ep_g * val;
-                    C2[(size_t)row * ldc2 + col] = t2;
-                    if (sym && row != col) C2[(size_t)col * ldc2 + row] = t2;
+                    if (!handover) {
+                        C2[(size_t)row * ldc2 + col] = t2;
+                        if (sym && row != col) C2[(size_t)col * ldc2 + row] = t2;
+                    }
                     if (P.C3) {
                         P.C3[(size_t)row * P.ldc3 + col] = (float)t2;
                         if (sym && row != col) P.C3[(size_t)col * P.ldc3 + row] = (float)t2;

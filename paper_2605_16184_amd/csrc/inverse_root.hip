@@ -710,32 +710,6 @@ __global__ __launch_bounds__(64) void root_control_kernel(const FactorDev *fd, F
     }
 }
 
-// fp64 -> fp32 hand-over of M before iteration j (run after control(j)); X and T are kept in
-// fp32 all along.  One workgroup per 128 x 128 tile (full square tiling).
-__global__ __launch_bounds__(256) void root_to_fp32_kernel(const FactorDev *fd, const int *state, int nf, int j,
-                                                           const int *sq_tile_start)
-{
-    int lo = 0, hi = nf - 1;
-    while (lo < hi) {
-        const int mid = (lo + hi + 1) >> 1;
-        if (sq_tile_start[mid] <= (int)blockIdx.x) lo = mid; else hi = mid - 1;
-    }
-    const FactorDev &F = fd[lo];
-    if (state[lo] != ST_RUN) return;
-    const int lt = (int)blockIdx.x - sq_tile_start[lo];
-    const int n = F.n;
-    const int tpr = (n + BN - 1) / BN;
-    const int ti = lt / tpr, tj = lt % tpr;
-    const int par = j & 1;
-    const double *Ms = F.M64[par];
-    float *Md = F.M32[par];
-    for (int e = threadIdx.x; e < BM * BN; e += 256) {
-        const int row = ti * BM + e / BN, col = tj * BN + e % BN;
-        if (row >= n || col >= n) continue;
-        Md[(size_t)row * F.ld32 + col] = (float)Ms[(size_t)row * F.ld64 + col];
-    }
-}
-
 // Copy X from the workspace buffer to the caller's X where the last fp32 update landed there,
 // and publish the per-factor outcome.  One workgroup per 128 x 128 tile.
 __global__ __launch_bounds__(256) void root_finalize_kernel(const FactorDev *fd, const FactorScal *fs,
@@ -814,8 +788,9 @@ void simulate_schedule(double lo0, int n, int root, bool adapted, double stop, d
     if (lead_full) *lead_full = leadf;
 }
 
-// The fp32 work matrices of the M-chain (M x 2, T^4) are first written at the fp64 -> fp32 hand-over,
-// when the fp64 T and T^4 are dead: they share one region.
+// The fp32 work matrices of the M-chain (M x 2, T^4) are first written when the fp64 tier hands over - M
+// by the epilogue of its last M-update, which no longer stores the fp64 T that lies there - and the
+// fp64 T and T^4 are dead from then on: they share one region.
 size_t shared_region_bytes(int n, bool use64, bool use32)
 {
     const size_t b32 = use32 ? 3 * Carver::need((size_t)n * ld4(n), sizeof(float)) : 0;
@@ -845,7 +820,7 @@ size_t factor_small_bytes(int n)
     return 3 * Carver::need((size_t)ld4(n), sizeof(float)) + 2 * Carver::need((size_t)pmb, sizeof(float2)) +
            Carver::need(2 * (size_t)tri_tiles(n), sizeof(float)) + Carver::need((size_t)tri_tiles(n) * PM_TILE_WORDS, sizeof(float)) +
            sizeof(FactorDev) + sizeof(FactorScal) +
-           2 * sizeof(int) + 14 * sizeof(GemmProblem);
+           2 * sizeof(int) + 16 * sizeof(GemmProblem);
 }
 
 size_t fixed_bytes() { return 64 * 256; }   // alignment slack of the shared arrays + coefficient table
@@ -933,6 +908,7 @@ asteria_status validate(const asteria_factor *f, int nf, int root, const float *
 struct RootTables {
     GemmProblem *xt[2];
     GemmProblem *tab[2][2][3];
+    GemmProblem *last64[2];    // [parity] the M-update of the last fp64 iteration: it hands M over in fp32
 };
 
 // one thread per factor writes its entry of every table
@@ -990,6 +966,14 @@ __global__ void root_tables_kernel(const FactorDev *__restrict__ fd, FactorScal 
             q.coef = fs[i].coef_next;
             q.flags = GEMM_SYM | GEMM_EPI_ROOT;
             rt.tab[pr][pa][2][i] = q;
+            if (pr == 1 && use32) {
+                // ... and when it is the last fp64 iteration: the fp64 M' and T' would never be read, the fp32
+                // tier starts from M' in the buffer its parity expects (it lies over the fp64 T, which this
+                // product does not read)
+                q.flags |= GEMM_EPI_HANDOVER;
+                q.C4 = F.M32[pa ^ 1]; q.ldc4 = F.ld32;
+                rt.last64[pa][i] = q;
+            }
         }
     }
 }
@@ -1012,6 +996,8 @@ asteria_status run_pass(const asteria_factor *f, const std::vector<int> &order, 
     for (int pr = 0; pr < 2; ++pr)
         for (int pa = 0; pa < 2; ++pa)
             for (int l = 0; l < 3; ++l) d_tab[pr][pa][l] = cv.take<GemmProblem>(cnt);
+    GemmProblem *d_last64[2];      // [parity] M-update of the last fp64 iteration
+    for (int pa = 0; pa < 2; ++pa) d_last64[pa] = cv.take<GemmProblem>(cnt);
 
     std::vector<FactorDev> fd(cnt);
     std::vector<int> sq(cnt);
@@ -1107,6 +1093,7 @@ asteria_status run_pass(const asteria_factor *f, const std::vector<int> &order, 
     for (int pr = 0; pr < 2; ++pr)
         for (int pa = 0; pa < 2; ++pa)
             for (int l = 0; l < 3; ++l) rt.tab[pr][pa][l] = d_tab[pr][pa][l];
+    for (int pa = 0; pa < 2; ++pa) rt.last64[pa] = d_last64[pa];
     if (ns8 > 0) ASTERIA_HIP_TRY(upload_async(d_xf, xfh.data(), sizeof(I8Factor) * cnt, stream));
     hipLaunchKernelGGL(root_tables_kernel, dim3((cnt + 127) / 128), dim3(128), 0, stream, d_fd, d_fs, cnt, root,
                        pl.use32 ? 1 : 0, pl.use64 ? 1 : 0, rt, d_xf);
@@ -1144,8 +1131,6 @@ asteria_status run_pass(const asteria_factor *f, const std::vector<int> &order, 
         const bool p32 = k >= j64;
         hipLaunchKernelGGL(root_control_kernel, dim3(cnt), dim3(64), 0, stream, d_fd, d_fs, d_state, k,
                            p32 ? 1 : 0, 0, pl.stop_resid, root, pl.adapted ? 1 : 0, pl.xt_lowp ? 1 : 0);
-        if (k == j64 && j64 > 0)
-            hipLaunchKernelGGL(root_to_fp32_kernel, dim3(sq_total), dim3(256), 0, stream, d_fd, d_state, cnt, j64, d_sq);
         const int pa = k & 1;
         const bool lowp = p32 && k >= jlow;
         // X' = X T (X_1 comes from the start kernel).  X only needs the accuracy of the result, so
@@ -1170,6 +1155,8 @@ asteria_status run_pass(const asteria_factor *f, const std::vector<int> &order, 
         } else {
             for (int l = 0; l < 3; ++l) {
                 if (l == 1 && root != 4) continue;
+                // the M-update of the last fp64 iteration writes the fp32 M the next tier starts from
+                const GemmProblem *tab = (l == 2 && k == j64 - 1 && pl.use32) ? d_last64[pa] : d_tab[1][pa][l];
                 if (ns8 > 0) {
                     // Cut the A operand into slices, decide per factor, multiply.  T goes to buffer 1
                     // and stays there: T T reads it twice, and T^4 M reads it as M (B mode 1), so M
@@ -1182,17 +1169,17 @@ asteria_status run_pass(const asteria_factor *f, const std::vector<int> &order, 
                         if (ns8 == 5) ASTERIA_HIP_TRY(ensure_dynamic_lds(reinterpret_cast<const void *>(i8_slice_kernel<5>), i8_slice_lds_bytes(I8_SLICE_LDS_K), cfg5s));
                         else ASTERIA_HIP_TRY(ensure_dynamic_lds(reinterpret_cast<const void *>(i8_slice_kernel<4>), i8_slice_lds_bytes(I8_SLICE_LDS_K), cfg4s));
                     }
-                    if (ns8 == 5) hipLaunchKernelGGL(i8_slice_kernel<5>, sgrid, dim3(256), i8_slice_lds_bytes(lds_k), stream, d_tab[1][pa][l], d_xf, d_state, 0, abuf, lds_k);
-                    else hipLaunchKernelGGL(i8_slice_kernel<4>, sgrid, dim3(256), i8_slice_lds_bytes(lds_k), stream, d_tab[1][pa][l], d_xf, d_state, 0, abuf, lds_k);
+                    if (ns8 == 5) hipLaunchKernelGGL(i8_slice_kernel<5>, sgrid, dim3(256), i8_slice_lds_bytes(lds_k), stream, tab, d_xf, d_state, 0, abuf, lds_k);
+                    else hipLaunchKernelGGL(i8_slice_kernel<4>, sgrid, dim3(256), i8_slice_lds_bytes(lds_k), stream, tab, d_xf, d_state, 0, abuf, lds_k);
                     // per factor: 4 slices where the estimate allows, else 5 (if the planes have them), else fp64
                     hipLaunchKernelGGL(i8_gate_kernel, dim3(ctl_blocks), dim3(128), 0, stream, d_xf, cnt, &d_fs[0].lo_cur,
                                        (int)sizeof(FactorScal), 4, ns8, abuf, bbuf, bmode,
                                        I8_THETA * 2.0f / (float)std::max(2, j64), d_state, profile_i8_counters());
                     ASTERIA_HIP_TRY(hipGetLastError());
-                    if (ns8 == 5) ASTERIA_HIP_TRY((launch_gemm_i8_grouped<5>(d_tab[1][pa][l], d_xf, cnt, tri_total, d_state, abuf, bbuf, bmode, stream)));
-                    else ASTERIA_HIP_TRY((launch_gemm_i8_grouped<4>(d_tab[1][pa][l], d_xf, cnt, tri_total, d_state, abuf, bbuf, bmode, stream)));
+                    if (ns8 == 5) ASTERIA_HIP_TRY((launch_gemm_i8_grouped<5>(tab, d_xf, cnt, tri_total, d_state, abuf, bbuf, bmode, stream)));
+                    else ASTERIA_HIP_TRY((launch_gemm_i8_grouped<4>(tab, d_xf, cnt, tri_total, d_state, abuf, bbuf, bmode, stream)));
                 }
-                ASTERIA_HIP_TRY((launch_gemm_grouped<double, double, double, false, false>(d_tab[1][pa][l], cnt, tri_total, d_state, stream)));
+                ASTERIA_HIP_TRY((launch_gemm_grouped<double, double, double, false, false>(tab, cnt, tri_total, d_state, stream)));
             }
         }
     }
